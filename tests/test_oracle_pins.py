@@ -1,0 +1,294 @@
+"""Pins for oracle/models.py and oracle/lanczos.py against things other than
+themselves: finite differences, Hessian symmetry, the dense Hessian of the
+tiny MLP, Algorithm 1 run literally under PyTorch autograd, closed forms,
+Gauss-quadrature identities and dense eigenvalues."""
+import os
+
+import numpy as np
+import pytest
+
+import synth_inputs as si
+from oracle import lanczos as olz
+from oracle import models as om
+
+from alg1_torch import alg1_hvp
+
+TINY = {
+    "mlp": dict(model=si.CONFIGS["mlp_tiny"]["model"], batch=32, seq=1, tokens=None),
+    "gpt": dict(model=si._gpt(2, 16, 2, 32, 23, 8), batch=2, seq=8, tokens="uniform"),
+    "gpt_untied": dict(model=si._gpt(1, 16, 4, 24, 19, 6, tie=0), batch=3, seq=6, tokens="zipf"),
+    "llama": dict(model=si._llama(2, 16, 2, 24, 21, 8), batch=2, seq=8, tokens="zipf"),
+}
+
+
+def setup(name, seed=0):
+    cfg = TINY[name]
+    model = cfg["model"]
+    # perturb gains/biases and scale weights up so every term is exercised
+    p = si.make_params(model, seed=42 + seed, perturb=0.3).astype(np.float64)
+    if model["arch"] != "mlp":
+        p = p * 6.0
+        for nm, off, sh in om.layout(model):
+            if nm.endswith(".g"):
+                sl = slice(off, off + int(np.prod(sh)))
+                p[sl] = p[sl] / 6.0 + 0.7
+    x, y = si.make_batch(cfg, seed=43 + seed)
+    n = om.num_params(model)
+    rng = np.random.default_rng(100 + seed)
+    return model, p, x, y, rng.standard_normal(n), rng.standard_normal(n)
+
+
+@pytest.mark.parametrize("name", list(TINY))
+def test_layout_matches_generator(name):
+    model = TINY[name]["model"]
+    spec = si.param_spec(model)
+    lay = om.layout(model)
+    assert [(a, tuple(s)) for a, s, _ in spec] == [(a, tuple(s)) for a, _, s in lay]
+    assert om.num_params(model) == si.num_params(model)
+
+
+def test_param_counts_of_the_five_workloads():
+    want = {"mlp_tiny": 1386, "gpt_2l_d128": 470528, "gpt2_small": 124046592,
+            "gpt_1p3b": 1276235776, "llama_7b": 6738415616}
+    for k, n in want.items():
+        assert om.num_params(si.CONFIGS[k]["model"]) == n
+
+
+@pytest.mark.parametrize("name", list(TINY))
+def test_gradient_vs_finite_difference_of_loss(name):
+    model, p, x, y, v, w = setup(name)
+    loss, g, _, loss_t = om.loss_grad_hvp(model, p, x, y, v)
+    eps = 1e-6
+    num = (om.loss_only(model, p + eps * v, x, y) - om.loss_only(model, p - eps * v, x, y)) / (2 * eps)
+    assert abs(num - g @ v) <= 1e-7 * max(1.0, abs(num))
+    assert abs(loss_t - g @ v) <= 1e-10 * max(1.0, abs(num))
+    # per-parameter on a sample of coordinates
+    rng = np.random.default_rng(5)
+    for j in rng.choice(len(p), size=12, replace=False):
+        e = np.zeros_like(p); e[j] = 1.0
+        num = (om.loss_only(model, p + eps * e, x, y) - om.loss_only(model, p - eps * e, x, y)) / (2 * eps)
+        assert abs(num - g[j]) <= 1e-7 * max(1.0, abs(g).max())
+
+
+@pytest.mark.parametrize("name", list(TINY))
+def test_hvp_vs_finite_difference_of_gradient(name):
+    model, p, x, y, v, w = setup(name)
+    _, _, hv, _ = om.loss_grad_hvp(model, p, x, y, v)
+    eps = 1e-5 * np.linalg.norm(p) / np.linalg.norm(v)
+    gp = om.loss_grad_hvp(model, p + eps * v, x, y)[1]
+    gm = om.loss_grad_hvp(model, p - eps * v, x, y)[1]
+    num = (gp - gm) / (2 * eps)
+    rel = np.linalg.norm(num - hv) / np.linalg.norm(hv)
+    assert rel <= 1e-6, rel
+
+
+@pytest.mark.parametrize("name", list(TINY))
+def test_hessian_symmetry(name):
+    model, p, x, y, v, w = setup(name)
+    hv = om.hvp(model, p, x, y, v)
+    hw = om.hvp(model, p, x, y, w)
+    a, b = w @ hv, v @ hw
+    assert abs(a - b) <= 1e-10 * max(abs(a), abs(b), 1e-3)
+
+
+@pytest.mark.parametrize("name", list(TINY))
+def test_against_algorithm1_run_with_autograd(name):
+    model, p, x, y, v, w = setup(name)
+    loss, g, hv, _ = om.loss_grad_hvp(model, p, x, y, v)
+    P, Vd = om.unflatten(model, p), om.unflatten(model, v)
+    names = [nm for nm, _, _ in om.layout(model)]
+    l2, g2, hv2 = alg1_hvp(model, [(nm, P[nm]) for nm in names], [(nm, Vd[nm]) for nm in names], x, y)
+    assert abs(loss - l2) <= 1e-12 * max(1, abs(l2))
+    assert np.linalg.norm(g - g2) <= 1e-10 * np.linalg.norm(g2)
+    assert np.linalg.norm(hv - hv2) <= 1e-10 * np.linalg.norm(hv2)
+
+
+def test_algorithm1_at_workload_2_shape():
+    cfg = si.CONFIGS["gpt_2l_d128"]
+    model = cfg["model"]
+    p = si.make_params(model).astype(np.float64)
+    x, y = si.make_batch(cfg, batch=2)
+    v = si.make_direction(om.num_params(model), 9).astype(np.float64)
+    loss, g, hv, _ = om.loss_grad_hvp(model, p, x, y, v)
+    P, Vd = om.unflatten(model, p), om.unflatten(model, v)
+    names = [nm for nm, _, _ in om.layout(model)]
+    l2, g2, hv2 = alg1_hvp(model, [(nm, P[nm]) for nm in names], [(nm, Vd[nm]) for nm in names], x, y)
+    assert abs(loss - l2) <= 1e-12 * abs(l2)
+    assert np.linalg.norm(hv - hv2) <= 1e-10 * np.linalg.norm(hv2)
+    # at N(0, 0.02) init the logits are near zero: loss is close to ln(V)
+    assert abs(loss - np.log(model["vocab"])) < 0.05
+
+
+# ----------------------------------------------------- dense Hessian (MLP) ----
+
+@pytest.fixture(scope="module")
+def mlp_dense():
+    cfg = si.CONFIGS["mlp_tiny"]
+    model = cfg["model"]
+    p = si.make_params(model).astype(np.float64)
+    x, y = si.make_batch(cfg)
+    Hm = om.dense_hessian(model, p, x, y)
+    return model, p, x, y, Hm
+
+
+def test_dense_hessian_symmetric_and_fd_jacobian(mlp_dense):
+    model, p, x, y, Hm = mlp_dense
+    assert np.abs(Hm - Hm.T).max() <= 1e-12 * np.abs(Hm).max()
+    rng = np.random.default_rng(3)
+    eps = 1e-6
+    for j in rng.choice(len(p), size=10, replace=False):
+        e = np.zeros_like(p); e[j] = 1
+        col = (om.loss_grad_hvp(model, p + eps * e, x, y)[1] - om.loss_grad_hvp(model, p - eps * e, x, y)[1]) / (2 * eps)
+        np.testing.assert_allclose(Hm[:, j], col, atol=1e-8)
+
+
+def test_output_layer_block_closed_form(mlp_dense):
+    """z is linear in (W2, b2), so that Hessian block is the Gauss-Newton form
+    mean_i [h_i;1][h_i;1]^T (x) (diag(p_i) - p_i p_i^T)  (textbook)."""
+    model, p, x, y, Hm = mlp_dense
+    P = om.unflatten(model, p)
+    h = np.tanh(x.astype(np.float64) @ P["W1"] + P["b1"])
+    z = h @ P["W2"] + P["b2"]
+    pr = np.exp(z - z.max(1, keepdims=True)); pr /= pr.sum(1, keepdims=True)
+    lay = {nm: (off, sh) for nm, off, sh in om.layout(model)}
+    oW, _ = lay["W2"]; ob, _ = lay["b2"]
+    nh, no = P["W2"].shape
+    blk = np.zeros((nh * no, nh * no))
+    bb = np.zeros((no, no))
+    for i in range(len(x)):
+        A = np.diag(pr[i]) - np.outer(pr[i], pr[i])
+        blk += np.kron(np.outer(h[i], h[i]), A)
+        bb += A
+    np.testing.assert_allclose(Hm[oW:oW + nh * no, oW:oW + nh * no], blk / len(x), atol=1e-13)
+    np.testing.assert_allclose(Hm[ob:ob + no, ob:ob + no], bb / len(x), atol=1e-13)
+
+
+def test_lanczos_full_reorth_on_dense_hessian(mlp_dense):
+    model, p, x, y, Hm = mlp_dense
+    n = len(p)
+    lam = np.linalg.eigvalsh(Hm)
+    z = si.make_probe(n, 0)
+    m = 80
+    a, b, m_eff, Q = olz.lanczos(lambda q: Hm @ q, z, m, reorth="full", return_basis=True)
+    assert m_eff == m
+    Qk = Q[:m]
+    assert np.abs(Qk @ Qk.T - np.eye(m)).max() <= 1e-10
+    T = olz.tridiagonal(a, b)
+    assert np.abs(Qk @ Hm @ Qk.T - T).max() <= 1e-10 * max(1, np.abs(lam).max())
+    theta, wts = olz.slq_readout(a, b)
+    assert np.all(np.diff(theta) >= 0) and np.all(wts >= 0)
+    assert abs(wts.sum() - 1) <= 1e-12
+    assert theta[0] >= lam[0] - 1e-10 and theta[-1] <= lam[-1] + 1e-10
+    # extreme Ritz values within the residual bound |beta_{m-1} y_i[m-1]|
+    _, Y = np.linalg.eigh(T)
+    for i, target in ((0, lam[0]), (m - 1, lam[-1])):
+        bound = abs(b[m - 1] * Y[m - 1, i])
+        assert np.min(np.abs(lam - theta[i])) <= bound + 1e-12
+    assert abs(theta[-1] - lam[-1]) <= 1e-3 * abs(lam[-1])
+    # Gauss quadrature: sum_i w_i theta_i^p = q0^T H^p q0, p = 0..6
+    q0 = z.astype(np.float64) / np.linalg.norm(z.astype(np.float64))
+    vec = q0.copy()
+    for pw in range(7):
+        exact = q0 @ vec
+        quad = (wts * theta ** pw).sum()
+        assert abs(exact - quad) <= 1e-9 * max(1.0, abs(exact)), pw
+        vec = Hm @ vec
+    # alpha_0 = q0^T H q0 exactly
+    assert abs(a[0] - q0 @ Hm @ q0) <= 1e-13 * max(1, abs(a[0]))
+
+
+def test_lanczos_three_term_equals_full_early_and_matches_hvp_operator(mlp_dense):
+    model, p, x, y, Hm = mlp_dense
+    z = si.make_probe(len(p), 1)
+    a1, b1, _ = olz.lanczos(lambda q: Hm @ q, z, 6, reorth="none")
+    a2, b2, _ = olz.lanczos(lambda q: om.hvp(model, p, x, y, q), z, 6, reorth="full")
+    np.testing.assert_allclose(a1, a2, rtol=1e-8, atol=1e-12)
+    np.testing.assert_allclose(b1, b2, rtol=1e-8, atol=1e-12)
+
+
+def test_hutchinson_trace(mlp_dense):
+    model, p, x, y, Hm = mlp_dense
+    n = len(p)
+    est = []
+    for i in range(4):
+        z = si.make_probe(n, i)
+        a, b, _ = olz.lanczos(lambda q: Hm @ q, z, 5)
+        th, w = olz.slq_readout(a, b)
+        assert abs((w * th).sum() - a[0]) <= 1e-12 * max(1, abs(a[0]))
+        est.append(n * a[0])
+    var = 2 * ((Hm ** 2).sum() - (np.diag(Hm) ** 2).sum())      # Rademacher variance
+    assert abs(np.mean(est) - np.trace(Hm)) <= 3 * np.sqrt(var / 4)
+
+
+def test_lanczos_m_equals_n_recovers_spectrum():
+    rng = np.random.default_rng(11)
+    A = rng.standard_normal((40, 40)); A = (A + A.T) / 2
+    a, b, m_eff = olz.lanczos(lambda q: A @ q, rng.standard_normal(40), 40, reorth="full")
+    theta, w = olz.slq_readout(a, b)
+    np.testing.assert_allclose(theta, np.linalg.eigvalsh(A), rtol=0, atol=1e-10)
+
+
+def test_lanczos_diagonal_operator_and_breakdown():
+    d = np.linspace(-3.0, 5.0, 400) ** 3
+    z = np.ones(400)
+    a, b, m_eff = olz.lanczos(lambda q: d * q, z, 60, reorth="full")
+    theta, _ = olz.slq_readout(a, b)
+    assert abs(theta[-1] - d.max()) <= 1e-6 * d.max()
+    assert abs(theta[0] - d.min()) <= 1e-6 * abs(d.min())
+    # an operator with 3 distinct eigenvalues breaks down at step 3
+    d3 = np.repeat([1.0, 2.0, 4.0], 5)
+    a, b, m_eff = olz.lanczos(lambda q: d3 * q, np.ones(15), 10, reorth="none", tol=1e-9)
+    assert m_eff == 3
+    np.testing.assert_allclose(olz.slq_readout(a, b)[0], [1.0, 2.0, 4.0], atol=1e-12)
+
+
+def test_ghosts_without_reorthogonalisation_in_float32():
+    """Section 'Memory Compute trade off': without re-orthogonalisation the
+    three-term recurrence in finite precision repeats converged extreme Ritz
+    values; with the stored basis it does not."""
+    d = np.concatenate([np.linspace(0, 1, 300), [50.0, 80.0]])
+    z = np.ones_like(d)
+
+    def run32(reorth, m=40):
+        q = (z / np.linalg.norm(z)).astype(np.float32); qp = None
+        al, be, Q = [], [], [q.copy()]
+        for k in range(m):
+            r = (d.astype(np.float32) * q)
+            if k: r = r - np.float32(be[-1]) * qp
+            a = np.float32(q @ r); r = r - a * q
+            if reorth:
+                Qm = np.stack(Q); r = r - Qm.T @ (Qm @ r)
+            b = np.float32(np.linalg.norm(r)); al.append(a); be.append(b)
+            qp, q = q, r / b; Q.append(q.copy())
+        return olz.slq_readout(np.array(al, dtype=np.float64), np.array(be, dtype=np.float64))[0]
+    full, none = run32(True), run32(False)
+    near = lambda th: int(np.sum(np.abs(th - 80.0) <= 1e-3 * 80.0))
+    assert near(full) == 1
+    assert near(none) >= 2
+
+
+def test_table2_layout_invariants():
+    """The paper's Table 2 prints, per run, ten (Ritz value, weight) pairs for
+    ten iterations: ascending Ritz values, non-negative weights summing to one
+    within print precision.  The read-out must have the same structure."""
+    path = os.path.join(os.path.dirname(__file__), "golden", "table2_ritz_weights.txt")
+    runs = {}
+    for line in open(path):
+        if line.startswith("#") or not line.strip():
+            continue
+        name, th, w = line.split()
+        runs.setdefault(name, []).append((float(th), float(w)))
+    assert set(runs) == {"wikitext", "realnewslike"}
+    for rows in runs.values():
+        th = np.array([r[0] for r in rows]); w = np.array([r[1] for r in rows])
+        assert len(rows) == 10 and np.all(np.diff(th) > 0) and np.all(w >= 0)
+        assert abs(w.sum() - 1.0) < 1e-4
+    rng = np.random.default_rng(2)
+    a, b = rng.standard_normal(10), np.abs(rng.standard_normal(10)) + 0.1
+    th, w = olz.slq_readout(a, b)
+    assert len(th) == 10 and np.all(np.diff(th) > 0) and np.all(w >= 0) and abs(w.sum() - 1) < 1e-12
+
+
+def test_float32_weight_error_bound_constant():
+    # Section "A note on numerical precision": 2 k u with k = 10, u = 2^-24
+    assert abs(2 * 10 * 2.0 ** -24 - 1.19e-6) < 0.01e-6
