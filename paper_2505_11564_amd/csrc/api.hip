@@ -1,0 +1,327 @@
+// C ABI of libhessformer_hip (declared in include/hessformer.h): argument
+// checking, context life cycle, the Lanczos / SLQ drivers (Algorithm 2 of the
+// paper and the Ritz value / weight read-out of its Table 2).
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <mutex>
+
+#include "engine.h"
+
+using namespace hf;
+
+namespace {
+std::mutex g_err_mu;
+std::string g_create_err;
+void set_create_err(const std::string& m) {
+  std::lock_guard<std::mutex> lk(g_err_mu);
+  g_create_err = m;
+}
+
+// Eigen-decomposition of a symmetric tridiagonal matrix by cyclic Jacobi
+// rotations on its dense form (k is at most a few hundred).  V's columns are
+// the eigenvectors.
+void jacobi_eig(std::vector<double>& A, std::vector<double>& Vm, int k) {
+  Vm.assign((size_t)k * k, 0.0);
+  for (int i = 0; i < k; ++i) Vm[(size_t)i * k + i] = 1.0;
+  double fro = 0.0;
+  for (double x : A) fro += x * x;
+  if (fro == 0.0) return;
+  for (int sweep = 0; sweep < 100; ++sweep) {
+    double off = 0.0;
+    for (int p = 0; p < k; ++p)
+      for (int q = p + 1; q < k; ++q) off += A[(size_t)p * k + q] * A[(size_t)p * k + q];
+    if (off <= 1e-34 * fro) break;
+    for (int p = 0; p < k - 1; ++p) {
+      for (int q = p + 1; q < k; ++q) {
+        const double apq = A[(size_t)p * k + q];
+        if (apq == 0.0) continue;
+        const double app = A[(size_t)p * k + p], aqq = A[(size_t)q * k + q];
+        const double tau = (aqq - app) / (2.0 * apq);
+        const double t = (tau >= 0.0 ? 1.0 : -1.0) / (std::fabs(tau) + std::sqrt(1.0 + tau * tau));
+        const double cs = 1.0 / std::sqrt(1.0 + t * t), sn = t * cs;
+        for (int i = 0; i < k; ++i) {  // columns p, q of A
+          const double aip = A[(size_t)i * k + p], aiq = A[(size_t)i * k + q];
+          A[(size_t)i * k + p] = cs * aip - sn * aiq;
+          A[(size_t)i * k + q] = sn * aip + cs * aiq;
+        }
+        for (int i = 0; i < k; ++i) {  // rows p, q of A
+          const double api = A[(size_t)p * k + i], aqi = A[(size_t)q * k + i];
+          A[(size_t)p * k + i] = cs * api - sn * aqi;
+          A[(size_t)q * k + i] = sn * api + cs * aqi;
+        }
+        for (int i = 0; i < k; ++i) {
+          const double vip = Vm[(size_t)i * k + p], viq = Vm[(size_t)i * k + q];
+          Vm[(size_t)i * k + p] = cs * vip - sn * viq;
+          Vm[(size_t)i * k + q] = sn * vip + cs * viq;
+        }
+      }
+    }
+  }
+}
+}  // namespace
+
+extern "C" {
+
+const char* hf_version(void) { return "hessformer-hip 0.1 (gfx950)"; }
+
+int64_t hf_desc_num_params(const hf_model_desc* desc) {
+  if (!desc) return HF_EINVAL;
+  std::vector<LayoutEntry> lay;
+  const int rc = build_layout(*desc, lay, nullptr);
+  if (rc != HF_OK) return rc;
+  return lay.back().offset + lay.back().count();
+}
+
+int32_t hf_layout_count(const hf_model_desc* desc) {
+  if (!desc) return HF_EINVAL;
+  std::vector<LayoutEntry> lay;
+  const int rc = build_layout(*desc, lay, nullptr);
+  if (rc != HF_OK) return rc;
+  return (int32_t)lay.size();
+}
+
+int32_t hf_layout_entry(const hf_model_desc* desc, int32_t idx, char* name, int32_t name_cap, int64_t* offset,
+                        int64_t shape[2]) {
+  if (!desc) return HF_EINVAL;
+  std::vector<LayoutEntry> lay;
+  const int rc = build_layout(*desc, lay, nullptr);
+  if (rc != HF_OK) return rc;
+  if (idx < 0 || idx >= (int32_t)lay.size()) return HF_EINVAL;
+  const LayoutEntry& e = lay[idx];
+  if (name && name_cap > 0) {
+    std::strncpy(name, e.name.c_str(), (size_t)name_cap - 1);
+    name[name_cap - 1] = 0;
+  }
+  if (offset) *offset = e.offset;
+  if (shape) { shape[0] = e.shape[0]; shape[1] = e.shape[1]; }
+  return HF_OK;
+}
+
+int32_t hf_tridiag_readout(const double* alpha, const double* beta, int32_t k, double* ritz, double* weights,
+                           double* last_row) {
+  if (!alpha || !ritz || !weights || k <= 0 || (k > 1 && !beta)) return HF_EINVAL;
+  if (k > 2048) return HF_ESHAPE;
+  std::vector<double> A((size_t)k * k, 0.0), Vm;
+  for (int i = 0; i < k; ++i) {
+    A[(size_t)i * k + i] = alpha[i];
+    if (i + 1 < k) A[(size_t)i * k + i + 1] = A[(size_t)(i + 1) * k + i] = beta[i];
+  }
+  jacobi_eig(A, Vm, k);
+  std::vector<int> ord(k);
+  for (int i = 0; i < k; ++i) ord[i] = i;
+  std::sort(ord.begin(), ord.end(), [&](int a, int b) { return A[(size_t)a * k + a] < A[(size_t)b * k + b]; });
+  for (int i = 0; i < k; ++i) {
+    const int j = ord[i];
+    ritz[i] = A[(size_t)j * k + j];
+    const double y0 = Vm[j];  // row 0, column j
+    weights[i] = y0 * y0;
+    if (last_row) last_row[i] = Vm[(size_t)(k - 1) * k + j];
+  }
+  return HF_OK;
+}
+
+int32_t hf_create(const hf_model_desc* desc, int32_t hip_device, int32_t max_batch, int32_t max_m, hf_ctx** out) {
+  if (!desc || !out) { set_create_err("hf_create: NULL argument"); return HF_EINVAL; }
+  *out = nullptr;
+  if (max_batch <= 0 || max_m < 0) { set_create_err("hf_create: max_batch must be > 0 and max_m >= 0"); return HF_EINVAL; }
+  hf_ctx* c = new (std::nothrow) hf_ctx();
+  if (!c) { set_create_err("hf_create: out of host memory"); return HF_ENOMEM; }
+  c->desc = *desc;
+  std::string why;
+  int rc = build_layout(*desc, c->layout, &why);
+  if (rc != HF_OK) { set_create_err("hf_create: " + why); delete c; return rc; }
+  c->n = c->layout.back().offset + c->layout.back().count();
+  c->bf = desc->param_dtype == HF_BF16;
+  c->max_batch = max_batch;
+  c->max_m = max_m;
+  c->device = hip_device;
+  // named offsets
+  if (desc->arch != HF_ARCH_MLP) c->loff.resize(desc->n_layer);
+  for (const auto& e : c->layout) {
+    const std::string& nm = e.name;
+    const int64_t o = e.offset;
+    if (nm == "W1") c->off_w1 = o; else if (nm == "b1") c->off_b1 = o;
+    else if (nm == "W2") c->off_w2 = o; else if (nm == "b2") c->off_b2 = o;
+    else if (nm == "wte") c->off_wte = o; else if (nm == "wpe") c->off_wpe = o;
+    else if (nm == "lnf.g" || nm == "rmsf.g") c->off_nfg = o; else if (nm == "lnf.b") c->off_nfb = o;
+    else if (nm == "lm_head") c->off_head = o;
+    else if (nm[0] == 'h') {
+      const size_t dot = nm.find('.');
+      const int l = std::stoi(nm.substr(1, dot - 1));
+      const std::string t = nm.substr(dot + 1);
+      LayerOff& lo = c->loff[l];
+      if (t == "ln1.g" || t == "rms1.g") lo.n1g = o; else if (t == "ln1.b") lo.n1b = o;
+      else if (t == "ln2.g" || t == "rms2.g") lo.n2g = o; else if (t == "ln2.b") lo.n2b = o;
+      else if (t == "Wqkv") lo.wqkv = o; else if (t == "bqkv") lo.bqkv = o;
+      else if (t == "Wq") lo.wq = o; else if (t == "Wk") lo.wk = o; else if (t == "Wv") lo.wv = o;
+      else if (t == "Wo") lo.wo = o; else if (t == "bo") lo.bo = o;
+      else if (t == "Wfc") lo.wfc = o; else if (t == "bfc") lo.bfc = o;
+      else if (t == "Wproj") lo.wproj = o; else if (t == "bproj") lo.bproj = o;
+      else if (t == "Wgate") lo.wgate = o; else if (t == "Wup") lo.wup = o; else if (t == "Wdown") lo.wdown = o;
+    }
+    // H v blocks that are accumulated with atomics start from zero: every
+    // vector parameter, the position table, and the token table unless the
+    // tied head product writes it first.
+    const bool tied_wte = (nm == "wte" && desc->arch == HF_ARCH_GPT && desc->tie_embeddings);
+    if (e.shape[1] == 0 || nm == "wpe" || (nm == "wte" && !tied_wte)) {
+      if (!c->zero_ranges.empty() && c->zero_ranges.back().first + c->zero_ranges.back().second == o)
+        c->zero_ranges.back().second += e.count();
+      else c->zero_ranges.push_back({o, e.count()});
+    }
+  }
+  hipError_t he = hipSetDevice(hip_device);
+  if (he != hipSuccess) {
+    set_create_err(std::string("hf_create: hipSetDevice failed: ") + hipGetErrorString(he));
+    (void)hipGetLastError();
+    delete c;
+    return HF_EDEVICE;
+  }
+  rc = c->plan_and_alloc();
+  if (rc != HF_OK) { set_create_err("hf_create: " + c->err); hf_destroy(c); return rc; }
+  *out = c;
+  return HF_OK;
+}
+
+void hf_destroy(hf_ctx* ctx) {
+  if (!ctx) return;
+  if (ctx->arena) (void)hipFree(ctx->arena);
+  if (ctx->host_scal) (void)hipHostFree(ctx->host_scal);
+  delete ctx;
+}
+
+int64_t hf_num_params(const hf_ctx* ctx) { return ctx ? ctx->n : (int64_t)HF_EINVAL; }
+int64_t hf_workspace_bytes(const hf_ctx* ctx) { return ctx ? ctx->arena_bytes : (int64_t)HF_EINVAL; }
+
+const char* hf_last_error(const hf_ctx* ctx) {
+  if (ctx) return ctx->err.c_str();
+  static thread_local std::string copy;
+  std::lock_guard<std::mutex> lk(g_err_mu);
+  copy = g_create_err;
+  return copy.c_str();
+}
+
+int32_t hf_hvp(hf_ctx* ctx, const void* params_dev, const void* inputs_dev, const int32_t* labels_dev, int32_t batch,
+               int32_t seq, const float* v_dev, float* out_dev, double* loss_host, void* hip_stream) {
+  if (!ctx) return HF_EINVAL;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (out_dev == v_dev || (const void*)out_dev == params_dev) return ctx->fail(HF_EINVAL, "hf_hvp: out_dev aliases an input");
+  int rc = ctx->hvp_enqueue(params_dev, inputs_dev, labels_dev, batch, seq, v_dev, out_dev, st);
+  if (rc != HF_OK) return rc;
+  return ctx->finish_hvp(loss_host, st);
+}
+
+int32_t hf_lanczos_init(hf_ctx* ctx, const float* q0_dev, int32_t reorth, void* hip_stream) {
+  if (!ctx) return HF_EINVAL;
+  hf_ctx* c = ctx;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (!q0_dev) return c->fail(HF_EINVAL, "hf_lanczos_init: NULL q0_dev");
+  if (reorth != HF_REORTH_NONE && reorth != HF_REORTH_FULL) return c->fail(HF_EINVAL, "hf_lanczos_init: bad reorth");
+  if (c->max_m <= 0) return c->fail(HF_ESHAPE, "hf_lanczos_init: context was created with max_m = 0");
+  c->lz_k = -1;
+  c->iq = 0; c->iqp = 1; c->ir = 2;
+  float* q = c->lz_vec[c->iq];
+  const int bq = c->desc.basis_dtype == HF_BF16;
+#define CKI(expr)                                                                                   \
+  do {                                                                                              \
+    hipError_t e_ = (expr);                                                                         \
+    if (e_ != hipSuccess) return c->fail(HF_EDEVICE, std::string(#expr) + ": " + hipGetErrorString(e_)); \
+  } while (0)
+  CKI(hipMemcpyAsync(q, q0_dev, (size_t)c->n * 4, hipMemcpyDeviceToDevice, st));
+  CKI(launch_fill_f32((float*)c->scal, S_COUNT * 2, 0.f, st));
+  CKI(lz_norm_q0(q, c->n, c->scal, c->partials, st));
+  CKI(hipMemcpyAsync(c->host_scal, c->scal, S_COUNT * sizeof(double), hipMemcpyDeviceToHost, st));
+  CKI(hipStreamSynchronize(st));
+  const double nrm = c->host_scal[S_Q0NORM];
+  if (!(nrm > 0.0) || !std::isfinite(nrm)) return c->fail(HF_EINVAL, "hf_lanczos_init: q0 has zero or non-finite norm");
+  CKI(lz_scale(q, q, reorth == HF_REORTH_FULL ? c->basis : nullptr, bq, c->n, c->scal, S_Q0NORM, st));
+  c->lz_reorth = reorth;
+  c->lz_k = 0;
+  c->lz_done = 0;
+  return HF_OK;
+}
+
+int32_t hf_lanczos_step(hf_ctx* ctx, const void* params_dev, const void* inputs_dev, const int32_t* labels_dev,
+                        int32_t batch, int32_t seq, double tol, double* alpha_k, double* beta_k, void* hip_stream) {
+  if (!ctx) return HF_EINVAL;
+  hf_ctx* c = ctx;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (c->lz_k < 0) return c->fail(HF_ESTATE, "hf_lanczos_step: call hf_lanczos_init first");
+  if (c->lz_done) return c->fail(HF_ESTATE, "hf_lanczos_step: the iteration has ended (breakdown)");
+  if (c->lz_reorth == HF_REORTH_FULL && c->lz_k >= c->max_m) return c->fail(HF_ESHAPE, "hf_lanczos_step: max_m iterations reached");
+  float* r = c->lz_vec[c->ir];
+  int rc = c->hvp_enqueue(params_dev, inputs_dev, labels_dev, batch, seq, c->lz_vec[c->iq], r, st);
+  if (rc != HF_OK) return rc;
+  rc = c->lanczos_update(r, tol, alpha_k, beta_k, st);
+  if (rc < 0) return rc;
+  // the stream was synchronised inside lanczos_update: surface device-side input errors
+  int fl[2];
+  CKI(hipMemcpy(fl, c->flags, sizeof(fl), hipMemcpyDeviceToHost));
+  if (fl[0] & 1) return c->fail(HF_EINVAL, "token id outside [0, vocab)");
+  if (fl[0] & 2) return c->fail(HF_EINVAL, "label >= number of classes");
+  if (fl[1] == 0) return c->fail(HF_EINVAL, "no valid label in the batch");
+  return rc;
+}
+
+int32_t hf_lanczos_update(hf_ctx* ctx, float* r_dev, double tol, double* alpha_k, double* beta_k,
+                          void* hip_stream) {
+  if (!ctx) return HF_EINVAL;
+  hf_ctx* c = ctx;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (!r_dev) return c->fail(HF_EINVAL, "hf_lanczos_update: NULL r_dev");
+  if (c->lz_k < 0) return c->fail(HF_ESTATE, "hf_lanczos_update: call hf_lanczos_init first");
+  if (c->lz_done) return c->fail(HF_ESTATE, "hf_lanczos_update: the iteration has ended (breakdown)");
+  if (c->lz_reorth == HF_REORTH_FULL && c->lz_k >= c->max_m) return c->fail(HF_ESHAPE, "hf_lanczos_update: max_m iterations reached");
+  if ((uintptr_t)r_dev & 15) return c->fail(HF_EINVAL, "hf_lanczos_update: r_dev must be 16-byte aligned");
+  return c->lanczos_update(r_dev, tol, alpha_k, beta_k, st);
+}
+
+int32_t hf_lanczos_iterations(const hf_ctx* ctx) { return ctx ? ctx->lz_k : (int32_t)HF_EINVAL; }
+
+int32_t hf_lanczos_get_vector(hf_ctx* ctx, int32_t which, float* dst_dev, void* hip_stream) {
+  if (!ctx) return HF_EINVAL;
+  hf_ctx* c = ctx;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (!dst_dev) return c->fail(HF_EINVAL, "hf_lanczos_get_vector: NULL dst_dev");
+  if (c->lz_k < 0) return c->fail(HF_ESTATE, "hf_lanczos_get_vector: no iteration in progress");
+  if (which >= 0 && which < 3) {
+    const int idx = which == 0 ? c->iq : (which == 1 ? c->iqp : c->ir);
+    CKI(hipMemcpyAsync(dst_dev, c->lz_vec[idx], (size_t)c->n * 4, hipMemcpyDeviceToDevice, st));
+    return HF_OK;
+  }
+  const int j = which - 16;
+  const int have = c->lz_reorth == HF_REORTH_FULL ? std::min(c->lz_k + 1, c->max_m) : 0;
+  if (j < 0 || j >= have) return c->fail(HF_EINVAL, "hf_lanczos_get_vector: no such vector");
+  const int bq = c->desc.basis_dtype == HF_BF16;
+  CKI(lz_widen((char*)c->basis + (int64_t)j * c->ldq * (bq ? 2 : 4), bq, dst_dev, c->n, st));
+  return HF_OK;
+}
+
+int32_t hf_slq(hf_ctx* ctx, const void* params_dev, const void* inputs_dev, const int32_t* labels_dev, int32_t batch,
+               int32_t seq, const float* probes_dev, int32_t n_probes, int32_t m, int32_t reorth, double tol,
+               double* alpha, double* beta, double* ritz, double* weights, int32_t* m_eff, void* hip_stream) {
+  if (!ctx) return HF_EINVAL;
+  hf_ctx* c = ctx;
+  if (!probes_dev || !alpha || !beta || !ritz || !weights || !m_eff) return c->fail(HF_EINVAL, "hf_slq: NULL argument");
+  if (n_probes <= 0 || m <= 0) return c->fail(HF_EINVAL, "hf_slq: n_probes and m must be positive");
+  if (m > c->max_m) return c->fail(HF_ESHAPE, "hf_slq: m exceeds max_m of hf_create");
+  int status = HF_OK;
+  for (int p = 0; p < n_probes; ++p) {
+    int rc = hf_lanczos_init(c, probes_dev + (int64_t)p * c->n, reorth, hip_stream);
+    if (rc != HF_OK) return rc;
+    int k = 0;
+    for (; k < m; ++k) {
+      rc = hf_lanczos_step(c, params_dev, inputs_dev, labels_dev, batch, seq, tol, alpha + (int64_t)p * m + k,
+                           beta + (int64_t)p * m + k, hip_stream);
+      if (rc < 0) return rc;
+      if (rc == HF_EBREAKDOWN) { status = HF_EBREAKDOWN; ++k; break; }
+    }
+    m_eff[p] = k;
+    rc = hf_tridiag_readout(alpha + (int64_t)p * m, beta + (int64_t)p * m, k, ritz + (int64_t)p * m,
+                            weights + (int64_t)p * m, nullptr);
+    if (rc != HF_OK) return c->fail(rc, "hf_slq: read-out failed");
+  }
+  return status;
+}
+
+}  // extern "C"

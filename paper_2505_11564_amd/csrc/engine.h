@@ -1,0 +1,94 @@
+// Context of libhessformer_hip: model description, canonical layout, device
+// workspace, and the host-side schedules of the Hessian-vector product
+// (Algorithm 1 of the paper, evaluated forward-over-reverse) and of the
+// Lanczos iteration (Algorithm 2).
+#pragma once
+
+#include "hf_internal.h"
+#include "lanczos.h"
+
+namespace hf {
+
+struct LayoutEntry {
+  std::string name;
+  int64_t offset;
+  int64_t shape[2];
+  int64_t count() const { return shape[0] * (shape[1] ? shape[1] : 1); }
+};
+
+// Fills `out` with the canonical flat order; returns HF_OK or HF_EINVAL.
+int build_layout(const hf_model_desc& d, std::vector<LayoutEntry>& out, std::string* why);
+
+// Offsets (elements) of one transformer layer's tensors in the flat vector.
+struct LayerOff {
+  int64_t n1g = -1, n1b = -1, wqkv = -1, bqkv = -1, wq = -1, wk = -1, wv = -1, wo = -1, bo = -1;
+  int64_t n2g = -1, n2b = -1, wfc = -1, bfc = -1, wproj = -1, bproj = -1, wgate = -1, wup = -1, wdown = -1;
+};
+
+// Device buffers of one layer kept from the forward pass for the backward
+// pass (each with its tangent twin `*_t`).
+struct LayerBuf {
+  float *x1, *x1_t, *x2, *x2_t, *st1, *st2;          // residual stream, norm statistics
+  void *a, *a_t, *qkv, *qkv_t, *P, *P_t, *o, *o_t;   // attention branch
+  void *m, *m_t, *f, *f_t, *g, *g_t;                 // MLP branch: norm out, pre-activation, activation out
+  void *up, *up_t;                                   // LLAMA: up projection (f = gate)
+};
+
+}  // namespace hf
+
+struct hf_ctx {
+  hf_model_desc desc;
+  int device = 0;
+  int max_batch = 0, max_m = 0;
+  int bf = 0;  // 1: bf16 parameters / operands
+  int64_t n = 0;
+  std::vector<hf::LayoutEntry> layout;
+  std::vector<hf::LayerOff> loff;
+  int64_t off_wte = -1, off_wpe = -1, off_nfg = -1, off_nfb = -1, off_head = -1;
+  int64_t off_w1 = -1, off_b1 = -1, off_w2 = -1, off_b2 = -1;
+  std::vector<std::pair<int64_t, int64_t>> zero_ranges;  // H v regions filled by atomics
+  std::string err;
+
+  // device memory
+  char* arena = nullptr;
+  int64_t arena_bytes = 0;
+  std::vector<hf::LayerBuf> lb;
+  hf::bf16* vb = nullptr;  // bf16 copy of the direction (bf16 mode)
+  float *xL = nullptr, *xL_t = nullptr, *stf = nullptr;
+  void *xf = nullptr, *xf_t = nullptr;
+  float *z = nullptr, *z_t = nullptr;
+  void *dz = nullptr, *dz_t = nullptr;
+  int64_t ldz = 0;
+  float* loss_rows = nullptr;
+  float *sc = nullptr, *sc_t = nullptr;
+  void *dS = nullptr, *dS_t = nullptr;
+  float *dx = nullptr, *dx_t = nullptr, *tmpd = nullptr, *tmpd_t = nullptr;
+  void *dxb = nullptr, *dxb_t = nullptr, *dob = nullptr, *dob_t = nullptr;
+  void *dqkv = nullptr, *dqkv_t = nullptr;
+  void *dg = nullptr, *dg_t = nullptr, *dup = nullptr, *dup_t = nullptr, *dy = nullptr, *dy_t = nullptr;
+  void* xin = nullptr;  // MLP input in operand type (bf16 mode)
+  int* flags = nullptr;  // [0] error bits, [1] number of valid labels
+  double* loss_dev = nullptr;
+
+  // Lanczos state
+  float* lz_vec[3] = {nullptr, nullptr, nullptr};  // rotating q, q_prev, r
+  int iq = 0, iqp = 1, ir = 2;
+  void* basis = nullptr;
+  int64_t ldq = 0;
+  double *scal = nullptr, *cvec = nullptr, *partials = nullptr;
+  double* host_scal = nullptr;  // pinned, S_COUNT + 2 doubles
+  int lz_k = -1;                // iterations done; -1 = not initialised
+  int lz_reorth = 0;
+  int lz_done = 0;
+
+  int fail(int code, const std::string& m) { err = m; return code; }
+  int plan_and_alloc();
+  int hvp_enqueue(const void* params, const void* inputs, const int32_t* labels, int batch, int seq, const float* v,
+                  float* out, hipStream_t st);
+  int hvp_mlp(const void* params, const void* inputs, const int32_t* labels, int B, const float* v, float* out,
+              hipStream_t st);
+  int hvp_transformer(const void* params, const int32_t* tok, const int32_t* labels, int B, int S, const float* v,
+                      float* out, hipStream_t st);
+  int finish_hvp(double* loss_host, hipStream_t st);
+  int lanczos_update(float* r, double tol, double* alpha_k, double* beta_k, hipStream_t st);
+};

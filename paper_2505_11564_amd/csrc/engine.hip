@@ -1,0 +1,510 @@
+// Host-side schedule of the Hessian-vector product: Algorithm 1 of the paper
+// (u = d<dL/dp, v>/dp on one batch) evaluated forward-over-reverse.  One sweep
+// forward computes every activation a together with its tangent a_t (its
+// derivative along the parameter direction v); one sweep backward computes
+// every adjoint da with its tangent da_t and emits, per parameter tensor, only
+// the H v block (the tangent of the gradient); the plain gradient is never
+// formed.  For a linear layer Y = X W + b:
+//   Y_t = X_t W + X W_t + b_t          dX   = dY W^T
+//   dX_t = dY_t W^T + dY W_t^T         (Hv)_W = X_t^T dY + X^T dY_t
+//   (Hv)_b = column sums of dY_t
+#include "engine.h"
+
+#include <algorithm>
+#include <cmath>
+
+using namespace hf;
+
+// ------------------------------------------------------------------ layout ----
+
+int hf::build_layout(const hf_model_desc& d, std::vector<LayoutEntry>& out, std::string* why) {
+  out.clear();
+  int64_t off = 0;
+  auto add = [&](const std::string& nm, int64_t a, int64_t b) {
+    LayoutEntry e;
+    e.name = nm; e.offset = off; e.shape[0] = a; e.shape[1] = b;
+    off += e.count();
+    out.push_back(e);
+  };
+  auto bad = [&](const char* m) { if (why) *why = m; return (int)HF_EINVAL; };
+  if (d.param_dtype != HF_F32 && d.param_dtype != HF_BF16) return bad("param_dtype must be HF_F32 or HF_BF16");
+  if (d.basis_dtype != HF_F32 && d.basis_dtype != HF_BF16) return bad("basis_dtype must be HF_F32 or HF_BF16");
+  if (d.arch == HF_ARCH_MLP) {
+    if (d.mlp_in <= 0 || d.mlp_hidden <= 0 || d.mlp_out <= 1) return bad("MLP sizes must be positive (mlp_out >= 2)");
+    add("W1", d.mlp_in, d.mlp_hidden); add("b1", d.mlp_hidden, 0);
+    add("W2", d.mlp_hidden, d.mlp_out); add("b2", d.mlp_out, 0);
+    return HF_OK;
+  }
+  if (d.arch != HF_ARCH_GPT && d.arch != HF_ARCH_LLAMA) return bad("unknown arch");
+  if (d.n_layer <= 0 || d.d_model <= 0 || d.n_head <= 0 || d.d_ff <= 0 || d.vocab <= 1 || d.max_seq <= 0)
+    return bad("transformer sizes must be positive");
+  if (d.d_model % d.n_head) return bad("d_model must be a multiple of n_head");
+  if (d.d_model > 8192) return bad("d_model > 8192 is not supported by the norm kernels");
+  if (!(d.norm_eps > 0.f)) return bad("norm_eps must be positive");
+  const int64_t D = d.d_model, F = d.d_ff, V = d.vocab;
+  if (d.arch == HF_ARCH_GPT) {
+    add("wte", V, D); add("wpe", d.max_seq, D);
+    for (int l = 0; l < d.n_layer; ++l) {
+      const std::string p = "h" + std::to_string(l) + ".";
+      add(p + "ln1.g", D, 0); add(p + "ln1.b", D, 0);
+      add(p + "Wqkv", D, 3 * D); add(p + "bqkv", 3 * D, 0);
+      add(p + "Wo", D, D); add(p + "bo", D, 0);
+      add(p + "ln2.g", D, 0); add(p + "ln2.b", D, 0);
+      add(p + "Wfc", D, F); add(p + "bfc", F, 0);
+      add(p + "Wproj", F, D); add(p + "bproj", D, 0);
+    }
+    add("lnf.g", D, 0); add("lnf.b", D, 0);
+    if (!d.tie_embeddings) add("lm_head", D, V);
+  } else {
+    if ((d.d_model / d.n_head) % 2) return bad("rotary embedding needs an even head width");
+    if (!(d.rope_theta > 0.f)) return bad("rope_theta must be positive");
+    add("wte", V, D);
+    for (int l = 0; l < d.n_layer; ++l) {
+      const std::string p = "h" + std::to_string(l) + ".";
+      add(p + "rms1.g", D, 0);
+      add(p + "Wq", D, D); add(p + "Wk", D, D); add(p + "Wv", D, D); add(p + "Wo", D, D);
+      add(p + "rms2.g", D, 0);
+      add(p + "Wgate", D, F); add(p + "Wup", D, F); add(p + "Wdown", F, D);
+    }
+    add("rmsf.g", D, 0); add("lm_head", D, V);
+  }
+  return HF_OK;
+}
+
+// --------------------------------------------------------------- workspace ----
+
+namespace {
+struct Planner {
+  int64_t off = 0;
+  std::vector<std::pair<void**, int64_t>> fix;
+  template <typename T>
+  void add(T*& ptr, int64_t bytes) {
+    fix.push_back({(void**)&ptr, off});
+    off += (std::max<int64_t>(bytes, 1) + 255) / 256 * 256;
+  }
+};
+int64_t round_up(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
+}  // namespace
+
+int hf_ctx::plan_and_alloc() {
+  Planner pl;
+  const int64_t e = bf ? 2 : 4;
+  if (desc.arch == HF_ARCH_MLP) {
+    const int64_t B = max_batch, Hd = desc.mlp_hidden, O = desc.mlp_out;
+    lb.resize(1);
+    LayerBuf& b = lb[0];
+    b = LayerBuf{};
+    pl.add(b.f, B * Hd * e); pl.add(b.f_t, B * Hd * e);
+    pl.add(b.g, B * Hd * e); pl.add(b.g_t, B * Hd * e);
+    pl.add(dg, B * Hd * e); pl.add(dg_t, B * Hd * e);
+    ldz = round_up(O, 8);
+    pl.add(z, B * ldz * 4); pl.add(z_t, B * ldz * 4);
+    pl.add(dz, B * ldz * e); pl.add(dz_t, B * ldz * e);
+    pl.add(loss_rows, B * 4);
+    if (bf) pl.add(xin, B * desc.mlp_in * e);
+  } else {
+    const int64_t S = desc.max_seq, B = max_batch, T = B * S, D = desc.d_model, F = desc.d_ff, H = desc.n_head;
+    const int64_t SS = B * H * S * S;
+    const bool llama = desc.arch == HF_ARCH_LLAMA;
+    lb.resize(desc.n_layer);
+    for (auto& b : lb) {
+      b = LayerBuf{};
+      pl.add(b.x1, T * D * 4); pl.add(b.x1_t, T * D * 4); pl.add(b.x2, T * D * 4); pl.add(b.x2_t, T * D * 4);
+      pl.add(b.st1, T * 16); pl.add(b.st2, T * 16);
+      pl.add(b.a, T * D * e); pl.add(b.a_t, T * D * e);
+      pl.add(b.qkv, T * 3 * D * e); pl.add(b.qkv_t, T * 3 * D * e);
+      pl.add(b.P, SS * e); pl.add(b.P_t, SS * e);
+      pl.add(b.o, T * D * e); pl.add(b.o_t, T * D * e);
+      pl.add(b.m, T * D * e); pl.add(b.m_t, T * D * e);
+      pl.add(b.f, T * F * e); pl.add(b.f_t, T * F * e);
+      pl.add(b.g, T * F * e); pl.add(b.g_t, T * F * e);
+      if (llama) { pl.add(b.up, T * F * e); pl.add(b.up_t, T * F * e); }
+    }
+    pl.add(xL, T * D * 4); pl.add(xL_t, T * D * 4); pl.add(stf, T * 16);
+    pl.add(xf, T * D * e); pl.add(xf_t, T * D * e);
+    ldz = round_up(desc.vocab, 64);
+    pl.add(z, T * ldz * 4); pl.add(z_t, T * ldz * 4);
+    pl.add(dz, T * ldz * e); pl.add(dz_t, T * ldz * e);
+    pl.add(loss_rows, T * 4);
+    pl.add(sc, SS * 4); pl.add(sc_t, SS * 4);
+    pl.add(dS, SS * e); pl.add(dS_t, SS * e);
+    pl.add(dx, T * D * 4); pl.add(dx_t, T * D * 4); pl.add(tmpd, T * D * 4); pl.add(tmpd_t, T * D * 4);
+    if (bf) { pl.add(dxb, T * D * e); pl.add(dxb_t, T * D * e); }
+    pl.add(dob, T * D * e); pl.add(dob_t, T * D * e);
+    pl.add(dqkv, T * 3 * D * e); pl.add(dqkv_t, T * 3 * D * e);
+    pl.add(dg, T * F * e); pl.add(dg_t, T * F * e);
+    if (llama) {
+      pl.add(dup, T * F * e); pl.add(dup_t, T * F * e);
+      pl.add(dy, T * F * e); pl.add(dy_t, T * F * e);
+    }
+  }
+  if (bf) pl.add(vb, n * 2);
+  pl.add(flags, 64);
+  pl.add(loss_dev, 64);
+  // Lanczos
+  if (max_m > 0) {
+    for (int i = 0; i < 3; ++i) pl.add(lz_vec[i], n * 4);
+    ldq = round_up(n, 64);
+    pl.add(basis, (int64_t)max_m * ldq * (desc.basis_dtype == HF_BF16 ? 2 : 4));
+    pl.add(scal, S_COUNT * 8);
+    pl.add(cvec, (int64_t)max_m * 8);
+    pl.add(partials, (int64_t)LZ_NBLK * max_m * 8);
+  }
+  arena_bytes = pl.off;
+  hipError_t e1 = hipMalloc((void**)&arena, (size_t)arena_bytes);
+  if (e1 != hipSuccess) {
+    arena = nullptr;
+    (void)hipGetLastError();
+    return fail(HF_ENOMEM, "hipMalloc of " + std::to_string(arena_bytes) + " bytes failed: " + hipGetErrorString(e1));
+  }
+  for (auto& f : pl.fix) *f.first = arena + f.second;
+  if (!bf) { dxb = dx; dxb_t = dx_t; }
+  if (max_m > 0) {
+    e1 = hipHostMalloc((void**)&host_scal, (S_COUNT + 2) * sizeof(double), hipHostMallocDefault);
+    if (e1 != hipSuccess) return fail(HF_ENOMEM, std::string("hipHostMalloc failed: ") + hipGetErrorString(e1));
+  }
+  return HF_OK;
+}
+
+// ------------------------------------------------------------ GEMM helpers ----
+
+namespace {
+
+#define CK(expr)                                                                                   \
+  do {                                                                                             \
+    hipError_t e_ = (expr);                                                                        \
+    if (e_ != hipSuccess) return c->fail(HF_EDEVICE, std::string(#expr) + ": " + hipGetErrorString(e_)); \
+  } while (0)
+
+struct Lin {
+  hf_ctx* c;
+  const void* params;
+  const float* v;
+  float* out;
+  hipStream_t st;
+  int bf;
+  const void* Wp(int64_t off) const { return (const char*)params + off * (bf ? 2 : 4); }
+  const void* Wt(int64_t off) const { return bf ? (const void*)(c->vb + off) : (const void*)(v + off); }
+
+  // Y = X W (+ b) (+ add);  Y_t = X_t W + X W_t (+ b_t) (+ add_t).   W: [K, N] at woff.
+  // X_t == nullptr means a zero input tangent.
+  int fwd(const void* X, const void* X_t, int M, int K, int N, int64_t ldx, int64_t woff, int64_t boff, void* Y,
+          void* Y_t, int64_t ldy, int out_bf16, const float* add = nullptr, const float* add_t = nullptr,
+          int transW = 0, int64_t ldw = -1) const {
+    Gemm g;
+    g.M = M; g.N = N; g.K = K; g.lda = ldx; g.ldb = ldw < 0 ? N : ldw; g.ldc = ldy; g.transB = transW;
+    g.in_bf16 = bf; g.out_bf16 = out_bf16;
+    g.A[0] = X; g.B[0] = Wp(woff); g.C = Y; g.Cadd = add;
+    if (boff >= 0) g.bias = Wp(boff);
+    CK(launch_gemm(g, st));
+    Gemm t = g;
+    t.C = Y_t; t.Cadd = add_t; t.bias = nullptr;
+    if (boff >= 0) t.bias_t = v + boff;
+    if (X_t) { t.A[0] = X_t; t.B[0] = Wp(woff); t.A[1] = X; t.B[1] = Wt(woff); }
+    else { t.A[0] = X; t.B[0] = Wt(woff); }
+    CK(launch_gemm(t, st));
+    return HF_OK;
+  }
+
+  // dX = dY W^T (+ add);  dX_t = dY_t W^T + dY W_t^T (+ add_t).   W: [K_in, N_out] at woff.
+  int bwd_dx(const void* dY, const void* dY_t, int M, int Kin, int Nout, int64_t lddy, int64_t woff, void* dX,
+             void* dX_t, int64_t lddx, int out_bf16, const float* add = nullptr, const float* add_t = nullptr,
+             int transW = 0, int64_t ldw = -1) const {
+    Gemm g;
+    g.M = M; g.N = Kin; g.K = Nout; g.lda = lddy; g.ldb = ldw < 0 ? Nout : ldw; g.ldc = lddx; g.transB = !transW;
+    g.in_bf16 = bf; g.out_bf16 = out_bf16;
+    g.A[0] = dY; g.B[0] = Wp(woff); g.C = dX; g.Cadd = add;
+    CK(launch_gemm(g, st));
+    Gemm t = g;
+    t.C = dX_t; t.Cadd = add_t;
+    t.A[0] = dY_t; t.B[0] = Wp(woff); t.A[1] = dY; t.B[1] = Wt(woff);
+    CK(launch_gemm(t, st));
+    return HF_OK;
+  }
+
+  // (Hv)_W = X_t^T dY + X^T dY_t  -> out[woff] as [Kin, Nout];  (Hv)_b += colsum(dY_t).
+  int bwd_dw(const void* X, const void* X_t, const void* dY, const void* dY_t, int T, int Kin, int Nout, int64_t ldx,
+             int64_t lddy, int64_t woff, int64_t boff, const void* dYt_for_bias, int bias_src_bf16) const {
+    Gemm g;
+    g.M = Kin; g.N = Nout; g.K = T; g.lda = ldx; g.ldb = lddy; g.ldc = Nout; g.transA = 1;
+    g.in_bf16 = bf; g.out_bf16 = 0;
+    g.C = out + woff;
+    if (X_t) { g.A[0] = X_t; g.B[0] = dY; g.A[1] = X; g.B[1] = dY_t; }
+    else { g.A[0] = X; g.B[0] = dY_t; }
+    CK(launch_gemm(g, st));
+    if (boff >= 0) CK(launch_colsum(bias_src_bf16, dYt_for_bias, T, Nout, lddy, out + boff, st));
+    return HF_OK;
+  }
+};
+
+}  // namespace
+
+// ------------------------------------------------------------------- common ----
+
+int hf_ctx::hvp_enqueue(const void* params, const void* inputs, const int32_t* labels, int batch, int seq,
+                        const float* v, float* out, hipStream_t st) {
+  hf_ctx* c = this;
+  if (!params || !inputs || !labels || !v || !out) return fail(HF_EINVAL, "hf_hvp: NULL pointer argument");
+  if (((uintptr_t)v | (uintptr_t)out | (uintptr_t)params) & 15) return fail(HF_EINVAL, "hf_hvp: params, v and out must be 16-byte aligned");
+  if (batch <= 0 || batch > max_batch) return fail(HF_ESHAPE, "hf_hvp: batch outside [1, max_batch]");
+  if (desc.arch != HF_ARCH_MLP && (seq <= 0 || seq > desc.max_seq)) return fail(HF_ESHAPE, "hf_hvp: seq outside [1, max_seq]");
+  if (desc.arch != HF_ARCH_MLP && (int64_t)batch * seq > (int64_t)max_batch * desc.max_seq) return fail(HF_ESHAPE, "hf_hvp: too many tokens");
+  CK(launch_fill_f32((float*)flags, 2, 0.f, st));
+  for (auto& zr : zero_ranges) CK(launch_fill_f32(out + zr.first, zr.second, 0.f, st));
+  if (bf) CK(launch_f32_to_bf16(v, vb, n, st));
+  if (desc.arch == HF_ARCH_MLP) return hvp_mlp(params, inputs, labels, batch, v, out, st);
+  return hvp_transformer(params, (const int32_t*)inputs, labels, batch, seq, v, out, st);
+}
+
+int hf_ctx::finish_hvp(double* loss_host, hipStream_t st) {
+  hf_ctx* c = this;
+  struct { int flags[2]; double loss; } h;
+  CK(hipMemcpyAsync(h.flags, flags, 2 * sizeof(int), hipMemcpyDeviceToHost, st));
+  CK(hipMemcpyAsync(&h.loss, loss_dev, sizeof(double), hipMemcpyDeviceToHost, st));
+  CK(hipStreamSynchronize(st));
+  if (h.flags[0] & 1) return fail(HF_EINVAL, "token id outside [0, vocab)");
+  if (h.flags[0] & 2) return fail(HF_EINVAL, "label >= number of classes");
+  if (h.flags[1] == 0) return fail(HF_EINVAL, "no valid label in the batch");
+  if (loss_host) *loss_host = h.loss;
+  return HF_OK;
+}
+
+// ---------------------------------------------------------------------- MLP ----
+
+int hf_ctx::hvp_mlp(const void* params, const void* inputs, const int32_t* labels, int B, const float* v, float* out,
+                    hipStream_t st) {
+  hf_ctx* c = this;
+  const int I = desc.mlp_in, Hd = desc.mlp_hidden, O = desc.mlp_out;
+  Lin L{this, params, v, out, st, bf};
+  LayerBuf& b = lb[0];
+  const void* X = inputs;
+  if (bf) { CK(launch_f32_to_bf16((const float*)inputs, (bf16*)xin, (int64_t)B * I, st)); X = xin; }
+  int rc;
+  if ((rc = L.fwd(X, nullptr, B, I, Hd, I, off_w1, off_b1, b.f, b.f_t, Hd, bf))) return rc;
+  CK(launch_act_fwd(bf, ACT_TANH, b.f, b.f_t, b.g, b.g_t, (int64_t)B * Hd, st));
+  if ((rc = L.fwd(b.g, b.g_t, B, Hd, O, Hd, off_w2, off_b2, z, z_t, ldz, 0))) return rc;
+  CK(launch_count_valid(labels, B, O, flags + 1, flags, st));
+  CK(launch_ce(bf, z, z_t, labels, flags + 1, B, O, ldz, dz, dz_t, loss_rows, st));
+  CK(launch_sum_rows_f64(loss_rows, B, flags + 1, loss_dev, st));
+  if ((rc = L.bwd_dw(b.g, b.g_t, dz, dz_t, B, Hd, O, Hd, ldz, off_w2, off_b2, dz_t, bf))) return rc;
+  if ((rc = L.bwd_dx(dz, dz_t, B, Hd, O, ldz, off_w2, dg, dg_t, Hd, bf))) return rc;
+  CK(launch_act_bwd(bf, ACT_TANH, b.f, b.f_t, dg, dg_t, dg, dg_t, (int64_t)B * Hd, st));
+  if ((rc = L.bwd_dw(X, nullptr, dg, dg_t, B, I, Hd, I, Hd, off_w1, off_b1, dg_t, bf))) return rc;
+  return HF_OK;
+}
+
+// -------------------------------------------------------------- transformer ----
+
+int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_t* labels, int B, int S,
+                            const float* v, float* out, hipStream_t st) {
+  hf_ctx* c = this;
+  const int D = desc.d_model, H = desc.n_head, dh = D / H, F = desc.d_ff, V = desc.vocab, NL = desc.n_layer;
+  const int T = B * S;
+  const bool llama = desc.arch == HF_ARCH_LLAMA;
+  const int rms = llama ? 1 : 0;
+  const float eps = desc.norm_eps;
+  const float cs = 1.f / sqrtf((float)dh);
+  const int64_t e = bf ? 2 : 4;
+  Lin L{this, params, v, out, st, bf};
+  auto at = [&](void* p, int64_t elems) -> void* { return (char*)p + elems * e; };
+  auto cat = [&](const void* p, int64_t elems) -> const void* { return (const char*)p + elems * e; };
+  int rc;
+
+  // Batched per-(batch, head) attention products.  Scores are [B,H,S,S].
+  const int64_t SS = (int64_t)S * S;
+  auto att = [&](Gemm& g) {
+    g.nb1 = B; g.nb2 = H; g.in_bf16 = bf;
+  };
+  auto set_qkv = [&](int64_t& s1, int64_t& s2) { s1 = (int64_t)S * 3 * D; s2 = dh; };
+  auto set_sc = [&](int64_t& s1, int64_t& s2) { s1 = (int64_t)H * SS; s2 = SS; };
+  auto set_td = [&](int64_t& s1, int64_t& s2) { s1 = (int64_t)S * D; s2 = dh; };
+
+  // ------------------------------ forward with tangents ----------------------
+  CK(launch_embed_fwd(bf, L.Wp(off_wte), llama ? nullptr : L.Wp(off_wpe), v + off_wte, llama ? nullptr : v + off_wpe,
+                      tok, T, S, D, V, lb[0].x1, lb[0].x1_t, flags, st));
+  for (int l = 0; l < NL; ++l) {
+    LayerBuf& b = lb[l];
+    const LayerOff& o = loff[l];
+    float* xn = (l + 1 < NL) ? lb[l + 1].x1 : xL;
+    float* xn_t = (l + 1 < NL) ? lb[l + 1].x1_t : xL_t;
+    CK(launch_norm_fwd(bf, rms, b.x1, b.x1_t, L.Wp(o.n1g), rms ? nullptr : L.Wp(o.n1b), v + o.n1g,
+                       rms ? nullptr : v + o.n1b, T, D, eps, b.a, b.a_t, b.st1, st));
+    if (!llama) {
+      if ((rc = L.fwd(b.a, b.a_t, T, D, 3 * D, D, o.wqkv, o.bqkv, b.qkv, b.qkv_t, 3 * D, bf))) return rc;
+    } else {
+      const int64_t w3[3] = {o.wq, o.wk, o.wv};
+      for (int i = 0; i < 3; ++i)
+        if ((rc = L.fwd(b.a, b.a_t, T, D, D, D, w3[i], -1, at(b.qkv, (int64_t)i * D), at(b.qkv_t, (int64_t)i * D), 3 * D, bf))) return rc;
+      CK(launch_rope(bf, b.qkv, b.qkv_t, T, S, 3 * D, 2 * H, dh, desc.rope_theta, 0, st));
+    }
+    {  // scores S = c Q K^T, S_t = c (Q_t K^T + Q K_t^T); lower-triangular tiles only
+      Gemm g; att(g);
+      g.M = S; g.N = S; g.K = dh; g.lda = 3 * D; g.ldb = 3 * D; g.ldc = S; g.transB = 1; g.alpha = cs; g.skip_upper = 1;
+      set_qkv(g.sA1, g.sA2); set_qkv(g.sB1, g.sB2); set_sc(g.sC1, g.sC2);
+      g.A[0] = b.qkv; g.B[0] = cat(b.qkv, D); g.C = sc;
+      CK(launch_gemm(g, st));
+      g.A[0] = b.qkv_t; g.B[0] = cat(b.qkv, D); g.A[1] = b.qkv; g.B[1] = cat(b.qkv_t, D); g.C = sc_t;
+      CK(launch_gemm(g, st));
+    }
+    CK(launch_softmax_fwd(bf, sc, sc_t, b.P, b.P_t, B * H, S, st));
+    {  // O = P V, O_t = P_t V + P V_t
+      Gemm g; att(g);
+      g.M = S; g.N = dh; g.K = S; g.lda = S; g.ldb = 3 * D; g.ldc = D; g.klimit = 1; g.out_bf16 = bf;
+      set_sc(g.sA1, g.sA2); set_qkv(g.sB1, g.sB2); set_td(g.sC1, g.sC2);
+      g.A[0] = b.P; g.B[0] = cat(b.qkv, 2 * D); g.C = b.o;
+      CK(launch_gemm(g, st));
+      g.A[0] = b.P_t; g.B[0] = cat(b.qkv, 2 * D); g.A[1] = b.P; g.B[1] = cat(b.qkv_t, 2 * D); g.C = b.o_t;
+      CK(launch_gemm(g, st));
+    }
+    if ((rc = L.fwd(b.o, b.o_t, T, D, D, D, o.wo, o.bo, b.x2, b.x2_t, D, 0, b.x1, b.x1_t))) return rc;
+    CK(launch_norm_fwd(bf, rms, b.x2, b.x2_t, L.Wp(o.n2g), rms ? nullptr : L.Wp(o.n2b), v + o.n2g,
+                       rms ? nullptr : v + o.n2b, T, D, eps, b.m, b.m_t, b.st2, st));
+    if (!llama) {
+      if ((rc = L.fwd(b.m, b.m_t, T, D, F, D, o.wfc, o.bfc, b.f, b.f_t, F, bf))) return rc;
+      CK(launch_act_fwd(bf, ACT_GELU, b.f, b.f_t, b.g, b.g_t, (int64_t)T * F, st));
+      if ((rc = L.fwd(b.g, b.g_t, T, F, D, F, o.wproj, o.bproj, xn, xn_t, D, 0, b.x2, b.x2_t))) return rc;
+    } else {
+      if ((rc = L.fwd(b.m, b.m_t, T, D, F, D, o.wgate, -1, b.f, b.f_t, F, bf))) return rc;
+      if ((rc = L.fwd(b.m, b.m_t, T, D, F, D, o.wup, -1, b.up, b.up_t, F, bf))) return rc;
+      CK(launch_swiglu_fwd(bf, b.f, b.f_t, b.up, b.up_t, b.g, b.g_t, (int64_t)T * F, st));
+      if ((rc = L.fwd(b.g, b.g_t, T, F, D, F, o.wdown, -1, xn, xn_t, D, 0, b.x2, b.x2_t))) return rc;
+    }
+  }
+  CK(launch_norm_fwd(bf, rms, xL, xL_t, L.Wp(off_nfg), rms ? nullptr : L.Wp(off_nfb), v + off_nfg,
+                     rms ? nullptr : v + off_nfb, T, D, eps, xf, xf_t, stf, st));
+  const bool tied = off_head < 0;
+  if (tied) { if ((rc = L.fwd(xf, xf_t, T, D, V, D, off_wte, -1, z, z_t, ldz, 0, nullptr, nullptr, 1, D))) return rc; }
+  else { if ((rc = L.fwd(xf, xf_t, T, D, V, D, off_head, -1, z, z_t, ldz, 0))) return rc; }
+
+  // ------------------------------ loss and adjoint seeds ----------------------
+  CK(launch_count_valid(labels, T, V, flags + 1, flags, st));
+  CK(launch_ce(bf, z, z_t, labels, flags + 1, T, V, ldz, dz, dz_t, loss_rows, st));
+  CK(launch_sum_rows_f64(loss_rows, T, flags + 1, loss_dev, st));
+
+  // ------------------------------ backward with tangents ----------------------
+  if (tied) {
+    // z = xf wte^T:  (Hv)_wte = dz_t^T xf + dz^T xf_t  [V, D];  dxf = dz wte
+    Gemm g;
+    g.M = V; g.N = D; g.K = T; g.lda = ldz; g.ldb = D; g.ldc = D; g.transA = 1; g.in_bf16 = bf;
+    g.A[0] = dz_t; g.B[0] = xf; g.A[1] = dz; g.B[1] = xf_t; g.C = out + off_wte;
+    CK(launch_gemm(g, st));
+    if ((rc = L.bwd_dx(dz, dz_t, T, D, V, ldz, off_wte, tmpd, tmpd_t, D, 0, nullptr, nullptr, 1, D))) return rc;
+  } else {
+    if ((rc = L.bwd_dw(xf, xf_t, dz, dz_t, T, D, V, D, ldz, off_head, -1, nullptr, 0))) return rc;
+    if ((rc = L.bwd_dx(dz, dz_t, T, D, V, ldz, off_head, tmpd, tmpd_t, D, 0))) return rc;
+  }
+  CK(launch_norm_bwd(bf, rms, tmpd, tmpd_t, xL, xL_t, stf, L.Wp(off_nfg), v + off_nfg, T, D, 0, dx, dx_t,
+                     out + off_nfg, rms ? nullptr : out + off_nfb, st));
+
+  for (int l = NL - 1; l >= 0; --l) {
+    LayerBuf& b = lb[l];
+    const LayerOff& o = loff[l];
+    // ---- MLP branch
+    if (bf) CK(launch_cast_pair(1, dx, dx_t, dxb, dxb_t, (int64_t)T * D, st));
+    if (!llama) {
+      if ((rc = L.bwd_dw(b.g, b.g_t, dxb, dxb_t, T, F, D, F, D, o.wproj, o.bproj, dx_t, 0))) return rc;
+      if ((rc = L.bwd_dx(dxb, dxb_t, T, F, D, D, o.wproj, dg, dg_t, F, bf))) return rc;
+      CK(launch_act_bwd(bf, ACT_GELU, b.f, b.f_t, dg, dg_t, dg, dg_t, (int64_t)T * F, st));
+      if ((rc = L.bwd_dw(b.m, b.m_t, dg, dg_t, T, D, F, D, F, o.wfc, o.bfc, dg_t, bf))) return rc;
+      if ((rc = L.bwd_dx(dg, dg_t, T, D, F, F, o.wfc, tmpd, tmpd_t, D, 0))) return rc;
+    } else {
+      if ((rc = L.bwd_dw(b.g, b.g_t, dxb, dxb_t, T, F, D, F, D, o.wdown, -1, nullptr, 0))) return rc;
+      if ((rc = L.bwd_dx(dxb, dxb_t, T, F, D, D, o.wdown, dy, dy_t, F, bf))) return rc;
+      CK(launch_swiglu_bwd(bf, b.f, b.f_t, b.up, b.up_t, dy, dy_t, dg, dg_t, dup, dup_t, (int64_t)T * F, st));
+      if ((rc = L.bwd_dw(b.m, b.m_t, dg, dg_t, T, D, F, D, F, o.wgate, -1, nullptr, 0))) return rc;
+      if ((rc = L.bwd_dw(b.m, b.m_t, dup, dup_t, T, D, F, D, F, o.wup, -1, nullptr, 0))) return rc;
+      if ((rc = L.bwd_dx(dg, dg_t, T, D, F, F, o.wgate, tmpd, tmpd_t, D, 0))) return rc;
+      if ((rc = L.bwd_dx(dup, dup_t, T, D, F, F, o.wup, tmpd, tmpd_t, D, 0, tmpd, tmpd_t))) return rc;
+    }
+    CK(launch_norm_bwd(bf, rms, tmpd, tmpd_t, b.x2, b.x2_t, b.st2, L.Wp(o.n2g), v + o.n2g, T, D, 1, dx, dx_t,
+                       out + o.n2g, rms ? nullptr : out + o.n2b, st));
+    // ---- attention branch
+    if (bf) CK(launch_cast_pair(1, dx, dx_t, dxb, dxb_t, (int64_t)T * D, st));
+    if ((rc = L.bwd_dw(b.o, b.o_t, dxb, dxb_t, T, D, D, D, D, o.wo, o.bo, dx_t, 0))) return rc;
+    if ((rc = L.bwd_dx(dxb, dxb_t, T, D, D, D, o.wo, dob, dob_t, D, bf))) return rc;
+    {  // dV = P^T dO, dV_t = P_t^T dO + P^T dO_t   -> v third of dqkv
+      Gemm g; att(g);
+      g.M = S; g.N = dh; g.K = S; g.lda = S; g.ldb = D; g.ldc = 3 * D; g.transA = 1; g.klimit = 2; g.out_bf16 = bf;
+      set_sc(g.sA1, g.sA2); set_td(g.sB1, g.sB2); set_qkv(g.sC1, g.sC2);
+      g.A[0] = b.P; g.B[0] = dob; g.C = at(dqkv, 2 * D);
+      CK(launch_gemm(g, st));
+      g.A[0] = b.P_t; g.B[0] = dob; g.A[1] = b.P; g.B[1] = dob_t; g.C = at(dqkv_t, 2 * D);
+      CK(launch_gemm(g, st));
+    }
+    {  // dP = dO V^T, dP_t = dO_t V^T + dO V_t^T
+      Gemm g; att(g);
+      g.M = S; g.N = S; g.K = dh; g.lda = D; g.ldb = 3 * D; g.ldc = S; g.transB = 1; g.skip_upper = 1;
+      set_td(g.sA1, g.sA2); set_qkv(g.sB1, g.sB2); set_sc(g.sC1, g.sC2);
+      g.A[0] = dob; g.B[0] = cat(b.qkv, 2 * D); g.C = sc;
+      CK(launch_gemm(g, st));
+      g.A[0] = dob_t; g.B[0] = cat(b.qkv, 2 * D); g.A[1] = dob; g.B[1] = cat(b.qkv_t, 2 * D); g.C = sc_t;
+      CK(launch_gemm(g, st));
+    }
+    CK(launch_softmax_bwd(bf, b.P, b.P_t, sc, sc_t, dS, dS_t, B * H, S, st));
+    {  // dQ = c dS K, dQ_t = c (dS_t K + dS K_t)
+      Gemm g; att(g);
+      g.M = S; g.N = dh; g.K = S; g.lda = S; g.ldb = 3 * D; g.ldc = 3 * D; g.klimit = 1; g.alpha = cs; g.out_bf16 = bf;
+      set_sc(g.sA1, g.sA2); set_qkv(g.sB1, g.sB2); set_qkv(g.sC1, g.sC2);
+      g.A[0] = dS; g.B[0] = cat(b.qkv, D); g.C = dqkv;
+      CK(launch_gemm(g, st));
+      g.A[0] = dS_t; g.B[0] = cat(b.qkv, D); g.A[1] = dS; g.B[1] = cat(b.qkv_t, D); g.C = dqkv_t;
+      CK(launch_gemm(g, st));
+      // dK = c dS^T Q, dK_t = c (dS_t^T Q + dS^T Q_t)
+      g.transA = 1; g.klimit = 2;
+      g.A[0] = dS; g.B[0] = b.qkv; g.A[1] = nullptr; g.B[1] = nullptr; g.C = at(dqkv, D);
+      CK(launch_gemm(g, st));
+      g.A[0] = dS_t; g.B[0] = b.qkv; g.A[1] = dS; g.B[1] = b.qkv_t; g.C = at(dqkv_t, D);
+      CK(launch_gemm(g, st));
+    }
+    if (!llama) {
+      if ((rc = L.bwd_dw(b.a, b.a_t, dqkv, dqkv_t, T, D, 3 * D, D, 3 * D, o.wqkv, o.bqkv, dqkv_t, bf))) return rc;
+      if ((rc = L.bwd_dx(dqkv, dqkv_t, T, D, 3 * D, 3 * D, o.wqkv, tmpd, tmpd_t, D, 0))) return rc;
+    } else {
+      CK(launch_rope(bf, dqkv, dqkv_t, T, S, 3 * D, 2 * H, dh, desc.rope_theta, 1, st));
+      const int64_t w3[3] = {o.wq, o.wk, o.wv};
+      for (int i = 0; i < 3; ++i) {
+        const void* dyi = cat(dqkv, (int64_t)i * D);
+        const void* dyi_t = cat(dqkv_t, (int64_t)i * D);
+        if ((rc = L.bwd_dw(b.a, b.a_t, dyi, dyi_t, T, D, D, D, 3 * D, w3[i], -1, nullptr, 0))) return rc;
+        if ((rc = L.bwd_dx(dyi, dyi_t, T, D, D, 3 * D, w3[i], tmpd, tmpd_t, D, 0, i ? tmpd : nullptr, i ? tmpd_t : nullptr))) return rc;
+      }
+    }
+    CK(launch_norm_bwd(bf, rms, tmpd, tmpd_t, b.x1, b.x1_t, b.st1, L.Wp(o.n1g), v + o.n1g, T, D, 1, dx, dx_t,
+                       out + o.n1g, rms ? nullptr : out + o.n1b, st));
+  }
+  CK(launch_embed_bwd(dx_t, tok, T, S, D, V, out + off_wte, llama ? nullptr : out + off_wpe, st));
+  return HF_OK;
+}
+
+// ------------------------------------------------------------------ Lanczos ----
+
+int hf_ctx::lanczos_update(float* r, double tol, double* alpha_k, double* beta_k, hipStream_t st) {
+  hf_ctx* c = this;
+  const int k = lz_k;
+  const int bq = desc.basis_dtype == HF_BF16;
+  float* q = lz_vec[iq];
+  float* qp = lz_vec[iqp];
+  CK(lz_axpy_dot(r, q, qp, n, k > 0, scal, partials, st));
+  CK(lz_axpy_nrm(r, q, n, scal, partials, st));
+  if (lz_reorth == HF_REORTH_FULL) {
+    CK(lz_reorth_pass(basis, bq, ldq, r, n, k + 1, 0, scal, cvec, partials, st));
+    CK(lz_reorth_pass(basis, bq, ldq, r, n, k + 1, 1, scal, cvec, partials, st));
+  }
+  CK(hipMemcpyAsync(host_scal, scal, S_COUNT * sizeof(double), hipMemcpyDeviceToHost, st));
+  CK(hipStreamSynchronize(st));
+  const double a = host_scal[S_ALPHA], bt = host_scal[S_BETA];
+  if (alpha_k) *alpha_k = a;
+  if (beta_k) *beta_k = bt;
+  lz_k = k + 1;
+  if (!(bt >= tol) || !(bt > 0.0)) {  // also catches NaN
+    lz_done = 1;
+    return HF_EBREAKDOWN;
+  }
+  // q_{k+1} = r / beta_k into the q_{k-1} buffer, then rotate; beta_prev <- beta
+  void* bdst = nullptr;
+  if (lz_reorth == HF_REORTH_FULL && lz_k < max_m) bdst = (char*)basis + (int64_t)lz_k * ldq * (bq ? 2 : 4);
+  CK(lz_scale(r, qp, bdst, bq, n, scal, S_BETA, st));
+  CK(hipMemcpyAsync(scal + S_BETA_PREV, scal + S_BETA, sizeof(double), hipMemcpyDeviceToDevice, st));
+  std::swap(iq, iqp);
+  return HF_OK;
+}

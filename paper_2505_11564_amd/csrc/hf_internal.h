@@ -1,0 +1,126 @@
+// Internal declarations shared by the HIP sources of libhessformer_hip.
+// Nothing here is part of the C ABI (see include/hessformer.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "hessformer.h"
+
+namespace hf {
+
+typedef __bf16 bf16;
+
+// ---------------------------------------------------------------- errors ----
+
+struct Err {
+  int code = HF_OK;
+  std::string msg;
+};
+
+#define HF_HIP_TRY(expr)                                                        \
+  do {                                                                          \
+    hipError_t e_ = (expr);                                                     \
+    if (e_ != hipSuccess) {                                                     \
+      return fail(HF_EDEVICE, std::string(#expr) + ": " + hipGetErrorString(e_)); \
+    }                                                                           \
+  } while (0)
+
+// ------------------------------------------------------------- GEMM ----------
+
+// C[z] = alpha * (A0 op B0 + A1 op B1) + bias + bias_t + Cadd[z]
+//   A element (m,k): transA ? A[k*lda + m] : A[m*lda + k]
+//   B element (k,n): transB ? B[n*ldb + k] : B[k*ldb + n]
+//   batch z = z1*nb2 + z2, operand offset z1*s?1 + z2*s?2 (elements)
+//   in_bf16: A and B are bf16 (MFMA path) else fp32 (FMA path)
+//   out_bf16: C is bf16 else fp32.  Cadd (fp32, same ld/strides as C, may be C
+//   itself) only with fp32 C.  bias: per-column, type of the parameters;
+//   bias_t: per-column fp32.
+//   causal: 0 none; 1 = output tiles strictly above the diagonal are skipped
+//   (left untouched); 2 = k-range limited to k <= last row of the tile (A is
+//   lower triangular, e.g. P V); 3 = k-range limited to k >= first column...
+struct Gemm {
+  const void* A[2] = {nullptr, nullptr};
+  const void* B[2] = {nullptr, nullptr};
+  void* C = nullptr;
+  const float* Cadd = nullptr;
+  const void* bias = nullptr;
+  const float* bias_t = nullptr;
+  int M = 0, N = 0, K = 0;
+  int64_t lda = 0, ldb = 0, ldc = 0;
+  int transA = 0, transB = 0;
+  int nb1 = 1, nb2 = 1;
+  int64_t sA1 = 0, sA2 = 0, sB1 = 0, sB2 = 0, sC1 = 0, sC2 = 0;
+  float alpha = 1.f;
+  int in_bf16 = 0, out_bf16 = 0;
+  int klimit = 0;  // 0 none; 1: k <= row (A lower-triangular in (m,k));
+                   // 2: k >= m (A upper-triangular in (m,k))
+  int skip_upper = 0;  // skip output tiles with n0 > m_last (causal scores)
+};
+
+hipError_t launch_gemm(const Gemm& g, hipStream_t st);
+
+// -------------------------------------------------------- row / pointwise ----
+// AT = operand type of activations (float or bf16); PT = parameter type.
+// Launchers take `bf` = 1 for bf16 mode (AT = PT = bf16), 0 for fp32 mode.
+
+hipError_t launch_fill_f32(float* p, int64_t n, float val, hipStream_t st);
+hipError_t launch_f32_to_bf16(const float* src, bf16* dst, int64_t n, hipStream_t st);
+hipError_t launch_cast_pair(int bf, const float* a, const float* b, void* oa, void* ob, int64_t n, hipStream_t st);
+
+// x[t,:] = wte[tok[t],:] (+ wpe[t % S,:]) and the same gather of the direction.
+hipError_t launch_embed_fwd(int bf, const void* wte, const void* wpe, const float* wte_t, const float* wpe_t,
+                            const int32_t* tok, int T, int S, int d, int vocab, float* x, float* x_t,
+                            int* err_flag, hipStream_t st);
+// out_wte[tok[t],:] += dx_t[t,:]; out_wpe[t % S,:] += dx_t[t,:]   (atomic adds)
+hipError_t launch_embed_bwd(const float* dx_t, const int32_t* tok, int T, int S, int d, int vocab, float* out_wte,
+                            float* out_wpe, hipStream_t st);
+
+// LayerNorm (rms = 0) / RMSNorm (rms = 1) with tangent.  stats: [T,4].
+hipError_t launch_norm_fwd(int bf, int rms, const float* x, const float* x_t, const void* gam, const void* bet,
+                           const float* gam_t, const float* bet_t, int T, int d, float eps, void* y, void* y_t,
+                           float* stats, hipStream_t st);
+// dx (+)= ..., dx_t (+)= ...; hv_gam / hv_bet += column sums (atomic).
+hipError_t launch_norm_bwd(int bf, int rms, const float* dy, const float* dy_t, const float* x, const float* x_t,
+                           const float* stats, const void* gam, const float* gam_t, int T, int d, int accumulate,
+                           float* dx, float* dx_t, float* hv_gam, float* hv_bet, hipStream_t st);
+
+enum Act { ACT_TANH = 0, ACT_GELU = 1 };
+hipError_t launch_act_fwd(int bf, int act, const void* a, const void* a_t, void* y, void* y_t, int64_t n, hipStream_t st);
+hipError_t launch_act_bwd(int bf, int act, const void* a, const void* a_t, const void* dy, const void* dy_t, void* da,
+                          void* da_t, int64_t n, hipStream_t st);
+hipError_t launch_swiglu_fwd(int bf, const void* g, const void* g_t, const void* u, const void* u_t, void* y, void* y_t,
+                             int64_t n, hipStream_t st);
+hipError_t launch_swiglu_bwd(int bf, const void* g, const void* g_t, const void* u, const void* u_t, const void* dy,
+                             const void* dy_t, void* dg, void* dg_t, void* du, void* du_t, int64_t n, hipStream_t st);
+
+// Causal softmax over rows of scores [nbh, S, S] with tangent.
+hipError_t launch_softmax_fwd(int bf, const float* s, const float* s_t, void* p, void* p_t, int nbh, int S,
+                              hipStream_t st);
+hipError_t launch_softmax_bwd(int bf, const void* p, const void* p_t, const float* dp, const float* dp_t, void* ds,
+                              void* ds_t, int nbh, int S, hipStream_t st);
+
+// Rotary embedding of the q and k thirds... applied in place to [T, ld] rows,
+// n_head heads of width dh starting at column col0; inverse = transpose.
+hipError_t launch_rope(int bf, void* x, void* x_t, int T, int S, int64_t ld, int n_head, int dh, float theta,
+                       int inverse, hipStream_t st);
+
+// Softmax cross-entropy with tangent: dz, dz_t (operand type) from z, z_t
+// (fp32, leading dimension ldz); loss_rows[T] = per-row loss (0 if ignored);
+// n_valid: device int.  err_flag set if a label >= V.
+hipError_t launch_count_valid(const int32_t* labels, int T, int V, int* n_valid, int* err_flag, hipStream_t st);
+hipError_t launch_ce(int bf, const float* z, const float* z_t, const int32_t* labels, const int* n_valid, int T, int V,
+                     int64_t ldz, void* dz, void* dz_t, float* loss_rows, hipStream_t st);
+hipError_t launch_sum_rows_f64(const float* v, int n, const int* n_valid, double* out, hipStream_t st);
+
+// hv_b[c] = sum_rows y_t[r, c]   (y_t operand type or fp32)
+hipError_t launch_colsum(int is_bf16, const void* y, int T, int N, int64_t ld, float* out, hipStream_t st);
+
+// ------------------------------------------------------------- Lanczos ------
+
+struct LzScalars;  // device-resident doubles, see lanczos.hip
+
+}  // namespace hf

@@ -1,0 +1,33 @@
+// Internal interface of the Lanczos vector kernels (lanczos.hip).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace hf {
+
+// Slots of the device-resident scalar array.
+enum {
+  S_ALPHA = 0,       // alpha_k
+  S_BETA = 1,        // current ||r|| (beta_k once the iteration's updates are done)
+  S_BETA_PREV = 2,   // beta_{k-1}
+  S_NRM_BEFORE = 3,  // ||r|| before the orthogonalisation pass in flight
+  S_REDO = 4,        // 1.0 when a second orthogonalisation pass is required
+  S_Q0NORM = 5,      // ||q0|| before normalisation
+  S_COUNT = 8
+};
+
+constexpr int LZ_NBLK = 2048;  // upper bound on blocks (= partial sums) per reduction
+
+hipError_t lz_norm_q0(const float* z, int64_t n, double* scal, double* partials, hipStream_t st);
+hipError_t lz_axpy_dot(float* r, const float* q, const float* qp, int64_t n, int use_prev, double* scal,
+                       double* partials, hipStream_t st);
+hipError_t lz_axpy_nrm(float* r, const float* q, int64_t n, double* scal, double* partials, hipStream_t st);
+hipError_t lz_scale(const float* src, float* dst, void* basis, int basis_bf16, int64_t n, const double* scal, int idx,
+                    hipStream_t st);
+// One classical Gram-Schmidt pass of r against Q[0..nq); pass 1 is a no-op
+// unless pass 0 set the redo flag.
+hipError_t lz_reorth_pass(const void* Q, int basis_bf16, int64_t ldq, float* r, int64_t n, int nq, int pass,
+                          double* scal, double* c, double* partials, hipStream_t st);
+hipError_t lz_widen(const void* src, int is_bf16, float* dst, int64_t n, hipStream_t st);
+
+}  // namespace hf

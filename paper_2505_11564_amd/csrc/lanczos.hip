@@ -1,0 +1,308 @@
+// Bandwidth-bound vector kernels of the Lanczos iteration (Algorithm 2 of the
+// paper) and of the full orthogonalisation against a stored basis Q that
+// Section "Memory Compute trade off" uses as its baseline.
+//
+// Per iteration, with r = H q_k already computed:
+//   lz_axpy_dot : r -= beta_{k-1} q_{k-1};  alpha_k = <q_k, r>        (3R + 1W)
+//   lz_axpy_nrm : r -= alpha_k q_k;         beta_k  = ||r||           (2R + 1W)
+//   lz_qtr      : c = Q^T r      (k+1 dot products, Q read once)
+//   lz_sub_qc   : r -= Q c;  beta_k = ||r||   (Q read once)
+//   lz_scale    : q_{k+1} = r / beta_k, appended to the basis         (1R + 1W)
+// Scalars stay on the device (array `scal` of doubles) so consecutive kernels
+// need no host round trip.  Reductions: fp64 per-thread accumulators, one
+// partial per block, summed in a fixed order by a small second kernel, so
+// results are bitwise reproducible.
+#include "hf_internal.h"
+#include "lanczos.h"
+
+namespace hf {
+
+__device__ __forceinline__ double wave_sum_d(double v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+__device__ __forceinline__ double block_sum_d(double v, double* red) {
+  v = wave_sum_d(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return red[0] + red[1] + red[2] + red[3];
+}
+
+// mode 0: partial sum of z^2 (r unused)
+// mode 1: r -= scal[S_BETA_PREV] * qp (if use_prev); partial <q, r>
+// mode 2: r -= scal[S_ALPHA] * q; partial <r, r>
+template <int MODE>
+__global__ __launch_bounds__(256) void lz_fused_kernel(float* __restrict__ r, const float* __restrict__ q,
+                                                       const float* __restrict__ qp, int64_t n, int use_prev,
+                                                       const double* __restrict__ scal, double* __restrict__ partials) {
+  __shared__ double red[4];
+  float coef = 0.f;
+  if (MODE == 1 && use_prev) coef = (float)scal[S_BETA_PREV];
+  if (MODE == 2) coef = (float)scal[S_ALPHA];
+  double acc = 0.0;
+  const int64_t n4 = n >> 2;
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += stride) {
+    if (MODE == 0) {
+      const float4 a = ((const float4*)q)[i];
+      acc += (double)(a.x * a.x + a.y * a.y) + (double)(a.z * a.z + a.w * a.w);
+    } else if (MODE == 1) {
+      float4 rv = ((float4*)r)[i];
+      const float4 qv = ((const float4*)q)[i];
+      if (use_prev) {
+        const float4 pv = ((const float4*)qp)[i];
+        rv.x = fmaf(-coef, pv.x, rv.x); rv.y = fmaf(-coef, pv.y, rv.y);
+        rv.z = fmaf(-coef, pv.z, rv.z); rv.w = fmaf(-coef, pv.w, rv.w);
+        ((float4*)r)[i] = rv;
+      }
+      acc += (double)rv.x * qv.x + (double)rv.y * qv.y + (double)rv.z * qv.z + (double)rv.w * qv.w;
+    } else {
+      float4 rv = ((float4*)r)[i];
+      const float4 qv = ((const float4*)q)[i];
+      rv.x = fmaf(-coef, qv.x, rv.x); rv.y = fmaf(-coef, qv.y, rv.y);
+      rv.z = fmaf(-coef, qv.z, rv.z); rv.w = fmaf(-coef, qv.w, rv.w);
+      ((float4*)r)[i] = rv;
+      acc += (double)rv.x * rv.x + (double)rv.y * rv.y + (double)rv.z * rv.z + (double)rv.w * rv.w;
+    }
+  }
+  // ragged tail (n not a multiple of 4)
+  for (int64_t i = (n4 << 2) + (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) {
+    if (MODE == 0) { acc += (double)q[i] * q[i]; }
+    else if (MODE == 1) {
+      float rv = r[i];
+      if (use_prev) { rv = fmaf(-coef, qp[i], rv); r[i] = rv; }
+      acc += (double)rv * q[i];
+    } else {
+      const float rv = fmaf(-coef, q[i], r[i]);
+      r[i] = rv;
+      acc += (double)rv * rv;
+    }
+  }
+  acc = block_sum_d(acc, red);
+  if (threadIdx.x == 0) partials[blockIdx.x] = acc;
+}
+
+// what 0: scal[S_Q0NORM] = sqrt(sum); 1: scal[S_ALPHA] = sum;
+// 2: scal[S_BETA] = scal[S_NRM_BEFORE] = sqrt(sum), redo flag cleared;
+// 3 (after an orthogonalisation pass): scal[S_BETA] = sqrt(sum), redo flag set
+//    iff this was the first pass and the norm fell below 1/sqrt(2) of its
+//    value before the pass.
+__global__ __launch_bounds__(256) void lz_finish_kernel(const double* partials, int nblk, int what, int pass,
+                                                        double* scal) {
+  __shared__ double red[4];
+  if (what == 3 && pass == 1 && scal[S_REDO] == 0.0) return;
+  double s = 0.0;
+  for (int i = threadIdx.x; i < nblk; i += 256) s += partials[i];
+  s = block_sum_d(s, red);
+  if (threadIdx.x != 0) return;
+  if (what == 0) scal[S_Q0NORM] = sqrt(s);
+  else if (what == 1) scal[S_ALPHA] = s;
+  else if (what == 2) { scal[S_BETA] = sqrt(s); scal[S_NRM_BEFORE] = sqrt(s); scal[S_REDO] = 0.0; }
+  else {
+    const double nb = sqrt(s);
+    scal[S_BETA] = nb;
+    scal[S_REDO] = (pass == 0 && nb < scal[S_NRM_BEFORE] * 0.70710678118654752) ? 1.0 : 0.0;
+    scal[S_NRM_BEFORE] = nb;
+  }
+}
+
+// dst = src / scal[idx]; optional basis copy (fp32 or bf16, round-to-nearest-even).
+template <typename BT>
+__global__ __launch_bounds__(256) void lz_scale_kernel(const float* src, float* dst, BT* basis, int64_t n, const double* scal, int idx) {
+  const float inv = (float)(1.0 / scal[idx]);
+  const int64_t n4 = n >> 2;
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += stride) {
+    float4 v = ((const float4*)src)[i];
+    v.x *= inv; v.y *= inv; v.z *= inv; v.w *= inv;
+    ((float4*)dst)[i] = v;
+    if (basis) {
+      if (sizeof(BT) == 4) ((float4*)basis)[i] = v;
+      else {
+        bf16 o[4] = {(bf16)v.x, (bf16)v.y, (bf16)v.z, (bf16)v.w};
+        ((uint2*)basis)[i] = *(const uint2*)o;
+      }
+    }
+  }
+  for (int64_t i = (n4 << 2) + (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) {
+    const float v = src[i] * inv;
+    dst[i] = v;
+    if (basis) basis[i] = (BT)v;
+  }
+}
+
+template <typename BT>
+__device__ __forceinline__ float4 load4(const BT* p, int64_t i4);
+template <>
+__device__ __forceinline__ float4 load4<float>(const float* p, int64_t i4) { return ((const float4*)p)[i4]; }
+template <>
+__device__ __forceinline__ float4 load4<bf16>(const bf16* p, int64_t i4) {
+  const uint2 u = ((const uint2*)p)[i4];
+  float4 v;
+  v.x = __uint_as_float(u.x << 16); v.y = __uint_as_float(u.x & 0xffff0000u);
+  v.z = __uint_as_float(u.y << 16); v.w = __uint_as_float(u.y & 0xffff0000u);
+  return v;
+}
+
+// c_j = <Q_j, r> for j in [0, nq): block b owns the contiguous slice
+// [b*slice, (b+1)*slice) of the vectors and walks the basis in groups of JG
+// columns with fp64 accumulators; partials[j*nblk + b].
+constexpr int LZ_JG = 8;
+template <typename BT>
+__global__ __launch_bounds__(256) void lz_qtr_kernel(const BT* __restrict__ Q, int64_t ldq, const float* __restrict__ r,
+                                                     int64_t n, int nq, int64_t slice4, const double* scal, int pass,
+                                                     double* __restrict__ partials) {
+  __shared__ double red[4];
+  if (pass == 1 && scal[S_REDO] == 0.0) return;
+  const int64_t n4 = n >> 2;
+  const int64_t b0 = (int64_t)blockIdx.x * slice4, b1 = min(n4, b0 + slice4);
+  for (int j0 = 0; j0 < nq; j0 += LZ_JG) {
+    double acc[LZ_JG];
+#pragma unroll
+    for (int u = 0; u < LZ_JG; ++u) acc[u] = 0.0;
+    for (int64_t i = b0 + threadIdx.x; i < b1; i += 256) {
+      const float4 rv = ((const float4*)r)[i];
+#pragma unroll
+      for (int u = 0; u < LZ_JG; ++u) {
+        if (j0 + u < nq) {
+          const float4 qv = load4<BT>(Q + (int64_t)(j0 + u) * ldq, i);
+          acc[u] += (double)(qv.x * rv.x + qv.y * rv.y) + (double)(qv.z * rv.z + qv.w * rv.w);
+        }
+      }
+    }
+    if (blockIdx.x == gridDim.x - 1) {  // ragged tail elements
+      for (int64_t i = (n4 << 2) + threadIdx.x; i < n; i += 256)
+#pragma unroll
+        for (int u = 0; u < LZ_JG; ++u)
+          if (j0 + u < nq) acc[u] += (double)((float)Q[(int64_t)(j0 + u) * ldq + i] * r[i]);
+    }
+#pragma unroll
+    for (int u = 0; u < LZ_JG; ++u) {
+      if (j0 + u < nq) {
+        const double s = block_sum_d(acc[u], red);
+        if (threadIdx.x == 0) partials[(int64_t)(j0 + u) * gridDim.x + blockIdx.x] = s;
+      }
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void lz_qtr_finish_kernel(const double* partials, int nblk, const double* scal,
+                                                            int pass, double* c) {
+  __shared__ double red[4];
+  if (pass == 1 && scal[S_REDO] == 0.0) return;
+  const int j = blockIdx.x;
+  double s = 0.0;
+  for (int i = threadIdx.x; i < nblk; i += 256) s += partials[(int64_t)j * nblk + i];
+  s = block_sum_d(s, red);
+  if (threadIdx.x == 0) c[j] = s;
+}
+
+// r -= sum_j c_j Q_j, partial ||r||^2.
+template <typename BT>
+__global__ __launch_bounds__(256) void lz_sub_qc_kernel(const BT* __restrict__ Q, int64_t ldq, float* __restrict__ r,
+                                                        int64_t n, int nq, const double* __restrict__ c,
+                                                        const double* scal, int pass, double* __restrict__ partials) {
+  extern __shared__ float cs[];
+  __shared__ double red[4];
+  if (pass == 1 && scal[S_REDO] == 0.0) return;
+  for (int j = threadIdx.x; j < nq; j += 256) cs[j] = (float)c[j];
+  __syncthreads();
+  double acc = 0.0;
+  const int64_t n4 = n >> 2;
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += stride) {
+    float4 rv = ((float4*)r)[i];
+    for (int j = 0; j < nq; ++j) {
+      const float4 qv = load4<BT>(Q + (int64_t)j * ldq, i);
+      const float cj = cs[j];
+      rv.x = fmaf(-cj, qv.x, rv.x); rv.y = fmaf(-cj, qv.y, rv.y);
+      rv.z = fmaf(-cj, qv.z, rv.z); rv.w = fmaf(-cj, qv.w, rv.w);
+    }
+    ((float4*)r)[i] = rv;
+    acc += (double)rv.x * rv.x + (double)rv.y * rv.y + (double)rv.z * rv.z + (double)rv.w * rv.w;
+  }
+  for (int64_t i = (n4 << 2) + (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) {
+    float rv = r[i];
+    for (int j = 0; j < nq; ++j) rv = fmaf(-cs[j], (float)Q[(int64_t)j * ldq + i], rv);
+    r[i] = rv;
+    acc += (double)rv * rv;
+  }
+  acc = block_sum_d(acc, red);
+  if (threadIdx.x == 0) partials[blockIdx.x] = acc;
+}
+
+template <typename BT>
+__global__ void lz_widen_kernel(const BT* src, float* dst, int64_t n) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
+    dst[i] = (float)src[i];
+}
+
+// ------------------------------------------------------------- launchers ----
+
+static int vec_blocks(int64_t n) {
+  const int64_t want = (n / 4 + 255) / 256;
+  return (int)std::max<int64_t>(1, std::min<int64_t>(want, LZ_NBLK));
+}
+
+hipError_t lz_norm_q0(const float* z, int64_t n, double* scal, double* partials, hipStream_t st) {
+  const int nb = vec_blocks(n);
+  hipLaunchKernelGGL(lz_fused_kernel<0>, dim3(nb), dim3(256), 0, st, nullptr, z, nullptr, n, 0, scal, partials);
+  hipLaunchKernelGGL(lz_finish_kernel, dim3(1), dim3(256), 0, st, partials, nb, 0, 0, scal);
+  return hipGetLastError();
+}
+
+hipError_t lz_axpy_dot(float* r, const float* q, const float* qp, int64_t n, int use_prev, double* scal,
+                       double* partials, hipStream_t st) {
+  const int nb = vec_blocks(n);
+  hipLaunchKernelGGL(lz_fused_kernel<1>, dim3(nb), dim3(256), 0, st, r, q, qp, n, use_prev, scal, partials);
+  hipLaunchKernelGGL(lz_finish_kernel, dim3(1), dim3(256), 0, st, partials, nb, 1, 0, scal);
+  return hipGetLastError();
+}
+
+hipError_t lz_axpy_nrm(float* r, const float* q, int64_t n, double* scal, double* partials, hipStream_t st) {
+  const int nb = vec_blocks(n);
+  hipLaunchKernelGGL(lz_fused_kernel<2>, dim3(nb), dim3(256), 0, st, r, q, nullptr, n, 0, scal, partials);
+  hipLaunchKernelGGL(lz_finish_kernel, dim3(1), dim3(256), 0, st, partials, nb, 2, 0, scal);
+  return hipGetLastError();
+}
+
+hipError_t lz_scale(const float* src, float* dst, void* basis, int basis_bf16, int64_t n, const double* scal, int idx,
+                    hipStream_t st) {
+  const int nb = vec_blocks(n);
+  if (basis_bf16) hipLaunchKernelGGL(lz_scale_kernel<bf16>, dim3(nb), dim3(256), 0, st, src, dst, (bf16*)basis, n, scal, idx);
+  else hipLaunchKernelGGL(lz_scale_kernel<float>, dim3(nb), dim3(256), 0, st, src, dst, (float*)basis, n, scal, idx);
+  return hipGetLastError();
+}
+
+hipError_t lz_reorth_pass(const void* Q, int basis_bf16, int64_t ldq, float* r, int64_t n, int nq, int pass,
+                          double* scal, double* c, double* partials, hipStream_t st) {
+  if (nq <= 0) return hipSuccess;
+  const int64_t n4 = n >> 2;
+  int nb = (int)std::max<int64_t>(1, std::min<int64_t>((n4 + 1023) / 1024, LZ_NBLK));
+  const int64_t slice4 = (std::max<int64_t>(n4, 1) + nb - 1) / nb;
+  nb = (int)std::max<int64_t>(1, (std::max<int64_t>(n4, 1) + slice4 - 1) / slice4);
+  const int nb2 = vec_blocks(n);
+  if (basis_bf16) {
+    hipLaunchKernelGGL(lz_qtr_kernel<bf16>, dim3(nb), dim3(256), 0, st, (const bf16*)Q, ldq, r, n, nq, slice4, scal, pass, partials);
+    hipLaunchKernelGGL(lz_qtr_finish_kernel, dim3(nq), dim3(256), 0, st, partials, nb, scal, pass, c);
+    hipLaunchKernelGGL(lz_sub_qc_kernel<bf16>, dim3(nb2), dim3(256), nq * sizeof(float), st, (const bf16*)Q, ldq, r, n, nq, c, scal, pass, partials);
+  } else {
+    hipLaunchKernelGGL(lz_qtr_kernel<float>, dim3(nb), dim3(256), 0, st, (const float*)Q, ldq, r, n, nq, slice4, scal, pass, partials);
+    hipLaunchKernelGGL(lz_qtr_finish_kernel, dim3(nq), dim3(256), 0, st, partials, nb, scal, pass, c);
+    hipLaunchKernelGGL(lz_sub_qc_kernel<float>, dim3(nb2), dim3(256), nq * sizeof(float), st, (const float*)Q, ldq, r, n, nq, c, scal, pass, partials);
+  }
+  hipLaunchKernelGGL(lz_finish_kernel, dim3(1), dim3(256), 0, st, partials, nb2, 3, pass, scal);
+  return hipGetLastError();
+}
+
+hipError_t lz_widen(const void* src, int is_bf16, float* dst, int64_t n, hipStream_t st) {
+  const int nb = (int)std::max<int64_t>(1, std::min<int64_t>((n + 255) / 256, 8192));
+  if (is_bf16) hipLaunchKernelGGL(lz_widen_kernel<bf16>, dim3(nb), dim3(256), 0, st, (const bf16*)src, dst, n);
+  else hipLaunchKernelGGL(lz_widen_kernel<float>, dim3(nb), dim3(256), 0, st, (const float*)src, dst, n);
+  return hipGetLastError();
+}
+
+}  // namespace hf

@@ -1,0 +1,589 @@
+// Row-wise and pointwise operators of the Hessian-vector product, each in the
+// two fused forms the forward-over-reverse evaluation of Algorithm 1 needs:
+//   *_fwd : y and its tangent y_t (directional derivative along v)
+//   *_bwd : the adjoint dx and its tangent dx_t, plus the H v block of the
+//           operator's own parameters.
+// For y = f(a):  y_t = f'(a) a_t;  da = f'(a) dy;  da_t = f'(a) dy_t + f''(a) a_t dy.
+// All statistics and accumulations are fp32; AT is the storage type of
+// activations that feed matrix products (float, or bf16 in bf16 mode).
+#include "hf_internal.h"
+
+namespace hf {
+
+// ---------------------------------------------------------------- helpers ----
+
+template <typename T>
+__device__ __forceinline__ float ldf(const T* p, int64_t i) { return (float)p[i]; }
+template <typename T>
+__device__ __forceinline__ void stf(T* p, int64_t i, float v) { p[i] = (T)v; }
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// Sum of N values per thread over a 256-thread block; result in every thread.
+template <int N>
+__device__ __forceinline__ void block_sum(float (&v)[N], float* red /* [4*N] */) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int i = 0; i < N; ++i) v[i] = wave_sum(v[i]);
+  __syncthreads();
+  if (lane == 0)
+#pragma unroll
+    for (int i = 0; i < N; ++i) red[wave * N + i] = v[i];
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < N; ++i) v[i] = red[i] + red[N + i] + red[2 * N + i] + red[3 * N + i];
+}
+
+__device__ __forceinline__ float block_max(float v, float* red) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  v = wave_max(v);
+  __syncthreads();
+  if (lane == 0) red[wave] = v;
+  __syncthreads();
+  return fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+}
+
+static inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// ------------------------------------------------------------ fill / cast ----
+
+__global__ void fill_f32_kernel(float* p, int64_t n, float val) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = val;
+}
+hipError_t launch_fill_f32(float* p, int64_t n, float val, hipStream_t st) {
+  if (n <= 0) return hipSuccess;
+  const int blocks = (int)std::min<int64_t>(cdiv(n, 256), 4096);
+  hipLaunchKernelGGL(fill_f32_kernel, dim3(blocks), dim3(256), 0, st, p, n, val);
+  return hipGetLastError();
+}
+
+__global__ void f32_to_bf16_kernel(const float* __restrict__ src, bf16* __restrict__ dst, int64_t n) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x * 4;
+  for (int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4; i < n; i += stride) {
+    if (i + 4 <= n) {
+      const float4 v = *(const float4*)(src + i);
+      bf16 o[4] = {(bf16)v.x, (bf16)v.y, (bf16)v.z, (bf16)v.w};
+      *(uint2*)(dst + i) = *(const uint2*)o;
+    } else {
+      for (int64_t j = i; j < n; ++j) dst[j] = (bf16)src[j];
+    }
+  }
+}
+hipError_t launch_f32_to_bf16(const float* src, bf16* dst, int64_t n, hipStream_t st) {
+  if (n <= 0) return hipSuccess;
+  const int blocks = (int)std::min<int64_t>(cdiv(n, 1024), 8192);
+  hipLaunchKernelGGL(f32_to_bf16_kernel, dim3(blocks), dim3(256), 0, st, src, dst, n);
+  return hipGetLastError();
+}
+
+template <typename AT>
+__global__ void cast_pair_kernel(const float* a, const float* b, AT* oa, AT* ob, int64_t n) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+    oa[i] = (AT)a[i];
+    ob[i] = (AT)b[i];
+  }
+}
+hipError_t launch_cast_pair(int bf, const float* a, const float* b, void* oa, void* ob, int64_t n, hipStream_t st) {
+  if (n <= 0) return hipSuccess;
+  const int blocks = (int)std::min<int64_t>(cdiv(n, 256), 8192);
+  if (bf) hipLaunchKernelGGL(cast_pair_kernel<bf16>, dim3(blocks), dim3(256), 0, st, a, b, (bf16*)oa, (bf16*)ob, n);
+  else hipLaunchKernelGGL(cast_pair_kernel<float>, dim3(blocks), dim3(256), 0, st, a, b, (float*)oa, (float*)ob, n);
+  return hipGetLastError();
+}
+
+// -------------------------------------------------------------- embedding ----
+
+template <typename PT>
+__global__ void embed_fwd_kernel(const PT* wte, const PT* wpe, const float* wte_t, const float* wpe_t,
+                                 const int32_t* tok, int S, int d, int vocab, float* x, float* x_t, int* err_flag) {
+  const int t = blockIdx.x;
+  int id = tok[t];
+  if (id < 0 || id >= vocab) {
+    if (threadIdx.x == 0) atomicOr(err_flag, 1);
+    id = 0;
+  }
+  const int pos = t % S;
+  for (int c = threadIdx.x; c < d; c += blockDim.x) {
+    float v = ldf(wte, (int64_t)id * d + c), vt = wte_t[(int64_t)id * d + c];
+    if (wpe) {
+      v += ldf(wpe, (int64_t)pos * d + c);
+      vt += wpe_t[(int64_t)pos * d + c];
+    }
+    x[(int64_t)t * d + c] = v;
+    x_t[(int64_t)t * d + c] = vt;
+  }
+}
+hipError_t launch_embed_fwd(int bf, const void* wte, const void* wpe, const float* wte_t, const float* wpe_t,
+                            const int32_t* tok, int T, int S, int d, int vocab, float* x, float* x_t, int* err_flag,
+                            hipStream_t st) {
+  if (bf) hipLaunchKernelGGL(embed_fwd_kernel<bf16>, dim3(T), dim3(256), 0, st, (const bf16*)wte, (const bf16*)wpe, wte_t, wpe_t, tok, S, d, vocab, x, x_t, err_flag);
+  else hipLaunchKernelGGL(embed_fwd_kernel<float>, dim3(T), dim3(256), 0, st, (const float*)wte, (const float*)wpe, wte_t, wpe_t, tok, S, d, vocab, x, x_t, err_flag);
+  return hipGetLastError();
+}
+
+__global__ void embed_bwd_kernel(const float* dx_t, const int32_t* tok, int S, int d, int vocab, float* out_wte, float* out_wpe) {
+  const int t = blockIdx.x;
+  int id = tok[t];
+  if (id < 0 || id >= vocab) return;
+  const int pos = t % S;
+  for (int c = threadIdx.x; c < d; c += blockDim.x) {
+    const float v = dx_t[(int64_t)t * d + c];
+    atomicAdd(out_wte + (int64_t)id * d + c, v);
+    if (out_wpe) atomicAdd(out_wpe + (int64_t)pos * d + c, v);
+  }
+}
+hipError_t launch_embed_bwd(const float* dx_t, const int32_t* tok, int T, int S, int d, int vocab, float* out_wte,
+                            float* out_wpe, hipStream_t st) {
+  hipLaunchKernelGGL(embed_bwd_kernel, dim3(T), dim3(256), 0, st, dx_t, tok, S, d, vocab, out_wte, out_wpe);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ norms ----
+// LayerNorm: xh = (x - mu) rstd, y = gam xh + bet.  With s_t = mean(xh x_t):
+//   xh_t = (x_t - mean(x_t) - xh s_t) rstd,  y_t = gam_t xh + gam xh_t + bet_t.
+// RMSNorm is the same with mu = mean(x_t) = 0 and rstd = 1/sqrt(mean(x^2)+eps).
+// stats row: [mu, rstd, mean(x_t), s_t].
+
+template <typename PT, typename AT, bool RMS>
+__global__ __launch_bounds__(256) void norm_fwd_kernel(const float* __restrict__ x, const float* __restrict__ x_t,
+                                                       const PT* gam, const PT* bet, const float* gam_t,
+                                                       const float* bet_t, int d, float eps, AT* y, AT* y_t,
+                                                       float* stats) {
+  __shared__ float red[16];
+  const int64_t row = blockIdx.x;
+  const float* xr = x + row * d;
+  const float* xtr = x_t + row * d;
+  const float inv_d = 1.f / (float)d;
+  float mu = 0.f, mxt = 0.f;
+  if (!RMS) {
+    float s[2] = {0.f, 0.f};
+    for (int c = threadIdx.x; c < d; c += 256) { s[0] += xr[c]; s[1] += xtr[c]; }
+    block_sum<2>(s, red);
+    mu = s[0] * inv_d;
+    mxt = s[1] * inv_d;
+  }
+  float s2[2] = {0.f, 0.f};
+  for (int c = threadIdx.x; c < d; c += 256) {
+    const float xc = xr[c] - mu;
+    s2[0] += xc * xc;
+    s2[1] += xc * xtr[c];
+  }
+  block_sum<2>(s2, red);
+  const float rstd = rsqrtf(s2[0] * inv_d + eps);
+  const float st = s2[1] * inv_d * rstd;  // mean(xh * x_t)
+  for (int c = threadIdx.x; c < d; c += 256) {
+    const float xh = (xr[c] - mu) * rstd;
+    const float xht = (xtr[c] - mxt - xh * st) * rstd;
+    const float g = ldf(gam, c);
+    float yv = g * xh, yt = gam_t[c] * xh + g * xht;
+    if (!RMS) { yv += ldf(bet, c); yt += bet_t[c]; }
+    stf(y, row * d + c, yv);
+    stf(y_t, row * d + c, yt);
+  }
+  if (threadIdx.x == 0) {
+    float4 o = make_float4(mu, rstd, mxt, st);
+    *(float4*)(stats + row * 4) = o;
+  }
+}
+
+hipError_t launch_norm_fwd(int bf, int rms, const float* x, const float* x_t, const void* gam, const void* bet,
+                           const float* gam_t, const float* bet_t, int T, int d, float eps, void* y, void* y_t,
+                           float* stats, hipStream_t st) {
+#define HF_NF(PT, AT, R) hipLaunchKernelGGL((norm_fwd_kernel<PT, AT, R>), dim3(T), dim3(256), 0, st, x, x_t, (const PT*)gam, (const PT*)bet, gam_t, bet_t, d, eps, (AT*)y, (AT*)y_t, stats)
+  if (bf) { if (rms) HF_NF(bf16, bf16, true); else HF_NF(bf16, bf16, false); }
+  else { if (rms) HF_NF(float, float, true); else HF_NF(float, float, false); }
+#undef HF_NF
+  return hipGetLastError();
+}
+
+// Adjoint of the norm with its tangent.  g = gam dy, g_t = gam_t dy + gam dy_t,
+//   dx   = (g - mean(g) - xh mean(g xh)) rstd
+//   dx_t = (g_t - mean(g_t) - xh_t mean(g xh) - xh mean(g_t xh + g xh_t)) rstd - dx s_t rstd
+//   (Hv)_gam = sum_rows (dy_t xh + dy xh_t),  (Hv)_bet = sum_rows dy_t.
+// Each block walks `rows_per_block` rows and keeps its column partial sums in
+// registers, so the atomics on hv_gam / hv_bet are one per column per block.
+constexpr int NORM_MAXC = 32;  // columns per thread: d <= 8192
+
+template <typename PT, bool RMS>
+__global__ __launch_bounds__(256) void norm_bwd_kernel(const float* __restrict__ dy, const float* __restrict__ dy_t,
+                                                       const float* __restrict__ x, const float* __restrict__ x_t,
+                                                       const float* __restrict__ stats, const PT* gam,
+                                                       const float* gam_t, int T, int d, int rows_per_block,
+                                                       int accumulate, float* dx, float* dx_t, float* hv_gam,
+                                                       float* hv_bet) {
+  __shared__ float red[16];
+  float pg[NORM_MAXC], pb[NORM_MAXC];
+#pragma unroll
+  for (int i = 0; i < NORM_MAXC; ++i) { pg[i] = 0.f; pb[i] = 0.f; }
+  const float inv_d = 1.f / (float)d;
+  const int r0 = blockIdx.x * rows_per_block;
+  const int r1 = min(T, r0 + rows_per_block);
+  for (int row = r0; row < r1; ++row) {
+    const int64_t base = (int64_t)row * d;
+    const float4 s = *(const float4*)(stats + (int64_t)row * 4);
+    const float mu = s.x, rstd = s.y, mxt = s.z, st = s.w;
+    float m[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int c = threadIdx.x; c < d; c += 256) {
+      const float xh = (x[base + c] - mu) * rstd;
+      const float xht = (x_t[base + c] - mxt - xh * st) * rstd;
+      const float gm = ldf(gam, c);
+      const float g = gm * dy[base + c];
+      const float gt = gam_t[c] * dy[base + c] + gm * dy_t[base + c];
+      m[0] += g; m[1] += g * xh; m[2] += gt; m[3] += gt * xh + g * xht;
+    }
+    block_sum<4>(m, red);
+    float m1 = m[0] * inv_d, m2 = m[1] * inv_d, m1t = m[2] * inv_d, m2t = m[3] * inv_d;
+    if (RMS) { m1 = 0.f; m1t = 0.f; }
+    int ci = 0;
+    for (int c = threadIdx.x; c < d; c += 256, ++ci) {
+      const float xh = (x[base + c] - mu) * rstd;
+      const float xht = (x_t[base + c] - mxt - xh * st) * rstd;
+      const float gm = ldf(gam, c);
+      const float dyv = dy[base + c], dytv = dy_t[base + c];
+      const float g = gm * dyv;
+      const float gt = gam_t[c] * dyv + gm * dytv;
+      const float dxv = (g - m1 - xh * m2) * rstd;
+      const float dxt = (gt - m1t - xht * m2 - xh * m2t) * rstd - dxv * st * rstd;
+      if (accumulate) { dx[base + c] += dxv; dx_t[base + c] += dxt; }
+      else { dx[base + c] = dxv; dx_t[base + c] = dxt; }
+      pg[ci] += dytv * xh + dyv * xht;
+      pb[ci] += dytv;
+    }
+  }
+  int ci = 0;
+  for (int c = threadIdx.x; c < d; c += 256, ++ci) {
+    atomicAdd(hv_gam + c, pg[ci]);
+    if (!RMS) atomicAdd(hv_bet + c, pb[ci]);
+  }
+}
+
+hipError_t launch_norm_bwd(int bf, int rms, const float* dy, const float* dy_t, const float* x, const float* x_t,
+                           const float* stats, const void* gam, const float* gam_t, int T, int d, int accumulate,
+                           float* dx, float* dx_t, float* hv_gam, float* hv_bet, hipStream_t st) {
+  if (d > 256 * NORM_MAXC) return hipErrorInvalidValue;
+  const int rpb = std::max(1, T / 512);
+  const int blocks = (T + rpb - 1) / rpb;
+#define HF_NB(PT, R) hipLaunchKernelGGL((norm_bwd_kernel<PT, R>), dim3(blocks), dim3(256), 0, st, dy, dy_t, x, x_t, stats, (const PT*)gam, gam_t, T, d, rpb, accumulate, dx, dx_t, hv_gam, hv_bet)
+  if (bf) { if (rms) HF_NB(bf16, true); else HF_NB(bf16, false); }
+  else { if (rms) HF_NB(float, true); else HF_NB(float, false); }
+#undef HF_NB
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------ activations ----
+
+__device__ __forceinline__ void act_derivs(int act, float a, float& f, float& f1, float& f2) {
+  if (act == ACT_TANH) {
+    const float t = tanhf(a);
+    f = t; f1 = 1.f - t * t; f2 = -2.f * t * f1;
+  } else {  // erf GELU: f = a Phi(a), f' = Phi + a phi, f'' = phi (2 - a^2)
+    const float Phi = 0.5f * (1.f + erff(a * 0.70710678118654752f));
+    const float phi = 0.39894228040143268f * __expf(-0.5f * a * a);
+    f = a * Phi; f1 = Phi + a * phi; f2 = phi * (2.f - a * a);
+  }
+}
+
+template <typename AT>
+__global__ void act_fwd_kernel(int act, const AT* a, const AT* a_t, AT* y, AT* y_t, int64_t n) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+    float f, f1, f2;
+    act_derivs(act, ldf(a, i), f, f1, f2);
+    stf(y, i, f);
+    stf(y_t, i, f1 * ldf(a_t, i));
+  }
+}
+template <typename AT>
+__global__ void act_bwd_kernel(int act, const AT* a, const AT* a_t, const AT* dy, const AT* dy_t, AT* da, AT* da_t,
+                               int64_t n) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+    float f, f1, f2;
+    act_derivs(act, ldf(a, i), f, f1, f2);
+    const float d = ldf(dy, i);
+    stf(da, i, f1 * d);
+    stf(da_t, i, f1 * ldf(dy_t, i) + f2 * ldf(a_t, i) * d);
+  }
+}
+static inline int ew_blocks(int64_t n) { return (int)std::min<int64_t>(cdiv(n, 256), 16384); }
+
+hipError_t launch_act_fwd(int bf, int act, const void* a, const void* a_t, void* y, void* y_t, int64_t n, hipStream_t st) {
+  if (n <= 0) return hipSuccess;
+  if (bf) hipLaunchKernelGGL(act_fwd_kernel<bf16>, dim3(ew_blocks(n)), dim3(256), 0, st, act, (const bf16*)a, (const bf16*)a_t, (bf16*)y, (bf16*)y_t, n);
+  else hipLaunchKernelGGL(act_fwd_kernel<float>, dim3(ew_blocks(n)), dim3(256), 0, st, act, (const float*)a, (const float*)a_t, (float*)y, (float*)y_t, n);
+  return hipGetLastError();
+}
+hipError_t launch_act_bwd(int bf, int act, const void* a, const void* a_t, const void* dy, const void* dy_t, void* da,
+                          void* da_t, int64_t n, hipStream_t st) {
+  if (n <= 0) return hipSuccess;
+  if (bf) hipLaunchKernelGGL(act_bwd_kernel<bf16>, dim3(ew_blocks(n)), dim3(256), 0, st, act, (const bf16*)a, (const bf16*)a_t, (const bf16*)dy, (const bf16*)dy_t, (bf16*)da, (bf16*)da_t, n);
+  else hipLaunchKernelGGL(act_bwd_kernel<float>, dim3(ew_blocks(n)), dim3(256), 0, st, act, (const float*)a, (const float*)a_t, (const float*)dy, (const float*)dy_t, (float*)da, (float*)da_t, n);
+  return hipGetLastError();
+}
+
+// SwiGLU y = s(g) u with s(g) = g sigmoid(g):
+//   s' = sig + g sig', s'' = sig' (2 + g (1 - 2 sig)), sig' = sig (1 - sig).
+template <typename AT>
+__global__ void swiglu_fwd_kernel(const AT* g, const AT* g_t, const AT* u, const AT* u_t, AT* y, AT* y_t, int64_t n) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+    const float gv = ldf(g, i), uv = ldf(u, i);
+    const float sg = 1.f / (1.f + __expf(-gv));
+    const float s = gv * sg, s1 = sg + gv * sg * (1.f - sg);
+    stf(y, i, s * uv);
+    stf(y_t, i, s1 * ldf(g_t, i) * uv + s * ldf(u_t, i));
+  }
+}
+template <typename AT>
+__global__ void swiglu_bwd_kernel(const AT* g, const AT* g_t, const AT* u, const AT* u_t, const AT* dy, const AT* dy_t,
+                                  AT* dg, AT* dg_t, AT* du, AT* du_t, int64_t n) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+    const float gv = ldf(g, i), uv = ldf(u, i), gt = ldf(g_t, i), ut = ldf(u_t, i);
+    const float d = ldf(dy, i), dt = ldf(dy_t, i);
+    const float sg = 1.f / (1.f + __expf(-gv));
+    const float dsg = sg * (1.f - sg);
+    const float s = gv * sg, s1 = sg + gv * dsg, s2 = dsg * (2.f + gv * (1.f - 2.f * sg));
+    stf(dg, i, s1 * uv * d);
+    stf(du, i, s * d);
+    stf(dg_t, i, s2 * gt * uv * d + s1 * ut * d + s1 * uv * dt);
+    stf(du_t, i, s1 * gt * d + s * dt);
+  }
+}
+hipError_t launch_swiglu_fwd(int bf, const void* g, const void* g_t, const void* u, const void* u_t, void* y, void* y_t,
+                             int64_t n, hipStream_t st) {
+  if (n <= 0) return hipSuccess;
+  if (bf) hipLaunchKernelGGL(swiglu_fwd_kernel<bf16>, dim3(ew_blocks(n)), dim3(256), 0, st, (const bf16*)g, (const bf16*)g_t, (const bf16*)u, (const bf16*)u_t, (bf16*)y, (bf16*)y_t, n);
+  else hipLaunchKernelGGL(swiglu_fwd_kernel<float>, dim3(ew_blocks(n)), dim3(256), 0, st, (const float*)g, (const float*)g_t, (const float*)u, (const float*)u_t, (float*)y, (float*)y_t, n);
+  return hipGetLastError();
+}
+hipError_t launch_swiglu_bwd(int bf, const void* g, const void* g_t, const void* u, const void* u_t, const void* dy,
+                             const void* dy_t, void* dg, void* dg_t, void* du, void* du_t, int64_t n, hipStream_t st) {
+  if (n <= 0) return hipSuccess;
+  if (bf) hipLaunchKernelGGL(swiglu_bwd_kernel<bf16>, dim3(ew_blocks(n)), dim3(256), 0, st, (const bf16*)g, (const bf16*)g_t, (const bf16*)u, (const bf16*)u_t, (const bf16*)dy, (const bf16*)dy_t, (bf16*)dg, (bf16*)dg_t, (bf16*)du, (bf16*)du_t, n);
+  else hipLaunchKernelGGL(swiglu_bwd_kernel<float>, dim3(ew_blocks(n)), dim3(256), 0, st, (const float*)g, (const float*)g_t, (const float*)u, (const float*)u_t, (const float*)dy, (const float*)dy_t, (float*)dg, (float*)dg_t, (float*)du, (float*)du_t, n);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------- causal softmax ----
+// Row i of a [S,S] score matrix has i+1 live entries.  One wavefront per row.
+//   p = softmax(s),  p_t = p (s_t - sum_j p_j s_t_j).  Entries j > i are 0.
+
+template <typename AT>
+__global__ __launch_bounds__(256) void softmax_fwd_kernel(const float* __restrict__ s, const float* __restrict__ s_t,
+                                                          AT* p, AT* p_t, int64_t rows, int S) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const int i = (int)(row % S);
+  const float* sr = s + row * S;
+  const float* str = s_t + row * S;
+  float mx = -INFINITY;
+  for (int j = lane; j <= i; j += 64) mx = fmaxf(mx, sr[j]);
+  mx = wave_max(mx);
+  float sum = 0.f, dot = 0.f;
+  for (int j = lane; j <= i; j += 64) {
+    const float e = __expf(sr[j] - mx);
+    sum += e;
+    dot += e * str[j];
+  }
+  sum = wave_sum(sum);
+  dot = wave_sum(dot);
+  const float inv = 1.f / sum;
+  dot *= inv;
+  for (int j = lane; j < S; j += 64) {
+    float pv = 0.f, pt = 0.f;
+    if (j <= i) {
+      pv = __expf(sr[j] - mx) * inv;
+      pt = pv * (str[j] - dot);
+    }
+    stf(p, row * S + j, pv);
+    stf(p_t, row * S + j, pt);
+  }
+}
+hipError_t launch_softmax_fwd(int bf, const float* s, const float* s_t, void* p, void* p_t, int nbh, int S, hipStream_t st) {
+  const int64_t rows = (int64_t)nbh * S;
+  const int blocks = (int)cdiv(rows, 4);
+  if (bf) hipLaunchKernelGGL(softmax_fwd_kernel<bf16>, dim3(blocks), dim3(256), 0, st, s, s_t, (bf16*)p, (bf16*)p_t, rows, S);
+  else hipLaunchKernelGGL(softmax_fwd_kernel<float>, dim3(blocks), dim3(256), 0, st, s, s_t, (float*)p, (float*)p_t, rows, S);
+  return hipGetLastError();
+}
+
+// delta = sum p dp; delta_t = sum (p_t dp + p dp_t);
+// ds = p (dp - delta); ds_t = p_t (dp - delta) + p (dp_t - delta_t).
+template <typename AT>
+__global__ __launch_bounds__(256) void softmax_bwd_kernel(const AT* __restrict__ p, const AT* __restrict__ p_t,
+                                                          const float* __restrict__ dp, const float* __restrict__ dp_t,
+                                                          AT* ds, AT* ds_t, int64_t rows, int S) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const int i = (int)(row % S);
+  const int64_t b = row * S;
+  float dl = 0.f, dlt = 0.f;
+  for (int j = lane; j <= i; j += 64) {
+    const float pv = ldf(p, b + j), pt = ldf(p_t, b + j);
+    dl += pv * dp[b + j];
+    dlt += pt * dp[b + j] + pv * dp_t[b + j];
+  }
+  dl = wave_sum(dl);
+  dlt = wave_sum(dlt);
+  for (int j = lane; j < S; j += 64) {
+    float a = 0.f, at = 0.f;
+    if (j <= i) {
+      const float pv = ldf(p, b + j), pt = ldf(p_t, b + j);
+      a = pv * (dp[b + j] - dl);
+      at = pt * (dp[b + j] - dl) + pv * (dp_t[b + j] - dlt);
+    }
+    stf(ds, b + j, a);
+    stf(ds_t, b + j, at);
+  }
+}
+hipError_t launch_softmax_bwd(int bf, const void* p, const void* p_t, const float* dp, const float* dp_t, void* ds,
+                              void* ds_t, int nbh, int S, hipStream_t st) {
+  const int64_t rows = (int64_t)nbh * S;
+  const int blocks = (int)cdiv(rows, 4);
+  if (bf) hipLaunchKernelGGL(softmax_bwd_kernel<bf16>, dim3(blocks), dim3(256), 0, st, (const bf16*)p, (const bf16*)p_t, dp, dp_t, (bf16*)ds, (bf16*)ds_t, rows, S);
+  else hipLaunchKernelGGL(softmax_bwd_kernel<float>, dim3(blocks), dim3(256), 0, st, (const float*)p, (const float*)p_t, dp, dp_t, (float*)ds, (float*)ds_t, rows, S);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------- RoPE ----
+// Pair (i, i + dh/2) of every head is rotated by pos * theta^(-2i/dh); the
+// tangent takes the same rotation, adjoints the transposed one.
+
+template <typename AT>
+__global__ void rope_kernel(AT* x, AT* x_t, int T, int S, int64_t ld, int n_head, int dh, float log2_theta, int inverse) {
+  const int half = dh / 2;
+  const int64_t total = (int64_t)T * n_head * half;
+  for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * blockDim.x) {
+    const int i = (int)(idx % half);
+    const int h = (int)((idx / half) % n_head);
+    const int64_t t = idx / ((int64_t)half * n_head);
+    const int pos = (int)(t % S);
+    const double ang = (double)pos * exp2(-2.0 * (double)i / (double)dh * (double)log2_theta);
+    float sn = (float)sin(ang), cs = (float)cos(ang);
+    if (inverse) sn = -sn;
+    const int64_t a = t * ld + (int64_t)h * dh + i, b = a + half;
+    const float x1 = ldf(x, a), x2 = ldf(x, b);
+    stf(x, a, x1 * cs - x2 * sn);
+    stf(x, b, x2 * cs + x1 * sn);
+    const float y1 = ldf(x_t, a), y2 = ldf(x_t, b);
+    stf(x_t, a, y1 * cs - y2 * sn);
+    stf(x_t, b, y2 * cs + y1 * sn);
+  }
+}
+hipError_t launch_rope(int bf, void* x, void* x_t, int T, int S, int64_t ld, int n_head, int dh, float theta,
+                       int inverse, hipStream_t st) {
+  const int64_t total = (int64_t)T * n_head * (dh / 2);
+  if (total <= 0) return hipSuccess;
+  const float l2 = log2f(theta);
+  if (bf) hipLaunchKernelGGL(rope_kernel<bf16>, dim3(ew_blocks(total)), dim3(256), 0, st, (bf16*)x, (bf16*)x_t, T, S, ld, n_head, dh, l2, inverse);
+  else hipLaunchKernelGGL(rope_kernel<float>, dim3(ew_blocks(total)), dim3(256), 0, st, (float*)x, (float*)x_t, T, S, ld, n_head, dh, l2, inverse);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------ softmax cross-entropy ------
+// L = mean over valid rows of lse(z) - z[y];  dz = (p - onehot)/N;
+// dz_t = p (z_t - <p, z_t>)/N.  Ignored rows (label < 0) produce zeros.
+
+__global__ void count_valid_kernel(const int32_t* labels, int T, int V, int* n_valid, int* err_flag) {
+  int cnt = 0, bad = 0;
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < T; i += gridDim.x * blockDim.x) {
+    const int y = labels[i];
+    cnt += (y >= 0);
+    bad |= (y >= V);
+  }
+  float c = wave_sum((float)cnt);
+  if ((threadIdx.x & 63) == 0 && c > 0.f) atomicAdd(n_valid, (int)c);
+  if (bad) atomicOr(err_flag, 2);
+}
+hipError_t launch_count_valid(const int32_t* labels, int T, int V, int* n_valid, int* err_flag, hipStream_t st) {
+  hipLaunchKernelGGL(count_valid_kernel, dim3((int)std::min<int64_t>(cdiv(T, 256), 256)), dim3(256), 0, st, labels, T, V, n_valid, err_flag);
+  return hipGetLastError();
+}
+
+template <typename AT>
+__global__ __launch_bounds__(256) void ce_kernel(const float* __restrict__ z, const float* __restrict__ z_t,
+                                                 const int32_t* labels, const int* n_valid, int V, int64_t ldz, AT* dz,
+                                                 AT* dz_t, float* loss_rows) {
+  __shared__ float red[16];
+  const int64_t row = blockIdx.x;
+  const float* zr = z + row * ldz;
+  const float* ztr = z_t + row * ldz;
+  const int y = labels[row];
+  if (y < 0 || y >= V) {
+    for (int c = threadIdx.x; c < V; c += 256) { stf(dz, row * ldz + c, 0.f); stf(dz_t, row * ldz + c, 0.f); }
+    if (threadIdx.x == 0) loss_rows[row] = 0.f;
+    return;
+  }
+  float mx = -INFINITY;
+  for (int c = threadIdx.x; c < V; c += 256) mx = fmaxf(mx, zr[c]);
+  mx = block_max(mx, red);
+  float s[2] = {0.f, 0.f};
+  for (int c = threadIdx.x; c < V; c += 256) {
+    const float e = __expf(zr[c] - mx);
+    s[0] += e;
+    s[1] += e * ztr[c];
+  }
+  block_sum<2>(s, red);
+  const float inv = 1.f / s[0];
+  const float pz = s[1] * inv;
+  const float invN = 1.f / (float)max(1, *n_valid);
+  for (int c = threadIdx.x; c < V; c += 256) {
+    const float pv = __expf(zr[c] - mx) * inv;
+    stf(dz, row * ldz + c, (pv - (c == y ? 1.f : 0.f)) * invN);
+    stf(dz_t, row * ldz + c, pv * (ztr[c] - pz) * invN);
+  }
+  if (threadIdx.x == 0) loss_rows[row] = logf(s[0]) + mx - zr[y];
+}
+hipError_t launch_ce(int bf, const float* z, const float* z_t, const int32_t* labels, const int* n_valid, int T, int V,
+                     int64_t ldz, void* dz, void* dz_t, float* loss_rows, hipStream_t st) {
+  if (bf) hipLaunchKernelGGL(ce_kernel<bf16>, dim3(T), dim3(256), 0, st, z, z_t, labels, n_valid, V, ldz, (bf16*)dz, (bf16*)dz_t, loss_rows);
+  else hipLaunchKernelGGL(ce_kernel<float>, dim3(T), dim3(256), 0, st, z, z_t, labels, n_valid, V, ldz, (float*)dz, (float*)dz_t, loss_rows);
+  return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void sum_rows_f64_kernel(const float* v, int n, const int* n_valid, double* out) {
+  __shared__ double red[256];
+  double s = 0.0;
+  for (int i = threadIdx.x; i < n; i += 256) s += (double)v[i];
+  red[threadIdx.x] = s;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if (threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) out[0] = red[0] / (double)max(1, *n_valid);
+}
+hipError_t launch_sum_rows_f64(const float* v, int n, const int* n_valid, double* out, hipStream_t st) {
+  hipLaunchKernelGGL(sum_rows_f64_kernel, dim3(1), dim3(256), 0, st, v, n, n_valid, out);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------ column sums ----
+
+template <typename AT>
+__global__ void colsum_kernel(const AT* y, int T, int N, int64_t ld, int rows_per_block, float* out) {
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= N) return;
+  const int r0 = blockIdx.y * rows_per_block, r1 = min(T, r0 + rows_per_block);
+  float s = 0.f;
+  for (int r = r0; r < r1; ++r) s += ldf(y, (int64_t)r * ld + c);
+  atomicAdd(out + c, s);
+}
+hipError_t launch_colsum(int is_bf16, const void* y, int T, int N, int64_t ld, float* out, hipStream_t st) {
+  if (T <= 0 || N <= 0) return hipSuccess;
+  const int rpb = 64;
+  dim3 grid((N + 255) / 256, (T + rpb - 1) / rpb);
+  if (is_bf16) hipLaunchKernelGGL(colsum_kernel<bf16>, grid, dim3(256), 0, st, (const bf16*)y, T, N, ld, rpb, out);
+  else hipLaunchKernelGGL(colsum_kernel<float>, grid, dim3(256), 0, st, (const float*)y, T, N, ld, rpb, out);
+  return hipGetLastError();
+}
+
+}  // namespace hf

@@ -1,0 +1,116 @@
+"""Parity of the HIP Hessian-vector product (hf_hvp, through the C ABI) with
+the float64 oracle on the same seeded inputs.  Tolerances: relative L2 error
+<= 1e-4 with fp32 parameters, <= 2e-2 with bf16 parameters."""
+import numpy as np
+import pytest
+
+import synth_inputs as si
+from oracle import models as om
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+SHAPES = {
+    # tiny, ragged: nothing is a multiple of a tile
+    "mlp_ragged": dict(model=si._mlp(13, 21, 7), batch=37, seq=1, tokens=None),
+    "gpt_tiny": dict(model=si._gpt(2, 16, 2, 40, 23, 9), batch=3, seq=7, tokens="uniform"),
+    "gpt_untied": dict(model=si._gpt(1, 24, 3, 32, 19, 6, tie=0), batch=2, seq=6, tokens="zipf"),
+    "llama_tiny": dict(model=si._llama(2, 16, 2, 24, 21, 8), batch=2, seq=8, tokens="zipf"),
+    # several 128-wide tiles with ragged tails in every dimension
+    "gpt_mid": dict(model=si._gpt(2, 192, 3, 328, 1003, 160), batch=3, seq=150, tokens="zipf"),
+    "llama_mid": dict(model=si._llama(2, 256, 4, 344, 777, 136), batch=2, seq=136, tokens="zipf"),
+}
+
+
+def run_case(cfg, dtype, seed=0, short_seq=None):
+    from gpu_util import gpu_hvp, rel_l2, block_errors
+    model = cfg["model"]
+    p = si.make_params(model, seed=42 + seed, param_dtype=dtype, perturb=0.1)
+    if dtype == "bf16":
+        p = si.bf16_bits_to_f32(si.f32_to_bf16_bits(p))
+    x, y = si.make_batch(cfg, seed=43 + seed, seq=short_seq)
+    n = om.num_params(model)
+    v = si.make_direction(n, 7 + seed)
+    want_loss, _, want, _ = om.loss_grad_hvp(model, p.astype(np.float64), x, y, v.astype(np.float64))
+    got, loss = gpu_hvp(model, p, x, y, v, dtype, max_batch=cfg["batch"])
+    err = rel_l2(got, want)
+    if not err <= TOL[dtype]:
+        rows = sorted(block_errors(model, got, want, om.layout(model)), key=lambda r: -r[1])[:12]
+        raise AssertionError(f"rel L2 {err:.3e} > {TOL[dtype]}; worst blocks: {rows}")
+    assert abs(loss - want_loss) <= (1e-5 if dtype == "f32" else 2e-2) * max(1.0, abs(want_loss))
+    return err
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("name", list(SHAPES))
+def test_hvp_parity_small(name, dtype):
+    run_case(SHAPES[name], dtype)
+
+
+def test_hvp_shorter_sequence_than_max():
+    run_case(SHAPES["gpt_mid"], "f32", seed=1, short_seq=77)
+
+
+def test_hvp_ignored_labels_and_single_valid():
+    from gpu_util import gpu_hvp, rel_l2
+    cfg = SHAPES["gpt_tiny"]
+    model = cfg["model"]
+    p = si.make_params(model, perturb=0.1)
+    x, y = si.make_batch(cfg)
+    y[:] = -1
+    y[1, 3] = 5
+    v = si.make_direction(om.num_params(model), 3)
+    want = om.hvp(model, p.astype(np.float64), x, y, v.astype(np.float64))
+    got, _ = gpu_hvp(model, p, x, y, v)
+    assert rel_l2(got, want) <= 1e-4
+
+
+@pytest.mark.parametrize("name", ["mlp_tiny", "gpt_2l_d128"])
+def test_hvp_parity_workloads_1_and_2(name):
+    cfg = si.CONFIGS[name]
+    run_case(dict(model=cfg["model"], batch=cfg["batch"], seq=cfg["seq"], tokens=cfg["tokens"]), "f32")
+
+
+def test_hvp_symmetry_on_gpu():
+    from gpu_util import gpu_hvp
+    cfg = si.CONFIGS["gpt_2l_d128"]
+    model = cfg["model"]
+    p = si.make_params(model)
+    x, y = si.make_batch(cfg)
+    n = om.num_params(model)
+    v, w = si.make_direction(n, 1), si.make_direction(n, 2)
+    hv, _ = gpu_hvp(model, p, x, y, v)
+    hw, _ = gpu_hvp(model, p, x, y, w)
+    a, b = float(w.astype(np.float64) @ hv), float(v.astype(np.float64) @ hw)
+    assert abs(a - b) <= 1e-4 * max(abs(a), abs(b))
+
+
+def test_hvp_input_errors():
+    import paper_2505_11564_amd as hf
+    import torch
+    cfg = SHAPES["gpt_tiny"]
+    model = cfg["model"]
+    ctx = hf.Context(model, cfg["batch"], 0)
+    p = torch.from_numpy(si.make_params(model)).cuda()
+    x, y = si.make_batch(cfg)
+    v = torch.ones(ctx.n, device="cuda")
+    out = torch.empty(ctx.n, device="cuda")
+    xd, yd = torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda()
+    with pytest.raises(hf.HessformerError) as e:
+        ctx.hf_hvp(p, xd, yd, cfg["batch"] + 1, cfg["seq"], v, out)
+    assert e.value.code == hf.binding.HF_ESHAPE
+    with pytest.raises(hf.HessformerError) as e:
+        ctx.hf_hvp(p, xd, yd, cfg["batch"], cfg["seq"], v, v)
+    assert e.value.code == hf.binding.HF_EINVAL
+    bad = x.copy(); bad[0, 0] = model["vocab"]
+    with pytest.raises(hf.HessformerError) as e:
+        ctx.hf_hvp(p, torch.from_numpy(bad).cuda(), yd, cfg["batch"], cfg["seq"], v, out)
+    assert e.value.code == hf.binding.HF_EINVAL
+    ybad = y.copy(); ybad[0, 0] = model["vocab"] + 3
+    with pytest.raises(hf.HessformerError) as e:
+        ctx.hf_hvp(p, xd, torch.from_numpy(ybad).cuda(), cfg["batch"], cfg["seq"], v, out)
+    assert e.value.code == hf.binding.HF_EINVAL
+    # and the context still works afterwards
+    ctx.hf_hvp(p, xd, yd, cfg["batch"], cfg["seq"], v, out)
+    ctx.close()
