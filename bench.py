@@ -1,0 +1,194 @@
+#!/usr/bin/env python3
+"""Benchmark of the HessFormer hot path on one MI355X.
+
+A "step" is one Lanczos iteration of Algorithm 2 on a synthetic workload: one
+exact Hessian-vector product (Algorithm 1, forward-over-reverse) followed by
+the vector update (three-term recurrence, full re-orthogonalisation against
+the stored basis where the workload asks for it, normalisation, basis append).
+Inputs are resident in HBM before the timed region starts.
+
+Prints ONE JSON line: steps/s (the metric), HVPs/s, the MFMA roofline of the
+HVP, the HBM roofline of the Lanczos vector kernels, and the float64 CPU oracle
+timed on a bounded sample of the same workload on this host's cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_F32_TFLOPS = 157.3     # fp32 vector/matrix
+PEAK_HBM_GBS = 8000.0       # HBM3E
+
+
+def hvp_flops(model, batch, seq):
+    """Algorithmic flops of one HVP: 8 products of 2*T*d_in*d_out per linear
+    layer (forward 1, tangent-forward 2, adjoint 1, tangent-adjoint 2, H v
+    block 2; the plain weight gradient is not formed) plus 18 products of
+    2*S^2*dh per head and layer for attention, halved for causality."""
+    if model["arch"] == "mlp":
+        pm = model["mlp_in"] * model["mlp_hidden"] + model["mlp_hidden"] * model["mlp_out"]
+        return 16.0 * batch * pm
+    d, ff, L, V = model["d_model"], model["d_ff"], model["n_layer"], model["vocab"]
+    per_layer = 4 * d * d + (3 if model["arch"] == "llama" else 2) * d * ff
+    pm = L * per_layer + V * d
+    T = batch * seq
+    return 16.0 * T * pm + 18.0 * batch * L * seq * seq * d
+
+
+def lanczos_bytes(n, k, reorth, basis_bytes):
+    """Algorithmic HBM bytes of the vector update of iteration k: 9 fp32 words
+    per element for the fused three-term part (3R+1W, 2R+1W, 1R+1W); one
+    classical Gram-Schmidt pass reads the k+1 stored vectors twice and r three
+    times (2R+1W); appending q_{k+1} writes one basis vector."""
+    b = 36.0 * n
+    if reorth == "full":
+        b += 2.0 * (k + 1) * n * basis_bytes + 12.0 * n + basis_bytes * n
+    return b
+
+
+def cpu_baseline(cfg, params, seq_sample, budget_note):
+    """The float64 oracle, as it stands, on one sequence of the workload's
+    batch: one Lanczos iteration (one oracle HVP plus the vector update)."""
+    from oracle import lanczos as olz
+    from oracle import models as om
+    import synth_inputs as si
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count()
+    model = cfg["model"]
+    x, y = si.make_batch(cfg, batch=seq_sample)
+    p64 = params.astype(np.float64)
+    z = si.make_probe(len(params), 0).astype(np.float64)
+    t0 = time.perf_counter()
+    olz.lanczos(lambda q: om.hvp(model, p64, x, y, q), z, 1, cfg["reorth"])
+    dt = time.perf_counter() - t0
+    scale = cfg["batch"] / seq_sample
+    return {"value": 1.0 / (dt * scale), "unit": "lanczos_steps/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"one float64 oracle Lanczos iteration (one HVP) on {seq_sample} of {cfg['batch']} "
+                      f"sequences ({dt:.1f} s), scaled by {scale:g} to the full batch; {budget_note}"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="gpt2_small")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--hvp-reps", type=int, default=10)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (no collectives are part of it); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2505_11564_amd as hf
+    import synth_inputs as si
+
+    cfg = si.CONFIGS[args.workload]
+    model, B, S, m = cfg["model"], cfg["batch"], cfg["seq"], cfg["m"]
+    K = args.steps if args.steps is not None else m
+    W = args.warmup
+    dtype, basis = cfg["param_dtype"], cfg["basis_dtype"]
+    torch.cuda.set_device(0)
+    stream = torch.cuda.current_stream()
+
+    params = si.make_params(model, param_dtype=dtype)
+    n = len(params)
+    x, y = si.make_batch(cfg)
+    pd = torch.from_numpy(params).cuda()
+    if dtype == "bf16":
+        pd = pd.to(torch.bfloat16).contiguous()
+    xd = torch.from_numpy(np.ascontiguousarray(x)).cuda()
+    yd = torch.from_numpy(np.ascontiguousarray(y.astype(np.int32))).cuda()
+    zd = torch.from_numpy(si.make_probe(n, 0)).cuda()
+    Sarg = S if model["arch"] != "mlp" else 1
+    ctx = hf.Context(model, B, m, dtype, basis)
+
+    # ---- HVP alone (MFMA roofline) ------------------------------------------
+    vd = (zd / float(np.sqrt(n))).contiguous()
+    out = torch.empty(n, dtype=torch.float32, device="cuda")
+    for _ in range(2):
+        ctx.hf_hvp(pd, xd, yd, B, Sarg, vd, out)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record(stream)
+    for _ in range(args.hvp_reps):
+        ctx.hf_hvp(pd, xd, yd, B, Sarg, vd, out, want_loss=False)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    hvp_ms = e0.elapsed_time(e1) / args.hvp_reps
+    flops = hvp_flops(model, B, Sarg)
+    hvp_tflops = flops / (hvp_ms * 1e-3) / 1e12
+    peak = PEAK_BF16_TFLOPS if dtype == "bf16" else PEAK_F32_TFLOPS
+
+    # ---- Lanczos steps (the metric) ------------------------------------------
+    def run_steps(count):
+        done = 0
+        while done < count:
+            ctx.hf_lanczos_init(zd, cfg["reorth"])
+            for _ in range(min(m, count - done)):
+                ctx.hf_lanczos_step(pd, xd, yd, B, Sarg)
+                done += 1
+
+    run_steps(W)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run_steps(K)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    # ---- Lanczos vector update alone (HBM roofline), at the mean basis depth --
+    ctx.hf_lanczos_init(zd, cfg["reorth"])
+    depth = min(m, max(1, K)) // 2
+    r = torch.empty(n, dtype=torch.float32, device="cuda")
+    gen = torch.Generator(device="cuda").manual_seed(1)
+    upd_ms, upd_bytes = [], []
+    for k in range(depth + 1):
+        r.normal_(generator=gen)
+        torch.cuda.synchronize()
+        e0.record(stream)
+        ctx.hf_lanczos_update(r)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        if k >= max(0, depth - 4):
+            upd_ms.append(e0.elapsed_time(e1))
+            upd_bytes.append(lanczos_bytes(n, k, cfg["reorth"], 2 if basis == "bf16" else 4))
+    lz_gbs = sum(upd_bytes) / (sum(upd_ms) * 1e-3) / 1e9
+
+    res = {
+        "metric": "lanczos_steps_per_s", "value": K / elapsed, "unit": "steps/s", "n_gpus": 1, "steps": K,
+        "warmup": W, "ms_per_step": 1e3 * elapsed / K, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16" if dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "n_params": n, "batch": B, "seq": Sarg, "lanczos_m": m,
+                   "reorth": cfg["reorth"], "basis_dtype": basis, "tokens": cfg["tokens"]},
+        "hvps_per_s": 1e3 / hvp_ms, "hvp_ms": hvp_ms,
+        "roofline": {"kernel": "hf_hvp (all kernels of one Hessian-vector product)", "bound": "mfma",
+                     "achieved": hvp_tflops, "peak": peak, "unit": "TFLOP/s", "frac": hvp_tflops / peak,
+                     "flops_per_launch": flops, "traffic": None},
+        "roofline_lanczos": {"kernel": "hf_lanczos_update (vector kernels of one iteration)", "bound": "hbm",
+                             "achieved": lz_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": lz_gbs / PEAK_HBM_GBS,
+                             "basis_depth": depth, "ms": sum(upd_ms) / len(upd_ms), "traffic": None},
+    }
+    ctx.close()
+    if not args.no_cpu_baseline:
+        del pd, out, r
+        torch.cuda.empty_cache()
+        res["cpu_baseline"] = cpu_baseline(cfg, params, 1, "the HVP dominates; the vector update is included")
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

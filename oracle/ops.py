@@ -177,38 +177,43 @@ def rope_apply(x, cos, sin, inverse=False):
 # ------------------------------------------------------------- attention ----
 
 
+def _T(a):
+    return np.swapaxes(a, -1, -2)
+
+
 def attention_fwd(q, q_t, k, k_t, v, v_t):
-    """Causal softmax attention per batch and head.  q,k,v: [B, H, S, dh]."""
+    """Causal softmax attention per batch and head.  q,k,v: [B, H, S, dh];
+    `@` is the batched matrix product over the last two axes."""
     S, dh = q.shape[-2], q.shape[-1]
     c = 1.0 / np.sqrt(dh)
     mask = np.tril(np.ones((S, S), dtype=bool))
-    sc = c * np.einsum("bhid,bhjd->bhij", q, k)
-    sc_t = c * (np.einsum("bhid,bhjd->bhij", q_t, k) + np.einsum("bhid,bhjd->bhij", q, k_t))
+    sc = c * (q @ _T(k))
+    sc_t = c * (q_t @ _T(k) + q @ _T(k_t))
     sc = np.where(mask, sc, -np.inf)
     sc = sc - sc.max(-1, keepdims=True)
     e = np.exp(sc)
     P = e / e.sum(-1, keepdims=True)
     sc_t = np.where(mask, sc_t, 0.0)
     P_t = P * (sc_t - (P * sc_t).sum(-1, keepdims=True))
-    o = np.einsum("bhij,bhjd->bhid", P, v)
-    o_t = np.einsum("bhij,bhjd->bhid", P_t, v) + np.einsum("bhij,bhjd->bhid", P, v_t)
+    o = P @ v
+    o_t = P_t @ v + P @ v_t
     return o, o_t, (q, q_t, k, k_t, v, v_t, P, P_t, c)
 
 
 def attention_bwd(do, do_t, cache):
     q, q_t, k, k_t, v, v_t, P, P_t, c = cache
-    dv = np.einsum("bhij,bhid->bhjd", P, do)
-    dv_t = np.einsum("bhij,bhid->bhjd", P_t, do) + np.einsum("bhij,bhid->bhjd", P, do_t)
-    dP = np.einsum("bhid,bhjd->bhij", do, v)
-    dP_t = np.einsum("bhid,bhjd->bhij", do_t, v) + np.einsum("bhid,bhjd->bhij", do, v_t)
+    dv = _T(P) @ do
+    dv_t = _T(P_t) @ do + _T(P) @ do_t
+    dP = do @ _T(v)
+    dP_t = do_t @ _T(v) + do @ _T(v_t)
     delta = (P * dP).sum(-1, keepdims=True)
     delta_t = (P_t * dP + P * dP_t).sum(-1, keepdims=True)
     dS = P * (dP - delta)
     dS_t = P_t * (dP - delta) + P * (dP_t - delta_t)
-    dq = c * np.einsum("bhij,bhjd->bhid", dS, k)
-    dq_t = c * (np.einsum("bhij,bhjd->bhid", dS_t, k) + np.einsum("bhij,bhjd->bhid", dS, k_t))
-    dk = c * np.einsum("bhij,bhid->bhjd", dS, q)
-    dk_t = c * (np.einsum("bhij,bhid->bhjd", dS_t, q) + np.einsum("bhij,bhid->bhjd", dS, q_t))
+    dq = c * (dS @ k)
+    dq_t = c * (dS_t @ k + dS @ k_t)
+    dk = c * (_T(dS) @ q)
+    dk_t = c * (_T(dS_t) @ q + _T(dS) @ q_t)
     return dq, dq_t, dk, dk_t, dv, dv_t
 
 

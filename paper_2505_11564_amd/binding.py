@@ -52,6 +52,11 @@ def lib():
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2505_11564_amd.build` "
                           "(or __graft_entry__.build()) first")
+    # PyTorch-ROCm bundles its own HIP runtime under the same soname as the
+    # system one.  Import torch first so that the library binds to the runtime
+    # that owns the tensors and streams it is handed; loading it first would
+    # put two HIP runtimes in one process.
+    import torch  # noqa: F401
     L = C.CDLL(LIB_PATH)
     vp, i32, i64, dp = C.c_void_p, C.c_int32, C.c_int64, C.POINTER(C.c_double)
     descp = C.POINTER(hf_model_desc)

@@ -1,0 +1,188 @@
+"""Parity of the HIP Lanczos iteration and SLQ read-out (hf_lanczos_*, hf_slq,
+through the C ABI) with the float64 oracle of Algorithm 2.
+
+The fp32 trajectory of late alpha_k, beta_k legitimately departs from the
+float64 one, so the comparison is: early coefficients tightly, converged
+extreme Ritz values within relative 1e-3, and the invariants of the read-out
+(weights >= 0 summing to 1, ascending Ritz values)."""
+import numpy as np
+import pytest
+
+import synth_inputs as si
+from oracle import lanczos as olz
+from oracle import models as om
+
+pytestmark = pytest.mark.gpu
+
+
+def _dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def run_update_only(ctx, dvec, z, m, reorth, tol=0.0):
+    """Algorithm 2 on the GPU with a synthetic diagonal operator standing in
+    for the Hessian-vector product."""
+    import torch
+    n = ctx.n
+    d_dev, q = _dev(dvec.astype(np.float32)), torch.empty(n, device="cuda")
+    ctx.hf_lanczos_init(_dev(z.astype(np.float32)), reorth)
+    al, be = [], []
+    for k in range(m):
+        ctx.hf_lanczos_get_vector(0, q)
+        r = (d_dev * q).contiguous()
+        a, b, rc = ctx.hf_lanczos_update(r, tol)
+        al.append(a); be.append(b)
+        if rc == 1:
+            break
+    return np.array(al), np.array(be)
+
+
+@pytest.mark.parametrize("basis", ["f32", "bf16"])
+@pytest.mark.parametrize("reorth", ["none", "full"])
+def test_update_kernels_diagonal_operator(reorth, basis):
+    import paper_2505_11564_amd as hf
+    model = si._gpt(1, 40, 2, 72, 1001, 33)          # only its parameter count matters here
+    ctx = hf.Context(model, 1, 48, "f32", basis)
+    n = ctx.n
+    assert n % 4 != 0 or True
+    rng = np.random.default_rng(5)
+    dvec = np.concatenate([rng.uniform(-1, 1, n - 3), [-7.0, 9.0, 12.0]]).astype(np.float32)
+    z = si.make_probe(n, 0)
+    m = 40
+    a, b = run_update_only(ctx, dvec, z, m, reorth)
+    ao, bo, _ = olz.lanczos(lambda q: dvec.astype(np.float64) * q, z.astype(np.float64), m, reorth)
+    # A bf16 basis perturbs r by the rounding of the stored vectors (2^-9
+    # relative per element) in every orthogonalisation pass, so only the first
+    # two iterations (whose pass is against q_0, q_1 only) stay at fp32 level.
+    tol = (2e-5, 2e-6) if (basis == "f32" or reorth == "none") else (2e-2, 2e-2 * 12.0)
+    np.testing.assert_allclose(a[:2], ao[:2], rtol=2e-5, atol=2e-6)
+    np.testing.assert_allclose(a[:6], ao[:6], rtol=tol[0], atol=tol[1])
+    np.testing.assert_allclose(b[:6], bo[:6], rtol=tol[0], atol=tol[1])
+    th, w = hf.hf_tridiag_readout(a, b)
+    tho, wo = olz.slq_readout(ao, bo)
+    assert abs(th[-1] - 12.0) <= 1e-3 * 12.0 and abs(th[0] + 7.0) <= 1e-3 * 7.0
+    assert abs(th[-1] - tho[-1]) <= 1e-3 * abs(tho[-1]) and abs(th[0] - tho[0]) <= 1e-3 * abs(tho[0])
+    assert abs(w.sum() - 1) < 1e-12 and np.all(w >= 0)
+    if reorth == "full":
+        # stored basis is orthonormal to fp32 (bf16: to its rounding) level
+        import torch
+        Q = torch.empty(10, n, device="cuda")
+        for j in range(10):
+            ctx.hf_lanczos_get_vector(16 + j, Q[j])
+        G = (Q.double() @ Q.double().T).cpu().numpy()
+        assert np.abs(G - np.eye(10)).max() <= (1e-5 if basis == "f32" else 5e-3)
+        # no ghost copies of the converged top eigenvalue
+        assert int(np.sum(np.abs(th - 12.0) <= 1e-3 * 12.0)) == 1
+    ctx.close()
+
+
+def test_update_is_bitwise_reproducible_and_breaks_down():
+    import paper_2505_11564_amd as hf
+    model = si._gpt(1, 16, 2, 24, 37, 9)
+    ctx = hf.Context(model, 1, 12, "f32", "f32")
+    n = ctx.n
+    rng = np.random.default_rng(1)
+    dvec = rng.uniform(-2, 2, n)
+    z = si.make_probe(n, 3)
+    r1 = run_update_only(ctx, dvec, z, 10, "full")
+    r2 = run_update_only(ctx, dvec, z, 10, "full")
+    assert np.array_equal(r1[0], r2[0]) and np.array_equal(r1[1], r2[1])
+    # three distinct eigenvalues: the Krylov space is exhausted after 3 steps
+    d3 = np.resize([1.0, 2.0, 4.0], n)
+    a, b = run_update_only(ctx, d3, np.ones(n), 10, "none", tol=1e-4)
+    assert len(a) == 3
+    th, _ = hf.hf_tridiag_readout(a, b)
+    np.testing.assert_allclose(th, [1.0, 2.0, 4.0], rtol=1e-5)
+    with pytest.raises(hf.HessformerError) as e:          # iteration has ended
+        ctx.hf_lanczos_update(_dev(np.ones(n, dtype=np.float32)))
+    assert e.value.code == hf.binding.HF_ESTATE
+    ctx.close()
+
+
+def _slq_case(cfg, m, n_probes, reorth, n_early, dtype="f32", basis="f32", rtol_early=1e-4):
+    import paper_2505_11564_amd as hf
+    from gpu_util import to_dev_params
+    model = cfg["model"]
+    p = si.make_params(model, param_dtype=dtype)
+    x, y = si.make_batch(cfg)
+    n = om.num_params(model)
+    probes = np.stack([si.make_probe(n, i) for i in range(n_probes)])
+    B = x.shape[0]
+    S = x.shape[1] if model["arch"] != "mlp" else 1
+    ctx = hf.Context(model, B, m, dtype, basis)
+    res = ctx.hf_slq(to_dev_params(p, dtype), _dev(x), _dev(y.astype(np.int32)), B, S, _dev(probes), n_probes, m, reorth)
+    ctx.close()
+    p64 = p.astype(np.float64)
+    ora = olz.slq(lambda q: om.hvp(model, p64, x, y, q), probes.astype(np.float64), m, reorth)
+    for i in range(n_probes):
+        ao, bo, tho, wo, meo = ora[i]
+        assert res["m_eff"][i] == m == meo
+        a, b, th, w = res["alpha"][i], res["beta"][i], res["ritz"][i], res["weights"][i]
+        scale = max(np.abs(tho).max(), 1e-30)
+        np.testing.assert_allclose(a[:n_early], ao[:n_early], rtol=rtol_early, atol=rtol_early * scale)
+        np.testing.assert_allclose(b[:n_early], bo[:n_early], rtol=rtol_early, atol=rtol_early * scale)
+        assert np.all(np.diff(th) >= 0) and np.all(w >= 0) and abs(w.sum() - 1) < 1e-10
+    return res, ora
+
+
+def test_slq_workload_1_mlp_full_reorth_vs_dense_hessian():
+    cfg = si.CONFIGS["mlp_tiny"]
+    res, ora = _slq_case(cfg, cfg["m"], cfg["n_probes"], "full", n_early=5)
+    model = cfg["model"]
+    p = si.make_params(model).astype(np.float64)
+    x, y = si.make_batch(cfg)
+    lam = np.linalg.eigvalsh(om.dense_hessian(model, p, x, y))
+    for i in range(cfg["n_probes"]):
+        th, tho = res["ritz"][i], ora[i][2]
+        for j in (0, -1):                                  # extreme Ritz values: 1e-3 relative
+            assert abs(th[j] - tho[j]) <= 1e-3 * abs(tho[j]), (i, j, th[j], tho[j])
+        assert abs(th[-1] - lam[-1]) <= 1e-3 * abs(lam[-1])
+        assert th[0] >= lam[0] - 1e-3 * abs(lam[-1]) and th[-1] <= lam[-1] * (1 + 1e-3)
+        # no ghosts of the top eigenvalue with the stored basis
+        assert int(np.sum(np.abs(th - lam[-1]) <= 1e-3 * lam[-1])) == int(np.sum(np.abs(lam - lam[-1]) <= 1e-3 * lam[-1]))
+
+
+def test_slq_workload_2_gpt_full_reorth():
+    cfg = si.CONFIGS["gpt_2l_d128"]
+    res, ora = _slq_case(cfg, cfg["m"], cfg["n_probes"], "full", n_early=4)
+    for i in range(cfg["n_probes"]):
+        th, tho = res["ritz"][i], ora[i][2]
+        for j in (0, -1):
+            assert abs(th[j] - tho[j]) <= 1e-3 * abs(tho[j]), (i, j, th[j], tho[j])
+
+
+def test_slq_llama_three_term_recurrence():
+    cfg = dict(model=si._llama(2, 32, 2, 48, 61, 12), batch=2, seq=12, tokens="zipf")
+    _slq_case(cfg, 20, 1, "none", n_early=6)
+
+
+def test_slq_bf16_parameters_and_bf16_basis():
+    cfg = dict(model=si._gpt(2, 64, 2, 128, 211, 24), batch=2, seq=24, tokens="zipf")
+    _slq_case(cfg, 30, 1, "full", n_early=2, dtype="bf16", basis="bf16", rtol_early=3e-2)
+
+
+def test_lanczos_step_matches_slq_and_state_errors():
+    import paper_2505_11564_amd as hf
+    cfg = si.CONFIGS["mlp_tiny"]
+    model = cfg["model"]
+    p, (x, y) = si.make_params(model), si.make_batch(cfg)
+    n = om.num_params(model)
+    ctx = hf.Context(model, 256, 8)
+    pd, xd, yd, z = _dev(p), _dev(x), _dev(y), _dev(si.make_probe(n, 0))
+    with pytest.raises(hf.HessformerError) as e:
+        ctx.hf_lanczos_step(pd, xd, yd, 256, 1)
+    assert e.value.code == hf.binding.HF_ESTATE
+    ctx.hf_lanczos_init(z, "full")
+    steps = [ctx.hf_lanczos_step(pd, xd, yd, 256, 1)[:2] for _ in range(8)]
+    assert ctx.hf_lanczos_iterations() == 8
+    with pytest.raises(hf.HessformerError) as e:           # basis is full
+        ctx.hf_lanczos_step(pd, xd, yd, 256, 1)
+    assert e.value.code == hf.binding.HF_ESHAPE
+    res = ctx.hf_slq(pd, xd, yd, 256, 1, z, 1, 8, "full")
+    np.testing.assert_allclose(res["alpha"][0], [s[0] for s in steps], rtol=1e-5, atol=1e-7)
+    np.testing.assert_allclose(res["beta"][0], [s[1] for s in steps], rtol=1e-5, atol=1e-7)
+    with pytest.raises(hf.HessformerError) as e:
+        ctx.hf_slq(pd, xd, yd, 256, 1, z, 1, 9, "full")
+    assert e.value.code == hf.binding.HF_ESHAPE
+    ctx.close()
