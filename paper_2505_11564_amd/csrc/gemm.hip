@@ -13,29 +13,11 @@
 //   gemm_f32_kernel  : fp32 operands, plain FMA, fully guarded; used by the
 //                      fp32 parity configurations, which are launch-bound.
 #include "hf_internal.h"
+#include "gemm_params.h"
+
+#include <cstdlib>
 
 namespace hf {
-
-struct GemmP {
-  const void* A0;
-  const void* A1;
-  const void* B0;
-  const void* B1;
-  void* C;
-  const float* Cadd;
-  const void* bias;
-  const float* bias_t;
-  int M, N, K;
-  int64_t lda, ldb, ldc;
-  int transA, transB;
-  int nb2;
-  int64_t sA1, sA2, sB1, sB2, sC1, sC2;
-  float alpha;
-  int out_bf16, bias_bf16;
-  int klimit, skip_upper;
-  int tiles_n;
-  int vecA, vecB;  // operands satisfy the alignment the vector loaders need
-};
 
 // ------------------------------------------------------------------ fp32 ----
 
@@ -322,6 +304,16 @@ hipError_t launch_gemm(const Gemm& g, hipStream_t st) {
   };
   p.vecA = vec_ok(g.A[0], g.A[1], g.lda, g.sA1, g.sA2, !g.transA);
   p.vecB = vec_ok(g.B[0], g.B[1], g.ldb, g.sB1, g.sB2, g.transB != 0);
+  // Fast path: every operand row starts 16-byte aligned (both loaders move
+  // 16 B chunks) and the problem is at least one tile's worth of work.
+  auto fast_ok = [&](const void* x0, const void* x1, int64_t ld, int64_t s1, int64_t s2, int rows_contig, int R) {
+    return aligned_to(x0, 16) && aligned_to(x1, 16) && ld % 8 == 0 && s1 % 8 == 0 && s2 % 8 == 0 &&
+           (!rows_contig || ld >= ((R + 7) / 8) * 8);
+  };
+  static const int force_v1 = std::getenv("HF_GEMM_V1") ? 1 : 0;
+  if (!force_v1 && g.M >= 8 && g.N >= 8 && fast_ok(g.A[0], g.A[1], g.lda, g.sA1, g.sA2, g.transA, g.M) &&
+      fast_ok(g.B[0], g.B[1], g.ldb, g.sB1, g.sB2, !g.transB, g.N))
+    return launch_gemm_mfma(p, nb, g.allow_splitk, g.force_cfg, g.force_ks, st);
   constexpr int BM = 128, BN = 128;
   p.tiles_n = (g.N + BN - 1) / BN;
   dim3 grid(p.tiles_n * ((g.M + BM - 1) / BM), nb);

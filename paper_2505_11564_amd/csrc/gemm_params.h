@@ -1,0 +1,33 @@
+// Kernel-side parameter block shared by the matrix-product kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace hf {
+
+struct GemmP {
+  const void* A0;
+  const void* A1;
+  const void* B0;
+  const void* B1;
+  void* C;
+  const float* Cadd;
+  const void* bias;
+  const float* bias_t;
+  int M, N, K;
+  int64_t lda, ldb, ldc;
+  int transA, transB;
+  int nb2;
+  int64_t sA1, sA2, sB1, sB2, sC1, sC2;
+  float alpha;
+  int out_bf16, bias_bf16;
+  int klimit, skip_upper;
+  int tiles_n;
+  int vecA, vecB;  // operands satisfy the alignment the vector loaders need
+};
+
+// MFMA path with direct global->LDS loads; needs 16-byte aligned operand rows.
+// force_cfg / force_ks < 0 (<= 0): choose automatically.
+hipError_t launch_gemm_mfma(GemmP p, int nb, int allow_splitk, int force_cfg, int force_ks, hipStream_t st);
+
+}  // namespace hf

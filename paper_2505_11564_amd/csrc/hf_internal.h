@@ -59,6 +59,8 @@ struct Gemm {
   int klimit = 0;  // 0 none; 1: k <= row (A lower-triangular in (m,k));
                    // 2: k >= m (A upper-triangular in (m,k))
   int skip_upper = 0;  // skip output tiles with n0 > m_last (causal scores)
+  int allow_splitk = 0;  // fp32 C only: few output tiles, long k -> split k with atomics
+  int force_cfg = -1, force_ks = 0;  // tuning / tests: tile configuration and k-split override
 };
 
 hipError_t launch_gemm(const Gemm& g, hipStream_t st);
