@@ -213,6 +213,7 @@ struct Lin {
     Gemm g;
     g.M = M; g.N = Kin; g.K = Nout; g.lda = lddy; g.ldb = ldw < 0 ? Nout : ldw; g.ldc = lddx; g.transB = !transW;
     g.in_bf16 = bf; g.out_bf16 = out_bf16;
+    g.allow_splitk = 1;
     g.A[0] = dY; g.B[0] = Wp(woff); g.C = dX; g.Cadd = add;
     CK(launch_gemm(g, st));
     Gemm t = g;
@@ -228,6 +229,7 @@ struct Lin {
     Gemm g;
     g.M = Kin; g.N = Nout; g.K = T; g.lda = ldx; g.ldb = lddy; g.ldc = Nout; g.transA = 1;
     g.in_bf16 = bf; g.out_bf16 = 0;
+    g.allow_splitk = 1;
     g.C = out + woff;
     if (X_t) { g.A[0] = X_t; g.B[0] = dY; g.A[1] = X; g.B[1] = dY_t; }
     else { g.A[0] = X; g.B[0] = dY_t; }

@@ -278,9 +278,9 @@ hipError_t launch_gemm_mfma(GemmP p, int nb, int allow_splitk, int force_cfg, in
   const int64_t nt = tiles(bm, bn);
   int ks = 1;
   if (force_ks > 0) ks = force_ks;
-  else if (allow_splitk && !p.out_bf16 && !p.klimit && nt < 192) {
+  else if (allow_splitk && !p.out_bf16 && !p.klimit && nt < 384) {
     const int slabs = (p.A1 ? 2 : 1) * (p.K / KT);
-    ks = (int)std::min<int64_t>(std::max<int64_t>(1, 512 / nt), std::max(1, slabs / 4));
+    ks = (int)std::min<int64_t>(std::max<int64_t>(1, (512 + nt - 1) / nt), std::max(1, slabs / 4));
     ks = std::min(ks, 16);
   }
   if (ks > 1) {
