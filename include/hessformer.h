@@ -72,7 +72,7 @@ typedef enum {
 } hf_status;
 
 typedef enum { HF_ARCH_MLP = 0, HF_ARCH_GPT = 1, HF_ARCH_LLAMA = 2 } hf_arch;
-typedef enum { HF_F32 = 0, HF_BF16 = 1 } hf_dtype;
+typedef enum { HF_F32 = 0, HF_BF16 = 1, HF_NONE = 2 /* basis_dtype only: store no basis */ } hf_dtype;
 typedef enum { HF_REORTH_NONE = 0, HF_REORTH_FULL = 1 } hf_reorth;
 
 /* Model description.  MLP uses mlp_*; GPT/LLAMA use the transformer fields.
@@ -90,7 +90,8 @@ typedef struct {
   float norm_eps;
   float rope_theta;
   int32_t param_dtype;    /* hf_dtype of params_dev */
-  int32_t basis_dtype;    /* hf_dtype of the stored Lanczos basis */
+  int32_t basis_dtype;    /* hf_dtype of the stored Lanczos basis; HF_NONE: no basis is
+                             allocated and only HF_REORTH_NONE iterations can run */
 } hf_model_desc;
 
 /* ---- host-only helpers (no GPU needed) ---------------------------------- */

@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(HERE, "libhessformer_hip.so")
 HF_OK, HF_EBREAKDOWN = 0, 1
 HF_EINVAL, HF_ENOMEM, HF_EDEVICE, HF_ESHAPE, HF_ESTATE = -1, -2, -3, -4, -5
 HF_ARCH = {"mlp": 0, "gpt": 1, "llama": 2}
-HF_DTYPE = {"f32": 0, "bf16": 1}
+HF_DTYPE = {"f32": 0, "bf16": 1, "none": 2}
 HF_REORTH = {"none": 0, "full": 1}
 
 EXPORTS = [

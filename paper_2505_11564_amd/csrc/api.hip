@@ -218,6 +218,7 @@ int32_t hf_lanczos_init(hf_ctx* ctx, const float* q0_dev, int32_t reorth, void* 
   if (!q0_dev) return c->fail(HF_EINVAL, "hf_lanczos_init: NULL q0_dev");
   if (reorth != HF_REORTH_NONE && reorth != HF_REORTH_FULL) return c->fail(HF_EINVAL, "hf_lanczos_init: bad reorth");
   if (c->max_m <= 0) return c->fail(HF_ESHAPE, "hf_lanczos_init: context was created with max_m = 0");
+  if (reorth == HF_REORTH_FULL && !c->basis) return c->fail(HF_ESHAPE, "hf_lanczos_init: context was created without a basis (basis_dtype HF_NONE)");
   c->lz_k = -1;
   c->iq = 0; c->iqp = 1; c->ir = 2;
   float* q = c->lz_vec[c->iq];

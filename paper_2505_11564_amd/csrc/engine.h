@@ -55,7 +55,10 @@ struct hf_ctx {
   std::vector<hf::LayerBuf> lb;
   hf::bf16* vb = nullptr;  // bf16 copy of the direction (bf16 mode)
   float *xL = nullptr, *xL_t = nullptr, *stf = nullptr;
-  void *xf = nullptr, *xf_t = nullptr;
+  void *xf = nullptr, *xf_t = nullptr, *xf_lo = nullptr;
+  // bf16 mode: low-order halves of the primal forward activations (reused by every layer)
+  void *a_lo = nullptr, *qkv_lo = nullptr, *P_lo = nullptr, *o_lo = nullptr, *f_lo = nullptr, *up_lo = nullptr, *g_lo = nullptr;
+  float *rq = nullptr, *rq_t = nullptr;  // LLAMA: fp32 q|k (or their adjoints) before the rotation
   float *z = nullptr, *z_t = nullptr;
   void *dz = nullptr, *dz_t = nullptr;
   int64_t ldz = 0;

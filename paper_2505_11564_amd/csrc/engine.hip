@@ -28,7 +28,7 @@ int hf::build_layout(const hf_model_desc& d, std::vector<LayoutEntry>& out, std:
   };
   auto bad = [&](const char* m) { if (why) *why = m; return (int)HF_EINVAL; };
   if (d.param_dtype != HF_F32 && d.param_dtype != HF_BF16) return bad("param_dtype must be HF_F32 or HF_BF16");
-  if (d.basis_dtype != HF_F32 && d.basis_dtype != HF_BF16) return bad("basis_dtype must be HF_F32 or HF_BF16");
+  if (d.basis_dtype != HF_F32 && d.basis_dtype != HF_BF16 && d.basis_dtype != HF_NONE) return bad("basis_dtype must be HF_F32, HF_BF16 or HF_NONE");
   if (d.arch == HF_ARCH_MLP) {
     if (d.mlp_in <= 0 || d.mlp_hidden <= 0 || d.mlp_out <= 1) return bad("MLP sizes must be positive (mlp_out >= 2)");
     add("W1", d.mlp_in, d.mlp_hidden); add("b1", d.mlp_hidden, 0);
@@ -122,6 +122,12 @@ int hf_ctx::plan_and_alloc() {
     }
     pl.add(xL, T * D * 4); pl.add(xL_t, T * D * 4); pl.add(stf, T * 16);
     pl.add(xf, T * D * e); pl.add(xf_t, T * D * e);
+    if (bf) {
+      pl.add(xf_lo, T * D * e); pl.add(a_lo, T * D * e); pl.add(o_lo, T * D * e); pl.add(qkv_lo, T * 3 * D * e);
+      pl.add(P_lo, SS * e); pl.add(f_lo, T * F * e); pl.add(g_lo, T * F * e);
+      if (llama) pl.add(up_lo, T * F * e);
+    }
+    if (llama) { pl.add(rq, T * 2 * D * 4); pl.add(rq_t, T * 2 * D * 4); }
     ldz = round_up(desc.vocab, 64);
     pl.add(z, T * ldz * 4); pl.add(z_t, T * ldz * 4);
     pl.add(dz, T * ldz * e); pl.add(dz_t, T * ldz * e);
@@ -145,7 +151,7 @@ int hf_ctx::plan_and_alloc() {
   if (max_m > 0) {
     for (int i = 0; i < 3; ++i) pl.add(lz_vec[i], n * 4);
     ldq = round_up(n, 64);
-    pl.add(basis, (int64_t)max_m * ldq * (desc.basis_dtype == HF_BF16 ? 2 : 4));
+    if (desc.basis_dtype != HF_NONE) pl.add(basis, (int64_t)max_m * ldq * (desc.basis_dtype == HF_BF16 ? 2 : 4));
     pl.add(scal, S_COUNT * 8);
     pl.add(cvec, (int64_t)max_m * 8);
     pl.add(partials, (int64_t)LZ_NBLK * max_m * 8);
@@ -190,14 +196,21 @@ struct Lin {
   // X_t == nullptr means a zero input tangent.
   int fwd(const void* X, const void* X_t, int M, int K, int N, int64_t ldx, int64_t woff, int64_t boff, void* Y,
           void* Y_t, int64_t ldy, int out_bf16, const float* add = nullptr, const float* add_t = nullptr,
-          int transW = 0, int64_t ldw = -1) const {
+          int transW = 0, int64_t ldw = -1, const void* X_lo = nullptr, void* Y_lo = nullptr) const {
+    // X_lo (bf16 mode): low-order half of the primal input, added as a second
+    // term against the same (exact bf16) weights; Y_lo: low-order half of a
+    // bf16 primal output.  The primal forward chain so keeps ~16 mantissa
+    // bits; tangents and adjoints (linear in their inputs) use the high halves.
     Gemm g;
     g.M = M; g.N = N; g.K = K; g.lda = ldx; g.ldb = ldw < 0 ? N : ldw; g.ldc = ldy; g.transB = transW;
     g.in_bf16 = bf; g.out_bf16 = out_bf16;
     g.A[0] = X; g.B[0] = Wp(woff); g.C = Y; g.Cadd = add;
+    if (X_lo) { g.A[1] = X_lo; g.B[1] = g.B[0]; }
+    if (out_bf16) g.C_lo = Y_lo;
     if (boff >= 0) g.bias = Wp(boff);
     CK(launch_gemm(g, st));
     Gemm t = g;
+    t.A[1] = nullptr; t.B[1] = nullptr; t.C_lo = nullptr;
     t.C = Y_t; t.Cadd = add_t; t.bias = nullptr;
     if (boff >= 0) t.bias_t = v + boff;
     if (X_t) { t.A[0] = X_t; t.B[0] = Wp(woff); t.A[1] = X; t.B[1] = Wt(woff); }
@@ -283,7 +296,7 @@ int hf_ctx::hvp_mlp(const void* params, const void* inputs, const int32_t* label
   if (bf) { CK(launch_f32_to_bf16((const float*)inputs, (bf16*)xin, (int64_t)B * I, st)); X = xin; }
   int rc;
   if ((rc = L.fwd(X, nullptr, B, I, Hd, I, off_w1, off_b1, b.f, b.f_t, Hd, bf))) return rc;
-  CK(launch_act_fwd(bf, ACT_TANH, b.f, b.f_t, b.g, b.g_t, (int64_t)B * Hd, st));
+  CK(launch_act_fwd(bf, ACT_TANH, b.f, b.f_t, nullptr, b.g, b.g_t, nullptr, (int64_t)B * Hd, st));
   if ((rc = L.fwd(b.g, b.g_t, B, Hd, O, Hd, off_w2, off_b2, z, z_t, ldz, 0))) return rc;
   CK(launch_count_valid(labels, B, O, flags + 1, flags, st));
   CK(launch_ce(bf, z, z_t, labels, flags + 1, B, O, ldz, dz, dz_t, loss_rows, st));
@@ -329,54 +342,71 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
     const LayerOff& o = loff[l];
     float* xn = (l + 1 < NL) ? lb[l + 1].x1 : xL;
     float* xn_t = (l + 1 < NL) ? lb[l + 1].x1_t : xL_t;
+    // *_lo buffers (bf16 mode, shared by all layers) hold the low-order halves
+    // of the primal activations of the forward chain.
     CK(launch_norm_fwd(bf, rms, b.x1, b.x1_t, L.Wp(o.n1g), rms ? nullptr : L.Wp(o.n1b), v + o.n1g,
-                       rms ? nullptr : v + o.n1b, T, D, eps, b.a, b.a_t, b.st1, st));
+                       rms ? nullptr : v + o.n1b, T, D, eps, b.a, b.a_t, a_lo, b.st1, st));
     if (!llama) {
-      if ((rc = L.fwd(b.a, b.a_t, T, D, 3 * D, D, o.wqkv, o.bqkv, b.qkv, b.qkv_t, 3 * D, bf))) return rc;
+      if ((rc = L.fwd(b.a, b.a_t, T, D, 3 * D, D, o.wqkv, o.bqkv, b.qkv, b.qkv_t, 3 * D, bf, nullptr, nullptr, 0, -1, a_lo, qkv_lo))) return rc;
     } else {
-      const int64_t w3[3] = {o.wq, o.wk, o.wv};
-      for (int i = 0; i < 3; ++i)
-        if ((rc = L.fwd(b.a, b.a_t, T, D, D, D, w3[i], -1, at(b.qkv, (int64_t)i * D), at(b.qkv_t, (int64_t)i * D), 3 * D, bf))) return rc;
-      CK(launch_rope(bf, b.qkv, b.qkv_t, T, S, 3 * D, 2 * H, dh, desc.rope_theta, 0, st));
+      // q and k leave their products in fp32 and are rounded once, after the rotation
+      if ((rc = L.fwd(b.a, b.a_t, T, D, D, D, o.wq, -1, rq, rq_t, 2 * D, 0, nullptr, nullptr, 0, -1, a_lo))) return rc;
+      if ((rc = L.fwd(b.a, b.a_t, T, D, D, D, o.wk, -1, rq + D, rq_t + D, 2 * D, 0, nullptr, nullptr, 0, -1, a_lo))) return rc;
+      if ((rc = L.fwd(b.a, b.a_t, T, D, D, D, o.wv, -1, at(b.qkv, 2 * D), at(b.qkv_t, 2 * D), 3 * D, bf, nullptr, nullptr, 0, -1, a_lo,
+                      qkv_lo ? at(qkv_lo, 2 * D) : nullptr))) return rc;
+      CK(launch_rope(bf, rq, rq_t, 2 * D, b.qkv, b.qkv_t, qkv_lo, 3 * D, T, S, 2 * H, dh, desc.rope_theta, 0, st));
     }
     {  // scores S = c Q K^T, S_t = c (Q_t K^T + Q K_t^T); lower-triangular tiles only
       Gemm g; att(g);
       g.M = S; g.N = S; g.K = dh; g.lda = 3 * D; g.ldb = 3 * D; g.ldc = S; g.transB = 1; g.alpha = cs; g.skip_upper = 1;
       set_qkv(g.sA1, g.sA2); set_qkv(g.sB1, g.sB2); set_sc(g.sC1, g.sC2);
       g.A[0] = b.qkv; g.B[0] = cat(b.qkv, D); g.C = sc;
+      if (qkv_lo) {  // (q + q_lo)(k + k_lo)^T without the lo*lo term
+        g.A[1] = qkv_lo; g.B[1] = cat(b.qkv, D);
+        g.A[2] = b.qkv; g.B[2] = cat(qkv_lo, D);
+      }
       CK(launch_gemm(g, st));
+      g.A[2] = nullptr; g.B[2] = nullptr;
       g.A[0] = b.qkv_t; g.B[0] = cat(b.qkv, D); g.A[1] = b.qkv; g.B[1] = cat(b.qkv_t, D); g.C = sc_t;
       CK(launch_gemm(g, st));
     }
-    CK(launch_softmax_fwd(bf, sc, sc_t, b.P, b.P_t, B * H, S, st));
+    CK(launch_softmax_fwd(bf, sc, sc_t, b.P, b.P_t, P_lo, B * H, S, st));
     {  // O = P V, O_t = P_t V + P V_t
       Gemm g; att(g);
       g.M = S; g.N = dh; g.K = S; g.lda = S; g.ldb = 3 * D; g.ldc = D; g.klimit = 1; g.out_bf16 = bf;
       set_sc(g.sA1, g.sA2); set_qkv(g.sB1, g.sB2); set_td(g.sC1, g.sC2);
       g.A[0] = b.P; g.B[0] = cat(b.qkv, 2 * D); g.C = b.o;
+      if (P_lo) {
+        g.A[1] = P_lo; g.B[1] = cat(b.qkv, 2 * D);
+        g.A[2] = b.P; g.B[2] = cat(qkv_lo, 2 * D);
+        g.C_lo = o_lo;
+      }
       CK(launch_gemm(g, st));
+      g.A[2] = nullptr; g.B[2] = nullptr; g.C_lo = nullptr;
       g.A[0] = b.P_t; g.B[0] = cat(b.qkv, 2 * D); g.A[1] = b.P; g.B[1] = cat(b.qkv_t, 2 * D); g.C = b.o_t;
       CK(launch_gemm(g, st));
     }
-    if ((rc = L.fwd(b.o, b.o_t, T, D, D, D, o.wo, o.bo, b.x2, b.x2_t, D, 0, b.x1, b.x1_t))) return rc;
+    if ((rc = L.fwd(b.o, b.o_t, T, D, D, D, o.wo, o.bo, b.x2, b.x2_t, D, 0, b.x1, b.x1_t, 0, -1, o_lo))) return rc;
     CK(launch_norm_fwd(bf, rms, b.x2, b.x2_t, L.Wp(o.n2g), rms ? nullptr : L.Wp(o.n2b), v + o.n2g,
-                       rms ? nullptr : v + o.n2b, T, D, eps, b.m, b.m_t, b.st2, st));
+                       rms ? nullptr : v + o.n2b, T, D, eps, b.m, b.m_t, a_lo, b.st2, st));
     if (!llama) {
-      if ((rc = L.fwd(b.m, b.m_t, T, D, F, D, o.wfc, o.bfc, b.f, b.f_t, F, bf))) return rc;
-      CK(launch_act_fwd(bf, ACT_GELU, b.f, b.f_t, b.g, b.g_t, (int64_t)T * F, st));
-      if ((rc = L.fwd(b.g, b.g_t, T, F, D, F, o.wproj, o.bproj, xn, xn_t, D, 0, b.x2, b.x2_t))) return rc;
+      if ((rc = L.fwd(b.m, b.m_t, T, D, F, D, o.wfc, o.bfc, b.f, b.f_t, F, bf, nullptr, nullptr, 0, -1, a_lo, f_lo))) return rc;
+      CK(launch_act_fwd(bf, ACT_GELU, b.f, b.f_t, f_lo, b.g, b.g_t, g_lo, (int64_t)T * F, st));
+      if ((rc = L.fwd(b.g, b.g_t, T, F, D, F, o.wproj, o.bproj, xn, xn_t, D, 0, b.x2, b.x2_t, 0, -1, g_lo))) return rc;
     } else {
-      if ((rc = L.fwd(b.m, b.m_t, T, D, F, D, o.wgate, -1, b.f, b.f_t, F, bf))) return rc;
-      if ((rc = L.fwd(b.m, b.m_t, T, D, F, D, o.wup, -1, b.up, b.up_t, F, bf))) return rc;
-      CK(launch_swiglu_fwd(bf, b.f, b.f_t, b.up, b.up_t, b.g, b.g_t, (int64_t)T * F, st));
-      if ((rc = L.fwd(b.g, b.g_t, T, F, D, F, o.wdown, -1, xn, xn_t, D, 0, b.x2, b.x2_t))) return rc;
+      if ((rc = L.fwd(b.m, b.m_t, T, D, F, D, o.wgate, -1, b.f, b.f_t, F, bf, nullptr, nullptr, 0, -1, a_lo, f_lo))) return rc;
+      if ((rc = L.fwd(b.m, b.m_t, T, D, F, D, o.wup, -1, b.up, b.up_t, F, bf, nullptr, nullptr, 0, -1, a_lo, up_lo))) return rc;
+      CK(launch_swiglu_fwd(bf, b.f, b.f_t, b.up, b.up_t, f_lo, up_lo, b.g, b.g_t, g_lo, (int64_t)T * F, st));
+      if ((rc = L.fwd(b.g, b.g_t, T, F, D, F, o.wdown, -1, xn, xn_t, D, 0, b.x2, b.x2_t, 0, -1, g_lo))) return rc;
     }
   }
   CK(launch_norm_fwd(bf, rms, xL, xL_t, L.Wp(off_nfg), rms ? nullptr : L.Wp(off_nfb), v + off_nfg,
-                     rms ? nullptr : v + off_nfb, T, D, eps, xf, xf_t, stf, st));
+                     rms ? nullptr : v + off_nfb, T, D, eps, xf, xf_t, xf_lo, stf, st));
   const bool tied = off_head < 0;
-  if (tied) { if ((rc = L.fwd(xf, xf_t, T, D, V, D, off_wte, -1, z, z_t, ldz, 0, nullptr, nullptr, 1, D))) return rc; }
-  else { if ((rc = L.fwd(xf, xf_t, T, D, V, D, off_head, -1, z, z_t, ldz, 0))) return rc; }
+  // The softmax turns an absolute error of a logit into a relative error of
+  // every probability, so the primal logits also take the low-order half.
+  if (tied) { if ((rc = L.fwd(xf, xf_t, T, D, V, D, off_wte, -1, z, z_t, ldz, 0, nullptr, nullptr, 1, D, xf_lo))) return rc; }
+  else { if ((rc = L.fwd(xf, xf_t, T, D, V, D, off_head, -1, z, z_t, ldz, 0, nullptr, nullptr, 0, -1, xf_lo))) return rc; }
 
   // ------------------------------ loss and adjoint seeds ----------------------
   CK(launch_count_valid(labels, T, V, flags + 1, flags, st));
@@ -447,22 +477,27 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
       Gemm g; att(g);
       g.M = S; g.N = dh; g.K = S; g.lda = S; g.ldb = 3 * D; g.ldc = 3 * D; g.klimit = 1; g.alpha = cs; g.out_bf16 = bf;
       set_sc(g.sA1, g.sA2); set_qkv(g.sB1, g.sB2); set_qkv(g.sC1, g.sC2);
-      g.A[0] = dS; g.B[0] = cat(b.qkv, D); g.C = dqkv;
+      void *cq = dqkv, *cq_t = dqkv_t, *ck = at(dqkv, D), *ck_t = at(dqkv_t, D);
+      if (llama) {  // fp32 staging [T, 2D]; rounded once after the inverse rotation
+        g.out_bf16 = 0; g.ldc = 2 * D; g.sC1 = (int64_t)S * 2 * D; g.sC2 = dh;
+        cq = rq; cq_t = rq_t; ck = rq + D; ck_t = rq_t + D;
+      }
+      g.A[0] = dS; g.B[0] = cat(b.qkv, D); g.C = cq;
       CK(launch_gemm(g, st));
-      g.A[0] = dS_t; g.B[0] = cat(b.qkv, D); g.A[1] = dS; g.B[1] = cat(b.qkv_t, D); g.C = dqkv_t;
+      g.A[0] = dS_t; g.B[0] = cat(b.qkv, D); g.A[1] = dS; g.B[1] = cat(b.qkv_t, D); g.C = cq_t;
       CK(launch_gemm(g, st));
       // dK = c dS^T Q, dK_t = c (dS_t^T Q + dS^T Q_t)
       g.transA = 1; g.klimit = 2;
-      g.A[0] = dS; g.B[0] = b.qkv; g.A[1] = nullptr; g.B[1] = nullptr; g.C = at(dqkv, D);
+      g.A[0] = dS; g.B[0] = b.qkv; g.A[1] = nullptr; g.B[1] = nullptr; g.C = ck;
       CK(launch_gemm(g, st));
-      g.A[0] = dS_t; g.B[0] = b.qkv; g.A[1] = dS; g.B[1] = b.qkv_t; g.C = at(dqkv_t, D);
+      g.A[0] = dS_t; g.B[0] = b.qkv; g.A[1] = dS; g.B[1] = b.qkv_t; g.C = ck_t;
       CK(launch_gemm(g, st));
     }
     if (!llama) {
       if ((rc = L.bwd_dw(b.a, b.a_t, dqkv, dqkv_t, T, D, 3 * D, D, 3 * D, o.wqkv, o.bqkv, dqkv_t, bf))) return rc;
       if ((rc = L.bwd_dx(dqkv, dqkv_t, T, D, 3 * D, 3 * D, o.wqkv, tmpd, tmpd_t, D, 0))) return rc;
     } else {
-      CK(launch_rope(bf, dqkv, dqkv_t, T, S, 3 * D, 2 * H, dh, desc.rope_theta, 1, st));
+      CK(launch_rope(bf, rq, rq_t, 2 * D, dqkv, dqkv_t, nullptr, 3 * D, T, S, 2 * H, dh, desc.rope_theta, 1, st));
       const int64_t w3[3] = {o.wq, o.wk, o.wv};
       for (int i = 0; i < 3; ++i) {
         const void* dyi = cat(dqkv, (int64_t)i * D);

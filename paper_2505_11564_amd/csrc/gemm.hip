@@ -36,10 +36,10 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmP p) {
   if (p.klimit == 2) kbeg = (m0 / BK) * BK;
   const int tx = t % 16, ty = t / 16;
   float acc[4][4] = {};
-  const int nterm = p.A1 ? 2 : 1;
+  const int nterm = p.nterm;
   for (int term = 0; term < nterm; ++term) {
-    const float* A = (const float*)(term ? p.A1 : p.A0) + offA;
-    const float* B = (const float*)(term ? p.B1 : p.B0) + offB;
+    const float* A = (const float*)p.A[term] + offA;
+    const float* B = (const float*)p.B[term] + offB;
     for (int k0 = kbeg; k0 < kend; k0 += BK) {
       for (int i = t; i < BM * BK; i += 256) {
         int m, k;
@@ -86,7 +86,13 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmP p) {
       if (p.bias_t) v += p.bias_t[gn];
       const int64_t ci = offC + (int64_t)gm * p.ldc + gn;
       if (p.Cadd) v += p.Cadd[ci];
-      if (p.out_bf16) ((bf16*)p.C)[ci] = (bf16)v; else ((float*)p.C)[ci] = v;
+      if (p.out_bf16) {
+            const bf16 hi = (bf16)v;
+            ((bf16*)p.C)[ci] = hi;
+            if (p.C_lo) ((bf16*)p.C_lo)[ci] = (bf16)(v - (float)hi);
+          } else {
+            ((float*)p.C)[ci] = v;
+          }
     }
   }
 }
@@ -208,13 +214,13 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmP p) {
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   const int nk = (kend - kbeg + BK - 1) / BK;
-  const int nterm = p.A1 ? 2 : 1;
+  const int nterm = p.nterm;
   const int total = nk * nterm;
   uint4 ra[BM / 64], rb[BN / 64];
   auto fetch = [&](int it) {
     const int term = it / nk, k0 = kbeg + (it % nk) * BK;
-    const bf16* A = (const bf16*)(term ? p.A1 : p.A0) + offA;
-    const bf16* B = (const bf16*)(term ? p.B1 : p.B0) + offB;
+    const bf16* A = (const bf16*)p.A[term] + offA;
+    const bf16* B = (const bf16*)p.B[term] + offB;
     // A is k-contiguous when not transposed; B (element (k,n)) when transposed.
     tile_fetch<BM, !TA>(ra, A, p.lda, m0, k0, p.M, kend, p.vecA, t);
     tile_fetch<BN, TB>(rb, B, p.ldb, n0, k0, p.N, kend, p.vecB, t);
@@ -259,7 +265,13 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmP p) {
         float v = p.alpha * acc[i][j][r] + bsum;
         const int64_t ci = offC + (int64_t)gm * p.ldc + gn;
         if (p.Cadd) v += p.Cadd[ci];
-        if (p.out_bf16) ((bf16*)p.C)[ci] = (bf16)v; else ((float*)p.C)[ci] = v;
+        if (p.out_bf16) {
+            const bf16 hi = (bf16)v;
+            ((bf16*)p.C)[ci] = hi;
+            if (p.C_lo) ((bf16*)p.C_lo)[ci] = (bf16)(v - (float)hi);
+          } else {
+            ((float*)p.C)[ci] = v;
+          }
       }
     }
   }
@@ -278,9 +290,13 @@ static bool aligned_to(const void* ptr, size_t a) { return ptr == nullptr || ((u
 
 hipError_t launch_gemm(const Gemm& g, hipStream_t st) {
   if (g.M <= 0 || g.N <= 0 || g.nb1 <= 0 || g.nb2 <= 0) return hipSuccess;
-  if (!g.A[0] || !g.B[0] || !g.C || (g.A[1] && !g.B[1]) || (g.Cadd && g.out_bf16)) return hipErrorInvalidValue;
+  if (!g.A[0] || !g.B[0] || !g.C || (g.A[1] && !g.B[1]) || (g.A[2] && (!g.B[2] || !g.A[1])) || (g.Cadd && g.out_bf16) ||
+      (g.C_lo && !g.out_bf16))
+    return hipErrorInvalidValue;
   GemmP p;
-  p.A0 = g.A[0]; p.A1 = g.A[1]; p.B0 = g.B[0]; p.B1 = g.B[1];
+  p.nterm = 0;
+  for (int i = 0; i < 3; ++i) { p.A[i] = g.A[i]; p.B[i] = g.B[i]; if (g.A[i]) p.nterm = i + 1; }
+  p.C_lo = g.C_lo;
   p.C = g.C; p.Cadd = g.Cadd; p.bias = g.bias; p.bias_t = g.bias_t;
   p.M = g.M; p.N = g.N; p.K = g.K; p.lda = g.lda; p.ldb = g.ldb; p.ldc = g.ldc;
   p.transA = g.transA; p.transB = g.transB; p.nb2 = g.nb2;
@@ -298,21 +314,21 @@ hipError_t launch_gemm(const Gemm& g, hipStream_t st) {
   }
   // vector loaders: k-contiguous operands need 16 B alignment of every row
   // start and batch slice, r-contiguous ones 4 B.
-  auto vec_ok = [&](const void* x0, const void* x1, int64_t ld, int64_t s1, int64_t s2, bool kcontig) {
+  auto vec_ok = [&](const void* x0, const void* x1, const void* x2, int64_t ld, int64_t s1, int64_t s2, bool kcontig) {
     const int64_t q = kcontig ? 8 : 2;
-    return aligned_to(x0, q * 2) && aligned_to(x1, q * 2) && ld % q == 0 && s1 % q == 0 && s2 % q == 0;
+    return aligned_to(x0, q * 2) && aligned_to(x1, q * 2) && aligned_to(x2, q * 2) && ld % q == 0 && s1 % q == 0 && s2 % q == 0;
   };
-  p.vecA = vec_ok(g.A[0], g.A[1], g.lda, g.sA1, g.sA2, !g.transA);
-  p.vecB = vec_ok(g.B[0], g.B[1], g.ldb, g.sB1, g.sB2, g.transB != 0);
+  p.vecA = vec_ok(g.A[0], g.A[1], g.A[2], g.lda, g.sA1, g.sA2, !g.transA);
+  p.vecB = vec_ok(g.B[0], g.B[1], g.B[2], g.ldb, g.sB1, g.sB2, g.transB != 0);
   // Fast path: every operand row starts 16-byte aligned (both loaders move
   // 16 B chunks) and the problem is at least one tile's worth of work.
-  auto fast_ok = [&](const void* x0, const void* x1, int64_t ld, int64_t s1, int64_t s2, int rows_contig, int R) {
-    return aligned_to(x0, 16) && aligned_to(x1, 16) && ld % 8 == 0 && s1 % 8 == 0 && s2 % 8 == 0 &&
+  auto fast_ok = [&](const void* x0, const void* x1, const void* x2, int64_t ld, int64_t s1, int64_t s2, int rows_contig, int R) {
+    return aligned_to(x0, 16) && aligned_to(x1, 16) && aligned_to(x2, 16) && ld % 8 == 0 && s1 % 8 == 0 && s2 % 8 == 0 &&
            (!rows_contig || ld >= ((R + 7) / 8) * 8);
   };
   static const int force_v1 = std::getenv("HF_GEMM_V1") ? 1 : 0;
-  if (!force_v1 && g.M >= 8 && g.N >= 8 && fast_ok(g.A[0], g.A[1], g.lda, g.sA1, g.sA2, g.transA, g.M) &&
-      fast_ok(g.B[0], g.B[1], g.ldb, g.sB1, g.sB2, !g.transB, g.N))
+  if (!force_v1 && g.M >= 8 && g.N >= 8 && fast_ok(g.A[0], g.A[1], g.A[2], g.lda, g.sA1, g.sA2, g.transA, g.M) &&
+      fast_ok(g.B[0], g.B[1], g.B[2], g.ldb, g.sB1, g.sB2, !g.transB, g.N))
     return launch_gemm_mfma(p, nb, g.allow_splitk, g.force_cfg, g.force_ks, st);
   constexpr int BM = 128, BN = 128;
   p.tiles_n = (g.N + BN - 1) / BN;

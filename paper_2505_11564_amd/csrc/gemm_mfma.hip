@@ -152,7 +152,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmP p) {
 
   const int nfull = (kend - kbeg) / KT;          // full slabs per term
   const int ktail = (kend - kbeg) - nfull * KT;  // ragged remainder
-  const int nterm = p.A1 ? 2 : 1;
+  const int nterm = p.nterm;
   // split-K: this block handles slabs [it0, it1) of the nterm*nfull full slabs
   const int total = nterm * nfull;
   const int ks = blockIdx.z, nks = gridDim.z;
@@ -160,8 +160,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmP p) {
 
   auto issue = [&](int it, int buf) {
     const int term = it / nfull, k0 = kbeg + (it % nfull) * KT;
-    const bf16* A = (const bf16*)(term ? p.A1 : p.A0) + offA;
-    const bf16* B = (const bf16*)(term ? p.B1 : p.B0) + offB;
+    const bf16* A = (const bf16*)p.A[term] + offA;
+    const bf16* B = (const bf16*)p.B[term] + offB;
     HF_LDS bf16* sa = smem + buf * STAGE;
     slab_issue<BM, AKC>(A, p.lda, m0, k0, p.M, sa, wave, lane);
     slab_issue<BN, BKC>(B, p.ldb, n0, k0, p.N, sa + A_EL, wave, lane);
@@ -201,8 +201,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmP p) {
   // ragged k remainder (handled by the last split only)
   if (ktail > 0 && ks == nks - 1) {
     for (int term = 0; term < nterm; ++term) {
-      const bf16* A = (const bf16*)(term ? p.A1 : p.A0) + offA;
-      const bf16* B = (const bf16*)(term ? p.B1 : p.B0) + offB;
+      const bf16* A = (const bf16*)p.A[term] + offA;
+      const bf16* B = (const bf16*)p.B[term] + offB;
       const int k0 = kbeg + nfull * KT;
       __syncthreads();
       slab_guarded<BM, AKC>(A, p.lda, m0, k0, p.M, kend, smem, t);
@@ -235,7 +235,13 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmP p) {
           atomicAdd((float*)p.C + ci, v);  // C was zero-filled (or holds Cadd) by the launcher
         } else {
           if (p.Cadd) v += p.Cadd[ci];
-          if (p.out_bf16) ((bf16*)p.C)[ci] = (bf16)v; else ((float*)p.C)[ci] = v;
+          if (p.out_bf16) {
+            const bf16 hi = (bf16)v;
+            ((bf16*)p.C)[ci] = hi;
+            if (p.C_lo) ((bf16*)p.C_lo)[ci] = (bf16)(v - (float)hi);
+          } else {
+            ((float*)p.C)[ci] = v;
+          }
         }
       }
     }
@@ -279,7 +285,7 @@ hipError_t launch_gemm_mfma(GemmP p, int nb, int allow_splitk, int force_cfg, in
   int ks = 1;
   if (force_ks > 0) ks = force_ks;
   else if (allow_splitk && !p.out_bf16 && !p.klimit && nt < 384) {
-    const int slabs = (p.A1 ? 2 : 1) * (p.K / KT);
+    const int slabs = p.nterm * (p.K / KT);
     ks = (int)std::min<int64_t>(std::max<int64_t>(1, (512 + nt - 1) / nt), std::max(1, slabs / 4));
     ks = std::min(ks, 16);
   }

@@ -6,11 +6,11 @@
 namespace hf {
 
 struct GemmP {
-  const void* A0;
-  const void* A1;
-  const void* B0;
-  const void* B1;
+  const void* A[3];  // up to three (A, B) terms accumulate into one product
+  const void* B[3];
+  int nterm;
   void* C;
+  void* C_lo;  // bf16 C only: optional low-order part, C_lo = bf16(v - float(bf16(v)))
   const float* Cadd;
   const void* bias;
   const float* bias_t;

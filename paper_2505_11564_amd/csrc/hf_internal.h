@@ -31,7 +31,7 @@ struct Err {
 
 // ------------------------------------------------------------- GEMM ----------
 
-// C[z] = alpha * (A0 op B0 + A1 op B1) + bias + bias_t + Cadd[z]
+// C[z] = alpha * (A0 op B0 + A1 op B1 + A2 op B2) + bias + bias_t + Cadd[z]
 //   A element (m,k): transA ? A[k*lda + m] : A[m*lda + k]
 //   B element (k,n): transB ? B[n*ldb + k] : B[k*ldb + n]
 //   batch z = z1*nb2 + z2, operand offset z1*s?1 + z2*s?2 (elements)
@@ -43,9 +43,10 @@ struct Err {
 //   (left untouched); 2 = k-range limited to k <= last row of the tile (A is
 //   lower triangular, e.g. P V); 3 = k-range limited to k >= first column...
 struct Gemm {
-  const void* A[2] = {nullptr, nullptr};
-  const void* B[2] = {nullptr, nullptr};
+  const void* A[3] = {nullptr, nullptr, nullptr};
+  const void* B[3] = {nullptr, nullptr, nullptr};
   void* C = nullptr;
+  void* C_lo = nullptr;  // bf16 C only: low-order part of the result
   const float* Cadd = nullptr;
   const void* bias = nullptr;
   const float* bias_t = nullptr;
@@ -84,31 +85,34 @@ hipError_t launch_embed_bwd(const float* dx_t, const int32_t* tok, int T, int S,
 // LayerNorm (rms = 0) / RMSNorm (rms = 1) with tangent.  stats: [T,4].
 hipError_t launch_norm_fwd(int bf, int rms, const float* x, const float* x_t, const void* gam, const void* bet,
                            const float* gam_t, const float* bet_t, int T, int d, float eps, void* y, void* y_t,
-                           float* stats, hipStream_t st);
+                           void* y_lo, float* stats, hipStream_t st);
 // dx (+)= ..., dx_t (+)= ...; hv_gam / hv_bet += column sums (atomic).
 hipError_t launch_norm_bwd(int bf, int rms, const float* dy, const float* dy_t, const float* x, const float* x_t,
                            const float* stats, const void* gam, const float* gam_t, int T, int d, int accumulate,
                            float* dx, float* dx_t, float* hv_gam, float* hv_bet, hipStream_t st);
 
 enum Act { ACT_TANH = 0, ACT_GELU = 1 };
-hipError_t launch_act_fwd(int bf, int act, const void* a, const void* a_t, void* y, void* y_t, int64_t n, hipStream_t st);
+// a_lo / y_lo (nullable): low-order halves of the primal input / output.
+hipError_t launch_act_fwd(int bf, int act, const void* a, const void* a_t, const void* a_lo, void* y, void* y_t,
+                          void* y_lo, int64_t n, hipStream_t st);
 hipError_t launch_act_bwd(int bf, int act, const void* a, const void* a_t, const void* dy, const void* dy_t, void* da,
                           void* da_t, int64_t n, hipStream_t st);
-hipError_t launch_swiglu_fwd(int bf, const void* g, const void* g_t, const void* u, const void* u_t, void* y, void* y_t,
-                             int64_t n, hipStream_t st);
+hipError_t launch_swiglu_fwd(int bf, const void* g, const void* g_t, const void* u, const void* u_t, const void* g_lo,
+                             const void* u_lo, void* y, void* y_t, void* y_lo, int64_t n, hipStream_t st);
 hipError_t launch_swiglu_bwd(int bf, const void* g, const void* g_t, const void* u, const void* u_t, const void* dy,
                              const void* dy_t, void* dg, void* dg_t, void* du, void* du_t, int64_t n, hipStream_t st);
 
 // Causal softmax over rows of scores [nbh, S, S] with tangent.
-hipError_t launch_softmax_fwd(int bf, const float* s, const float* s_t, void* p, void* p_t, int nbh, int S,
+hipError_t launch_softmax_fwd(int bf, const float* s, const float* s_t, void* p, void* p_t, void* p_lo, int nbh, int S,
                               hipStream_t st);
 hipError_t launch_softmax_bwd(int bf, const void* p, const void* p_t, const float* dp, const float* dp_t, void* ds,
                               void* ds_t, int nbh, int S, hipStream_t st);
 
-// Rotary embedding of the q and k thirds... applied in place to [T, ld] rows,
-// n_head heads of width dh starting at column col0; inverse = transpose.
-hipError_t launch_rope(int bf, void* x, void* x_t, int T, int S, int64_t ld, int n_head, int dh, float theta,
-                       int inverse, hipStream_t st);
+// Rotary embedding: src (fp32, [T, lds], n_head heads of width dh from column
+// 0) rotated into dst (operand type, [T, ldd]); the tangent takes the same
+// rotation; inverse = the transposed rotation (adjoints).
+hipError_t launch_rope(int bf, const float* src, const float* src_t, int64_t lds, void* dst, void* dst_t, void* dst_lo,
+                       int64_t ldd, int T, int S, int n_head, int dh, float theta, int inverse, hipStream_t st);
 
 // Softmax cross-entropy with tangent: dz, dz_t (operand type) from z, z_t
 // (fp32, leading dimension ldz); loss_rows[T] = per-row loss (0 if ignored);

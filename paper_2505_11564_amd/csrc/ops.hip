@@ -157,7 +157,7 @@ template <typename PT, typename AT, bool RMS>
 __global__ __launch_bounds__(256) void norm_fwd_kernel(const float* __restrict__ x, const float* __restrict__ x_t,
                                                        const PT* gam, const PT* bet, const float* gam_t,
                                                        const float* bet_t, int d, float eps, AT* y, AT* y_t,
-                                                       float* stats) {
+                                                       AT* y_lo, float* stats) {
   __shared__ float red[16];
   const int64_t row = blockIdx.x;
   const float* xr = x + row * d;
@@ -188,6 +188,8 @@ __global__ __launch_bounds__(256) void norm_fwd_kernel(const float* __restrict__
     if (!RMS) { yv += ldf(bet, c); yt += bet_t[c]; }
     stf(y, row * d + c, yv);
     stf(y_t, row * d + c, yt);
+    // optional low-order part: y = (AT)y + y_lo to about twice the mantissa
+    if (y_lo) stf(y_lo, row * d + c, yv - (float)(AT)yv);
   }
   if (threadIdx.x == 0) {
     float4 o = make_float4(mu, rstd, mxt, st);
@@ -197,8 +199,8 @@ __global__ __launch_bounds__(256) void norm_fwd_kernel(const float* __restrict__
 
 hipError_t launch_norm_fwd(int bf, int rms, const float* x, const float* x_t, const void* gam, const void* bet,
                            const float* gam_t, const float* bet_t, int T, int d, float eps, void* y, void* y_t,
-                           float* stats, hipStream_t st) {
-#define HF_NF(PT, AT, R) hipLaunchKernelGGL((norm_fwd_kernel<PT, AT, R>), dim3(T), dim3(256), 0, st, x, x_t, (const PT*)gam, (const PT*)bet, gam_t, bet_t, d, eps, (AT*)y, (AT*)y_t, stats)
+                           void* y_lo, float* stats, hipStream_t st) {
+#define HF_NF(PT, AT, R) hipLaunchKernelGGL((norm_fwd_kernel<PT, AT, R>), dim3(T), dim3(256), 0, st, x, x_t, (const PT*)gam, (const PT*)bet, gam_t, bet_t, d, eps, (AT*)y, (AT*)y_t, (AT*)y_lo, stats)
   if (bf) { if (rms) HF_NF(bf16, bf16, true); else HF_NF(bf16, bf16, false); }
   else { if (rms) HF_NF(float, float, true); else HF_NF(float, float, false); }
 #undef HF_NF
@@ -292,13 +294,18 @@ __device__ __forceinline__ void act_derivs(int act, float a, float& f, float& f1
   }
 }
 
+// a_lo / y_lo (optional): low-order parts, a = a + a_lo on input and
+// y_lo = y - round(y) on output, so the primal chain keeps ~16 mantissa bits.
 template <typename AT>
-__global__ void act_fwd_kernel(int act, const AT* a, const AT* a_t, AT* y, AT* y_t, int64_t n) {
+__global__ void act_fwd_kernel(int act, const AT* a, const AT* a_t, const AT* a_lo, AT* y, AT* y_t, AT* y_lo, int64_t n) {
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
     float f, f1, f2;
-    act_derivs(act, ldf(a, i), f, f1, f2);
+    float av = ldf(a, i);
+    if (a_lo) av += ldf(a_lo, i);
+    act_derivs(act, av, f, f1, f2);
     stf(y, i, f);
     stf(y_t, i, f1 * ldf(a_t, i));
+    if (y_lo) stf(y_lo, i, f - (float)(AT)f);
   }
 }
 template <typename AT>
@@ -314,10 +321,11 @@ __global__ void act_bwd_kernel(int act, const AT* a, const AT* a_t, const AT* dy
 }
 static inline int ew_blocks(int64_t n) { return (int)std::min<int64_t>(cdiv(n, 256), 16384); }
 
-hipError_t launch_act_fwd(int bf, int act, const void* a, const void* a_t, void* y, void* y_t, int64_t n, hipStream_t st) {
+hipError_t launch_act_fwd(int bf, int act, const void* a, const void* a_t, const void* a_lo, void* y, void* y_t,
+                          void* y_lo, int64_t n, hipStream_t st) {
   if (n <= 0) return hipSuccess;
-  if (bf) hipLaunchKernelGGL(act_fwd_kernel<bf16>, dim3(ew_blocks(n)), dim3(256), 0, st, act, (const bf16*)a, (const bf16*)a_t, (bf16*)y, (bf16*)y_t, n);
-  else hipLaunchKernelGGL(act_fwd_kernel<float>, dim3(ew_blocks(n)), dim3(256), 0, st, act, (const float*)a, (const float*)a_t, (float*)y, (float*)y_t, n);
+  if (bf) hipLaunchKernelGGL(act_fwd_kernel<bf16>, dim3(ew_blocks(n)), dim3(256), 0, st, act, (const bf16*)a, (const bf16*)a_t, (const bf16*)a_lo, (bf16*)y, (bf16*)y_t, (bf16*)y_lo, n);
+  else hipLaunchKernelGGL(act_fwd_kernel<float>, dim3(ew_blocks(n)), dim3(256), 0, st, act, (const float*)a, (const float*)a_t, (const float*)a_lo, (float*)y, (float*)y_t, (float*)y_lo, n);
   return hipGetLastError();
 }
 hipError_t launch_act_bwd(int bf, int act, const void* a, const void* a_t, const void* dy, const void* dy_t, void* da,
@@ -331,13 +339,17 @@ hipError_t launch_act_bwd(int bf, int act, const void* a, const void* a_t, const
 // SwiGLU y = s(g) u with s(g) = g sigmoid(g):
 //   s' = sig + g sig', s'' = sig' (2 + g (1 - 2 sig)), sig' = sig (1 - sig).
 template <typename AT>
-__global__ void swiglu_fwd_kernel(const AT* g, const AT* g_t, const AT* u, const AT* u_t, AT* y, AT* y_t, int64_t n) {
+__global__ void swiglu_fwd_kernel(const AT* g, const AT* g_t, const AT* u, const AT* u_t, const AT* g_lo,
+                                  const AT* u_lo, AT* y, AT* y_t, AT* y_lo, int64_t n) {
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
-    const float gv = ldf(g, i), uv = ldf(u, i);
+    float gv = ldf(g, i), uv = ldf(u, i);
+    if (g_lo) { gv += ldf(g_lo, i); uv += ldf(u_lo, i); }
     const float sg = 1.f / (1.f + __expf(-gv));
     const float s = gv * sg, s1 = sg + gv * sg * (1.f - sg);
-    stf(y, i, s * uv);
+    const float yv = s * uv;
+    stf(y, i, yv);
     stf(y_t, i, s1 * ldf(g_t, i) * uv + s * ldf(u_t, i));
+    if (y_lo) stf(y_lo, i, yv - (float)(AT)yv);
   }
 }
 template <typename AT>
@@ -355,11 +367,11 @@ __global__ void swiglu_bwd_kernel(const AT* g, const AT* g_t, const AT* u, const
     stf(du_t, i, s1 * gt * d + s * dt);
   }
 }
-hipError_t launch_swiglu_fwd(int bf, const void* g, const void* g_t, const void* u, const void* u_t, void* y, void* y_t,
-                             int64_t n, hipStream_t st) {
+hipError_t launch_swiglu_fwd(int bf, const void* g, const void* g_t, const void* u, const void* u_t, const void* g_lo,
+                             const void* u_lo, void* y, void* y_t, void* y_lo, int64_t n, hipStream_t st) {
   if (n <= 0) return hipSuccess;
-  if (bf) hipLaunchKernelGGL(swiglu_fwd_kernel<bf16>, dim3(ew_blocks(n)), dim3(256), 0, st, (const bf16*)g, (const bf16*)g_t, (const bf16*)u, (const bf16*)u_t, (bf16*)y, (bf16*)y_t, n);
-  else hipLaunchKernelGGL(swiglu_fwd_kernel<float>, dim3(ew_blocks(n)), dim3(256), 0, st, (const float*)g, (const float*)g_t, (const float*)u, (const float*)u_t, (float*)y, (float*)y_t, n);
+  if (bf) hipLaunchKernelGGL(swiglu_fwd_kernel<bf16>, dim3(ew_blocks(n)), dim3(256), 0, st, (const bf16*)g, (const bf16*)g_t, (const bf16*)u, (const bf16*)u_t, (const bf16*)g_lo, (const bf16*)u_lo, (bf16*)y, (bf16*)y_t, (bf16*)y_lo, n);
+  else hipLaunchKernelGGL(swiglu_fwd_kernel<float>, dim3(ew_blocks(n)), dim3(256), 0, st, (const float*)g, (const float*)g_t, (const float*)u, (const float*)u_t, (const float*)g_lo, (const float*)u_lo, (float*)y, (float*)y_t, (float*)y_lo, n);
   return hipGetLastError();
 }
 hipError_t launch_swiglu_bwd(int bf, const void* g, const void* g_t, const void* u, const void* u_t, const void* dy,
@@ -376,7 +388,7 @@ hipError_t launch_swiglu_bwd(int bf, const void* g, const void* g_t, const void*
 
 template <typename AT>
 __global__ __launch_bounds__(256) void softmax_fwd_kernel(const float* __restrict__ s, const float* __restrict__ s_t,
-                                                          AT* p, AT* p_t, int64_t rows, int S) {
+                                                          AT* p, AT* p_t, AT* p_lo, int64_t rows, int S) {
   const int lane = threadIdx.x & 63;
   const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows) return;
@@ -404,13 +416,15 @@ __global__ __launch_bounds__(256) void softmax_fwd_kernel(const float* __restric
     }
     stf(p, row * S + j, pv);
     stf(p_t, row * S + j, pt);
+    if (p_lo) stf(p_lo, row * S + j, pv - (float)(AT)pv);
   }
 }
-hipError_t launch_softmax_fwd(int bf, const float* s, const float* s_t, void* p, void* p_t, int nbh, int S, hipStream_t st) {
+hipError_t launch_softmax_fwd(int bf, const float* s, const float* s_t, void* p, void* p_t, void* p_lo, int nbh, int S,
+                              hipStream_t st) {
   const int64_t rows = (int64_t)nbh * S;
   const int blocks = (int)cdiv(rows, 4);
-  if (bf) hipLaunchKernelGGL(softmax_fwd_kernel<bf16>, dim3(blocks), dim3(256), 0, st, s, s_t, (bf16*)p, (bf16*)p_t, rows, S);
-  else hipLaunchKernelGGL(softmax_fwd_kernel<float>, dim3(blocks), dim3(256), 0, st, s, s_t, (float*)p, (float*)p_t, rows, S);
+  if (bf) hipLaunchKernelGGL(softmax_fwd_kernel<bf16>, dim3(blocks), dim3(256), 0, st, s, s_t, (bf16*)p, (bf16*)p_t, (bf16*)p_lo, rows, S);
+  else hipLaunchKernelGGL(softmax_fwd_kernel<float>, dim3(blocks), dim3(256), 0, st, s, s_t, (float*)p, (float*)p_t, (float*)p_lo, rows, S);
   return hipGetLastError();
 }
 
@@ -458,7 +472,8 @@ hipError_t launch_softmax_bwd(int bf, const void* p, const void* p_t, const floa
 // tangent takes the same rotation, adjoints the transposed one.
 
 template <typename AT>
-__global__ void rope_kernel(AT* x, AT* x_t, int T, int S, int64_t ld, int n_head, int dh, float log2_theta, int inverse) {
+__global__ void rope_kernel(const float* src, const float* src_t, int64_t lds, AT* dst, AT* dst_t, AT* dst_lo,
+                            int64_t ldd, int T, int S, int n_head, int dh, float log2_theta, int inverse) {
   const int half = dh / 2;
   const int64_t total = (int64_t)T * n_head * half;
   for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * blockDim.x) {
@@ -469,22 +484,25 @@ __global__ void rope_kernel(AT* x, AT* x_t, int T, int S, int64_t ld, int n_head
     const double ang = (double)pos * exp2(-2.0 * (double)i / (double)dh * (double)log2_theta);
     float sn = (float)sin(ang), cs = (float)cos(ang);
     if (inverse) sn = -sn;
-    const int64_t a = t * ld + (int64_t)h * dh + i, b = a + half;
-    const float x1 = ldf(x, a), x2 = ldf(x, b);
-    stf(x, a, x1 * cs - x2 * sn);
-    stf(x, b, x2 * cs + x1 * sn);
-    const float y1 = ldf(x_t, a), y2 = ldf(x_t, b);
-    stf(x_t, a, y1 * cs - y2 * sn);
-    stf(x_t, b, y2 * cs + y1 * sn);
+    const int64_t a = t * lds + (int64_t)h * dh + i, b = a + half;
+    const int64_t oa = t * ldd + (int64_t)h * dh + i, ob = oa + half;
+    const float x1 = src[a], x2 = src[b];
+    const float r1 = x1 * cs - x2 * sn, r2 = x2 * cs + x1 * sn;
+    stf(dst, oa, r1);
+    stf(dst, ob, r2);
+    if (dst_lo) { stf(dst_lo, oa, r1 - (float)(AT)r1); stf(dst_lo, ob, r2 - (float)(AT)r2); }
+    const float y1 = src_t[a], y2 = src_t[b];
+    stf(dst_t, oa, y1 * cs - y2 * sn);
+    stf(dst_t, ob, y2 * cs + y1 * sn);
   }
 }
-hipError_t launch_rope(int bf, void* x, void* x_t, int T, int S, int64_t ld, int n_head, int dh, float theta,
-                       int inverse, hipStream_t st) {
+hipError_t launch_rope(int bf, const float* src, const float* src_t, int64_t lds, void* dst, void* dst_t, void* dst_lo,
+                       int64_t ldd, int T, int S, int n_head, int dh, float theta, int inverse, hipStream_t st) {
   const int64_t total = (int64_t)T * n_head * (dh / 2);
   if (total <= 0) return hipSuccess;
   const float l2 = log2f(theta);
-  if (bf) hipLaunchKernelGGL(rope_kernel<bf16>, dim3(ew_blocks(total)), dim3(256), 0, st, (bf16*)x, (bf16*)x_t, T, S, ld, n_head, dh, l2, inverse);
-  else hipLaunchKernelGGL(rope_kernel<float>, dim3(ew_blocks(total)), dim3(256), 0, st, (float*)x, (float*)x_t, T, S, ld, n_head, dh, l2, inverse);
+  if (bf) hipLaunchKernelGGL(rope_kernel<bf16>, dim3(ew_blocks(total)), dim3(256), 0, st, src, src_t, lds, (bf16*)dst, (bf16*)dst_t, (bf16*)dst_lo, ldd, T, S, n_head, dh, l2, inverse);
+  else hipLaunchKernelGGL(rope_kernel<float>, dim3(ew_blocks(total)), dim3(256), 0, st, src, src_t, lds, (float*)dst, (float*)dst_t, (float*)dst_lo, ldd, T, S, n_head, dh, l2, inverse);
   return hipGetLastError();
 }
 

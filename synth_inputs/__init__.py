@@ -56,7 +56,7 @@ CONFIGS = {
                      reorth="full", basis_dtype="bf16", n_probes=1),
     "llama_7b": dict(model=_llama(32, 4096, 32, 11008, 32000, 512), batch=1,
                      seq=512, tokens="zipf", param_dtype="bf16", m=20,
-                     reorth="none", basis_dtype="f32", n_probes=1),
+                     reorth="none", basis_dtype="none", n_probes=1),
 }
 
 SEED_PARAMS = 42

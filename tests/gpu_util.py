@@ -47,3 +47,35 @@ def block_errors(model, got, want, lay):
         den = np.linalg.norm(w)
         rows.append((nm, float(np.linalg.norm(g - w) / den) if den > 0 else float(np.linalg.norm(g - w)), float(den)))
     return rows
+
+
+def device_params(model, param_dtype, seed=42):
+    """Random-init parameters generated directly on the GPU (std 0.02 matrices
+    and embeddings, gains 1, biases 0), for full-size invariant tests where no
+    host copy is needed.  Returns a flat tensor in the storage dtype."""
+    gen = torch.Generator(device="cuda").manual_seed(seed)
+    n = si.num_params(model)
+    dt = torch.bfloat16 if param_dtype == "bf16" else torch.float32
+    flat = torch.empty(n, dtype=dt, device="cuda")
+    off = 0
+    for _, shape, init in si.param_spec(model):
+        cnt = int(np.prod(shape))
+        if init[0] == "normal":
+            step = 1 << 28
+            for a in range(0, cnt, step):
+                b = min(cnt, a + step)
+                flat[off + a:off + b] = (torch.randn(b - a, generator=gen, device="cuda") * init[1]).to(dt)
+        else:
+            flat[off:off + cnt] = 1.0 if init[0] == "ones" else 0.0
+        off += cnt
+    return flat
+
+
+def device_randn(n, seed):
+    gen = torch.Generator(device="cuda").manual_seed(seed)
+    out = torch.empty(n, dtype=torch.float32, device="cuda")
+    step = 1 << 28
+    for a in range(0, n, step):
+        b = min(n, a + step)
+        out[a:b] = torch.randn(b - a, generator=gen, device="cuda")
+    return out
