@@ -180,9 +180,10 @@ class Context:
         self.max_m = max_m
 
     def close(self):
-        if getattr(self, "h", None) is not None and self.h:
-            self.L.hf_destroy(self.h)
-            self.h = C.c_void_p()
+        h = getattr(self, "h", None)
+        if h:
+            self.h = None
+            self.L.hf_destroy(h)
 
     __del__ = close
 

@@ -45,6 +45,7 @@ __global__ __launch_bounds__(256) void lz_fused_kernel(float* __restrict__ r, co
   double acc = 0.0;
   const int64_t n4 = n >> 2;
   const int64_t stride = (int64_t)gridDim.x * 256;
+#pragma unroll 2
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += stride) {
     if (MODE == 0) {
       const float4 a = ((const float4*)q)[i];
@@ -115,6 +116,7 @@ __global__ __launch_bounds__(256) void lz_scale_kernel(const float* src, float* 
   const float inv = (float)(1.0 / scal[idx]);
   const int64_t n4 = n >> 2;
   const int64_t stride = (int64_t)gridDim.x * 256;
+#pragma unroll 2
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += stride) {
     float4 v = ((const float4*)src)[i];
     v.x *= inv; v.y *= inv; v.z *= inv; v.w *= inv;
@@ -147,46 +149,123 @@ __device__ __forceinline__ float4 load4<bf16>(const bf16* p, int64_t i4) {
   return v;
 }
 
-// c_j = <Q_j, r> for j in [0, nq): block b owns the contiguous slice
-// [b*slice, (b+1)*slice) of the vectors and walks the basis in groups of JG
-// columns with fp64 accumulators; partials[j*nblk + b].
-constexpr int LZ_JG = 8;
+// Re-orthogonalisation kernels.  Both stream the basis once: the vectors are
+// cut into slices of LZ_SLICE elements; a block keeps its slice of r in
+// registers (16 floats per thread) and walks the stored vectors j = 0..nq-1,
+// issuing 16 B loads for the whole slice of Q_j before using them, so every
+// basis byte is read exactly once per kernel with many loads in flight and
+// contiguous 16 KB / 8 KB runs per vector (measured best among 2K..16K); the loads of vector
+// j+1 are issued before vector j is consumed.
+#ifndef HF_LZ_SLICE
+#define HF_LZ_SLICE 4096
+#endif
+constexpr int LZ_SLICE = HF_LZ_SLICE;     // elements per slice
+constexpr int LZ_RPT = LZ_SLICE / 256;    // r elements per thread
+
+typedef float lz_f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned lz_u32x4 __attribute__((ext_vector_type(4)));
+template <typename BT> struct QVec;
+template <> struct QVec<float> {  // 4 elements per 16 B load, 16 loads per slice
+  static constexpr int E = 4, U = LZ_RPT / 4;
+  typedef lz_f32x4 raw;
+  __device__ static __forceinline__ void unpack(const raw& q, float* o) { o[0] = q.x; o[1] = q.y; o[2] = q.z; o[3] = q.w; }
+};
+template <> struct QVec<bf16> {   // 8 elements per 16 B load, 8 loads per slice
+  static constexpr int E = 8, U = LZ_RPT / 8;
+  typedef lz_u32x4 raw;
+  __device__ static __forceinline__ void unpack(const raw& q, float* o) {
+    o[0] = __uint_as_float(q.x << 16); o[1] = __uint_as_float(q.x & 0xffff0000u);
+    o[2] = __uint_as_float(q.y << 16); o[3] = __uint_as_float(q.y & 0xffff0000u);
+    o[4] = __uint_as_float(q.z << 16); o[5] = __uint_as_float(q.z & 0xffff0000u);
+    o[6] = __uint_as_float(q.w << 16); o[7] = __uint_as_float(q.w & 0xffff0000u);
+  }
+};
+
+// Thread t owns elements base + (t + 256 u) E .. + E of the slice, u < U.
 template <typename BT>
-__global__ __launch_bounds__(256) void lz_qtr_kernel(const BT* __restrict__ Q, int64_t ldq, const float* __restrict__ r,
-                                                     int64_t n, int nq, int64_t slice4, const double* scal, int pass,
-                                                     double* __restrict__ partials) {
-  __shared__ double red[4];
-  if (pass == 1 && scal[S_REDO] == 0.0) return;
-  const int64_t n4 = n >> 2;
-  const int64_t b0 = (int64_t)blockIdx.x * slice4, b1 = min(n4, b0 + slice4);
-  for (int j0 = 0; j0 < nq; j0 += LZ_JG) {
-    double acc[LZ_JG];
+__device__ __forceinline__ void load_r_slice(const float* __restrict__ r, int64_t base, int64_t n, float (&rv)[LZ_RPT]) {
+  typedef QVec<BT> V;
 #pragma unroll
-    for (int u = 0; u < LZ_JG; ++u) acc[u] = 0.0;
-    for (int64_t i = b0 + threadIdx.x; i < b1; i += 256) {
-      const float4 rv = ((const float4*)r)[i];
+  for (int u = 0; u < V::U; ++u) {
+    const int64_t e0 = base + (int64_t)(threadIdx.x + 256 * u) * V::E;
 #pragma unroll
-      for (int u = 0; u < LZ_JG; ++u) {
-        if (j0 + u < nq) {
-          const float4 qv = load4<BT>(Q + (int64_t)(j0 + u) * ldq, i);
-          acc[u] += (double)(qv.x * rv.x + qv.y * rv.y) + (double)(qv.z * rv.z + qv.w * rv.w);
-        }
+    for (int h = 0; h < V::E / 4; ++h) {
+      float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (e0 + h * 4 + 4 <= n) x = *(const float4*)(r + e0 + h * 4);
+      else {
+        float t4[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int q = 0; q < 4; ++q) if (e0 + h * 4 + q < n) t4[q] = r[e0 + h * 4 + q];
+        x = make_float4(t4[0], t4[1], t4[2], t4[3]);
       }
-    }
-    if (blockIdx.x == gridDim.x - 1) {  // ragged tail elements
-      for (int64_t i = (n4 << 2) + threadIdx.x; i < n; i += 256)
-#pragma unroll
-        for (int u = 0; u < LZ_JG; ++u)
-          if (j0 + u < nq) acc[u] += (double)((float)Q[(int64_t)(j0 + u) * ldq + i] * r[i]);
-    }
-#pragma unroll
-    for (int u = 0; u < LZ_JG; ++u) {
-      if (j0 + u < nq) {
-        const double s = block_sum_d(acc[u], red);
-        if (threadIdx.x == 0) partials[(int64_t)(j0 + u) * gridDim.x + blockIdx.x] = s;
-      }
+      rv[u * V::E + h * 4 + 0] = x.x; rv[u * V::E + h * 4 + 1] = x.y;
+      rv[u * V::E + h * 4 + 2] = x.z; rv[u * V::E + h * 4 + 3] = x.w;
     }
   }
+}
+
+template <typename BT>
+__device__ __forceinline__ void load_q_slice(const BT* __restrict__ q, int64_t base, int64_t n, bool full,
+                                             typename QVec<BT>::raw (&qv)[QVec<BT>::U]) {
+  typedef QVec<BT> V;
+#pragma unroll
+  for (int u = 0; u < V::U; ++u) {
+    const int64_t e0 = base + (int64_t)(threadIdx.x + 256 * u) * V::E;
+    if (full || e0 + V::E <= n) {
+#ifdef HF_LZ_PLAIN_LOADS
+      qv[u] = *(const typename V::raw*)(q + e0);
+#else
+      qv[u] = __builtin_nontemporal_load((const typename V::raw*)(q + e0));
+#endif
+    } else {
+      BT t8[V::E];
+      for (int k = 0; k < V::E; ++k) t8[k] = (e0 + k < n) ? q[e0 + k] : (BT)0.f;
+      qv[u] = *(const typename V::raw*)t8;
+    }
+  }
+}
+
+// c_j = <Q_j, r>: partials[j * nblk + block] (fp64), summed by lz_qtr_finish_kernel.
+template <typename BT>
+__global__ __launch_bounds__(256) void lz_qtr_kernel(const BT* __restrict__ Q, int64_t ldq, const float* __restrict__ r,
+                                                     int64_t n, int nq, int64_t nslices, const double* scal, int pass,
+                                                     double* __restrict__ partials) {
+  typedef QVec<BT> V;
+  extern __shared__ double accs[];  // [4 waves][nq]
+  if (pass == 1 && scal[S_REDO] == 0.0) return;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int j = threadIdx.x; j < 4 * nq; j += 256) accs[j] = 0.0;
+  __syncthreads();
+  for (int64_t sl = blockIdx.x; sl < nslices; sl += gridDim.x) {
+    const int64_t base = sl * LZ_SLICE;
+    const bool full = base + LZ_SLICE <= n;
+    float rv[LZ_RPT];
+    load_r_slice<BT>(r, base, n, rv);
+    auto dot_j = [&](const typename V::raw (&qv)[V::U], int j) {
+      float s = 0.f;
+#pragma unroll
+      for (int u = 0; u < V::U; ++u) {
+        float qf[V::E];
+        V::unpack(qv[u], qf);
+#pragma unroll
+        for (int k = 0; k < V::E; ++k) s = fmaf(qf[k], rv[u * V::E + k], s);
+      }
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+      if (lane == 0) accs[wave * nq + j] += (double)s;
+    };
+    typename V::raw qa[V::U], qb[V::U];
+    load_q_slice<BT>(Q, base, n, full, qa);
+#pragma unroll 1
+    for (int j = 0; j < nq; j += 2) {
+      if (j + 1 < nq) load_q_slice<BT>(Q + (int64_t)(j + 1) * ldq, base, n, full, qb);
+      dot_j(qa, j);
+      if (j + 2 < nq) load_q_slice<BT>(Q + (int64_t)(j + 2) * ldq, base, n, full, qa);
+      if (j + 1 < nq) dot_j(qb, j + 1);
+    }
+  }
+  __syncthreads();
+  for (int j = threadIdx.x; j < nq; j += 256)
+    partials[(int64_t)j * gridDim.x + blockIdx.x] = accs[j] + accs[nq + j] + accs[2 * nq + j] + accs[3 * nq + j];
 }
 
 __global__ __launch_bounds__(256) void lz_qtr_finish_kernel(const double* partials, int nblk, const double* scal,
@@ -203,32 +282,56 @@ __global__ __launch_bounds__(256) void lz_qtr_finish_kernel(const double* partia
 // r -= sum_j c_j Q_j, partial ||r||^2.
 template <typename BT>
 __global__ __launch_bounds__(256) void lz_sub_qc_kernel(const BT* __restrict__ Q, int64_t ldq, float* __restrict__ r,
-                                                        int64_t n, int nq, const double* __restrict__ c,
+                                                        int64_t n, int nq, int64_t nslices, const double* __restrict__ c,
                                                         const double* scal, int pass, double* __restrict__ partials) {
+  typedef QVec<BT> V;
   extern __shared__ float cs[];
   __shared__ double red[4];
   if (pass == 1 && scal[S_REDO] == 0.0) return;
   for (int j = threadIdx.x; j < nq; j += 256) cs[j] = (float)c[j];
   __syncthreads();
   double acc = 0.0;
-  const int64_t n4 = n >> 2;
-  const int64_t stride = (int64_t)gridDim.x * 256;
-  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += stride) {
-    float4 rv = ((float4*)r)[i];
-    for (int j = 0; j < nq; ++j) {
-      const float4 qv = load4<BT>(Q + (int64_t)j * ldq, i);
+  for (int64_t sl = blockIdx.x; sl < nslices; sl += gridDim.x) {
+    const int64_t base = sl * LZ_SLICE;
+    const bool full = base + LZ_SLICE <= n;
+    float rv[LZ_RPT];
+    load_r_slice<BT>(r, base, n, rv);
+    auto sub_j = [&](const typename V::raw (&qv)[V::U], int j) {
       const float cj = cs[j];
-      rv.x = fmaf(-cj, qv.x, rv.x); rv.y = fmaf(-cj, qv.y, rv.y);
-      rv.z = fmaf(-cj, qv.z, rv.z); rv.w = fmaf(-cj, qv.w, rv.w);
+#pragma unroll
+      for (int u = 0; u < V::U; ++u) {
+        float qf[V::E];
+        V::unpack(qv[u], qf);
+#pragma unroll
+        for (int k = 0; k < V::E; ++k) rv[u * V::E + k] = fmaf(-cj, qf[k], rv[u * V::E + k]);
+      }
+    };
+    typename V::raw qa[V::U], qb[V::U];
+    load_q_slice<BT>(Q, base, n, full, qa);
+#pragma unroll 1
+    for (int j = 0; j < nq; j += 2) {
+      if (j + 1 < nq) load_q_slice<BT>(Q + (int64_t)(j + 1) * ldq, base, n, full, qb);
+      sub_j(qa, j);
+      if (j + 2 < nq) load_q_slice<BT>(Q + (int64_t)(j + 2) * ldq, base, n, full, qa);
+      if (j + 1 < nq) sub_j(qb, j + 1);
     }
-    ((float4*)r)[i] = rv;
-    acc += (double)rv.x * rv.x + (double)rv.y * rv.y + (double)rv.z * rv.z + (double)rv.w * rv.w;
-  }
-  for (int64_t i = (n4 << 2) + (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) {
-    float rv = r[i];
-    for (int j = 0; j < nq; ++j) rv = fmaf(-cs[j], (float)Q[(int64_t)j * ldq + i], rv);
-    r[i] = rv;
-    acc += (double)rv * rv;
+    float s = 0.f;
+#pragma unroll
+    for (int u = 0; u < V::U; ++u) {
+      const int64_t e0 = base + (int64_t)(threadIdx.x + 256 * u) * V::E;
+#pragma unroll
+      for (int h = 0; h < V::E / 4; ++h) {
+        const float* x = rv + u * V::E + h * 4;
+        if (e0 + h * 4 + 4 <= n) {
+          *(float4*)(r + e0 + h * 4) = make_float4(x[0], x[1], x[2], x[3]);
+          s += x[0] * x[0] + x[1] * x[1] + x[2] * x[2] + x[3] * x[3];
+        } else {
+          for (int q = 0; q < 4; ++q)
+            if (e0 + h * 4 + q < n) { r[e0 + h * 4 + q] = x[q]; s += x[q] * x[q]; }
+        }
+      }
+    }
+    acc += (double)s;
   }
   acc = block_sum_d(acc, red);
   if (threadIdx.x == 0) partials[blockIdx.x] = acc;
@@ -280,21 +383,19 @@ hipError_t lz_scale(const float* src, float* dst, void* basis, int basis_bf16, i
 hipError_t lz_reorth_pass(const void* Q, int basis_bf16, int64_t ldq, float* r, int64_t n, int nq, int pass,
                           double* scal, double* c, double* partials, hipStream_t st) {
   if (nq <= 0) return hipSuccess;
-  const int64_t n4 = n >> 2;
-  int nb = (int)std::max<int64_t>(1, std::min<int64_t>((n4 + 1023) / 1024, LZ_NBLK));
-  const int64_t slice4 = (std::max<int64_t>(n4, 1) + nb - 1) / nb;
-  nb = (int)std::max<int64_t>(1, (std::max<int64_t>(n4, 1) + slice4 - 1) / slice4);
-  const int nb2 = vec_blocks(n);
+  const int64_t nslices = (n + LZ_SLICE - 1) / LZ_SLICE;
+  const int nb = (int)std::max<int64_t>(1, std::min<int64_t>(nslices, LZ_NBLK));
+  const size_t sh1 = (size_t)4 * nq * sizeof(double), sh2 = (size_t)nq * sizeof(float);
   if (basis_bf16) {
-    hipLaunchKernelGGL(lz_qtr_kernel<bf16>, dim3(nb), dim3(256), 0, st, (const bf16*)Q, ldq, r, n, nq, slice4, scal, pass, partials);
+    hipLaunchKernelGGL(lz_qtr_kernel<bf16>, dim3(nb), dim3(256), sh1, st, (const bf16*)Q, ldq, r, n, nq, nslices, scal, pass, partials);
     hipLaunchKernelGGL(lz_qtr_finish_kernel, dim3(nq), dim3(256), 0, st, partials, nb, scal, pass, c);
-    hipLaunchKernelGGL(lz_sub_qc_kernel<bf16>, dim3(nb2), dim3(256), nq * sizeof(float), st, (const bf16*)Q, ldq, r, n, nq, c, scal, pass, partials);
+    hipLaunchKernelGGL(lz_sub_qc_kernel<bf16>, dim3(nb), dim3(256), sh2, st, (const bf16*)Q, ldq, r, n, nq, nslices, c, scal, pass, partials);
   } else {
-    hipLaunchKernelGGL(lz_qtr_kernel<float>, dim3(nb), dim3(256), 0, st, (const float*)Q, ldq, r, n, nq, slice4, scal, pass, partials);
+    hipLaunchKernelGGL(lz_qtr_kernel<float>, dim3(nb), dim3(256), sh1, st, (const float*)Q, ldq, r, n, nq, nslices, scal, pass, partials);
     hipLaunchKernelGGL(lz_qtr_finish_kernel, dim3(nq), dim3(256), 0, st, partials, nb, scal, pass, c);
-    hipLaunchKernelGGL(lz_sub_qc_kernel<float>, dim3(nb2), dim3(256), nq * sizeof(float), st, (const float*)Q, ldq, r, n, nq, c, scal, pass, partials);
+    hipLaunchKernelGGL(lz_sub_qc_kernel<float>, dim3(nb), dim3(256), sh2, st, (const float*)Q, ldq, r, n, nq, nslices, c, scal, pass, partials);
   }
-  hipLaunchKernelGGL(lz_finish_kernel, dim3(1), dim3(256), 0, st, partials, nb2, 3, pass, scal);
+  hipLaunchKernelGGL(lz_finish_kernel, dim3(1), dim3(256), 0, st, partials, nb, 3, pass, scal);
   return hipGetLastError();
 }
 
