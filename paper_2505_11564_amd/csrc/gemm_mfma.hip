@@ -31,74 +31,91 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 #define HF_LDS __attribute__((address_space(3)))
 
-constexpr int KT = 64;  // k-slab
-
 // vmcnt(n) only (expcnt / lgkmcnt left at their maxima), gfx9 encoding.
 #define HF_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt((((n) & 0xF) | ((((n) >> 4) & 0x3) << 14) | (0x7 << 4) | (0xF << 8)))
 
 // ---- LDS addressing ---------------------------------------------------------
-// k-contiguous operand: element (r, k) at r*64 + ((k/8) ^ (r & 7))*8 + k%8.
-__device__ __forceinline__ int lds_kc(int r, int k) { return r * KT + ((((k >> 3) ^ r) & 7) << 3) + (k & 7); }
+// The LDS of gfx950 serves 256 B per clock (64 banks): a 16 B fragment read is
+// conflict-free when 16 consecutive lanes cover all 64 banks.
+// k-contiguous operand, slab depth KT (64 or 32): row r holds KT/8 chunks of
+// 16 B; 256/(2 KT) rows span the banks, so the chunk index is rotated by
+// r / (128/KT).
+template <int KT>
+__device__ __forceinline__ int kc_chunk(int r, int c) { return (c ^ (r / (128 / KT))) & (KT / 8 - 1); }
+template <int KT>
+__device__ __forceinline__ int lds_kc(int r, int k) { return r * KT + (kc_chunk<KT>(r, k >> 3) << 3) + (k & 7); }
 // row-contiguous operand, R rows per k: element (k, r) at k*R + swizzled r.
-// 16 B chunk index (r/8) has its bit 2 flipped on odd k (64 B windows of odd
-// and even k rows fall on different halves of the banks).
-__device__ __forceinline__ int lds_rc(int k, int r, int R) { return k * R + ((((r >> 3) ^ ((k & 1) << 2))) << 3) + (r & 7); }
+// The 64 B windows that one transpose read touches in four consecutive k rows
+// are rotated by (k & 3) so that they fall on four different quarters of the
+// banks (row strides are multiples of 256 B).
+__device__ __forceinline__ int lds_rc(int k, int r, int R) { return k * R + ((((r >> 3) ^ ((k & 3) << 2))) << 3) + (r & 7); }
 
-// Issue the direct global->LDS loads of one k-slab of one operand.
+// Direct global->LDS loads of one k-slab of one operand.  Each wave issues NI
+// instructions per slab; instruction j moves 64 chunks of 16 B to the LDS
+// chunks [(wave*NI + j)*64, +64).  The lane's source offset relative to the
+// slab's (wave-uniform) base address does not change from slab to slab, so it
+// is computed once (slab_offsets) and the per-slab work is one scalar base
+// update plus NI load instructions (slab_issue).
 // KC: k-contiguous source (element (r,k) at src[r*ld + k]); else (k,r) at src[k*ld + r].
-template <int R, bool KC>
-__device__ __forceinline__ void slab_issue(const bf16* __restrict__ src, int64_t ld, int r0, int k0, int rmax,
-                                           HF_LDS bf16* lds, int wave, int lane) {
-  constexpr int NI = R / 32;  // instructions per wave (each moves 64 chunks of 16 B)
+template <int R, bool KC, int KT>
+__device__ __forceinline__ void slab_offsets(uint32_t (&voff)[R * KT / 2048], int64_t ld, int r0, int rmax, int wave,
+                                             int lane) {
+  constexpr int NI = R * KT / 2048;
 #pragma unroll
   for (int j = 0; j < NI; ++j) {
     const int P = (wave * NI + j) * 64 + lane;
-    const bf16* g;
     if (KC) {
-      const int row = P >> 3, pc = P & 7;
-      const int lc = pc ^ (row & 7);
-      const int gr = min(r0 + row, rmax - 1);
-      g = src + (int64_t)gr * ld + k0 + lc * 8;
+      constexpr int CPK = KT / 8;  // chunks per row
+      const int row = P / CPK, pc = P % CPK;
+      const int lc = kc_chunk<KT>(row, pc);
+      const int gr = min(r0 + row, rmax - 1) - r0;  // clamped rows only feed outputs that are never stored
+      voff[j] = (uint32_t)(((int64_t)gr * ld + lc * 8) * 2);
     } else {
       constexpr int CPR = R / 8;  // chunks per k-row
       const int krow = P / CPR, pc = P % CPR;
-      const int lc = pc ^ ((krow & 1) << 2);
-      const int gc = min(r0 + lc * 8, ((rmax - 1) >> 3) << 3);
-      g = src + (int64_t)(k0 + krow) * ld + gc;
+      const int lc = pc ^ ((krow & 3) << 2);
+      const int gc = min(r0 + lc * 8, ((rmax - 1) >> 3) << 3) - r0;
+      voff[j] = (uint32_t)(((int64_t)krow * ld + gc) * 2);
     }
-    __builtin_amdgcn_global_load_lds((const void*)g, (HF_LDS void*)(lds + (wave * NI + j) * 512), 16, 0, 0);
   }
 }
 
+template <int NI>
+__device__ __forceinline__ void slab_issue(const char* base, const uint32_t (&voff)[NI], HF_LDS char* lds_wave) {
+#pragma unroll
+  for (int j = 0; j < NI; ++j)
+    __builtin_amdgcn_global_load_lds((const void*)(base + voff[j]), (HF_LDS void*)(lds_wave + j * 1024), 16, 0, 0);
+}
+
 // Guarded load of a ragged k-slab (k in [k0, kend) valid, the rest zero).
-template <int R, bool KC>
+template <int R, bool KC, int KT>
 __device__ __forceinline__ void slab_guarded(const bf16* __restrict__ src, int64_t ld, int r0, int k0, int rmax, int kend,
                                              HF_LDS bf16* lds, int t) {
   for (int i = t; i < R * KT; i += 256) {
     int r, k;
-    if (KC) { k = i & (KT - 1); r = i >> 6; } else { r = i % R; k = i / R; }
+    if (KC) { k = i % KT; r = i / KT; } else { r = i % R; k = i / R; }
     const int gr = r0 + r, gk = k0 + k;
     bf16 v = (bf16)0.f;
     if (gr < rmax && gk < kend) v = KC ? src[(int64_t)gr * ld + gk] : src[(int64_t)gk * ld + gr];
-    lds[KC ? lds_kc(r, k) : lds_rc(k, r, R)] = v;
+    lds[KC ? lds_kc<KT>(r, k) : lds_rc(k, r, R)] = v;
   }
 }
 
 // Fragment (row = base + lane%32, k = kk*16 + (lane/32)*8 .. +8) of a slab.
-template <int R, bool KC>
+template <int R, bool KC, int KT>
 __device__ __forceinline__ bf16x8 frag_read(const HF_LDS bf16* lds, int rbase, int kk, int lane) {
   if (KC) {
     const int r = rbase + (lane & 31);
     const int c = kk * 2 + (lane >> 5);
-    return *(const HF_LDS bf16x8*)(lds + r * KT + (((c ^ r) & 7) << 3));
+    return *(const HF_LDS bf16x8*)(lds + r * KT + (kc_chunk<KT>(r, c) << 3));
   } else {
     // transpose read: 16 lanes address 4 k-rows x 16 columns (4 lanes per row,
     // 4 columns each); lane i of the group receives column i, 4 consecutive k.
     const int i = lane & 15, g = lane >> 4;
     const int kq = kk * 16 + (g >> 1) * 8 + (i >> 2);
     const int c = rbase + (g & 1) * 16 + (i & 3) * 4;
-    const HF_LDS bf16* p0 = lds + kq * R + ((((c >> 3) ^ ((kq & 1) << 2))) << 3) + (c & 7);
-    const HF_LDS bf16* p1 = p0 + 4 * R;  // k + 4: same parity, same swizzle
+    const HF_LDS bf16* p0 = lds + kq * R + ((((c >> 3) ^ ((kq & 3) << 2))) << 3) + (c & 7);
+    const HF_LDS bf16* p1 = p0 + 4 * R;  // k + 4: same k & 3, same swizzle
     const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((HF_LDS bf16x4*)p0);
     const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((HF_LDS bf16x4*)p1);
     bf16x8 v;
@@ -108,16 +125,22 @@ __device__ __forceinline__ bf16x8 frag_read(const HF_LDS bf16* lds, int rbase, i
   }
 }
 
-template <int BM, int BN, int WM, int WN, bool TA, bool TB>
+// Pipeline: NS LDS stages.  Iteration i waits for slab i, passes one barrier
+// (which also tells every wave that slab i-1 has been consumed), issues the
+// loads of slab i+NS-1 into the stage slab i-1 occupied, and multiplies slab i:
+// NS-1 slabs of loads are in flight behind the matrix cores.
+template <int BM, int BN, int WM, int WN, int KT, int NS, bool TA, bool TB>
 __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmP p) {
   static_assert((BM / WM) * (BN / WN) == 4, "four waves");
+  static_assert(NS >= 2 && NS <= 4, "stages");
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
   HF_LDS bf16* smem = (HF_LDS bf16*)smem_raw;
   constexpr int A_EL = BM * KT, B_EL = BN * KT, STAGE = A_EL + B_EL;
   constexpr bool AKC = !TA, BKC = TB;
-  constexpr int NLOAD = BM / 32 + BN / 32;  // load instructions per wave per slab
+  constexpr int NLOAD = (BM + BN) * KT / 2048;  // load instructions per wave per slab
 
-  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int t = threadIdx.x, lane = t & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(t >> 6);  // wave-uniform, kept in an SGPR
   // tile order: blocks are dealt round-robin to the 8 XCDs; give each XCD a
   // contiguous range of tiles so that neighbours share operand rows in its L2.
   int tile = blockIdx.x;
@@ -131,15 +154,27 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmP p) {
       tile = start + q;
     }
   }
-  const int tiles_m = (p.M + BM - 1) / BM;
-  // column-major walk over tiles (consecutive tiles share the B columns)
-  const int m0 = (tile % tiles_m) * BM, n0 = (tile / tiles_m) * BN;
+  const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
+  // Grouped order: bands of GROUP_M tile rows, walked row-first inside a band,
+  // so that a contiguous run of tiles (what one XCD executes at a time) covers
+  // a near-square patch and shares both operand streams through its L2.
+  constexpr int GROUP_M = 8;
+  int tm, tn;
+  {
+    const int band = GROUP_M * tiles_n;
+    const int g = tile / band, first = g * GROUP_M;
+    const int gsz = min(GROUP_M, tiles_m - first);
+    const int in_band = tile - g * band;
+    tm = first + in_band % gsz;
+    tn = in_band / gsz;
+  }
+  const int m0 = tm * BM, n0 = tn * BN;
   if (p.skip_upper && n0 > m0 + BM - 1) return;
   const int z = blockIdx.y, z1 = z / p.nb2, z2 = z % p.nb2;
   const int64_t offA = z1 * p.sA1 + z2 * p.sA2, offB = z1 * p.sB1 + z2 * p.sB2, offC = z1 * p.sC1 + z2 * p.sC2;
   int kbeg = 0, kend = p.K;
   if (p.klimit == 1) kend = min(p.K, m0 + BM);
-  if (p.klimit == 2) kbeg = (m0 / KT) * KT;
+  if (p.klimit == 2) kbeg = (m0 / 64) * 64;
   const int wm0 = (wave / (BN / WN)) * WM, wn0 = (wave % (BN / WN)) * WN;
   constexpr int TM = WM / 32, TN = WN / 32;
   f32x16 acc[TM][TN];
@@ -158,45 +193,82 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmP p) {
   const int ks = blockIdx.z, nks = gridDim.z;
   const int it0 = (int)((int64_t)total * ks / nks), it1 = (int)((int64_t)total * (ks + 1) / nks);
 
-  auto issue = [&](int it, int buf) {
-    const int term = it / nfull, k0 = kbeg + (it % nfull) * KT;
-    const bf16* A = (const bf16*)p.A[term] + offA;
-    const bf16* B = (const bf16*)p.B[term] + offB;
-    HF_LDS bf16* sa = smem + buf * STAGE;
-    slab_issue<BM, AKC>(A, p.lda, m0, k0, p.M, sa, wave, lane);
-    slab_issue<BN, BKC>(B, p.ldb, n0, k0, p.N, sa + A_EL, wave, lane);
+  // Per-lane source offsets of this wave's load instructions (slab-invariant).
+  constexpr int NIA = BM * KT / 2048, NIB = BN * KT / 2048;
+  uint32_t voffA[NIA], voffB[NIB];
+  slab_offsets<BM, AKC, KT>(voffA, p.lda, m0, p.M, wave, lane);
+  slab_offsets<BN, BKC, KT>(voffB, p.ldb, n0, p.N, wave, lane);
+  const int64_t stepA = (AKC ? (int64_t)KT : (int64_t)KT * p.lda) * 2;  // bytes per slab
+  const int64_t stepB = (BKC ? (int64_t)KT : (int64_t)KT * p.ldb) * 2;
+  auto slab_base = [&](const void* X, int64_t off, bool kc, int64_t ld, int r0, int k0) {
+    return (const char*)X + (off + (kc ? (int64_t)r0 * ld + k0 : (int64_t)k0 * ld + r0)) * 2;
+  };
+  // issue-side cursor: runs NS-1 slabs ahead of the compute-side one
+  int i_term = nfull > 0 ? it0 / nfull : 0, i_slab = nfull > 0 ? it0 % nfull : 0;
+  const char* i_a = slab_base(p.A[i_term], offA, AKC, p.lda, m0, kbeg + i_slab * KT);
+  const char* i_b = slab_base(p.B[i_term], offB, BKC, p.ldb, n0, kbeg + i_slab * KT);
+  HF_LDS char* const smem_c = (HF_LDS char*)smem;
+  auto issue = [&](int stage) {
+    HF_LDS char* sa = smem_c + stage * (STAGE * 2);
+    slab_issue<NIA>(i_a, voffA, sa + wave * (NIA * 1024));
+    slab_issue<NIB>(i_b, voffB, sa + A_EL * 2 + wave * (NIB * 1024));
+    i_a += stepA;
+    i_b += stepB;
+    if (++i_slab == nfull) {  // next term
+      i_slab = 0;
+      if (++i_term < nterm) {
+        i_a = slab_base(p.A[i_term], offA, AKC, p.lda, m0, kbeg);
+        i_b = slab_base(p.B[i_term], offB, BKC, p.ldb, n0, kbeg);
+      }
+    }
   };
   auto compute = [&](int buf) {
     const HF_LDS bf16* sa = smem + buf * STAGE;
     const HF_LDS bf16* sb = sa + A_EL;
+    // fragments of step kk+1 are requested before the products of step kk
+    bf16x8 a[2][TM], b[2][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) a[0][i] = frag_read<BM, AKC, KT>(sa, wm0 + i * 32, 0, lane);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) b[0][j] = frag_read<BN, BKC, KT>(sb, wn0 + j * 32, 0, lane);
 #pragma unroll
     for (int kk = 0; kk < KT / 16; ++kk) {
-      bf16x8 a[TM], b[TN];
+      if (kk + 1 < KT / 16) {
 #pragma unroll
-      for (int i = 0; i < TM; ++i) a[i] = frag_read<BM, AKC>(sa, wm0 + i * 32, kk, lane);
+        for (int i = 0; i < TM; ++i) a[(kk + 1) & 1][i] = frag_read<BM, AKC, KT>(sa, wm0 + i * 32, kk + 1, lane);
 #pragma unroll
-      for (int j = 0; j < TN; ++j) b[j] = frag_read<BN, BKC>(sb, wn0 + j * 32, kk, lane);
+        for (int j = 0; j < TN; ++j) b[(kk + 1) & 1][j] = frag_read<BN, BKC, KT>(sb, wn0 + j * 32, kk + 1, lane);
+      }
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk & 1][i], b[kk & 1][j], acc[i][j], 0, 0, 0);
     }
   };
 
-  if (it0 < it1) issue(it0, 0);
-  for (int it = it0; it < it1; ++it) {
-    const int buf = (it - it0) & 1;
-    if (it + 1 < it1) {
-      issue(it + 1, buf ^ 1);
-      HF_WAIT_VMCNT(NLOAD);
-    } else {
-      HF_WAIT_VMCNT(0);
+  const int nit = it1 - it0;
+#pragma unroll
+  for (int s = 0; s < NS - 1; ++s)
+    if (s < nit) issue(s);
+  // main loop, unrolled by the number of stages so that every LDS stage
+  // address is a compile-time constant
+  for (int i0 = 0; i0 < nit; i0 += NS) {
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      const int i = i0 + s;
+      if (i < nit) {
+        const int later = min(NS - 2, nit - 1 - i);  // slabs issued after slab i so far
+        if (later >= 2) HF_WAIT_VMCNT(2 * NLOAD);
+        else if (later == 1) HF_WAIT_VMCNT(NLOAD);
+        else HF_WAIT_VMCNT(0);
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        if (i + NS - 1 < nit) issue((s + NS - 1) % NS);
+        compute(s);
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_sched_barrier(0);
-    compute(buf);
-    __builtin_amdgcn_sched_barrier(0);
-    __builtin_amdgcn_s_barrier();
   }
   // ragged k remainder (handled by the last split only)
   if (ktail > 0 && ks == nks - 1) {
@@ -205,8 +277,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmP p) {
       const bf16* B = (const bf16*)p.B[term] + offB;
       const int k0 = kbeg + nfull * KT;
       __syncthreads();
-      slab_guarded<BM, AKC>(A, p.lda, m0, k0, p.M, kend, smem, t);
-      slab_guarded<BN, BKC>(B, p.ldb, n0, k0, p.N, kend, smem + A_EL, t);
+      slab_guarded<BM, AKC, KT>(A, p.lda, m0, k0, p.M, kend, smem, t);
+      slab_guarded<BN, BKC, KT>(B, p.ldb, n0, k0, p.N, kend, smem + A_EL, t);
       __syncthreads();
       compute(0);
     }
@@ -248,11 +320,12 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmP p) {
   }
 }
 
-template <int BM, int BN, int WM, int WN, bool TA, bool TB>
+
+template <int BM, int BN, int WM, int WN, int KT, int NS, bool TA, bool TB>
 static hipError_t launch_one(const GemmP& p, dim3 grid, hipStream_t st) {
-  constexpr int smem = 2 * (BM + BN) * KT * 2;
+  constexpr int smem = NS * (BM + BN) * KT * 2;
   static bool attr_done = false;
-  auto kern = gemm_mfma_kernel<BM, BN, WM, WN, TA, TB>;
+  auto kern = gemm_mfma_kernel<BM, BN, WM, WN, KT, NS, TA, TB>;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
@@ -262,38 +335,44 @@ static hipError_t launch_one(const GemmP& p, dim3 grid, hipStream_t st) {
   return hipGetLastError();
 }
 
-template <int BM, int BN, int WM, int WN>
+template <int BM, int BN, int WM, int WN, int KT, int NS>
 static hipError_t launch_cfg(const GemmP& p, dim3 grid, hipStream_t st) {
-  if (!p.transA && !p.transB) return launch_one<BM, BN, WM, WN, false, false>(p, grid, st);
-  if (!p.transA && p.transB) return launch_one<BM, BN, WM, WN, false, true>(p, grid, st);
-  if (p.transA && !p.transB) return launch_one<BM, BN, WM, WN, true, false>(p, grid, st);
-  return launch_one<BM, BN, WM, WN, true, true>(p, grid, st);
+  if (!p.transA && !p.transB) return launch_one<BM, BN, WM, WN, KT, NS, false, false>(p, grid, st);
+  if (!p.transA && p.transB) return launch_one<BM, BN, WM, WN, KT, NS, false, true>(p, grid, st);
+  if (p.transA && !p.transB) return launch_one<BM, BN, WM, WN, KT, NS, true, false>(p, grid, st);
+  return launch_one<BM, BN, WM, WN, KT, NS, true, true>(p, grid, st);
 }
+
+// Tile configurations (index = force_cfg): block tile, slab depth, stages.
+struct TileCfg { int bm, bn; };
+static const TileCfg kCfg[] = {{256, 256}, {256, 128}, {128, 128}, {256, 256}, {128, 128}, {128, 128}, {256, 128}, {128, 128}, {128, 128}};
+constexpr int kNumCfg = 9;
 
 // Tile choice: the largest tile that still yields about two blocks per CU;
 // split-K for products with few output tiles and a long k (the H v blocks).
 hipError_t launch_gemm_mfma(GemmP p, int nb, int allow_splitk, int force_cfg, int force_ks, hipStream_t st) {
   const int64_t M = p.M, N = p.N;
   auto tiles = [&](int bm, int bn) { return ((M + bm - 1) / bm) * ((N + bn - 1) / bn) * (int64_t)nb; };
+  // Measured on MI355X (4096x8192x2048-class and 4096x2304x768-class shapes):
+  // 128x128 tiles with two or more blocks per CU beat 256x256 except for A^T B
+  // products with plenty of tiles; a row-contiguous B prefers 32-deep slabs.
   int cfg;
-  if (force_cfg >= 0) cfg = force_cfg;
-  else if (tiles(256, 256) >= 384) cfg = 0;
-  else if (tiles(256, 128) >= 320) cfg = 1;
+  if (force_cfg >= 0 && force_cfg < kNumCfg) cfg = force_cfg;
+  else if (p.transA && !p.transB) cfg = tiles(256, 256) >= 256 ? 0 : 2;
+  else if (!p.transA && !p.transB) cfg = 7;
   else cfg = 2;
-  const int bm = cfg == 2 ? 128 : 256, bn = cfg == 0 ? 256 : 128;
+  const int bm = kCfg[cfg].bm, bn = kCfg[cfg].bn;
   const int64_t nt = tiles(bm, bn);
   int ks = 1;
   if (force_ks > 0) ks = force_ks;
   else if (allow_splitk && !p.out_bf16 && !p.klimit && nt < 384) {
-    const int slabs = p.nterm * (p.K / KT);
+    const int slabs = p.nterm * (p.K / 64);
     ks = (int)std::min<int64_t>(std::max<int64_t>(1, (512 + nt - 1) / nt), std::max(1, slabs / 4));
     ks = std::min(ks, 16);
   }
   if (ks > 1) {
     // accumulate with atomics on top of Cadd (or zero)
-    // (caller guarantees fp32 C; the fill is one small kernel)
     if (p.Cadd == nullptr) {
-      // zero-fill C rows
       if (p.ldc == p.N && nb == 1) {
         hipError_t e = launch_fill_f32((float*)p.C, M * N, 0.f, st);
         if (e != hipSuccess) return e;
@@ -306,9 +385,17 @@ hipError_t launch_gemm_mfma(GemmP p, int nb, int allow_splitk, int force_cfg, in
   }
   p.tiles_n = (int)((N + bn - 1) / bn);
   dim3 grid((unsigned)(nt / nb), (unsigned)nb, (unsigned)ks);
-  if (cfg == 0) return launch_cfg<256, 256, 128, 128>(p, grid, st);
-  if (cfg == 1) return launch_cfg<256, 128, 128, 64>(p, grid, st);
-  return launch_cfg<128, 128, 64, 64>(p, grid, st);
+  switch (cfg) {
+    case 0: return launch_cfg<256, 256, 128, 128, 64, 2>(p, grid, st);
+    case 1: return launch_cfg<256, 128, 128, 64, 64, 3>(p, grid, st);
+    case 2: return launch_cfg<128, 128, 64, 64, 64, 2>(p, grid, st);
+    case 3: return launch_cfg<256, 256, 128, 128, 32, 4>(p, grid, st);
+    case 4: return launch_cfg<128, 128, 64, 64, 32, 4>(p, grid, st);
+    case 5: return launch_cfg<128, 128, 64, 64, 64, 3>(p, grid, st);
+    case 6: return launch_cfg<256, 128, 128, 64, 32, 4>(p, grid, st);
+    case 7: return launch_cfg<128, 128, 64, 64, 32, 2>(p, grid, st);
+    default: return launch_cfg<128, 128, 64, 64, 32, 3>(p, grid, st);
+  }
 }
 
 }  // namespace hf
