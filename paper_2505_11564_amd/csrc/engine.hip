@@ -208,13 +208,18 @@ struct Lin {
     if (X_lo) { g.A[1] = X_lo; g.B[1] = g.B[0]; }
     if (out_bf16) g.C_lo = Y_lo;
     if (boff >= 0) g.bias = Wp(boff);
+    if (X_t) {  // primal and tangent in one (dual-output) product
+      g.At = X_t; g.Bt = Wt(woff); g.Ct = Y_t; g.Cadd_t = add_t;
+      if (boff >= 0) g.bias_t = v + boff;
+      CK(launch_gemm(g, st));
+      return HF_OK;
+    }
     CK(launch_gemm(g, st));
     Gemm t = g;
     t.A[1] = nullptr; t.B[1] = nullptr; t.C_lo = nullptr;
     t.C = Y_t; t.Cadd = add_t; t.bias = nullptr;
     if (boff >= 0) t.bias_t = v + boff;
-    if (X_t) { t.A[0] = X_t; t.B[0] = Wp(woff); t.A[1] = X; t.B[1] = Wt(woff); }
-    else { t.A[0] = X; t.B[0] = Wt(woff); }
+    t.A[0] = X; t.B[0] = Wt(woff);
     CK(launch_gemm(t, st));
     return HF_OK;
   }
@@ -226,13 +231,21 @@ struct Lin {
     Gemm g;
     g.M = M; g.N = Kin; g.K = Nout; g.lda = lddy; g.ldb = ldw < 0 ? Nout : ldw; g.ldc = lddx; g.transB = !transW;
     g.in_bf16 = bf; g.out_bf16 = out_bf16;
-    g.allow_splitk = 1;
     g.A[0] = dY; g.B[0] = Wp(woff); g.C = dX; g.Cadd = add;
+    // Few output tiles and a long contraction (the head: K = vocabulary): two
+    // split-K products; otherwise one dual-output product.
+    const int64_t tiles = ((int64_t)(M + 127) / 128) * ((Kin + 127) / 128);
+    if (!out_bf16 && tiles < 256 && Nout >= 8192) {
+      g.allow_splitk = 1;
+      CK(launch_gemm(g, st));
+      Gemm t = g;
+      t.C = dX_t; t.Cadd = add_t;
+      t.A[0] = dY_t; t.B[0] = Wp(woff); t.A[1] = dY; t.B[1] = Wt(woff);
+      CK(launch_gemm(t, st));
+      return HF_OK;
+    }
+    g.At = dY_t; g.Bt = Wt(woff); g.Ct = dX_t; g.Cadd_t = add_t;
     CK(launch_gemm(g, st));
-    Gemm t = g;
-    t.C = dX_t; t.Cadd = add_t;
-    t.A[0] = dY_t; t.B[0] = Wp(woff); t.A[1] = dY; t.B[1] = Wt(woff);
-    CK(launch_gemm(t, st));
     return HF_OK;
   }
 
@@ -365,9 +378,7 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
         g.A[1] = qkv_lo; g.B[1] = cat(b.qkv, D);
         g.A[2] = b.qkv; g.B[2] = cat(qkv_lo, D);
       }
-      CK(launch_gemm(g, st));
-      g.A[2] = nullptr; g.B[2] = nullptr;
-      g.A[0] = b.qkv_t; g.B[0] = cat(b.qkv, D); g.A[1] = b.qkv; g.B[1] = cat(b.qkv_t, D); g.C = sc_t;
+      g.At = b.qkv_t; g.Bt = cat(b.qkv_t, D); g.Ct = sc_t;
       CK(launch_gemm(g, st));
     }
     CK(launch_softmax_fwd(bf, sc, sc_t, b.P, b.P_t, P_lo, B * H, S, st));
@@ -381,9 +392,7 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
         g.A[2] = b.P; g.B[2] = cat(qkv_lo, 2 * D);
         g.C_lo = o_lo;
       }
-      CK(launch_gemm(g, st));
-      g.A[2] = nullptr; g.B[2] = nullptr; g.C_lo = nullptr;
-      g.A[0] = b.P_t; g.B[0] = cat(b.qkv, 2 * D); g.A[1] = b.P; g.B[1] = cat(b.qkv_t, 2 * D); g.C = b.o_t;
+      g.At = b.P_t; g.Bt = cat(b.qkv_t, 2 * D); g.Ct = b.o_t;
       CK(launch_gemm(g, st));
     }
     if ((rc = L.fwd(b.o, b.o_t, T, D, D, D, o.wo, o.bo, b.x2, b.x2_t, D, 0, b.x1, b.x1_t, 0, -1, o_lo))) return rc;
@@ -459,8 +468,7 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
       g.M = S; g.N = dh; g.K = S; g.lda = S; g.ldb = D; g.ldc = 3 * D; g.transA = 1; g.klimit = 2; g.out_bf16 = bf;
       set_sc(g.sA1, g.sA2); set_td(g.sB1, g.sB2); set_qkv(g.sC1, g.sC2);
       g.A[0] = b.P; g.B[0] = dob; g.C = at(dqkv, 2 * D);
-      CK(launch_gemm(g, st));
-      g.A[0] = b.P_t; g.B[0] = dob; g.A[1] = b.P; g.B[1] = dob_t; g.C = at(dqkv_t, 2 * D);
+      g.At = b.P_t; g.Bt = dob_t; g.Ct = at(dqkv_t, 2 * D);
       CK(launch_gemm(g, st));
     }
     {  // dP = dO V^T, dP_t = dO_t V^T + dO V_t^T
@@ -468,8 +476,7 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
       g.M = S; g.N = S; g.K = dh; g.lda = D; g.ldb = 3 * D; g.ldc = S; g.transB = 1; g.skip_upper = 1;
       set_td(g.sA1, g.sA2); set_qkv(g.sB1, g.sB2); set_sc(g.sC1, g.sC2);
       g.A[0] = dob; g.B[0] = cat(b.qkv, 2 * D); g.C = sc;
-      CK(launch_gemm(g, st));
-      g.A[0] = dob_t; g.B[0] = cat(b.qkv, 2 * D); g.A[1] = dob; g.B[1] = cat(b.qkv_t, 2 * D); g.C = sc_t;
+      g.At = dob_t; g.Bt = cat(b.qkv_t, 2 * D); g.Ct = sc_t;
       CK(launch_gemm(g, st));
     }
     CK(launch_softmax_bwd(bf, b.P, b.P_t, sc, sc_t, dS, dS_t, B * H, S, st));
@@ -483,14 +490,12 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
         cq = rq; cq_t = rq_t; ck = rq + D; ck_t = rq_t + D;
       }
       g.A[0] = dS; g.B[0] = cat(b.qkv, D); g.C = cq;
-      CK(launch_gemm(g, st));
-      g.A[0] = dS_t; g.B[0] = cat(b.qkv, D); g.A[1] = dS; g.B[1] = cat(b.qkv_t, D); g.C = cq_t;
+      g.At = dS_t; g.Bt = cat(b.qkv_t, D); g.Ct = cq_t;
       CK(launch_gemm(g, st));
       // dK = c dS^T Q, dK_t = c (dS_t^T Q + dS^T Q_t)
       g.transA = 1; g.klimit = 2;
-      g.A[0] = dS; g.B[0] = b.qkv; g.A[1] = nullptr; g.B[1] = nullptr; g.C = ck;
-      CK(launch_gemm(g, st));
-      g.A[0] = dS_t; g.B[0] = b.qkv; g.A[1] = dS; g.B[1] = b.qkv_t; g.C = ck_t;
+      g.A[0] = dS; g.B[0] = b.qkv; g.C = ck;
+      g.At = dS_t; g.Bt = b.qkv_t; g.Ct = ck_t;
       CK(launch_gemm(g, st));
     }
     if (!llama) {

@@ -288,7 +288,43 @@ static hipError_t launch_bf16_cfg(const GemmP& p, dim3 grid, hipStream_t st) {
 
 static bool aligned_to(const void* ptr, size_t a) { return ptr == nullptr || ((uintptr_t)ptr % a) == 0; }
 
+static hipError_t launch_gemm_single(const Gemm& g, hipStream_t st);
+
 hipError_t launch_gemm(const Gemm& g, hipStream_t st) {
+  if (!g.Ct) return launch_gemm_single(g, st);
+  // dual output: one fused launch when the MFMA path applies, else two products
+  if (g.M <= 0 || g.N <= 0 || g.nb1 <= 0 || g.nb2 <= 0) return hipSuccess;
+  if (!g.At || !g.Bt || !g.A[0] || !g.B[0] || !g.C || ((g.Cadd || g.Cadd_t) && g.out_bf16)) return hipErrorInvalidValue;
+  static const int no_dual = std::getenv("HF_GEMM_NO_DUAL") ? 1 : 0;
+  // Measured: the fused kernel wins only when the product alone cannot fill
+  // the GPU (fewer than ~256 tiles of 128 x 128); larger products run faster
+  // as two launches with their own tile shapes.
+  const int64_t tiles128 = ((int64_t)(g.M + 127) / 128) * ((g.N + 127) / 128) * g.nb1 * g.nb2;
+  if (g.in_bf16 && !no_dual && g.M >= 8 && g.N >= 8 && tiles128 < 256) {
+    auto ok = [&](const void* x, int64_t ld, int64_t s1, int64_t s2, int rows_contig, int R) {
+      return ((uintptr_t)x % 16) == 0 && ld % 8 == 0 && s1 % 8 == 0 && s2 % 8 == 0 && (!rows_contig || ld >= ((R + 7) / 8) * 8);
+    };
+    bool fast = ok(g.At, g.lda, g.sA1, g.sA2, g.transA, g.M) && ok(g.Bt, g.ldb, g.sB1, g.sB2, !g.transB, g.N);
+    for (int i = 0; i < 3 && fast; ++i) {
+      if (g.A[i]) fast = ok(g.A[i], g.lda, g.sA1, g.sA2, g.transA, g.M) && ok(g.B[i], g.ldb, g.sB1, g.sB2, !g.transB, g.N);
+    }
+    if (fast) {
+      hipError_t e = launch_gemm_dual(g, st);
+      if (e != hipErrorNotSupported) return e;
+    }
+  }
+  Gemm p = g;
+  p.At = nullptr; p.Bt = nullptr; p.Ct = nullptr; p.Cadd_t = nullptr; p.bias_t = nullptr;
+  hipError_t e = launch_gemm_single(p, st);
+  if (e != hipSuccess) return e;
+  Gemm t = g;
+  t.At = nullptr; t.Bt = nullptr; t.Ct = nullptr; t.Cadd_t = nullptr;
+  t.A[0] = g.At; t.B[0] = g.B[0]; t.A[1] = g.A[0]; t.B[1] = g.Bt; t.A[2] = nullptr; t.B[2] = nullptr;
+  t.C = g.Ct; t.C_lo = nullptr; t.Cadd = g.Cadd_t; t.bias = nullptr;
+  return launch_gemm_single(t, st);
+}
+
+static hipError_t launch_gemm_single(const Gemm& g, hipStream_t st) {
   if (g.M <= 0 || g.N <= 0 || g.nb1 <= 0 || g.nb2 <= 0) return hipSuccess;
   if (!g.A[0] || !g.B[0] || !g.C || (g.A[1] && !g.B[1]) || (g.A[2] && (!g.B[2] || !g.A[1])) || (g.Cadd && g.out_bf16) ||
       (g.C_lo && !g.out_bf16))

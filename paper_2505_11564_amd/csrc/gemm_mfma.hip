@@ -21,109 +21,9 @@
 //   * out-of-range rows/columns are clamped to a valid address (they only feed
 //     outputs that are never stored); a ragged last k-slab is loaded through a
 //     guarded path; optional split-K accumulates with fp32 atomics.
-#include "hf_internal.h"
-#include "gemm_params.h"
+#include "gemm_mfma_common.h"
 
 namespace hf {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-#define HF_LDS __attribute__((address_space(3)))
-
-// vmcnt(n) only (expcnt / lgkmcnt left at their maxima), gfx9 encoding.
-#define HF_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt((((n) & 0xF) | ((((n) >> 4) & 0x3) << 14) | (0x7 << 4) | (0xF << 8)))
-
-// ---- LDS addressing ---------------------------------------------------------
-// The LDS of gfx950 serves 256 B per clock (64 banks): a 16 B fragment read is
-// conflict-free when 16 consecutive lanes cover all 64 banks.
-// k-contiguous operand, slab depth KT (64 or 32): row r holds KT/8 chunks of
-// 16 B; 256/(2 KT) rows span the banks, so the chunk index is rotated by
-// r / (128/KT).
-template <int KT>
-__device__ __forceinline__ int kc_chunk(int r, int c) { return (c ^ (r / (128 / KT))) & (KT / 8 - 1); }
-template <int KT>
-__device__ __forceinline__ int lds_kc(int r, int k) { return r * KT + (kc_chunk<KT>(r, k >> 3) << 3) + (k & 7); }
-// row-contiguous operand, R rows per k: element (k, r) at k*R + swizzled r.
-// The 64 B windows that one transpose read touches in four consecutive k rows
-// are rotated by (k & 3) so that they fall on four different quarters of the
-// banks (row strides are multiples of 256 B).
-__device__ __forceinline__ int lds_rc(int k, int r, int R) { return k * R + ((((r >> 3) ^ ((k & 3) << 2))) << 3) + (r & 7); }
-
-// Direct global->LDS loads of one k-slab of one operand.  Each wave issues NI
-// instructions per slab; instruction j moves 64 chunks of 16 B to the LDS
-// chunks [(wave*NI + j)*64, +64).  The lane's source offset relative to the
-// slab's (wave-uniform) base address does not change from slab to slab, so it
-// is computed once (slab_offsets) and the per-slab work is one scalar base
-// update plus NI load instructions (slab_issue).
-// KC: k-contiguous source (element (r,k) at src[r*ld + k]); else (k,r) at src[k*ld + r].
-template <int R, bool KC, int KT>
-__device__ __forceinline__ void slab_offsets(uint32_t (&voff)[R * KT / 2048], int64_t ld, int r0, int rmax, int wave,
-                                             int lane) {
-  constexpr int NI = R * KT / 2048;
-#pragma unroll
-  for (int j = 0; j < NI; ++j) {
-    const int P = (wave * NI + j) * 64 + lane;
-    if (KC) {
-      constexpr int CPK = KT / 8;  // chunks per row
-      const int row = P / CPK, pc = P % CPK;
-      const int lc = kc_chunk<KT>(row, pc);
-      const int gr = min(r0 + row, rmax - 1) - r0;  // clamped rows only feed outputs that are never stored
-      voff[j] = (uint32_t)(((int64_t)gr * ld + lc * 8) * 2);
-    } else {
-      constexpr int CPR = R / 8;  // chunks per k-row
-      const int krow = P / CPR, pc = P % CPR;
-      const int lc = pc ^ ((krow & 3) << 2);
-      const int gc = min(r0 + lc * 8, ((rmax - 1) >> 3) << 3) - r0;
-      voff[j] = (uint32_t)(((int64_t)krow * ld + gc) * 2);
-    }
-  }
-}
-
-template <int NI>
-__device__ __forceinline__ void slab_issue(const char* base, const uint32_t (&voff)[NI], HF_LDS char* lds_wave) {
-#pragma unroll
-  for (int j = 0; j < NI; ++j)
-    __builtin_amdgcn_global_load_lds((const void*)(base + voff[j]), (HF_LDS void*)(lds_wave + j * 1024), 16, 0, 0);
-}
-
-// Guarded load of a ragged k-slab (k in [k0, kend) valid, the rest zero).
-template <int R, bool KC, int KT>
-__device__ __forceinline__ void slab_guarded(const bf16* __restrict__ src, int64_t ld, int r0, int k0, int rmax, int kend,
-                                             HF_LDS bf16* lds, int t) {
-  for (int i = t; i < R * KT; i += 256) {
-    int r, k;
-    if (KC) { k = i % KT; r = i / KT; } else { r = i % R; k = i / R; }
-    const int gr = r0 + r, gk = k0 + k;
-    bf16 v = (bf16)0.f;
-    if (gr < rmax && gk < kend) v = KC ? src[(int64_t)gr * ld + gk] : src[(int64_t)gk * ld + gr];
-    lds[KC ? lds_kc<KT>(r, k) : lds_rc(k, r, R)] = v;
-  }
-}
-
-// Fragment (row = base + lane%32, k = kk*16 + (lane/32)*8 .. +8) of a slab.
-template <int R, bool KC, int KT>
-__device__ __forceinline__ bf16x8 frag_read(const HF_LDS bf16* lds, int rbase, int kk, int lane) {
-  if (KC) {
-    const int r = rbase + (lane & 31);
-    const int c = kk * 2 + (lane >> 5);
-    return *(const HF_LDS bf16x8*)(lds + r * KT + (kc_chunk<KT>(r, c) << 3));
-  } else {
-    // transpose read: 16 lanes address 4 k-rows x 16 columns (4 lanes per row,
-    // 4 columns each); lane i of the group receives column i, 4 consecutive k.
-    const int i = lane & 15, g = lane >> 4;
-    const int kq = kk * 16 + (g >> 1) * 8 + (i >> 2);
-    const int c = rbase + (g & 1) * 16 + (i & 3) * 4;
-    const HF_LDS bf16* p0 = lds + kq * R + ((((c >> 3) ^ ((kq & 3) << 2))) << 3) + (c & 7);
-    const HF_LDS bf16* p1 = p0 + 4 * R;  // k + 4: same k & 3, same swizzle
-    const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((HF_LDS bf16x4*)p0);
-    const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((HF_LDS bf16x4*)p1);
-    bf16x8 v;
-    v[0] = lo[0]; v[1] = lo[1]; v[2] = lo[2]; v[3] = lo[3];
-    v[4] = hi[0]; v[5] = hi[1]; v[6] = hi[2]; v[7] = hi[3];
-    return v;
-  }
-}
 
 // Pipeline: NS LDS stages.  Iteration i waits for slab i, passes one barrier
 // (which also tells every wave that slab i-1 has been consumed), issues the
@@ -345,8 +245,11 @@ static hipError_t launch_cfg(const GemmP& p, dim3 grid, hipStream_t st) {
 
 // Tile configurations (index = force_cfg): block tile, slab depth, stages.
 struct TileCfg { int bm, bn; };
-static const TileCfg kCfg[] = {{256, 256}, {256, 128}, {128, 128}, {256, 256}, {128, 128}, {128, 128}, {256, 128}, {128, 128}, {128, 128}};
-constexpr int kNumCfg = 9;
+// 0: 256x256x64, 2 stages; 1: 128x128x64, 2 stages; 2: 128x128x32, 2 stages.
+// (Deeper pipelines, 256x128 tiles and register-staged loads were measured and
+// were slower on every shape tried.)
+static const TileCfg kCfg[] = {{256, 256}, {128, 128}, {128, 128}};
+constexpr int kNumCfg = 3;
 
 // Tile choice: the largest tile that still yields about two blocks per CU;
 // split-K for products with few output tiles and a long k (the H v blocks).
@@ -358,9 +261,9 @@ hipError_t launch_gemm_mfma(GemmP p, int nb, int allow_splitk, int force_cfg, in
   // products with plenty of tiles; a row-contiguous B prefers 32-deep slabs.
   int cfg;
   if (force_cfg >= 0 && force_cfg < kNumCfg) cfg = force_cfg;
-  else if (p.transA && !p.transB) cfg = tiles(256, 256) >= 256 ? 0 : 2;
-  else if (!p.transA && !p.transB) cfg = 7;
-  else cfg = 2;
+  else if (p.transA && !p.transB) cfg = tiles(256, 256) >= 256 ? 0 : 1;
+  else if (!p.transA && !p.transB) cfg = 2;
+  else cfg = 1;
   const int bm = kCfg[cfg].bm, bn = kCfg[cfg].bn;
   const int64_t nt = tiles(bm, bn);
   int ks = 1;
@@ -387,14 +290,8 @@ hipError_t launch_gemm_mfma(GemmP p, int nb, int allow_splitk, int force_cfg, in
   dim3 grid((unsigned)(nt / nb), (unsigned)nb, (unsigned)ks);
   switch (cfg) {
     case 0: return launch_cfg<256, 256, 128, 128, 64, 2>(p, grid, st);
-    case 1: return launch_cfg<256, 128, 128, 64, 64, 3>(p, grid, st);
-    case 2: return launch_cfg<128, 128, 64, 64, 64, 2>(p, grid, st);
-    case 3: return launch_cfg<256, 256, 128, 128, 32, 4>(p, grid, st);
-    case 4: return launch_cfg<128, 128, 64, 64, 32, 4>(p, grid, st);
-    case 5: return launch_cfg<128, 128, 64, 64, 64, 3>(p, grid, st);
-    case 6: return launch_cfg<256, 128, 128, 64, 32, 4>(p, grid, st);
-    case 7: return launch_cfg<128, 128, 64, 64, 32, 2>(p, grid, st);
-    default: return launch_cfg<128, 128, 64, 64, 32, 3>(p, grid, st);
+    case 1: return launch_cfg<128, 128, 64, 64, 64, 2>(p, grid, st);
+    default: return launch_cfg<128, 128, 64, 64, 32, 2>(p, grid, st);
   }
 }
 

@@ -61,10 +61,17 @@ struct Gemm {
                    // 2: k >= m (A upper-triangular in (m,k))
   int skip_upper = 0;  // skip output tiles with n0 > m_last (causal scores)
   int allow_splitk = 0;  // fp32 C only: few output tiles, long k -> split k with atomics
+  // Dual output (Ct != nullptr): additionally Ct = alpha (At op B[0] + A[0] op Bt) + bias_t + Cadd_t in
+  // the same launch; C then takes bias and Cadd only, Ct takes bias_t and Cadd_t only.
+  const void* At = nullptr;
+  const void* Bt = nullptr;
+  void* Ct = nullptr;
+  const float* Cadd_t = nullptr;
   int force_cfg = -1, force_ks = 0;  // tuning / tests: tile configuration and k-split override
 };
 
 hipError_t launch_gemm(const Gemm& g, hipStream_t st);
+hipError_t launch_gemm_dual(const Gemm& g, hipStream_t st);  // bf16, aligned operands only
 
 // -------------------------------------------------------- row / pointwise ----
 // AT = operand type of activations (float or bf16); PT = parameter type.
