@@ -184,46 +184,101 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmP p) {
     }
   }
 
-  // epilogue: lane holds column (lane & 31), rows 8*(r/4) + 4*(lane/32) + r%4
+  // epilogue.  An accumulator tile holds, per lane, column (lane & 31) and rows
+  // 8*(r/4) + 4*(lane/32) + r%4.  Split-K adds with atomics straight from that
+  // layout; otherwise each wave stages 32 x WN results in LDS and writes them
+  // out row-wise, 8 consecutive columns (16 B of bf16, 32 B of fp32) per lane.
   const bool first = (ks == 0);
+  float bsum[TN];
 #pragma unroll
   for (int j = 0; j < TN; ++j) {
     const int gn = n0 + wn0 + j * 32 + (lane & 31);
-    if (gn >= p.N) continue;
-    float bsum = 0.f;
-    if (first) {
-      if (p.bias) bsum += p.bias_bf16 ? (float)((const bf16*)p.bias)[gn] : ((const float*)p.bias)[gn];
-      if (p.bias_t) bsum += p.bias_t[gn];
+    bsum[j] = 0.f;
+    if (first && gn < p.N) {
+      if (p.bias) bsum[j] += p.bias_bf16 ? (float)((const bf16*)p.bias)[gn] : ((const float*)p.bias)[gn];
+      if (p.bias_t) bsum[j] += p.bias_t[gn];
     }
+  }
+  if (nks > 1) {
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
+    for (int j = 0; j < TN; ++j) {
+      const int gn = n0 + wn0 + j * 32 + (lane & 31);
+      if (gn >= p.N) continue;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int gm = m0 + wm0 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-        if (gm >= p.M) continue;
-        float v = p.alpha * acc[i][j][r] + bsum;
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int gm = m0 + wm0 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+          if (gm >= p.M) continue;
+          // C was zero-filled (or holds Cadd) by the launcher
+          atomicAdd((float*)p.C + offC + (int64_t)gm * p.ldc + gn, p.alpha * acc[i][j][r] + bsum[j]);
+        }
+    }
+    return;
+  }
+  constexpr int LDW = WN + 4;               // staging row stride (floats)
+  constexpr int CPRW = WN / 8;              // 8-column chunks per staged row
+  constexpr int RPP = 64 / CPRW;            // rows written per pass of the wave
+  HF_LDS float* stg = (HF_LDS float*)smem + wave * (32 * LDW);
+  const bool vec = p.vecA != 0;             // C (and Cadd / C_lo) rows are 16-byte aligned
+  __syncthreads();                          // every wave is done reading operand tiles
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        stg[((r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * LDW + j * 32 + (lane & 31)] = p.alpha * acc[i][j][r] + bsum[j];
+    __syncthreads();
+#pragma unroll
+    for (int ps = 0; ps < 32 / RPP; ++ps) {
+      const int row = ps * RPP + lane / CPRW, ch = lane % CPRW;
+      const int gm = m0 + wm0 + i * 32 + row, gn = n0 + wn0 + ch * 8;
+      if (gm < p.M && gn < p.N) {
+        typedef float f32x4_t __attribute__((ext_vector_type(4)));
+        const f32x4_t x0 = *(const HF_LDS f32x4_t*)(stg + row * LDW + ch * 8);
+        const f32x4_t x1 = *(const HF_LDS f32x4_t*)(stg + row * LDW + ch * 8 + 4);
+        float v[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
         const int64_t ci = offC + (int64_t)gm * p.ldc + gn;
-        if (nks > 1) {
-          atomicAdd((float*)p.C + ci, v);  // C was zero-filled (or holds Cadd) by the launcher
-        } else {
-          if (p.Cadd) v += p.Cadd[ci];
+        if (vec && gn + 8 <= p.N) {
+          if (p.Cadd) {
+            const float4 c0 = *(const float4*)(p.Cadd + ci), c1 = *(const float4*)(p.Cadd + ci + 4);
+            v[0] += c0.x; v[1] += c0.y; v[2] += c0.z; v[3] += c0.w; v[4] += c1.x; v[5] += c1.y; v[6] += c1.z; v[7] += c1.w;
+          }
           if (p.out_bf16) {
-            const bf16 hi = (bf16)v;
-            ((bf16*)p.C)[ci] = hi;
-            if (p.C_lo) ((bf16*)p.C_lo)[ci] = (bf16)(v - (float)hi);
+            bf16 hi[8], lo[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) { hi[q] = (bf16)v[q]; lo[q] = (bf16)(v[q] - (float)hi[q]); }
+            *(uint4*)((bf16*)p.C + ci) = *(const uint4*)hi;
+            if (p.C_lo) *(uint4*)((bf16*)p.C_lo + ci) = *(const uint4*)lo;
           } else {
-            ((float*)p.C)[ci] = v;
+            *(float4*)((float*)p.C + ci) = make_float4(v[0], v[1], v[2], v[3]);
+            *(float4*)((float*)p.C + ci + 4) = make_float4(v[4], v[5], v[6], v[7]);
+          }
+        } else {
+          for (int q = 0; q < 8; ++q) {
+            if (gn + q >= p.N) break;
+            float x = v[q];
+            if (p.Cadd) x += p.Cadd[ci + q];
+            if (p.out_bf16) {
+              const bf16 h = (bf16)x;
+              ((bf16*)p.C)[ci + q] = h;
+              if (p.C_lo) ((bf16*)p.C_lo)[ci + q] = (bf16)(x - (float)h);
+            } else {
+              ((float*)p.C)[ci + q] = x;
+            }
           }
         }
       }
     }
+    __syncthreads();
   }
 }
 
-
 template <int BM, int BN, int WM, int WN, int KT, int NS, bool TA, bool TB>
 static hipError_t launch_one(const GemmP& p, dim3 grid, hipStream_t st) {
-  constexpr int smem = NS * (BM + BN) * KT * 2;
+  constexpr int smem_pipe = NS * (BM + BN) * KT * 2, smem_epi = 4 * 32 * (WN + 4) * 4;
+  constexpr int smem = smem_pipe > smem_epi ? smem_pipe : smem_epi;
   static bool attr_done = false;
   auto kern = gemm_mfma_kernel<BM, BN, WM, WN, KT, NS, TA, TB>;
   if (!attr_done) {
@@ -262,7 +317,7 @@ hipError_t launch_gemm_mfma(GemmP p, int nb, int allow_splitk, int force_cfg, in
   int cfg;
   if (force_cfg >= 0 && force_cfg < kNumCfg) cfg = force_cfg;
   else if (p.transA && !p.transB) cfg = tiles(256, 256) >= 256 ? 0 : 1;
-  else if (!p.transA && !p.transB) cfg = 2;
+  else if (!p.transA && !p.transB) cfg = tiles(256, 256) >= 256 ? 0 : 2;
   else cfg = 1;
   const int bm = kCfg[cfg].bm, bn = kCfg[cfg].bn;
   const int64_t nt = tiles(bm, bn);
@@ -287,6 +342,11 @@ hipError_t launch_gemm_mfma(GemmP p, int nb, int allow_splitk, int force_cfg, in
     }
   }
   p.tiles_n = (int)((N + bn - 1) / bn);
+  {  // vectorised stores need 16-byte aligned rows of C (and of Cadd / C_lo)
+    const int64_t q = p.out_bf16 ? 8 : 4;
+    auto al = [&](const void* x) { return x == nullptr || ((uintptr_t)x % 16) == 0; };
+    p.vecA = al(p.C) && al(p.Cadd) && al(p.C_lo) && p.ldc % q == 0 && p.sC1 % q == 0 && p.sC2 % q == 0;
+  }
   dim3 grid((unsigned)(nt / nb), (unsigned)nb, (unsigned)ks);
   switch (cfg) {
     case 0: return launch_cfg<256, 256, 128, 128, 64, 2>(p, grid, st);
