@@ -33,7 +33,8 @@ struct DualP {
   int klimit, skip_upper;
 };
 
-template <bool TA, bool TB>
+// NT: operand tiles per stage: 4 (A, A_t, B, B_t), 5 (+ A_lo) or 6 (+ A_lo, B_lo).
+template <bool TA, bool TB, int NT>
 __global__ __launch_bounds__(256) void gemm_dual_kernel(DualP p) {
   constexpr int BM = 128, BN = 128, KT = 32;
   constexpr int TILE = 128 * KT;  // elements per operand tile
@@ -44,12 +45,10 @@ __global__ __launch_bounds__(256) void gemm_dual_kernel(DualP p) {
 
   const int t = threadIdx.x, lane = t & 63;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
-  const bool hasAlo = p.Alo != nullptr, hasBlo = p.Blo != nullptr;
-  const int ntile = 4 + (hasAlo ? 1 : 0) + (hasBlo ? 1 : 0);
-  const int stage_el = ntile * TILE;
+  constexpr bool hasAlo = NT >= 5, hasBlo = NT >= 6;
+  constexpr int stage_el = NT * TILE;
   // tile slots inside a stage
-  const int sA = 0, sAt = TILE, sB = 2 * TILE, sBt = 3 * TILE;
-  const int sAlo = 4 * TILE, sBlo = (hasAlo ? 5 : 4) * TILE;
+  constexpr int sA = 0, sAt = TILE, sB = 2 * TILE, sBt = 3 * TILE, sAlo = 4 * TILE, sBlo = 5 * TILE;
 
   int tile = blockIdx.x;
   {
@@ -111,65 +110,92 @@ __global__ __launch_bounds__(256) void gemm_dual_kernel(DualP p) {
     curA += stepA;
     curB += stepB;
   };
-  auto compute = [&](int stage) {
-    const HF_LDS bf16* st = smem + stage * stage_el;
+  // per-lane LDS byte addresses of the fragments inside an operand tile
+  constexpr int NKK = KT / 16;
+  const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
+  uint32_t adA[AKC ? NKK : 1][2], adB[BKC ? NKK : 1][2];
 #pragma unroll
-    for (int kk = 0; kk < KT / 16; ++kk) {
-      bf16x8 a[2], at[2], b[2], bt[2];
+  for (int kk = 0; kk < (AKC ? NKK : 1); ++kk)
+#pragma unroll
+    for (int i = 0; i < 2; ++i) adA[kk][i] = lds0 + frag_addr<BM, AKC, KT>(wm0 + i * 32, kk, lane);
+#pragma unroll
+  for (int kk = 0; kk < (BKC ? NKK : 1); ++kk)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) adB[kk][j] = lds0 + frag_addr<BN, BKC, KT>(wn0 + j * 32, kk, lane);
+
+  // Products of the slab in stage S; the fragments of k-step kk+1 are requested
+  // as soon as those of step kk have landed (explicit reads and waits, see
+  // gemm_mfma_common.h).
+  auto compute = [&](auto stage_c) {
+    constexpr int S = decltype(stage_c)::value;
+    Frag<AKC> a[2][2], at[2][2], al[2][2];
+    Frag<BKC> b[2][2], bt[2][2], bl[2][2];
+    auto request = [&](auto kk_c) {
+      constexpr int kk = decltype(kk_c)::value;
+      constexpr int offA = S * stage_el * 2 + (AKC ? 0 : kk * 16 * BM * 2);
+      constexpr int offB = S * stage_el * 2 + (BKC ? 0 : kk * 16 * BN * 2);
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
-        a[i] = frag_read<BM, AKC, KT>(st + sA, wm0 + i * 32, kk, lane);
-        at[i] = frag_read<BM, AKC, KT>(st + sAt, wm0 + i * 32, kk, lane);
+        a[kk & 1][i].template read<offA + sA * 2, 4 * BM * 2>(adA[AKC ? kk : 0][i]);
+        at[kk & 1][i].template read<offA + sAt * 2, 4 * BM * 2>(adA[AKC ? kk : 0][i]);
       }
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
-        b[j] = frag_read<BN, BKC, KT>(st + sB, wn0 + j * 32, kk, lane);
-        bt[j] = frag_read<BN, BKC, KT>(st + sBt, wn0 + j * 32, kk, lane);
+        b[kk & 1][j].template read<offB + sB * 2, 4 * BN * 2>(adB[BKC ? kk : 0][j]);
+        bt[kk & 1][j].template read<offB + sBt * 2, 4 * BN * 2>(adB[BKC ? kk : 0][j]);
       }
+      if constexpr (hasAlo) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) al[kk & 1][i].template read<offA + sAlo * 2, 4 * BM * 2>(adA[AKC ? kk : 0][i]);
+      }
+      if constexpr (hasBlo) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) bl[kk & 1][j].template read<offB + sBlo * 2, 4 * BN * 2>(adB[BKC ? kk : 0][j]);
+      }
+    };
+    request(std::integral_constant<int, 0>{});
+    static_for<NKK>([&](auto kk_c) {
+      constexpr int kk = decltype(kk_c)::value, c = kk & 1;
+      __builtin_amdgcn_sched_barrier(0);
+      lds_wait_all();
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        a[c][i].tie(); at[c][i].tie(); b[c][i].tie(); bt[c][i].tie();
+        if constexpr (hasAlo) al[c][i].tie();
+        if constexpr (hasBlo) bl[c][i].tie();
+      }
+      if constexpr (kk + 1 < NKK) request(std::integral_constant<int, kk + 1>{});
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
-          accp[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], accp[i][j], 0, 0, 0);
-          acct[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at[i], b[j], acct[i][j], 0, 0, 0);
-          acct[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], bt[j], acct[i][j], 0, 0, 0);
+          accp[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[c][i].get(), b[c][j].get(), accp[i][j], 0, 0, 0);
+          acct[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at[c][i].get(), b[c][j].get(), acct[i][j], 0, 0, 0);
+          acct[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[c][i].get(), bt[c][j].get(), acct[i][j], 0, 0, 0);
+          if constexpr (hasAlo)
+            accp[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[c][i].get(), b[c][j].get(), accp[i][j], 0, 0, 0);
+          if constexpr (hasBlo)
+            accp[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[c][i].get(), bl[c][j].get(), accp[i][j], 0, 0, 0);
         }
-      if (hasAlo) {
-        bf16x8 al[2];
-#pragma unroll
-        for (int i = 0; i < 2; ++i) al[i] = frag_read<BM, AKC, KT>(st + sAlo, wm0 + i * 32, kk, lane);
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-          for (int j = 0; j < 2; ++j) accp[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[i], b[j], accp[i][j], 0, 0, 0);
-      }
-      if (hasBlo) {
-        bf16x8 bl[2];
-#pragma unroll
-        for (int j = 0; j < 2; ++j) bl[j] = frag_read<BN, BKC, KT>(st + sBlo, wn0 + j * 32, kk, lane);
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-          for (int j = 0; j < 2; ++j) accp[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], bl[j], accp[i][j], 0, 0, 0);
-      }
-    }
+    });
   };
 
   // two LDS stages: the loads of slab i+1 fly while slab i is multiplied
   if (nfull > 0) issue(0);
   for (int i0 = 0; i0 < nfull; i0 += 2) {
-#pragma unroll
-    for (int s = 0; s < 2; ++s) {
+    static_for<2>([&](auto s_c) {
+      constexpr int s = decltype(s_c)::value;
       const int i = i0 + s;
       if (i < nfull) {
         HF_WAIT_VMCNT(0);
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
         if (i + 1 < nfull) issue(s ^ 1);
-        compute(s);
+        compute(s_c);
         __builtin_amdgcn_sched_barrier(0);
       }
-    }
+    });
   }
   if (ktail > 0) {
     const int k0 = kbeg + nfull * KT;
@@ -182,7 +208,7 @@ __global__ __launch_bounds__(256) void gemm_dual_kernel(DualP p) {
     if (hasAlo) guarded(p.Alo, sAlo, true);
     if (hasBlo) guarded(p.Blo, sBlo, false);
     __syncthreads();
-    compute(0);
+    compute(std::integral_constant<int, 0>{});
   }
 
   // epilogue: lane holds column (lane & 31), rows 8*(r/4) + 4*(lane/32) + r%4
@@ -218,17 +244,24 @@ __global__ __launch_bounds__(256) void gemm_dual_kernel(DualP p) {
   }
 }
 
-template <bool TA, bool TB>
-static hipError_t launch_dual_one(const DualP& p, dim3 grid, int smem, hipStream_t st) {
+template <bool TA, bool TB, int NT>
+static hipError_t launch_dual_nt(const DualP& p, dim3 grid, hipStream_t st) {
   static bool attr_done = false;
-  auto kern = gemm_dual_kernel<TA, TB>;
+  auto kern = gemm_dual_kernel<TA, TB, NT>;
+  constexpr int smem = 2 * NT * 128 * 32 * 2;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 6 * 128 * 32 * 2 * 2);
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
   hipLaunchKernelGGL(kern, grid, dim3(256), smem, st, p);
   return hipGetLastError();
+}
+template <bool TA, bool TB>
+static hipError_t launch_dual_one(const DualP& p, dim3 grid, hipStream_t st) {
+  if (p.Blo) return launch_dual_nt<TA, TB, 6>(p, grid, st);
+  if (p.Alo) return launch_dual_nt<TA, TB, 5>(p, grid, st);
+  return launch_dual_nt<TA, TB, 4>(p, grid, st);
 }
 
 // g.Ct != nullptr.  Returns hipErrorNotSupported when the description does not
@@ -248,14 +281,13 @@ hipError_t launch_gemm_dual(const Gemm& g, hipStream_t st) {
   p.M = g.M; p.N = g.N; p.K = g.K; p.lda = g.lda; p.ldb = g.ldb; p.ldc = g.ldc; p.nb2 = g.nb2;
   p.sA1 = g.sA1; p.sA2 = g.sA2; p.sB1 = g.sB1; p.sB2 = g.sB2; p.sC1 = g.sC1; p.sC2 = g.sC2;
   p.alpha = g.alpha; p.out_bf16 = g.out_bf16; p.bias_bf16 = 1; p.klimit = g.klimit; p.skip_upper = g.skip_upper;
-  const int ntile = 4 + (p.Alo ? 1 : 0) + (p.Blo ? 1 : 0);
-  const int smem = 2 * ntile * 128 * 32 * 2;
+  if (p.Blo && !p.Alo) return hipErrorNotSupported;
   const int64_t nt = ((g.M + 127) / 128) * (int64_t)((g.N + 127) / 128);
   dim3 grid((unsigned)nt, (unsigned)(g.nb1 * g.nb2), 1);
-  if (!g.transA && !g.transB) return launch_dual_one<false, false>(p, grid, smem, st);
-  if (!g.transA && g.transB) return launch_dual_one<false, true>(p, grid, smem, st);
-  if (g.transA && !g.transB) return launch_dual_one<true, false>(p, grid, smem, st);
-  return launch_dual_one<true, true>(p, grid, smem, st);
+  if (!g.transA && !g.transB) return launch_dual_one<false, false>(p, grid, st);
+  if (!g.transA && g.transB) return launch_dual_one<false, true>(p, grid, st);
+  if (g.transA && !g.transB) return launch_dual_one<true, false>(p, grid, st);
+  return launch_dual_one<true, true>(p, grid, st);
 }
 
 }  // namespace hf

@@ -122,29 +122,54 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmP p) {
       }
     }
   };
-  auto compute = [&](int buf) {
-    const HF_LDS bf16* sa = smem + buf * STAGE;
-    const HF_LDS bf16* sb = sa + A_EL;
-    // fragments of step kk+1 are requested before the products of step kk
-    bf16x8 a[2][TM], b[2][TN];
+  // Per-lane LDS byte addresses of this wave's fragments (stage 0): one per
+  // k-step for a k-contiguous operand (the chunk swizzle depends on k), one in
+  // all for a row-contiguous operand (k-steps are a constant offset apart).
+  constexpr int NKK = KT / 16;
+  const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
+  uint32_t adA[AKC ? NKK : 1][TM], adB[BKC ? NKK : 1][TN];
 #pragma unroll
-    for (int i = 0; i < TM; ++i) a[0][i] = frag_read<BM, AKC, KT>(sa, wm0 + i * 32, 0, lane);
+  for (int kk = 0; kk < (AKC ? NKK : 1); ++kk)
 #pragma unroll
-    for (int j = 0; j < TN; ++j) b[0][j] = frag_read<BN, BKC, KT>(sb, wn0 + j * 32, 0, lane);
+    for (int i = 0; i < TM; ++i) adA[kk][i] = lds0 + frag_addr<BM, AKC, KT>(wm0 + i * 32, kk, lane);
 #pragma unroll
-    for (int kk = 0; kk < KT / 16; ++kk) {
-      if (kk + 1 < KT / 16) {
+  for (int kk = 0; kk < (BKC ? NKK : 1); ++kk)
 #pragma unroll
-        for (int i = 0; i < TM; ++i) a[(kk + 1) & 1][i] = frag_read<BM, AKC, KT>(sa, wm0 + i * 32, kk + 1, lane);
+    for (int j = 0; j < TN; ++j) adB[kk][j] = lds0 + A_EL * 2 + frag_addr<BN, BKC, KT>(wn0 + j * 32, kk, lane);
+
+  // Products of one slab held in LDS stage S.  The fragments of k-step kk+1
+  // are requested right after those of step kk have landed, so their latency
+  // runs behind the matrix instructions of step kk.
+  auto compute = [&](auto stage_c) {
+    constexpr int S = decltype(stage_c)::value;
+    Frag<AKC> a[2][TM];
+    Frag<BKC> b[2][TN];
+    auto request = [&](auto kk_c) {
+      constexpr int kk = decltype(kk_c)::value;
+      constexpr int offA = S * STAGE * 2 + (AKC ? 0 : kk * 16 * BM * 2);
+      constexpr int offB = S * STAGE * 2 + (BKC ? 0 : kk * 16 * BN * 2);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) b[(kk + 1) & 1][j] = frag_read<BN, BKC, KT>(sb, wn0 + j * 32, kk + 1, lane);
-      }
+      for (int i = 0; i < TM; ++i) a[kk & 1][i].template read<offA, 4 * BM * 2>(adA[AKC ? kk : 0][i]);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) b[kk & 1][j].template read<offB, 4 * BN * 2>(adB[BKC ? kk : 0][j]);
+    };
+    request(std::integral_constant<int, 0>{});
+    static_for<NKK>([&](auto kk_c) {
+      constexpr int kk = decltype(kk_c)::value;
+      __builtin_amdgcn_sched_barrier(0);
+      lds_wait_all();
+#pragma unroll
+      for (int i = 0; i < TM; ++i) a[kk & 1][i].tie();
+#pragma unroll
+      for (int j = 0; j < TN; ++j) b[kk & 1][j].tie();
+      if constexpr (kk + 1 < NKK) request(std::integral_constant<int, kk + 1>{});
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk & 1][i], b[kk & 1][j], acc[i][j], 0, 0, 0);
-    }
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk & 1][i].get(), b[kk & 1][j].get(), acc[i][j], 0, 0, 0);
+    });
   };
 
   const int nit = it1 - it0;
@@ -154,8 +179,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmP p) {
   // main loop, unrolled by the number of stages so that every LDS stage
   // address is a compile-time constant
   for (int i0 = 0; i0 < nit; i0 += NS) {
-#pragma unroll
-    for (int s = 0; s < NS; ++s) {
+    static_for<NS>([&](auto s_c) {
+      constexpr int s = decltype(s_c)::value;
       const int i = i0 + s;
       if (i < nit) {
         const int later = min(NS - 2, nit - 1 - i);  // slabs issued after slab i so far
@@ -165,10 +190,10 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmP p) {
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
         if (i + NS - 1 < nit) issue((s + NS - 1) % NS);
-        compute(s);
+        compute(s_c);
         __builtin_amdgcn_sched_barrier(0);
       }
-    }
+    });
   }
   // ragged k remainder (handled by the last split only)
   if (ktail > 0 && ks == nks - 1) {
@@ -180,7 +205,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmP p) {
       slab_guarded<BM, AKC, KT>(A, p.lda, m0, k0, p.M, kend, smem, t);
       slab_guarded<BN, BKC, KT>(B, p.ldb, n0, k0, p.N, kend, smem + A_EL, t);
       __syncthreads();
-      compute(0);
+      compute(std::integral_constant<int, 0>{});
     }
   }
 

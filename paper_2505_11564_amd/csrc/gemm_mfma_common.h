@@ -5,6 +5,9 @@
 #include "hf_internal.h"
 #include "gemm_params.h"
 
+#include <type_traits>
+#include <utility>
+
 namespace hf {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -105,5 +108,88 @@ __device__ __forceinline__ bf16x8 frag_read(const HF_LDS bf16* lds, int rbase, i
     return v;
   }
 }
+
+// ---- explicit LDS fragment reads ---------------------------------------------
+// The main loop issues its fragment reads as inline instructions and waits for
+// them itself.  Left to the compiler, a transpose read that follows a
+// global->LDS load is preceded by a wait for ALL outstanding vector-memory
+// loads (it cannot prove that the two do not touch the same LDS bytes), which
+// would serialise the slab prefetch with the products; here the stage being
+// read and the stage being filled are disjoint by construction and ordered by
+// the barrier at the top of each iteration.
+// addr: byte address in LDS; OFF: compile-time byte offset (split into the
+// 16-bit immediate and a part added to the address).
+template <int OFF>
+__device__ __forceinline__ bf16x8 lds_read_b128(uint32_t addr) {
+  bf16x8 v;
+  constexpr int hi = OFF & ~0xFFFF, lo = OFF & 0xFFFF;
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr + hi), "n"(lo));
+  return v;
+}
+template <int OFF>
+__device__ __forceinline__ bf16x4 lds_read_tr64(uint32_t addr) {
+  bf16x4 v;
+  constexpr int hi = OFF & ~0xFFFF, lo = OFF & 0xFFFF;
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr + hi), "n"(lo));
+  return v;
+}
+// All LDS reads issued so far have landed; the operands tie the fragments to
+// this point so that nothing that uses them is moved above the wait.
+__device__ __forceinline__ void lds_wait_all() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+__device__ __forceinline__ void lds_tie(bf16x8& v) { asm volatile("" : "+v"(v)); }
+__device__ __forceinline__ void lds_tie(bf16x4& v) { asm volatile("" : "+v"(v)); }
+
+// Per-lane byte address (relative to the operand's slab in LDS) of the
+// fragment rows rbase + lane%32 at k-step kk (k-contiguous layout) or at
+// k-step 0 (row-contiguous layout, where k-step kk adds kk*16*R*2 bytes and
+// the second half of the fragment another 4*R*2).
+template <int R, bool KC, int KT>
+__device__ __forceinline__ uint32_t frag_addr(int rbase, int kk, int lane) {
+  if (KC) {
+    const int r = rbase + (lane & 31);
+    const int c = kk * 2 + (lane >> 5);
+    return (uint32_t)((r * KT + (kc_chunk<KT>(r, c) << 3)) * 2);
+  } else {
+    const int i = lane & 15, g = lane >> 4;
+    const int kq = (g >> 1) * 8 + (i >> 2);
+    const int c = rbase + (g & 1) * 16 + (i & 3) * 4;
+    return (uint32_t)((kq * R + ((((c >> 3) ^ ((kq & 3) << 2))) << 3) + (c & 7)) * 2);
+  }
+}
+
+// Compile-time loop: f(std::integral_constant<int, 0>{}), ..., f(<N-1>{}).
+template <typename F, int... I>
+__device__ __forceinline__ void static_for_impl(F& f, std::integer_sequence<int, I...>) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
+// One MFMA operand fragment (8 bf16 per lane) on its way from LDS: a single
+// 16 B read for a k-contiguous operand, two transpose reads for a
+// row-contiguous one.
+template <bool KC>
+struct Frag;
+template <>
+struct Frag<true> {
+  bf16x8 v;
+  template <int OFF, int KSTEP>
+  __device__ __forceinline__ void read(uint32_t addr) { v = lds_read_b128<OFF>(addr); }
+  __device__ __forceinline__ void tie() { lds_tie(v); }
+  __device__ __forceinline__ bf16x8 get() const { return v; }
+};
+template <>
+struct Frag<false> {
+  bf16x4 lo, hi;
+  template <int OFF, int KSTEP>
+  __device__ __forceinline__ void read(uint32_t addr) {
+    lo = lds_read_tr64<OFF>(addr);
+    hi = lds_read_tr64<OFF + KSTEP>(addr);
+  }
+  __device__ __forceinline__ void tie() { lds_tie(lo); lds_tie(hi); }
+  __device__ __forceinline__ bf16x8 get() const { return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7); }
+};
 
 }  // namespace hf

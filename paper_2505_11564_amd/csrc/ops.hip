@@ -8,6 +8,8 @@
 // activations that feed matrix products (float, or bf16 in bf16 mode).
 #include "hf_internal.h"
 
+#include <initializer_list>
+
 namespace hf {
 
 // ---------------------------------------------------------------- helpers ----
@@ -54,6 +56,33 @@ __device__ __forceinline__ float block_max(float v, float* red) {
 
 static inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
+// 8 consecutive elements per thread: one 16 B access of bf16, two of fp32.
+__device__ __forceinline__ void ld8(const float* p, int64_t i8, float (&o)[8]) {
+  const float4 a = ((const float4*)p)[2 * i8], b = ((const float4*)p)[2 * i8 + 1];
+  o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w; o[4] = b.x; o[5] = b.y; o[6] = b.z; o[7] = b.w;
+}
+__device__ __forceinline__ void ld8(const bf16* p, int64_t i8, float (&o)[8]) {
+  const uint4 u = ((const uint4*)p)[i8];
+  o[0] = __uint_as_float(u.x << 16); o[1] = __uint_as_float(u.x & 0xffff0000u);
+  o[2] = __uint_as_float(u.y << 16); o[3] = __uint_as_float(u.y & 0xffff0000u);
+  o[4] = __uint_as_float(u.z << 16); o[5] = __uint_as_float(u.z & 0xffff0000u);
+  o[6] = __uint_as_float(u.w << 16); o[7] = __uint_as_float(u.w & 0xffff0000u);
+}
+__device__ __forceinline__ void st8(float* p, int64_t i8, const float (&v)[8]) {
+  ((float4*)p)[2 * i8] = make_float4(v[0], v[1], v[2], v[3]);
+  ((float4*)p)[2 * i8 + 1] = make_float4(v[4], v[5], v[6], v[7]);
+}
+__device__ __forceinline__ void st8(bf16* p, int64_t i8, const float (&v)[8]) {
+  bf16 o[8];
+#pragma unroll
+  for (int q = 0; q < 8; ++q) o[q] = (bf16)v[q];
+  ((uint4*)p)[i8] = *(const uint4*)o;
+}
+static inline bool all_aligned16(std::initializer_list<const void*> ps) {
+  for (const void* x : ps) if (x && ((uintptr_t)x & 15)) return false;
+  return true;
+}
+
 // ------------------------------------------------------------ fill / cast ----
 
 __global__ void fill_f32_kernel(float* p, int64_t n, float val) {
@@ -85,6 +114,14 @@ hipError_t launch_f32_to_bf16(const float* src, bf16* dst, int64_t n, hipStream_
   return hipGetLastError();
 }
 
+static inline int ew_blocks(int64_t n) { return (int)std::min<int64_t>(cdiv(n, 256), 16384); }
+__global__ void cast_pair_vec_kernel(const float* a, const float* b, bf16* oa, bf16* ob, int64_t n8) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n8; i += (int64_t)gridDim.x * blockDim.x) {
+    float x[8], y[8];
+    ld8(a, i, x); ld8(b, i, y);
+    st8(oa, i, x); st8(ob, i, y);
+  }
+}
 template <typename AT>
 __global__ void cast_pair_kernel(const float* a, const float* b, AT* oa, AT* ob, int64_t n) {
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
@@ -94,6 +131,10 @@ __global__ void cast_pair_kernel(const float* a, const float* b, AT* oa, AT* ob,
 }
 hipError_t launch_cast_pair(int bf, const float* a, const float* b, void* oa, void* ob, int64_t n, hipStream_t st) {
   if (n <= 0) return hipSuccess;
+  if (bf && n % 8 == 0 && all_aligned16({a, b, oa, ob})) {
+    hipLaunchKernelGGL(cast_pair_vec_kernel, dim3(ew_blocks(n / 8)), dim3(256), 0, st, a, b, (bf16*)oa, (bf16*)ob, n / 8);
+    return hipGetLastError();
+  }
   const int blocks = (int)std::min<int64_t>(cdiv(n, 256), 8192);
   if (bf) hipLaunchKernelGGL(cast_pair_kernel<bf16>, dim3(blocks), dim3(256), 0, st, a, b, (bf16*)oa, (bf16*)ob, n);
   else hipLaunchKernelGGL(cast_pair_kernel<float>, dim3(blocks), dim3(256), 0, st, a, b, (float*)oa, (float*)ob, n);
@@ -268,10 +309,123 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(const float* __restrict__
   }
 }
 
+// Vector variant for d % 4 == 0: each thread owns NCH groups of 4 consecutive
+// columns (group j of thread t covers columns 4 (256 j + t) .. +3), keeps the
+// row's four inputs in registers between the reduction and the write, and
+// moves 16 bytes per access.
+__device__ __forceinline__ float4 ld4(const float* p, int64_t i4) { return ((const float4*)p)[i4]; }
+__device__ __forceinline__ float4 ld4(const bf16* p, int64_t i4) {
+  const uint2 u = ((const uint2*)p)[i4];
+  return make_float4(__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xffff0000u), __uint_as_float(u.y << 16),
+                     __uint_as_float(u.y & 0xffff0000u));
+}
+
+template <typename PT, bool RMS, int NCH>
+__global__ __launch_bounds__(256) void norm_bwd_vec_kernel(const float* __restrict__ dy, const float* __restrict__ dy_t,
+                                                           const float* __restrict__ x, const float* __restrict__ x_t,
+                                                           const float* __restrict__ stats, const PT* gam,
+                                                           const float* gam_t, int T, int d, int rows_per_block,
+                                                           int accumulate, float* dx, float* dx_t, float* hv_gam,
+                                                           float* hv_bet) {
+  __shared__ float red[16];
+  const int d4 = d >> 2;
+  float4 pg[NCH], pb[NCH], gm[NCH], gmt[NCH];
+#pragma unroll
+  for (int j = 0; j < NCH; ++j) {
+    pg[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+    pb[j] = pg[j];
+    const int c4 = j * 256 + threadIdx.x;
+    gm[j] = c4 < d4 ? ld4(gam, c4) : pg[j];
+    gmt[j] = c4 < d4 ? ld4(gam_t, c4) : pg[j];
+  }
+  const float inv_d = 1.f / (float)d;
+  const int r0 = blockIdx.x * rows_per_block;
+  const int r1 = min(T, r0 + rows_per_block);
+  for (int row = r0; row < r1; ++row) {
+    const int64_t base4 = (int64_t)row * d4;
+    const float4 s = *(const float4*)(stats + (int64_t)row * 4);
+    const float mu = s.x, rstd = s.y, mxt = s.z, st = s.w;
+    float4 xh[NCH], xht[NCH], dv[NCH], dtv[NCH];
+    float m[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int j = 0; j < NCH; ++j) {
+      const int c4 = j * 256 + threadIdx.x;
+      if (c4 < d4) {
+        const float4 xv = ld4(x, base4 + c4), xtv = ld4(x_t, base4 + c4);
+        dv[j] = ld4(dy, base4 + c4);
+        dtv[j] = ld4(dy_t, base4 + c4);
+#define HF_NBV(q)                                                         \
+  {                                                                       \
+    const float h = (xv.q - mu) * rstd;                                   \
+    const float ht = (xtv.q - mxt - h * st) * rstd;                       \
+    xh[j].q = h; xht[j].q = ht;                                           \
+    const float g = gm[j].q * dv[j].q;                                    \
+    const float gt = gmt[j].q * dv[j].q + gm[j].q * dtv[j].q;             \
+    m[0] += g; m[1] += g * h; m[2] += gt; m[3] += gt * h + g * ht;        \
+  }
+        HF_NBV(x) HF_NBV(y) HF_NBV(z) HF_NBV(w)
+#undef HF_NBV
+      }
+    }
+    block_sum<4>(m, red);
+    float m1 = m[0] * inv_d, m2 = m[1] * inv_d, m1t = m[2] * inv_d, m2t = m[3] * inv_d;
+    if (RMS) { m1 = 0.f; m1t = 0.f; }
+#pragma unroll
+    for (int j = 0; j < NCH; ++j) {
+      const int c4 = j * 256 + threadIdx.x;
+      if (c4 < d4) {
+        float4 o, ot;
+#define HF_NBV(q)                                                                                   \
+  {                                                                                                 \
+    const float g = gm[j].q * dv[j].q;                                                              \
+    const float gt = gmt[j].q * dv[j].q + gm[j].q * dtv[j].q;                                       \
+    o.q = (g - m1 - xh[j].q * m2) * rstd;                                                           \
+    ot.q = (gt - m1t - xht[j].q * m2 - xh[j].q * m2t) * rstd - o.q * st * rstd;                     \
+    pg[j].q += dtv[j].q * xh[j].q + dv[j].q * xht[j].q;                                             \
+    pb[j].q += dtv[j].q;                                                                            \
+  }
+        HF_NBV(x) HF_NBV(y) HF_NBV(z) HF_NBV(w)
+#undef HF_NBV
+        if (accumulate) {
+          const float4 a = ld4(dx, base4 + c4), b = ld4(dx_t, base4 + c4);
+          o.x += a.x; o.y += a.y; o.z += a.z; o.w += a.w;
+          ot.x += b.x; ot.y += b.y; ot.z += b.z; ot.w += b.w;
+        }
+        ((float4*)dx)[base4 + c4] = o;
+        ((float4*)dx_t)[base4 + c4] = ot;
+      }
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < NCH; ++j) {
+    const int c = 4 * (j * 256 + threadIdx.x);
+    if (c < d) {
+      atomicAdd(hv_gam + c, pg[j].x); atomicAdd(hv_gam + c + 1, pg[j].y);
+      atomicAdd(hv_gam + c + 2, pg[j].z); atomicAdd(hv_gam + c + 3, pg[j].w);
+      if (!RMS) {
+        atomicAdd(hv_bet + c, pb[j].x); atomicAdd(hv_bet + c + 1, pb[j].y);
+        atomicAdd(hv_bet + c + 2, pb[j].z); atomicAdd(hv_bet + c + 3, pb[j].w);
+      }
+    }
+  }
+}
+
 hipError_t launch_norm_bwd(int bf, int rms, const float* dy, const float* dy_t, const float* x, const float* x_t,
                            const float* stats, const void* gam, const float* gam_t, int T, int d, int accumulate,
                            float* dx, float* dx_t, float* hv_gam, float* hv_bet, hipStream_t st) {
   if (d > 256 * NORM_MAXC) return hipErrorInvalidValue;
+  if (d % 4 == 0 && all_aligned16({dy, dy_t, x, x_t, dx, dx_t, gam_t}) && ((uintptr_t)gam & (bf ? 7 : 15)) == 0) {
+    const int rpb = std::max(1, T / 512);  // the column atomics at the end bound the block count
+    const int blocks = (T + rpb - 1) / rpb;
+    const int nch = (d / 4 + 255) / 256;
+#define HF_NBV2(PT, R, N) hipLaunchKernelGGL((norm_bwd_vec_kernel<PT, R, N>), dim3(blocks), dim3(256), 0, st, dy, dy_t, x, x_t, stats, (const PT*)gam, gam_t, T, d, rpb, accumulate, dx, dx_t, hv_gam, hv_bet)
+#define HF_NBV1(PT, R) { if (nch <= 1) HF_NBV2(PT, R, 1); else if (nch <= 2) HF_NBV2(PT, R, 2); else if (nch <= 4) HF_NBV2(PT, R, 4); else HF_NBV2(PT, R, 8); }
+    if (bf) { if (rms) HF_NBV1(bf16, true) else HF_NBV1(bf16, false) }
+    else { if (rms) HF_NBV1(float, true) else HF_NBV1(float, false) }
+#undef HF_NBV1
+#undef HF_NBV2
+    return hipGetLastError();
+  }
   const int rpb = std::max(1, T / 512);
   const int blocks = (T + rpb - 1) / rpb;
 #define HF_NB(PT, R) hipLaunchKernelGGL((norm_bwd_kernel<PT, R>), dim3(blocks), dim3(256), 0, st, dy, dy_t, x, x_t, stats, (const PT*)gam, gam_t, T, d, rpb, accumulate, dx, dx_t, hv_gam, hv_bet)
@@ -319,11 +473,87 @@ __global__ void act_bwd_kernel(int act, const AT* a, const AT* a_t, const AT* dy
     stf(da_t, i, f1 * ldf(dy_t, i) + f2 * ldf(a_t, i) * d);
   }
 }
-static inline int ew_blocks(int64_t n) { return (int)std::min<int64_t>(cdiv(n, 256), 16384); }
+
+template <typename AT>
+__global__ void act_fwd_vec_kernel(int act, const AT* a, const AT* a_t, const AT* a_lo, AT* y, AT* y_t, AT* y_lo, int64_t n8) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n8; i += (int64_t)gridDim.x * blockDim.x) {
+    float av[8], at[8], yv[8], yt[8], yl[8];
+    ld8(a, i, av); ld8(a_t, i, at);
+    if (a_lo) { float al[8]; ld8(a_lo, i, al);
+#pragma unroll
+      for (int q = 0; q < 8; ++q) av[q] += al[q]; }
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      float f, f1, f2;
+      act_derivs(act, av[q], f, f1, f2);
+      yv[q] = f; yt[q] = f1 * at[q]; yl[q] = f - (float)(AT)f;
+    }
+    st8(y, i, yv); st8(y_t, i, yt);
+    if (y_lo) st8(y_lo, i, yl);
+  }
+}
+template <typename AT>
+__global__ void act_bwd_vec_kernel(int act, const AT* a, const AT* a_t, const AT* dy, const AT* dy_t, AT* da, AT* da_t, int64_t n8) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n8; i += (int64_t)gridDim.x * blockDim.x) {
+    float av[8], at[8], d[8], dt[8], o[8], ot[8];
+    ld8(a, i, av); ld8(a_t, i, at); ld8(dy, i, d); ld8(dy_t, i, dt);
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      float f, f1, f2;
+      act_derivs(act, av[q], f, f1, f2);
+      o[q] = f1 * d[q]; ot[q] = f1 * dt[q] + f2 * at[q] * d[q];
+    }
+    st8(da, i, o); st8(da_t, i, ot);
+  }
+}
+template <typename AT>
+__global__ void swiglu_fwd_vec_kernel(const AT* g, const AT* g_t, const AT* u, const AT* u_t, const AT* g_lo, const AT* u_lo,
+                                      AT* y, AT* y_t, AT* y_lo, int64_t n8) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n8; i += (int64_t)gridDim.x * blockDim.x) {
+    float gv[8], gt[8], uv[8], ut[8], yv[8], yt[8], yl[8];
+    ld8(g, i, gv); ld8(g_t, i, gt); ld8(u, i, uv); ld8(u_t, i, ut);
+    if (g_lo) { float a8[8], b8[8]; ld8(g_lo, i, a8); ld8(u_lo, i, b8);
+#pragma unroll
+      for (int q = 0; q < 8; ++q) { gv[q] += a8[q]; uv[q] += b8[q]; } }
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const float sg = 1.f / (1.f + __expf(-gv[q]));
+      const float s = gv[q] * sg, s1 = sg + gv[q] * sg * (1.f - sg);
+      yv[q] = s * uv[q]; yt[q] = s1 * gt[q] * uv[q] + s * ut[q]; yl[q] = yv[q] - (float)(AT)yv[q];
+    }
+    st8(y, i, yv); st8(y_t, i, yt);
+    if (y_lo) st8(y_lo, i, yl);
+  }
+}
+template <typename AT>
+__global__ void swiglu_bwd_vec_kernel(const AT* g, const AT* g_t, const AT* u, const AT* u_t, const AT* dy, const AT* dy_t,
+                                      AT* dg, AT* dg_t, AT* du, AT* du_t, int64_t n8) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n8; i += (int64_t)gridDim.x * blockDim.x) {
+    float gv[8], gt[8], uv[8], ut[8], d[8], dt[8], o1[8], o2[8], o3[8], o4[8];
+    ld8(g, i, gv); ld8(g_t, i, gt); ld8(u, i, uv); ld8(u_t, i, ut); ld8(dy, i, d); ld8(dy_t, i, dt);
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const float sg = 1.f / (1.f + __expf(-gv[q]));
+      const float dsg = sg * (1.f - sg);
+      const float s = gv[q] * sg, s1 = sg + gv[q] * dsg, s2 = dsg * (2.f + gv[q] * (1.f - 2.f * sg));
+      o1[q] = s1 * uv[q] * d[q];
+      o3[q] = s * d[q];
+      o2[q] = s2 * gt[q] * uv[q] * d[q] + s1 * ut[q] * d[q] + s1 * uv[q] * dt[q];
+      o4[q] = s1 * gt[q] * d[q] + s * dt[q];
+    }
+    st8(dg, i, o1); st8(dg_t, i, o2); st8(du, i, o3); st8(du_t, i, o4);
+  }
+}
 
 hipError_t launch_act_fwd(int bf, int act, const void* a, const void* a_t, const void* a_lo, void* y, void* y_t,
                           void* y_lo, int64_t n, hipStream_t st) {
   if (n <= 0) return hipSuccess;
+  if (n % 8 == 0 && all_aligned16({a, a_t, a_lo, y, y_t, y_lo})) {
+    const int nb = ew_blocks(n / 8);
+    if (bf) hipLaunchKernelGGL(act_fwd_vec_kernel<bf16>, dim3(nb), dim3(256), 0, st, act, (const bf16*)a, (const bf16*)a_t, (const bf16*)a_lo, (bf16*)y, (bf16*)y_t, (bf16*)y_lo, n / 8);
+    else hipLaunchKernelGGL(act_fwd_vec_kernel<float>, dim3(nb), dim3(256), 0, st, act, (const float*)a, (const float*)a_t, (const float*)a_lo, (float*)y, (float*)y_t, (float*)y_lo, n / 8);
+    return hipGetLastError();
+  }
   if (bf) hipLaunchKernelGGL(act_fwd_kernel<bf16>, dim3(ew_blocks(n)), dim3(256), 0, st, act, (const bf16*)a, (const bf16*)a_t, (const bf16*)a_lo, (bf16*)y, (bf16*)y_t, (bf16*)y_lo, n);
   else hipLaunchKernelGGL(act_fwd_kernel<float>, dim3(ew_blocks(n)), dim3(256), 0, st, act, (const float*)a, (const float*)a_t, (const float*)a_lo, (float*)y, (float*)y_t, (float*)y_lo, n);
   return hipGetLastError();
@@ -331,6 +561,12 @@ hipError_t launch_act_fwd(int bf, int act, const void* a, const void* a_t, const
 hipError_t launch_act_bwd(int bf, int act, const void* a, const void* a_t, const void* dy, const void* dy_t, void* da,
                           void* da_t, int64_t n, hipStream_t st) {
   if (n <= 0) return hipSuccess;
+  if (n % 8 == 0 && all_aligned16({a, a_t, dy, dy_t, da, da_t})) {
+    const int nb = ew_blocks(n / 8);
+    if (bf) hipLaunchKernelGGL(act_bwd_vec_kernel<bf16>, dim3(nb), dim3(256), 0, st, act, (const bf16*)a, (const bf16*)a_t, (const bf16*)dy, (const bf16*)dy_t, (bf16*)da, (bf16*)da_t, n / 8);
+    else hipLaunchKernelGGL(act_bwd_vec_kernel<float>, dim3(nb), dim3(256), 0, st, act, (const float*)a, (const float*)a_t, (const float*)dy, (const float*)dy_t, (float*)da, (float*)da_t, n / 8);
+    return hipGetLastError();
+  }
   if (bf) hipLaunchKernelGGL(act_bwd_kernel<bf16>, dim3(ew_blocks(n)), dim3(256), 0, st, act, (const bf16*)a, (const bf16*)a_t, (const bf16*)dy, (const bf16*)dy_t, (bf16*)da, (bf16*)da_t, n);
   else hipLaunchKernelGGL(act_bwd_kernel<float>, dim3(ew_blocks(n)), dim3(256), 0, st, act, (const float*)a, (const float*)a_t, (const float*)dy, (const float*)dy_t, (float*)da, (float*)da_t, n);
   return hipGetLastError();
@@ -370,6 +606,12 @@ __global__ void swiglu_bwd_kernel(const AT* g, const AT* g_t, const AT* u, const
 hipError_t launch_swiglu_fwd(int bf, const void* g, const void* g_t, const void* u, const void* u_t, const void* g_lo,
                              const void* u_lo, void* y, void* y_t, void* y_lo, int64_t n, hipStream_t st) {
   if (n <= 0) return hipSuccess;
+  if (n % 8 == 0 && all_aligned16({g, g_t, u, u_t, g_lo, u_lo, y, y_t, y_lo})) {
+    const int nb = ew_blocks(n / 8);
+    if (bf) hipLaunchKernelGGL(swiglu_fwd_vec_kernel<bf16>, dim3(nb), dim3(256), 0, st, (const bf16*)g, (const bf16*)g_t, (const bf16*)u, (const bf16*)u_t, (const bf16*)g_lo, (const bf16*)u_lo, (bf16*)y, (bf16*)y_t, (bf16*)y_lo, n / 8);
+    else hipLaunchKernelGGL(swiglu_fwd_vec_kernel<float>, dim3(nb), dim3(256), 0, st, (const float*)g, (const float*)g_t, (const float*)u, (const float*)u_t, (const float*)g_lo, (const float*)u_lo, (float*)y, (float*)y_t, (float*)y_lo, n / 8);
+    return hipGetLastError();
+  }
   if (bf) hipLaunchKernelGGL(swiglu_fwd_kernel<bf16>, dim3(ew_blocks(n)), dim3(256), 0, st, (const bf16*)g, (const bf16*)g_t, (const bf16*)u, (const bf16*)u_t, (const bf16*)g_lo, (const bf16*)u_lo, (bf16*)y, (bf16*)y_t, (bf16*)y_lo, n);
   else hipLaunchKernelGGL(swiglu_fwd_kernel<float>, dim3(ew_blocks(n)), dim3(256), 0, st, (const float*)g, (const float*)g_t, (const float*)u, (const float*)u_t, (const float*)g_lo, (const float*)u_lo, (float*)y, (float*)y_t, (float*)y_lo, n);
   return hipGetLastError();
@@ -377,6 +619,12 @@ hipError_t launch_swiglu_fwd(int bf, const void* g, const void* g_t, const void*
 hipError_t launch_swiglu_bwd(int bf, const void* g, const void* g_t, const void* u, const void* u_t, const void* dy,
                              const void* dy_t, void* dg, void* dg_t, void* du, void* du_t, int64_t n, hipStream_t st) {
   if (n <= 0) return hipSuccess;
+  if (n % 8 == 0 && all_aligned16({g, g_t, u, u_t, dy, dy_t, dg, dg_t, du, du_t})) {
+    const int nb = ew_blocks(n / 8);
+    if (bf) hipLaunchKernelGGL(swiglu_bwd_vec_kernel<bf16>, dim3(nb), dim3(256), 0, st, (const bf16*)g, (const bf16*)g_t, (const bf16*)u, (const bf16*)u_t, (const bf16*)dy, (const bf16*)dy_t, (bf16*)dg, (bf16*)dg_t, (bf16*)du, (bf16*)du_t, n / 8);
+    else hipLaunchKernelGGL(swiglu_bwd_vec_kernel<float>, dim3(nb), dim3(256), 0, st, (const float*)g, (const float*)g_t, (const float*)u, (const float*)u_t, (const float*)dy, (const float*)dy_t, (float*)dg, (float*)dg_t, (float*)du, (float*)du_t, n / 8);
+    return hipGetLastError();
+  }
   if (bf) hipLaunchKernelGGL(swiglu_bwd_kernel<bf16>, dim3(ew_blocks(n)), dim3(256), 0, st, (const bf16*)g, (const bf16*)g_t, (const bf16*)u, (const bf16*)u_t, (const bf16*)dy, (const bf16*)dy_t, (bf16*)dg, (bf16*)dg_t, (bf16*)du, (bf16*)du_t, n);
   else hipLaunchKernelGGL(swiglu_bwd_kernel<float>, dim3(ew_blocks(n)), dim3(256), 0, st, (const float*)g, (const float*)g_t, (const float*)u, (const float*)u_t, (const float*)dy, (const float*)dy_t, (float*)dg, (float*)dg_t, (float*)du, (float*)du_t, n);
   return hipGetLastError();
