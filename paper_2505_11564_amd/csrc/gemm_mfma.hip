@@ -137,11 +137,40 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmP p) {
 #pragma unroll
     for (int j = 0; j < TN; ++j) adB[kk][j] = lds0 + A_EL * 2 + frag_addr<BN, BKC, KT>(wn0 + j * 32, kk, lane);
 
+  // Issue-side helpers for loads interleaved with the products: load number L
+  // of the next slab (A tiles first), and the cursor update after the last.
+  auto issue_one = [&](auto stage_c, auto l_c) {
+    constexpr int stage = decltype(stage_c)::value, L = decltype(l_c)::value;
+    HF_LDS char* sa = smem_c + stage * (STAGE * 2);
+    if constexpr (L < NIA)
+      __builtin_amdgcn_global_load_lds((const void*)(i_a + voffA[L]), (HF_LDS void*)(sa + wave * (NIA * 1024) + L * 1024), 16, 0, 0);
+    else
+      __builtin_amdgcn_global_load_lds((const void*)(i_b + voffB[L - NIA]),
+                                       (HF_LDS void*)(sa + A_EL * 2 + wave * (NIB * 1024) + (L - NIA) * 1024), 16, 0, 0);
+  };
+  auto issue_advance = [&]() {
+    i_a += stepA;
+    i_b += stepB;
+    if (++i_slab == nfull) {  // next term
+      i_slab = 0;
+      if (++i_term < nterm) {
+        i_a = slab_base(p.A[i_term], offA, AKC, p.lda, m0, kbeg);
+        i_b = slab_base(p.B[i_term], offB, BKC, p.ldb, n0, kbeg);
+      }
+    }
+  };
+
   // Products of one slab held in LDS stage S.  The fragments of k-step kk+1
   // are requested right after those of step kk have landed, so their latency
-  // runs behind the matrix instructions of step kk.
-  auto compute = [&](auto stage_c) {
+  // runs behind the matrix instructions of step kk.  With ISSUE, the loads of
+  // the slab NS-1 ahead (into the stage that the barrier at the top of this
+  // iteration has released) are dealt out between the matrix instructions, one
+  // per MPL of them, so that issuing them never leaves the matrix cores idle.
+  auto compute = [&](auto stage_c, auto issue_c, uint32_t dyn_off) {
     constexpr int S = decltype(stage_c)::value;
+    constexpr bool ISSUE = decltype(issue_c)::value;
+    constexpr int Q = TM * TN, LPK = NLOAD / NKK, MPL = Q / LPK;
+    static_assert(NLOAD % NKK == 0 && Q % LPK == 0, "loads divide evenly over the k-steps");
     Frag<AKC> a[2][TM];
     Frag<BKC> b[2][TN];
     auto request = [&](auto kk_c) {
@@ -149,9 +178,9 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmP p) {
       constexpr int offA = S * STAGE * 2 + (AKC ? 0 : kk * 16 * BM * 2);
       constexpr int offB = S * STAGE * 2 + (BKC ? 0 : kk * 16 * BN * 2);
 #pragma unroll
-      for (int i = 0; i < TM; ++i) a[kk & 1][i].template read<offA, 4 * BM * 2>(adA[AKC ? kk : 0][i]);
+      for (int i = 0; i < TM; ++i) a[kk & 1][i].template read<offA, 4 * BM * 2>(adA[AKC ? kk : 0][i] + dyn_off);
 #pragma unroll
-      for (int j = 0; j < TN; ++j) b[kk & 1][j].template read<offB, 4 * BN * 2>(adB[BKC ? kk : 0][j]);
+      for (int j = 0; j < TN; ++j) b[kk & 1][j].template read<offB, 4 * BN * 2>(adB[BKC ? kk : 0][j] + dyn_off);
     };
     request(std::integral_constant<int, 0>{});
     static_for<NKK>([&](auto kk_c) {
@@ -164,36 +193,51 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmP p) {
       for (int j = 0; j < TN; ++j) b[kk & 1][j].tie();
       if constexpr (kk + 1 < NKK) request(std::integral_constant<int, kk + 1>{});
       __builtin_amdgcn_sched_barrier(0);
+      static_for<LPK>([&](auto g_c) {
+        constexpr int g = decltype(g_c)::value;
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk & 1][i].get(), b[kk & 1][j].get(), acc[i][j], 0, 0, 0);
+        for (int q = g * MPL; q < (g + 1) * MPL; ++q)
+          acc[q / TN][q % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk & 1][q / TN].get(), b[kk & 1][q % TN].get(),
+                                                                        acc[q / TN][q % TN], 0, 0, 0);
+        if constexpr (ISSUE) {
+          issue_one(std::integral_constant<int, (S + NS - 1) % NS>{}, std::integral_constant<int, kk * LPK + g>{});
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      });
     });
+    if constexpr (ISSUE) issue_advance();
   };
 
   const int nit = it1 - it0;
 #pragma unroll
   for (int s = 0; s < NS - 1; ++s)
     if (s < nit) issue(s);
-  // main loop, unrolled by the number of stages so that every LDS stage
-  // address is a compile-time constant
-  for (int i0 = 0; i0 < nit; i0 += NS) {
+  // main loop over the slabs that still have a slab to prefetch, unrolled by
+  // the number of stages so that every LDS stage address is a compile-time
+  // constant; then the last NS-1 slabs, which only multiply (their stage is a
+  // run-time offset).
+  const int n_main = max(0, nit - (NS - 1));
+  for (int i0 = 0; i0 < n_main; i0 += NS) {
     static_for<NS>([&](auto s_c) {
       constexpr int s = decltype(s_c)::value;
-      const int i = i0 + s;
-      if (i < nit) {
-        const int later = min(NS - 2, nit - 1 - i);  // slabs issued after slab i so far
-        if (later >= 2) HF_WAIT_VMCNT(2 * NLOAD);
-        else if (later == 1) HF_WAIT_VMCNT(NLOAD);
-        else HF_WAIT_VMCNT(0);
+      if (i0 + s < n_main) {
+        HF_WAIT_VMCNT((NS - 2) * NLOAD);
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
-        if (i + NS - 1 < nit) issue((s + NS - 1) % NS);
-        compute(s_c);
+        compute(s_c, std::true_type{}, 0u);
         __builtin_amdgcn_sched_barrier(0);
       }
     });
+  }
+  for (int i = n_main; i < nit; ++i) {
+    const int later = min(NS - 2, nit - 1 - i);  // slabs issued after slab i
+    if (later >= 2) HF_WAIT_VMCNT(2 * NLOAD);
+    else if (later == 1) HF_WAIT_VMCNT(NLOAD);
+    else HF_WAIT_VMCNT(0);
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    compute(std::integral_constant<int, 0>{}, std::false_type{}, (uint32_t)((i % NS) * (STAGE * 2)));
+    __builtin_amdgcn_sched_barrier(0);
   }
   // ragged k remainder (handled by the last split only)
   if (ktail > 0 && ks == nks - 1) {
@@ -205,7 +249,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmP p) {
       slab_guarded<BM, AKC, KT>(A, p.lda, m0, k0, p.M, kend, smem, t);
       slab_guarded<BN, BKC, KT>(B, p.ldb, n0, k0, p.N, kend, smem + A_EL, t);
       __syncthreads();
-      compute(std::integral_constant<int, 0>{});
+      compute(std::integral_constant<int, 0>{}, std::false_type{}, 0u);
     }
   }
 
@@ -338,11 +382,12 @@ hipError_t launch_gemm_mfma(GemmP p, int nb, int allow_splitk, int force_cfg, in
   auto tiles = [&](int bm, int bn) { return ((M + bm - 1) / bm) * ((N + bn - 1) / bn) * (int64_t)nb; };
   // Measured on MI355X (4096x8192x2048-class and 4096x2304x768-class shapes):
   // 128x128 tiles with two or more blocks per CU beat 256x256 except for A^T B
-  // products with plenty of tiles; a row-contiguous B prefers 32-deep slabs.
+  // products with plenty of tiles; a row-contiguous B with a short k prefers
+  // 32-deep slabs (the pipeline fills sooner).
   int cfg;
   if (force_cfg >= 0 && force_cfg < kNumCfg) cfg = force_cfg;
   else if (p.transA && !p.transB) cfg = tiles(256, 256) >= 256 ? 0 : 1;
-  else if (!p.transA && !p.transB) cfg = tiles(256, 256) >= 256 ? 0 : 2;
+  else if (!p.transA && !p.transB) cfg = tiles(256, 256) >= 256 ? 0 : (p.K >= 1536 ? 1 : 2);
   else cfg = 1;
   const int bm = kCfg[cfg].bm, bn = kCfg[cfg].bn;
   const int64_t nt = tiles(bm, bn);
