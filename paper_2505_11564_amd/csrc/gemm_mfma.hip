@@ -29,8 +29,14 @@ namespace hf {
 // (which also tells every wave that slab i-1 has been consumed), issues the
 // loads of slab i+NS-1 into the stage slab i-1 occupied, and multiplies slab i:
 // NS-1 slabs of loads are in flight behind the matrix cores.
+// 128x128 tiles with 32-deep slabs are compiled for three resident blocks per
+// CU (768 slots), which fits the 576- and 768-tile products of the small
+// models in one round; the other shapes take what registers they need.
+template <int BM, int BN, int KT>
+constexpr int min_blocks() { return (BM == 128 && BN == 128 && KT == 32) ? 3 : 1; }
+
 template <int BM, int BN, int WM, int WN, int KT, int NS, bool TA, bool TB>
-__global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmP p) {
+__global__ __launch_bounds__(256, (min_blocks<BM, BN, KT>())) void gemm_mfma_kernel(GemmP p) {
   static_assert((BM / WM) * (BN / WN) == 4, "four waves");
   static_assert(NS >= 2 && NS <= 4, "stages");
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
