@@ -55,6 +55,22 @@ def lanczos_bytes(n, k, reorth, basis_bytes):
     return b
 
 
+def measured_traffic(workload):
+    """HBM bytes per Hessian-vector product from the committed rocprofv3 --pmc
+    summary of this workload (FETCH_SIZE and WRITE_SIZE summed over the
+    kernels of one product, scaled by a copy kernel of known size); None when
+    no summary has been committed for it."""
+    path = os.path.join(ROOT, "profiles", f"hvp_{workload}_hbm_traffic.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("traffic_bytes_per_hvp:"):
+                    return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(cfg, params, seq_sample, budget_note):
     """The float64 oracle, as it stands, on one sequence of the workload's
     batch: one Lanczos iteration (one oracle HVP plus the vector update)."""
@@ -87,6 +103,9 @@ def main():
     ap.add_argument("--workload", default="gpt2_small")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--hvp-reps", type=int, default=10)
+    ap.add_argument("--hvp-only", type=int, default=0, metavar="N",
+                    help="profiling aid: run N Hessian-vector products, then one elementwise pass over a "
+                         "1 GiB fp32 tensor (a kernel of known HBM traffic that calibrates the byte counters), and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (no collectives are part of it); run with --gpus 1",
@@ -120,6 +139,19 @@ def main():
     # ---- HVP alone (MFMA roofline) ------------------------------------------
     vd = (zd / float(np.sqrt(n))).contiguous()
     out = torch.empty(n, dtype=torch.float32, device="cuda")
+    if args.hvp_only > 0:
+        for _ in range(args.hvp_only):
+            ctx.hf_hvp(pd, xd, yd, B, Sarg, vd, out, want_loss=False)
+        torch.cuda.synchronize()
+        cal = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        cal2 = torch.empty_like(cal)
+        torch.cuda.synchronize()
+        torch.mul(cal, 2.0, out=cal2)  # last dispatch of the run: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        print(json.dumps({"workload": args.workload, "hvps": args.hvp_only, "calibration_read_bytes": 4 << 28,
+                          "calibration_write_bytes": 4 << 28}))
+        ctx.close()
+        return
     for _ in range(2):
         ctx.hf_hvp(pd, xd, yd, B, Sarg, vd, out)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -182,7 +214,7 @@ def main():
         "hvps_per_s": 1e3 / hvp_ms, "hvp_ms": hvp_ms,
         "roofline": {"kernel": "hf_hvp (all kernels of one Hessian-vector product)", "bound": "mfma",
                      "achieved": hvp_tflops, "peak": peak, "unit": "TFLOP/s", "frac": hvp_tflops / peak,
-                     "flops_per_launch": flops, "traffic": None},
+                     "flops_per_launch": flops, "traffic": measured_traffic(args.workload)},
         "roofline_lanczos": {"kernel": "hf_lanczos_update (vector kernels of one iteration)", "bound": "hbm",
                              "achieved": lz_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": lz_gbs / PEAK_HBM_GBS,
                              "basis_depth": depth, "ms": sum(upd_ms) / len(upd_ms), "traffic": None},
