@@ -219,6 +219,28 @@ def main():
                              "achieved": lz_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": lz_gbs / PEAK_HBM_GBS,
                              "basis_depth": depth, "ms": sum(upd_ms) / len(upd_ms), "traffic": None},
     }
+    # ---- widened rows: Hessian-column statistics (two streaming passes over an
+    # n-vector, 8 n bytes) and the batch loop of Algorithm 1 over two half batches
+    thr = 10.0 ** np.arange(-12, 0, dtype=np.float64)
+    ctx.hf_column_stats(out, n, thr, 50)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(3):
+        ctx.hf_column_stats(out, n, thr, 50)
+    cs_ms = (time.perf_counter() - t0) / 3 * 1e3
+    res["next_rows"] = {"column_stats": {"bound": "hbm", "bytes": 8.0 * n, "ms": cs_ms,
+                                         "achieved": 8.0 * n / (cs_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                         "frac": 8.0 * n / (cs_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                                         "note": "wall clock of hf_column_stats incl. its two host synchronisations"}}
+    if B >= 2:
+        half = B // 2
+        ctx.hf_hvp_accumulate(pd, xd, yd, B, half, Sarg, vd, out)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ctx.hf_hvp_accumulate(pd, xd, yd, B, half, Sarg, vd, out)
+        acc_ms = (time.perf_counter() - t0) * 1e3
+        res["next_rows"]["hvp_accumulate"] = {"samples": B, "micro_batch": half, "ms": acc_ms,
+                                              "tflops": flops / (acc_ms * 1e-3) / 1e12}
     ctx.close()
     if not args.no_cpu_baseline:
         del pd, out, r, dvec

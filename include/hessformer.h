@@ -200,6 +200,65 @@ int32_t hf_slq(hf_ctx* ctx, const void* params_dev, const void* inputs_dev,
 int32_t hf_lanczos_update(hf_ctx* ctx, float* r_dev, double tol,
                           double* alpha_k, double* beta_k, void* hip_stream);
 
+/* ---- Widened rows ------------------------------------------------------------ */
+
+/* Dataset-averaged Hessian-vector product: the batch loop of Algorithm 1.
+ * inputs_dev / labels_dev hold n_samples samples (tokens [n_samples, seq] and
+ * labels [n_samples, seq]; MLP: x [n_samples, mlp_in] and labels [n_samples]).
+ * They are walked in consecutive batches of micro_batch samples (the last one
+ * may be smaller, micro_batch <= max_batch of hf_create); each batch's product
+ * u_B of its own mean loss is accumulated as h += u_B |B| with |B| the number of
+ * samples in the batch, and out_dev (device, fp32[n], 16-byte aligned, must not
+ * alias an input) receives h / n_samples.  loss_host (host, may be NULL)
+ * receives the same weighted mean of the batch losses.  Allocates one
+ * n-float auxiliary device vector on first use (HF_ENOMEM if that fails); it is
+ * owned by the context.  Synchronises the stream once per batch.  Errors as
+ * hf_hvp. */
+int32_t hf_hvp_accumulate(hf_ctx* ctx, const void* params_dev, const void* inputs_dev,
+                          const int32_t* labels_dev, int32_t n_samples, int32_t micro_batch,
+                          int32_t seq, const float* v_dev, float* out_dev, double* loss_host,
+                          void* hip_stream);
+
+/* One column of the Hessian (section "Banded Hessians"): the product with the
+ * vector that is 1 at `index` (0 <= index < n, canonical order) and 0
+ * elsewhere.  column_dev: device, fp32[n], caller-owned, must not alias
+ * params_dev.  Uses the context's auxiliary vector (see hf_hvp_accumulate).
+ * Other arguments and errors as hf_hvp. */
+int32_t hf_hessian_column(hf_ctx* ctx, const void* params_dev, const void* inputs_dev,
+                          const int32_t* labels_dev, int32_t batch, int32_t seq, int64_t index,
+                          float* column_dev, double* loss_host, void* hip_stream);
+
+/* Sparsity summary of a vector, as tabulated in section "Banded Hessians":
+ * below[k] = number of i with |h_i| < thresholds[k] (float32 comparison);
+ * *max_abs = max_i |h_i|; hist = histogram of |h_i| with n_bins equal bins over
+ * [0, max_abs]: entry i falls in bin floor(|h_i| * (n_bins / max_abs)), quotient
+ * and product each rounded to float32, clamped to the last bin (which therefore
+ * holds the maximum).  A vector of zeros puts every entry in bin 0.  NaN
+ * entries are below no threshold and are left out of max_abs and hist.
+ * h_dev: device, fp32[n], 4-byte aligned, read-only, n < 2^40 (n = 0 allowed).
+ * thresholds (host, n_thresholds <= 16), below (host, int64[n_thresholds]),
+ * max_abs (host), hist (host, int64[n_bins], 1 <= n_bins <= 256).  Two
+ * streaming passes over h_dev; synchronises the stream.  HF_EINVAL on bad
+ * arguments. */
+int32_t hf_column_stats(hf_ctx* ctx, const float* h_dev, int64_t n, const float* thresholds,
+                        int32_t n_thresholds, int32_t n_bins, int64_t* below, float* max_abs,
+                        int64_t* hist, void* hip_stream);
+
+/* Smoothed spectral density from the quadrature nodes and weights of hf_slq
+ * (the smoothed densities the paper plots; Table 2 lists the underlying nodes
+ * and weights): density[g] = (1/n_probes) sum_p sum_{i < m_eff[p]}
+ * weights[p*m+i] N(grid[g]; ritz[p*m+i], sigma^2).  Host only, float64; all
+ * arrays caller-owned.  HF_EINVAL on NULL, sigma <= 0 or m_eff[p] outside [0, m]. */
+int32_t hf_slq_density(const double* ritz, const double* weights, const int32_t* m_eff,
+                       int32_t n_probes, int32_t m, double sigma, const double* grid,
+                       int32_t n_grid, double* density);
+
+/* Moment estimates from the same nodes and weights: moments[q] =
+ * (1/n_probes) sum_p sum_i weights[p*m+i] ritz[p*m+i]^q, q = 0..n_moments-1, the
+ * quadrature estimate of tr(H^q)/n for Rademacher probes.  Host only. */
+int32_t hf_slq_moments(const double* ritz, const double* weights, const int32_t* m_eff,
+                       int32_t n_probes, int32_t m, int32_t n_moments, double* moments);
+
 #ifdef __cplusplus
 }
 #endif

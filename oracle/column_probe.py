@@ -11,8 +11,9 @@ Decisions taken in float32, the precision the column is produced in: an entry
 counts as below a threshold t when |h_i| < t with both sides float32; the
 histogram spans [0, max_i |h_i|] with n_bins equal bins, entry i falls in bin
 floor(|h_i| * (n_bins / max)) with the quotient and the product each rounded to
-float32, and the largest entry belongs to the last bin.  A column of zeros puts
-every entry in bin 0.  NaN entries are below no threshold and are left out of
+float32, and the largest entry belongs to the last bin (so does an entry whose
+product is not a number, which takes an infinite maximum).  A column of zeros
+puts every entry in bin 0.  NaN entries are below no threshold and are left out of
 the maximum and of the histogram.
 """
 from __future__ import annotations
@@ -39,8 +40,10 @@ def column_stats(h, thresholds, n_bins):
     hist = np.zeros(n_bins, dtype=np.int64)
     if mx > 0:
         scale = np.float32(n_bins) / mx                       # float32 quotient
-        idx = np.floor(a[ok] * scale).astype(np.int64)         # float32 product
-        idx = np.minimum(idx, n_bins - 1)
+        with np.errstate(invalid="ignore"):
+            prod = a[ok] * scale                               # float32 product
+        idx = np.where(np.isnan(prod), n_bins - 1, np.minimum(np.floor(np.nan_to_num(prod, nan=0.0)), n_bins - 1))
+        idx = idx.astype(np.int64)
         np.add.at(hist, idx, 1)
     else:
         hist[0] = int(ok.sum())

@@ -23,6 +23,7 @@ EXPORTS = [
     "hf_create", "hf_destroy", "hf_num_params", "hf_workspace_bytes", "hf_last_error",
     "hf_hvp", "hf_lanczos_init", "hf_lanczos_step", "hf_lanczos_iterations", "hf_lanczos_get_vector",
     "hf_slq", "hf_lanczos_update",
+    "hf_hvp_accumulate", "hf_hessian_column", "hf_column_stats", "hf_slq_density", "hf_slq_moments",
 ]
 
 
@@ -83,6 +84,17 @@ def lib():
     L.hf_slq.restype = i32
     L.hf_lanczos_update.argtypes = [vp, vp, C.c_double, dp, dp, vp]
     L.hf_lanczos_update.restype = i32
+    L.hf_hvp_accumulate.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp, vp, dp, vp]
+    L.hf_hvp_accumulate.restype = i32
+    L.hf_hessian_column.argtypes = [vp, vp, vp, vp, i32, i32, i64, vp, dp, vp]
+    L.hf_hessian_column.restype = i32
+    L.hf_column_stats.argtypes = [vp, vp, i64, C.POINTER(C.c_float), i32, i32, C.POINTER(i64), C.POINTER(C.c_float),
+                                  C.POINTER(i64), vp]
+    L.hf_column_stats.restype = i32
+    L.hf_slq_density.argtypes = [dp, dp, C.POINTER(i32), i32, i32, C.c_double, dp, i32, dp]
+    L.hf_slq_density.restype = i32
+    L.hf_slq_moments.argtypes = [dp, dp, C.POINTER(i32), i32, i32, i32, dp]
+    L.hf_slq_moments.restype = i32
     _lib = L
     return L
 
@@ -163,6 +175,40 @@ def hf_tridiag_readout(alpha, beta, want_last_row=False):
     return (ritz, w, last) if want_last_row else (ritz, w)
 
 
+def _slq_arrays(ritz, weights, m_eff):
+    r = np.ascontiguousarray(np.atleast_2d(ritz), dtype=np.float64)
+    w = np.ascontiguousarray(np.atleast_2d(weights), dtype=np.float64)
+    if r.shape != w.shape:
+        raise ValueError("ritz and weights must have the same shape")
+    me = np.ascontiguousarray(m_eff, dtype=np.int32)
+    if me.shape != (r.shape[0],):
+        raise ValueError("m_eff needs one entry per probe")
+    return r, w, me
+
+
+def hf_slq_density(ritz, weights, m_eff, sigma, grid):
+    r, w, me = _slq_arrays(ritz, weights, m_eff)
+    g = np.ascontiguousarray(grid, dtype=np.float64)
+    out = np.empty_like(g)
+    dp = C.POINTER(C.c_double)
+    rc = lib().hf_slq_density(r.ctypes.data_as(dp), w.ctypes.data_as(dp), me.ctypes.data_as(C.POINTER(C.c_int32)),
+                              r.shape[0], r.shape[1], float(sigma), g.ctypes.data_as(dp), len(g), out.ctypes.data_as(dp))
+    if rc != HF_OK:
+        raise HessformerError(rc, "hf_slq_density")
+    return out
+
+
+def hf_slq_moments(ritz, weights, m_eff, n_moments):
+    r, w, me = _slq_arrays(ritz, weights, m_eff)
+    out = np.empty(n_moments)
+    dp = C.POINTER(C.c_double)
+    rc = lib().hf_slq_moments(r.ctypes.data_as(dp), w.ctypes.data_as(dp), me.ctypes.data_as(C.POINTER(C.c_int32)),
+                              r.shape[0], r.shape[1], n_moments, out.ctypes.data_as(dp))
+    if rc != HF_OK:
+        raise HessformerError(rc, "hf_slq_moments")
+    return out
+
+
 # ---- context ----------------------------------------------------------------
 
 class Context:
@@ -201,6 +247,29 @@ class Context:
                            C.byref(loss) if want_loss else None, _stream(stream))
         self._check(rc)
         return loss.value
+
+    def hf_hvp_accumulate(self, params, inputs, labels, n_samples, micro_batch, seq, v, out, stream=None):
+        loss = C.c_double(float("nan"))
+        self._check(self.L.hf_hvp_accumulate(self.h, _ptr(params), _ptr(inputs), _ptr(labels), n_samples, micro_batch,
+                                             seq, _ptr(v), _ptr(out), C.byref(loss), _stream(stream)))
+        return loss.value
+
+    def hf_hessian_column(self, params, inputs, labels, batch, seq, index, column, stream=None):
+        loss = C.c_double(float("nan"))
+        self._check(self.L.hf_hessian_column(self.h, _ptr(params), _ptr(inputs), _ptr(labels), batch, seq, int(index),
+                                             _ptr(column), C.byref(loss), _stream(stream)))
+        return loss.value
+
+    def hf_column_stats(self, h, n, thresholds, n_bins, stream=None):
+        thr = np.ascontiguousarray(thresholds, dtype=np.float32)
+        below = np.zeros(max(len(thr), 1), dtype=np.int64)
+        hist = np.zeros(max(n_bins, 1), dtype=np.int64)
+        mx = C.c_float(0.0)
+        i64p = C.POINTER(C.c_int64)
+        self._check(self.L.hf_column_stats(self.h, _ptr(h), int(n), thr.ctypes.data_as(C.POINTER(C.c_float)), len(thr),
+                                           n_bins, below.ctypes.data_as(i64p), C.byref(mx), hist.ctypes.data_as(i64p),
+                                           _stream(stream)))
+        return below[:len(thr)], np.float32(mx.value), hist[:n_bins]
 
     def hf_lanczos_init(self, q0, reorth="none", stream=None):
         self._check(self.L.hf_lanczos_init(self.h, _ptr(q0), HF_REORTH[reorth], _stream(stream)))

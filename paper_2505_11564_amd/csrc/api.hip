@@ -187,6 +187,7 @@ void hf_destroy(hf_ctx* ctx) {
   if (!ctx) return;
   if (ctx->arena) (void)hipFree(ctx->arena);
   if (ctx->host_scal) (void)hipHostFree(ctx->host_scal);
+  if (ctx->aux_vec) (void)hipFree(ctx->aux_vec);
   delete ctx;
 }
 
@@ -323,6 +324,129 @@ int32_t hf_slq(hf_ctx* ctx, const void* params_dev, const void* inputs_dev, cons
     if (rc != HF_OK) return c->fail(rc, "hf_slq: read-out failed");
   }
   return status;
+}
+
+// ---- widened rows ---------------------------------------------------------------
+
+int32_t hf_hvp_accumulate(hf_ctx* ctx, const void* params_dev, const void* inputs_dev, const int32_t* labels_dev,
+                          int32_t n_samples, int32_t micro_batch, int32_t seq, const float* v_dev, float* out_dev,
+                          double* loss_host, void* hip_stream) {
+  if (!ctx) return HF_EINVAL;
+  hf_ctx* c = ctx;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (!params_dev || !inputs_dev || !labels_dev || !v_dev || !out_dev) return c->fail(HF_EINVAL, "hf_hvp_accumulate: NULL argument");
+  if (n_samples <= 0 || micro_batch <= 0) return c->fail(HF_EINVAL, "hf_hvp_accumulate: n_samples and micro_batch must be positive");
+  if (micro_batch > c->max_batch) return c->fail(HF_ESHAPE, "hf_hvp_accumulate: micro_batch exceeds max_batch of hf_create");
+  if (out_dev == v_dev || (const void*)out_dev == params_dev) return c->fail(HF_EINVAL, "hf_hvp_accumulate: out_dev aliases an input");
+  if ((uintptr_t)out_dev & 15) return c->fail(HF_EINVAL, "hf_hvp_accumulate: out_dev must be 16-byte aligned");
+  int rc = c->ensure_aux();
+  if (rc != HF_OK) return rc;
+  const bool mlp = c->desc.arch == HF_ARCH_MLP;
+  const int64_t in_row = mlp ? (int64_t)c->desc.mlp_in * 4 : (int64_t)seq * 4;  // bytes per sample
+  const int64_t lab_row = mlp ? 1 : seq;
+  double loss_acc = 0.0;
+  for (int b0 = 0; b0 < n_samples; b0 += micro_batch) {
+    const int b = std::min(micro_batch, n_samples - b0);
+    rc = c->hvp_enqueue(params_dev, (const char*)inputs_dev + b0 * in_row, labels_dev + b0 * lab_row, b, seq, v_dev, c->aux_vec, st);
+    if (rc != HF_OK) return rc;
+    double loss_b = 0.0;
+    rc = c->finish_hvp(&loss_b, st);
+    if (rc != HF_OK) return rc;
+    // h += u_B |B| with the final division by N folded in
+    CKI(launch_scale_add(out_dev, c->aux_vec, (float)((double)b / (double)n_samples), b0 == 0, c->n, st));
+    loss_acc += loss_b * b;
+  }
+  CKI(hipStreamSynchronize(st));
+  if (loss_host) *loss_host = loss_acc / n_samples;
+  return HF_OK;
+}
+
+int32_t hf_hessian_column(hf_ctx* ctx, const void* params_dev, const void* inputs_dev, const int32_t* labels_dev,
+                          int32_t batch, int32_t seq, int64_t index, float* column_dev, double* loss_host,
+                          void* hip_stream) {
+  if (!ctx) return HF_EINVAL;
+  hf_ctx* c = ctx;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (!column_dev) return c->fail(HF_EINVAL, "hf_hessian_column: NULL column_dev");
+  if (index < 0 || index >= c->n) return c->fail(HF_EINVAL, "hf_hessian_column: index outside [0, n)");
+  if ((const void*)column_dev == params_dev) return c->fail(HF_EINVAL, "hf_hessian_column: column_dev aliases params_dev");
+  int rc = c->ensure_aux();
+  if (rc != HF_OK) return rc;
+  CKI(launch_fill_f32(c->aux_vec, c->n, 0.f, st));
+  CKI(launch_fill_f32(c->aux_vec + index, 1, 1.f, st));
+  rc = c->hvp_enqueue(params_dev, inputs_dev, labels_dev, batch, seq, c->aux_vec, column_dev, st);
+  if (rc != HF_OK) return rc;
+  return c->finish_hvp(loss_host, st);
+}
+
+int32_t hf_column_stats(hf_ctx* ctx, const float* h_dev, int64_t n, const float* thresholds, int32_t n_thresholds,
+                        int32_t n_bins, int64_t* below, float* max_abs, int64_t* hist, void* hip_stream) {
+  if (!ctx) return HF_EINVAL;
+  hf_ctx* c = ctx;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (n < 0 || (n > 0 && !h_dev)) return c->fail(HF_EINVAL, "hf_column_stats: bad h_dev / n");
+  if ((uintptr_t)h_dev & 3) return c->fail(HF_EINVAL, "hf_column_stats: h_dev must be 4-byte aligned");
+  if (n_thresholds < 0 || n_thresholds > CS_MAX_THRESHOLDS) return c->fail(HF_EINVAL, "hf_column_stats: at most 16 thresholds");
+  if (n_bins < 1 || n_bins > CS_MAX_BINS) return c->fail(HF_EINVAL, "hf_column_stats: n_bins must be in [1, 256]");
+  if ((n_thresholds > 0 && (!thresholds || !below)) || !hist || !max_abs) return c->fail(HF_EINVAL, "hf_column_stats: NULL argument");
+  if (n >= ((int64_t)1 << 40)) return c->fail(HF_ESHAPE, "hf_column_stats: n must be below 2^40");
+  ColThresholds thr;
+  for (int k = 0; k < CS_MAX_THRESHOLDS; ++k) thr.t[k] = k < n_thresholds ? thresholds[k] : 0.f;
+  unsigned long long hs[CS_STATS_WORDS];
+  CKI(launch_fill_f32((float*)c->stats_dev, CS_STATS_WORDS * 2, 0.f, st));
+  if (n > 0) CKI(launch_colstats_pass1(h_dev, n, thr, n_thresholds, c->stats_dev, st));
+  CKI(hipMemcpyAsync(hs, c->stats_dev, 32 * 8, hipMemcpyDeviceToHost, st));
+  CKI(hipStreamSynchronize(st));
+  for (int k = 0; k < n_thresholds; ++k) below[k] = (int64_t)hs[k];
+  float mx;
+  const unsigned bits = (unsigned)hs[16];
+  memcpy(&mx, &bits, 4);
+  *max_abs = mx;
+  for (int k = 0; k < n_bins; ++k) hist[k] = 0;
+  if (!(mx > 0.f)) {
+    hist[0] = (int64_t)hs[17];  // a column of zeros: every entry in the first bin
+    return HF_OK;
+  }
+  const volatile float nbf = (float)n_bins;
+  const volatile float scale = nbf / mx;  // one float32 division, as the definition states
+  CKI(launch_colstats_hist(h_dev, n, scale, n_bins, c->stats_dev + 32, st));
+  CKI(hipMemcpyAsync(hs + 32, c->stats_dev + 32, (size_t)n_bins * 8, hipMemcpyDeviceToHost, st));
+  CKI(hipStreamSynchronize(st));
+  for (int k = 0; k < n_bins; ++k) hist[k] = (int64_t)hs[32 + k];
+  return HF_OK;
+}
+
+int32_t hf_slq_density(const double* ritz, const double* weights, const int32_t* m_eff, int32_t n_probes, int32_t m,
+                       double sigma, const double* grid, int32_t n_grid, double* density) {
+  if (!ritz || !weights || !m_eff || !grid || !density || n_probes <= 0 || m <= 0 || n_grid < 0 || !(sigma > 0.0))
+    return HF_EINVAL;
+  for (int p = 0; p < n_probes; ++p)
+    if (m_eff[p] < 0 || m_eff[p] > m) return HF_EINVAL;
+  const double norm = 1.0 / (sigma * std::sqrt(2.0 * M_PI));
+  for (int g = 0; g < n_grid; ++g) {
+    double acc = 0.0;
+    for (int p = 0; p < n_probes; ++p)
+      for (int i = 0; i < m_eff[p]; ++i) {
+        const double z = (grid[g] - ritz[(int64_t)p * m + i]) / sigma;
+        acc += weights[(int64_t)p * m + i] * std::exp(-0.5 * z * z) * norm;
+      }
+    density[g] = acc / n_probes;
+  }
+  return HF_OK;
+}
+
+int32_t hf_slq_moments(const double* ritz, const double* weights, const int32_t* m_eff, int32_t n_probes, int32_t m,
+                       int32_t n_moments, double* moments) {
+  if (!ritz || !weights || !m_eff || !moments || n_probes <= 0 || m <= 0 || n_moments < 0) return HF_EINVAL;
+  for (int p = 0; p < n_probes; ++p)
+    if (m_eff[p] < 0 || m_eff[p] > m) return HF_EINVAL;
+  for (int q = 0; q < n_moments; ++q) {
+    double acc = 0.0;
+    for (int p = 0; p < n_probes; ++p)
+      for (int i = 0; i < m_eff[p]; ++i) acc += weights[(int64_t)p * m + i] * std::pow(ritz[(int64_t)p * m + i], (double)q);
+    moments[q] = acc / n_probes;
+  }
+  return HF_OK;
 }
 
 }  // extern "C"

@@ -72,6 +72,9 @@ struct hf_ctx {
   void* xin = nullptr;  // MLP input in operand type (bf16 mode)
   int* flags = nullptr;  // [0] error bits, [1] number of valid labels
   double* loss_dev = nullptr;
+  unsigned long long* stats_dev = nullptr;  // column statistics counters
+  float* aux_vec = nullptr;  // n floats, allocated on first use (batch-loop partial result, unit vector)
+  int ensure_aux();
 
   // Lanczos state
   float* lz_vec[3] = {nullptr, nullptr, nullptr};  // rotating q, q_prev, r

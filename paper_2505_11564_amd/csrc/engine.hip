@@ -147,6 +147,7 @@ int hf_ctx::plan_and_alloc() {
   if (bf) pl.add(vb, n * 2);
   pl.add(flags, 64);
   pl.add(loss_dev, 64);
+  pl.add(stats_dev, CS_STATS_WORDS * 8);
   // Lanczos
   if (max_m > 0) {
     for (int i = 0; i < 3; ++i) pl.add(lz_vec[i], n * 4);
@@ -282,6 +283,17 @@ int hf_ctx::hvp_enqueue(const void* params, const void* inputs, const int32_t* l
   if (bf) CK(launch_f32_to_bf16(v, vb, n, st));
   if (desc.arch == HF_ARCH_MLP) return hvp_mlp(params, inputs, labels, batch, v, out, st);
   return hvp_transformer(params, (const int32_t*)inputs, labels, batch, seq, v, out, st);
+}
+
+int hf_ctx::ensure_aux() {
+  if (aux_vec) return HF_OK;
+  hipError_t e = hipMalloc((void**)&aux_vec, (size_t)n * 4);
+  if (e != hipSuccess) {
+    aux_vec = nullptr;
+    (void)hipGetLastError();
+    return fail(HF_ENOMEM, "hipMalloc of the auxiliary vector (" + std::to_string(n * 4) + " bytes) failed");
+  }
+  return HF_OK;
 }
 
 int hf_ctx::finish_hvp(double* loss_host, hipStream_t st) {

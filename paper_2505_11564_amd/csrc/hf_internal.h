@@ -78,6 +78,14 @@ hipError_t launch_gemm_dual(const Gemm& g, hipStream_t st);  // bf16, aligned op
 // Launchers take `bf` = 1 for bf16 mode (AT = PT = bf16), 0 for fp32 mode.
 
 hipError_t launch_fill_f32(float* p, int64_t n, float val, hipStream_t st);
+
+// probe.hip: batch-loop accumulation and Hessian-column statistics
+constexpr int CS_MAX_THRESHOLDS = 16, CS_MAX_BINS = 256, CS_STATS_WORDS = 32 + CS_MAX_BINS;
+struct ColThresholds { float t[CS_MAX_THRESHOLDS]; };
+hipError_t launch_scale_add(float* h, const float* u, float w, int first, int64_t n, hipStream_t st);
+hipError_t launch_colstats_pass1(const float* h, int64_t n, const ColThresholds& thr, int nt, unsigned long long* stats,
+                                 hipStream_t st);
+hipError_t launch_colstats_hist(const float* h, int64_t n, float scale, int nb, unsigned long long* hist, hipStream_t st);
 hipError_t launch_f32_to_bf16(const float* src, bf16* dst, int64_t n, hipStream_t st);
 hipError_t launch_cast_pair(int bf, const float* a, const float* b, void* oa, void* ob, int64_t n, hipStream_t st);
 

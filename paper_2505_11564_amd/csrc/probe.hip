@@ -1,0 +1,145 @@
+// Kernels of the widened rows: the weighted accumulation of the batch loop of
+// Algorithm 1 and the Hessian-column statistics of the section "Banded
+// Hessians" (counts of entries below thresholds, equal-width histogram of the
+// absolute values).  All HBM-bound streaming passes.
+#include "hf_internal.h"
+
+namespace hf {
+
+static inline int64_t cdiv64(int64_t a, int64_t b) { return (a + b - 1) / b; }
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+// h <- w u (first batch) or h <- h + w u: the step "h += u |B|" with the
+// division by N folded into w = |B| / N.
+__global__ void scale_add_kernel(float* __restrict__ h, const float* __restrict__ u, float w, int first, int64_t n) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  const int64_t n4 = n >> 2;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
+    const float4 x = ((const float4*)u)[i];
+    float4 y = first ? make_float4(0.f, 0.f, 0.f, 0.f) : ((const float4*)h)[i];
+    y.x += w * x.x; y.y += w * x.y; y.z += w * x.z; y.w += w * x.w;
+    ((float4*)h)[i] = y;
+  }
+  for (int64_t i = (n4 << 2) + (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride)
+    h[i] = (first ? 0.f : h[i]) + w * u[i];
+}
+hipError_t launch_scale_add(float* h, const float* u, float w, int first, int64_t n, hipStream_t st) {
+  if (n <= 0) return hipSuccess;
+  if (((uintptr_t)h | (uintptr_t)u) & 15) return hipErrorInvalidValue;
+  const int blocks = (int)std::min<int64_t>(cdiv64(n, 1024), 4096);
+  hipLaunchKernelGGL(scale_add_kernel, dim3(blocks), dim3(256), 0, st, h, u, w, first, n);
+  return hipGetLastError();
+}
+
+// ---- column statistics --------------------------------------------------------
+// stats (uint64): [0, 16) counts below each threshold; [16] bit pattern of the
+// largest |h_i| (non-negative floats order like their bit patterns); [17] number
+// of entries that are not NaN; [32, 32 + n_bins) histogram.
+
+__device__ __forceinline__ unsigned wave_sum_u32(unsigned v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
+  return v;
+}
+
+__global__ __launch_bounds__(256) void colstats_pass1_kernel(const float* __restrict__ h, int64_t n, ColThresholds thr,
+                                                            int nt, unsigned long long* stats) {
+  __shared__ unsigned red[4][CS_MAX_THRESHOLDS + 1];
+  __shared__ float redm[4];
+  unsigned cnt[CS_MAX_THRESHOLDS];
+#pragma unroll
+  for (int k = 0; k < CS_MAX_THRESHOLDS; ++k) cnt[k] = 0;
+  unsigned valid = 0;
+  float mx = 0.f;
+  auto take = [&](float x) {
+    const float a = fabsf(x);
+    if (a == a) { ++valid; mx = fmaxf(mx, a); }
+#pragma unroll
+    for (int k = 0; k < CS_MAX_THRESHOLDS; ++k)
+      if (k < nt && a < thr.t[k]) ++cnt[k];
+  };
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  // scalar head up to the first 16-byte boundary, vector body, scalar tail
+  const int64_t head = std::min<int64_t>(n, (int64_t)((16 - ((uintptr_t)h & 15)) & 15) / 4);
+  const int64_t n4 = (n - head) >> 2;
+  if (gid < head) take(h[gid]);
+  const f32x4_t* h4 = (const f32x4_t*)(h + head);
+  for (int64_t i = gid; i < n4; i += stride) {
+    const f32x4_t x = __builtin_nontemporal_load(h4 + i);
+    take(x.x); take(x.y); take(x.z); take(x.w);
+  }
+  for (int64_t i = head + (n4 << 2) + gid; i < n; i += stride) take(h[i]);
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int k = 0; k < CS_MAX_THRESHOLDS; ++k) {
+    const unsigned s = wave_sum_u32(cnt[k]);
+    if (lane == 0) red[wave][k] = s;
+  }
+  {
+    const unsigned s = wave_sum_u32(valid);
+    if (lane == 0) red[wave][CS_MAX_THRESHOLDS] = s;
+    float m = mx;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_down(m, o, 64));
+    if (lane == 0) redm[wave] = m;
+  }
+  __syncthreads();
+  if (threadIdx.x <= CS_MAX_THRESHOLDS) {
+    const unsigned long long s = (unsigned long long)red[0][threadIdx.x] + red[1][threadIdx.x] + red[2][threadIdx.x] + red[3][threadIdx.x];
+    if (s) atomicAdd(stats + (threadIdx.x < CS_MAX_THRESHOLDS ? threadIdx.x : 17), s);
+  }
+  if (threadIdx.x == 0) {
+    const float m = fmaxf(fmaxf(redm[0], redm[1]), fmaxf(redm[2], redm[3]));
+    atomicMax((unsigned*)(stats + 16), __float_as_uint(m));
+  }
+}
+
+// Bin of |h_i|: floor(|h_i| * scale), scale = n_bins / max as a float32
+// quotient formed on the host; the maximum itself (and a product that is not a
+// number, which needs an infinite maximum) lands in the last bin.
+__global__ __launch_bounds__(256) void colstats_hist_kernel(const float* __restrict__ h, int64_t n, float scale, int nb,
+                                                           unsigned long long* hist) {
+  __shared__ unsigned lh[CS_MAX_BINS];
+  for (int i = threadIdx.x; i < nb; i += 256) lh[i] = 0;
+  __syncthreads();
+  auto take = [&](float x) {
+    const float a = fabsf(x);
+    if (a == a) {
+      const float s = __fmul_rn(a, scale);
+      int b = (s == s) ? (int)fminf(floorf(s), (float)(nb - 1)) : nb - 1;
+      atomicAdd(&lh[b], 1u);
+    }
+  };
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t head = std::min<int64_t>(n, (int64_t)((16 - ((uintptr_t)h & 15)) & 15) / 4);
+  const int64_t n4 = (n - head) >> 2;
+  if (gid < head) take(h[gid]);
+  const f32x4_t* h4 = (const f32x4_t*)(h + head);
+  for (int64_t i = gid; i < n4; i += stride) {
+    const f32x4_t x = __builtin_nontemporal_load(h4 + i);
+    take(x.x); take(x.y); take(x.z); take(x.w);
+  }
+  for (int64_t i = head + (n4 << 2) + gid; i < n; i += stride) take(h[i]);
+  __syncthreads();
+  for (int i = threadIdx.x; i < nb; i += 256)
+    if (lh[i]) atomicAdd(hist + i, (unsigned long long)lh[i]);
+}
+
+// Each thread sees at most n / (blocks * 256) + 4 elements, so 32-bit per-thread
+// and per-block counters cannot overflow for n < 2^40 with these grids.
+static inline int colstats_blocks(int64_t n) { return (int)std::max<int64_t>(1, std::min<int64_t>(cdiv64(n, 4096), 2048)); }
+
+hipError_t launch_colstats_pass1(const float* h, int64_t n, const ColThresholds& thr, int nt, unsigned long long* stats,
+                                 hipStream_t st) {
+  hipLaunchKernelGGL(colstats_pass1_kernel, dim3(colstats_blocks(n)), dim3(256), 0, st, h, n, thr, nt, stats);
+  return hipGetLastError();
+}
+hipError_t launch_colstats_hist(const float* h, int64_t n, float scale, int nb, unsigned long long* hist, hipStream_t st) {
+  hipLaunchKernelGGL(colstats_hist_kernel, dim3(colstats_blocks(n)), dim3(256), 0, st, h, n, scale, nb, hist);
+  return hipGetLastError();
+}
+
+}  // namespace hf

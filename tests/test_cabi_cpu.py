@@ -101,3 +101,23 @@ def test_readout_and_create_argument_errors():
     assert L.hf_lanczos_iterations(None) == binding.HF_EINVAL
     assert L.hf_hvp(None, None, None, None, 1, 1, None, None, None, None) == binding.HF_EINVAL
     L.hf_destroy(None)
+
+
+def test_density_and_moments_match_oracle():
+    from oracle import density
+    rng = np.random.default_rng(3)
+    P, m = 3, 7
+    ritz = np.sort(rng.standard_normal((P, m)) * 2.0, axis=1)
+    w = rng.random((P, m))
+    m_eff = np.array([7, 5, 1], dtype=np.int32)
+    for p in range(P):
+        w[p, :m_eff[p]] /= w[p, :m_eff[p]].sum()
+    grid = np.linspace(-8.0, 8.0, 401)
+    got = hf.hf_slq_density(ritz, w, m_eff, 0.25, grid)
+    np.testing.assert_allclose(got, density.smoothed_density(ritz, w, m_eff, 0.25, grid), rtol=1e-12, atol=1e-300)
+    got = hf.hf_slq_moments(ritz, w, m_eff, 4)
+    np.testing.assert_allclose(got, density.moments(ritz, w, m_eff, 4), rtol=1e-12)
+    with pytest.raises(hf.HessformerError):
+        hf.hf_slq_density(ritz, w, m_eff, 0.0, grid)
+    with pytest.raises(hf.HessformerError):
+        hf.hf_slq_moments(ritz, w, np.array([8, 1, 1], dtype=np.int32), 2)
