@@ -133,6 +133,11 @@ int hf_ctx::plan_and_alloc() {
     pl.add(dz, T * ldz * e); pl.add(dz_t, T * ldz * e);
     pl.add(loss_rows, T * 4);
     pl.add(sc, SS * 4); pl.add(sc_t, SS * 4);
+    att_SS = SS;
+    if (bf) {
+      const int64_t rows = SS / desc.max_seq, np = (desc.max_seq + 63) / 64;  // B*H*S rows
+      pl.add(att_part, rows * np * 3 * 4); pl.add(att_rstat, rows * 3 * 4);
+    }
     pl.add(dS, SS * e); pl.add(dS_t, SS * e);
     pl.add(dx, T * D * 4); pl.add(dx_t, T * D * 4); pl.add(tmpd, T * D * 4); pl.add(tmpd_t, T * D * 4);
     if (bf) { pl.add(dxb, T * D * e); pl.add(dxb_t, T * D * e); }
@@ -359,6 +364,24 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
   auto set_sc = [&](int64_t& s1, int64_t& s2) { s1 = (int64_t)H * SS; s2 = SS; };
   auto set_td = [&](int64_t& s1, int64_t& s2) { s1 = (int64_t)S * D; s2 = dh; };
 
+  // Fused attention epilogues (bf16 operands, 16-byte aligned rows).  The fused
+  // kernels write only the score tiles on and below the diagonal; tiles above it
+  // are read as zeros by products that run with larger tiles, so they are
+  // cleared whenever the [B,H,S,S] layout changes.
+  static const bool no_fused = std::getenv("HF_NO_FUSED_ATT") != nullptr;
+  const bool fused_att = bf && !no_fused && D % 8 == 0 && dh % 32 == 0 && S % 8 == 0;
+  if (fused_att && (att_zero_B != B || att_zero_S != S)) {
+    const int64_t words = (int64_t)B * H * SS / 2;  // bf16 pairs
+    for (auto& b : lb) {
+      CK(launch_fill_f32((float*)b.P, words, 0.f, st));
+      CK(launch_fill_f32((float*)b.P_t, words, 0.f, st));
+    }
+    CK(launch_fill_f32((float*)P_lo, words, 0.f, st));
+    CK(launch_fill_f32((float*)dS, words, 0.f, st));
+    CK(launch_fill_f32((float*)dS_t, words, 0.f, st));
+    att_zero_B = B; att_zero_S = S;
+  }
+
   // ------------------------------ forward with tangents ----------------------
   CK(launch_embed_fwd(bf, L.Wp(off_wte), llama ? nullptr : L.Wp(off_wpe), v + off_wte, llama ? nullptr : v + off_wpe,
                       tok, T, S, D, V, lb[0].x1, lb[0].x1_t, flags, st));
@@ -381,6 +404,24 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
                       qkv_lo ? at(qkv_lo, 2 * D) : nullptr))) return rc;
       CK(launch_rope(bf, rq, rq_t, 2 * D, b.qkv, b.qkv_t, qkv_lo, 3 * D, T, S, 2 * H, dh, desc.rope_theta, 0, st));
     }
+    if (fused_att) {
+      // scores without a trip through memory: the product is formed twice by the
+      // dual-output kernel, first to reduce (max, sum, tangent sum) per row over
+      // 64-column parts, then to write P, P_lo, P_t with the combined statistics
+      Gemm g; att(g);
+      g.M = S; g.N = S; g.K = dh; g.lda = 3 * D; g.ldb = 3 * D; g.ldc = S; g.transB = 1; g.alpha = cs; g.skip_upper = 1;
+      set_qkv(g.sA1, g.sA2); set_qkv(g.sB1, g.sB2); set_sc(g.sC1, g.sC2);
+      g.A[0] = b.qkv; g.B[0] = cat(b.qkv, D);
+      g.A[1] = qkv_lo; g.B[1] = cat(b.qkv, D);
+      g.A[2] = b.qkv; g.B[2] = cat(qkv_lo, D);
+      g.At = b.qkv_t; g.Bt = cat(b.qkv_t, D);
+      g.C = b.P; g.Ct = b.P_t; g.out_bf16 = 1;
+      g.epi = EPI_FWD_STATS; g.part = att_part;
+      CK(launch_gemm(g, st));
+      CK(launch_attn_combine(0, att_part, (S + 63) / 64, S, (int64_t)B * H * S, att_rstat, st));
+      g.epi = EPI_FWD_SOFTMAX; g.part = nullptr; g.rstat = att_rstat; g.C_lo = P_lo;
+      CK(launch_gemm(g, st));
+    } else {
     {  // scores S = c Q K^T, S_t = c (Q_t K^T + Q K_t^T); lower-triangular tiles only
       Gemm g; att(g);
       g.M = S; g.N = S; g.K = dh; g.lda = 3 * D; g.ldb = 3 * D; g.ldc = S; g.transB = 1; g.alpha = cs; g.skip_upper = 1;
@@ -394,6 +435,7 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
       CK(launch_gemm(g, st));
     }
     CK(launch_softmax_fwd(bf, sc, sc_t, b.P, b.P_t, P_lo, B * H, S, st));
+    }
     {  // O = P V, O_t = P_t V + P V_t
       Gemm g; att(g);
       g.M = S; g.N = dh; g.K = S; g.lda = S; g.ldb = 3 * D; g.ldc = D; g.klimit = 1; g.out_bf16 = bf;
@@ -483,6 +525,21 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
       g.At = b.P_t; g.Bt = dob_t; g.Ct = at(dqkv_t, 2 * D);
       CK(launch_gemm(g, st));
     }
+    if (fused_att) {
+      // dP = dO V^T and its tangent, reduced to (delta, delta_t) per row on the
+      // first pass and turned into dS, dS_t on the second; dP never reaches memory
+      Gemm g; att(g);
+      g.M = S; g.N = S; g.K = dh; g.lda = D; g.ldb = 3 * D; g.ldc = S; g.transB = 1; g.skip_upper = 1;
+      set_td(g.sA1, g.sA2); set_qkv(g.sB1, g.sB2); set_sc(g.sC1, g.sC2);
+      g.A[0] = dob; g.B[0] = cat(b.qkv, 2 * D);
+      g.At = dob_t; g.Bt = cat(b.qkv_t, 2 * D);
+      g.C = dS; g.Ct = dS_t; g.out_bf16 = 1; g.E0 = b.P; g.E1 = b.P_t;
+      g.epi = EPI_BWD_STATS; g.part = att_part;
+      CK(launch_gemm(g, st));
+      CK(launch_attn_combine(1, att_part, (S + 63) / 64, S, (int64_t)B * H * S, att_rstat, st));
+      g.epi = EPI_BWD_DS; g.part = nullptr; g.rstat = att_rstat;
+      CK(launch_gemm(g, st));
+    } else {
     {  // dP = dO V^T, dP_t = dO_t V^T + dO V_t^T
       Gemm g; att(g);
       g.M = S; g.N = S; g.K = dh; g.lda = D; g.ldb = 3 * D; g.ldc = S; g.transB = 1; g.skip_upper = 1;
@@ -492,6 +549,7 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
       CK(launch_gemm(g, st));
     }
     CK(launch_softmax_bwd(bf, b.P, b.P_t, sc, sc_t, dS, dS_t, B * H, S, st));
+    }
     {  // dQ = c dS K, dQ_t = c (dS_t K + dS K_t)
       Gemm g; att(g);
       g.M = S; g.N = dh; g.K = S; g.lda = S; g.ldb = 3 * D; g.ldc = 3 * D; g.klimit = 1; g.alpha = cs; g.out_bf16 = bf;

@@ -300,7 +300,8 @@ hipError_t launch_gemm(const Gemm& g, hipStream_t st) {
   // the GPU (fewer than ~256 tiles of 128 x 128); larger products run faster
   // as two launches with their own tile shapes.
   const int64_t tiles128 = ((int64_t)(g.M + 127) / 128) * ((g.N + 127) / 128) * g.nb1 * g.nb2;
-  if (g.in_bf16 && !no_dual && g.M >= 8 && g.N >= 8 && tiles128 < 256) {
+  if (g.epi != EPI_NONE && !g.in_bf16) return hipErrorInvalidValue;
+  if (g.in_bf16 && g.M >= 8 && g.N >= 8 && (g.epi != EPI_NONE || (!no_dual && tiles128 < 256))) {
     auto ok = [&](const void* x, int64_t ld, int64_t s1, int64_t s2, int rows_contig, int R) {
       return ((uintptr_t)x % 16) == 0 && ld % 8 == 0 && s1 % 8 == 0 && s2 % 8 == 0 && (!rows_contig || ld >= ((R + 7) / 8) * 8);
     };
@@ -313,6 +314,7 @@ hipError_t launch_gemm(const Gemm& g, hipStream_t st) {
       if (e != hipErrorNotSupported) return e;
     }
   }
+  if (g.epi != EPI_NONE) return hipErrorNotSupported;  // the caller takes the unfused path
   Gemm p = g;
   p.At = nullptr; p.Bt = nullptr; p.Ct = nullptr; p.Cadd_t = nullptr; p.bias_t = nullptr;
   hipError_t e = launch_gemm_single(p, st);

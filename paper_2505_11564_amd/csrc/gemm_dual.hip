@@ -31,11 +31,20 @@ struct DualP {
   float alpha;
   int out_bf16, bias_bf16;
   int klimit, skip_upper;
+  int epi;             // attention epilogue (EPI_* of hf_internal.h)
+  int vec;             // C, Ct, Clo, E0, E1, Cadd, Cadd_t rows allow 16-byte accesses
+  int NP;              // parts per row of `part`
+  float* part;
+  const float* rstat;
+  const void *E0, *E1;
 };
 
 // NT: operand tiles per stage: 4 (A, A_t, B, B_t), 5 (+ A_lo) or 6 (+ A_lo, B_lo).
-template <bool TA, bool TB, int NT>
-__global__ __launch_bounds__(256) void gemm_dual_kernel(DualP p) {
+// NS: LDS stages (slabs in flight + 1).  The attention products have a k of one
+// head dimension (2-4 slabs), so their variants keep every slab in flight.
+// EPI: epilogue (EPI_* of hf_internal.h), compile-time.
+template <bool TA, bool TB, int NT, int NS, int EPI>
+__global__ __launch_bounds__(256, (EPI != EPI_NONE && NT == 4 && NS == 2 ? 2 : 1)) void gemm_dual_kernel(DualP p) {
   constexpr int BM = 128, BN = 128, KT = 32;
   constexpr int TILE = 128 * KT;  // elements per operand tile
   constexpr bool AKC = !TA, BKC = TB;
@@ -181,21 +190,92 @@ __global__ __launch_bounds__(256) void gemm_dual_kernel(DualP p) {
     });
   };
 
-  // two LDS stages: the loads of slab i+1 fly while slab i is multiplied
-  if (nfull > 0) issue(0);
-  for (int i0 = 0; i0 < nfull; i0 += 2) {
-    static_for<2>([&](auto s_c) {
+  // NS LDS stages: iteration i waits for slab i, passes one barrier (every wave
+  // is then done with slab i-1), issues slab i+NS-1 into the stage just freed
+  // and multiplies slab i.
+  constexpr int NLOAD = NT * NI;
+#pragma unroll
+  for (int s0 = 0; s0 < NS - 1; ++s0)
+    if (s0 < nfull) issue(s0);
+  for (int i0 = 0; i0 < nfull; i0 += NS) {
+    static_for<NS>([&](auto s_c) {
       constexpr int s = decltype(s_c)::value;
       const int i = i0 + s;
       if (i < nfull) {
-        HF_WAIT_VMCNT(0);
+        const int later = min(NS - 2, nfull - 1 - i);  // slabs issued after slab i so far
+        if (later >= 2) HF_WAIT_VMCNT(2 * NLOAD);
+        else if (later == 1) HF_WAIT_VMCNT(NLOAD);
+        else HF_WAIT_VMCNT(0);
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
-        if (i + 1 < nfull) issue(s ^ 1);
+        if (i + NS - 1 < nfull) issue((s + NS - 1) % NS);
         compute(s_c);
         __builtin_amdgcn_sched_barrier(0);
       }
     });
+  }
+  if constexpr (EPI != EPI_NONE && NT == 4) {
+    // Low-order primal terms A_lo B and A B_lo (forward scores) as further
+    // k-slabs of two operand tiles each, through the same two stages: the
+    // kernel stays at four tiles per stage and two resident blocks per CU.
+    static_assert(NS == 2, "the low-order loops assume two stages");
+    auto lo_loop = [&](const void* Ax, const void* Bx) {
+      int64_t cA = a0, cB = b0;
+      auto issue_lo = [&](int stage) {
+        HF_LDS char* st = smem_c + (int64_t)stage * stage_el * 2 + wave_off;
+        slab_issue<NI>((const char*)Ax + cA, voffA, st + sA * 2);
+        slab_issue<NI>((const char*)Bx + cB, voffB, st + sB * 2);
+        cA += stepA;
+        cB += stepB;
+      };
+      auto compute_lo = [&](auto stage_c) {
+        constexpr int S = decltype(stage_c)::value;
+        Frag<AKC> a[2][2];
+        Frag<BKC> b[2][2];
+        auto request = [&](auto kk_c) {
+          constexpr int kk = decltype(kk_c)::value;
+          constexpr int offA = S * stage_el * 2 + (AKC ? 0 : kk * 16 * BM * 2);
+          constexpr int offB = S * stage_el * 2 + (BKC ? 0 : kk * 16 * BN * 2);
+#pragma unroll
+          for (int i = 0; i < 2; ++i) a[kk & 1][i].template read<offA + sA * 2, 4 * BM * 2>(adA[AKC ? kk : 0][i]);
+#pragma unroll
+          for (int j = 0; j < 2; ++j) b[kk & 1][j].template read<offB + sB * 2, 4 * BN * 2>(adB[BKC ? kk : 0][j]);
+        };
+        request(std::integral_constant<int, 0>{});
+        static_for<NKK>([&](auto kk_c) {
+          constexpr int kk = decltype(kk_c)::value, c = kk & 1;
+          __builtin_amdgcn_sched_barrier(0);
+          lds_wait_all();
+#pragma unroll
+          for (int i = 0; i < 2; ++i) { a[c][i].tie(); b[c][i].tie(); }
+          if constexpr (kk + 1 < NKK) request(std::integral_constant<int, kk + 1>{});
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+              accp[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[c][i].get(), b[c][j].get(), accp[i][j], 0, 0, 0);
+        });
+      };
+      __builtin_amdgcn_s_barrier();  // every wave is done with both stages
+      if (nfull > 0) issue_lo(0);
+      for (int i0 = 0; i0 < nfull; i0 += 2) {
+        static_for<2>([&](auto s_c) {
+          constexpr int s = decltype(s_c)::value;
+          const int i = i0 + s;
+          if (i < nfull) {
+            HF_WAIT_VMCNT(0);
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+            if (i + 1 < nfull) issue_lo(s ^ 1);
+            compute_lo(s_c);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        });
+      }
+    };
+    if (p.Alo) lo_loop(p.Alo, p.B);
+    if (p.Blo) lo_loop(p.A, p.Blo);
   }
   if (ktail > 0) {
     const int k0 = kbeg + nfull * KT;
@@ -211,44 +291,227 @@ __global__ __launch_bounds__(256) void gemm_dual_kernel(DualP p) {
     compute(std::integral_constant<int, 0>{});
   }
 
-  // epilogue: lane holds column (lane & 31), rows 8*(r/4) + 4*(lane/32) + r%4
+  // ---- epilogue -------------------------------------------------------------
+  // An accumulator tile holds, per lane, column (lane & 31) and rows
+  // 8*(r/4) + 4*(lane/32) + r%4.  Each wave stages 32 rows x 64 columns of both
+  // results in LDS and walks them row-wise, 8 consecutive columns per lane (8
+  // lanes per row), so that memory is touched 16 bytes at a time and the row
+  // reductions of the attention epilogues are three cross-lane steps.
+  constexpr int LDW = 64 + 4;
+  HF_LDS float* stgP = (HF_LDS float*)smem + wave * (2 * 32 * LDW);
+  HF_LDS float* stgT = stgP + 32 * LDW;
+  float bp[2], bt[2];
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
     const int gn = n0 + wn0 + j * 32 + (lane & 31);
-    if (gn >= p.N) continue;
-    float bp = 0.f, bt = 0.f;
-    if (p.bias) bp = p.bias_bf16 ? (float)((const bf16*)p.bias)[gn] : ((const float*)p.bias)[gn];
-    if (p.bias_t) bt = p.bias_t[gn];
+    bp[j] = 0.f; bt[j] = 0.f;
+    if (gn < p.N) {
+      if (p.bias) bp[j] = p.bias_bf16 ? (float)((const bf16*)p.bias)[gn] : ((const float*)p.bias)[gn];
+      if (p.bias_t) bt[j] = p.bias_t[gn];
+    }
+  }
+  constexpr int epi = EPI;
+  const bool causal = p.skip_upper != 0;
+  const int64_t zrow0 = (int64_t)z * p.M;
+  auto xor8_sum = [](float v) { v += __shfl_xor(v, 1, 64); v += __shfl_xor(v, 2, 64); v += __shfl_xor(v, 4, 64); return v; };
+  auto xor8_max = [](float v) {
+    v = fmaxf(v, __shfl_xor(v, 1, 64)); v = fmaxf(v, __shfl_xor(v, 2, 64)); v = fmaxf(v, __shfl_xor(v, 4, 64));
+    return v;
+  };
+  auto store8_bf16 = [&](void* X, int64_t ci, int gn, const float (&v)[8]) {
+    if (p.vec && gn + 8 <= p.N) {
+      bf16 o[8];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+      for (int q = 0; q < 8; ++q) o[q] = (bf16)v[q];
+      *(uint4*)((bf16*)X + ci) = *(const uint4*)o;
+    } else {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int gm = m0 + wm0 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-        if (gm >= p.M) continue;
-        const int64_t ci = offC + (int64_t)gm * p.ldc + gn;
-        float vp = p.alpha * accp[i][j][r] + bp;
-        float vt = p.alpha * acct[i][j][r] + bt;
-        if (p.Cadd) vp += p.Cadd[ci];
-        if (p.Cadd_t) vt += p.Cadd_t[ci];
-        if (p.out_bf16) {
-          const bf16 hi = (bf16)vp;
-          ((bf16*)p.C)[ci] = hi;
-          if (p.Clo) ((bf16*)p.Clo)[ci] = (bf16)(vp - (float)hi);
-          ((bf16*)p.Ct)[ci] = (bf16)vt;
-        } else {
-          ((float*)p.C)[ci] = vp;
-          ((float*)p.Ct)[ci] = vt;
+      for (int q = 0; q < 8; ++q)
+        if (gn + q < p.N) ((bf16*)X)[ci + q] = (bf16)v[q];
+    }
+  };
+  // Inputs of the attention epilogues (row statistics, P and P_t), requested
+  // together before the staging so that one round trip covers all of them.  Epilogue pass (i, ps) of a lane
+  // covers row m0 + wm0 + 32 i + 8 ps + lane/8, columns n0 + wn0 + 8 (lane%8) .. +7.
+  // These variants require 16-byte aligned rows and N % 8 == 0 (checked by the
+  // launcher), so a lane's 8 columns are valid together.
+  constexpr bool kNeedStat = EPI == EPI_FWD_SOFTMAX || EPI == EPI_BWD_DS;
+  constexpr bool kNeedP = EPI == EPI_BWD_STATS || EPI == EPI_BWD_DS;
+  float pre_s[kNeedStat ? 8 : 1][3];
+  uint4 pre_p[kNeedP ? 8 : 1], pre_pt[kNeedP ? 8 : 1];
+  if constexpr (kNeedStat || kNeedP) {
+    const int64_t zr = (int64_t)z * p.M;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int gm = m0 + wm0 + (e >> 2) * 32 + (e & 3) * 8 + (lane >> 3), gn = n0 + wn0 + (lane & 7) * 8;
+      if constexpr (kNeedStat) {
+        pre_s[e][0] = 0.f; pre_s[e][1] = 0.f; pre_s[e][2] = 0.f;
+        if (gm < p.M) {
+          const float* rs = p.rstat + (zr + gm) * 3;
+          pre_s[e][0] = rs[0]; pre_s[e][1] = rs[1];
+          if (EPI == EPI_FWD_SOFTMAX) pre_s[e][2] = rs[2];
+        }
+      }
+      if constexpr (kNeedP) {
+        pre_p[e] = make_uint4(0, 0, 0, 0); pre_pt[e] = pre_p[e];
+        if (gm < p.M && gn < p.N) {
+          const int64_t ci = offC + (int64_t)gm * p.ldc + gn;
+          pre_p[e] = *(const uint4*)((const bf16*)p.E0 + ci);
+          pre_pt[e] = *(const uint4*)((const bf16*)p.E1 + ci);
         }
       }
     }
   }
+
+  __syncthreads();  // every wave is done reading operand tiles
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int idx = ((r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * LDW + j * 32 + (lane & 31);
+        stgP[idx] = p.alpha * accp[i][j][r] + bp[j];
+        stgT[idx] = p.alpha * acct[i][j][r] + bt[j];
+      }
+    __syncthreads();
+#pragma unroll
+    for (int ps = 0; ps < 4; ++ps) {
+      const int row = ps * 8 + (lane >> 3), ch = lane & 7;
+      const int gm = m0 + wm0 + i * 32 + row, gn = n0 + wn0 + ch * 8;
+      const bool rowok = gm < p.M;
+      typedef float f32x4_t __attribute__((ext_vector_type(4)));
+      float vp[8], vt[8];
+      {
+        const f32x4_t a0 = *(const HF_LDS f32x4_t*)(stgP + row * LDW + ch * 8), a1 = *(const HF_LDS f32x4_t*)(stgP + row * LDW + ch * 8 + 4);
+        const f32x4_t b0 = *(const HF_LDS f32x4_t*)(stgT + row * LDW + ch * 8), b1 = *(const HF_LDS f32x4_t*)(stgT + row * LDW + ch * 8 + 4);
+        vp[0] = a0.x; vp[1] = a0.y; vp[2] = a0.z; vp[3] = a0.w; vp[4] = a1.x; vp[5] = a1.y; vp[6] = a1.z; vp[7] = a1.w;
+        vt[0] = b0.x; vt[1] = b0.y; vt[2] = b0.z; vt[3] = b0.w; vt[4] = b1.x; vt[5] = b1.y; vt[6] = b1.z; vt[7] = b1.w;
+      }
+      const int64_t ci = offC + (int64_t)gm * p.ldc + gn;
+      bool ok[8];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) ok[q] = rowok && gn + q < p.N && (!causal || gn + q <= gm);
+      if constexpr (epi == EPI_NONE) {
+        if (!rowok || gn >= p.N) continue;
+        if (p.vec && gn + 8 <= p.N) {
+          if (p.Cadd) {
+            const float4 c0 = *(const float4*)(p.Cadd + ci), c1 = *(const float4*)(p.Cadd + ci + 4);
+            vp[0] += c0.x; vp[1] += c0.y; vp[2] += c0.z; vp[3] += c0.w; vp[4] += c1.x; vp[5] += c1.y; vp[6] += c1.z; vp[7] += c1.w;
+          }
+          if (p.Cadd_t) {
+            const float4 c0 = *(const float4*)(p.Cadd_t + ci), c1 = *(const float4*)(p.Cadd_t + ci + 4);
+            vt[0] += c0.x; vt[1] += c0.y; vt[2] += c0.z; vt[3] += c0.w; vt[4] += c1.x; vt[5] += c1.y; vt[6] += c1.z; vt[7] += c1.w;
+          }
+          if (p.out_bf16) {
+            store8_bf16(p.C, ci, gn, vp);
+            if (p.Clo) {
+              float lo[8];
+#pragma unroll
+              for (int q = 0; q < 8; ++q) lo[q] = vp[q] - (float)(bf16)vp[q];
+              store8_bf16(p.Clo, ci, gn, lo);
+            }
+            store8_bf16(p.Ct, ci, gn, vt);
+          } else {
+            *(float4*)((float*)p.C + ci) = make_float4(vp[0], vp[1], vp[2], vp[3]);
+            *(float4*)((float*)p.C + ci + 4) = make_float4(vp[4], vp[5], vp[6], vp[7]);
+            *(float4*)((float*)p.Ct + ci) = make_float4(vt[0], vt[1], vt[2], vt[3]);
+            *(float4*)((float*)p.Ct + ci + 4) = make_float4(vt[4], vt[5], vt[6], vt[7]);
+          }
+        } else {
+          for (int q = 0; q < 8; ++q) {
+            if (gn + q >= p.N) break;
+            float x = vp[q], xt = vt[q];
+            if (p.Cadd) x += p.Cadd[ci + q];
+            if (p.Cadd_t) xt += p.Cadd_t[ci + q];
+            if (p.out_bf16) {
+              const bf16 hi = (bf16)x;
+              ((bf16*)p.C)[ci + q] = hi;
+              if (p.Clo) ((bf16*)p.Clo)[ci + q] = (bf16)(x - (float)hi);
+              ((bf16*)p.Ct)[ci + q] = (bf16)xt;
+            } else {
+              ((float*)p.C)[ci + q] = x;
+              ((float*)p.Ct)[ci + q] = xt;
+            }
+          }
+        }
+      } else if constexpr (epi == EPI_FWD_STATS) {
+        float m = -INFINITY;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) if (ok[q]) m = fmaxf(m, vp[q]);
+        m = xor8_max(m);
+        float l = 0.f, rr = 0.f;
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+          if (ok[q]) { const float e = __expf(vp[q] - m); l += e; rr += e * vt[q]; }
+        l = xor8_sum(l);
+        rr = xor8_sum(rr);
+        if (ch == 0 && rowok && n0 + wn0 < p.N) {
+          float* dst = p.part + ((zrow0 + gm) * p.NP + (n0 + wn0) / 64) * 3;
+          dst[0] = m; dst[1] = l; dst[2] = rr;
+        }
+      } else if constexpr (epi == EPI_FWD_SOFTMAX) {
+        const float m = pre_s[i * 4 + ps][0], inv = pre_s[i * 4 + ps][1], rbar = pre_s[i * 4 + ps][2];
+        if (!rowok || gn >= p.N) continue;
+        float P[8], Pl[8], Pt[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+          P[q] = ok[q] ? __expf(vp[q] - m) * inv : 0.f;
+          Pt[q] = ok[q] ? P[q] * (vt[q] - rbar) : 0.f;
+          Pl[q] = P[q] - (float)(bf16)P[q];
+        }
+        store8_bf16(p.C, ci, gn, P);
+        if (p.Clo) store8_bf16(p.Clo, ci, gn, Pl);
+        store8_bf16(p.Ct, ci, gn, Pt);
+      } else {
+        float P[8], Pt[8];
+        {
+          const uint4 u = pre_p[kNeedP ? i * 4 + ps : 0], w = pre_pt[kNeedP ? i * 4 + ps : 0];
+          P[0] = __uint_as_float(u.x << 16); P[1] = __uint_as_float(u.x & 0xffff0000u);
+          P[2] = __uint_as_float(u.y << 16); P[3] = __uint_as_float(u.y & 0xffff0000u);
+          P[4] = __uint_as_float(u.z << 16); P[5] = __uint_as_float(u.z & 0xffff0000u);
+          P[6] = __uint_as_float(u.w << 16); P[7] = __uint_as_float(u.w & 0xffff0000u);
+          Pt[0] = __uint_as_float(w.x << 16); Pt[1] = __uint_as_float(w.x & 0xffff0000u);
+          Pt[2] = __uint_as_float(w.y << 16); Pt[3] = __uint_as_float(w.y & 0xffff0000u);
+          Pt[4] = __uint_as_float(w.z << 16); Pt[5] = __uint_as_float(w.z & 0xffff0000u);
+          Pt[6] = __uint_as_float(w.w << 16); Pt[7] = __uint_as_float(w.w & 0xffff0000u);
+        }
+        if constexpr (epi == EPI_BWD_STATS) {
+          float d = 0.f, dt = 0.f;
+#pragma unroll
+          for (int q = 0; q < 8; ++q)
+            if (ok[q]) { d += P[q] * vp[q]; dt += Pt[q] * vp[q] + P[q] * vt[q]; }
+          d = xor8_sum(d);
+          dt = xor8_sum(dt);
+          if (ch == 0 && rowok && n0 + wn0 < p.N) {
+            float* dst = p.part + ((zrow0 + gm) * p.NP + (n0 + wn0) / 64) * 3;
+            dst[0] = d; dst[1] = dt; dst[2] = 0.f;
+          }
+        } else {  // EPI_BWD_DS
+          const float d = pre_s[kNeedStat ? i * 4 + ps : 0][0], dt = pre_s[kNeedStat ? i * 4 + ps : 0][1];
+          if (!rowok || gn >= p.N) continue;
+          float dS[8], dSt[8];
+#pragma unroll
+          for (int q = 0; q < 8; ++q) {
+            dS[q] = ok[q] ? P[q] * (vp[q] - d) : 0.f;
+            dSt[q] = ok[q] ? Pt[q] * (vp[q] - d) + P[q] * (vt[q] - dt) : 0.f;
+          }
+          store8_bf16(p.C, ci, gn, dS);
+          store8_bf16(p.Ct, ci, gn, dSt);
+        }
+      }
+    }
+    __syncthreads();
+  }
 }
 
-template <bool TA, bool TB, int NT>
-static hipError_t launch_dual_nt(const DualP& p, dim3 grid, hipStream_t st) {
+template <bool TA, bool TB, int NT, int NS, int EPI>
+static hipError_t launch_dual_k(const DualP& p, dim3 grid, hipStream_t st) {
   static bool attr_done = false;
-  auto kern = gemm_dual_kernel<TA, TB, NT>;
-  constexpr int smem = 2 * NT * 128 * 32 * 2;
+  auto kern = gemm_dual_kernel<TA, TB, NT, NS, EPI>;
+  constexpr int smem_pipe = NS * NT * 128 * 32 * 2, smem_epi = 4 * 2 * 32 * (64 + 4) * 4;
+  constexpr int smem = smem_pipe > smem_epi ? smem_pipe : smem_epi;
+  static_assert(smem <= 160 * 1024, "LDS");
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
@@ -259,9 +522,18 @@ static hipError_t launch_dual_nt(const DualP& p, dim3 grid, hipStream_t st) {
 }
 template <bool TA, bool TB>
 static hipError_t launch_dual_one(const DualP& p, dim3 grid, hipStream_t st) {
-  if (p.Blo) return launch_dual_nt<TA, TB, 6>(p, grid, st);
-  if (p.Alo) return launch_dual_nt<TA, TB, 5>(p, grid, st);
-  return launch_dual_nt<TA, TB, 4>(p, grid, st);
+  if (p.Blo) return launch_dual_k<TA, TB, 6, 2, EPI_NONE>(p, grid, st);
+  if (p.Alo) return launch_dual_k<TA, TB, 5, 2, EPI_NONE>(p, grid, st);
+  return launch_dual_k<TA, TB, 4, 2, EPI_NONE>(p, grid, st);
+}
+// Attention epilogues: A B^T products with k = head dimension.  Four operand
+// tiles per stage and two stages (optional low-order terms run as further
+// slabs), so that two blocks are resident per CU: with so short a k the
+// per-block prologue and epilogue dominate and only a second block hides them.
+template <int EPI>
+static hipError_t launch_dual_att(const DualP& p, dim3 grid, hipStream_t st) {
+  if (p.K % 32 != 0) return hipErrorNotSupported;  // the low-order loops have no ragged-k path
+  return launch_dual_k<false, true, 4, 2, EPI>(p, grid, st);
 }
 
 // g.Ct != nullptr.  Returns hipErrorNotSupported when the description does not
@@ -281,9 +553,34 @@ hipError_t launch_gemm_dual(const Gemm& g, hipStream_t st) {
   p.M = g.M; p.N = g.N; p.K = g.K; p.lda = g.lda; p.ldb = g.ldb; p.ldc = g.ldc; p.nb2 = g.nb2;
   p.sA1 = g.sA1; p.sA2 = g.sA2; p.sB1 = g.sB1; p.sB2 = g.sB2; p.sC1 = g.sC1; p.sC2 = g.sC2;
   p.alpha = g.alpha; p.out_bf16 = g.out_bf16; p.bias_bf16 = 1; p.klimit = g.klimit; p.skip_upper = g.skip_upper;
+  p.epi = g.epi; p.part = g.part; p.rstat = g.rstat; p.E0 = g.E0; p.E1 = g.E1; p.NP = (g.N + 63) / 64;
+  if (g.epi != EPI_NONE) {
+    const bool stats = g.epi == EPI_FWD_STATS || g.epi == EPI_BWD_STATS;
+    const bool reads = g.epi == EPI_BWD_STATS || g.epi == EPI_BWD_DS;
+    if ((stats && !g.part) || (!stats && (!g.rstat || !g.out_bf16)) || (reads && (!g.E0 || !g.E1)) || g.Cadd || g.Cadd_t ||
+        g.bias || g.bias_t)
+      return hipErrorInvalidValue;
+    if (g.transA || !g.transB) return hipErrorNotSupported;
+  }
+  {
+    const int64_t q = (g.out_bf16 || g.epi != EPI_NONE) ? 8 : 4;
+    auto al = [&](const void* x) { return x == nullptr || ((uintptr_t)x % 16) == 0; };
+    p.vec = al(g.C) && al(g.Ct) && al(g.C_lo) && al(g.E0) && al(g.E1) && al(g.Cadd) && al(g.Cadd_t) && g.ldc % q == 0 &&
+            g.sC1 % q == 0 && g.sC2 % q == 0;
+  }
   if (p.Blo && !p.Alo) return hipErrorNotSupported;
   const int64_t nt = ((g.M + 127) / 128) * (int64_t)((g.N + 127) / 128);
   dim3 grid((unsigned)nt, (unsigned)(g.nb1 * g.nb2), 1);
+  if (g.epi != EPI_NONE) {
+    if (!p.vec || g.N % 8 != 0) return hipErrorNotSupported;
+    switch (g.epi) {
+      case EPI_FWD_STATS: return launch_dual_att<EPI_FWD_STATS>(p, grid, st);
+      case EPI_FWD_SOFTMAX: return launch_dual_att<EPI_FWD_SOFTMAX>(p, grid, st);
+      case EPI_BWD_STATS: return launch_dual_att<EPI_BWD_STATS>(p, grid, st);
+      case EPI_BWD_DS: return launch_dual_att<EPI_BWD_DS>(p, grid, st);
+      default: return hipErrorInvalidValue;
+    }
+  }
   if (!g.transA && !g.transB) return launch_dual_one<false, false>(p, grid, st);
   if (!g.transA && g.transB) return launch_dual_one<false, true>(p, grid, st);
   if (g.transA && !g.transB) return launch_dual_one<true, false>(p, grid, st);

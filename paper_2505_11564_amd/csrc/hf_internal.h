@@ -68,7 +68,22 @@ struct Gemm {
   void* Ct = nullptr;
   const float* Cadd_t = nullptr;
   int force_cfg = -1, force_ks = 0;  // tuning / tests: tile configuration and k-split override
+  // Attention epilogues of the dual-output kernel (bf16 operands, Ct != nullptr).  With them the
+  // score-shaped products never go to memory in fp32: the product is formed twice, once to reduce
+  // row statistics over 64-column parts and once to apply them.
+  //   EPI_FWD_STATS   : part[row][N/64][3] = (max, sum exp(s - max), sum exp(s - max) s_t) of the part
+  //   EPI_FWD_SOFTMAX : C = P = exp(s - m) / l, C_lo = its low-order half, Ct = P (s_t - r); rstat[row] = (m, 1/l, r)
+  //   EPI_BWD_STATS   : part[row][N/64][3] = (sum P c, sum P_t c + P c_t, -) with P = E0, P_t = E1
+  //   EPI_BWD_DS      : C = P (c - delta), Ct = P_t (c - delta) + P (c_t - delta_t); rstat[row] = (delta, delta_t, -)
+  // s / c are the primal product, s_t / c_t its tangent; rows are batch-major (batch index * M + m);
+  // entries with column > row are masked (zero) when skip_upper is set.
+  int epi = 0;
+  float* part = nullptr;
+  const float* rstat = nullptr;
+  const void* E0 = nullptr;
+  const void* E1 = nullptr;
 };
+enum { EPI_NONE = 0, EPI_FWD_STATS = 1, EPI_FWD_SOFTMAX = 2, EPI_BWD_STATS = 3, EPI_BWD_DS = 4 };
 
 hipError_t launch_gemm(const Gemm& g, hipStream_t st);
 hipError_t launch_gemm_dual(const Gemm& g, hipStream_t st);  // bf16, aligned operands only
@@ -78,6 +93,9 @@ hipError_t launch_gemm_dual(const Gemm& g, hipStream_t st);  // bf16, aligned op
 // Launchers take `bf` = 1 for bf16 mode (AT = PT = bf16), 0 for fp32 mode.
 
 hipError_t launch_fill_f32(float* p, int64_t n, float val, hipStream_t st);
+// Combine the per-part row statistics of the attention epilogues: forward (online softmax merge)
+// -> rstat[row] = (m, 1/l, r); backward (plain sums) -> rstat[row] = (delta, delta_t, 0).
+hipError_t launch_attn_combine(int backward, const float* part, int NP, int M, int64_t rows, float* rstat, hipStream_t st);
 
 // probe.hip: batch-loop accumulation and Hessian-column statistics
 constexpr int CS_MAX_THRESHOLDS = 16, CS_MAX_BINS = 256, CS_STATS_WORDS = 32 + CS_MAX_BINS;

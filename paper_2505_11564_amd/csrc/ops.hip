@@ -83,6 +83,37 @@ static inline bool all_aligned16(std::initializer_list<const void*> ps) {
   return true;
 }
 
+// ------------------------------------------------- attention row statistics ----
+// Row i of a causal score matrix is covered by the parts 0 .. i/64 (64 columns each).
+__global__ void attn_combine_kernel(int backward, const float* __restrict__ part, int NP, int M, int64_t rows,
+                                    float* __restrict__ rstat) {
+  const int64_t row = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (row >= rows) return;
+  const int np = (int)(row % M) / 64 + 1;
+  const float* pr = part + row * NP * 3;
+  if (backward) {
+    float d = 0.f, dt = 0.f;
+    for (int q = 0; q < np; ++q) { d += pr[q * 3]; dt += pr[q * 3 + 1]; }
+    rstat[row * 3] = d; rstat[row * 3 + 1] = dt; rstat[row * 3 + 2] = 0.f;
+    return;
+  }
+  float m = -INFINITY;
+  for (int q = 0; q < np; ++q) m = fmaxf(m, pr[q * 3]);
+  float l = 0.f, rr = 0.f;
+  for (int q = 0; q < np; ++q) {
+    const float w = __expf(pr[q * 3] - m);  // a part without a valid column has max -inf, weight 0
+    l += pr[q * 3 + 1] * w;
+    rr += pr[q * 3 + 2] * w;
+  }
+  const float inv = 1.f / l;
+  rstat[row * 3] = m; rstat[row * 3 + 1] = inv; rstat[row * 3 + 2] = rr * inv;
+}
+hipError_t launch_attn_combine(int backward, const float* part, int NP, int M, int64_t rows, float* rstat, hipStream_t st) {
+  if (rows <= 0) return hipSuccess;
+  hipLaunchKernelGGL(attn_combine_kernel, dim3((unsigned)cdiv(rows, 256)), dim3(256), 0, st, backward, part, NP, M, rows, rstat);
+  return hipGetLastError();
+}
+
 // ------------------------------------------------------------ fill / cast ----
 
 __global__ void fill_f32_kernel(float* p, int64_t n, float val) {
