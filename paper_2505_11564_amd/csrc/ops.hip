@@ -441,11 +441,121 @@ __global__ __launch_bounds__(256) void norm_bwd_vec_kernel(const float* __restri
   }
 }
 
+// Narrow rows (d <= 1024): one wavefront per row, so a block has four rows in
+// flight and the row reductions are wave shuffles without a block barrier.
+// Lane l owns the groups of 4 columns 4 (64 j + l) .. +3, j < NJ.  The column
+// sums of the four waves meet in LDS and leave as one atomic per column per block.
+template <typename PT, bool RMS, int NJ>
+__global__ __launch_bounds__(256) void norm_bwd_wave_kernel(const float* __restrict__ dy, const float* __restrict__ dy_t,
+                                                            const float* __restrict__ x, const float* __restrict__ x_t,
+                                                            const float* __restrict__ stats, const PT* gam,
+                                                            const float* gam_t, int T, int d, int rows_per_block,
+                                                            int accumulate, float* dx, float* dx_t, float* hv_gam,
+                                                            float* hv_bet) {
+  extern __shared__ float colred[];  // [2][4][d]
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int d4 = d >> 2;
+  float4 pg[NJ], pb[NJ], gm[NJ], gmt[NJ];
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) {
+    pg[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+    pb[j] = pg[j];
+    const int c4 = j * 64 + lane;
+    gm[j] = c4 < d4 ? ld4(gam, c4) : pg[j];
+    gmt[j] = c4 < d4 ? ld4(gam_t, c4) : pg[j];
+  }
+  const float inv_d = 1.f / (float)d;
+  const int r0 = blockIdx.x * rows_per_block;
+  const int r1 = min(T, r0 + rows_per_block);
+  for (int row = r0 + wave; row < r1; row += 4) {
+    const int64_t base4 = (int64_t)row * d4;
+    const float4 s = *(const float4*)(stats + (int64_t)row * 4);
+    const float mu = s.x, rstd = s.y, mxt = s.z, st = s.w;
+    float4 xh[NJ], xht[NJ], dv[NJ], dtv[NJ];
+    float m0 = 0.f, m1s = 0.f, m2s = 0.f, m3s = 0.f;
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      const int c4 = j * 64 + lane;
+      if (c4 < d4) {
+        const float4 xv = ld4(x, base4 + c4), xtv = ld4(x_t, base4 + c4);
+        dv[j] = ld4(dy, base4 + c4);
+        dtv[j] = ld4(dy_t, base4 + c4);
+#define HF_NBW(q)                                                       \
+  {                                                                     \
+    const float h = (xv.q - mu) * rstd;                                 \
+    const float ht = (xtv.q - mxt - h * st) * rstd;                     \
+    xh[j].q = h; xht[j].q = ht;                                         \
+    const float g = gm[j].q * dv[j].q;                                  \
+    const float gt = gmt[j].q * dv[j].q + gm[j].q * dtv[j].q;           \
+    m0 += g; m1s += g * h; m2s += gt; m3s += gt * h + g * ht;           \
+  }
+        HF_NBW(x) HF_NBW(y) HF_NBW(z) HF_NBW(w)
+#undef HF_NBW
+      }
+    }
+    m0 = wave_sum(m0); m1s = wave_sum(m1s); m2s = wave_sum(m2s); m3s = wave_sum(m3s);
+    float m1 = m0 * inv_d, m2 = m1s * inv_d, m1t = m2s * inv_d, m2t = m3s * inv_d;
+    if (RMS) { m1 = 0.f; m1t = 0.f; }
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      const int c4 = j * 64 + lane;
+      if (c4 < d4) {
+        float4 o, ot;
+#define HF_NBW(q)                                                                               \
+  {                                                                                             \
+    const float g = gm[j].q * dv[j].q;                                                          \
+    const float gt = gmt[j].q * dv[j].q + gm[j].q * dtv[j].q;                                   \
+    o.q = (g - m1 - xh[j].q * m2) * rstd;                                                       \
+    ot.q = (gt - m1t - xht[j].q * m2 - xh[j].q * m2t) * rstd - o.q * st * rstd;                 \
+    pg[j].q += dtv[j].q * xh[j].q + dv[j].q * xht[j].q;                                         \
+    pb[j].q += dtv[j].q;                                                                        \
+  }
+        HF_NBW(x) HF_NBW(y) HF_NBW(z) HF_NBW(w)
+#undef HF_NBW
+        if (accumulate) {
+          const float4 a = ld4(dx, base4 + c4), b = ld4(dx_t, base4 + c4);
+          o.x += a.x; o.y += a.y; o.z += a.z; o.w += a.w;
+          ot.x += b.x; ot.y += b.y; ot.z += b.z; ot.w += b.w;
+        }
+        ((float4*)dx)[base4 + c4] = o;
+        ((float4*)dx_t)[base4 + c4] = ot;
+      }
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) {
+    const int c4 = j * 64 + lane;
+    if (c4 < d4) {
+      ((float4*)(colred + (size_t)wave * d))[c4] = pg[j];
+      ((float4*)(colred + (size_t)(4 + wave) * d))[c4] = pb[j];
+    }
+  }
+  __syncthreads();
+  for (int c = threadIdx.x; c < d; c += 256) {
+    atomicAdd(hv_gam + c, (colred[c] + colred[d + c]) + (colred[2 * d + c] + colred[3 * d + c]));
+    if (!RMS) atomicAdd(hv_bet + c, (colred[4 * d + c] + colred[5 * d + c]) + (colred[6 * d + c] + colred[7 * d + c]));
+  }
+}
+
 hipError_t launch_norm_bwd(int bf, int rms, const float* dy, const float* dy_t, const float* x, const float* x_t,
                            const float* stats, const void* gam, const float* gam_t, int T, int d, int accumulate,
                            float* dx, float* dx_t, float* hv_gam, float* hv_bet, hipStream_t st) {
   if (d > 256 * NORM_MAXC) return hipErrorInvalidValue;
-  if (d % 4 == 0 && all_aligned16({dy, dy_t, x, x_t, dx, dx_t, gam_t}) && ((uintptr_t)gam & (bf ? 7 : 15)) == 0) {
+  const bool vec_ok = d % 4 == 0 && all_aligned16({dy, dy_t, x, x_t, dx, dx_t, gam_t}) && ((uintptr_t)gam & (bf ? 7 : 15)) == 0;
+  if (vec_ok && d <= 1024 && T >= 64) {
+    const int rpb = std::max(4, (T / 512 + 3) / 4 * 4);
+    const int blocks = (T + rpb - 1) / rpb;
+    const int nj = (d / 4 + 63) / 64;
+    const size_t lds = (size_t)8 * d * sizeof(float);
+#define HF_NBW2(PT, R, N) hipLaunchKernelGGL((norm_bwd_wave_kernel<PT, R, N>), dim3(blocks), dim3(256), lds, st, dy, dy_t, x, x_t, stats, (const PT*)gam, gam_t, T, d, rpb, accumulate, dx, dx_t, hv_gam, hv_bet)
+#define HF_NBW1(PT, R) { if (nj <= 1) HF_NBW2(PT, R, 1); else if (nj <= 2) HF_NBW2(PT, R, 2); else if (nj <= 3) HF_NBW2(PT, R, 3); else HF_NBW2(PT, R, 4); }
+    if (bf) { if (rms) HF_NBW1(bf16, true) else HF_NBW1(bf16, false) }
+    else { if (rms) HF_NBW1(float, true) else HF_NBW1(float, false) }
+#undef HF_NBW1
+#undef HF_NBW2
+    return hipGetLastError();
+  }
+  if (vec_ok) {
     const int rpb = std::max(1, T / 512);  // the column atomics at the end bound the block count
     const int blocks = (T + rpb - 1) / rpb;
     const int nch = (d / 4 + 255) / 256;
@@ -805,6 +915,15 @@ hipError_t launch_count_valid(const int32_t* labels, int T, int V, int* n_valid,
   return hipGetLastError();
 }
 
+// Two passes over a row of logits (rows are 16-byte aligned: ldz % 64 == 0):
+// an online-softmax pass that keeps (max, sum exp, sum exp * z_t) per thread,
+// rescaled when the running maximum moves, then the pass that writes dz, dz_t.
+__device__ __forceinline__ void st4f(float* p, int64_t i, float a, float b, float c, float d) { *(float4*)(p + i) = make_float4(a, b, c, d); }
+__device__ __forceinline__ void st4f(bf16* p, int64_t i, float a, float b, float c, float d) {
+  bf16 o[4] = {(bf16)a, (bf16)b, (bf16)c, (bf16)d};
+  *(uint2*)(p + i) = *(const uint2*)o;
+}
+
 template <typename AT>
 __global__ __launch_bounds__(256) void ce_kernel(const float* __restrict__ z, const float* __restrict__ z_t,
                                                  const int32_t* labels, const int* n_valid, int V, int64_t ldz, AT* dz,
@@ -814,25 +933,49 @@ __global__ __launch_bounds__(256) void ce_kernel(const float* __restrict__ z, co
   const float* zr = z + row * ldz;
   const float* ztr = z_t + row * ldz;
   const int y = labels[row];
+  const int V4 = V >> 2;
   if (y < 0 || y >= V) {
-    for (int c = threadIdx.x; c < V; c += 256) { stf(dz, row * ldz + c, 0.f); stf(dz_t, row * ldz + c, 0.f); }
+    for (int c = threadIdx.x; c < V4; c += 256) { st4f(dz, row * ldz + 4 * c, 0.f, 0.f, 0.f, 0.f); st4f(dz_t, row * ldz + 4 * c, 0.f, 0.f, 0.f, 0.f); }
+    for (int c = 4 * V4 + threadIdx.x; c < V; c += 256) { stf(dz, row * ldz + c, 0.f); stf(dz_t, row * ldz + c, 0.f); }
     if (threadIdx.x == 0) loss_rows[row] = 0.f;
     return;
   }
-  float mx = -INFINITY;
-  for (int c = threadIdx.x; c < V; c += 256) mx = fmaxf(mx, zr[c]);
-  mx = block_max(mx, red);
-  float s[2] = {0.f, 0.f};
-  for (int c = threadIdx.x; c < V; c += 256) {
-    const float e = __expf(zr[c] - mx);
-    s[0] += e;
-    s[1] += e * ztr[c];
+  float m = -INFINITY, se = 0.f, sd = 0.f;
+  for (int c = threadIdx.x; c < V4; c += 256) {
+    const float4 x = ((const float4*)zr)[c], t = ((const float4*)ztr)[c];
+    const float mn = fmaxf(fmaxf(m, fmaxf(x.x, x.y)), fmaxf(x.z, x.w));
+    const float sc = __expf(m - mn);  // exp(-inf) = 0 on the first visit
+    const float e0 = __expf(x.x - mn), e1 = __expf(x.y - mn), e2 = __expf(x.z - mn), e3 = __expf(x.w - mn);
+    se = se * sc + ((e0 + e1) + (e2 + e3));
+    sd = sd * sc + ((e0 * t.x + e1 * t.y) + (e2 * t.z + e3 * t.w));
+    m = mn;
+  }
+  for (int c = 4 * V4 + threadIdx.x; c < V; c += 256) {
+    const float x = zr[c], mn = fmaxf(m, x), sc = __expf(m - mn), e = __expf(x - mn);
+    se = se * sc + e;
+    sd = sd * sc + e * ztr[c];
+    m = mn;
+  }
+  const float mx = block_max(m, red);
+  float s[2];
+  {
+    const float sc = (m == -INFINITY) ? 0.f : __expf(m - mx);  // a thread that saw no column contributes nothing
+    s[0] = se * sc;
+    s[1] = sd * sc;
   }
   block_sum<2>(s, red);
   const float inv = 1.f / s[0];
   const float pz = s[1] * inv;
   const float invN = 1.f / (float)max(1, *n_valid);
-  for (int c = threadIdx.x; c < V; c += 256) {
+  for (int c = threadIdx.x; c < V4; c += 256) {
+    const float4 x = ((const float4*)zr)[c], t = ((const float4*)ztr)[c];
+    const float p0 = __expf(x.x - mx) * inv, p1 = __expf(x.y - mx) * inv, p2 = __expf(x.z - mx) * inv, p3 = __expf(x.w - mx) * inv;
+    const int c0 = 4 * c;
+    st4f(dz, row * ldz + c0, (p0 - (c0 == y ? 1.f : 0.f)) * invN, (p1 - (c0 + 1 == y ? 1.f : 0.f)) * invN,
+         (p2 - (c0 + 2 == y ? 1.f : 0.f)) * invN, (p3 - (c0 + 3 == y ? 1.f : 0.f)) * invN);
+    st4f(dz_t, row * ldz + c0, p0 * (t.x - pz) * invN, p1 * (t.y - pz) * invN, p2 * (t.z - pz) * invN, p3 * (t.w - pz) * invN);
+  }
+  for (int c = 4 * V4 + threadIdx.x; c < V; c += 256) {
     const float pv = __expf(zr[c] - mx) * inv;
     stf(dz, row * ldz + c, (pv - (c == y ? 1.f : 0.f)) * invN);
     stf(dz_t, row * ldz + c, pv * (ztr[c] - pz) * invN);
