@@ -64,6 +64,7 @@ struct hf_ctx {
   int64_t ldz = 0;
   float* loss_rows = nullptr;
   float *sc = nullptr, *sc_t = nullptr;
+  float* norm_part = nullptr;  // per-block column sums of the norm backward kernels
   float *att_part = nullptr, *att_rstat = nullptr;  // row statistics of the fused attention epilogues
   int64_t att_SS = 0;                                 // elements of one score-shaped buffer
   int att_zero_B = -1, att_zero_S = -1;               // shape for which the never-written score tiles were last cleared

@@ -134,6 +134,7 @@ int hf_ctx::plan_and_alloc() {
     pl.add(loss_rows, T * 4);
     pl.add(sc, SS * 4); pl.add(sc_t, SS * 4);
     att_SS = SS;
+    pl.add(norm_part, (int64_t)NORM_PART_BLOCKS * 2 * D * 4);
     if (bf) {
       const int64_t rows = SS / desc.max_seq, np = (desc.max_seq + 63) / 64;  // B*H*S rows
       pl.add(att_part, rows * np * 3 * 4); pl.add(att_rstat, rows * 3 * 4);
@@ -489,7 +490,7 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
     if ((rc = L.bwd_dx(dz, dz_t, T, D, V, ldz, off_head, tmpd, tmpd_t, D, 0))) return rc;
   }
   CK(launch_norm_bwd(bf, rms, tmpd, tmpd_t, xL, xL_t, stf, L.Wp(off_nfg), v + off_nfg, T, D, 0, dx, dx_t,
-                     out + off_nfg, rms ? nullptr : out + off_nfb, st));
+                     out + off_nfg, rms ? nullptr : out + off_nfb, norm_part, st));
 
   for (int l = NL - 1; l >= 0; --l) {
     LayerBuf& b = lb[l];
@@ -512,7 +513,7 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
       if ((rc = L.bwd_dx(dup, dup_t, T, D, F, F, o.wup, tmpd, tmpd_t, D, 0, tmpd, tmpd_t))) return rc;
     }
     CK(launch_norm_bwd(bf, rms, tmpd, tmpd_t, b.x2, b.x2_t, b.st2, L.Wp(o.n2g), v + o.n2g, T, D, 1, dx, dx_t,
-                       out + o.n2g, rms ? nullptr : out + o.n2b, st));
+                       out + o.n2g, rms ? nullptr : out + o.n2b, norm_part, st));
     // ---- attention branch
     if (bf) CK(launch_cast_pair(1, dx, dx_t, dxb, dxb_t, (int64_t)T * D, st));
     if ((rc = L.bwd_dw(b.o, b.o_t, dxb, dxb_t, T, D, D, D, D, o.wo, o.bo, dx_t, 0))) return rc;
@@ -582,7 +583,7 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
       }
     }
     CK(launch_norm_bwd(bf, rms, tmpd, tmpd_t, b.x1, b.x1_t, b.st1, L.Wp(o.n1g), v + o.n1g, T, D, 1, dx, dx_t,
-                       out + o.n1g, rms ? nullptr : out + o.n1b, st));
+                       out + o.n1g, rms ? nullptr : out + o.n1b, norm_part, st));
   }
   CK(launch_embed_bwd(dx_t, tok, T, S, D, V, out + off_wte, llama ? nullptr : out + off_wpe, st));
   return HF_OK;

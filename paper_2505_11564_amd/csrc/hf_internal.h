@@ -120,9 +120,10 @@ hipError_t launch_norm_fwd(int bf, int rms, const float* x, const float* x_t, co
                            const float* gam_t, const float* bet_t, int T, int d, float eps, void* y, void* y_t,
                            void* y_lo, float* stats, hipStream_t st);
 // dx (+)= ..., dx_t (+)= ...; hv_gam / hv_bet += column sums (atomic).
+constexpr int NORM_PART_BLOCKS = 1024;  // upper bound of the blocks launch_norm_bwd uses with `part`
 hipError_t launch_norm_bwd(int bf, int rms, const float* dy, const float* dy_t, const float* x, const float* x_t,
                            const float* stats, const void* gam, const float* gam_t, int T, int d, int accumulate,
-                           float* dx, float* dx_t, float* hv_gam, float* hv_bet, hipStream_t st);
+                           float* dx, float* dx_t, float* hv_gam, float* hv_bet, float* part, hipStream_t st);
 
 enum Act { ACT_TANH = 0, ACT_GELU = 1 };
 // a_lo / y_lo (nullable): low-order halves of the primal input / output.

@@ -357,7 +357,7 @@ __global__ __launch_bounds__(256) void norm_bwd_vec_kernel(const float* __restri
                                                            const float* __restrict__ stats, const PT* gam,
                                                            const float* gam_t, int T, int d, int rows_per_block,
                                                            int accumulate, float* dx, float* dx_t, float* hv_gam,
-                                                           float* hv_bet) {
+                                                           float* hv_bet, float* part) {
   __shared__ float red[16];
   const int d4 = d >> 2;
   float4 pg[NCH], pb[NCH], gm[NCH], gmt[NCH];
@@ -431,11 +431,16 @@ __global__ __launch_bounds__(256) void norm_bwd_vec_kernel(const float* __restri
   for (int j = 0; j < NCH; ++j) {
     const int c = 4 * (j * 256 + threadIdx.x);
     if (c < d) {
-      atomicAdd(hv_gam + c, pg[j].x); atomicAdd(hv_gam + c + 1, pg[j].y);
-      atomicAdd(hv_gam + c + 2, pg[j].z); atomicAdd(hv_gam + c + 3, pg[j].w);
-      if (!RMS) {
-        atomicAdd(hv_bet + c, pb[j].x); atomicAdd(hv_bet + c + 1, pb[j].y);
-        atomicAdd(hv_bet + c + 2, pb[j].z); atomicAdd(hv_bet + c + 3, pb[j].w);
+      if (part) {  // per-block partial sums, summed by norm_colsum_kernel
+        *(float4*)(part + ((size_t)blockIdx.x * 2) * d + c) = pg[j];
+        if (!RMS) *(float4*)(part + ((size_t)blockIdx.x * 2 + 1) * d + c) = pb[j];
+      } else {
+        atomicAdd(hv_gam + c, pg[j].x); atomicAdd(hv_gam + c + 1, pg[j].y);
+        atomicAdd(hv_gam + c + 2, pg[j].z); atomicAdd(hv_gam + c + 3, pg[j].w);
+        if (!RMS) {
+          atomicAdd(hv_bet + c, pb[j].x); atomicAdd(hv_bet + c + 1, pb[j].y);
+          atomicAdd(hv_bet + c + 2, pb[j].z); atomicAdd(hv_bet + c + 3, pb[j].w);
+        }
       }
     }
   }
@@ -451,7 +456,7 @@ __global__ __launch_bounds__(256) void norm_bwd_wave_kernel(const float* __restr
                                                             const float* __restrict__ stats, const PT* gam,
                                                             const float* gam_t, int T, int d, int rows_per_block,
                                                             int accumulate, float* dx, float* dx_t, float* hv_gam,
-                                                            float* hv_bet) {
+                                                            float* hv_bet, float* part) {
   extern __shared__ float colred[];  // [2][4][d]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int d4 = d >> 2;
@@ -532,40 +537,71 @@ __global__ __launch_bounds__(256) void norm_bwd_wave_kernel(const float* __restr
   }
   __syncthreads();
   for (int c = threadIdx.x; c < d; c += 256) {
-    atomicAdd(hv_gam + c, (colred[c] + colred[d + c]) + (colred[2 * d + c] + colred[3 * d + c]));
-    if (!RMS) atomicAdd(hv_bet + c, (colred[4 * d + c] + colred[5 * d + c]) + (colred[6 * d + c] + colred[7 * d + c]));
+    const float sg = (colred[c] + colred[d + c]) + (colred[2 * d + c] + colred[3 * d + c]);
+    const float sb = (colred[4 * d + c] + colred[5 * d + c]) + (colred[6 * d + c] + colred[7 * d + c]);
+    if (part) {
+      part[((size_t)blockIdx.x * 2) * d + c] = sg;
+      if (!RMS) part[((size_t)blockIdx.x * 2 + 1) * d + c] = sb;
+    } else {
+      atomicAdd(hv_gam + c, sg);
+      if (!RMS) atomicAdd(hv_bet + c, sb);
+    }
   }
+}
+
+// hv[c] += sum over blocks of part[block][which][c]: grid (d / 256, groups, 2);
+// each block sums its share of the partial rows and adds once per column.
+__global__ void norm_colsum_kernel(const float* __restrict__ part, int nblocks, int d, float* hv_gam, float* hv_bet) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= d) return;
+  const int which = blockIdx.z;
+  float* hv = which ? hv_bet : hv_gam;
+  const int per = (nblocks + gridDim.y - 1) / gridDim.y;
+  const int b0 = blockIdx.y * per, b1 = min(nblocks, b0 + per);
+  float s = 0.f;
+  for (int b = b0; b < b1; ++b) s += part[((size_t)b * 2 + which) * d + c];
+  if (b1 > b0) atomicAdd(hv + c, s);
 }
 
 hipError_t launch_norm_bwd(int bf, int rms, const float* dy, const float* dy_t, const float* x, const float* x_t,
                            const float* stats, const void* gam, const float* gam_t, int T, int d, int accumulate,
-                           float* dx, float* dx_t, float* hv_gam, float* hv_bet, hipStream_t st) {
+                           float* dx, float* dx_t, float* hv_gam, float* hv_bet, float* part, hipStream_t st) {
   if (d > 256 * NORM_MAXC) return hipErrorInvalidValue;
+  // part (optional): room for NORM_PART_BLOCKS x 2 x d floats; the vector kernels then leave their
+  // column sums there and a second kernel adds them up (the atomics otherwise cost more than the rows)
+  auto finish = [&](int blocks) {
+    hipLaunchKernelGGL(norm_colsum_kernel, dim3((d + 255) / 256, 16, rms ? 1 : 2), dim3(256), 0, st, part, blocks, d, hv_gam, hv_bet);
+    return hipGetLastError();
+  };
   const bool vec_ok = d % 4 == 0 && all_aligned16({dy, dy_t, x, x_t, dx, dx_t, gam_t}) && ((uintptr_t)gam & (bf ? 7 : 15)) == 0;
   if (vec_ok && d <= 1024 && T >= 64) {
     const int rpb = std::max(4, (T / 512 + 3) / 4 * 4);
     const int blocks = (T + rpb - 1) / rpb;
     const int nj = (d / 4 + 63) / 64;
+    part = nullptr;  // narrow rows: the atomics are cheaper than a second launch
     const size_t lds = (size_t)8 * d * sizeof(float);
-#define HF_NBW2(PT, R, N) hipLaunchKernelGGL((norm_bwd_wave_kernel<PT, R, N>), dim3(blocks), dim3(256), lds, st, dy, dy_t, x, x_t, stats, (const PT*)gam, gam_t, T, d, rpb, accumulate, dx, dx_t, hv_gam, hv_bet)
+#define HF_NBW2(PT, R, N) hipLaunchKernelGGL((norm_bwd_wave_kernel<PT, R, N>), dim3(blocks), dim3(256), lds, st, dy, dy_t, x, x_t, stats, (const PT*)gam, gam_t, T, d, rpb, accumulate, dx, dx_t, hv_gam, hv_bet, part)
 #define HF_NBW1(PT, R) { if (nj <= 1) HF_NBW2(PT, R, 1); else if (nj <= 2) HF_NBW2(PT, R, 2); else if (nj <= 3) HF_NBW2(PT, R, 3); else HF_NBW2(PT, R, 4); }
     if (bf) { if (rms) HF_NBW1(bf16, true) else HF_NBW1(bf16, false) }
     else { if (rms) HF_NBW1(float, true) else HF_NBW1(float, false) }
 #undef HF_NBW1
 #undef HF_NBW2
-    return hipGetLastError();
+    if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
+    return part ? finish(blocks) : hipSuccess;
   }
   if (vec_ok) {
     const int rpb = std::max(1, T / 512);  // the column atomics at the end bound the block count
     const int blocks = (T + rpb - 1) / rpb;
     const int nch = (d / 4 + 255) / 256;
-#define HF_NBV2(PT, R, N) hipLaunchKernelGGL((norm_bwd_vec_kernel<PT, R, N>), dim3(blocks), dim3(256), 0, st, dy, dy_t, x, x_t, stats, (const PT*)gam, gam_t, T, d, rpb, accumulate, dx, dx_t, hv_gam, hv_bet)
+    if (blocks > NORM_PART_BLOCKS) part = nullptr;
+#define HF_NBV2(PT, R, N) hipLaunchKernelGGL((norm_bwd_vec_kernel<PT, R, N>), dim3(blocks), dim3(256), 0, st, dy, dy_t, x, x_t, stats, (const PT*)gam, gam_t, T, d, rpb, accumulate, dx, dx_t, hv_gam, hv_bet, part)
 #define HF_NBV1(PT, R) { if (nch <= 1) HF_NBV2(PT, R, 1); else if (nch <= 2) HF_NBV2(PT, R, 2); else if (nch <= 4) HF_NBV2(PT, R, 4); else HF_NBV2(PT, R, 8); }
     if (bf) { if (rms) HF_NBV1(bf16, true) else HF_NBV1(bf16, false) }
     else { if (rms) HF_NBV1(float, true) else HF_NBV1(float, false) }
 #undef HF_NBV1
 #undef HF_NBV2
-    return hipGetLastError();
+    if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
+    return part ? finish(blocks) : hipSuccess;
   }
   const int rpb = std::max(1, T / 512);
   const int blocks = (T + rpb - 1) / rpb;
