@@ -390,6 +390,8 @@ hipError_t launch_gemm_mfma(GemmP p, int nb, int allow_splitk, int force_cfg, in
   // 128x128 tiles with two or more blocks per CU beat 256x256 except for A^T B
   // products with plenty of tiles; a row-contiguous B with a short k prefers
   // 32-deep slabs (the pipeline fills sooner).
+  // (a 256-wide tile on a 128-column product, attention's P V, wastes half its matrix instructions
+  // and was still measured faster than 128 x 128 tiles there)
   int cfg;
   if (force_cfg >= 0 && force_cfg < kNumCfg) cfg = force_cfg;
   else if (p.transA && !p.transB) cfg = tiles(256, 256) >= 256 ? 0 : 1;

@@ -1053,8 +1053,45 @@ __global__ void colsum_kernel(const AT* y, int T, int N, int64_t ld, int rows_pe
   for (int r = r0; r < r1; ++r) s += ldf(y, (int64_t)r * ld + c);
   atomicAdd(out + c, s);
 }
+// 8 consecutive columns per thread (16-byte loads of bf16, two of fp32), 8 row
+// lanes per block that meet in LDS: one atomic per column per block.
+template <typename AT>
+__global__ __launch_bounds__(256) void colsum_vec_kernel(const AT* __restrict__ y, int T, int N, int64_t ld, int rows_per_block,
+                                                         float* out) {
+  __shared__ float red[8][256 + 8];
+  const int cg = threadIdx.x & 31, rl = threadIdx.x >> 5;
+  const int c = blockIdx.x * 256 + cg * 8;
+  const int r0 = blockIdx.y * rows_per_block, r1 = min(T, r0 + rows_per_block);
+  float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if (c < N) {
+    for (int r = r0 + rl; r < r1; r += 8) {
+      float v[8];
+      ld8(y + (int64_t)r * ld + c, 0, v);
+#pragma unroll
+      for (int q = 0; q < 8; ++q) s[q] += v[q];
+    }
+  }
+#pragma unroll
+  for (int q = 0; q < 8; ++q) red[rl][cg * 8 + q] = s[q];
+  __syncthreads();
+  const int col = blockIdx.x * 256 + threadIdx.x;
+  if (col < N) {
+    float t = 0.f;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) t += red[k][threadIdx.x];
+    atomicAdd(out + col, t);
+  }
+}
+
 hipError_t launch_colsum(int is_bf16, const void* y, int T, int N, int64_t ld, float* out, hipStream_t st) {
   if (T <= 0 || N <= 0) return hipSuccess;
+  if (N % 8 == 0 && ld % 8 == 0 && ((uintptr_t)y & 15) == 0 && T >= 256) {
+    const int rows = 128;
+    dim3 grid((N + 255) / 256, (T + rows - 1) / rows);
+    if (is_bf16) hipLaunchKernelGGL(colsum_vec_kernel<bf16>, grid, dim3(256), 0, st, (const bf16*)y, T, N, ld, rows, out);
+    else hipLaunchKernelGGL(colsum_vec_kernel<float>, grid, dim3(256), 0, st, (const float*)y, T, N, ld, rows, out);
+    return hipGetLastError();
+  }
   const int rpb = 64;
   dim3 grid((N + 255) / 256, (T + rpb - 1) / rpb);
   if (is_bf16) hipLaunchKernelGGL(colsum_kernel<bf16>, grid, dim3(256), 0, st, (const bf16*)y, T, N, ld, rpb, out);
