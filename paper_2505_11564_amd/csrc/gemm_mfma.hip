@@ -175,8 +175,8 @@ __global__ __launch_bounds__(256, (min_blocks<BM, BN, KT>())) void gemm_mfma_ker
   auto compute = [&](auto stage_c, auto issue_c, uint32_t dyn_off) {
     constexpr int S = decltype(stage_c)::value;
     constexpr bool ISSUE = decltype(issue_c)::value;
-    constexpr int Q = TM * TN, LPK = NLOAD / NKK, MPL = Q / LPK;
-    static_assert(NLOAD % NKK == 0 && Q % LPK == 0, "loads divide evenly over the k-steps");
+    constexpr int Q = TM * TN, QS = Q * NKK;  // matrix instructions per k-step / per slab
+    static_assert(NLOAD <= QS, "at most one load per matrix instruction");
     Frag<AKC> a[2][TM];
     Frag<BKC> b[2][TN];
     auto request = [&](auto kk_c) {
@@ -199,14 +199,16 @@ __global__ __launch_bounds__(256, (min_blocks<BM, BN, KT>())) void gemm_mfma_ker
       for (int j = 0; j < TN; ++j) b[kk & 1][j].tie();
       if constexpr (kk + 1 < NKK) request(std::integral_constant<int, kk + 1>{});
       __builtin_amdgcn_sched_barrier(0);
-      static_for<LPK>([&](auto g_c) {
-        constexpr int g = decltype(g_c)::value;
-#pragma unroll
-        for (int q = g * MPL; q < (g + 1) * MPL; ++q)
-          acc[q / TN][q % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk & 1][q / TN].get(), b[kk & 1][q % TN].get(),
-                                                                        acc[q / TN][q % TN], 0, 0, 0);
-        if constexpr (ISSUE) {
-          issue_one(std::integral_constant<int, (S + NS - 1) % NS>{}, std::integral_constant<int, kk * LPK + g>{});
+      // matrix instruction number g of the slab is followed by load number
+      // floor((g+1) NLOAD / QS) - 1 when that differs from floor(g NLOAD / QS) - 1:
+      // the loads are spread evenly over the slab's matrix instructions
+      static_for<Q>([&](auto q_c) {
+        constexpr int q = decltype(q_c)::value, g = kk * Q + q;
+        acc[q / TN][q % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk & 1][q / TN].get(), b[kk & 1][q % TN].get(),
+                                                                      acc[q / TN][q % TN], 0, 0, 0);
+        constexpr int l0 = (g * NLOAD) / QS, l1 = ((g + 1) * NLOAD) / QS;
+        if constexpr (ISSUE && l1 > l0) {
+          issue_one(std::integral_constant<int, (S + NS - 1) % NS>{}, std::integral_constant<int, l0>{});
           __builtin_amdgcn_sched_barrier(0);
         }
       });
@@ -378,8 +380,9 @@ struct TileCfg { int bm, bn; };
 // 0: 256x256x64, 2 stages; 1: 128x128x64, 2 stages; 2: 128x128x32, 2 stages.
 // (Deeper pipelines, 256x128 tiles and register-staged loads were measured and
 // were slower on every shape tried.)
-static const TileCfg kCfg[] = {{256, 256}, {128, 128}, {128, 128}};
-constexpr int kNumCfg = 3;
+// 3: 256x128x64 and 4: 128x64x64 for products one attention head wide (N = 128 / N <= 64).
+static const TileCfg kCfg[] = {{256, 256}, {128, 128}, {128, 128}, {256, 128}, {128, 64}};
+constexpr int kNumCfg = 5;
 
 // Tile choice: the largest tile that still yields about two blocks per CU;
 // split-K for products with few output tiles and a long k (the H v blocks).
@@ -394,6 +397,8 @@ hipError_t launch_gemm_mfma(GemmP p, int nb, int allow_splitk, int force_cfg, in
   // and was still measured faster than 128 x 128 tiles there)
   int cfg;
   if (force_cfg >= 0 && force_cfg < kNumCfg) cfg = force_cfg;
+  else if (!p.transB && N <= 64 && M >= 128) cfg = 4;
+  else if (!p.transB && N <= 128 && N > 64 && tiles(256, 128) >= 128) cfg = 3;
   else if (p.transA && !p.transB) cfg = tiles(256, 256) >= 256 ? 0 : 1;
   else if (!p.transA && !p.transB) cfg = tiles(256, 256) >= 256 ? 0 : (p.K >= 1536 ? 1 : 2);
   else cfg = 1;
@@ -429,6 +434,8 @@ hipError_t launch_gemm_mfma(GemmP p, int nb, int allow_splitk, int force_cfg, in
   switch (cfg) {
     case 0: return launch_cfg<256, 256, 128, 128, 64, 2>(p, grid, st);
     case 1: return launch_cfg<128, 128, 64, 64, 64, 2>(p, grid, st);
+    case 3: return launch_cfg<256, 128, 128, 64, 64, 2>(p, grid, st);
+    case 4: return launch_cfg<128, 64, 64, 32, 64, 2>(p, grid, st);
     default: return launch_cfg<128, 128, 64, 64, 32, 2>(p, grid, st);
   }
 }

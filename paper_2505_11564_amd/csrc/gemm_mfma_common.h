@@ -32,7 +32,9 @@ __device__ __forceinline__ int lds_kc(int r, int k) { return r * KT + (kc_chunk<
 // The 64 B windows that one transpose read touches in four consecutive k rows
 // are rotated by (k & 3) so that they fall on four different quarters of the
 // banks (row strides are multiples of 256 B).
-__device__ __forceinline__ int lds_rc(int k, int r, int R) { return k * R + ((((r >> 3) ^ ((k & 3) << 2))) << 3) + (r & 7); }
+// (rows of fewer than 16 chunks keep the low bits of the rotation)
+__device__ __forceinline__ int rc_rot(int k, int R) { return ((k & 3) << 2) & (R / 8 - 1); }
+__device__ __forceinline__ int lds_rc(int k, int r, int R) { return k * R + ((((r >> 3) ^ rc_rot(k, R))) << 3) + (r & 7); }
 
 // Direct global->LDS loads of one k-slab of one operand.  Each wave issues NI
 // instructions per slab; instruction j moves 64 chunks of 16 B to the LDS
@@ -57,7 +59,7 @@ __device__ __forceinline__ void slab_offsets(uint32_t (&voff)[R * KT / 2048], in
     } else {
       constexpr int CPR = R / 8;  // chunks per k-row
       const int krow = P / CPR, pc = P % CPR;
-      const int lc = pc ^ ((krow & 3) << 2);
+      const int lc = pc ^ rc_rot(krow, R);
       const int gc = min(r0 + lc * 8, ((rmax - 1) >> 3) << 3) - r0;
       voff[j] = (uint32_t)(((int64_t)krow * ld + gc) * 2);
     }
@@ -98,7 +100,7 @@ __device__ __forceinline__ bf16x8 frag_read(const HF_LDS bf16* lds, int rbase, i
     const int i = lane & 15, g = lane >> 4;
     const int kq = kk * 16 + (g >> 1) * 8 + (i >> 2);
     const int c = rbase + (g & 1) * 16 + (i & 3) * 4;
-    const HF_LDS bf16* p0 = lds + kq * R + ((((c >> 3) ^ ((kq & 3) << 2))) << 3) + (c & 7);
+    const HF_LDS bf16* p0 = lds + kq * R + ((((c >> 3) ^ rc_rot(kq, R))) << 3) + (c & 7);
     const HF_LDS bf16* p1 = p0 + 4 * R;  // k + 4: same k & 3, same swizzle
     const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((HF_LDS bf16x4*)p0);
     const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((HF_LDS bf16x4*)p1);
@@ -153,7 +155,7 @@ __device__ __forceinline__ uint32_t frag_addr(int rbase, int kk, int lane) {
     const int i = lane & 15, g = lane >> 4;
     const int kq = (g >> 1) * 8 + (i >> 2);
     const int c = rbase + (g & 1) * 16 + (i & 3) * 4;
-    return (uint32_t)((kq * R + ((((c >> 3) ^ ((kq & 3) << 2))) << 3) + (c & 7)) * 2);
+    return (uint32_t)((kq * R + ((((c >> 3) ^ rc_rot(kq, R))) << 3) + (c & 7)) * 2);
   }
 }
 
