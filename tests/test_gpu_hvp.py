@@ -20,6 +20,9 @@ SHAPES = {
     # several 128-wide tiles with ragged tails in every dimension
     "gpt_mid": dict(model=si._gpt(2, 192, 3, 328, 1003, 160), batch=3, seq=150, tokens="zipf"),
     "llama_mid": dict(model=si._llama(2, 256, 4, 344, 777, 136), batch=2, seq=136, tokens="zipf"),
+    # sequence length a multiple of 8 and head width of 32: in bf16 mode the scores take the fused
+    # attention epilogues (two column tiles, the second one ragged)
+    "gpt_fused": dict(model=si._gpt(2, 128, 4, 264, 517, 200), batch=2, seq=200, tokens="zipf"),
 }
 
 
@@ -50,6 +53,26 @@ def test_hvp_parity_small(name, dtype):
 
 def test_hvp_shorter_sequence_than_max():
     run_case(SHAPES["gpt_mid"], "f32", seed=1, short_seq=77)
+
+
+def test_hvp_bf16_sequence_length_changes_on_one_context():
+    # The fused attention kernels write only the score tiles on and below the diagonal and rely on
+    # the rest having been cleared for the current [batch, seq] layout: alternate layouts on one
+    # context and check every product against the oracle.
+    import paper_2505_11564_amd as hf
+    from gpu_util import gpu_hvp, rel_l2
+    cfg = SHAPES["gpt_fused"]
+    model = cfg["model"]
+    p = si.bf16_bits_to_f32(si.f32_to_bf16_bits(si.make_params(model, param_dtype="bf16", perturb=0.1)))
+    n = om.num_params(model)
+    ctx = hf.Context(model, cfg["batch"], 0, "bf16")
+    for k, (batch, seq) in enumerate([(2, 200), (2, 136), (1, 200), (2, 72), (2, 200)]):
+        x, y = si.make_batch(cfg, seed=50 + k, batch=batch, seq=seq)
+        v = si.make_direction(n, 60 + k)
+        want = om.hvp(model, p.astype(np.float64), x, y, v.astype(np.float64))
+        got, _ = gpu_hvp(model, p, x, y, v, "bf16", ctx=ctx)
+        assert rel_l2(got, want) <= TOL["bf16"], (batch, seq)
+    ctx.close()
 
 
 def test_hvp_ignored_labels_and_single_valid():
