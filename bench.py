@@ -245,7 +245,10 @@ def main():
     if not args.no_cpu_baseline:
         del pd, out, r, dvec
         torch.cuda.empty_cache()
-        res["cpu_baseline"] = cpu_baseline(cfg, params, 1, "the HVP dominates; the vector update is included")
+        # sample sized for roughly 15 s of oracle work (the oracle sustains about 3e11 flop/s here)
+        per_seq_s = flops / B / 3e11
+        sample = int(max(1, min(B, round(15.0 / max(per_seq_s, 1e-9)))))
+        res["cpu_baseline"] = cpu_baseline(cfg, params, sample, "the HVP dominates; the vector update is included")
     print(json.dumps(res))
 
 

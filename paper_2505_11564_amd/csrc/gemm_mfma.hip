@@ -399,7 +399,7 @@ hipError_t launch_gemm_mfma(GemmP p, int nb, int allow_splitk, int force_cfg, in
   if (force_cfg >= 0 && force_cfg < kNumCfg) cfg = force_cfg;
   else if (!p.transB && N <= 64 && M >= 128) cfg = 4;
   else if (!p.transB && N <= 128 && N > 64 && tiles(256, 128) >= 128) cfg = 3;
-  else if (p.transA && !p.transB) cfg = tiles(256, 256) >= 256 ? 0 : 1;
+  else if (p.transA && !p.transB) cfg = tiles(256, 256) >= 160 ? 0 : 1;
   else if (!p.transA && !p.transB) cfg = tiles(256, 256) >= 256 ? 0 : (p.K >= 1536 ? 1 : 2);
   else cfg = 1;
   const int bm = kCfg[cfg].bm, bn = kCfg[cfg].bn;
