@@ -259,6 +259,24 @@ int32_t hf_slq_density(const double* ritz, const double* weights, const int32_t*
 int32_t hf_slq_moments(const double* ritz, const double* weights, const int32_t* m_eff,
                        int32_t n_probes, int32_t m, int32_t n_moments, double* moments);
 
+/* ---- Lanczos state hand-over (checkpoint / resume of Algorithm 2) ---------------
+ * The state after k iterations is k, q_k, q_{k-1}, beta_{k-1}, the
+ * re-orthogonalisation mode and (full mode) the stored basis q_0..q_k; the
+ * coefficients alpha, beta already returned are the caller's to keep.
+ * hf_lanczos_state_bytes: size of the image for the current state (negative
+ * hf_status when no iteration is in progress).
+ * hf_lanczos_export: writes the image to state_dev (device, caller-owned,
+ * 256-byte aligned, capacity_bytes >= hf_lanczos_state_bytes).
+ * hf_lanczos_import: restores an image into a context of the same parameter
+ * count, basis precision and max_m >= stored rows, replacing whatever iteration
+ * it held; the next hf_lanczos_step continues at iteration k.  The image is
+ * plain device memory (copy it to a file or another process as you like); it
+ * is only meaningful to this library version.  Both synchronise the stream.
+ * HF_ESTATE / HF_ESHAPE / HF_EINVAL as described. */
+int64_t hf_lanczos_state_bytes(const hf_ctx* ctx);
+int32_t hf_lanczos_export(hf_ctx* ctx, void* state_dev, int64_t capacity_bytes, void* hip_stream);
+int32_t hf_lanczos_import(hf_ctx* ctx, const void* state_dev, int64_t bytes, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

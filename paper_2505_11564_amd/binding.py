@@ -24,6 +24,7 @@ EXPORTS = [
     "hf_hvp", "hf_lanczos_init", "hf_lanczos_step", "hf_lanczos_iterations", "hf_lanczos_get_vector",
     "hf_slq", "hf_lanczos_update",
     "hf_hvp_accumulate", "hf_hessian_column", "hf_column_stats", "hf_slq_density", "hf_slq_moments",
+    "hf_lanczos_state_bytes", "hf_lanczos_export", "hf_lanczos_import",
 ]
 
 
@@ -95,6 +96,9 @@ def lib():
     L.hf_slq_density.restype = i32
     L.hf_slq_moments.argtypes = [dp, dp, C.POINTER(i32), i32, i32, i32, dp]
     L.hf_slq_moments.restype = i32
+    L.hf_lanczos_state_bytes.argtypes, L.hf_lanczos_state_bytes.restype = [vp], i64
+    L.hf_lanczos_export.argtypes, L.hf_lanczos_export.restype = [vp, vp, i64, vp], i32
+    L.hf_lanczos_import.argtypes, L.hf_lanczos_import.restype = [vp, vp, i64, vp], i32
     _lib = L
     return L
 
@@ -286,6 +290,18 @@ class Context:
         rc = self.L.hf_lanczos_update(self.h, _ptr(r), tol, C.byref(a), C.byref(b), _stream(stream))
         self._check(rc, (HF_OK, HF_EBREAKDOWN))
         return a.value, b.value, rc
+
+    def hf_lanczos_state_bytes(self):
+        b = int(self.L.hf_lanczos_state_bytes(self.h))
+        if b < 0:
+            raise HessformerError(b, "hf_lanczos_state_bytes: no iteration in progress")
+        return b
+
+    def hf_lanczos_export(self, state, capacity_bytes, stream=None):
+        self._check(self.L.hf_lanczos_export(self.h, _ptr(state), int(capacity_bytes), _stream(stream)))
+
+    def hf_lanczos_import(self, state, nbytes, stream=None):
+        self._check(self.L.hf_lanczos_import(self.h, _ptr(state), int(nbytes), _stream(stream)))
 
     def hf_lanczos_iterations(self):
         return int(self.L.hf_lanczos_iterations(self.h))

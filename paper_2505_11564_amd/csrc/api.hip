@@ -3,6 +3,7 @@
 // paper and the Ritz value / weight read-out of its Table 2).
 #include <algorithm>
 #include <cmath>
+#include <cstddef>
 #include <cstring>
 #include <mutex>
 
@@ -446,6 +447,97 @@ int32_t hf_slq_moments(const double* ritz, const double* weights, const int32_t*
       for (int i = 0; i < m_eff[p]; ++i) acc += weights[(int64_t)p * m + i] * std::pow(ritz[(int64_t)p * m + i], (double)q);
     moments[q] = acc / n_probes;
   }
+  return HF_OK;
+}
+
+// ---- Lanczos state hand-over (checkpoint / resume) --------------------------------
+// Device image: 128-byte header, then q_k, q_{k-1} (fp32[n] each, 256-byte aligned
+// starts), then the stored basis rows q_0 .. q_{rows-1} densely (n elements each) in the
+// basis precision.
+namespace {
+struct LzHeader {
+  int64_t magic, version, n, k, reorth, basis_dtype, done, rows;
+  double beta_prev;
+  int64_t pad[7];
+};
+static_assert(sizeof(LzHeader) == 128, "header size");
+constexpr int64_t kLzMagic = 0x5a4c4648;  // "HFLZ"
+int64_t lz_align(int64_t b) { return (b + 255) / 256 * 256; }
+int64_t lz_rows(const hf_ctx* c) {
+  return c->lz_reorth == HF_REORTH_FULL ? std::min<int64_t>(c->lz_k + 1, c->max_m) : 0;
+}
+int64_t lz_image_bytes(int64_t n, int64_t rows, int basis_dtype) {
+  const int64_t be = basis_dtype == HF_BF16 ? 2 : 4;
+  return 128 + 2 * lz_align(n * 4) + rows * n * be;
+}
+}  // namespace
+
+int64_t hf_lanczos_state_bytes(const hf_ctx* ctx) {
+  if (!ctx || ctx->lz_k < 0) return HF_ESTATE;
+  return lz_image_bytes(ctx->n, lz_rows(ctx), ctx->desc.basis_dtype);
+}
+
+int32_t hf_lanczos_export(hf_ctx* ctx, void* state_dev, int64_t capacity_bytes, void* hip_stream) {
+  if (!ctx) return HF_EINVAL;
+  hf_ctx* c = ctx;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (c->lz_k < 0) return c->fail(HF_ESTATE, "hf_lanczos_export: no iteration in progress");
+  if (!state_dev || ((uintptr_t)state_dev & 255)) return c->fail(HF_EINVAL, "hf_lanczos_export: state_dev must be non-NULL and 256-byte aligned");
+  const int64_t rows = lz_rows(c), need = lz_image_bytes(c->n, rows, c->desc.basis_dtype);
+  if (capacity_bytes < need) return c->fail(HF_ESHAPE, "hf_lanczos_export: buffer too small (see hf_lanczos_state_bytes)");
+  LzHeader h{};
+  h.magic = kLzMagic; h.version = 1; h.n = c->n; h.k = c->lz_k; h.reorth = c->lz_reorth;
+  h.basis_dtype = c->desc.basis_dtype; h.done = c->lz_done; h.rows = rows; h.beta_prev = 0.0;
+  char* base = (char*)state_dev;
+  CKI(hipMemcpyAsync(base, &h, sizeof(h), hipMemcpyHostToDevice, st));
+  CKI(hipStreamSynchronize(st));  // h lives on this stack frame
+  CKI(hipMemcpyAsync(base + offsetof(LzHeader, beta_prev), c->scal + S_BETA_PREV, sizeof(double), hipMemcpyDeviceToDevice, st));
+  const int64_t vb = lz_align(c->n * 4);
+  CKI(hipMemcpyAsync(base + 128, c->lz_vec[c->iq], (size_t)c->n * 4, hipMemcpyDeviceToDevice, st));
+  CKI(hipMemcpyAsync(base + 128 + vb, c->lz_vec[c->iqp], (size_t)c->n * 4, hipMemcpyDeviceToDevice, st));
+  const int64_t be = c->desc.basis_dtype == HF_BF16 ? 2 : 4;
+  if (rows > 0)
+    CKI(hipMemcpy2DAsync(base + 128 + 2 * vb, (size_t)c->n * be, c->basis, (size_t)c->ldq * be, (size_t)c->n * be, (size_t)rows,
+                         hipMemcpyDeviceToDevice, st));
+  CKI(hipStreamSynchronize(st));
+  return HF_OK;
+}
+
+int32_t hf_lanczos_import(hf_ctx* ctx, const void* state_dev, int64_t bytes, void* hip_stream) {
+  if (!ctx) return HF_EINVAL;
+  hf_ctx* c = ctx;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (!state_dev || ((uintptr_t)state_dev & 255) || bytes < 128) return c->fail(HF_EINVAL, "hf_lanczos_import: bad state_dev / bytes");
+  if (c->max_m <= 0) return c->fail(HF_ESHAPE, "hf_lanczos_import: context was created with max_m = 0");
+  LzHeader h;
+  CKI(hipMemcpyAsync(&h, state_dev, sizeof(h), hipMemcpyDeviceToHost, st));
+  CKI(hipStreamSynchronize(st));
+  if (h.magic != kLzMagic || h.version != 1) return c->fail(HF_EINVAL, "hf_lanczos_import: not a Lanczos state image");
+  if (h.n != c->n) return c->fail(HF_ESHAPE, "hf_lanczos_import: the image belongs to a model with another parameter count");
+  if (h.k < 0 || h.rows < 0 || (h.reorth != HF_REORTH_NONE && h.reorth != HF_REORTH_FULL)) return c->fail(HF_EINVAL, "hf_lanczos_import: corrupt header");
+  if (h.reorth == HF_REORTH_FULL) {
+    if (!c->basis) return c->fail(HF_ESHAPE, "hf_lanczos_import: the image holds a basis, the context was created without one");
+    if (h.basis_dtype != c->desc.basis_dtype) return c->fail(HF_ESHAPE, "hf_lanczos_import: basis precision differs from the context's");
+    if (h.rows > c->max_m || h.rows != std::min<int64_t>(h.k + 1, h.rows)) return c->fail(HF_ESHAPE, "hf_lanczos_import: more basis rows than max_m of hf_create");
+  } else if (h.rows != 0) {
+    return c->fail(HF_EINVAL, "hf_lanczos_import: corrupt header");
+  }
+  if (bytes < lz_image_bytes(h.n, h.rows, (int)h.basis_dtype)) return c->fail(HF_EINVAL, "hf_lanczos_import: image is truncated");
+  const char* base = (const char*)state_dev;
+  const int64_t vb = lz_align(c->n * 4);
+  c->iq = 0; c->iqp = 1; c->ir = 2;
+  CKI(launch_fill_f32((float*)c->scal, S_COUNT * 2, 0.f, st));
+  CKI(hipMemcpyAsync(c->scal + S_BETA_PREV, base + offsetof(LzHeader, beta_prev), sizeof(double), hipMemcpyDeviceToDevice, st));
+  CKI(hipMemcpyAsync(c->lz_vec[0], base + 128, (size_t)c->n * 4, hipMemcpyDeviceToDevice, st));
+  CKI(hipMemcpyAsync(c->lz_vec[1], base + 128 + vb, (size_t)c->n * 4, hipMemcpyDeviceToDevice, st));
+  const int64_t be = c->desc.basis_dtype == HF_BF16 ? 2 : 4;
+  if (h.rows > 0)
+    CKI(hipMemcpy2DAsync(c->basis, (size_t)c->ldq * be, base + 128 + 2 * vb, (size_t)c->n * be, (size_t)c->n * be, (size_t)h.rows,
+                         hipMemcpyDeviceToDevice, st));
+  CKI(hipStreamSynchronize(st));
+  c->lz_k = (int)h.k;
+  c->lz_reorth = (int)h.reorth;
+  c->lz_done = (int)h.done;
   return HF_OK;
 }
 

@@ -186,3 +186,78 @@ def test_lanczos_step_matches_slq_and_state_errors():
         ctx.hf_slq(pd, xd, yd, 256, 1, z, 1, 9, "full")
     assert e.value.code == hf.binding.HF_ESHAPE
     ctx.close()
+
+
+def _continue_update_only(ctx, d_dev, steps):
+    import torch
+    q = torch.empty(ctx.n, device="cuda")
+    al, be = [], []
+    for _ in range(steps):
+        ctx.hf_lanczos_get_vector(0, q)
+        r = (d_dev * q).contiguous()
+        a, b, _ = ctx.hf_lanczos_update(r, 0.0)
+        al.append(a); be.append(b)
+    return al, be
+
+
+@pytest.mark.parametrize("reorth,basis", [("none", "none"), ("full", "f32"), ("full", "bf16")])
+def test_state_export_import_continues_the_same_iteration(reorth, basis):
+    # A run interrupted after 7 iterations, moved through the state image into a
+    # fresh context and continued, yields the coefficients of the uninterrupted
+    # run bit for bit (the vector kernels are deterministic).
+    import torch
+    import paper_2505_11564_amd as hf
+    model = si._gpt(1, 40, 2, 72, 1001, 33)
+    a_ctx = hf.Context(model, 1, 20, "f32", basis)
+    n = a_ctx.n
+    rng = np.random.default_rng(9)
+    d_dev = _dev(rng.uniform(-2, 3, n).astype(np.float32))
+    a_ctx.hf_lanczos_init(_dev(si.make_probe(n, 1)), reorth)
+    first = _continue_update_only(a_ctx, d_dev, 7)
+    nbytes = a_ctx.hf_lanczos_state_bytes()
+    image = torch.empty(nbytes + 256, dtype=torch.uint8, device="cuda")
+    a_ctx.hf_lanczos_export(image, nbytes)
+    rest = _continue_update_only(a_ctx, d_dev, 9)
+    a_ctx.close()
+    b_ctx = hf.Context(model, 1, 20, "f32", basis)
+    host_copy = image.cpu()                       # the image is plain memory: through the host and back
+    image2 = host_copy.cuda()
+    b_ctx.hf_lanczos_import(image2, nbytes)
+    assert b_ctx.hf_lanczos_iterations() == 7
+    resumed = _continue_update_only(b_ctx, d_dev, 9)
+    assert resumed[0] == rest[0] and resumed[1] == rest[1]
+    # against the oracle's uninterrupted run, first coefficients
+    dv = d_dev.cpu().numpy().astype(np.float64)
+    ao, bo, _ = olz.lanczos(lambda q: dv * q, si.make_probe(n, 1).astype(np.float64), 16, reorth)
+    got_a = np.array(first[0] + resumed[0])
+    tol = 2e-2 if basis == "bf16" else 1e-4
+    np.testing.assert_allclose(got_a[:4], ao[:4], rtol=tol, atol=tol)
+    b_ctx.close()
+
+
+def test_state_image_errors():
+    import torch
+    import paper_2505_11564_amd as hf
+    model = si._gpt(1, 40, 2, 72, 1001, 33)
+    ctx = hf.Context(model, 1, 8, "f32", "f32")
+    with pytest.raises(hf.HessformerError):
+        ctx.hf_lanczos_state_bytes()              # nothing in progress
+    ctx.hf_lanczos_init(_dev(si.make_probe(ctx.n, 0)), "full")
+    nbytes = ctx.hf_lanczos_state_bytes()
+    image = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+    with pytest.raises(hf.HessformerError):
+        ctx.hf_lanczos_export(image, nbytes - 1)  # too small
+    ctx.hf_lanczos_export(image, nbytes)
+    with pytest.raises(hf.HessformerError):
+        ctx.hf_lanczos_import(image, 100)         # truncated
+    other = hf.Context(si._gpt(1, 48, 2, 72, 1001, 33), 1, 8, "f32", "f32")
+    with pytest.raises(hf.HessformerError):
+        other.hf_lanczos_import(image, nbytes)    # another parameter count
+    nobasis = hf.Context(model, 1, 8, "f32", "none")
+    with pytest.raises(hf.HessformerError):
+        nobasis.hf_lanczos_import(image, nbytes)  # the image holds a basis
+    junk = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+    with pytest.raises(hf.HessformerError):
+        ctx.hf_lanczos_import(junk, nbytes)       # not an image
+    for c in (ctx, other, nobasis):
+        c.close()
