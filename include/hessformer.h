@@ -74,9 +74,11 @@ typedef enum {
 typedef enum { HF_ARCH_MLP = 0, HF_ARCH_GPT = 1, HF_ARCH_LLAMA = 2 } hf_arch;
 typedef enum { HF_F32 = 0, HF_BF16 = 1, HF_NONE = 2 /* basis_dtype only: store no basis */ } hf_dtype;
 typedef enum { HF_REORTH_NONE = 0, HF_REORTH_FULL = 1 } hf_reorth;
+typedef enum { HF_ACT_GELU_ERF = 0, HF_ACT_GELU_TANH = 1 } hf_activation;
 
 /* Model description.  MLP uses mlp_*; GPT/LLAMA use the transformer fields.
- * GPT: pre-LayerNorm decoder, learned positions, erf GELU, causal attention
+ * GPT: pre-LayerNorm decoder, learned positions, GELU (erf or tanh form, see
+ * `activation`), causal attention
  * with scale 1/sqrt(dh).  LLAMA: RMSNorm, rotary positions on pairs
  * (i, i + dh/2) with base rope_theta, SwiGLU, no biases.
  * param_dtype HF_BF16: weights are bf16 MFMA operands, activations fed to
@@ -92,6 +94,8 @@ typedef struct {
   int32_t param_dtype;    /* hf_dtype of params_dev */
   int32_t basis_dtype;    /* hf_dtype of the stored Lanczos basis; HF_NONE: no basis is
                              allocated and only HF_REORTH_NONE iterations can run */
+  int32_t activation;     /* GPT only: HF_ACT_GELU_ERF (0) or HF_ACT_GELU_TANH (1), the form
+                             a/2 (1 + tanh(sqrt(2/pi)(a + 0.044715 a^3))) */
 } hf_model_desc;
 
 /* ---- host-only helpers (no GPU needed) ---------------------------------- */

@@ -11,7 +11,8 @@ verifies against PyTorch's autograd run exactly as Algorithm 1 is written.
 Architectures (the paper only says "HuggingFace causal LM .loss"; these are the
 standard definitions of the shapes the workloads name):
   mlp   : h = tanh(x W1 + b1); z = h W2 + b2
-  gpt   : pre-LayerNorm decoder, learned positions, erf-GELU, optional tied head
+  gpt   : pre-LayerNorm decoder, learned positions, erf-GELU (model["act"] ==
+          "gelu_tanh": the tanh form), optional tied head
   llama : RMSNorm, rotary positions (half-split pairs), SwiGLU, no biases
 Loss: mean softmax cross-entropy over positions with label >= 0 (next-token
 prediction); MLP: mean over the samples.
@@ -135,7 +136,8 @@ def _gpt(model, P, V, tokens, labels):
         x, x_t = x + y, x_t + y_t
         m, m_t, c_ln2 = ops.layernorm_fwd(x, x_t, P[p + "ln2.g"], V[p + "ln2.g"], P[p + "ln2.b"], V[p + "ln2.b"], eps)
         f, f_t, c_fc = ops.linear_fwd(m, m_t, P[p + "Wfc"], V[p + "Wfc"], P[p + "bfc"], V[p + "bfc"])
-        g, g_t, c_act = ops.gelu_fwd(f, f_t)
+        tanh_form = model.get("act", "gelu_erf") == "gelu_tanh"
+        g, g_t, c_act = (ops.gelu_tanh_fwd if tanh_form else ops.gelu_fwd)(f, f_t)
         y, y_t, c_pr = ops.linear_fwd(g, g_t, P[p + "Wproj"], V[p + "Wproj"], P[p + "bproj"], V[p + "bproj"])
         x, x_t = x + y, x_t + y_t
         caches.append((c_ln1, c_qkv, c_att, c_o, c_ln2, c_fc, c_act, c_pr))
@@ -153,7 +155,7 @@ def _gpt(model, P, V, tokens, labels):
         p = f"h{l}."
         c_ln1, c_qkv, c_att, c_o, c_ln2, c_fc, c_act, c_pr = caches[l]
         dg, dg_t, G[p + "Wproj"], U[p + "Wproj"], G[p + "bproj"], U[p + "bproj"] = ops.linear_bwd(dx, dx_t, c_pr)
-        df, df_t = ops.gelu_bwd(dg, dg_t, c_act)
+        df, df_t = (ops.gelu_tanh_bwd if model.get("act", "gelu_erf") == "gelu_tanh" else ops.gelu_bwd)(dg, dg_t, c_act)
         dm, dm_t, G[p + "Wfc"], U[p + "Wfc"], G[p + "bfc"], U[p + "bfc"] = ops.linear_bwd(df, df_t, c_fc)
         r, r_t, G[p + "ln2.g"], U[p + "ln2.g"], G[p + "ln2.b"], U[p + "ln2.b"] = ops.layernorm_bwd(dm, dm_t, c_ln2)
         dx, dx_t = dx + r, dx_t + r_t

@@ -78,6 +78,27 @@ def gelu_bwd(dy, dy_t, cache):
     return f1 * dy, f1 * dy_t + f2 * a_t * dy
 
 
+_GT_C = np.sqrt(2.0 / np.pi)
+_GT_A = 0.044715
+
+
+def gelu_tanh_fwd(a, a_t):
+    """tanh-form GELU: f(a) = a/2 (1 + tanh u), u = sqrt(2/pi) (a + 0.044715 a^3)."""
+    t = np.tanh(_GT_C * (a + _GT_A * a ** 3))
+    u1 = _GT_C * (1.0 + 3.0 * _GT_A * a * a)
+    t1 = (1.0 - t * t) * u1
+    f1 = 0.5 * (1.0 + t) + 0.5 * a * t1
+    return 0.5 * a * (1.0 + t), f1 * a_t, (a, a_t, f1, t, u1, t1)
+
+
+def gelu_tanh_bwd(dy, dy_t, cache):
+    a, a_t, f1, t, u1, t1 = cache
+    u2 = 6.0 * _GT_A * _GT_C * a
+    t2 = (1.0 - t * t) * (u2 - 2.0 * t * u1 * u1)
+    f2 = t1 + 0.5 * a * t2
+    return f1 * dy, f1 * dy_t + f2 * a_t * dy
+
+
 def swiglu_fwd(g, g_t, u, u_t):
     """y = silu(g) * u, silu(g) = g sigmoid(g)."""
     sg = 1.0 / (1.0 + np.exp(-g))

@@ -17,6 +17,7 @@ HF_EINVAL, HF_ENOMEM, HF_EDEVICE, HF_ESHAPE, HF_ESTATE = -1, -2, -3, -4, -5
 HF_ARCH = {"mlp": 0, "gpt": 1, "llama": 2}
 HF_DTYPE = {"f32": 0, "bf16": 1, "none": 2}
 HF_REORTH = {"none": 0, "full": 1}
+HF_ACT = {"gelu_erf": 0, "gelu_tanh": 1}
 
 EXPORTS = [
     "hf_desc_num_params", "hf_layout_count", "hf_layout_entry", "hf_tridiag_readout", "hf_version",
@@ -33,7 +34,7 @@ class hf_model_desc(C.Structure):
                 ("d_ff", C.c_int32), ("vocab", C.c_int32), ("max_seq", C.c_int32), ("mlp_in", C.c_int32),
                 ("mlp_hidden", C.c_int32), ("mlp_out", C.c_int32), ("tie_embeddings", C.c_int32),
                 ("norm_eps", C.c_float), ("rope_theta", C.c_float), ("param_dtype", C.c_int32),
-                ("basis_dtype", C.c_int32)]
+                ("basis_dtype", C.c_int32), ("activation", C.c_int32)]
 
 
 class HessformerError(RuntimeError):
@@ -113,6 +114,7 @@ def make_desc(model, param_dtype="f32", basis_dtype="f32"):
     d.rope_theta = float(model["rope_theta"])
     d.param_dtype = HF_DTYPE[param_dtype]
     d.basis_dtype = HF_DTYPE[basis_dtype]
+    d.activation = HF_ACT[model.get("act", "gelu_erf")]
     return d
 
 

@@ -41,6 +41,7 @@ int hf::build_layout(const hf_model_desc& d, std::vector<LayoutEntry>& out, std:
   if (d.d_model % d.n_head) return bad("d_model must be a multiple of n_head");
   if (d.d_model > 8192) return bad("d_model > 8192 is not supported by the norm kernels");
   if (!(d.norm_eps > 0.f)) return bad("norm_eps must be positive");
+  if (d.activation != HF_ACT_GELU_ERF && d.activation != HF_ACT_GELU_TANH) return bad("activation must be HF_ACT_GELU_ERF or HF_ACT_GELU_TANH");
   const int64_t D = d.d_model, F = d.d_ff, V = d.vocab;
   if (d.arch == HF_ARCH_GPT) {
     add("wte", V, D); add("wpe", d.max_seq, D);
@@ -350,6 +351,7 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
   const int rms = llama ? 1 : 0;
   const float eps = desc.norm_eps;
   const float cs = 1.f / sqrtf((float)dh);
+  const int gelu_kind = desc.activation == HF_ACT_GELU_TANH ? ACT_GELU_TANH : ACT_GELU;
   const int64_t e = bf ? 2 : 4;
   Lin L{this, params, v, out, st, bf};
   auto at = [&](void* p, int64_t elems) -> void* { return (char*)p + elems * e; };
@@ -455,7 +457,7 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
                        rms ? nullptr : v + o.n2b, T, D, eps, b.m, b.m_t, a_lo, b.st2, st));
     if (!llama) {
       if ((rc = L.fwd(b.m, b.m_t, T, D, F, D, o.wfc, o.bfc, b.f, b.f_t, F, bf, nullptr, nullptr, 0, -1, a_lo, f_lo))) return rc;
-      CK(launch_act_fwd(bf, ACT_GELU, b.f, b.f_t, f_lo, b.g, b.g_t, g_lo, (int64_t)T * F, st));
+      CK(launch_act_fwd(bf, gelu_kind, b.f, b.f_t, f_lo, b.g, b.g_t, g_lo, (int64_t)T * F, st));
       if ((rc = L.fwd(b.g, b.g_t, T, F, D, F, o.wproj, o.bproj, xn, xn_t, D, 0, b.x2, b.x2_t, 0, -1, g_lo))) return rc;
     } else {
       if ((rc = L.fwd(b.m, b.m_t, T, D, F, D, o.wgate, -1, b.f, b.f_t, F, bf, nullptr, nullptr, 0, -1, a_lo, f_lo))) return rc;
@@ -500,7 +502,7 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
     if (!llama) {
       if ((rc = L.bwd_dw(b.g, b.g_t, dxb, dxb_t, T, F, D, F, D, o.wproj, o.bproj, dx_t, 0))) return rc;
       if ((rc = L.bwd_dx(dxb, dxb_t, T, F, D, D, o.wproj, dg, dg_t, F, bf))) return rc;
-      CK(launch_act_bwd(bf, ACT_GELU, b.f, b.f_t, dg, dg_t, dg, dg_t, (int64_t)T * F, st));
+      CK(launch_act_bwd(bf, gelu_kind, b.f, b.f_t, dg, dg_t, dg, dg_t, (int64_t)T * F, st));
       if ((rc = L.bwd_dw(b.m, b.m_t, dg, dg_t, T, D, F, D, F, o.wfc, o.bfc, dg_t, bf))) return rc;
       if ((rc = L.bwd_dx(dg, dg_t, T, D, F, F, o.wfc, tmpd, tmpd_t, D, 0))) return rc;
     } else {

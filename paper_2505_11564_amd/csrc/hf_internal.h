@@ -125,7 +125,7 @@ hipError_t launch_norm_bwd(int bf, int rms, const float* dy, const float* dy_t, 
                            const float* stats, const void* gam, const float* gam_t, int T, int d, int accumulate,
                            float* dx, float* dx_t, float* hv_gam, float* hv_bet, float* part, hipStream_t st);
 
-enum Act { ACT_TANH = 0, ACT_GELU = 1 };
+enum Act { ACT_TANH = 0, ACT_GELU = 1, ACT_GELU_TANH = 2 };
 // a_lo / y_lo (nullable): low-order halves of the primal input / output.
 hipError_t launch_act_fwd(int bf, int act, const void* a, const void* a_t, const void* a_lo, void* y, void* y_t,
                           void* y_lo, int64_t n, hipStream_t st);

@@ -618,6 +618,15 @@ __device__ __forceinline__ void act_derivs(int act, float a, float& f, float& f1
   if (act == ACT_TANH) {
     const float t = tanhf(a);
     f = t; f1 = 1.f - t * t; f2 = -2.f * t * f1;
+  } else if (act == ACT_GELU_TANH) {
+    // f = a/2 (1 + t), t = tanh u, u = c (a + k a^3):  t' = (1 - t^2) u',
+    // t'' = (1 - t^2)(u'' - 2 t u'^2),  f' = (1 + t)/2 + a t'/2,  f'' = t' + a t''/2
+    const float c = 0.79788456080286536f, k = 0.044715f;
+    const float t = tanhf(c * (a + k * a * a * a));
+    const float u1 = c * (1.f + 3.f * k * a * a), u2 = 6.f * k * c * a;
+    const float s = 1.f - t * t;
+    const float t1 = s * u1, t2 = s * (u2 - 2.f * t * u1 * u1);
+    f = 0.5f * a * (1.f + t); f1 = 0.5f * (1.f + t) + 0.5f * a * t1; f2 = t1 + 0.5f * a * t2;
   } else {  // erf GELU: f = a Phi(a), f' = Phi + a phi, f'' = phi (2 - a^2)
     const float Phi = 0.5f * (1.f + erff(a * 0.70710678118654752f));
     const float phi = 0.39894228040143268f * __expf(-0.5f * a * a);

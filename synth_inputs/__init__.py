@@ -25,9 +25,9 @@ def _mlp(mlp_in, hidden, out):
                 tie_embeddings=0, norm_eps=1e-5, rope_theta=10000.0)
 
 
-def _gpt(n_layer, d, h, ff, vocab, max_seq, tie=1):
+def _gpt(n_layer, d, h, ff, vocab, max_seq, tie=1, act="gelu_erf"):
     return dict(arch="gpt", n_layer=n_layer, d_model=d, n_head=h, d_ff=ff,
-                vocab=vocab, max_seq=max_seq, tie_embeddings=tie,
+                vocab=vocab, max_seq=max_seq, tie_embeddings=tie, act=act,
                 mlp_in=0, mlp_hidden=0, mlp_out=0, norm_eps=1e-5,
                 rope_theta=10000.0)
 

@@ -53,7 +53,8 @@ def forward_loss(model, P, inputs, labels):
             o = F.scaled_dot_product_attention(q, k, v, is_causal=True)
             x = x + o.transpose(1, 2).reshape(B, S, d) @ P[p + "Wo"] + P[p + "bo"]
             y = F.layer_norm(x, (d,), P[p + "ln2.g"], P[p + "ln2.b"], eps)
-            x = x + F.gelu(y @ P[p + "Wfc"] + P[p + "bfc"]) @ P[p + "Wproj"] + P[p + "bproj"]
+            approx = "tanh" if model.get("act", "gelu_erf") == "gelu_tanh" else "none"
+            x = x + F.gelu(y @ P[p + "Wfc"] + P[p + "bfc"], approximate=approx) @ P[p + "Wproj"] + P[p + "bproj"]
         x = F.layer_norm(x, (d,), P["lnf.g"], P["lnf.b"], eps)
         z = x @ (P["wte"].T if model["tie_embeddings"] else P["lm_head"])
     else:

@@ -22,6 +22,7 @@ SHAPES = {
     "llama_mid": dict(model=si._llama(2, 256, 4, 344, 777, 136), batch=2, seq=136, tokens="zipf"),
     # sequence length a multiple of 8 and head width of 32: in bf16 mode the scores take the fused
     # attention epilogues (two column tiles, the second one ragged)
+    "gpt_gelu_tanh": dict(model=si._gpt(2, 64, 2, 136, 301, 40, act="gelu_tanh"), batch=2, seq=40, tokens="zipf"),
     "gpt_fused": dict(model=si._gpt(2, 128, 4, 264, 517, 200), batch=2, seq=200, tokens="zipf"),
 }
 

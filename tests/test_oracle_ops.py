@@ -59,9 +59,10 @@ def test_linear():
     np.testing.assert_allclose(y, ref, rtol=1e-13)
 
 
-@pytest.mark.parametrize("name", ["tanh", "gelu"])
+@pytest.mark.parametrize("name", ["tanh", "gelu", "gelu_tanh"])
 def test_pointwise(name):
-    f, b = (ops.tanh_fwd, ops.tanh_bwd) if name == "tanh" else (ops.gelu_fwd, ops.gelu_bwd)
+    f, b = {"tanh": (ops.tanh_fwd, ops.tanh_bwd), "gelu": (ops.gelu_fwd, ops.gelu_bwd),
+            "gelu_tanh": (ops.gelu_tanh_fwd, ops.gelu_tanh_bwd)}[name]
 
     def fwd(xs, xts):
         y, yt, c = f(xs[0], xts[0])
@@ -72,7 +73,8 @@ def test_pointwise(name):
         return [dx], [dxt]
     x = rnd(6, 7) * 2
     check_op(fwd, bwd, [x], [rnd(6, 7)])
-    ref = (torch.tanh if name == "tanh" else F.gelu)(torch.tensor(x)).numpy()
+    tfn = {"tanh": torch.tanh, "gelu": F.gelu, "gelu_tanh": lambda t: F.gelu(t, approximate="tanh")}[name]
+    ref = tfn(torch.tensor(x)).numpy()
     np.testing.assert_allclose(f(x, x)[0], ref, rtol=1e-12, atol=1e-15)
 
 
