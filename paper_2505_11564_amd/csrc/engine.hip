@@ -162,7 +162,7 @@ int hf_ctx::plan_and_alloc() {
     if (desc.basis_dtype != HF_NONE) pl.add(basis, (int64_t)max_m * ldq * (desc.basis_dtype == HF_BF16 ? 2 : 4));
     pl.add(scal, S_COUNT * 8);
     pl.add(cvec, (int64_t)max_m * 8);
-    pl.add(partials, (int64_t)LZ_NBLK * max_m * 8);
+    pl.add(partials, std::max<int64_t>((int64_t)LZ_NBLK * max_m, LZ_NBLK_VEC) * 8);
   }
   arena_bytes = pl.off;
   hipError_t e1 = hipMalloc((void**)&arena, (size_t)arena_bytes);

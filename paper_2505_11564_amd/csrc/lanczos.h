@@ -16,7 +16,8 @@ enum {
   S_COUNT = 8
 };
 
-constexpr int LZ_NBLK = 2048;  // upper bound on blocks (= partial sums) per reduction
+constexpr int LZ_NBLK = 2048;  // upper bound on blocks (= partial sums per basis vector) of the re-orthogonalisation kernels
+constexpr int LZ_NBLK_VEC = 4096;  // upper bound on blocks (= partial sums) of the three-term kernels
 
 hipError_t lz_norm_q0(const float* z, int64_t n, double* scal, double* partials, hipStream_t st);
 hipError_t lz_axpy_dot(float* r, const float* q, const float* qp, int64_t n, int use_prev, double* scal,

@@ -45,8 +45,12 @@ __global__ __launch_bounds__(256) void lz_fused_kernel(float* __restrict__ r, co
   double acc = 0.0;
   const int64_t n4 = n >> 2;
   const int64_t stride = (int64_t)gridDim.x * 256;
+  // each block streams one contiguous range (measured faster than a grid-stride walk for these
+  // read-modify-write passes once the grid has 4096 blocks)
+  const int64_t per = (n4 + gridDim.x - 1) / gridDim.x;
+  const int64_t i_end = min(n4, (int64_t)(blockIdx.x + 1) * per);
 #pragma unroll 2
-  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += stride) {
+  for (int64_t i = (int64_t)blockIdx.x * per + threadIdx.x; i < i_end; i += 256) {
     if (MODE == 0) {
       const float4 a = ((const float4*)q)[i];
       acc += (double)(a.x * a.x + a.y * a.y) + (double)(a.z * a.z + a.w * a.w);
@@ -116,8 +120,10 @@ __global__ __launch_bounds__(256) void lz_scale_kernel(const float* src, float* 
   const float inv = (float)(1.0 / scal[idx]);
   const int64_t n4 = n >> 2;
   const int64_t stride = (int64_t)gridDim.x * 256;
+  const int64_t per = (n4 + gridDim.x - 1) / gridDim.x;
+  const int64_t i_end = min(n4, (int64_t)(blockIdx.x + 1) * per);
 #pragma unroll 2
-  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += stride) {
+  for (int64_t i = (int64_t)blockIdx.x * per + threadIdx.x; i < i_end; i += 256) {
     float4 v = ((const float4*)src)[i];
     v.x *= inv; v.y *= inv; v.z *= inv; v.w *= inv;
     ((float4*)dst)[i] = v;
@@ -347,7 +353,7 @@ __global__ void lz_widen_kernel(const BT* src, float* dst, int64_t n) {
 
 static int vec_blocks(int64_t n) {
   const int64_t want = (n / 4 + 255) / 256;
-  return (int)std::max<int64_t>(1, std::min<int64_t>(want, LZ_NBLK));
+  return (int)std::max<int64_t>(1, std::min<int64_t>(want, LZ_NBLK_VEC));
 }
 
 hipError_t lz_norm_q0(const float* z, int64_t n, double* scal, double* partials, hipStream_t st) {
