@@ -406,10 +406,14 @@ hipError_t launch_gemm_mfma(GemmP p, int nb, int allow_splitk, int force_cfg, in
   const int64_t nt = tiles(bm, bn);
   int ks = 1;
   if (force_ks > 0) ks = force_ks;
-  else if (allow_splitk && !p.out_bf16 && !p.klimit && nt < 384) {
+  else if (allow_splitk && !p.out_bf16 && !p.klimit) {
+    // Split k only while all blocks of the split product are resident at once (256 CUs, one block
+    // of a 256-wide tile or two of the others each) and every split keeps at least 8 slabs: a split
+    // costs a zero-fill and an atomic read-modify-write of C per part, which for short k outweighs
+    // the parallelism (4096 x 4096 x 512: 45 us unsplit, 143 us split in two).
+    const int64_t slots = (cfg == 0 || cfg == 3) ? 256 : 512;
     const int slabs = p.nterm * (p.K / 64);
-    ks = (int)std::min<int64_t>(std::max<int64_t>(1, (512 + nt - 1) / nt), std::max(1, slabs / 4));
-    ks = std::min(ks, 16);
+    if (nt * 2 <= slots) ks = (int)std::min<int64_t>(std::min<int64_t>(slots / nt, std::max(1, slabs / 8)), 16);
   }
   if (ks > 1) {
     // accumulate with atomics on top of Cadd (or zero)
