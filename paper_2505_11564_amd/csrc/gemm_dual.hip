@@ -520,11 +520,14 @@ static hipError_t launch_dual_k(const DualP& p, dim3 grid, hipStream_t st) {
   hipLaunchKernelGGL(kern, grid, dim3(256), smem, st, p);
   return hipGetLastError();
 }
+// A launch of at most one block per CU cannot hide a slab's load latency behind another block, so
+// it keeps two or three slabs in flight instead of one (the LDS is its own anyway).
 template <bool TA, bool TB>
 static hipError_t launch_dual_one(const DualP& p, dim3 grid, hipStream_t st) {
-  if (p.Blo) return launch_dual_k<TA, TB, 6, 2, EPI_NONE>(p, grid, st);
-  if (p.Alo) return launch_dual_k<TA, TB, 5, 2, EPI_NONE>(p, grid, st);
-  return launch_dual_k<TA, TB, 4, 2, EPI_NONE>(p, grid, st);
+  const bool deep = (int64_t)grid.x * grid.y <= 256 && p.K >= 256;
+  if (p.Blo) return deep ? launch_dual_k<TA, TB, 6, 3, EPI_NONE>(p, grid, st) : launch_dual_k<TA, TB, 6, 2, EPI_NONE>(p, grid, st);
+  if (p.Alo) return deep ? launch_dual_k<TA, TB, 5, 3, EPI_NONE>(p, grid, st) : launch_dual_k<TA, TB, 5, 2, EPI_NONE>(p, grid, st);
+  return deep ? launch_dual_k<TA, TB, 4, 4, EPI_NONE>(p, grid, st) : launch_dual_k<TA, TB, 4, 2, EPI_NONE>(p, grid, st);
 }
 // Attention epilogues: A B^T products with k = head dimension.  Four operand
 // tiles per stage and two stages (optional low-order terms run as further
