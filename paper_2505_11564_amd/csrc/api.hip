@@ -391,21 +391,33 @@ int32_t hf_column_stats(hf_ctx* ctx, const float* h_dev, int64_t n, const float*
   if (n_bins < 1 || n_bins > CS_MAX_BINS) return c->fail(HF_EINVAL, "hf_column_stats: n_bins must be in [1, 256]");
   if ((n_thresholds > 0 && (!thresholds || !below)) || !hist || !max_abs) return c->fail(HF_EINVAL, "hf_column_stats: NULL argument");
   if (n >= ((int64_t)1 << 40)) return c->fail(HF_ESHAPE, "hf_column_stats: n must be below 2^40");
+  // sorted copy of the thresholds (padded with +inf), and where each caller threshold went
   ColThresholds thr;
-  for (int k = 0; k < CS_MAX_THRESHOLDS; ++k) thr.t[k] = k < n_thresholds ? thresholds[k] : 0.f;
+  int order[CS_MAX_THRESHOLDS];
+  for (int k = 0; k < n_thresholds; ++k) order[k] = k;
+  std::stable_sort(order, order + n_thresholds, [&](int a, int b) { return thresholds[a] < thresholds[b]; });
+  for (int k = 0; k < CS_MAX_THRESHOLDS; ++k) thr.t[k] = k < n_thresholds ? thresholds[order[k]] : INFINITY;
+  for (int k = 0; k < n_thresholds; ++k)
+    if (thresholds[k] != thresholds[k]) return c->fail(HF_EINVAL, "hf_column_stats: a threshold is NaN");
   unsigned long long hs[CS_STATS_WORDS];
   CKI(launch_fill_f32((float*)c->stats_dev, CS_STATS_WORDS * 2, 0.f, st));
   if (n > 0) CKI(launch_colstats_pass1(h_dev, n, thr, n_thresholds, c->stats_dev, st));
   CKI(hipMemcpyAsync(hs, c->stats_dev, 32 * 8, hipMemcpyDeviceToHost, st));
   CKI(hipStreamSynchronize(st));
-  for (int k = 0; k < n_thresholds; ++k) below[k] = (int64_t)hs[k];
+  // |h_i| < t_k (sorted) exactly when the entry reaches at most k thresholds: prefix sums of the buckets
+  unsigned long long run = 0, valid = 0;
+  for (int k = 0; k <= CS_MAX_THRESHOLDS; ++k) valid += hs[k];
+  for (int k = 0; k < n_thresholds; ++k) {
+    run += hs[k];
+    below[order[k]] = (int64_t)run;
+  }
   float mx;
-  const unsigned bits = (unsigned)hs[16];
+  const unsigned bits = (unsigned)hs[24];
   memcpy(&mx, &bits, 4);
   *max_abs = mx;
   for (int k = 0; k < n_bins; ++k) hist[k] = 0;
   if (!(mx > 0.f)) {
-    hist[0] = (int64_t)hs[17];  // a column of zeros: every entry in the first bin
+    hist[0] = (int64_t)valid;  // a column of zeros: every entry in the first bin
     return HF_OK;
   }
   const volatile float nbf = (float)n_bins;

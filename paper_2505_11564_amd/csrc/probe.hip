@@ -32,9 +32,9 @@ hipError_t launch_scale_add(float* h, const float* u, float w, int first, int64_
 }
 
 // ---- column statistics --------------------------------------------------------
-// stats (uint64): [0, 16) counts below each threshold; [16] bit pattern of the
-// largest |h_i| (non-negative floats order like their bit patterns); [17] number
-// of entries that are not NaN; [32, 32 + n_bins) histogram.
+// stats (uint64): [0, 17) bucket counts (bucket b: entries that reach exactly b of the sorted
+// thresholds), [17] NaN entries; [24] bit pattern of the largest |h_i| (non-negative floats order
+// like their bit patterns); [32, 32 + n_bins) histogram.
 
 __device__ __forceinline__ unsigned wave_sum_u32(unsigned v) {
 #pragma unroll
@@ -42,21 +42,36 @@ __device__ __forceinline__ unsigned wave_sum_u32(unsigned v) {
   return v;
 }
 
+// Thresholds arrive sorted ascending (the host sorts them and undoes the permutation), so an
+// entry's contribution is one bucket index b = #{k : |h_i| >= t_k}, found by a branch-free binary
+// search over the (padded to 16, +inf) thresholds; each thread counts buckets in its own LDS
+// column (no atomics, no bank conflicts: counter [bucket][thread]), and the per-threshold counts are
+// the prefix sums of the bucket counts, formed on the host.  NaN entries land in bucket 16.
 __global__ __launch_bounds__(256) void colstats_pass1_kernel(const float* __restrict__ h, int64_t n, ColThresholds thr,
                                                             int nt, unsigned long long* stats) {
-  __shared__ unsigned red[4][CS_MAX_THRESHOLDS + 1];
+  __shared__ unsigned cnt[18][256];
   __shared__ float redm[4];
-  unsigned cnt[CS_MAX_THRESHOLDS];
+  __shared__ float lt[CS_MAX_THRESHOLDS];
 #pragma unroll
-  for (int k = 0; k < CS_MAX_THRESHOLDS; ++k) cnt[k] = 0;
-  unsigned valid = 0;
+  for (int k = 0; k < 18; ++k) cnt[k][threadIdx.x] = 0;
+  if (threadIdx.x < CS_MAX_THRESHOLDS) lt[threadIdx.x] = thr.t[threadIdx.x];
+  __syncthreads();
   float mx = 0.f;
   auto take = [&](float x) {
     const float a = fabsf(x);
-    if (a == a) { ++valid; mx = fmaxf(mx, a); }
-#pragma unroll
-    for (int k = 0; k < CS_MAX_THRESHOLDS; ++k)
-      if (k < nt && a < thr.t[k]) ++cnt[k];
+    int b;
+    if (a == a) {
+      mx = fmaxf(mx, a);
+      // binary search: b in [0, 16]
+      b = a >= lt[7] ? 8 : 0;
+      b += a >= lt[b + 3] ? 4 : 0;
+      b += a >= lt[b + 1] ? 2 : 0;
+      b += a >= lt[b] ? 1 : 0;
+      b += (b == 15 && a >= lt[15]) ? 1 : 0;
+    } else {
+      b = 17;
+    }
+    cnt[b][threadIdx.x] += 1;
   };
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -72,27 +87,22 @@ __global__ __launch_bounds__(256) void colstats_pass1_kernel(const float* __rest
   for (int64_t i = head + (n4 << 2) + gid; i < n; i += stride) take(h[i]);
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-#pragma unroll
-  for (int k = 0; k < CS_MAX_THRESHOLDS; ++k) {
-    const unsigned s = wave_sum_u32(cnt[k]);
-    if (lane == 0) red[wave][k] = s;
-  }
   {
-    const unsigned s = wave_sum_u32(valid);
-    if (lane == 0) red[wave][CS_MAX_THRESHOLDS] = s;
     float m = mx;
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_down(m, o, 64));
     if (lane == 0) redm[wave] = m;
   }
   __syncthreads();
-  if (threadIdx.x <= CS_MAX_THRESHOLDS) {
-    const unsigned long long s = (unsigned long long)red[0][threadIdx.x] + red[1][threadIdx.x] + red[2][threadIdx.x] + red[3][threadIdx.x];
-    if (s) atomicAdd(stats + (threadIdx.x < CS_MAX_THRESHOLDS ? threadIdx.x : 17), s);
+  // bucket totals of the block: thread k < 18 sums row k
+  if (threadIdx.x < 18) {
+    unsigned long long s = 0;
+    for (int t = 0; t < 256; ++t) s += cnt[threadIdx.x][(t + threadIdx.x) & 255];
+    if (s) atomicAdd(stats + threadIdx.x, s);
   }
   if (threadIdx.x == 0) {
     const float m = fmaxf(fmaxf(redm[0], redm[1]), fmaxf(redm[2], redm[3]));
-    atomicMax((unsigned*)(stats + 16), __float_as_uint(m));
+    atomicMax((unsigned*)(stats + 24), __float_as_uint(m));
   }
 }
 
@@ -104,12 +114,21 @@ __global__ __launch_bounds__(256) void colstats_hist_kernel(const float* __restr
   __shared__ unsigned lh[CS_MAX_BINS];
   for (int i = threadIdx.x; i < nb; i += 256) lh[i] = 0;
   __syncthreads();
+  // consecutive entries of a thread that fall in the same bin are counted in a register and added
+  // to LDS once per run: a column that is nearly all zeros (the case the paper reports) would
+  // otherwise send every lane to the same LDS address
+  int last = -1;
+  unsigned run = 0;
   auto take = [&](float x) {
     const float a = fabsf(x);
     if (a == a) {
       const float s = __fmul_rn(a, scale);
-      int b = (s == s) ? (int)fminf(floorf(s), (float)(nb - 1)) : nb - 1;
-      atomicAdd(&lh[b], 1u);
+      const int b = (s == s) ? (int)fminf(floorf(s), (float)(nb - 1)) : nb - 1;
+      if (b == last) { ++run; }
+      else {
+        if (run) atomicAdd(&lh[last], run);
+        last = b; run = 1;
+      }
     }
   };
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
@@ -123,6 +142,7 @@ __global__ __launch_bounds__(256) void colstats_hist_kernel(const float* __restr
     take(x.x); take(x.y); take(x.z); take(x.w);
   }
   for (int64_t i = head + (n4 << 2) + gid; i < n; i += stride) take(h[i]);
+  if (run) atomicAdd(&lh[last], run);
   __syncthreads();
   for (int i = threadIdx.x; i < nb; i += 256)
     if (lh[i]) atomicAdd(hist + i, (unsigned long long)lh[i]);
