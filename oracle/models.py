@@ -13,7 +13,8 @@ standard definitions of the shapes the workloads name):
   mlp   : h = tanh(x W1 + b1); z = h W2 + b2
   gpt   : pre-LayerNorm decoder, learned positions, erf-GELU (model["act"] ==
           "gelu_tanh": the tanh form), optional tied head
-  llama : RMSNorm, rotary positions (half-split pairs), SwiGLU, no biases
+  llama : RMSNorm, rotary positions (half-split pairs), SwiGLU, no biases;
+          model["n_kv_head"] < n_head: grouped-query attention
 Loss: mean softmax cross-entropy over positions with label >= 0 (next-token
 prediction); MLP: mean over the samples.
 """
@@ -49,10 +50,11 @@ def layout(model):
             if not model["tie_embeddings"]:
                 names += [("lm_head", (d, V))]
         elif a == "llama":
+            dkv = d // model["n_head"] * model.get("n_kv_head", model["n_head"])
             names = [("wte", (V, d))]
             for l in range(L):
                 names += [(f"h{l}.rms1.g", (d,)), (f"h{l}.Wq", (d, d)),
-                          (f"h{l}.Wk", (d, d)), (f"h{l}.Wv", (d, d)),
+                          (f"h{l}.Wk", (d, dkv)), (f"h{l}.Wv", (d, dkv)),
                           (f"h{l}.Wo", (d, d)), (f"h{l}.rms2.g", (d,)),
                           (f"h{l}.Wgate", (d, ff)), (f"h{l}.Wup", (d, ff)),
                           (f"h{l}.Wdown", (ff, d))]
@@ -188,8 +190,16 @@ def _gpt(model, P, V, tokens, labels):
 def _llama(model, P, V, tokens, labels):
     B, S = tokens.shape
     H, d, L = model["n_head"], model["d_model"], model["n_layer"]
+    Hkv = model.get("n_kv_head", H)   # grouped-query attention: query head h reads key/value head h // grp
+    grp = H // Hkv
     eps = model["norm_eps"]
     cos, sin = ops.rope_tables(S, d // H, model["rope_theta"])
+
+    def spread(t):   # [B, Hkv, S, dh] -> [B, H, S, dh], each key/value head repeated for its group
+        return np.repeat(t, grp, axis=1)
+
+    def gather(t):   # adjoint of spread: sum over the query heads of each group
+        return t.reshape(B, Hkv, grp, S, -1).sum(axis=2)
     tok = tokens.reshape(-1)
     x, x_t = P["wte"][tok], V["wte"][tok]
     caches = []
@@ -200,8 +210,9 @@ def _llama(model, P, V, tokens, labels):
         k, k_t, c_k = ops.linear_fwd(a, a_t, P[p + "Wk"], V[p + "Wk"])
         v, v_t, c_v = ops.linear_fwd(a, a_t, P[p + "Wv"], V[p + "Wv"])
         qr, qr_t = ops.rope_apply(_heads(q, B, S, H), cos, sin), ops.rope_apply(_heads(q_t, B, S, H), cos, sin)
-        kr, kr_t = ops.rope_apply(_heads(k, B, S, H), cos, sin), ops.rope_apply(_heads(k_t, B, S, H), cos, sin)
-        o, o_t, c_att = ops.attention_fwd(qr, qr_t, kr, kr_t, _heads(v, B, S, H), _heads(v_t, B, S, H))
+        kr, kr_t = ops.rope_apply(_heads(k, B, S, Hkv), cos, sin), ops.rope_apply(_heads(k_t, B, S, Hkv), cos, sin)
+        o, o_t, c_att = ops.attention_fwd(qr, qr_t, spread(kr), spread(kr_t), spread(_heads(v, B, S, Hkv)),
+                                          spread(_heads(v_t, B, S, Hkv)))
         y, y_t, c_o = ops.linear_fwd(_unheads(o), _unheads(o_t), P[p + "Wo"], V[p + "Wo"])
         x, x_t = x + y, x_t + y_t
         u, u_t, c_n2 = ops.rmsnorm_fwd(x, x_t, P[p + "rms2.g"], V[p + "rms2.g"], eps)
@@ -229,6 +240,7 @@ def _llama(model, P, V, tokens, labels):
         dx, dx_t = dx + r, dx_t + r_t
         do, do_t, G[p + "Wo"], U[p + "Wo"] = ops.linear_bwd(dx, dx_t, c_o)
         dq, dq_t, dk, dk_t, dv, dv_t = ops.attention_bwd(_heads(do, B, S, H), _heads(do_t, B, S, H), c_att)
+        dk, dk_t, dv, dv_t = gather(dk), gather(dk_t), gather(dv), gather(dv_t)
         dq, dq_t = ops.rope_apply(dq, cos, sin, True), ops.rope_apply(dq_t, cos, sin, True)
         dk, dk_t = ops.rope_apply(dk, cos, sin, True), ops.rope_apply(dk_t, cos, sin, True)
         da1, da1_t, G[p + "Wq"], U[p + "Wq"] = ops.linear_bwd(_unheads(dq), _unheads(dq_t), c_q)

@@ -32,9 +32,10 @@ def _gpt(n_layer, d, h, ff, vocab, max_seq, tie=1, act="gelu_erf"):
                 rope_theta=10000.0)
 
 
-def _llama(n_layer, d, h, ff, vocab, max_seq):
+def _llama(n_layer, d, h, ff, vocab, max_seq, n_kv=None):
+    """n_kv: key/value heads (grouped-query attention); None = one per query head."""
     return dict(arch="llama", n_layer=n_layer, d_model=d, n_head=h, d_ff=ff,
-                vocab=vocab, max_seq=max_seq, tie_embeddings=0,
+                vocab=vocab, max_seq=max_seq, tie_embeddings=0, n_kv_head=(n_kv or h),
                 mlp_in=0, mlp_hidden=0, mlp_out=0, norm_eps=1e-5,
                 rope_theta=10000.0)
 
@@ -105,12 +106,13 @@ def param_spec(model):
             out += [("lm_head", (d, V), N)]
         return out
     if a == "llama":
+        dkv = d // model["n_head"] * model.get("n_kv_head", model["n_head"])
         out += [("wte", (V, d), N)]
         for l in range(L):
             p = f"h{l}."
             out += [(p + "rms1.g", (d,), O),
-                    (p + "Wq", (d, d), N), (p + "Wk", (d, d), N),
-                    (p + "Wv", (d, d), N), (p + "Wo", (d, d), N),
+                    (p + "Wq", (d, d), N), (p + "Wk", (d, dkv), N),
+                    (p + "Wv", (d, dkv), N), (p + "Wo", (d, d), N),
                     (p + "rms2.g", (d,), O),
                     (p + "Wgate", (d, ff), N), (p + "Wup", (d, ff), N),
                     (p + "Wdown", (ff, d), N)]

@@ -64,8 +64,11 @@ def forward_loss(model, P, inputs, labels):
         for l in range(L):
             p = f"h{l}."
             y = rms(x, P[p + "rms1.g"])
-            q, k, v = _attn(y @ P[p + "Wq"], y @ P[p + "Wk"], y @ P[p + "Wv"], B, S, H)
+            Hkv = model.get("n_kv_head", H)
+            q = _attn(y @ P[p + "Wq"], y @ P[p + "Wq"], y @ P[p + "Wq"], B, S, H)[0]
+            k, v = _attn(y @ P[p + "Wk"], y @ P[p + "Wk"], y @ P[p + "Wv"], B, S, Hkv)[1:]
             q, k = _rope(q, model["rope_theta"]), _rope(k, model["rope_theta"])
+            k, v = k.repeat_interleave(H // Hkv, dim=1), v.repeat_interleave(H // Hkv, dim=1)
             o = F.scaled_dot_product_attention(q, k, v, is_causal=True)
             x = x + o.transpose(1, 2).reshape(B, S, d) @ P[p + "Wo"]
             y = rms(x, P[p + "rms2.g"])

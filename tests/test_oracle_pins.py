@@ -18,6 +18,7 @@ TINY = {
     "gpt": dict(model=si._gpt(2, 16, 2, 32, 23, 8), batch=2, seq=8, tokens="uniform"),
     "gpt_untied": dict(model=si._gpt(1, 16, 4, 24, 19, 6, tie=0), batch=3, seq=6, tokens="zipf"),
     "llama": dict(model=si._llama(2, 16, 2, 24, 21, 8), batch=2, seq=8, tokens="zipf"),
+    "llama_gqa": dict(model=si._llama(2, 24, 6, 24, 21, 8, n_kv=2), batch=2, seq=8, tokens="zipf"),
     "gpt_gelu_tanh": dict(model=si._gpt(2, 16, 2, 32, 23, 8, act="gelu_tanh"), batch=2, seq=8, tokens="uniform"),
 }
 
