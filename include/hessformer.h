@@ -80,7 +80,8 @@ typedef enum { HF_ACT_GELU_ERF = 0, HF_ACT_GELU_TANH = 1 } hf_activation;
  * GPT: pre-LayerNorm decoder, learned positions, GELU (erf or tanh form, see
  * `activation`), causal attention
  * with scale 1/sqrt(dh).  LLAMA: RMSNorm, rotary positions on pairs
- * (i, i + dh/2) with base rope_theta, SwiGLU, no biases.
+ * (i, i + dh/2) with base rope_theta, SwiGLU, no biases, optional grouped-query
+ * attention (n_kv_head).
  * param_dtype HF_BF16: weights are bf16 MFMA operands, activations fed to
  * matrix products are rounded to bf16, accumulation / residual stream /
  * normalisation and softmax statistics are fp32.  HF_F32: fp32 throughout. */
@@ -96,6 +97,10 @@ typedef struct {
                              allocated and only HF_REORTH_NONE iterations can run */
   int32_t activation;     /* GPT only: HF_ACT_GELU_ERF (0) or HF_ACT_GELU_TANH (1), the form
                              a/2 (1 + tanh(sqrt(2/pi)(a + 0.044715 a^3))) */
+  int32_t n_kv_head;      /* LLAMA only: key/value heads of grouped-query attention (query head h
+                             reads key/value head h / (n_head / n_kv_head)); Wk, Wv are
+                             [d_model, n_kv_head * d_model / n_head].  0 = n_head.  Must divide
+                             n_head; GPT takes 0 or n_head. */
 } hf_model_desc;
 
 /* ---- host-only helpers (no GPU needed) ---------------------------------- */

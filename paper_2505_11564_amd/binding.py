@@ -34,7 +34,7 @@ class hf_model_desc(C.Structure):
                 ("d_ff", C.c_int32), ("vocab", C.c_int32), ("max_seq", C.c_int32), ("mlp_in", C.c_int32),
                 ("mlp_hidden", C.c_int32), ("mlp_out", C.c_int32), ("tie_embeddings", C.c_int32),
                 ("norm_eps", C.c_float), ("rope_theta", C.c_float), ("param_dtype", C.c_int32),
-                ("basis_dtype", C.c_int32), ("activation", C.c_int32)]
+                ("basis_dtype", C.c_int32), ("activation", C.c_int32), ("n_kv_head", C.c_int32)]
 
 
 class HessformerError(RuntimeError):
@@ -115,6 +115,7 @@ def make_desc(model, param_dtype="f32", basis_dtype="f32"):
     d.param_dtype = HF_DTYPE[param_dtype]
     d.basis_dtype = HF_DTYPE[basis_dtype]
     d.activation = HF_ACT[model.get("act", "gelu_erf")]
+    d.n_kv_head = int(model.get("n_kv_head", 0) or 0) if model["arch"] == "llama" else 0
     return d
 
 

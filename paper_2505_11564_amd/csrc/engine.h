@@ -59,6 +59,8 @@ struct hf_ctx {
   // bf16 mode: low-order halves of the primal forward activations (reused by every layer)
   void *a_lo = nullptr, *qkv_lo = nullptr, *P_lo = nullptr, *o_lo = nullptr, *f_lo = nullptr, *up_lo = nullptr, *g_lo = nullptr;
   float *rq = nullptr, *rq_t = nullptr;  // LLAMA: fp32 q|k (or their adjoints) before the rotation
+  float *rv = nullptr, *rv_t = nullptr;  // grouped-query attention: fp32 dV summed over the heads of a group
+  void *dvb = nullptr, *dvb_t = nullptr; //   and its operand-type copy (bf16 mode)
   float *z = nullptr, *z_t = nullptr;
   void *dz = nullptr, *dz_t = nullptr;
   int64_t ldz = 0;

@@ -43,6 +43,10 @@ int hf::build_layout(const hf_model_desc& d, std::vector<LayoutEntry>& out, std:
   if (!(d.norm_eps > 0.f)) return bad("norm_eps must be positive");
   if (d.activation != HF_ACT_GELU_ERF && d.activation != HF_ACT_GELU_TANH) return bad("activation must be HF_ACT_GELU_ERF or HF_ACT_GELU_TANH");
   const int64_t D = d.d_model, F = d.d_ff, V = d.vocab;
+  const int hkv = d.n_kv_head > 0 ? d.n_kv_head : d.n_head;
+  if (hkv > d.n_head || d.n_head % hkv) return bad("n_kv_head must divide n_head");
+  if (d.arch == HF_ARCH_GPT && hkv != d.n_head) return bad("grouped-query attention (n_kv_head) is a LLAMA option");
+  const int64_t Dkv = D / d.n_head * hkv;
   if (d.arch == HF_ARCH_GPT) {
     add("wte", V, D); add("wpe", d.max_seq, D);
     for (int l = 0; l < d.n_layer; ++l) {
@@ -63,7 +67,7 @@ int hf::build_layout(const hf_model_desc& d, std::vector<LayoutEntry>& out, std:
     for (int l = 0; l < d.n_layer; ++l) {
       const std::string p = "h" + std::to_string(l) + ".";
       add(p + "rms1.g", D, 0);
-      add(p + "Wq", D, D); add(p + "Wk", D, D); add(p + "Wv", D, D); add(p + "Wo", D, D);
+      add(p + "Wq", D, D); add(p + "Wk", D, Dkv); add(p + "Wv", D, Dkv); add(p + "Wo", D, D);
       add(p + "rms2.g", D, 0);
       add(p + "Wgate", D, F); add(p + "Wup", D, F); add(p + "Wdown", F, D);
     }
@@ -107,13 +111,15 @@ int hf_ctx::plan_and_alloc() {
     const int64_t S = desc.max_seq, B = max_batch, T = B * S, D = desc.d_model, F = desc.d_ff, H = desc.n_head;
     const int64_t SS = B * H * S * S;
     const bool llama = desc.arch == HF_ARCH_LLAMA;
+    const int64_t Dkv = D / H * (desc.n_kv_head > 0 ? desc.n_kv_head : H);  // key / value width
+    const int64_t W3 = D + 2 * Dkv;                                           // packed q | k | v row
     lb.resize(desc.n_layer);
     for (auto& b : lb) {
       b = LayerBuf{};
       pl.add(b.x1, T * D * 4); pl.add(b.x1_t, T * D * 4); pl.add(b.x2, T * D * 4); pl.add(b.x2_t, T * D * 4);
       pl.add(b.st1, T * 16); pl.add(b.st2, T * 16);
       pl.add(b.a, T * D * e); pl.add(b.a_t, T * D * e);
-      pl.add(b.qkv, T * 3 * D * e); pl.add(b.qkv_t, T * 3 * D * e);
+      pl.add(b.qkv, T * W3 * e); pl.add(b.qkv_t, T * W3 * e);
       pl.add(b.P, SS * e); pl.add(b.P_t, SS * e);
       pl.add(b.o, T * D * e); pl.add(b.o_t, T * D * e);
       pl.add(b.m, T * D * e); pl.add(b.m_t, T * D * e);
@@ -124,11 +130,15 @@ int hf_ctx::plan_and_alloc() {
     pl.add(xL, T * D * 4); pl.add(xL_t, T * D * 4); pl.add(stf, T * 16);
     pl.add(xf, T * D * e); pl.add(xf_t, T * D * e);
     if (bf) {
-      pl.add(xf_lo, T * D * e); pl.add(a_lo, T * D * e); pl.add(o_lo, T * D * e); pl.add(qkv_lo, T * 3 * D * e);
+      pl.add(xf_lo, T * D * e); pl.add(a_lo, T * D * e); pl.add(o_lo, T * D * e); pl.add(qkv_lo, T * W3 * e);
       pl.add(P_lo, SS * e); pl.add(f_lo, T * F * e); pl.add(g_lo, T * F * e);
       if (llama) pl.add(up_lo, T * F * e);
     }
-    if (llama) { pl.add(rq, T * 2 * D * 4); pl.add(rq_t, T * 2 * D * 4); }
+    if (llama) { pl.add(rq, T * (D + Dkv) * 4); pl.add(rq_t, T * (D + Dkv) * 4); }
+    if (llama && Dkv != D) {  // grouped heads: dV is summed over a group in fp32, then rounded once
+      pl.add(rv, T * Dkv * 4); pl.add(rv_t, T * Dkv * 4);
+      if (bf) { pl.add(dvb, T * Dkv * e); pl.add(dvb_t, T * Dkv * e); }
+    }
     ldz = round_up(desc.vocab, 64);
     pl.add(z, T * ldz * 4); pl.add(z_t, T * ldz * 4);
     pl.add(dz, T * ldz * e); pl.add(dz_t, T * ldz * e);
@@ -144,7 +154,7 @@ int hf_ctx::plan_and_alloc() {
     pl.add(dx, T * D * 4); pl.add(dx_t, T * D * 4); pl.add(tmpd, T * D * 4); pl.add(tmpd_t, T * D * 4);
     if (bf) { pl.add(dxb, T * D * e); pl.add(dxb_t, T * D * e); }
     pl.add(dob, T * D * e); pl.add(dob_t, T * D * e);
-    pl.add(dqkv, T * 3 * D * e); pl.add(dqkv_t, T * 3 * D * e);
+    pl.add(dqkv, T * W3 * e); pl.add(dqkv_t, T * W3 * e);
     pl.add(dg, T * F * e); pl.add(dg_t, T * F * e);
     if (llama) {
       pl.add(dup, T * F * e); pl.add(dup_t, T * F * e);
@@ -352,6 +362,9 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
   const float eps = desc.norm_eps;
   const float cs = 1.f / sqrtf((float)dh);
   const int gelu_kind = desc.activation == HF_ACT_GELU_TANH ? ACT_GELU_TANH : ACT_GELU;
+  // grouped-query attention: Hkv key/value heads, query head h reads head h / grp
+  const int Hkv = desc.n_kv_head > 0 ? desc.n_kv_head : H, grp = H / Hkv;
+  const int Dkv = Hkv * dh, W3 = D + 2 * Dkv, offK = D, offV = D + Dkv, RQ = D + Dkv;
   const int64_t e = bf ? 2 : 4;
   Lin L{this, params, v, out, st, bf};
   auto at = [&](void* p, int64_t elems) -> void* { return (char*)p + elems * e; };
@@ -363,7 +376,7 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
   auto att = [&](Gemm& g) {
     g.nb1 = B; g.nb2 = H; g.in_bf16 = bf;
   };
-  auto set_qkv = [&](int64_t& s1, int64_t& s2) { s1 = (int64_t)S * 3 * D; s2 = dh; };
+  auto set_qkv = [&](int64_t& s1, int64_t& s2) { s1 = (int64_t)S * W3; s2 = dh; };
   auto set_sc = [&](int64_t& s1, int64_t& s2) { s1 = (int64_t)H * SS; s2 = SS; };
   auto set_td = [&](int64_t& s1, int64_t& s2) { s1 = (int64_t)S * D; s2 = dh; };
 
@@ -398,26 +411,26 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
     CK(launch_norm_fwd(bf, rms, b.x1, b.x1_t, L.Wp(o.n1g), rms ? nullptr : L.Wp(o.n1b), v + o.n1g,
                        rms ? nullptr : v + o.n1b, T, D, eps, b.a, b.a_t, a_lo, b.st1, st));
     if (!llama) {
-      if ((rc = L.fwd(b.a, b.a_t, T, D, 3 * D, D, o.wqkv, o.bqkv, b.qkv, b.qkv_t, 3 * D, bf, nullptr, nullptr, 0, -1, a_lo, qkv_lo))) return rc;
+      if ((rc = L.fwd(b.a, b.a_t, T, D, 3 * D, D, o.wqkv, o.bqkv, b.qkv, b.qkv_t, W3, bf, nullptr, nullptr, 0, -1, a_lo, qkv_lo))) return rc;
     } else {
       // q and k leave their products in fp32 and are rounded once, after the rotation
-      if ((rc = L.fwd(b.a, b.a_t, T, D, D, D, o.wq, -1, rq, rq_t, 2 * D, 0, nullptr, nullptr, 0, -1, a_lo))) return rc;
-      if ((rc = L.fwd(b.a, b.a_t, T, D, D, D, o.wk, -1, rq + D, rq_t + D, 2 * D, 0, nullptr, nullptr, 0, -1, a_lo))) return rc;
-      if ((rc = L.fwd(b.a, b.a_t, T, D, D, D, o.wv, -1, at(b.qkv, 2 * D), at(b.qkv_t, 2 * D), 3 * D, bf, nullptr, nullptr, 0, -1, a_lo,
-                      qkv_lo ? at(qkv_lo, 2 * D) : nullptr))) return rc;
-      CK(launch_rope(bf, rq, rq_t, 2 * D, b.qkv, b.qkv_t, qkv_lo, 3 * D, T, S, 2 * H, dh, desc.rope_theta, 0, st));
+      if ((rc = L.fwd(b.a, b.a_t, T, D, D, D, o.wq, -1, rq, rq_t, RQ, 0, nullptr, nullptr, 0, -1, a_lo))) return rc;
+      if ((rc = L.fwd(b.a, b.a_t, T, D, Dkv, D, o.wk, -1, rq + D, rq_t + D, RQ, 0, nullptr, nullptr, 0, -1, a_lo))) return rc;
+      if ((rc = L.fwd(b.a, b.a_t, T, D, Dkv, D, o.wv, -1, at(b.qkv, offV), at(b.qkv_t, offV), W3, bf, nullptr, nullptr, 0, -1, a_lo,
+                      qkv_lo ? at(qkv_lo, offV) : nullptr))) return rc;
+      CK(launch_rope(bf, rq, rq_t, RQ, b.qkv, b.qkv_t, qkv_lo, W3, T, S, H + Hkv, dh, desc.rope_theta, 0, st));
     }
     if (fused_att) {
       // scores without a trip through memory: the product is formed twice by the
       // dual-output kernel, first to reduce (max, sum, tangent sum) per row over
       // 64-column parts, then to write P, P_lo, P_t with the combined statistics
       Gemm g; att(g);
-      g.M = S; g.N = S; g.K = dh; g.lda = 3 * D; g.ldb = 3 * D; g.ldc = S; g.transB = 1; g.alpha = cs; g.skip_upper = 1;
+      g.M = S; g.N = S; g.K = dh; g.lda = W3; g.ldb = W3; g.ldc = S; g.transB = 1; g.alpha = cs; g.skip_upper = 1; g.divB = grp;
       set_qkv(g.sA1, g.sA2); set_qkv(g.sB1, g.sB2); set_sc(g.sC1, g.sC2);
-      g.A[0] = b.qkv; g.B[0] = cat(b.qkv, D);
-      g.A[1] = qkv_lo; g.B[1] = cat(b.qkv, D);
-      g.A[2] = b.qkv; g.B[2] = cat(qkv_lo, D);
-      g.At = b.qkv_t; g.Bt = cat(b.qkv_t, D);
+      g.A[0] = b.qkv; g.B[0] = cat(b.qkv, offK);
+      g.A[1] = qkv_lo; g.B[1] = cat(b.qkv, offK);
+      g.A[2] = b.qkv; g.B[2] = cat(qkv_lo, offK);
+      g.At = b.qkv_t; g.Bt = cat(b.qkv_t, offK);
       g.C = b.P; g.Ct = b.P_t; g.out_bf16 = 1;
       g.epi = EPI_FWD_STATS; g.part = att_part;
       CK(launch_gemm(g, st));
@@ -427,29 +440,29 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
     } else {
     {  // scores S = c Q K^T, S_t = c (Q_t K^T + Q K_t^T); lower-triangular tiles only
       Gemm g; att(g);
-      g.M = S; g.N = S; g.K = dh; g.lda = 3 * D; g.ldb = 3 * D; g.ldc = S; g.transB = 1; g.alpha = cs; g.skip_upper = 1;
+      g.M = S; g.N = S; g.K = dh; g.lda = W3; g.ldb = W3; g.ldc = S; g.transB = 1; g.alpha = cs; g.skip_upper = 1; g.divB = grp;
       set_qkv(g.sA1, g.sA2); set_qkv(g.sB1, g.sB2); set_sc(g.sC1, g.sC2);
-      g.A[0] = b.qkv; g.B[0] = cat(b.qkv, D); g.C = sc;
+      g.A[0] = b.qkv; g.B[0] = cat(b.qkv, offK); g.C = sc;
       if (qkv_lo) {  // (q + q_lo)(k + k_lo)^T without the lo*lo term
-        g.A[1] = qkv_lo; g.B[1] = cat(b.qkv, D);
-        g.A[2] = b.qkv; g.B[2] = cat(qkv_lo, D);
+        g.A[1] = qkv_lo; g.B[1] = cat(b.qkv, offK);
+        g.A[2] = b.qkv; g.B[2] = cat(qkv_lo, offK);
       }
-      g.At = b.qkv_t; g.Bt = cat(b.qkv_t, D); g.Ct = sc_t;
+      g.At = b.qkv_t; g.Bt = cat(b.qkv_t, offK); g.Ct = sc_t;
       CK(launch_gemm(g, st));
     }
     CK(launch_softmax_fwd(bf, sc, sc_t, b.P, b.P_t, P_lo, B * H, S, st));
     }
     {  // O = P V, O_t = P_t V + P V_t
       Gemm g; att(g);
-      g.M = S; g.N = dh; g.K = S; g.lda = S; g.ldb = 3 * D; g.ldc = D; g.klimit = 1; g.out_bf16 = bf;
+      g.M = S; g.N = dh; g.K = S; g.lda = S; g.ldb = W3; g.ldc = D; g.klimit = 1; g.out_bf16 = bf; g.divB = grp;
       set_sc(g.sA1, g.sA2); set_qkv(g.sB1, g.sB2); set_td(g.sC1, g.sC2);
-      g.A[0] = b.P; g.B[0] = cat(b.qkv, 2 * D); g.C = b.o;
+      g.A[0] = b.P; g.B[0] = cat(b.qkv, offV); g.C = b.o;
       if (P_lo) {
-        g.A[1] = P_lo; g.B[1] = cat(b.qkv, 2 * D);
-        g.A[2] = b.P; g.B[2] = cat(qkv_lo, 2 * D);
+        g.A[1] = P_lo; g.B[1] = cat(b.qkv, offV);
+        g.A[2] = b.P; g.B[2] = cat(qkv_lo, offV);
         g.C_lo = o_lo;
       }
-      g.At = b.P_t; g.Bt = cat(b.qkv_t, 2 * D); g.Ct = b.o_t;
+      g.At = b.P_t; g.Bt = cat(b.qkv_t, offV); g.Ct = b.o_t;
       CK(launch_gemm(g, st));
     }
     if ((rc = L.fwd(b.o, b.o_t, T, D, D, D, o.wo, o.bo, b.x2, b.x2_t, D, 0, b.x1, b.x1_t, 0, -1, o_lo))) return rc;
@@ -520,22 +533,44 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
     if (bf) CK(launch_cast_pair(1, dx, dx_t, dxb, dxb_t, (int64_t)T * D, st));
     if ((rc = L.bwd_dw(b.o, b.o_t, dxb, dxb_t, T, D, D, D, D, o.wo, o.bo, dx_t, 0))) return rc;
     if ((rc = L.bwd_dx(dxb, dxb_t, T, D, D, D, o.wo, dob, dob_t, D, bf))) return rc;
-    {  // dV = P^T dO, dV_t = P_t^T dO + P^T dO_t   -> v third of dqkv
+    // Products whose result belongs to a key/value head sum over the grp query heads that share
+    // it: one launch per member j of the groups (batch = key/value heads, query head kv * grp + j),
+    // the first writing and the others adding to an fp32 result.
+    auto grouped = [&](Gemm g, int64_t a_head, int64_t b_head, float* c, float* c_t) -> hipError_t {
+      g.nb2 = Hkv; g.out_bf16 = 0; g.sA2 = grp * a_head; g.sB2 = grp * b_head;
+      const char *a0 = (const char*)g.A[0], *at0 = (const char*)g.At, *b0 = (const char*)g.B[0], *bt0 = (const char*)g.Bt;
+      for (int j = 0; j < grp; ++j) {
+        g.A[0] = a0 + j * a_head * e; g.At = at0 + j * a_head * e;
+        g.B[0] = b0 + j * b_head * e; g.Bt = bt0 + j * b_head * e;
+        g.C = c; g.Ct = c_t;
+        g.Cadd = j ? c : nullptr; g.Cadd_t = j ? c_t : nullptr;
+        hipError_t er = launch_gemm(g, st);
+        if (er != hipSuccess) return er;
+      }
+      return hipSuccess;
+    };
+    {  // dV = P^T dO, dV_t = P_t^T dO + P^T dO_t   -> v part of dqkv
       Gemm g; att(g);
-      g.M = S; g.N = dh; g.K = S; g.lda = S; g.ldb = D; g.ldc = 3 * D; g.transA = 1; g.klimit = 2; g.out_bf16 = bf;
+      g.M = S; g.N = dh; g.K = S; g.lda = S; g.ldb = D; g.ldc = W3; g.transA = 1; g.klimit = 2; g.out_bf16 = bf;
       set_sc(g.sA1, g.sA2); set_td(g.sB1, g.sB2); set_qkv(g.sC1, g.sC2);
-      g.A[0] = b.P; g.B[0] = dob; g.C = at(dqkv, 2 * D);
-      g.At = b.P_t; g.Bt = dob_t; g.Ct = at(dqkv_t, 2 * D);
-      CK(launch_gemm(g, st));
+      g.A[0] = b.P; g.B[0] = dob; g.C = at(dqkv, offV);
+      g.At = b.P_t; g.Bt = dob_t; g.Ct = at(dqkv_t, offV);
+      if (grp == 1) {
+        CK(launch_gemm(g, st));
+      } else {  // fp32 [T, Dkv], rounded once below
+        g.ldc = Dkv; g.sC1 = (int64_t)S * Dkv; g.sC2 = dh;
+        CK(grouped(g, SS, dh, rv, rv_t));
+        if (bf) CK(launch_cast_pair(1, rv, rv_t, dvb, dvb_t, (int64_t)T * Dkv, st));
+      }
     }
     if (fused_att) {
       // dP = dO V^T and its tangent, reduced to (delta, delta_t) per row on the
       // first pass and turned into dS, dS_t on the second; dP never reaches memory
       Gemm g; att(g);
-      g.M = S; g.N = S; g.K = dh; g.lda = D; g.ldb = 3 * D; g.ldc = S; g.transB = 1; g.skip_upper = 1;
+      g.M = S; g.N = S; g.K = dh; g.lda = D; g.ldb = W3; g.ldc = S; g.transB = 1; g.skip_upper = 1; g.divB = grp;
       set_td(g.sA1, g.sA2); set_qkv(g.sB1, g.sB2); set_sc(g.sC1, g.sC2);
-      g.A[0] = dob; g.B[0] = cat(b.qkv, 2 * D);
-      g.At = dob_t; g.Bt = cat(b.qkv_t, 2 * D);
+      g.A[0] = dob; g.B[0] = cat(b.qkv, offV);
+      g.At = dob_t; g.Bt = cat(b.qkv_t, offV);
       g.C = dS; g.Ct = dS_t; g.out_bf16 = 1; g.E0 = b.P; g.E1 = b.P_t;
       g.epi = EPI_BWD_STATS; g.part = att_part;
       CK(launch_gemm(g, st));
@@ -545,43 +580,53 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
     } else {
     {  // dP = dO V^T, dP_t = dO_t V^T + dO V_t^T
       Gemm g; att(g);
-      g.M = S; g.N = S; g.K = dh; g.lda = D; g.ldb = 3 * D; g.ldc = S; g.transB = 1; g.skip_upper = 1;
+      g.M = S; g.N = S; g.K = dh; g.lda = D; g.ldb = W3; g.ldc = S; g.transB = 1; g.skip_upper = 1; g.divB = grp;
       set_td(g.sA1, g.sA2); set_qkv(g.sB1, g.sB2); set_sc(g.sC1, g.sC2);
-      g.A[0] = dob; g.B[0] = cat(b.qkv, 2 * D); g.C = sc;
-      g.At = dob_t; g.Bt = cat(b.qkv_t, 2 * D); g.Ct = sc_t;
+      g.A[0] = dob; g.B[0] = cat(b.qkv, offV); g.C = sc;
+      g.At = dob_t; g.Bt = cat(b.qkv_t, offV); g.Ct = sc_t;
       CK(launch_gemm(g, st));
     }
     CK(launch_softmax_bwd(bf, b.P, b.P_t, sc, sc_t, dS, dS_t, B * H, S, st));
     }
     {  // dQ = c dS K, dQ_t = c (dS_t K + dS K_t)
       Gemm g; att(g);
-      g.M = S; g.N = dh; g.K = S; g.lda = S; g.ldb = 3 * D; g.ldc = 3 * D; g.klimit = 1; g.alpha = cs; g.out_bf16 = bf;
+      g.M = S; g.N = dh; g.K = S; g.lda = S; g.ldb = W3; g.ldc = W3; g.klimit = 1; g.alpha = cs; g.out_bf16 = bf;
       set_sc(g.sA1, g.sA2); set_qkv(g.sB1, g.sB2); set_qkv(g.sC1, g.sC2);
-      void *cq = dqkv, *cq_t = dqkv_t, *ck = at(dqkv, D), *ck_t = at(dqkv_t, D);
-      if (llama) {  // fp32 staging [T, 2D]; rounded once after the inverse rotation
-        g.out_bf16 = 0; g.ldc = 2 * D; g.sC1 = (int64_t)S * 2 * D; g.sC2 = dh;
+      void *cq = dqkv, *cq_t = dqkv_t, *ck = at(dqkv, offK), *ck_t = at(dqkv_t, offK);
+      if (llama) {  // fp32 staging [T, D + Dkv]; rounded once after the inverse rotation
+        g.out_bf16 = 0; g.ldc = RQ; g.sC1 = (int64_t)S * RQ; g.sC2 = dh;
         cq = rq; cq_t = rq_t; ck = rq + D; ck_t = rq_t + D;
       }
-      g.A[0] = dS; g.B[0] = cat(b.qkv, D); g.C = cq;
-      g.At = dS_t; g.Bt = cat(b.qkv_t, D); g.Ct = cq_t;
+      g.A[0] = dS; g.B[0] = cat(b.qkv, offK); g.C = cq;
+      g.At = dS_t; g.Bt = cat(b.qkv_t, offK); g.Ct = cq_t;
+      g.divB = grp;
       CK(launch_gemm(g, st));
       // dK = c dS^T Q, dK_t = c (dS_t^T Q + dS^T Q_t)
-      g.transA = 1; g.klimit = 2;
+      g.transA = 1; g.klimit = 2; g.divB = 1;
       g.A[0] = dS; g.B[0] = b.qkv; g.C = ck;
       g.At = dS_t; g.Bt = b.qkv_t; g.Ct = ck_t;
-      CK(launch_gemm(g, st));
+      if (grp == 1) CK(launch_gemm(g, st));
+      else CK(grouped(g, SS, dh, (float*)ck, (float*)ck_t));  // grp > 1 is LLAMA: ck is the fp32 staging
     }
     if (!llama) {
-      if ((rc = L.bwd_dw(b.a, b.a_t, dqkv, dqkv_t, T, D, 3 * D, D, 3 * D, o.wqkv, o.bqkv, dqkv_t, bf))) return rc;
-      if ((rc = L.bwd_dx(dqkv, dqkv_t, T, D, 3 * D, 3 * D, o.wqkv, tmpd, tmpd_t, D, 0))) return rc;
+      if ((rc = L.bwd_dw(b.a, b.a_t, dqkv, dqkv_t, T, D, 3 * D, D, W3, o.wqkv, o.bqkv, dqkv_t, bf))) return rc;
+      if ((rc = L.bwd_dx(dqkv, dqkv_t, T, D, 3 * D, W3, o.wqkv, tmpd, tmpd_t, D, 0))) return rc;
     } else {
-      CK(launch_rope(bf, rq, rq_t, 2 * D, dqkv, dqkv_t, nullptr, 3 * D, T, S, 2 * H, dh, desc.rope_theta, 1, st));
+      CK(launch_rope(bf, rq, rq_t, RQ, dqkv, dqkv_t, nullptr, W3, T, S, H + Hkv, dh, desc.rope_theta, 1, st));
       const int64_t w3[3] = {o.wq, o.wk, o.wv};
+      const int64_t offs[3] = {0, offK, offV};
       for (int i = 0; i < 3; ++i) {
-        const void* dyi = cat(dqkv, (int64_t)i * D);
-        const void* dyi_t = cat(dqkv_t, (int64_t)i * D);
-        if ((rc = L.bwd_dw(b.a, b.a_t, dyi, dyi_t, T, D, D, D, 3 * D, w3[i], -1, nullptr, 0))) return rc;
-        if ((rc = L.bwd_dx(dyi, dyi_t, T, D, D, 3 * D, w3[i], tmpd, tmpd_t, D, 0, i ? tmpd : nullptr, i ? tmpd_t : nullptr))) return rc;
+        const void* dyi = cat(dqkv, offs[i]);
+        const void* dyi_t = cat(dqkv_t, offs[i]);
+        int64_t ldy = W3;
+        const int Ni = i ? Dkv : D;
+        if (i == 2 && grp > 1) {  // dV of grouped heads lives in its own [T, Dkv] buffer
+          dyi = bf ? (const void*)dvb : (const void*)rv;
+          dyi_t = bf ? (const void*)dvb_t : (const void*)rv_t;
+          ldy = Dkv;
+        }
+        if ((rc = L.bwd_dw(b.a, b.a_t, dyi, dyi_t, T, D, Ni, D, ldy, w3[i], -1, nullptr, 0))) return rc;
+        if ((rc = L.bwd_dx(dyi, dyi_t, T, D, Ni, ldy, w3[i], tmpd, tmpd_t, D, 0, i ? tmpd : nullptr, i ? tmpd_t : nullptr))) return rc;
       }
     }
     CK(launch_norm_bwd(bf, rms, tmpd, tmpd_t, b.x1, b.x1_t, b.st1, L.Wp(o.n1g), v + o.n1g, T, D, 1, dx, dx_t,

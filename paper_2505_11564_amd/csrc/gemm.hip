@@ -30,7 +30,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmP p) {
   const int m0 = (tile / p.tiles_n) * BM, n0 = (tile % p.tiles_n) * BN;
   if (p.skip_upper && n0 > m0 + BM - 1) return;
   const int z = blockIdx.y, z1 = z / p.nb2, z2 = z % p.nb2;
-  const int64_t offA = z1 * p.sA1 + z2 * p.sA2, offB = z1 * p.sB1 + z2 * p.sB2, offC = z1 * p.sC1 + z2 * p.sC2;
+  const int64_t offA = z1 * p.sA1 + z2 * p.sA2, offB = z1 * p.sB1 + (z2 / p.divB) * p.sB2, offC = z1 * p.sC1 + z2 * p.sC2;
   int kbeg = 0, kend = p.K;
   if (p.klimit == 1) kend = min(p.K, m0 + BM);
   if (p.klimit == 2) kbeg = (m0 / BK) * BK;
@@ -199,7 +199,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmP p) {
   const int m0 = (tile / p.tiles_n) * BM, n0 = (tile % p.tiles_n) * BN;
   if (p.skip_upper && n0 > m0 + BM - 1) return;
   const int z = blockIdx.y, z1 = z / p.nb2, z2 = z % p.nb2;
-  const int64_t offA = z1 * p.sA1 + z2 * p.sA2, offB = z1 * p.sB1 + z2 * p.sB2, offC = z1 * p.sC1 + z2 * p.sC2;
+  const int64_t offA = z1 * p.sA1 + z2 * p.sA2, offB = z1 * p.sB1 + (z2 / p.divB) * p.sB2, offC = z1 * p.sC1 + z2 * p.sC2;
   int kbeg = 0, kend = p.K;
   if (p.klimit == 1) kend = min(p.K, m0 + BM);
   if (p.klimit == 2) kbeg = (m0 / BK) * BK;
@@ -339,6 +339,7 @@ static hipError_t launch_gemm_single(const Gemm& g, hipStream_t st) {
   p.M = g.M; p.N = g.N; p.K = g.K; p.lda = g.lda; p.ldb = g.ldb; p.ldc = g.ldc;
   p.transA = g.transA; p.transB = g.transB; p.nb2 = g.nb2;
   p.sA1 = g.sA1; p.sA2 = g.sA2; p.sB1 = g.sB1; p.sB2 = g.sB2; p.sC1 = g.sC1; p.sC2 = g.sC2;
+  p.divB = g.divB > 0 ? g.divB : 1;
   p.alpha = g.alpha; p.out_bf16 = g.out_bf16; p.bias_bf16 = g.in_bf16;
   p.klimit = g.klimit; p.skip_upper = g.skip_upper;
   const int nb = g.nb1 * g.nb2;

@@ -26,7 +26,7 @@ struct DualP {
   const float* bias_t;
   int M, N, K;
   int64_t lda, ldb, ldc;
-  int nb2;
+  int nb2, divB;
   int64_t sA1, sA2, sB1, sB2, sC1, sC2;
   float alpha;
   int out_bf16, bias_bf16;
@@ -82,7 +82,7 @@ __global__ __launch_bounds__(256, (EPI != EPI_NONE && NT == 4 && NS == 2 ? 2 : 1
   const int m0 = tm * BM, n0 = tn * BN;
   if (p.skip_upper && n0 > m0 + BM - 1) return;
   const int z = blockIdx.y, z1 = z / p.nb2, z2 = z % p.nb2;
-  const int64_t offA = z1 * p.sA1 + z2 * p.sA2, offB = z1 * p.sB1 + z2 * p.sB2, offC = z1 * p.sC1 + z2 * p.sC2;
+  const int64_t offA = z1 * p.sA1 + z2 * p.sA2, offB = z1 * p.sB1 + (z2 / p.divB) * p.sB2, offC = z1 * p.sC1 + z2 * p.sC2;
   int kbeg = 0, kend = p.K;
   if (p.klimit == 1) kend = min(p.K, m0 + BM);
   if (p.klimit == 2) kbeg = (m0 / 64) * 64;
@@ -553,7 +553,7 @@ hipError_t launch_gemm_dual(const Gemm& g, hipStream_t st) {
     else return hipErrorNotSupported;
   }
   p.C = g.C; p.Ct = g.Ct; p.Clo = g.C_lo; p.Cadd = g.Cadd; p.Cadd_t = g.Cadd_t; p.bias = g.bias; p.bias_t = g.bias_t;
-  p.M = g.M; p.N = g.N; p.K = g.K; p.lda = g.lda; p.ldb = g.ldb; p.ldc = g.ldc; p.nb2 = g.nb2;
+  p.M = g.M; p.N = g.N; p.K = g.K; p.lda = g.lda; p.ldb = g.ldb; p.ldc = g.ldc; p.nb2 = g.nb2; p.divB = g.divB > 0 ? g.divB : 1;
   p.sA1 = g.sA1; p.sA2 = g.sA2; p.sB1 = g.sB1; p.sB2 = g.sB2; p.sC1 = g.sC1; p.sC2 = g.sC2;
   p.alpha = g.alpha; p.out_bf16 = g.out_bf16; p.bias_bf16 = 1; p.klimit = g.klimit; p.skip_upper = g.skip_upper;
   p.epi = g.epi; p.part = g.part; p.rstat = g.rstat; p.E0 = g.E0; p.E1 = g.E1; p.NP = (g.N + 63) / 64;

@@ -18,6 +18,7 @@ struct GemmP {
   int64_t lda, ldb, ldc;
   int transA, transB;
   int nb2;
+  int divB;  // the B operand of batch entry (z1, z2) is entry (z1, z2 / divB): shared key/value heads
   int64_t sA1, sA2, sB1, sB2, sC1, sC2;
   float alpha;
   int out_bf16, bias_bf16;

@@ -54,6 +54,7 @@ struct Gemm {
   int64_t lda = 0, ldb = 0, ldc = 0;
   int transA = 0, transB = 0;
   int nb1 = 1, nb2 = 1;
+  int divB = 1;  // batch entry (i1, i2) reads B of entry (i1, i2 / divB): grouped key/value heads
   int64_t sA1 = 0, sA2 = 0, sB1 = 0, sB2 = 0, sC1 = 0, sC2 = 0;
   float alpha = 1.f;
   int in_bf16 = 0, out_bf16 = 0;

@@ -39,6 +39,20 @@ def test_layout_matches_oracle_and_generator(name):
     assert hf.hf_desc_num_params(d) == om.num_params(cfg["model"])
 
 
+def test_layout_grouped_query_llama():
+    model = si._llama(3, 64, 8, 96, 101, 16, n_kv=2)
+    d = hf.make_desc(model)
+    lay = hf.hf_layout(d)
+    assert [(a, o, tuple(s)) for a, o, s in lay] == [(a, o, tuple(s)) for a, o, s in om.layout(model)]
+    assert dict((a, tuple(s)) for a, _, s in lay)["h0.Wk"] == (64, 16)
+    assert hf.hf_desc_num_params(d) == om.num_params(model) == si.num_params(model)
+    bad = hf.make_desc(si._llama(1, 64, 8, 96, 101, 16, n_kv=3))      # 3 does not divide 8
+    assert hf.hf_desc_num_params(bad) < 0
+    gpt = hf.make_desc(si._gpt(1, 64, 8, 96, 101, 16))
+    gpt.n_kv_head = 2                                                   # a LLAMA option only
+    assert hf.hf_desc_num_params(gpt) < 0
+
+
 def test_layout_untied_gpt_and_errors():
     m = si._gpt(1, 24, 3, 32, 19, 6, tie=0)
     lay = hf.hf_layout(hf.make_desc(m))

@@ -22,6 +22,9 @@ SHAPES = {
     "llama_mid": dict(model=si._llama(2, 256, 4, 344, 777, 136), batch=2, seq=136, tokens="zipf"),
     # sequence length a multiple of 8 and head width of 32: in bf16 mode the scores take the fused
     # attention epilogues (two column tiles, the second one ragged)
+    # grouped-query attention: 6 / 8 query heads on 2 key-value heads
+    "llama_gqa_tiny": dict(model=si._llama(2, 24, 6, 24, 21, 8, n_kv=2), batch=2, seq=8, tokens="zipf"),
+    "llama_gqa_mid": dict(model=si._llama(2, 256, 8, 344, 777, 136, n_kv=2), batch=2, seq=136, tokens="zipf"),
     "gpt_gelu_tanh": dict(model=si._gpt(2, 64, 2, 136, 301, 40, act="gelu_tanh"), batch=2, seq=40, tokens="zipf"),
     "gpt_fused": dict(model=si._gpt(2, 128, 4, 264, 517, 200), batch=2, seq=200, tokens="zipf"),
 }
