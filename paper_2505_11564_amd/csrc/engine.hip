@@ -385,6 +385,7 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
   // are read as zeros by products that run with larger tiles, so they are
   // cleared whenever the [B,H,S,S] layout changes.
   static const bool no_fused = std::getenv("HF_NO_FUSED_ATT") != nullptr;
+  static const bool delta_from_o = std::getenv("HF_ATT_DELTA_PASS") == nullptr;
   const bool fused_att = bf && !no_fused && D % 8 == 0 && dh % 32 == 0 && S % 8 == 0;
   if (fused_att && (att_zero_B != B || att_zero_S != S)) {
     const int64_t words = (int64_t)B * H * SS / 2;  // bf16 pairs
@@ -572,9 +573,15 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
       g.A[0] = dob; g.B[0] = cat(b.qkv, offV);
       g.At = dob_t; g.Bt = cat(b.qkv_t, offV);
       g.C = dS; g.Ct = dS_t; g.out_bf16 = 1; g.E0 = b.P; g.E1 = b.P_t;
-      g.epi = EPI_BWD_STATS; g.part = att_part;
-      CK(launch_gemm(g, st));
-      CK(launch_attn_combine(1, att_part, (S + 63) / 64, S, (int64_t)B * H * S, att_rstat, st));
+      // delta, delta_t from <dO, O> where the head width allows, else by a statistics pass
+      hipError_t ed = delta_from_o ? launch_attn_delta(dob, dob_t, b.o, o_lo, b.o_t, T, S, H, dh, att_rstat, st) : hipErrorNotSupported;
+      if (ed == hipErrorNotSupported) {
+        g.epi = EPI_BWD_STATS; g.part = att_part;
+        CK(launch_gemm(g, st));
+        CK(launch_attn_combine(1, att_part, (S + 63) / 64, S, (int64_t)B * H * S, att_rstat, st));
+      } else {
+        CK(ed);
+      }
       g.epi = EPI_BWD_DS; g.part = nullptr; g.rstat = att_rstat;
       CK(launch_gemm(g, st));
     } else {

@@ -96,6 +96,9 @@ hipError_t launch_gemm_dual(const Gemm& g, hipStream_t st);  // bf16, aligned op
 hipError_t launch_fill_f32(float* p, int64_t n, float val, hipStream_t st);
 // Combine the per-part row statistics of the attention epilogues: forward (online softmax merge)
 // -> rstat[row] = (m, 1/l, r); backward (plain sums) -> rstat[row] = (delta, delta_t, 0).
+// Softmax-adjoint row statistics from dO and O (bf16 operands, head width 8 * 2^k); hipErrorNotSupported otherwise.
+hipError_t launch_attn_delta(const void* dO, const void* dO_t, const void* O, const void* O_lo, const void* O_t, int T, int S,
+                             int H, int dh, float* rstat, hipStream_t st);
 hipError_t launch_attn_combine(int backward, const float* part, int NP, int M, int64_t rows, float* rstat, hipStream_t st);
 
 // probe.hip: batch-loop accumulation and Hessian-column statistics

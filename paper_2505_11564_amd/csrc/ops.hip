@@ -114,6 +114,52 @@ hipError_t launch_attn_combine(int backward, const float* part, int NP, int M, i
   return hipGetLastError();
 }
 
+// delta = <dO, O>, delta_t = <dO_t, O> + <dO, O_t> per (token, head): the row sums sum_j P dP and
+// sum_j (P_t dP + P dP_t) of the softmax adjoint, obtained without forming dP (O = P V, so
+// sum_j P_ij (dO_i . V_j) = dO_i . O_i).  Operands are bf16 [T, D]; O takes its low-order half.
+// One wavefront per token, 8 columns per lane; a head is dh / 8 adjacent lanes (a power of two).
+__global__ __launch_bounds__(256) void attn_delta_kernel(const bf16* __restrict__ dO, const bf16* __restrict__ dO_t,
+                                                         const bf16* __restrict__ O, const bf16* __restrict__ O_lo,
+                                                         const bf16* __restrict__ O_t, int T, int S, int H, int dh,
+                                                         float* __restrict__ rstat) {
+  const int lane = threadIdx.x & 63;
+  const int tok = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (tok >= T) return;
+  const int D = H * dh, lph = dh >> 3;  // lanes per head
+  const int b = tok / S, sq = tok % S;
+  for (int c0 = 0; c0 < D; c0 += 512) {
+    const int c = c0 + lane * 8;
+    float d = 0.f, dt = 0.f;
+    if (c < D) {
+      float a[8], at[8], o[8], ol[8], ot[8];
+      const int64_t i8 = ((int64_t)tok * D + c) >> 3;
+      ld8(dO, i8, a); ld8(dO_t, i8, at); ld8(O, i8, o); ld8(O_t, i8, ot);
+      if (O_lo) ld8(O_lo, i8, ol);
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        const float of = O_lo ? o[q] + ol[q] : o[q];
+        d += a[q] * of;
+        dt += at[q] * of + a[q] * ot[q];
+      }
+    }
+    for (int m = 1; m < lph; m <<= 1) { d += __shfl_xor(d, m, 64); dt += __shfl_xor(dt, m, 64); }
+    if (c < D && (lane & (lph - 1)) == 0) {
+      const int h = c / dh;
+      float* dst = rstat + (((int64_t)b * H + h) * S + sq) * 3;
+      dst[0] = d; dst[1] = dt; dst[2] = 0.f;
+    }
+  }
+}
+hipError_t launch_attn_delta(const void* dO, const void* dO_t, const void* O, const void* O_lo, const void* O_t, int T, int S,
+                             int H, int dh, float* rstat, hipStream_t st) {
+  const int lph = dh / 8;
+  if (dh % 8 || (lph & (lph - 1)) || lph > 64 || (H * dh) % 8) return hipErrorNotSupported;
+  if (!all_aligned16({dO, dO_t, O, O_lo, O_t})) return hipErrorNotSupported;
+  hipLaunchKernelGGL(attn_delta_kernel, dim3((T + 3) / 4), dim3(256), 0, st, (const bf16*)dO, (const bf16*)dO_t, (const bf16*)O,
+                     (const bf16*)O_lo, (const bf16*)O_t, T, S, H, dh, rstat);
+  return hipGetLastError();
+}
+
 // ------------------------------------------------------------ fill / cast ----
 
 __global__ void fill_f32_kernel(float* p, int64_t n, float val) {
