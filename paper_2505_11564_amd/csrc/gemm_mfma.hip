@@ -74,6 +74,10 @@ __global__ __launch_bounds__(256, (min_blocks<BM, BN, KT>())) void gemm_mfma_ker
     tm = first + in_band % gsz;
     tn = in_band / gsz;
   }
+  // Causal products (k clipped to the tile row's triangle) cost in proportion to the row index.
+  // The second half of the batch walks the rows in reverse, so that the two blocks a CU holds at a
+  // time (ids b and b + half the grid) are a heavy and a light one.
+  if (p.klimit && blockIdx.y * 2 >= gridDim.y) tm = tiles_m - 1 - tm;
   const int m0 = tm * BM, n0 = tn * BN;
   if (p.skip_upper && n0 > m0 + BM - 1) return;
   const int z = blockIdx.y, z1 = z / p.nb2, z2 = z % p.nb2;
@@ -398,6 +402,7 @@ hipError_t launch_gemm_mfma(GemmP p, int nb, int allow_splitk, int force_cfg, in
   int cfg;
   if (force_cfg >= 0 && force_cfg < kNumCfg) cfg = force_cfg;
   else if (!p.transB && N <= 64 && M >= 128) cfg = 4;
+  else if (!p.transB && N <= 128 && N > 64 && p.klimit) cfg = 1;  // causal: 128-row tiles pair up heavy and light rows
   else if (!p.transB && N <= 128 && N > 64 && tiles(256, 128) >= 128) cfg = 3;
   else if (p.transA && !p.transB) cfg = tiles(256, 256) >= 160 ? 0 : 1;
   else if (!p.transA && !p.transB) cfg = tiles(256, 256) >= 256 ? 0 : (p.K >= 1536 ? 1 : 2);
