@@ -32,11 +32,13 @@ namespace hf {
 // 128x128 tiles with 32-deep slabs are compiled for three resident blocks per
 // CU (768 slots), which fits the 576- and 768-tile products of the small
 // models in one round; the other shapes take what registers they need.
-template <int BM, int BN, int KT>
-constexpr int min_blocks() { return (BM == 128 && BN == 128 && KT == 32) ? 3 : 1; }
+constexpr int cmin(int a, int b) { return a < b ? a : b; }
 
-template <int BM, int BN, int WM, int WN, int KT, int NS, bool TA, bool TB>
-__global__ __launch_bounds__(256, (min_blocks<BM, BN, KT>())) void gemm_mfma_kernel(GemmP p) {
+template <int BM, int BN, int KT, int NS>
+constexpr int min_blocks() { return (BM == 128 && BN == 128 && KT == 32 && NS == 2) ? 3 : 1; }
+
+template <int BM, int BN, int WM, int WN, int KT, int NS, bool TA, bool TB, int FL = 1>
+__global__ __launch_bounds__(256, (min_blocks<BM, BN, KT, NS>())) void gemm_mfma_kernel(GemmP p) {
   static_assert((BM / WM) * (BN / WN) == 4, "four waves");
   static_assert(NS >= 2 && NS <= 4, "stages");
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
@@ -170,86 +172,125 @@ __global__ __launch_bounds__(256, (min_blocks<BM, BN, KT>())) void gemm_mfma_ker
     }
   };
 
-  // Products of one slab held in LDS stage S.  The fragments of k-step kk+1
-  // are requested right after those of step kk have landed, so their latency
-  // runs behind the matrix instructions of step kk.  With ISSUE, the loads of
-  // the slab NS-1 ahead (into the stage that the barrier at the top of this
-  // iteration has released) are dealt out between the matrix instructions, one
-  // per MPL of them, so that issuing them never leaves the matrix cores idle.
-  auto compute = [&](auto stage_c, auto issue_c, uint32_t dyn_off) {
-    constexpr int S = decltype(stage_c)::value;
-    constexpr bool ISSUE = decltype(issue_c)::value;
-    constexpr int Q = TM * TN, QS = Q * NKK;  // matrix instructions per k-step / per slab
-    static_assert(NLOAD <= QS, "at most one load per matrix instruction");
-    Frag<AKC> a[2][TM];
-    Frag<BKC> b[2][TN];
-    auto request = [&](auto kk_c) {
-      constexpr int kk = decltype(kk_c)::value;
-      constexpr int offA = S * STAGE * 2 + (AKC ? 0 : kk * 16 * BM * 2);
-      constexpr int offB = S * STAGE * 2 + (BKC ? 0 : kk * 16 * BN * 2);
+  // Fragment registers: two sets, alternating by k-step parity; they live
+  // across slab boundaries (the last k-step of a slab is multiplied after the
+  // barrier that hands over the next slab).
+  constexpr int Q = TM * TN, QS = Q * NKK;  // matrix instructions per k-step / per slab
+  static_assert(NLOAD * FL <= QS, "at most one load per matrix instruction");
+  static_assert(NS == 2 && NKK % 2 == 0, "two LDS stages, an even number of k-steps per slab");
+  Frag<AKC> fa[2][TM];
+  Frag<BKC> fb[2][TN];
+  // request fragment number f (A fragments first) of k-step kk of the slab in LDS stage S
+  // (plus a run-time byte offset)
+  constexpr int NF = TM + TN;
+  auto request_one = [&](auto stage_c, auto kk_c, auto f_c, uint32_t dyn) {
+    constexpr int S = decltype(stage_c)::value, kk = decltype(kk_c)::value, f = decltype(f_c)::value;
+    constexpr int oA = S * STAGE * 2 + (AKC ? 0 : kk * 16 * BM * 2);
+    constexpr int oB = S * STAGE * 2 + (BKC ? 0 : kk * 16 * BN * 2);
+    if constexpr (f < TM) fa[kk & 1][f].template read<oA, 4 * BM * 2>(adA[AKC ? kk : 0][f] + dyn);
+    else fb[kk & 1][f - TM].template read<oB, 4 * BN * 2>(adB[BKC ? kk : 0][f - TM] + dyn);
+  };
+  auto request = [&](auto stage_c, auto kk_c, uint32_t dyn) {
+    static_for<NF>([&](auto f_c) { request_one(stage_c, kk_c, f_c, dyn); });
+  };
+  // every LDS read requested so far has landed; pins the fragments of k-step kk to this point
+  auto landed = [&](auto kk_c) {
+    constexpr int kk = decltype(kk_c)::value;
+    __builtin_amdgcn_sched_barrier(0);
+    lds_wait_all();
 #pragma unroll
-      for (int i = 0; i < TM; ++i) a[kk & 1][i].template read<offA, 4 * BM * 2>(adA[AKC ? kk : 0][i] + dyn_off);
+    for (int i = 0; i < TM; ++i) fa[kk & 1][i].tie();
 #pragma unroll
-      for (int j = 0; j < TN; ++j) b[kk & 1][j].template read<offB, 4 * BN * 2>(adB[BKC ? kk : 0][j] + dyn_off);
-    };
-    request(std::integral_constant<int, 0>{});
-    static_for<NKK>([&](auto kk_c) {
-      constexpr int kk = decltype(kk_c)::value;
+    for (int j = 0; j < TN; ++j) fb[kk & 1][j].tie();
+  };
+  // The Q matrix instructions of k-step kk.  Everything else the wave has to issue is dealt out
+  // between them, so that the matrix pipe never waits behind a run of memory instructions:
+  //  * with REQ, the fragment reads of k-step RK of the slab in stage RS (into the other register
+  //    set), one or two after each of the first Q/2 matrix instructions;
+  //  * with ISSUE, this being phase PH (0 .. NKK-1) of a pipeline iteration, the NLOAD loads of
+  //    the slab two ahead, at most one after each of the iteration's first QS / FL matrix
+  //    instructions, into LDS stage LS.
+  auto mfmas = [&](auto kk_c, auto ph_c, auto issue_c, auto ls_c, auto req_c, auto rs_c, auto rk_c, uint32_t dyn) {
+    constexpr int kk = decltype(kk_c)::value, PH = decltype(ph_c)::value;
+    constexpr bool ISSUE = decltype(issue_c)::value, REQ = decltype(req_c)::value;
+    static_for<Q>([&](auto q_c) {
+      constexpr int q = decltype(q_c)::value, g = PH * Q + q;
+      acc[q / TN][q % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk & 1][q / TN].get(), fb[kk & 1][q % TN].get(),
+                                                                    acc[q / TN][q % TN], 0, 0, 0);
+      if constexpr (REQ) {
+        static_for<NF>([&](auto f_c) {
+          constexpr int f = decltype(f_c)::value;
+          if constexpr ((f * Q) / (2 * NF) == q) request_one(rs_c, rk_c, f_c, dyn);
+        });
+      }
+      constexpr int l0 = cmin((g * NLOAD * FL) / QS, NLOAD), l1 = cmin(((g + 1) * NLOAD * FL) / QS, NLOAD);
+      if constexpr (ISSUE && l1 > l0) issue_one(ls_c, std::integral_constant<int, l0>{});
       __builtin_amdgcn_sched_barrier(0);
-      lds_wait_all();
-#pragma unroll
-      for (int i = 0; i < TM; ++i) a[kk & 1][i].tie();
-#pragma unroll
-      for (int j = 0; j < TN; ++j) b[kk & 1][j].tie();
-      if constexpr (kk + 1 < NKK) request(std::integral_constant<int, kk + 1>{});
-      __builtin_amdgcn_sched_barrier(0);
-      // matrix instruction number g of the slab is followed by load number
-      // floor((g+1) NLOAD / QS) - 1 when that differs from floor(g NLOAD / QS) - 1:
-      // the loads are spread evenly over the slab's matrix instructions
-      static_for<Q>([&](auto q_c) {
-        constexpr int q = decltype(q_c)::value, g = kk * Q + q;
-        acc[q / TN][q % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk & 1][q / TN].get(), b[kk & 1][q % TN].get(),
-                                                                      acc[q / TN][q % TN], 0, 0, 0);
-        constexpr int l0 = (g * NLOAD) / QS, l1 = ((g + 1) * NLOAD) / QS;
-        if constexpr (ISSUE && l1 > l0) {
-          issue_one(std::integral_constant<int, (S + NS - 1) % NS>{}, std::integral_constant<int, l0>{});
-          __builtin_amdgcn_sched_barrier(0);
-        }
-      });
     });
-    if constexpr (ISSUE) issue_advance();
+  };
+  using I0 = std::integral_constant<int, 0>;
+  // k-steps 0 .. NKK-2 of a slab whose k-step 0 has been requested: each waits for its
+  // fragments and multiplies while the next k-step's are requested.  On return the fragments
+  // of k-step NKK-1 are in registers and no LDS read is outstanding.
+  auto ksteps = [&](auto stage_c, auto issue_c, auto ls_c, uint32_t dyn) {
+    static_for<NKK - 1>([&](auto k_c) {
+      constexpr int k = decltype(k_c)::value;
+      landed(k_c);
+      mfmas(k_c, std::integral_constant<int, k + 1>{}, issue_c, ls_c, std::true_type{}, stage_c,
+            std::integral_constant<int, k + 1>{}, dyn);
+    });
+    landed(std::integral_constant<int, NKK - 1>{});
+  };
+  // One pipeline iteration, entered right after the barrier that publishes the slab in LDS
+  // stage S: the matrix instructions of the previous slab's last k-step (its fragments are in
+  // registers) cover this slab's first fragment reads; then k-steps 0 .. NKK-2 of this slab.
+  // With ISSUE the loads of the slab after this one go to the other stage, which every wave
+  // has finished reading before that barrier.
+  auto iteration = [&](auto stage_c, auto issue_c, uint32_t dyn) {
+    constexpr int S = decltype(stage_c)::value;
+    using LS = std::integral_constant<int, 1 - S>;
+    mfmas(std::integral_constant<int, NKK - 1>{}, I0{}, issue_c, LS{}, std::true_type{}, stage_c, I0{}, dyn);
+    ksteps(stage_c, issue_c, LS{}, dyn);
+    if constexpr (decltype(issue_c)::value) issue_advance();
   };
 
   const int nit = it1 - it0;
-#pragma unroll
-  for (int s = 0; s < NS - 1; ++s)
-    if (s < nit) issue(s);
-  // main loop over the slabs that still have a slab to prefetch, unrolled by
-  // the number of stages so that every LDS stage address is a compile-time
-  // constant; then the last NS-1 slabs, which only multiply (their stage is a
-  // run-time offset).
-  const int n_main = max(0, nit - (NS - 1));
-  for (int i0 = 0; i0 < n_main; i0 += NS) {
-    static_for<NS>([&](auto s_c) {
-      constexpr int s = decltype(s_c)::value;
-      if (i0 + s < n_main) {
-        HF_WAIT_VMCNT((NS - 2) * NLOAD);
-        __builtin_amdgcn_s_barrier();
-        __builtin_amdgcn_sched_barrier(0);
-        compute(s_c, std::true_type{}, 0u);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-    });
-  }
-  for (int i = n_main; i < nit; ++i) {
-    const int later = min(NS - 2, nit - 1 - i);  // slabs issued after slab i
-    if (later >= 2) HF_WAIT_VMCNT(2 * NLOAD);
-    else if (later == 1) HF_WAIT_VMCNT(NLOAD);
-    else HF_WAIT_VMCNT(0);
+  if (nit > 0) {
+    issue(0);
+    if (nit > 1) {
+      issue(1);
+      HF_WAIT_VMCNT(NLOAD);
+    } else {
+      HF_WAIT_VMCNT(0);
+    }
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
-    compute(std::integral_constant<int, 0>{}, std::false_type{}, (uint32_t)((i % NS) * (STAGE * 2)));
-    __builtin_amdgcn_sched_barrier(0);
+    request(I0{}, I0{}, 0u);
+    ksteps(I0{}, std::false_type{}, I0{}, 0u);
+    // iterations that still have a slab to prefetch, unrolled by two so that the
+    // LDS stage addresses are compile-time constants; then the last one, whose
+    // stage is a run-time offset
+    const int n_issue = max(0, nit - 2);
+    for (int j0 = 0; j0 < n_issue; j0 += 2) {
+      static_for<2>([&](auto s_c) {
+        constexpr int s = decltype(s_c)::value;
+        if (j0 + s < n_issue) {
+          HF_WAIT_VMCNT(0);
+          __builtin_amdgcn_s_barrier();
+          __builtin_amdgcn_sched_barrier(0);
+          iteration(std::integral_constant<int, 1 - s>{}, std::true_type{}, 0u);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      });
+    }
+    if (nit > 1) {
+      HF_WAIT_VMCNT(0);
+      __builtin_amdgcn_s_barrier();
+      __builtin_amdgcn_sched_barrier(0);
+      iteration(I0{}, std::false_type{}, (uint32_t)(((nit - 1) & 1) * (STAGE * 2)));
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    mfmas(std::integral_constant<int, NKK - 1>{}, I0{}, std::false_type{}, I0{}, std::false_type{}, I0{}, I0{}, 0u);
   }
   // ragged k remainder (handled by the last split only)
   if (ktail > 0 && ks == nks - 1) {
@@ -261,7 +302,9 @@ __global__ __launch_bounds__(256, (min_blocks<BM, BN, KT>())) void gemm_mfma_ker
       slab_guarded<BM, AKC, KT>(A, p.lda, m0, k0, p.M, kend, smem, t);
       slab_guarded<BN, BKC, KT>(B, p.ldb, n0, k0, p.N, kend, smem + A_EL, t);
       __syncthreads();
-      compute(std::integral_constant<int, 0>{}, std::false_type{}, 0u);
+      request(I0{}, I0{}, 0u);
+      ksteps(I0{}, std::false_type{}, I0{}, 0u);
+      mfmas(std::integral_constant<int, NKK - 1>{}, I0{}, std::false_type{}, I0{}, std::false_type{}, I0{}, I0{}, 0u);
     }
   }
 
@@ -356,12 +399,12 @@ __global__ __launch_bounds__(256, (min_blocks<BM, BN, KT>())) void gemm_mfma_ker
   }
 }
 
-template <int BM, int BN, int WM, int WN, int KT, int NS, bool TA, bool TB>
+template <int BM, int BN, int WM, int WN, int KT, int NS, bool TA, bool TB, int FL = 1>
 static hipError_t launch_one(const GemmP& p, dim3 grid, hipStream_t st) {
   constexpr int smem_pipe = NS * (BM + BN) * KT * 2, smem_epi = 4 * 32 * (WN + 4) * 4;
   constexpr int smem = smem_pipe > smem_epi ? smem_pipe : smem_epi;
   static bool attr_done = false;
-  auto kern = gemm_mfma_kernel<BM, BN, WM, WN, KT, NS, TA, TB>;
+  auto kern = gemm_mfma_kernel<BM, BN, WM, WN, KT, NS, TA, TB, FL>;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
@@ -371,20 +414,21 @@ static hipError_t launch_one(const GemmP& p, dim3 grid, hipStream_t st) {
   return hipGetLastError();
 }
 
-template <int BM, int BN, int WM, int WN, int KT, int NS>
+template <int BM, int BN, int WM, int WN, int KT, int NS, int FL = 1>
 static hipError_t launch_cfg(const GemmP& p, dim3 grid, hipStream_t st) {
-  if (!p.transA && !p.transB) return launch_one<BM, BN, WM, WN, KT, NS, false, false>(p, grid, st);
-  if (!p.transA && p.transB) return launch_one<BM, BN, WM, WN, KT, NS, false, true>(p, grid, st);
-  if (p.transA && !p.transB) return launch_one<BM, BN, WM, WN, KT, NS, true, false>(p, grid, st);
-  return launch_one<BM, BN, WM, WN, KT, NS, true, true>(p, grid, st);
+  if (!p.transA && !p.transB) return launch_one<BM, BN, WM, WN, KT, NS, false, false, FL>(p, grid, st);
+  if (!p.transA && p.transB) return launch_one<BM, BN, WM, WN, KT, NS, false, true, FL>(p, grid, st);
+  if (p.transA && !p.transB) return launch_one<BM, BN, WM, WN, KT, NS, true, false, FL>(p, grid, st);
+  return launch_one<BM, BN, WM, WN, KT, NS, true, true, FL>(p, grid, st);
 }
 
-// Tile configurations (index = force_cfg): block tile, slab depth, stages.
+// Tile configurations (index = force_cfg): block tile, slab depth.
 struct TileCfg { int bm, bn; };
-// 0: 256x256x64, 2 stages; 1: 128x128x64, 2 stages; 2: 128x128x32, 2 stages.
-// (Deeper pipelines, 256x128 tiles and register-staged loads were measured and
-// were slower on every shape tried.)
-// 3: 256x128x64 and 4: 128x64x64 for products one attention head wide (N = 128 / N <= 64).
+// 0: 256x256x64; 1: 128x128x64; 2: 128x128x32; 3: 256x128x64 and 4: 128x64x64 for products one
+// attention head wide (N = 128 / N <= 64).  All but the last deal the loads of the next slab out
+// over the first half of a slab's matrix instructions (FL = 2), which leaves them the second
+// half to land; the 128x64 tile has too few matrix instructions per slab for that.
+// (Three- and four-stage pipelines with 32-deep slabs were measured and were slower.)
 static const TileCfg kCfg[] = {{256, 256}, {128, 128}, {128, 128}, {256, 128}, {128, 64}};
 constexpr int kNumCfg = 5;
 
@@ -393,20 +437,22 @@ constexpr int kNumCfg = 5;
 hipError_t launch_gemm_mfma(GemmP p, int nb, int allow_splitk, int force_cfg, int force_ks, hipStream_t st) {
   const int64_t M = p.M, N = p.N;
   auto tiles = [&](int bm, int bn) { return ((M + bm - 1) / bm) * ((N + bn - 1) / bn) * (int64_t)nb; };
-  // Measured on MI355X (4096x8192x2048-class and 4096x2304x768-class shapes):
-  // 128x128 tiles with two or more blocks per CU beat 256x256 except for A^T B
-  // products with plenty of tiles; a row-contiguous B with a short k prefers
-  // 32-deep slabs (the pipeline fills sooner).
-  // (a 256-wide tile on a 128-column product, attention's P V, wastes half its matrix instructions
-  // and was still measured faster than 128 x 128 tiles there)
+  // Measured on MI355X: 256x256 tiles (one block per CU) reach 1.3-1.5 PFLOP/s when their count
+  // fills the 256 CUs evenly, 128x128 tiles (two blocks per CU) 1.1-1.3 PFLOP/s; a product with
+  // 384 tiles of 256x256 (1.5 rounds) is faster on the small tile.  A^T B products read both
+  // operands through transposing LDS reads, which the small tile hides worse, so they keep the
+  // large tile down to 160 tiles.  A row-contiguous B with a short k prefers 32-deep slabs
+  // (the pipeline fills sooner).
+  const int64_t t256 = tiles(256, 256);
+  const bool even256 = t256 >= 256 && t256 * 100 >= ((t256 + 255) / 256) * 256 * 85;
   int cfg;
   if (force_cfg >= 0 && force_cfg < kNumCfg) cfg = force_cfg;
   else if (!p.transB && N <= 64 && M >= 128) cfg = 4;
   else if (!p.transB && N <= 128 && N > 64 && p.klimit) cfg = 1;  // causal: 128-row tiles pair up heavy and light rows
   else if (!p.transB && N <= 128 && N > 64 && tiles(256, 128) >= 128) cfg = 3;
-  else if (p.transA && !p.transB) cfg = tiles(256, 256) >= 160 ? 0 : 1;
-  else if (!p.transA && !p.transB) cfg = tiles(256, 256) >= 256 ? 0 : (p.K >= 1536 ? 1 : 2);
-  else cfg = 1;
+  else if (p.transA && !p.transB) cfg = t256 >= 160 ? 0 : 1;
+  else if (!p.transA && !p.transB) cfg = even256 ? 0 : (p.K >= 1536 ? 1 : 2);
+  else cfg = even256 ? 0 : 1;
   const int bm = kCfg[cfg].bm, bn = kCfg[cfg].bn;
   const int64_t nt = tiles(bm, bn);
   int ks = 1;
@@ -416,7 +462,7 @@ hipError_t launch_gemm_mfma(GemmP p, int nb, int allow_splitk, int force_cfg, in
     // of a 256-wide tile or two of the others each) and every split keeps at least 8 slabs: a split
     // costs a zero-fill and an atomic read-modify-write of C per part, which for short k outweighs
     // the parallelism (4096 x 4096 x 512: 45 us unsplit, 143 us split in two).
-    const int64_t slots = (cfg == 0 || cfg == 3) ? 256 : 512;
+    const int64_t slots = (bm == 256) ? 256 : 512;
     const int slabs = p.nterm * (p.K / 64);
     if (nt * 2 <= slots) ks = (int)std::min<int64_t>(std::min<int64_t>(slots / nt, std::max(1, slabs / 8)), 16);
   }
@@ -441,11 +487,11 @@ hipError_t launch_gemm_mfma(GemmP p, int nb, int allow_splitk, int force_cfg, in
   }
   dim3 grid((unsigned)(nt / nb), (unsigned)nb, (unsigned)ks);
   switch (cfg) {
-    case 0: return launch_cfg<256, 256, 128, 128, 64, 2>(p, grid, st);
-    case 1: return launch_cfg<128, 128, 64, 64, 64, 2>(p, grid, st);
-    case 3: return launch_cfg<256, 128, 128, 64, 64, 2>(p, grid, st);
-    case 4: return launch_cfg<128, 64, 64, 32, 64, 2>(p, grid, st);
-    default: return launch_cfg<128, 128, 64, 64, 32, 2>(p, grid, st);
+    case 0: return launch_cfg<256, 256, 128, 128, 64, 2, 2>(p, grid, st);
+    case 1: return launch_cfg<128, 128, 64, 64, 64, 2, 2>(p, grid, st);
+    case 3: return launch_cfg<256, 128, 128, 64, 64, 2, 2>(p, grid, st);
+    case 4: return launch_cfg<128, 64, 64, 32, 64, 2, 1>(p, grid, st);
+    default: return launch_cfg<128, 128, 64, 64, 32, 2, 2>(p, grid, st);
   }
 }
 
