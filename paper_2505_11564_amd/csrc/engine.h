@@ -79,6 +79,7 @@ struct hf_ctx {
   int* flags = nullptr;  // [0] error bits, [1] number of valid labels
   double* loss_dev = nullptr;
   unsigned long long* stats_dev = nullptr;  // column statistics counters
+  float* gemm_ws = nullptr;  // fp32 scratch of the k-split dual-output products (GEMM_WS_ELEMS floats)
   float* aux_vec = nullptr;  // n floats, allocated on first use (batch-loop partial result, unit vector)
   int ensure_aux();
 

@@ -146,6 +146,7 @@ int hf_ctx::plan_and_alloc() {
     pl.add(sc, SS * 4); pl.add(sc_t, SS * 4);
     att_SS = SS;
     pl.add(norm_part, (int64_t)NORM_PART_BLOCKS * 2 * D * 4);
+    if (bf) pl.add(gemm_ws, GEMM_WS_ELEMS * 4);
     if (bf) {
       const int64_t rows = SS / desc.max_seq, np = (desc.max_seq + 63) / 64;  // B*H*S rows
       pl.add(att_part, rows * np * 3 * 4); pl.add(att_rstat, rows * 3 * 4);
@@ -222,6 +223,7 @@ struct Lin {
     Gemm g;
     g.M = M; g.N = N; g.K = K; g.lda = ldx; g.ldb = ldw < 0 ? N : ldw; g.ldc = ldy; g.transB = transW;
     g.in_bf16 = bf; g.out_bf16 = out_bf16;
+    g.ws = c->gemm_ws; g.ws_elems = c->gemm_ws ? GEMM_WS_ELEMS : 0;
     g.A[0] = X; g.B[0] = Wp(woff); g.C = Y; g.Cadd = add;
     if (X_lo) { g.A[1] = X_lo; g.B[1] = g.B[0]; }
     if (out_bf16) g.C_lo = Y_lo;
@@ -249,6 +251,7 @@ struct Lin {
     Gemm g;
     g.M = M; g.N = Kin; g.K = Nout; g.lda = lddy; g.ldb = ldw < 0 ? Nout : ldw; g.ldc = lddx; g.transB = !transW;
     g.in_bf16 = bf; g.out_bf16 = out_bf16;
+    g.ws = c->gemm_ws; g.ws_elems = c->gemm_ws ? GEMM_WS_ELEMS : 0;
     g.A[0] = dY; g.B[0] = Wp(woff); g.C = dX; g.Cadd = add;
     // Few output tiles and a long contraction (the head: K = vocabulary): two
     // split-K products; otherwise one dual-output product.

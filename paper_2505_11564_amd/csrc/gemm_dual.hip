@@ -28,6 +28,7 @@ struct DualP {
   int64_t lda, ldb, ldc;
   int nb2, divB;
   int64_t sA1, sA2, sB1, sB2, sC1, sC2;
+  int64_t sCk;         // k-split (gridDim.z > 1): elements between the partial results of consecutive splits
   float alpha;
   int out_bf16, bias_bf16;
   int klimit, skip_upper;
@@ -82,7 +83,11 @@ __global__ __launch_bounds__(256, (EPI != EPI_NONE && NT == 4 && NS == 2 ? 2 : 1
   const int m0 = tm * BM, n0 = tn * BN;
   if (p.skip_upper && n0 > m0 + BM - 1) return;
   const int z = blockIdx.y, z1 = z / p.nb2, z2 = z % p.nb2;
-  const int64_t offA = z1 * p.sA1 + z2 * p.sA2, offB = z1 * p.sB1 + (z2 / p.divB) * p.sB2, offC = z1 * p.sC1 + z2 * p.sC2;
+  // k-split (plain products only): split blockIdx.z takes a contiguous share of the full slabs and
+  // writes its partial sums to its own slice of C / Ct; the last split also takes the ragged tail
+  const int ksp = blockIdx.z, nks = gridDim.z;
+  const int64_t offA = z1 * p.sA1 + z2 * p.sA2, offB = z1 * p.sB1 + (z2 / p.divB) * p.sB2,
+                offC = z1 * p.sC1 + z2 * p.sC2 + ksp * p.sCk;
   int kbeg = 0, kend = p.K;
   if (p.klimit == 1) kend = min(p.K, m0 + BM);
   if (p.klimit == 2) kbeg = (m0 / 64) * 64;
@@ -95,16 +100,17 @@ __global__ __launch_bounds__(256, (EPI != EPI_NONE && NT == 4 && NS == 2 ? 2 : 1
 #pragma unroll
       for (int r = 0; r < 16; ++r) { accp[i][j][r] = 0.f; acct[i][j][r] = 0.f; }
 
-  const int nfull = (kend - kbeg) / KT;
-  const int ktail = (kend - kbeg) - nfull * KT;
+  const int nfull_all = (kend - kbeg) / KT;
+  const int ktail = (ksp == nks - 1) ? (kend - kbeg) - nfull_all * KT : 0;
+  const int it0 = (int)((int64_t)nfull_all * ksp / nks), nfull = (int)((int64_t)nfull_all * (ksp + 1) / nks) - it0;
 
   uint32_t voffA[NI], voffB[NI];
   slab_offsets<BM, AKC, KT>(voffA, p.lda, m0, p.M, wave, lane);
   slab_offsets<BN, BKC, KT>(voffB, p.ldb, n0, p.N, wave, lane);
   const int64_t stepA = (AKC ? (int64_t)KT : (int64_t)KT * p.lda) * 2;
   const int64_t stepB = (BKC ? (int64_t)KT : (int64_t)KT * p.ldb) * 2;
-  const int64_t a0 = (offA + (AKC ? (int64_t)m0 * p.lda + kbeg : (int64_t)kbeg * p.lda + m0)) * 2;
-  const int64_t b0 = (offB + (BKC ? (int64_t)n0 * p.ldb + kbeg : (int64_t)kbeg * p.ldb + n0)) * 2;
+  const int64_t a0 = (offA + (AKC ? (int64_t)m0 * p.lda + kbeg : (int64_t)kbeg * p.lda + m0)) * 2 + it0 * stepA;
+  const int64_t b0 = (offB + (BKC ? (int64_t)n0 * p.ldb + kbeg : (int64_t)kbeg * p.ldb + n0)) * 2 + it0 * stepB;
   int64_t curA = a0, curB = b0;  // byte offset of the next slab to issue (same for every A- / B-side operand)
   HF_LDS char* const smem_c = (HF_LDS char*)smem;
   const int wave_off = wave * (NI * 1024);
@@ -278,7 +284,7 @@ __global__ __launch_bounds__(256, (EPI != EPI_NONE && NT == 4 && NS == 2 ? 2 : 1
     if (p.Blo) lo_loop(p.A, p.Blo);
   }
   if (ktail > 0) {
-    const int k0 = kbeg + nfull * KT;
+    const int k0 = kbeg + nfull_all * KT;
     __syncthreads();
     auto guarded = [&](const void* X, int slot, bool isA) {
       if (isA) slab_guarded<BM, AKC, KT>((const bf16*)X + offA, p.lda, m0, k0, p.M, kend, smem + slot, t);
@@ -524,7 +530,7 @@ static hipError_t launch_dual_k(const DualP& p, dim3 grid, hipStream_t st) {
 // it keeps two or three slabs in flight instead of one (the LDS is its own anyway).
 template <bool TA, bool TB>
 static hipError_t launch_dual_one(const DualP& p, dim3 grid, hipStream_t st) {
-  const bool deep = (int64_t)grid.x * grid.y <= 256 && p.K >= 256;
+  const bool deep = (int64_t)grid.x * grid.y * grid.z <= 256 && p.K >= 256;
   if (p.Blo) return deep ? launch_dual_k<TA, TB, 6, 3, EPI_NONE>(p, grid, st) : launch_dual_k<TA, TB, 6, 2, EPI_NONE>(p, grid, st);
   if (p.Alo) return deep ? launch_dual_k<TA, TB, 5, 3, EPI_NONE>(p, grid, st) : launch_dual_k<TA, TB, 5, 2, EPI_NONE>(p, grid, st);
   return deep ? launch_dual_k<TA, TB, 4, 4, EPI_NONE>(p, grid, st) : launch_dual_k<TA, TB, 4, 2, EPI_NONE>(p, grid, st);
@@ -572,8 +578,31 @@ hipError_t launch_gemm_dual(const Gemm& g, hipStream_t st) {
             g.sC1 % q == 0 && g.sC2 % q == 0;
   }
   if (p.Blo && !p.Alo) return hipErrorNotSupported;
+  p.sCk = 0;
   const int64_t nt = ((g.M + 127) / 128) * (int64_t)((g.N + 127) / 128);
   dim3 grid((unsigned)nt, (unsigned)(g.nb1 * g.nb2), 1);
+  // Few output tiles and a long k (a 7B-shaped layer at 512 tokens: 128 tiles, k = 4096 or 11008):
+  // split k so that every CU holds one block; the partial sums go to fp32 scratch and a second
+  // kernel adds them up and applies bias, addend and the output format.
+  if (g.epi == EPI_NONE && g.ws && g.nb1 * g.nb2 == 1 && nt * 2 <= 256 && g.K >= 1024 && !g.klimit && !g.skip_upper) {
+    const int64_t mn = (int64_t)g.M * g.N;
+    const int ks = (int)std::min<int64_t>(std::min<int64_t>(256 / nt, g.K / 512), 8);
+    if (ks >= 2 && 2 * ks * mn <= g.ws_elems) {
+      DualP q = p;
+      q.C = g.ws; q.Ct = g.ws + ks * mn; q.Clo = nullptr; q.Cadd = nullptr; q.Cadd_t = nullptr; q.bias = nullptr; q.bias_t = nullptr;
+      q.out_bf16 = 0; q.ldc = g.N; q.sCk = mn; q.vec = (g.N % 4 == 0 && ((uintptr_t)g.ws % 16) == 0 && mn % 4 == 0) ? 1 : 0;
+      grid.z = (unsigned)ks;
+      hipError_t e;
+      if (!g.transA && !g.transB) e = launch_dual_one<false, false>(q, grid, st);
+      else if (!g.transA && g.transB) e = launch_dual_one<false, true>(q, grid, st);
+      else if (g.transA && !g.transB) e = launch_dual_one<true, false>(q, grid, st);
+      else e = launch_dual_one<true, true>(q, grid, st);
+      if (e != hipSuccess) return e;
+      e = launch_splitk_reduce(g.ws, ks, g.M, g.N, g.bias, 1, nullptr, g.Cadd, g.C, g.C_lo, g.ldc, g.out_bf16, st);
+      if (e != hipSuccess) return e;
+      return launch_splitk_reduce(g.ws + ks * mn, ks, g.M, g.N, nullptr, 0, g.bias_t, g.Cadd_t, g.Ct, nullptr, g.ldc, g.out_bf16, st);
+    }
+  }
   if (g.epi != EPI_NONE) {
     if (!p.vec || g.N % 8 != 0) return hipErrorNotSupported;
     switch (g.epi) {

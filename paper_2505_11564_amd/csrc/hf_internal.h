@@ -69,6 +69,10 @@ struct Gemm {
   void* Ct = nullptr;
   const float* Cadd_t = nullptr;
   int force_cfg = -1, force_ks = 0;  // tuning / tests: tile configuration and k-split override
+  // Dual-output products with few output tiles and a long k: fp32 scratch for the partial sums
+  // of a k-split (2 * splits * M * N floats are used when they fit); nullptr = never split.
+  float* ws = nullptr;
+  int64_t ws_elems = 0;
   // Attention epilogues of the dual-output kernel (bf16 operands, Ct != nullptr).  With them the
   // score-shaped products never go to memory in fp32: the product is formed twice, once to reduce
   // row statistics over 64-column parts and once to apply them.
@@ -104,6 +108,12 @@ hipError_t launch_attn_combine(int backward, const float* part, int NP, int M, i
 // probe.hip: batch-loop accumulation and Hessian-column statistics
 constexpr int CS_MAX_THRESHOLDS = 16, CS_MAX_BINS = 256, CS_STATS_WORDS = 32 + CS_MAX_BINS;
 struct ColThresholds { float t[CS_MAX_THRESHOLDS]; };
+constexpr int64_t GEMM_WS_ELEMS = 16ll << 20;  // 64 MiB of fp32: two results x up to 8 splits of a 512 x 2048 product, 2 x 2 of 512 x 4096
+// C = sum over `splits` partial sums (each M x N, row stride N) + bias + Cadd, written as fp32 or
+// as bf16 with an optional low-order half; rows of C / Cadd / C_lo have stride ldc.
+hipError_t launch_splitk_reduce(const float* part, int splits, int M, int N, const void* bias, int bias_bf16,
+                                const float* bias_f32, const float* Cadd, void* C, void* C_lo, int64_t ldc, int out_bf16,
+                                hipStream_t st);
 hipError_t launch_scale_add(float* h, const float* u, float w, int first, int64_t n, hipStream_t st);
 hipError_t launch_colstats_pass1(const float* h, int64_t n, const ColThresholds& thr, int nt, unsigned long long* stats,
                                  hipStream_t st);

@@ -27,6 +27,10 @@ SHAPES = {
     "llama_gqa_mid": dict(model=si._llama(2, 256, 8, 344, 777, 136, n_kv=2), batch=2, seq=136, tokens="zipf"),
     "gpt_gelu_tanh": dict(model=si._gpt(2, 64, 2, 136, 301, 40, act="gelu_tanh"), batch=2, seq=40, tokens="zipf"),
     "gpt_fused": dict(model=si._gpt(2, 128, 4, 264, 517, 200), batch=2, seq=200, tokens="zipf"),
+    # few output tiles and a contraction over more than 1024: in bf16 mode the dual-output products
+    # of the feed-forward layers split k over blocks and are summed by a second kernel (ragged k)
+    "gpt_long_k": dict(model=si._gpt(1, 64, 2, 1048, 301, 50), batch=3, seq=50, tokens="zipf"),
+    "llama_long_k": dict(model=si._llama(1, 64, 2, 1544, 257, 40), batch=2, seq=40, tokens="zipf"),
 }
 
 
