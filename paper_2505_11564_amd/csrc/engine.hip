@@ -256,7 +256,7 @@ struct Lin {
     // Few output tiles and a long contraction (the head: K = vocabulary): two
     // split-K products; otherwise one dual-output product.
     const int64_t tiles = ((int64_t)(M + 127) / 128) * ((Kin + 127) / 128);
-    if (!out_bf16 && tiles < 256 && Nout >= 8192) {
+    if (!out_bf16 && tiles < 256 && Nout >= 8192 && (tiles * 2 > 256 || !c->gemm_ws)) {
       g.allow_splitk = 1;
       CK(launch_gemm(g, st));
       Gemm t = g;
