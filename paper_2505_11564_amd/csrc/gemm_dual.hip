@@ -138,87 +138,142 @@ __global__ __launch_bounds__(256, (EPI != EPI_NONE && NT == 4 && NS == 2 ? 2 : 1
 #pragma unroll
     for (int j = 0; j < 2; ++j) adB[kk][j] = lds0 + frag_addr<BN, BKC, KT>(wn0 + j * 32, kk, lane);
 
-  // Products of the slab in stage S; the fragments of k-step kk+1 are requested
-  // as soon as those of step kk have landed (explicit reads and waits, see
-  // gemm_mfma_common.h).
-  auto compute = [&](auto stage_c) {
-    constexpr int S = decltype(stage_c)::value;
-    Frag<AKC> a[2][2], at[2][2], al[2][2];
-    Frag<BKC> b[2][2], bt[2][2], bl[2][2];
-    auto request = [&](auto kk_c) {
-      constexpr int kk = decltype(kk_c)::value;
-      constexpr int offA = S * stage_el * 2 + (AKC ? 0 : kk * 16 * BM * 2);
-      constexpr int offB = S * stage_el * 2 + (BKC ? 0 : kk * 16 * BN * 2);
+  // One wave per SIMD issues everything in order, so (as in gemm_mfma_kernel) the fragment reads
+  // of the next k-step and the loads of a later slab are dealt out between the matrix
+  // instructions, and the hand-over barrier of a slab sits before its last k-step: the matrix
+  // instructions of that k-step (fragments already in registers) cover the first reads of the
+  // next slab.  Fragment registers: two sets alternating by k-step, alive across slabs.
+  static_assert(NKK == 2, "two k-steps per slab");
+  constexpr int NFR = 2 * NT;       // fragments per k-step: two per operand tile
+  constexpr int MQ = 4 * (NT - 1);  // matrix instructions per k-step (12, 16 or 20)
+  constexpr int NLOAD = NT * NI;    // load instructions per wave per slab
+  static_assert(NLOAD <= MQ, "at most one load per matrix instruction");
+  Frag<AKC> fa[2][2], fat[2][2], fal[2][2];
+  Frag<BKC> fb[2][2], fbt[2][2], fbl[2][2];
+  // fragment f of k-step kk of the slab in stage S (+ run-time byte offset): operand tile f / 2
+  // in the order A, A_t, B, B_t, A_lo, B_lo; row block f % 2
+  auto request_one = [&](auto stage_c, auto kk_c, auto f_c, uint32_t dyn) {
+    constexpr int S = decltype(stage_c)::value, kk = decltype(kk_c)::value, f = decltype(f_c)::value;
+    constexpr int tl = f / 2, ix = f % 2, c = kk & 1;
+    constexpr int offA = S * stage_el * 2 + (AKC ? 0 : kk * 16 * BM * 2);
+    constexpr int offB = S * stage_el * 2 + (BKC ? 0 : kk * 16 * BN * 2);
+    const uint32_t aA = adA[AKC ? kk : 0][ix] + dyn, aB = adB[BKC ? kk : 0][ix] + dyn;
+    if constexpr (tl == 0) fa[c][ix].template read<offA + sA * 2, 4 * BM * 2>(aA);
+    else if constexpr (tl == 1) fat[c][ix].template read<offA + sAt * 2, 4 * BM * 2>(aA);
+    else if constexpr (tl == 2) fb[c][ix].template read<offB + sB * 2, 4 * BN * 2>(aB);
+    else if constexpr (tl == 3) fbt[c][ix].template read<offB + sBt * 2, 4 * BN * 2>(aB);
+    else if constexpr (tl == 4) fal[c][ix].template read<offA + sAlo * 2, 4 * BM * 2>(aA);
+    else fbl[c][ix].template read<offB + sBlo * 2, 4 * BN * 2>(aB);
+  };
+  auto request = [&](auto stage_c, auto kk_c, uint32_t dyn) {
+    static_for<NFR>([&](auto f_c) { request_one(stage_c, kk_c, f_c, dyn); });
+  };
+  auto landed = [&](auto kk_c) {
+    constexpr int c = decltype(kk_c)::value & 1;
+    __builtin_amdgcn_sched_barrier(0);
+    lds_wait_all();
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        a[kk & 1][i].template read<offA + sA * 2, 4 * BM * 2>(adA[AKC ? kk : 0][i]);
-        at[kk & 1][i].template read<offA + sAt * 2, 4 * BM * 2>(adA[AKC ? kk : 0][i]);
+    for (int i = 0; i < 2; ++i) {
+      fa[c][i].tie(); fat[c][i].tie(); fb[c][i].tie(); fbt[c][i].tie();
+      if constexpr (hasAlo) fal[c][i].tie();
+      if constexpr (hasBlo) fbl[c][i].tie();
+    }
+  };
+  // load number l of the slab at the issue cursor, into LDS stage S
+  auto issue_one = [&](auto stage_c, auto l_c) {
+    constexpr int S = decltype(stage_c)::value, l = decltype(l_c)::value, tl = l / NI, j = l % NI;
+    HF_LDS char* st = smem_c + S * stage_el * 2 + wave_off + j * 1024;
+    const void* X = tl == 0 ? p.A : tl == 1 ? p.At : tl == 2 ? p.B : tl == 3 ? p.Bt : tl == 4 ? p.Alo : p.Blo;
+    constexpr bool onA = (tl == 0 || tl == 1 || tl == 4);
+    constexpr int slot = tl == 0 ? sA : tl == 1 ? sAt : tl == 2 ? sB : tl == 3 ? sBt : tl == 4 ? sAlo : sBlo;
+    const char* src = (const char*)X + (onA ? curA + voffA[j] : curB + voffB[j]);
+    __builtin_amdgcn_global_load_lds((const void*)src, (HF_LDS void*)(st + slot * 2), 16, 0, 0);
+  };
+  // The MQ matrix instructions of k-step kk, in the order A B, A_t B, A B_t, A_lo B, A B_lo (each over
+  // the four 32 x 32 tiles, so that the two updates of an accumulator are four instructions apart).
+  // With REQ the fragment reads of k-step RK of stage RS follow the first MQ/2 of them; with ISSUE
+  // (PH = 0: first k-step of a pipeline iteration) one load of the slab at the cursor follows each
+  // of the first NLOAD, into stage LS.
+  auto mfmas = [&](auto kk_c, auto ph_c, auto issue_c, auto ls_c, auto req_c, auto rs_c, auto rk_c, uint32_t dyn) {
+    constexpr int c = decltype(kk_c)::value & 1, PH = decltype(ph_c)::value;
+    constexpr bool ISSUE = decltype(issue_c)::value, REQ = decltype(req_c)::value;
+    static_for<MQ>([&](auto q_c) {
+      constexpr int q = decltype(q_c)::value, ty = q / 4, i = (q % 4) / 2, j = q % 2;
+      if constexpr (ty == 0) accp[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[c][i].get(), fb[c][j].get(), accp[i][j], 0, 0, 0);
+      else if constexpr (ty == 1) acct[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fat[c][i].get(), fb[c][j].get(), acct[i][j], 0, 0, 0);
+      else if constexpr (ty == 2) acct[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[c][i].get(), fbt[c][j].get(), acct[i][j], 0, 0, 0);
+      else if constexpr (ty == 3) accp[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fal[c][i].get(), fb[c][j].get(), accp[i][j], 0, 0, 0);
+      else accp[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[c][i].get(), fbl[c][j].get(), accp[i][j], 0, 0, 0);
+      if constexpr (REQ) {
+        static_for<NFR>([&](auto f_c) {
+          constexpr int f = decltype(f_c)::value;
+          if constexpr ((f * MQ) / (2 * NFR) == q) request_one(rs_c, rk_c, f_c, dyn);
+        });
       }
-#pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        b[kk & 1][j].template read<offB + sB * 2, 4 * BN * 2>(adB[BKC ? kk : 0][j]);
-        bt[kk & 1][j].template read<offB + sBt * 2, 4 * BN * 2>(adB[BKC ? kk : 0][j]);
-      }
-      if constexpr (hasAlo) {
-#pragma unroll
-        for (int i = 0; i < 2; ++i) al[kk & 1][i].template read<offA + sAlo * 2, 4 * BM * 2>(adA[AKC ? kk : 0][i]);
-      }
-      if constexpr (hasBlo) {
-#pragma unroll
-        for (int j = 0; j < 2; ++j) bl[kk & 1][j].template read<offB + sBlo * 2, 4 * BN * 2>(adB[BKC ? kk : 0][j]);
-      }
-    };
-    request(std::integral_constant<int, 0>{});
-    static_for<NKK>([&](auto kk_c) {
-      constexpr int kk = decltype(kk_c)::value, c = kk & 1;
+      if constexpr (ISSUE && PH == 0 && q < NLOAD) issue_one(ls_c, q_c);
       __builtin_amdgcn_sched_barrier(0);
-      lds_wait_all();
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        a[c][i].tie(); at[c][i].tie(); b[c][i].tie(); bt[c][i].tie();
-        if constexpr (hasAlo) al[c][i].tie();
-        if constexpr (hasBlo) bl[c][i].tie();
-      }
-      if constexpr (kk + 1 < NKK) request(std::integral_constant<int, kk + 1>{});
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          accp[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[c][i].get(), b[c][j].get(), accp[i][j], 0, 0, 0);
-          acct[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at[c][i].get(), b[c][j].get(), acct[i][j], 0, 0, 0);
-          acct[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[c][i].get(), bt[c][j].get(), acct[i][j], 0, 0, 0);
-          if constexpr (hasAlo)
-            accp[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[c][i].get(), b[c][j].get(), accp[i][j], 0, 0, 0);
-          if constexpr (hasBlo)
-            accp[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[c][i].get(), bl[c][j].get(), accp[i][j], 0, 0, 0);
-        }
     });
   };
+  using I0 = std::integral_constant<int, 0>;
+  using I1 = std::integral_constant<int, 1>;
+  // One pipeline iteration, entered after the barrier that publishes the slab in stage S and
+  // frees stage LS: last k-step of the previous slab (covering this slab's first reads and,
+  // with ISSUE, the loads of the slab NS-1 after this one), then this slab's first k-step.
+  auto iteration = [&](auto stage_c, auto issue_c, auto ls_c, uint32_t dyn) {
+    mfmas(I1{}, I0{}, issue_c, ls_c, std::true_type{}, stage_c, I0{}, dyn);
+    landed(I0{});
+    mfmas(I0{}, I1{}, issue_c, ls_c, std::true_type{}, stage_c, I1{}, dyn);
+    landed(I1{});
+    if constexpr (decltype(issue_c)::value) { curA += stepA; curB += stepB; }
+  };
+  // at most x slabs of loads may still be in flight (vmcnt counts instructions)
+  auto wait_slabs = [&](int x) {
+    if (x >= 3) HF_WAIT_VMCNT(3 * NLOAD);
+    else if (x == 2) HF_WAIT_VMCNT(2 * NLOAD);
+    else if (x == 1) HF_WAIT_VMCNT(NLOAD);
+    else HF_WAIT_VMCNT(0);
+  };
+  // a whole slab already in LDS stage 0 (prologue, ragged tail): both k-steps
+  auto first_slab = [&](auto last_c) {
+    request(I0{}, I0{}, 0u);
+    landed(I0{});
+    mfmas(I0{}, I1{}, std::false_type{}, I0{}, std::true_type{}, I0{}, I1{}, 0u);
+    landed(I1{});
+    if constexpr (decltype(last_c)::value)
+      mfmas(I1{}, I1{}, std::false_type{}, I0{}, std::false_type{}, I0{}, I0{}, 0u);
+  };
 
-  // NS LDS stages: iteration i waits for slab i, passes one barrier (every wave
-  // is then done with slab i-1), issues slab i+NS-1 into the stage just freed
-  // and multiplies slab i.
-  constexpr int NLOAD = NT * NI;
 #pragma unroll
-  for (int s0 = 0; s0 < NS - 1; ++s0)
+  for (int s0 = 0; s0 < NS; ++s0)
     if (s0 < nfull) issue(s0);
-  for (int i0 = 0; i0 < nfull; i0 += NS) {
-    static_for<NS>([&](auto s_c) {
-      constexpr int s = decltype(s_c)::value;
-      const int i = i0 + s;
-      if (i < nfull) {
-        const int later = min(NS - 2, nfull - 1 - i);  // slabs issued after slab i so far
-        if (later >= 2) HF_WAIT_VMCNT(2 * NLOAD);
-        else if (later == 1) HF_WAIT_VMCNT(NLOAD);
-        else HF_WAIT_VMCNT(0);
-        __builtin_amdgcn_s_barrier();
-        __builtin_amdgcn_sched_barrier(0);
-        if (i + NS - 1 < nfull) issue((s + NS - 1) % NS);
-        compute(s_c);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-    });
+  if (nfull > 0) {
+    wait_slabs(min(NS, nfull) - 1);
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    first_slab(std::false_type{});
+    // iterations that still have a slab to prefetch (stage numbers are compile-time constants),
+    // then the remaining ones with the stage as a run-time offset
+    const int n_issue = max(0, nfull - NS);
+    for (int j0 = 0; j0 < n_issue; j0 += NS) {
+      static_for<NS>([&](auto s_c) {
+        constexpr int s = decltype(s_c)::value;
+        if (j0 + s < n_issue) {
+          HF_WAIT_VMCNT((NS - 2) * NLOAD);
+          __builtin_amdgcn_s_barrier();
+          __builtin_amdgcn_sched_barrier(0);
+          iteration(std::integral_constant<int, (s + 1) % NS>{}, std::true_type{}, s_c, 0u);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      });
+    }
+    for (int j = n_issue; j + 1 < nfull; ++j) {
+      wait_slabs(min(nfull - 2 - j, NS - 2));
+      __builtin_amdgcn_s_barrier();
+      __builtin_amdgcn_sched_barrier(0);
+      iteration(I0{}, std::false_type{}, I0{}, (uint32_t)(((j + 1) % NS) * (stage_el * 2)));
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    mfmas(I1{}, I1{}, std::false_type{}, I0{}, std::false_type{}, I0{}, I0{}, 0u);
   }
   if constexpr (EPI != EPI_NONE && NT == 4) {
     // Low-order primal terms A_lo B and A B_lo (forward scores) as further
@@ -294,7 +349,7 @@ __global__ __launch_bounds__(256, (EPI != EPI_NONE && NT == 4 && NS == 2 ? 2 : 1
     if (hasAlo) guarded(p.Alo, sAlo, true);
     if (hasBlo) guarded(p.Blo, sBlo, false);
     __syncthreads();
-    compute(std::integral_constant<int, 0>{});
+    first_slab(std::true_type{});
   }
 
   // ---- epilogue -------------------------------------------------------------
