@@ -653,9 +653,10 @@ hipError_t launch_gemm_dual(const Gemm& g, hipStream_t st) {
       else if (g.transA && !g.transB) e = launch_dual_one<true, false>(q, grid, st);
       else e = launch_dual_one<true, true>(q, grid, st);
       if (e != hipSuccess) return e;
-      e = launch_splitk_reduce(g.ws, ks, g.M, g.N, g.bias, 1, nullptr, g.Cadd, g.C, g.C_lo, g.ldc, g.out_bf16, st);
-      if (e != hipSuccess) return e;
-      return launch_splitk_reduce(g.ws + ks * mn, ks, g.M, g.N, nullptr, 0, g.bias_t, g.Cadd_t, g.Ct, nullptr, g.ldc, g.out_bf16, st);
+      SplitKOut o0, o1;
+      o0.part = g.ws; o0.bias_bf16 = (const bf16*)g.bias; o0.Cadd = g.Cadd; o0.C = g.C; o0.C_lo = g.C_lo;
+      o1.part = g.ws + ks * mn; o1.bias_f32 = g.bias_t; o1.Cadd = g.Cadd_t; o1.C = g.Ct;
+      return launch_splitk_reduce(o0, o1, ks, g.M, g.N, g.ldc, g.out_bf16, st);
     }
   }
   if (g.epi != EPI_NONE) {

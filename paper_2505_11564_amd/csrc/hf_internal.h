@@ -109,10 +109,18 @@ hipError_t launch_attn_combine(int backward, const float* part, int NP, int M, i
 constexpr int CS_MAX_THRESHOLDS = 16, CS_MAX_BINS = 256, CS_STATS_WORDS = 32 + CS_MAX_BINS;
 struct ColThresholds { float t[CS_MAX_THRESHOLDS]; };
 constexpr int64_t GEMM_WS_ELEMS = 16ll << 20;  // 64 MiB of fp32: two results x up to 8 splits of a 512 x 2048 product, 2 x 2 of 512 x 4096
-// C = sum over `splits` partial sums (each M x N, row stride N) + bias + Cadd, written as fp32 or
-// as bf16 with an optional low-order half; rows of C / Cadd / C_lo have stride ldc.
-hipError_t launch_splitk_reduce(const float* part, int splits, int M, int N, const void* bias, int bias_bf16,
-                                const float* bias_f32, const float* Cadd, void* C, void* C_lo, int64_t ldc, int out_bf16,
+// One result of a k-split dual-output product: C = sum over the splits' partial sums (each
+// M x N, row stride N, consecutive splits M*N apart) + bias + Cadd, written as fp32 or as bf16
+// with an optional low-order half; rows of C / Cadd / C_lo have stride ldc.
+struct SplitKOut {
+  const float* part = nullptr;
+  const bf16* bias_bf16 = nullptr;
+  const float* bias_f32 = nullptr;
+  const float* Cadd = nullptr;
+  void* C = nullptr;
+  void* C_lo = nullptr;
+};
+hipError_t launch_splitk_reduce(const SplitKOut& o0, const SplitKOut& o1, int splits, int M, int N, int64_t ldc, int out_bf16,
                                 hipStream_t st);
 hipError_t launch_scale_add(float* h, const float* u, float w, int first, int64_t n, hipStream_t st);
 hipError_t launch_colstats_pass1(const float* h, int64_t n, const ColThresholds& thr, int nt, unsigned long long* stats,

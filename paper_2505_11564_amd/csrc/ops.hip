@@ -207,14 +207,13 @@ __global__ void cast_pair_kernel(const float* a, const float* b, AT* oa, AT* ob,
   }
 }
 // Second half of a k-split dual-output product: C = sum of the partial sums + bias + Cadd, in
-// the output format of the unsplit kernel (fp32, or bf16 with an optional low-order half).
+// the output format of the unsplit kernel (fp32, or bf16 with an optional low-order half), for
+// both results in one launch (blockIdx.y selects the result).
 // VEC: four consecutive columns per thread (N, ldc multiples of 4, 16-byte aligned rows).
 template <bool VEC>
-__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ part, int splits, int M, int N,
-                                                            const void* __restrict__ bias, int bias_bf16,
-                                                            const float* __restrict__ bias_f32,
-                                                            const float* __restrict__ Cadd, void* __restrict__ C,
-                                                            void* __restrict__ C_lo, int64_t ldc, int out_bf16) {
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(SplitKOut o0, SplitKOut o1, int splits, int M, int N, int64_t ldc,
+                                                            int out_bf16) {
+  const SplitKOut o = blockIdx.y ? o1 : o0;
   constexpr int W = VEC ? 4 : 1;
   const int64_t mn = (int64_t)M * N, nq = mn / W;
   const int ncol = N / W;
@@ -225,7 +224,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
 #pragma unroll
     for (int q = 0; q < W; ++q) v[q] = 0.f;
     for (int k = 0; k < splits; ++k) {
-      const float* src = part + k * mn + m * N + n;
+      const float* src = o.part + k * mn + m * N + n;
       if (VEC) {
         const float4 x = *(const float4*)src;
         v[0] += x.x; v[1 % W] += x.y; v[2 % W] += x.z; v[3 % W] += x.w;
@@ -235,41 +234,38 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
     }
 #pragma unroll
     for (int q = 0; q < W; ++q) {
-      if (bias) v[q] += bias_bf16 ? (float)((const bf16*)bias)[n + q] : ((const float*)bias)[n + q];
-      if (bias_f32) v[q] += bias_f32[n + q];
+      if (o.bias_bf16) v[q] += (float)o.bias_bf16[n + q];
+      if (o.bias_f32) v[q] += o.bias_f32[n + q];
     }
     const int64_t ci = m * ldc + n;
-    if (Cadd) {
+    if (o.Cadd) {
 #pragma unroll
-      for (int q = 0; q < W; ++q) v[q] += Cadd[ci + q];
+      for (int q = 0; q < W; ++q) v[q] += o.Cadd[ci + q];
     }
     if (out_bf16) {
 #pragma unroll
       for (int q = 0; q < W; ++q) {
         const bf16 h = (bf16)v[q];
-        ((bf16*)C)[ci + q] = h;
-        if (C_lo) ((bf16*)C_lo)[ci + q] = (bf16)(v[q] - (float)h);
+        ((bf16*)o.C)[ci + q] = h;
+        if (o.C_lo) ((bf16*)o.C_lo)[ci + q] = (bf16)(v[q] - (float)h);
       }
     } else {
-      if (VEC) *(float4*)((float*)C + ci) = make_float4(v[0], v[1 % W], v[2 % W], v[3 % W]);
-      else ((float*)C)[ci] = v[0];
+      if (VEC) *(float4*)((float*)o.C + ci) = make_float4(v[0], v[1 % W], v[2 % W], v[3 % W]);
+      else ((float*)o.C)[ci] = v[0];
     }
   }
 }
-hipError_t launch_splitk_reduce(const float* part, int splits, int M, int N, const void* bias, int bias_bf16,
-                                const float* bias_f32, const float* Cadd, void* C, void* C_lo, int64_t ldc, int out_bf16,
+hipError_t launch_splitk_reduce(const SplitKOut& o0, const SplitKOut& o1, int splits, int M, int N, int64_t ldc, int out_bf16,
                                 hipStream_t st) {
   if (M <= 0 || N <= 0) return hipSuccess;
-  if (!part || !C || splits < 1) return hipErrorInvalidValue;
-  const bool vec = N % 4 == 0 && ldc % 4 == 0 && (((uintptr_t)part | (uintptr_t)C | (uintptr_t)Cadd) & 15) == 0;
+  if (!o0.part || !o0.C || !o1.part || !o1.C || splits < 1) return hipErrorInvalidValue;
+  const uintptr_t al = (uintptr_t)o0.part | (uintptr_t)o0.C | (uintptr_t)o0.Cadd | (uintptr_t)o1.part | (uintptr_t)o1.C |
+                       (uintptr_t)o1.Cadd;
+  const bool vec = N % 4 == 0 && ldc % 4 == 0 && (al & 15) == 0;
   const int64_t nq = (int64_t)M * N / (vec ? 4 : 1);
-  const int nb = ew_blocks(nq);
-  if (vec)
-    hipLaunchKernelGGL(splitk_reduce_kernel<true>, dim3(nb), dim3(256), 0, st, part, splits, M, N, bias, bias_bf16, bias_f32, Cadd,
-                       C, C_lo, ldc, out_bf16);
-  else
-    hipLaunchKernelGGL(splitk_reduce_kernel<false>, dim3(nb), dim3(256), 0, st, part, splits, M, N, bias, bias_bf16, bias_f32,
-                       Cadd, C, C_lo, ldc, out_bf16);
+  dim3 grid((unsigned)ew_blocks(nq), 2);
+  if (vec) hipLaunchKernelGGL(splitk_reduce_kernel<true>, grid, dim3(256), 0, st, o0, o1, splits, M, N, ldc, out_bf16);
+  else hipLaunchKernelGGL(splitk_reduce_kernel<false>, grid, dim3(256), 0, st, o0, o1, splits, M, N, ldc, out_bf16);
   return hipGetLastError();
 }
 
