@@ -44,12 +44,14 @@ def hvp_flops(model, batch, seq):
     return 16.0 * T * pm + 18.0 * batch * L * seq * seq * d
 
 
-def lanczos_bytes(n, k, reorth, basis_bytes):
+def lanczos_bytes(n, k, reorth, basis_bytes, bf16_operands=False):
     """Algorithmic HBM bytes of the vector update of iteration k: 9 fp32 words
     per element for the fused three-term part (3R+1W, 2R+1W, 1R+1W); one
     classical Gram-Schmidt pass reads the k+1 stored vectors twice and r three
-    times (2R+1W); appending q_{k+1} writes one basis vector."""
-    b = 36.0 * n
+    times (2R+1W); appending q_{k+1} writes one basis vector; with bf16
+    operands the normalisation also writes the bf16 copy of q_{k+1} that the
+    next Hessian-vector product multiplies with."""
+    b = 36.0 * n + (2.0 * n if bf16_operands else 0.0)
     if reorth == "full":
         b += 2.0 * (k + 1) * n * basis_bytes + 12.0 * n + basis_bytes * n
     return b
@@ -202,7 +204,7 @@ def main():
         torch.cuda.synchronize()
         if k >= max(0, depth - 4):
             upd_ms.append(e0.elapsed_time(e1))
-            upd_bytes.append(lanczos_bytes(n, k, cfg["reorth"], {"bf16": 2, "f32": 4, "none": 0}[basis]))
+            upd_bytes.append(lanczos_bytes(n, k, cfg["reorth"], {"bf16": 2, "f32": 4, "none": 0}[basis], dtype == "bf16"))
     lz_gbs = sum(upd_bytes) / (sum(upd_ms) * 1e-3) / 1e9
 
     res = {

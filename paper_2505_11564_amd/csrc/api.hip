@@ -237,7 +237,8 @@ int32_t hf_lanczos_init(hf_ctx* ctx, const float* q0_dev, int32_t reorth, void* 
   CKI(hipStreamSynchronize(st));
   const double nrm = c->host_scal[S_Q0NORM];
   if (!(nrm > 0.0) || !std::isfinite(nrm)) return c->fail(HF_EINVAL, "hf_lanczos_init: q0 has zero or non-finite norm");
-  CKI(lz_scale(q, q, reorth == HF_REORTH_FULL ? c->basis : nullptr, bq, c->n, c->scal, S_Q0NORM, st));
+  CKI(lz_scale(q, q, reorth == HF_REORTH_FULL ? c->basis : nullptr, bq, c->bf ? c->vb : nullptr, c->n, c->scal, S_Q0NORM, st));
+  c->vb_of = c->bf ? q : nullptr;
   c->lz_reorth = reorth;
   c->lz_k = 0;
   c->lz_done = 0;
@@ -541,6 +542,7 @@ int32_t hf_lanczos_import(hf_ctx* ctx, const void* state_dev, int64_t bytes, voi
   CKI(launch_fill_f32((float*)c->scal, S_COUNT * 2, 0.f, st));
   CKI(hipMemcpyAsync(c->scal + S_BETA_PREV, base + offsetof(LzHeader, beta_prev), sizeof(double), hipMemcpyDeviceToDevice, st));
   CKI(hipMemcpyAsync(c->lz_vec[0], base + 128, (size_t)c->n * 4, hipMemcpyDeviceToDevice, st));
+  c->vb_of = nullptr;  // the imported q_k has no bf16 copy yet
   CKI(hipMemcpyAsync(c->lz_vec[1], base + 128 + vb, (size_t)c->n * 4, hipMemcpyDeviceToDevice, st));
   const int64_t be = c->desc.basis_dtype == HF_BF16 ? 2 : 4;
   if (h.rows > 0)

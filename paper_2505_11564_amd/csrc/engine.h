@@ -54,6 +54,7 @@ struct hf_ctx {
   int64_t arena_bytes = 0;
   std::vector<hf::LayerBuf> lb;
   hf::bf16* vb = nullptr;  // bf16 copy of the direction (bf16 mode)
+  const float* vb_of = nullptr;  // the Lanczos vector whose bf16 copy vb currently holds (written by the update), or nullptr
   float *xL = nullptr, *xL_t = nullptr, *stf = nullptr;
   void *xf = nullptr, *xf_t = nullptr, *xf_lo = nullptr;
   // bf16 mode: low-order halves of the primal forward activations (reused by every layer)

@@ -300,7 +300,9 @@ int hf_ctx::hvp_enqueue(const void* params, const void* inputs, const int32_t* l
   if (desc.arch != HF_ARCH_MLP && (int64_t)batch * seq > (int64_t)max_batch * desc.max_seq) return fail(HF_ESHAPE, "hf_hvp: too many tokens");
   CK(launch_fill_f32((float*)flags, 2, 0.f, st));
   for (auto& zr : zero_ranges) CK(launch_fill_f32(out + zr.first, zr.second, 0.f, st));
-  if (bf) CK(launch_f32_to_bf16(v, vb, n, st));
+  // The Lanczos update leaves the bf16 copy of q_{k+1} in vb; every other direction is converted here.
+  if (bf && !(vb_of != nullptr && vb_of == v)) CK(launch_f32_to_bf16(v, vb, n, st));
+  vb_of = nullptr;
   if (desc.arch == HF_ARCH_MLP) return hvp_mlp(params, inputs, labels, batch, v, out, st);
   return hvp_transformer(params, (const int32_t*)inputs, labels, batch, seq, v, out, st);
 }
@@ -673,7 +675,8 @@ int hf_ctx::lanczos_update(float* r, double tol, double* alpha_k, double* beta_k
   // q_{k+1} = r / beta_k into the q_{k-1} buffer, then rotate; beta_prev <- beta
   void* bdst = nullptr;
   if (lz_reorth == HF_REORTH_FULL && lz_k < max_m) bdst = (char*)basis + (int64_t)lz_k * ldq * (bq ? 2 : 4);
-  CK(lz_scale(r, qp, bdst, bq, n, scal, S_BETA, st));
+  CK(lz_scale(r, qp, bdst, bq, bf ? vb : nullptr, n, scal, S_BETA, st));
+  vb_of = bf ? qp : nullptr;
   CK(hipMemcpyAsync(scal + S_BETA_PREV, scal + S_BETA, sizeof(double), hipMemcpyDeviceToDevice, st));
   std::swap(iq, iqp);
   return HF_OK;

@@ -23,7 +23,7 @@ hipError_t lz_norm_q0(const float* z, int64_t n, double* scal, double* partials,
 hipError_t lz_axpy_dot(float* r, const float* q, const float* qp, int64_t n, int use_prev, double* scal,
                        double* partials, hipStream_t st);
 hipError_t lz_axpy_nrm(float* r, const float* q, int64_t n, double* scal, double* partials, hipStream_t st);
-hipError_t lz_scale(const float* src, float* dst, void* basis, int basis_bf16, int64_t n, const double* scal, int idx,
+hipError_t lz_scale(const float* src, float* dst, void* basis, int basis_bf16, bf16* vb, int64_t n, const double* scal, int idx,
                     hipStream_t st);
 // One classical Gram-Schmidt pass of r against Q[0..nq); pass 1 is a no-op
 // unless pass 0 set the redo flag.

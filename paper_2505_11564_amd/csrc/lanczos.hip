@@ -114,9 +114,12 @@ __global__ __launch_bounds__(256) void lz_finish_kernel(const double* partials, 
   }
 }
 
-// dst = src / scal[idx]; optional basis copy (fp32 or bf16, round-to-nearest-even).
+// dst = src / scal[idx]; optional basis copy (fp32 or bf16, round-to-nearest-even) and optional
+// bf16 copy `vb` (the operand-type copy of the next Hessian-vector product's direction, which
+// would otherwise cost that product a pass over q_{k+1}).
 template <typename BT>
-__global__ __launch_bounds__(256) void lz_scale_kernel(const float* src, float* dst, BT* basis, int64_t n, const double* scal, int idx) {
+__global__ __launch_bounds__(256) void lz_scale_kernel(const float* src, float* dst, BT* basis, bf16* vb, int64_t n,
+                                                       const double* scal, int idx) {
   const float inv = (float)(1.0 / scal[idx]);
   const int64_t n4 = n >> 2;
   const int64_t stride = (int64_t)gridDim.x * 256;
@@ -134,11 +137,16 @@ __global__ __launch_bounds__(256) void lz_scale_kernel(const float* src, float* 
         ((uint2*)basis)[i] = *(const uint2*)o;
       }
     }
+    if (vb) {
+      bf16 o[4] = {(bf16)v.x, (bf16)v.y, (bf16)v.z, (bf16)v.w};
+      ((uint2*)vb)[i] = *(const uint2*)o;
+    }
   }
   for (int64_t i = (n4 << 2) + (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) {
     const float v = src[i] * inv;
     dst[i] = v;
     if (basis) basis[i] = (BT)v;
+    if (vb) vb[i] = (bf16)v;
   }
 }
 
@@ -378,11 +386,11 @@ hipError_t lz_axpy_nrm(float* r, const float* q, int64_t n, double* scal, double
   return hipGetLastError();
 }
 
-hipError_t lz_scale(const float* src, float* dst, void* basis, int basis_bf16, int64_t n, const double* scal, int idx,
+hipError_t lz_scale(const float* src, float* dst, void* basis, int basis_bf16, bf16* vb, int64_t n, const double* scal, int idx,
                     hipStream_t st) {
   const int nb = vec_blocks(n);
-  if (basis_bf16) hipLaunchKernelGGL(lz_scale_kernel<bf16>, dim3(nb), dim3(256), 0, st, src, dst, (bf16*)basis, n, scal, idx);
-  else hipLaunchKernelGGL(lz_scale_kernel<float>, dim3(nb), dim3(256), 0, st, src, dst, (float*)basis, n, scal, idx);
+  if (basis_bf16) hipLaunchKernelGGL(lz_scale_kernel<bf16>, dim3(nb), dim3(256), 0, st, src, dst, (bf16*)basis, vb, n, scal, idx);
+  else hipLaunchKernelGGL(lz_scale_kernel<float>, dim3(nb), dim3(256), 0, st, src, dst, (float*)basis, vb, n, scal, idx);
   return hipGetLastError();
 }
 
