@@ -60,10 +60,21 @@ __global__ __launch_bounds__(256, (EPI != EPI_NONE && NT == 4 && NS == 2 ? 2 : 1
   // tile slots inside a stage
   constexpr int sA = 0, sAt = TILE, sB = 2 * TILE, sBt = 3 * TILE, sAlo = 4 * TILE, sBlo = 5 * TILE;
 
-  int tile = blockIdx.x;
+  // Blocks are dealt round-robin to the 8 XCDs in launch order (x fastest).
+  //  * Batched causal products (the attention scores): XCD c takes whole batch entries
+  //    (heads) c, c + 8, ...  Every XCD then holds the same number of tiles on or below the
+  //    diagonal (a column-wise split leaves XCD 0 with 8 times the work of XCD 7 at 8 x 8
+  //    tiles), and a head's Q and K tiles are fetched by one L2 only.
+  //  * Otherwise each XCD gets a contiguous range of tiles, so that neighbours share
+  //    operand rows in its L2.
+  int tile = blockIdx.x, z = blockIdx.y;
   {
     const int nt = gridDim.x;
-    if (nt >= 16) {
+    if (p.skip_upper && (nt & 7) == 0 && (gridDim.y & 7) == 0) {
+      const int x = blockIdx.x, y = blockIdx.y;
+      z = (y >> 3) * 8 + (x & 7);
+      tile = (y & 7) * (nt >> 3) + (x >> 3);
+    } else if (nt >= 16) {
       const int per = nt / 8, rem = nt % 8;
       const int x = tile % 8, q = tile / 8;
       tile = x * per + min(x, rem) + q;
@@ -82,7 +93,7 @@ __global__ __launch_bounds__(256, (EPI != EPI_NONE && NT == 4 && NS == 2 ? 2 : 1
   }
   const int m0 = tm * BM, n0 = tn * BN;
   if (p.skip_upper && n0 > m0 + BM - 1) return;
-  const int z = blockIdx.y, z1 = z / p.nb2, z2 = z % p.nb2;
+  const int z1 = z / p.nb2, z2 = z % p.nb2;
   // k-split (plain products only): split blockIdx.z takes a contiguous share of the full slabs and
   // writes its partial sums to its own slice of C / Ct; the last split also takes the ragged tail
   const int ksp = blockIdx.z, nks = gridDim.z;

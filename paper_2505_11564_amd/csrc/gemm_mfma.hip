@@ -51,10 +51,17 @@ __global__ __launch_bounds__(256, (min_blocks<BM, BN, KT, NS>())) void gemm_mfma
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);  // wave-uniform, kept in an SGPR
   // tile order: blocks are dealt round-robin to the 8 XCDs; give each XCD a
   // contiguous range of tiles so that neighbours share operand rows in its L2.
-  int tile = blockIdx.x;
+  // Batched causal products (attention, k clipped per tile row) instead give XCD c the whole
+  // batch entries (heads) c, c + 8, ...: every XCD gets the same mix of long and short tile
+  // rows, and a head's B operand (V, K, Q or dO) is fetched by one L2 only.
+  int tile = blockIdx.x, z = blockIdx.y;
   {
     const int nt = gridDim.x;
-    if (nt >= 16) {
+    if (p.klimit && (nt & 7) == 0 && (gridDim.y & 7) == 0) {
+      const int x = blockIdx.x, y = blockIdx.y;
+      z = (y >> 3) * 8 + (x & 7);
+      tile = (y & 7) * (nt >> 3) + (x >> 3);
+    } else if (nt >= 16) {
       const int per = nt / 8, rem = nt % 8;
       const int x = tile % 8, q = tile / 8;
       // XCD x owns `per` (+1 if x < rem) consecutive tiles
@@ -82,7 +89,7 @@ __global__ __launch_bounds__(256, (min_blocks<BM, BN, KT, NS>())) void gemm_mfma
   if (p.klimit && blockIdx.y * 2 >= gridDim.y) tm = tiles_m - 1 - tm;
   const int m0 = tm * BM, n0 = tn * BN;
   if (p.skip_upper && n0 > m0 + BM - 1) return;
-  const int z = blockIdx.y, z1 = z / p.nb2, z2 = z % p.nb2;
+  const int z1 = z / p.nb2, z2 = z % p.nb2;
   const int64_t offA = z1 * p.sA1 + z2 * p.sA2, offB = z1 * p.sB1 + (z2 / p.divB) * p.sB2, offC = z1 * p.sC1 + z2 * p.sC2;
   int kbeg = 0, kend = p.K;
   if (p.klimit == 1) kend = min(p.K, m0 + BM);

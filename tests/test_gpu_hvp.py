@@ -30,6 +30,8 @@ SHAPES = {
     # few output tiles and a contraction over more than 1024: in bf16 mode the dual-output products
     # of the feed-forward layers split k over blocks and are summed by a second kernel (ragged k)
     "gpt_long_k": dict(model=si._gpt(1, 64, 2, 1048, 301, 50), batch=3, seq=50, tokens="zipf"),
+    # 8 heads and 4 x 4 score tiles: the fused attention kernels deal whole heads to the XCDs
+    "gpt_heads8": dict(model=si._gpt(1, 256, 8, 72, 97, 400), batch=1, seq=400, tokens="zipf"),
     "llama_long_k": dict(model=si._llama(1, 64, 2, 1544, 257, 40), batch=2, seq=40, tokens="zipf"),
 }
 
