@@ -57,10 +57,12 @@ __global__ __launch_bounds__(256, (min_blocks<BM, BN, KT, NS>())) void gemm_mfma
   int tile = blockIdx.x, z = blockIdx.y;
   {
     const int nt = gridDim.x;
-    if (p.klimit && (nt & 7) == 0 && (gridDim.y & 7) == 0) {
-      const int x = blockIdx.x, y = blockIdx.y;
-      z = (y >> 3) * 8 + (x & 7);
-      tile = (y & 7) * (nt >> 3) + (x >> 3);
+    if (p.klimit && (gridDim.y & 7) == 0) {
+      // launch-order index L: XCD L % 8, its r-th block; XCD c walks the tiles of batch entry c,
+      // then of entry c + 8, ...
+      const int L = blockIdx.y * nt + blockIdx.x, r = L >> 3;
+      z = (r / nt) * 8 + (L & 7);
+      tile = r % nt;
     } else if (nt >= 16) {
       const int per = nt / 8, rem = nt % 8;
       const int x = tile % 8, q = tile / 8;
