@@ -11,6 +11,11 @@
 //     VGPR staging) into a double buffer, so the loads of k-slab i+1 are in
 //     flight while slab i is multiplied; only s_waitcnt vmcnt + s_barrier
 //     separate the stages;
+//   * one wave per SIMD issues everything in order, so fragment reads and loads are
+//     dealt out between the matrix instructions (a run of them in front of a k-step
+//     leaves the matrix pipe idle), and the barrier that hands a stage over sits
+//     before a slab's last k-step, whose matrix instructions cover the first
+//     fragment reads of the next slab;
 //   * an operand that is k-contiguous in memory is stored [row][64] with the
 //     16 B chunks of a row XOR-swizzled by (row & 7), so the 16 B fragment
 //     reads of 32 consecutive rows are bank-conflict free;
@@ -25,10 +30,10 @@
 
 namespace hf {
 
-// Pipeline: NS LDS stages.  Iteration i waits for slab i, passes one barrier
-// (which also tells every wave that slab i-1 has been consumed), issues the
-// loads of slab i+NS-1 into the stage slab i-1 occupied, and multiplies slab i:
-// NS-1 slabs of loads are in flight behind the matrix cores.
+// Pipeline: two LDS stages.  Iteration j waits for slab j+1, passes one barrier
+// (every wave then holds the fragments of slab j's last k-step in registers, so
+// slab j's stage is free), multiplies that last k-step and the first k-steps of
+// slab j+1 while the loads of slab j+2 go to the freed stage.
 // 128x128 tiles with 32-deep slabs are compiled for three resident blocks per
 // CU (768 slots), which fits the 576- and 768-tile products of the small
 // models in one round; the other shapes take what registers they need.
@@ -40,7 +45,7 @@ constexpr int min_blocks() { return (BM == 128 && BN == 128 && KT == 32 && NS ==
 template <int BM, int BN, int WM, int WN, int KT, int NS, bool TA, bool TB, int FL = 1>
 __global__ __launch_bounds__(256, (min_blocks<BM, BN, KT, NS>())) void gemm_mfma_kernel(GemmP p) {
   static_assert((BM / WM) * (BN / WN) == 4, "four waves");
-  static_assert(NS >= 2 && NS <= 4, "stages");
+  static_assert(NS == 2, "stages");
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
   HF_LDS bf16* smem = (HF_LDS bf16*)smem_raw;
   constexpr int A_EL = BM * KT, B_EL = BN * KT, STAGE = A_EL + B_EL;
