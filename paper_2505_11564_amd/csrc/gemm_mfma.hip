@@ -479,6 +479,15 @@ hipError_t launch_gemm_mfma(GemmP p, int nb, int allow_splitk, int force_cfg, in
     const int64_t slots = (bm == 256) ? 256 : 512;
     const int slabs = p.nterm * (p.K / 64);
     if (nt * 2 <= slots) ks = (int)std::min<int64_t>(std::min<int64_t>(slots / nt, std::max(1, slabs / 8)), 16);
+    // A very long k (the head adjoint: k = vocabulary, 1500 slabs) can afford more parts than
+    // are resident at once: take the smallest count whose blocks fill whole rounds of the slots
+    // (192 tiles x 8 = 3 x 512 instead of 384 of 512).  For shorter k the extra atomic passes
+    // over C cost more than the fuller rounds gain (measured on the weight-gradient products).
+    auto full_rounds = [&](int k2) { const int64_t rem = (nt * k2) % slots; return rem == 0 || rem >= slots - slots / 16; };
+    if (slabs >= 512 && !full_rounds(ks)) {
+      for (int k2 = ks + 1; k2 <= 16; ++k2)
+        if (full_rounds(k2) && slabs / k2 >= 16) { ks = k2; break; }
+    }
   }
   if (ks > 1) {
     // accumulate with atomics on top of Cadd (or zero)
