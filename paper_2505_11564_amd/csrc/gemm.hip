@@ -289,6 +289,8 @@ static hipError_t launch_bf16_cfg(const GemmP& p, dim3 grid, hipStream_t st) {
 static bool aligned_to(const void* ptr, size_t a) { return ptr == nullptr || ((uintptr_t)ptr % a) == 0; }
 
 static hipError_t launch_gemm_single(const Gemm& g, hipStream_t st);
+static int prepare_single(const Gemm& g, GemmP& p);
+static hipError_t launch_prepared(int kind, const Gemm& g, GemmP& p, hipStream_t st);
 
 hipError_t launch_gemm(const Gemm& g, hipStream_t st) {
   if (!g.Ct) return launch_gemm_single(g, st);
@@ -317,21 +319,28 @@ hipError_t launch_gemm(const Gemm& g, hipStream_t st) {
   if (g.epi != EPI_NONE) return hipErrorNotSupported;  // the caller takes the unfused path
   Gemm p = g;
   p.At = nullptr; p.Bt = nullptr; p.Ct = nullptr; p.Cadd_t = nullptr; p.bias_t = nullptr;
-  hipError_t e = launch_gemm_single(p, st);
-  if (e != hipSuccess) return e;
   Gemm t = g;
   t.At = nullptr; t.Bt = nullptr; t.Ct = nullptr; t.Cadd_t = nullptr;
   t.A[0] = g.At; t.B[0] = g.B[0]; t.A[1] = g.A[0]; t.B[1] = g.Bt; t.A[2] = nullptr; t.B[2] = nullptr;
   t.C = g.Ct; t.C_lo = nullptr; t.Cadd = g.Cadd_t; t.bias = nullptr;
-  return launch_gemm_single(t, st);
+  GemmP pp, pt;
+  const int kp = prepare_single(p, pp), kt = prepare_single(t, pt);
+  if (kp == 2 && kt == 2 && g.nb1 * g.nb2 == 1 && p.force_cfg < 0 && !p.allow_splitk) {
+    const hipError_t e2 = launch_gemm_mfma_pair(pp, pt, st);
+    if (e2 != hipErrorNotSupported) return e2;
+  }
+  hipError_t e = launch_prepared(kp, p, pp, st);
+  if (e != hipSuccess) return e;
+  return launch_prepared(kt, t, pt, st);
 }
 
-static hipError_t launch_gemm_single(const Gemm& g, hipStream_t st) {
-  if (g.M <= 0 || g.N <= 0 || g.nb1 <= 0 || g.nb2 <= 0) return hipSuccess;
+// Validates a single-output description and fills the kernel parameters.  Returns 0: nothing to
+// do, 1: fp32 kernel, 2: MFMA fast path, 3: register-staged bf16 fallback, -1: invalid.
+static int prepare_single(const Gemm& g, GemmP& p) {
+  if (g.M <= 0 || g.N <= 0 || g.nb1 <= 0 || g.nb2 <= 0) return 0;
   if (!g.A[0] || !g.B[0] || !g.C || (g.A[1] && !g.B[1]) || (g.A[2] && (!g.B[2] || !g.A[1])) || (g.Cadd && g.out_bf16) ||
       (g.C_lo && !g.out_bf16))
-    return hipErrorInvalidValue;
-  GemmP p;
+    return -1;
   p.nterm = 0;
   for (int i = 0; i < 3; ++i) { p.A[i] = g.A[i]; p.B[i] = g.B[i]; if (g.A[i]) p.nterm = i + 1; }
   p.C_lo = g.C_lo;
@@ -342,15 +351,8 @@ static hipError_t launch_gemm_single(const Gemm& g, hipStream_t st) {
   p.divB = g.divB > 0 ? g.divB : 1;
   p.alpha = g.alpha; p.out_bf16 = g.out_bf16; p.bias_bf16 = g.in_bf16;
   p.klimit = g.klimit; p.skip_upper = g.skip_upper;
-  const int nb = g.nb1 * g.nb2;
-  if (!g.in_bf16) {
-    constexpr int BM = 64, BN = 64;
-    p.tiles_n = (g.N + BN - 1) / BN;
-    p.vecA = p.vecB = 0;
-    dim3 grid(p.tiles_n * ((g.M + BM - 1) / BM), nb);
-    hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, 16>), grid, dim3(256), 0, st, p);
-    return hipGetLastError();
-  }
+  p.tiles_n = 0; p.vecA = p.vecB = 0;
+  if (!g.in_bf16) return 1;
   // vector loaders: k-contiguous operands need 16 B alignment of every row
   // start and batch slice, r-contiguous ones 4 B.
   auto vec_ok = [&](const void* x0, const void* x1, const void* x2, int64_t ld, int64_t s1, int64_t s2, bool kcontig) {
@@ -368,11 +370,33 @@ static hipError_t launch_gemm_single(const Gemm& g, hipStream_t st) {
   static const int force_v1 = std::getenv("HF_GEMM_V1") ? 1 : 0;
   if (!force_v1 && g.M >= 8 && g.N >= 8 && fast_ok(g.A[0], g.A[1], g.A[2], g.lda, g.sA1, g.sA2, g.transA, g.M) &&
       fast_ok(g.B[0], g.B[1], g.B[2], g.ldb, g.sB1, g.sB2, !g.transB, g.N))
-    return launch_gemm_mfma(p, nb, g.allow_splitk, g.force_cfg, g.force_ks, st);
+    return 2;
+  return 3;
+}
+
+static hipError_t launch_prepared(int kind, const Gemm& g, GemmP& p, hipStream_t st) {
+  const int nb = g.nb1 * g.nb2;
+  if (kind == 0) return hipSuccess;
+  if (kind < 0) return hipErrorInvalidValue;
+  if (kind == 1) {
+    constexpr int BM = 64, BN = 64;
+    p.tiles_n = (g.N + BN - 1) / BN;
+    p.vecA = p.vecB = 0;
+    dim3 grid(p.tiles_n * ((g.M + BM - 1) / BM), nb);
+    hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, 16>), grid, dim3(256), 0, st, p);
+    return hipGetLastError();
+  }
+  if (kind == 2) return launch_gemm_mfma(p, nb, g.allow_splitk, g.force_cfg, g.force_ks, st);
   constexpr int BM = 128, BN = 128;
   p.tiles_n = (g.N + BN - 1) / BN;
   dim3 grid(p.tiles_n * ((g.M + BM - 1) / BM), nb);
   return launch_bf16_cfg<BM, BN, 64, 64>(p, grid, st);
+}
+
+static hipError_t launch_gemm_single(const Gemm& g, hipStream_t st) {
+  GemmP p;
+  const int kind = prepare_single(g, p);
+  return launch_prepared(kind, g, p, st);
 }
 
 }  // namespace hf

@@ -42,8 +42,9 @@ constexpr int cmin(int a, int b) { return a < b ? a : b; }
 template <int BM, int BN, int KT, int NS>
 constexpr int min_blocks() { return (BM == 128 && BN == 128 && KT == 32 && NS == 2) ? 3 : 1; }
 
-template <int BM, int BN, int WM, int WN, int KT, int NS, bool TA, bool TB, int FL = 1>
-__global__ __launch_bounds__(256, (min_blocks<BM, BN, KT, NS>())) void gemm_mfma_kernel(GemmP p) {
+// The body of the kernel: one block's product.  ks / nks: this block's part of a k-split.
+template <int BM, int BN, int WM, int WN, int KT, int NS, bool TA, bool TB, int FL>
+__device__ __forceinline__ void gemm_mfma_body(const GemmP& p, const int ks, const int nks) {
   static_assert((BM / WM) * (BN / WN) == 4, "four waves");
   static_assert(NS == 2, "stages");
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
@@ -116,7 +117,6 @@ __global__ __launch_bounds__(256, (min_blocks<BM, BN, KT, NS>())) void gemm_mfma
   const int nterm = p.nterm;
   // split-K: this block handles slabs [it0, it1) of the nterm*nfull full slabs
   const int total = nterm * nfull;
-  const int ks = blockIdx.z, nks = gridDim.z;
   const int it0 = (int)((int64_t)total * ks / nks), it1 = (int)((int64_t)total * (ks + 1) / nks);
 
   // Per-lane source offsets of this wave's load instructions (slab-invariant).
@@ -414,6 +414,19 @@ __global__ __launch_bounds__(256, (min_blocks<BM, BN, KT, NS>())) void gemm_mfma
 }
 
 template <int BM, int BN, int WM, int WN, int KT, int NS, bool TA, bool TB, int FL = 1>
+__global__ __launch_bounds__(256, (min_blocks<BM, BN, KT, NS>())) void gemm_mfma_kernel(GemmP p) {
+  gemm_mfma_body<BM, BN, WM, WN, KT, NS, TA, TB, FL>(p, blockIdx.z, gridDim.z);
+}
+
+// Two products of the same shape in one launch (a primal product and its tangent, each too
+// small to fill the CUs with 256 x 256 tiles on its own): blockIdx.z selects the product.
+struct GemmPair { GemmP g[2]; };
+template <int BM, int BN, int WM, int WN, int KT, int NS, bool TA, bool TB, int FL = 1>
+__global__ __launch_bounds__(256, (min_blocks<BM, BN, KT, NS>())) void gemm_mfma_pair_kernel(GemmPair pp) {
+  gemm_mfma_body<BM, BN, WM, WN, KT, NS, TA, TB, FL>(pp.g[blockIdx.z], 0, 1);
+}
+
+template <int BM, int BN, int WM, int WN, int KT, int NS, bool TA, bool TB, int FL = 1>
 static hipError_t launch_one(const GemmP& p, dim3 grid, hipStream_t st) {
   constexpr int smem_pipe = NS * (BM + BN) * KT * 2, smem_epi = 4 * 32 * (WN + 4) * 4;
   constexpr int smem = smem_pipe > smem_epi ? smem_pipe : smem_epi;
@@ -516,6 +529,47 @@ hipError_t launch_gemm_mfma(GemmP p, int nb, int allow_splitk, int force_cfg, in
     case 4: return launch_cfg<128, 64, 64, 32, 64, 2, 1>(p, grid, st);
     default: return launch_cfg<128, 128, 64, 64, 32, 2, 2>(p, grid, st);
   }
+}
+
+template <bool TA, bool TB>
+static hipError_t launch_pair_256(const GemmPair& pp, dim3 grid, hipStream_t st) {
+  constexpr int smem = 2 * (256 + 256) * 64 * 2;
+  static bool attr_done = false;
+  auto kern = gemm_mfma_pair_kernel<256, 256, 128, 128, 64, 2, TA, TB, 2>;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  hipLaunchKernelGGL(kern, grid, dim3(256), smem, st, pp);
+  return hipGetLastError();
+}
+
+// A primal product and its tangent (same shape, layout and term count, not batched) as one launch
+// of 256 x 256 tiles, when the two together fill the 256 CUs evenly and one alone does not (4096 x
+// 2048: 128 + 128 tiles).  Returns hipErrorNotSupported when that is not the case; the caller then
+// launches the two products one after the other.
+hipError_t launch_gemm_mfma_pair(GemmP a, GemmP b, hipStream_t st) {
+  static const int no_pair = std::getenv("HF_GEMM_NO_PAIR") ? 1 : 0;
+  if (no_pair || a.M != b.M || a.N != b.N || a.K != b.K || a.transA != b.transA || a.transB != b.transB || a.nterm != b.nterm ||
+      a.klimit || b.klimit || a.skip_upper || b.skip_upper || (a.transA && a.transB))
+    return hipErrorNotSupported;
+  const int64_t t256 = ((int64_t)(a.M + 255) / 256) * ((a.N + 255) / 256);
+  auto even = [](int64_t t) { return t >= 256 && t * 100 >= ((t + 255) / 256) * 256 * 85; };
+  if (even(t256) || !even(2 * t256) || a.K < 512) return hipErrorNotSupported;
+  GemmPair pp;
+  pp.g[0] = a; pp.g[1] = b;
+  for (int i = 0; i < 2; ++i) {
+    GemmP& p = pp.g[i];
+    p.tiles_n = (p.N + 255) / 256;
+    const int64_t q = p.out_bf16 ? 8 : 4;
+    auto al = [&](const void* x) { return x == nullptr || ((uintptr_t)x % 16) == 0; };
+    p.vecA = al(p.C) && al(p.Cadd) && al(p.C_lo) && p.ldc % q == 0 && p.sC1 % q == 0 && p.sC2 % q == 0;
+  }
+  dim3 grid((unsigned)t256, 1, 2);
+  if (!a.transA && !a.transB) return launch_pair_256<false, false>(pp, grid, st);
+  if (!a.transA && a.transB) return launch_pair_256<false, true>(pp, grid, st);
+  return launch_pair_256<true, false>(pp, grid, st);
 }
 
 }  // namespace hf
