@@ -545,13 +545,14 @@ static hipError_t launch_pair_256(const GemmPair& pp, dim3 grid, hipStream_t st)
   return hipGetLastError();
 }
 
-// A primal product and its tangent (same shape, layout and term count, not batched) as one launch
-// of 256 x 256 tiles, when the two together fill the 256 CUs evenly and one alone does not (4096 x
-// 2048: 128 + 128 tiles).  Returns hipErrorNotSupported when that is not the case; the caller then
+// A primal product and its tangent (same shape and layout, not batched) as one launch of
+// 256 x 256 tiles, when the two together fill the 256 CUs evenly and one alone does not (4096 x
+// 2048: 128 + 128 tiles).  The term counts may differ (adjoint 1, its tangent 2): the launch then
+// lasts as long as the two-term blocks, still less than two launches of 128 x 128 tiles.  Returns hipErrorNotSupported when that is not the case; the caller then
 // launches the two products one after the other.
 hipError_t launch_gemm_mfma_pair(GemmP a, GemmP b, hipStream_t st) {
   static const int no_pair = std::getenv("HF_GEMM_NO_PAIR") ? 1 : 0;
-  if (no_pair || a.M != b.M || a.N != b.N || a.K != b.K || a.transA != b.transA || a.transB != b.transB || a.nterm != b.nterm ||
+  if (no_pair || a.M != b.M || a.N != b.N || a.K != b.K || a.transA != b.transA || a.transB != b.transB ||
       a.klimit || b.klimit || a.skip_upper || b.skip_upper || (a.transA && a.transB))
     return hipErrorNotSupported;
   const int64_t t256 = ((int64_t)(a.M + 255) / 256) * ((a.N + 255) / 256);
