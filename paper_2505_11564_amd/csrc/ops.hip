@@ -402,7 +402,7 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(const float* __restrict__
                                                        const float* __restrict__ stats, const PT* gam,
                                                        const float* gam_t, int T, int d, int rows_per_block,
                                                        int accumulate, float* dx, float* dx_t, float* hv_gam,
-                                                       float* hv_bet) {
+                                                       float* hv_bet, bf16* dxb, bf16* dxb_t) {
   __shared__ float red[16];
   float pg[NORM_MAXC], pb[NORM_MAXC];
 #pragma unroll
@@ -436,8 +436,10 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(const float* __restrict__
       const float gt = gam_t[c] * dyv + gm * dytv;
       const float dxv = (g - m1 - xh * m2) * rstd;
       const float dxt = (gt - m1t - xht * m2 - xh * m2t) * rstd - dxv * st * rstd;
-      if (accumulate) { dx[base + c] += dxv; dx_t[base + c] += dxt; }
-      else { dx[base + c] = dxv; dx_t[base + c] = dxt; }
+      float ov = dxv, ovt = dxt;
+      if (accumulate) { ov += dx[base + c]; ovt += dx_t[base + c]; }
+      dx[base + c] = ov; dx_t[base + c] = ovt;
+      if (dxb) { dxb[base + c] = (bf16)ov; dxb_t[base + c] = (bf16)ovt; }
       pg[ci] += dytv * xh + dyv * xht;
       pb[ci] += dytv;
     }
@@ -466,7 +468,7 @@ __global__ __launch_bounds__(256) void norm_bwd_vec_kernel(const float* __restri
                                                            const float* __restrict__ stats, const PT* gam,
                                                            const float* gam_t, int T, int d, int rows_per_block,
                                                            int accumulate, float* dx, float* dx_t, float* hv_gam,
-                                                           float* hv_bet, float* part) {
+                                                           float* hv_bet, float* part, bf16* dxb, bf16* dxb_t) {
   __shared__ float red[16];
   const int d4 = d >> 2;
   float4 pg[NCH], pb[NCH], gm[NCH], gmt[NCH];
@@ -533,6 +535,11 @@ __global__ __launch_bounds__(256) void norm_bwd_vec_kernel(const float* __restri
         }
         ((float4*)dx)[base4 + c4] = o;
         ((float4*)dx_t)[base4 + c4] = ot;
+        if (dxb) {  // operand-type copies for the products that consume the adjoint next
+          const bf16 h[4] = {(bf16)o.x, (bf16)o.y, (bf16)o.z, (bf16)o.w}, ht[4] = {(bf16)ot.x, (bf16)ot.y, (bf16)ot.z, (bf16)ot.w};
+          ((uint2*)dxb)[base4 + c4] = *(const uint2*)h;
+          ((uint2*)dxb_t)[base4 + c4] = *(const uint2*)ht;
+        }
       }
     }
   }
@@ -565,7 +572,7 @@ __global__ __launch_bounds__(256) void norm_bwd_wave_kernel(const float* __restr
                                                             const float* __restrict__ stats, const PT* gam,
                                                             const float* gam_t, int T, int d, int rows_per_block,
                                                             int accumulate, float* dx, float* dx_t, float* hv_gam,
-                                                            float* hv_bet, float* part) {
+                                                            float* hv_bet, float* part, bf16* dxb, bf16* dxb_t) {
   extern __shared__ float colred[];  // [2][4][d]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int d4 = d >> 2;
@@ -633,6 +640,11 @@ __global__ __launch_bounds__(256) void norm_bwd_wave_kernel(const float* __restr
         }
         ((float4*)dx)[base4 + c4] = o;
         ((float4*)dx_t)[base4 + c4] = ot;
+        if (dxb) {  // operand-type copies for the products that consume the adjoint next
+          const bf16 h[4] = {(bf16)o.x, (bf16)o.y, (bf16)o.z, (bf16)o.w}, ht[4] = {(bf16)ot.x, (bf16)ot.y, (bf16)ot.z, (bf16)ot.w};
+          ((uint2*)dxb)[base4 + c4] = *(const uint2*)h;
+          ((uint2*)dxb_t)[base4 + c4] = *(const uint2*)ht;
+        }
       }
     }
   }
@@ -674,8 +686,12 @@ __global__ void norm_colsum_kernel(const float* __restrict__ part, int nblocks, 
 
 hipError_t launch_norm_bwd(int bf, int rms, const float* dy, const float* dy_t, const float* x, const float* x_t,
                            const float* stats, const void* gam, const float* gam_t, int T, int d, int accumulate,
-                           float* dx, float* dx_t, float* hv_gam, float* hv_bet, float* part, hipStream_t st) {
+                           float* dx, float* dx_t, float* hv_gam, float* hv_bet, float* part, hipStream_t st, void* dxb_v,
+                           void* dxb_t_v) {
   if (d > 256 * NORM_MAXC) return hipErrorInvalidValue;
+  bf16* dxb = (bf16*)dxb_v;
+  bf16* dxb_t = (bf16*)dxb_t_v;
+  if ((dxb == nullptr) != (dxb_t == nullptr) || (((uintptr_t)dxb | (uintptr_t)dxb_t) & 7)) return hipErrorInvalidValue;
   // part (optional): room for NORM_PART_BLOCKS x 2 x d floats; the vector kernels then leave their
   // column sums there and a second kernel adds them up (the atomics otherwise cost more than the rows)
   auto finish = [&](int blocks) {
@@ -689,7 +705,7 @@ hipError_t launch_norm_bwd(int bf, int rms, const float* dy, const float* dy_t, 
     const int nj = (d / 4 + 63) / 64;
     part = nullptr;  // narrow rows: the atomics are cheaper than a second launch
     const size_t lds = (size_t)8 * d * sizeof(float);
-#define HF_NBW2(PT, R, N) hipLaunchKernelGGL((norm_bwd_wave_kernel<PT, R, N>), dim3(blocks), dim3(256), lds, st, dy, dy_t, x, x_t, stats, (const PT*)gam, gam_t, T, d, rpb, accumulate, dx, dx_t, hv_gam, hv_bet, part)
+#define HF_NBW2(PT, R, N) hipLaunchKernelGGL((norm_bwd_wave_kernel<PT, R, N>), dim3(blocks), dim3(256), lds, st, dy, dy_t, x, x_t, stats, (const PT*)gam, gam_t, T, d, rpb, accumulate, dx, dx_t, hv_gam, hv_bet, part, dxb, dxb_t)
 #define HF_NBW1(PT, R) { if (nj <= 1) HF_NBW2(PT, R, 1); else if (nj <= 2) HF_NBW2(PT, R, 2); else if (nj <= 3) HF_NBW2(PT, R, 3); else HF_NBW2(PT, R, 4); }
     if (bf) { if (rms) HF_NBW1(bf16, true) else HF_NBW1(bf16, false) }
     else { if (rms) HF_NBW1(float, true) else HF_NBW1(float, false) }
@@ -703,7 +719,7 @@ hipError_t launch_norm_bwd(int bf, int rms, const float* dy, const float* dy_t, 
     const int blocks = (T + rpb - 1) / rpb;
     const int nch = (d / 4 + 255) / 256;
     if (blocks > NORM_PART_BLOCKS) part = nullptr;
-#define HF_NBV2(PT, R, N) hipLaunchKernelGGL((norm_bwd_vec_kernel<PT, R, N>), dim3(blocks), dim3(256), 0, st, dy, dy_t, x, x_t, stats, (const PT*)gam, gam_t, T, d, rpb, accumulate, dx, dx_t, hv_gam, hv_bet, part)
+#define HF_NBV2(PT, R, N) hipLaunchKernelGGL((norm_bwd_vec_kernel<PT, R, N>), dim3(blocks), dim3(256), 0, st, dy, dy_t, x, x_t, stats, (const PT*)gam, gam_t, T, d, rpb, accumulate, dx, dx_t, hv_gam, hv_bet, part, dxb, dxb_t)
 #define HF_NBV1(PT, R) { if (nch <= 1) HF_NBV2(PT, R, 1); else if (nch <= 2) HF_NBV2(PT, R, 2); else if (nch <= 4) HF_NBV2(PT, R, 4); else HF_NBV2(PT, R, 8); }
     if (bf) { if (rms) HF_NBV1(bf16, true) else HF_NBV1(bf16, false) }
     else { if (rms) HF_NBV1(float, true) else HF_NBV1(float, false) }
@@ -714,7 +730,7 @@ hipError_t launch_norm_bwd(int bf, int rms, const float* dy, const float* dy_t, 
   }
   const int rpb = std::max(1, T / 512);
   const int blocks = (T + rpb - 1) / rpb;
-#define HF_NB(PT, R) hipLaunchKernelGGL((norm_bwd_kernel<PT, R>), dim3(blocks), dim3(256), 0, st, dy, dy_t, x, x_t, stats, (const PT*)gam, gam_t, T, d, rpb, accumulate, dx, dx_t, hv_gam, hv_bet)
+#define HF_NB(PT, R) hipLaunchKernelGGL((norm_bwd_kernel<PT, R>), dim3(blocks), dim3(256), 0, st, dy, dy_t, x, x_t, stats, (const PT*)gam, gam_t, T, d, rpb, accumulate, dx, dx_t, hv_gam, hv_bet, dxb, dxb_t)
   if (bf) { if (rms) HF_NB(bf16, true); else HF_NB(bf16, false); }
   else { if (rms) HF_NB(float, true); else HF_NB(float, false); }
 #undef HF_NB
