@@ -325,8 +325,8 @@ hipError_t launch_gemm(const Gemm& g, hipStream_t st) {
   t.C = g.Ct; t.C_lo = nullptr; t.Cadd = g.Cadd_t; t.bias = nullptr;
   GemmP pp, pt;
   const int kp = prepare_single(p, pp), kt = prepare_single(t, pt);
-  if (kp == 2 && kt == 2 && g.nb1 * g.nb2 == 1 && p.force_cfg < 0 && !p.allow_splitk) {
-    const hipError_t e2 = launch_gemm_mfma_pair(pp, pt, st);
+  if (kp == 2 && kt == 2 && p.force_cfg < 0 && !p.allow_splitk) {
+    const hipError_t e2 = launch_gemm_mfma_pair(pp, pt, g.nb1 * g.nb2, st);
     if (e2 != hipErrorNotSupported) return e2;
   }
   hipError_t e = launch_prepared(kp, p, pp, st);

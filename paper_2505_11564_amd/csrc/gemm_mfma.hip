@@ -531,11 +531,12 @@ hipError_t launch_gemm_mfma(GemmP p, int nb, int allow_splitk, int force_cfg, in
   }
 }
 
-template <bool TA, bool TB>
-static hipError_t launch_pair_256(const GemmPair& pp, dim3 grid, hipStream_t st) {
-  constexpr int smem = 2 * (256 + 256) * 64 * 2;
+template <int BM, int BN, int WM, int WN, int KT, int NS, bool TA, bool TB, int FL>
+static hipError_t launch_pair_one(const GemmPair& pp, dim3 grid, hipStream_t st) {
+  constexpr int smem_pipe = NS * (BM + BN) * KT * 2, smem_epi = 4 * 32 * (WN + 4) * 4;
+  constexpr int smem = smem_pipe > smem_epi ? smem_pipe : smem_epi;
   static bool attr_done = false;
-  auto kern = gemm_mfma_pair_kernel<256, 256, 128, 128, 64, 2, TA, TB, 2>;
+  auto kern = gemm_mfma_pair_kernel<BM, BN, WM, WN, KT, NS, TA, TB, FL>;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
@@ -544,33 +545,59 @@ static hipError_t launch_pair_256(const GemmPair& pp, dim3 grid, hipStream_t st)
   hipLaunchKernelGGL(kern, grid, dim3(256), smem, st, pp);
   return hipGetLastError();
 }
+template <int BM, int BN, int WM, int WN, int KT, int NS, int FL>
+static hipError_t launch_pair_cfg(const GemmPair& pp, dim3 grid, hipStream_t st) {
+  const GemmP& a = pp.g[0];
+  if (!a.transA && !a.transB) return launch_pair_one<BM, BN, WM, WN, KT, NS, false, false, FL>(pp, grid, st);
+  if (!a.transA && a.transB) return launch_pair_one<BM, BN, WM, WN, KT, NS, false, true, FL>(pp, grid, st);
+  if (a.transA && !a.transB) return launch_pair_one<BM, BN, WM, WN, KT, NS, true, false, FL>(pp, grid, st);
+  return hipErrorNotSupported;
+}
 
-// A primal product and its tangent (same shape and layout, not batched) as one launch of
-// 256 x 256 tiles, when the two together fill the 256 CUs evenly and one alone does not (4096 x
-// 2048: 128 + 128 tiles).  The term counts may differ (adjoint 1, its tangent 2): the launch then
-// lasts as long as the two-term blocks, still less than two launches of 128 x 128 tiles.  Returns hipErrorNotSupported when that is not the case; the caller then
-// launches the two products one after the other.
-hipError_t launch_gemm_mfma_pair(GemmP a, GemmP b, hipStream_t st) {
+// A primal product and its tangent (same shape and layout) as one launch; blockIdx.z selects the
+// product.  Two cases:
+//  * not batched: 256 x 256 tiles, when the two together fill the 256 CUs evenly and one alone
+//    does not (4096 x 2048: 128 + 128 tiles).  The term counts may differ (adjoint 1, its
+//    tangent 2): the launch then lasts as long as the two-term blocks, still less than two
+//    launches of 128 x 128 tiles;
+//  * batched causal products one attention head wide (P V and O_t, dS K and dQ_t, ...): the
+//    tiles a single launch would use; one launch instead of two short ones.
+// Returns hipErrorNotSupported otherwise; the caller then launches the two products in turn.
+hipError_t launch_gemm_mfma_pair(GemmP a, GemmP b, int nb, hipStream_t st) {
   static const int no_pair = std::getenv("HF_GEMM_NO_PAIR") ? 1 : 0;
+  static const int no_pair_att = std::getenv("HF_GEMM_NO_PAIR_ATT") ? 1 : 0;
   if (no_pair || a.M != b.M || a.N != b.N || a.K != b.K || a.transA != b.transA || a.transB != b.transB ||
-      a.klimit || b.klimit || a.skip_upper || b.skip_upper || (a.transA && a.transB))
+      a.klimit != b.klimit || a.skip_upper || b.skip_upper || (a.transA && a.transB))
     return hipErrorNotSupported;
+  GemmPair pp;
+  pp.g[0] = a; pp.g[1] = b;
+  auto finish = [&](int bn) {
+    for (int i = 0; i < 2; ++i) {
+      GemmP& p = pp.g[i];
+      p.tiles_n = (p.N + bn - 1) / bn;
+      const int64_t q = p.out_bf16 ? 8 : 4;
+      auto al = [&](const void* x) { return x == nullptr || ((uintptr_t)x % 16) == 0; };
+      p.vecA = al(p.C) && al(p.Cadd) && al(p.C_lo) && p.ldc % q == 0 && p.sC1 % q == 0 && p.sC2 % q == 0;
+    }
+  };
+  if (a.klimit) {
+    if (no_pair_att || a.transB || a.N > 128 || a.M < 128) return hipErrorNotSupported;
+    if (a.N > 64) {
+      finish(128);
+      dim3 grid((unsigned)((a.M + 127) / 128), (unsigned)nb, 2);
+      return launch_pair_cfg<128, 128, 64, 64, 64, 2, 2>(pp, grid, st);
+    }
+    finish(64);
+    dim3 grid((unsigned)((a.M + 127) / 128), (unsigned)nb, 2);
+    return launch_pair_cfg<128, 64, 64, 32, 64, 2, 1>(pp, grid, st);
+  }
+  if (nb != 1) return hipErrorNotSupported;
   const int64_t t256 = ((int64_t)(a.M + 255) / 256) * ((a.N + 255) / 256);
   auto even = [](int64_t t) { return t >= 256 && t * 100 >= ((t + 255) / 256) * 256 * 85; };
   if (even(t256) || !even(2 * t256) || a.K < 512) return hipErrorNotSupported;
-  GemmPair pp;
-  pp.g[0] = a; pp.g[1] = b;
-  for (int i = 0; i < 2; ++i) {
-    GemmP& p = pp.g[i];
-    p.tiles_n = (p.N + 255) / 256;
-    const int64_t q = p.out_bf16 ? 8 : 4;
-    auto al = [&](const void* x) { return x == nullptr || ((uintptr_t)x % 16) == 0; };
-    p.vecA = al(p.C) && al(p.Cadd) && al(p.C_lo) && p.ldc % q == 0 && p.sC1 % q == 0 && p.sC2 % q == 0;
-  }
+  finish(256);
   dim3 grid((unsigned)t256, 1, 2);
-  if (!a.transA && !a.transB) return launch_pair_256<false, false>(pp, grid, st);
-  if (!a.transA && a.transB) return launch_pair_256<false, true>(pp, grid, st);
-  return launch_pair_256<true, false>(pp, grid, st);
+  return launch_pair_cfg<256, 256, 128, 128, 64, 2, 2>(pp, grid, st);
 }
 
 }  // namespace hf

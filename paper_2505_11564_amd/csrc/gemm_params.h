@@ -31,6 +31,6 @@ struct GemmP {
 // force_cfg / force_ks < 0 (<= 0): choose automatically.
 hipError_t launch_gemm_mfma(GemmP p, int nb, int allow_splitk, int force_cfg, int force_ks, hipStream_t st);
 // Two products of one shape (primal and tangent) in one launch; hipErrorNotSupported = launch them separately.
-hipError_t launch_gemm_mfma_pair(GemmP a, GemmP b, hipStream_t st);
+hipError_t launch_gemm_mfma_pair(GemmP a, GemmP b, int nb, hipStream_t st);
 
 }  // namespace hf
