@@ -594,10 +594,21 @@ hipError_t launch_gemm_mfma_pair(GemmP a, GemmP b, int nb, hipStream_t st) {
   if (nb != 1) return hipErrorNotSupported;
   const int64_t t256 = ((int64_t)(a.M + 255) / 256) * ((a.N + 255) / 256);
   auto even = [](int64_t t) { return t >= 256 && t * 100 >= ((t + 255) / 256) * 256 * 85; };
-  if (even(t256) || !even(2 * t256) || a.K < 512) return hipErrorNotSupported;
-  finish(256);
-  dim3 grid((unsigned)t256, 1, 2);
-  return launch_pair_cfg<256, 256, 128, 128, 64, 2, 2>(pp, grid, st);
+  if (!even(t256) && even(2 * t256) && a.K >= 512) {
+    finish(256);
+    dim3 grid((unsigned)t256, 1, 2);
+    return launch_pair_cfg<256, 256, 128, 128, 64, 2, 2>(pp, grid, st);
+  }
+  // Products that take 128 x 128 tiles on their own (the small models' 576- and 768-tile
+  // products): the same tiles, one launch instead of two 40 us ones.
+  static const int no_pair_small = std::getenv("HF_GEMM_NO_PAIR_SMALL") ? 1 : 0;
+  if (no_pair_small || even(t256) || (a.transA && t256 >= 160) || a.N <= 128) return hipErrorNotSupported;
+  const int64_t t128 = ((int64_t)(a.M + 127) / 128) * ((a.N + 127) / 128);
+  if (t128 < 256 || t128 > 2048) return hipErrorNotSupported;
+  finish(128);
+  dim3 grid((unsigned)t128, 1, 2);
+  if (!a.transA && !a.transB && a.K < 1536) return launch_pair_cfg<128, 128, 64, 64, 32, 2, 2>(pp, grid, st);
+  return launch_pair_cfg<128, 128, 64, 64, 64, 2, 2>(pp, grid, st);
 }
 
 }  // namespace hf
