@@ -349,6 +349,8 @@ int32_t hf_hvp_accumulate(hf_ctx* ctx, const void* params_dev, const void* input
   double loss_acc = 0.0;
   for (int b0 = 0; b0 < n_samples; b0 += micro_batch) {
     const int b = std::min(micro_batch, n_samples - b0);
+    // the direction is the same for every micro-batch: its bf16 copy is made by the first product only
+    if (b0 > 0 && c->bf) c->vb_of = v_dev;
     rc = c->hvp_enqueue(params_dev, (const char*)inputs_dev + b0 * in_row, labels_dev + b0 * lab_row, b, seq, v_dev, c->aux_vec, st);
     if (rc != HF_OK) return rc;
     double loss_b = 0.0;
