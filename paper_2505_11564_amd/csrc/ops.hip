@@ -378,9 +378,112 @@ __global__ __launch_bounds__(256) void norm_fwd_kernel(const float* __restrict__
   }
 }
 
+// Same, one block per row with the row held in registers (NCH chunks of 4 columns per thread,
+// d <= 1024 NCH): x and x_t are read once, 16 bytes at a time, and the bf16 results leave 8 bytes
+// at a time.  Needs d % 4 == 0 and 16-byte (fp32) / 8-byte (bf16) aligned rows.
+__device__ __forceinline__ float4 ldq(const float* p, int64_t i4) { return ((const float4*)p)[i4]; }
+__device__ __forceinline__ float4 ldq(const bf16* p, int64_t i4) {
+  const uint2 u = ((const uint2*)p)[i4];
+  const bf16* h = (const bf16*)&u;
+  return make_float4((float)h[0], (float)h[1], (float)h[2], (float)h[3]);
+}
+__device__ __forceinline__ void stq(float* p, int64_t i4, float4 v) { ((float4*)p)[i4] = v; }
+__device__ __forceinline__ void stq(bf16* p, int64_t i4, float4 v) {
+  const bf16 h[4] = {(bf16)v.x, (bf16)v.y, (bf16)v.z, (bf16)v.w};
+  ((uint2*)p)[i4] = *(const uint2*)h;
+}
+__device__ __forceinline__ float4 lo_of(float4 v, float*) { return make_float4(0.f, 0.f, 0.f, 0.f); }
+__device__ __forceinline__ float4 lo_of(float4 v, bf16*) {
+  return make_float4(v.x - (float)(bf16)v.x, v.y - (float)(bf16)v.y, v.z - (float)(bf16)v.z, v.w - (float)(bf16)v.w);
+}
+
+template <typename PT, typename AT, bool RMS, int NCH>
+__global__ __launch_bounds__(256) void norm_fwd_vec_kernel(const float* __restrict__ x, const float* __restrict__ x_t,
+                                                           const PT* __restrict__ gam, const PT* __restrict__ bet,
+                                                           const float* __restrict__ gam_t, const float* __restrict__ bet_t,
+                                                           int d, float eps, AT* __restrict__ y, AT* __restrict__ y_t,
+                                                           AT* __restrict__ y_lo, float* __restrict__ stats) {
+  __shared__ float red[16];
+  const int64_t row = blockIdx.x;
+  const int d4 = d >> 2;
+  const int64_t base4 = row * d4;
+  const float inv_d = 1.f / (float)d;
+  float4 xv[NCH], tv[NCH];
+  float s[2] = {0.f, 0.f};
+#pragma unroll
+  for (int j = 0; j < NCH; ++j) {
+    const int c4 = j * 256 + threadIdx.x;
+    xv[j] = make_float4(0.f, 0.f, 0.f, 0.f); tv[j] = xv[j];
+    if (c4 < d4) {
+      xv[j] = ldq(x, base4 + c4); tv[j] = ldq(x_t, base4 + c4);
+      s[0] += (xv[j].x + xv[j].y) + (xv[j].z + xv[j].w);
+      s[1] += (tv[j].x + tv[j].y) + (tv[j].z + tv[j].w);
+    }
+  }
+  float mu = 0.f, mxt = 0.f;
+  if (!RMS) {
+    block_sum<2>(s, red);
+    mu = s[0] * inv_d;
+    mxt = s[1] * inv_d;
+  }
+  float s2[2] = {0.f, 0.f};
+#pragma unroll
+  for (int j = 0; j < NCH; ++j) {
+    const int c4 = j * 256 + threadIdx.x;
+    if (c4 < d4) {
+      xv[j].x -= mu; xv[j].y -= mu; xv[j].z -= mu; xv[j].w -= mu;
+      s2[0] += (xv[j].x * xv[j].x + xv[j].y * xv[j].y) + (xv[j].z * xv[j].z + xv[j].w * xv[j].w);
+      s2[1] += (xv[j].x * tv[j].x + xv[j].y * tv[j].y) + (xv[j].z * tv[j].z + xv[j].w * tv[j].w);
+    }
+  }
+  block_sum<2>(s2, red);
+  const float rstd = rsqrtf(s2[0] * inv_d + eps);
+  const float st = s2[1] * inv_d * rstd;  // mean(xh * x_t)
+#pragma unroll
+  for (int j = 0; j < NCH; ++j) {
+    const int c4 = j * 256 + threadIdx.x;
+    if (c4 < d4) {
+      const float4 g = ldq(gam, c4), gt = ldq(gam_t, c4);
+      float4 yv, yt;
+#define HF_NFV(q)                                            \
+  {                                                          \
+    const float xh = xv[j].q * rstd;                         \
+    const float xht = (tv[j].q - mxt - xh * st) * rstd;      \
+    yv.q = g.q * xh;                                         \
+    yt.q = gt.q * xh + g.q * xht;                            \
+  }
+      HF_NFV(x) HF_NFV(y) HF_NFV(z) HF_NFV(w)
+#undef HF_NFV
+      if (!RMS) {
+        const float4 b = ldq(bet, c4), bt = ldq(bet_t, c4);
+        yv.x += b.x; yv.y += b.y; yv.z += b.z; yv.w += b.w;
+        yt.x += bt.x; yt.y += bt.y; yt.z += bt.z; yt.w += bt.w;
+      }
+      stq(y, base4 + c4, yv);
+      stq(y_t, base4 + c4, yt);
+      if (y_lo) stq(y_lo, base4 + c4, lo_of(yv, y_lo));
+    }
+  }
+  if (threadIdx.x == 0) *(float4*)(stats + row * 4) = make_float4(mu, rstd, mxt, st);
+}
+
 hipError_t launch_norm_fwd(int bf, int rms, const float* x, const float* x_t, const void* gam, const void* bet,
                            const float* gam_t, const float* bet_t, int T, int d, float eps, void* y, void* y_t,
                            void* y_lo, float* stats, hipStream_t st) {
+  {
+    const uintptr_t a16 = (uintptr_t)x | (uintptr_t)x_t | (uintptr_t)gam_t | (uintptr_t)bet_t | (uintptr_t)stats;
+    const uintptr_t ap = (uintptr_t)gam | (uintptr_t)bet | (uintptr_t)y | (uintptr_t)y_t | (uintptr_t)y_lo;
+    if (d % 4 == 0 && d <= 8192 && (a16 & 15) == 0 && (ap & (bf ? 7 : 15)) == 0) {
+      const int nch = (d / 4 + 255) / 256;
+#define HF_NFV2(PT, AT, R, N) hipLaunchKernelGGL((norm_fwd_vec_kernel<PT, AT, R, N>), dim3(T), dim3(256), 0, st, x, x_t, (const PT*)gam, (const PT*)bet, gam_t, bet_t, d, eps, (AT*)y, (AT*)y_t, (AT*)y_lo, stats)
+#define HF_NFV1(PT, AT, R) { if (nch <= 1) HF_NFV2(PT, AT, R, 1); else if (nch <= 2) HF_NFV2(PT, AT, R, 2); else if (nch <= 4) HF_NFV2(PT, AT, R, 4); else HF_NFV2(PT, AT, R, 8); }
+      if (bf) { if (rms) HF_NFV1(bf16, bf16, true) else HF_NFV1(bf16, bf16, false) }
+      else { if (rms) HF_NFV1(float, float, true) else HF_NFV1(float, float, false) }
+#undef HF_NFV1
+#undef HF_NFV2
+      return hipGetLastError();
+    }
+  }
 #define HF_NF(PT, AT, R) hipLaunchKernelGGL((norm_fwd_kernel<PT, AT, R>), dim3(T), dim3(256), 0, st, x, x_t, (const PT*)gam, (const PT*)bet, gam_t, bet_t, d, eps, (AT*)y, (AT*)y_t, (AT*)y_lo, stats)
   if (bf) { if (rms) HF_NF(bf16, bf16, true); else HF_NF(bf16, bf16, false); }
   else { if (rms) HF_NF(float, float, true); else HF_NF(float, float, false); }
