@@ -556,8 +556,8 @@ static hipError_t launch_pair_cfg(const GemmPair& pp, dim3 grid, hipStream_t st)
 
 // A primal product and its tangent (same shape and layout) as one launch; blockIdx.z selects the
 // product.  Two cases:
-//  * not batched: 256 x 256 tiles, when the two together fill the 256 CUs evenly and one alone
-//    does not (4096 x 2048: 128 + 128 tiles).  The term counts may differ (adjoint 1, its
+//  * not batched: 256 x 256 tiles, when the two together fill the 256 CUs evenly, in particular
+//    when one alone does not (4096 x 2048: 128 + 128 tiles).  The term counts may differ (adjoint 1, its
 //    tangent 2): the launch then lasts as long as the two-term blocks, still less than two
 //    launches of 128 x 128 tiles;
 //  * batched causal products one attention head wide (P V and O_t, dS K and dQ_t, ...): the
@@ -594,7 +594,7 @@ hipError_t launch_gemm_mfma_pair(GemmP a, GemmP b, int nb, hipStream_t st) {
   if (nb != 1) return hipErrorNotSupported;
   const int64_t t256 = ((int64_t)(a.M + 255) / 256) * ((a.N + 255) / 256);
   auto even = [](int64_t t) { return t >= 256 && t * 100 >= ((t + 255) / 256) * 256 * 85; };
-  if (!even(t256) && even(2 * t256) && a.K >= 512) {
+  if (even(2 * t256) && a.K >= 512) {
     finish(256);
     dim3 grid((unsigned)t256, 1, 2);
     return launch_pair_cfg<256, 256, 128, 128, 64, 2, 2>(pp, grid, st);
