@@ -1255,8 +1255,90 @@ __global__ __launch_bounds__(256) void ce_kernel(const float* __restrict__ z, co
   }
   if (threadIdx.x == 0) loss_rows[row] = logf(s[0]) + mx - zr[y];
 }
+// One pass over a row: 1024 threads hold the row of z and of z_t in registers (EPT chunks of four
+// columns each, V <= 4096 EPT), so the logits are read once instead of twice.  Rows are 16-byte
+// aligned (ldz % 64 == 0); the V % 4 last columns go through thread-private scalars.
+template <typename AT, int EPT>
+__global__ __launch_bounds__(1024) void ce_row_kernel(const float* __restrict__ z, const float* __restrict__ z_t,
+                                                      const int32_t* __restrict__ labels, const int* __restrict__ n_valid,
+                                                      int V, int64_t ldz, AT* __restrict__ dz, AT* __restrict__ dz_t,
+                                                      float* __restrict__ loss_rows) {
+  __shared__ float red[48];
+  const int64_t row = blockIdx.x;
+  const float* zr = z + row * ldz;
+  const float* ztr = z_t + row * ldz;
+  const int y = labels[row];
+  const int V4 = V >> 2, t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int ct = 4 * V4 + t;  // this thread's tail column (valid if < V)
+  if (y < 0 || y >= V) {
+    for (int c = t; c < V4; c += 1024) { st4f(dz, row * ldz + 4 * c, 0.f, 0.f, 0.f, 0.f); st4f(dz_t, row * ldz + 4 * c, 0.f, 0.f, 0.f, 0.f); }
+    if (ct < V) { stf(dz, row * ldz + ct, 0.f); stf(dz_t, row * ldz + ct, 0.f); }
+    if (t == 0) loss_rows[row] = 0.f;
+    return;
+  }
+  float4 x[EPT], d[EPT];
+  float xt = -INFINITY, dt = 0.f;
+  float m = -INFINITY;
+#pragma unroll
+  for (int j = 0; j < EPT; ++j) {
+    const int c = t + 1024 * j;
+    x[j] = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+    d[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (c < V4) { x[j] = ((const float4*)zr)[c]; d[j] = ((const float4*)ztr)[c]; }
+    m = fmaxf(m, fmaxf(fmaxf(x[j].x, x[j].y), fmaxf(x[j].z, x[j].w)));
+  }
+  if (ct < V) { xt = zr[ct]; dt = ztr[ct]; m = fmaxf(m, xt); }
+  // block maximum over 16 waves
+  m = wave_max(m);
+  if (lane == 0) red[wave] = m;
+  __syncthreads();
+  float mx = red[0];
+#pragma unroll
+  for (int w = 1; w < 16; ++w) mx = fmaxf(mx, red[w]);
+  float se = 0.f, sd = 0.f;
+#pragma unroll
+  for (int j = 0; j < EPT; ++j) {
+    x[j].x = __expf(x[j].x - mx); x[j].y = __expf(x[j].y - mx); x[j].z = __expf(x[j].z - mx); x[j].w = __expf(x[j].w - mx);
+    se += (x[j].x + x[j].y) + (x[j].z + x[j].w);
+    sd += (x[j].x * d[j].x + x[j].y * d[j].y) + (x[j].z * d[j].z + x[j].w * d[j].w);
+  }
+  xt = __expf(xt - mx);  // exp(-inf) = 0 for a thread without a tail column
+  se += xt; sd += xt * dt;
+  se = wave_sum(se); sd = wave_sum(sd);
+  if (lane == 0) { red[16 + wave] = se; red[32 + wave] = sd; }
+  __syncthreads();
+  float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+  for (int w = 0; w < 16; ++w) { s0 += red[16 + w]; s1 += red[32 + w]; }
+  const float inv = 1.f / s0;
+  const float pz = s1 * inv;
+  const float invN = 1.f / (float)max(1, *n_valid);
+#pragma unroll
+  for (int j = 0; j < EPT; ++j) {
+    const int c = t + 1024 * j;
+    if (c < V4) {
+      const float p0 = x[j].x * inv, p1 = x[j].y * inv, p2 = x[j].z * inv, p3 = x[j].w * inv;
+      const int c0 = 4 * c;
+      st4f(dz, row * ldz + c0, (p0 - (c0 == y ? 1.f : 0.f)) * invN, (p1 - (c0 + 1 == y ? 1.f : 0.f)) * invN,
+           (p2 - (c0 + 2 == y ? 1.f : 0.f)) * invN, (p3 - (c0 + 3 == y ? 1.f : 0.f)) * invN);
+      st4f(dz_t, row * ldz + c0, p0 * (d[j].x - pz) * invN, p1 * (d[j].y - pz) * invN, p2 * (d[j].z - pz) * invN,
+           p3 * (d[j].w - pz) * invN);
+    }
+  }
+  if (ct < V) {
+    const float pv = xt * inv;
+    stf(dz, row * ldz + ct, (pv - (ct == y ? 1.f : 0.f)) * invN);
+    stf(dz_t, row * ldz + ct, pv * (dt - pz) * invN);
+  }
+  if (t == 0) loss_rows[row] = logf(s0) + mx - zr[y];
+}
+
 hipError_t launch_ce(int bf, const float* z, const float* z_t, const int32_t* labels, const int* n_valid, int T, int V,
                      int64_t ldz, void* dz, void* dz_t, float* loss_rows, hipStream_t st) {
+  if (bf && V >= 8192 && ldz % 4 == 0) {  // wide rows: the two-pass kernel reads them twice
+    if (V <= 4096 * 8) { hipLaunchKernelGGL((ce_row_kernel<bf16, 8>), dim3(T), dim3(1024), 0, st, z, z_t, labels, n_valid, V, ldz, (bf16*)dz, (bf16*)dz_t, loss_rows); return hipGetLastError(); }
+    if (V <= 4096 * 13) { hipLaunchKernelGGL((ce_row_kernel<bf16, 13>), dim3(T), dim3(1024), 0, st, z, z_t, labels, n_valid, V, ldz, (bf16*)dz, (bf16*)dz_t, loss_rows); return hipGetLastError(); }
+  }
   if (bf) hipLaunchKernelGGL(ce_kernel<bf16>, dim3(T), dim3(256), 0, st, z, z_t, labels, n_valid, V, ldz, (bf16*)dz, (bf16*)dz_t, loss_rows);
   else hipLaunchKernelGGL(ce_kernel<float>, dim3(T), dim3(256), 0, st, z, z_t, labels, n_valid, V, ldz, (float*)dz, (float*)dz_t, loss_rows);
   return hipGetLastError();
