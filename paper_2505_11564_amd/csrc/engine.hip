@@ -389,9 +389,7 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
   // kernels write only the score tiles on and below the diagonal; tiles above it
   // are read as zeros by products that run with larger tiles, so they are
   // cleared whenever the [B,H,S,S] layout changes.
-  static const bool no_fused = std::getenv("HF_NO_FUSED_ATT") != nullptr;
-  static const bool delta_from_o = std::getenv("HF_ATT_DELTA_PASS") == nullptr;
-  const bool fused_att = bf && !no_fused && D % 8 == 0 && dh % 32 == 0 && S % 8 == 0;
+  const bool fused_att = bf && D % 8 == 0 && dh % 32 == 0 && S % 8 == 0;
   if (fused_att && (att_zero_B != B || att_zero_S != S)) {
     const int64_t words = (int64_t)B * H * SS / 2;  // bf16 pairs
     for (auto& b : lb) {
@@ -578,7 +576,7 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
       g.At = dob_t; g.Bt = cat(b.qkv_t, offV);
       g.C = dS; g.Ct = dS_t; g.out_bf16 = 1; g.E0 = b.P; g.E1 = b.P_t;
       // delta, delta_t from <dO, O> where the head width allows, else by a statistics pass
-      hipError_t ed = delta_from_o ? launch_attn_delta(dob, dob_t, b.o, o_lo, b.o_t, T, S, H, dh, att_rstat, st) : hipErrorNotSupported;
+      hipError_t ed = launch_attn_delta(dob, dob_t, b.o, o_lo, b.o_t, T, S, H, dh, att_rstat, st);
       if (ed == hipErrorNotSupported) {
         g.epi = EPI_BWD_STATS; g.part = att_part;
         CK(launch_gemm(g, st));

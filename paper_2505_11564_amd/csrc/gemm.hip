@@ -297,13 +297,12 @@ hipError_t launch_gemm(const Gemm& g, hipStream_t st) {
   // dual output: one fused launch when the MFMA path applies, else two products
   if (g.M <= 0 || g.N <= 0 || g.nb1 <= 0 || g.nb2 <= 0) return hipSuccess;
   if (!g.At || !g.Bt || !g.A[0] || !g.B[0] || !g.C || ((g.Cadd || g.Cadd_t) && g.out_bf16)) return hipErrorInvalidValue;
-  static const int no_dual = std::getenv("HF_GEMM_NO_DUAL") ? 1 : 0;
   // Measured: the fused kernel wins only when the product alone cannot fill
   // the GPU (fewer than ~256 tiles of 128 x 128); larger products run faster
   // as two launches with their own tile shapes.
   const int64_t tiles128 = ((int64_t)(g.M + 127) / 128) * ((g.N + 127) / 128) * g.nb1 * g.nb2;
   if (g.epi != EPI_NONE && !g.in_bf16) return hipErrorInvalidValue;
-  if (g.in_bf16 && g.M >= 8 && g.N >= 8 && (g.epi != EPI_NONE || (!no_dual && tiles128 < 256))) {
+  if (g.in_bf16 && g.M >= 8 && g.N >= 8 && (g.epi != EPI_NONE || tiles128 < 256)) {
     auto ok = [&](const void* x, int64_t ld, int64_t s1, int64_t s2, int rows_contig, int R) {
       return ((uintptr_t)x % 16) == 0 && ld % 8 == 0 && s1 % 8 == 0 && s2 % 8 == 0 && (!rows_contig || ld >= ((R + 7) / 8) * 8);
     };
@@ -367,8 +366,7 @@ static int prepare_single(const Gemm& g, GemmP& p) {
     return aligned_to(x0, 16) && aligned_to(x1, 16) && aligned_to(x2, 16) && ld % 8 == 0 && s1 % 8 == 0 && s2 % 8 == 0 &&
            (!rows_contig || ld >= ((R + 7) / 8) * 8);
   };
-  static const int force_v1 = std::getenv("HF_GEMM_V1") ? 1 : 0;
-  if (!force_v1 && g.M >= 8 && g.N >= 8 && fast_ok(g.A[0], g.A[1], g.A[2], g.lda, g.sA1, g.sA2, g.transA, g.M) &&
+  if (g.M >= 8 && g.N >= 8 && fast_ok(g.A[0], g.A[1], g.A[2], g.lda, g.sA1, g.sA2, g.transA, g.M) &&
       fast_ok(g.B[0], g.B[1], g.B[2], g.ldb, g.sB1, g.sB2, !g.transB, g.N))
     return 2;
   return 3;

@@ -581,16 +581,12 @@ __global__ __launch_bounds__(256, (EPI != EPI_NONE && NT == 4 && NS == 2 ? 2 : 1
 
 template <bool TA, bool TB, int NT, int NS, int EPI>
 static hipError_t launch_dual_k(const DualP& p, dim3 grid, hipStream_t st) {
-  static bool attr_done = false;
+  static OncePerDevice once;
   auto kern = gemm_dual_kernel<TA, TB, NT, NS, EPI>;
   constexpr int smem_pipe = NS * NT * 128 * 32 * 2, smem_epi = 4 * 2 * 32 * (64 + 4) * 4;
   constexpr int smem = smem_pipe > smem_epi ? smem_pipe : smem_epi;
   static_assert(smem <= 160 * 1024, "LDS");
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  if (hipError_t e = once.lds_limit((const void*)kern, smem); e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, grid, dim3(256), smem, st, p);
   return hipGetLastError();
 }

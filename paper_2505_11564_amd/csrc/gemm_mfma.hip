@@ -430,13 +430,9 @@ template <int BM, int BN, int WM, int WN, int KT, int NS, bool TA, bool TB, int 
 static hipError_t launch_one(const GemmP& p, dim3 grid, hipStream_t st) {
   constexpr int smem_pipe = NS * (BM + BN) * KT * 2, smem_epi = 4 * 32 * (WN + 4) * 4;
   constexpr int smem = smem_pipe > smem_epi ? smem_pipe : smem_epi;
-  static bool attr_done = false;
+  static OncePerDevice once;
   auto kern = gemm_mfma_kernel<BM, BN, WM, WN, KT, NS, TA, TB, FL>;
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  if (hipError_t e = once.lds_limit((const void*)kern, smem); e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, grid, dim3(256), smem, st, p);
   return hipGetLastError();
 }
@@ -535,13 +531,9 @@ template <int BM, int BN, int WM, int WN, int KT, int NS, bool TA, bool TB, int 
 static hipError_t launch_pair_one(const GemmPair& pp, dim3 grid, hipStream_t st) {
   constexpr int smem_pipe = NS * (BM + BN) * KT * 2, smem_epi = 4 * 32 * (WN + 4) * 4;
   constexpr int smem = smem_pipe > smem_epi ? smem_pipe : smem_epi;
-  static bool attr_done = false;
+  static OncePerDevice once;
   auto kern = gemm_mfma_pair_kernel<BM, BN, WM, WN, KT, NS, TA, TB, FL>;
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  if (hipError_t e = once.lds_limit((const void*)kern, smem); e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, grid, dim3(256), smem, st, pp);
   return hipGetLastError();
 }
@@ -564,9 +556,7 @@ static hipError_t launch_pair_cfg(const GemmPair& pp, dim3 grid, hipStream_t st)
 //    tiles a single launch would use; one launch instead of two short ones.
 // Returns hipErrorNotSupported otherwise; the caller then launches the two products in turn.
 hipError_t launch_gemm_mfma_pair(GemmP a, GemmP b, int nb, hipStream_t st) {
-  static const int no_pair = std::getenv("HF_GEMM_NO_PAIR") ? 1 : 0;
-  static const int no_pair_att = std::getenv("HF_GEMM_NO_PAIR_ATT") ? 1 : 0;
-  if (no_pair || a.M != b.M || a.N != b.N || a.K != b.K || a.transA != b.transA || a.transB != b.transB ||
+  if (a.M != b.M || a.N != b.N || a.K != b.K || a.transA != b.transA || a.transB != b.transB ||
       a.klimit != b.klimit || a.skip_upper || b.skip_upper || (a.transA && a.transB))
     return hipErrorNotSupported;
   GemmPair pp;
@@ -581,7 +571,7 @@ hipError_t launch_gemm_mfma_pair(GemmP a, GemmP b, int nb, hipStream_t st) {
     }
   };
   if (a.klimit) {
-    if (no_pair_att || a.transB || a.N > 128 || a.M < 128) return hipErrorNotSupported;
+    if (a.transB || a.N > 128 || a.M < 128) return hipErrorNotSupported;
     if (a.N > 64) {
       finish(128);
       dim3 grid((unsigned)((a.M + 127) / 128), (unsigned)nb, 2);
@@ -601,8 +591,7 @@ hipError_t launch_gemm_mfma_pair(GemmP a, GemmP b, int nb, hipStream_t st) {
   }
   // Products that take 128 x 128 tiles on their own (the small models' 576- and 768-tile
   // products): the same tiles, one launch instead of two 40 us ones.
-  static const int no_pair_small = std::getenv("HF_GEMM_NO_PAIR_SMALL") ? 1 : 0;
-  if (no_pair_small || even(t256) || (a.transA && t256 >= 160) || a.N <= 128) return hipErrorNotSupported;
+  if (even(t256) || (a.transA && t256 >= 160) || a.N <= 128) return hipErrorNotSupported;
   const int64_t t128 = ((int64_t)(a.M + 127) / 128) * ((a.N + 127) / 128);
   if (t128 < 256 || t128 > 2048) return hipErrorNotSupported;
   finish(128);

@@ -7,8 +7,26 @@
 
 #include <type_traits>
 #include <utility>
+#include <atomic>
 
 namespace hf {
+
+// hipFuncSetAttribute acts on the current device, so "already done" is kept per device.
+struct OncePerDevice {
+  std::atomic<bool> done[64];
+  OncePerDevice() { for (auto& d : done) d.store(false); }
+  // Sets the dynamic-LDS limit of `kern` on the current device the first time it is asked to.
+  hipError_t lds_limit(const void* kern, int bytes) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const bool track = dev >= 0 && dev < 64;
+    if (track && done[dev].load(std::memory_order_acquire)) return hipSuccess;
+    e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess && track) done[dev].store(true, std::memory_order_release);
+    return e;
+  }
+};
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
