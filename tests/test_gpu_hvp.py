@@ -33,8 +33,8 @@ SHAPES = {
     # 8 heads and 4 x 4 score tiles: the fused attention kernels deal whole heads to the XCDs
     "gpt_heads8": dict(model=si._gpt(1, 256, 8, 72, 97, 400), batch=1, seq=400, tokens="zipf"),
     "llama_long_k": dict(model=si._llama(1, 64, 2, 1544, 257, 40), batch=2, seq=40, tokens="zipf"),
-    # 2000 x 4088 products with k = 264: a paired launch of 256 x 256 tiles with a ragged last
-    # tile in every dimension
+    # 2000 x 4088 products with k = 264: several hundred tiles with a ragged last tile in every
+    # dimension
     "gpt_wide_ffn": dict(model=si._gpt(1, 264, 4, 4088, 97, 500), batch=4, seq=500, tokens="zipf"),
 }
 
@@ -64,8 +64,8 @@ def test_hvp_parity_small(name, dtype):
     run_case(SHAPES[name], dtype)
 
 
-def test_hvp_parity_paired_whole_tiles():
-    # 2048 x 4096 products with k = 256: the paired 256 x 256 launch without any ragged edge
+def test_hvp_parity_many_whole_tiles():
+    # 2048 x 4096 products with k = 256: 512 tiles of 128 x 128 without any ragged edge
     run_case(dict(model=si._gpt(1, 256, 4, 4096, 97, 512), batch=4, seq=512, tokens="zipf"), "bf16")
 
 
