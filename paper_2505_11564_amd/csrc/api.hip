@@ -145,11 +145,14 @@ int32_t hf_create(const hf_model_desc* desc, int32_t hip_device, int32_t max_bat
     if (nm == "W1") c->off_w1 = o; else if (nm == "b1") c->off_b1 = o;
     else if (nm == "W2") c->off_w2 = o; else if (nm == "b2") c->off_b2 = o;
     else if (nm == "wte") c->off_wte = o; else if (nm == "wpe") c->off_wpe = o;
-    else if (nm == "lnf.g" || nm == "rmsf.g") c->off_nfg = o; else if (nm == "lnf.b") c->off_nfb = o;
+    else if (nm == "lnf.g" || nm == "rmsf.g") { c->off_nfg = o; c->layers_end = o + e.count(); }
+    else if (nm == "lnf.b") { c->off_nfb = o; c->layers_end = o + e.count(); }
     else if (nm == "lm_head") c->off_head = o;
     else if (nm[0] == 'h') {
       const size_t dot = nm.find('.');
       const int l = std::stoi(nm.substr(1, dot - 1));
+      if (c->layers_end == 0) c->layers_begin = o;
+      c->layers_end = o + e.count();
       const std::string t = nm.substr(dot + 1);
       LayerOff& lo = c->loff[l];
       if (t == "ln1.g" || t == "rms1.g") lo.n1g = o; else if (t == "ln1.b") lo.n1b = o;
@@ -166,7 +169,8 @@ int32_t hf_create(const hf_model_desc* desc, int32_t hip_device, int32_t max_bat
     // tied head product writes it first.
     const bool tied_wte = (nm == "wte" && desc->arch == HF_ARCH_GPT && desc->tie_embeddings);
     if (e.shape[1] == 0 || nm == "wpe" || (nm == "wte" && !tied_wte)) {
-      if (!c->zero_ranges.empty() && c->zero_ranges.back().first + c->zero_ranges.back().second == o)
+      // (a range never straddles the start of the layers, which may be cleared as a whole)
+      if (!c->zero_ranges.empty() && c->zero_ranges.back().first + c->zero_ranges.back().second == o && o != c->layers_begin)
         c->zero_ranges.back().second += e.count();
       else c->zero_ranges.push_back({o, e.count()});
     }

@@ -47,6 +47,8 @@ struct hf_ctx {
   int64_t off_wte = -1, off_wpe = -1, off_nfg = -1, off_nfb = -1, off_head = -1;
   int64_t off_w1 = -1, off_b1 = -1, off_w2 = -1, off_b2 = -1;
   std::vector<std::pair<int64_t, int64_t>> zero_ranges;  // H v regions filled by atomics
+  int64_t layers_begin = 0, layers_end = 0;  // the layers' parameters (through the final norm) in the flat vector
+  int dw_prezeroed = 0;  // this product cleared [layers_begin, layers_end) of H v in one pass
   std::string err;
 
   // device memory

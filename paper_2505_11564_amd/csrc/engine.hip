@@ -277,6 +277,7 @@ struct Lin {
     g.M = Kin; g.N = Nout; g.K = T; g.lda = ldx; g.ldb = lddy; g.ldc = Nout; g.transA = 1;
     g.in_bf16 = bf; g.out_bf16 = 0;
     g.allow_splitk = 1;
+    g.c_zeroed = c->dw_prezeroed && woff >= c->layers_begin && woff < c->layers_end;
     g.C = out + woff;
     if (X_t) { g.A[0] = X_t; g.B[0] = dY; g.A[1] = X; g.B[1] = dY_t; }
     else { g.A[0] = X; g.B[0] = dY_t; }
@@ -299,7 +300,25 @@ int hf_ctx::hvp_enqueue(const void* params, const void* inputs, const int32_t* l
   if (desc.arch != HF_ARCH_MLP && (seq <= 0 || seq > desc.max_seq)) return fail(HF_ESHAPE, "hf_hvp: seq outside [1, max_seq]");
   if (desc.arch != HF_ARCH_MLP && (int64_t)batch * seq > (int64_t)max_batch * desc.max_seq) return fail(HF_ESHAPE, "hf_hvp: too many tokens");
   CK(launch_fill_f32((float*)flags, 2, 0.f, st));
-  for (auto& zr : zero_ranges) CK(launch_fill_f32(out + zr.first, zr.second, 0.f, st));
+  // Small models: every weight-gradient product of a layer splits k and adds into a cleared
+  // result, and the vectors between them are accumulated with atomics as well.  One pass over the
+  // layers' whole range then replaces a fill per matrix and per group of vectors.
+  dw_prezeroed = 0;
+  if (bf && desc.arch != HF_ARCH_MLP && layers_end > layers_begin) {
+    const int T = batch * seq, D = desc.d_model, F = desc.d_ff;
+    const int hkv = desc.n_kv_head > 0 ? desc.n_kv_head : desc.n_head, Dkv = D / desc.n_head * hkv;
+    bool all = gemm_mfma_splits_k(D, D, T, 2) && gemm_mfma_splits_k(D, F, T, 2) && gemm_mfma_splits_k(F, D, T, 2);
+    if (desc.arch == HF_ARCH_GPT) all = all && gemm_mfma_splits_k(D, 3 * D, T, 2);
+    else all = all && gemm_mfma_splits_k(D, Dkv, T, 2);
+    if (all) {
+      CK(launch_fill_f32(out + layers_begin, layers_end - layers_begin, 0.f, st));
+      dw_prezeroed = 1;
+    }
+  }
+  for (auto& zr : zero_ranges) {
+    if (dw_prezeroed && zr.first >= layers_begin && zr.first + zr.second <= layers_end) continue;
+    CK(launch_fill_f32(out + zr.first, zr.second, 0.f, st));
+  }
   // The Lanczos update leaves the bf16 copy of q_{k+1} in vb; every other direction is converted here.
   if (bf && !(vb_of != nullptr && vb_of == v)) CK(launch_f32_to_bf16(v, vb, n, st));
   vb_of = nullptr;

@@ -384,7 +384,7 @@ static hipError_t launch_prepared(int kind, const Gemm& g, GemmP& p, hipStream_t
     hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, 16>), grid, dim3(256), 0, st, p);
     return hipGetLastError();
   }
-  if (kind == 2) return launch_gemm_mfma(p, nb, g.allow_splitk, g.force_cfg, g.force_ks, st);
+  if (kind == 2) return launch_gemm_mfma(p, nb, g.allow_splitk, g.force_cfg, g.force_ks, st, g.c_zeroed);
   constexpr int BM = 128, BN = 128;
   p.tiles_n = (g.N + BN - 1) / BN;
   dim3 grid(p.tiles_n * ((g.M + BM - 1) / BM), nb);

@@ -457,7 +457,7 @@ constexpr int kNumCfg = 5;
 
 // Tile choice: the largest tile that still yields about two blocks per CU;
 // split-K for products with few output tiles and a long k (the H v blocks).
-hipError_t launch_gemm_mfma(GemmP p, int nb, int allow_splitk, int force_cfg, int force_ks, hipStream_t st) {
+static void choose_tile_and_split(const GemmP& p, int nb, int allow_splitk, int force_cfg, int force_ks, int& cfg_out, int& ks_out) {
   const int64_t M = p.M, N = p.N;
   auto tiles = [&](int bm, int bn) { return ((M + bm - 1) / bm) * ((N + bn - 1) / bn) * (int64_t)nb; };
   // Measured on MI355X: 256x256 tiles (one block per CU) reach 1.3-1.5 PFLOP/s when their count
@@ -498,12 +498,35 @@ hipError_t launch_gemm_mfma(GemmP p, int nb, int allow_splitk, int force_cfg, in
         if (full_rounds(k2) && slabs / k2 >= 16) { ks = k2; break; }
     }
   }
+  cfg_out = cfg; ks_out = ks;
+}
+
+// Whether launch_gemm_mfma would split k (and so add into C with atomics, which needs C zeroed) for an
+// fp32-output A^T B product of this shape: lets a caller clear several results with one fill.
+bool gemm_mfma_splits_k(int M, int N, int K, int nterm) {
+  GemmP p = {};
+  p.M = M; p.N = N; p.K = K; p.nterm = nterm; p.transA = 1; p.transB = 0; p.out_bf16 = 0; p.klimit = 0;
+  int cfg, ks;
+  choose_tile_and_split(p, 1, 1, -1, -1, cfg, ks);
+  return ks > 1;
+}
+
+// c_zeroed: the caller has already cleared C (a split product then skips its own fill).
+hipError_t launch_gemm_mfma(GemmP p, int nb, int allow_splitk, int force_cfg, int force_ks, hipStream_t st, int c_zeroed) {
+  const int64_t M = p.M, N = p.N;
+  auto tiles = [&](int bm, int bn) { return ((M + bm - 1) / bm) * ((N + bn - 1) / bn) * (int64_t)nb; };
+  int cfg, ks;
+  choose_tile_and_split(p, nb, allow_splitk, force_cfg, force_ks, cfg, ks);
+  const int bm = kCfg[cfg].bm, bn = kCfg[cfg].bn;
+  const int64_t nt = tiles(bm, bn);
   if (ks > 1) {
     // accumulate with atomics on top of Cadd (or zero)
     if (p.Cadd == nullptr) {
       if (p.ldc == p.N && nb == 1) {
-        hipError_t e = launch_fill_f32((float*)p.C, M * N, 0.f, st);
-        if (e != hipSuccess) return e;
+        if (!c_zeroed) {
+          hipError_t e = launch_fill_f32((float*)p.C, M * N, 0.f, st);
+          if (e != hipSuccess) return e;
+        }
       } else {
         ks = 1;
       }

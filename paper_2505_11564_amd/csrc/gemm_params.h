@@ -29,7 +29,8 @@ struct GemmP {
 
 // MFMA path with direct global->LDS loads; needs 16-byte aligned operand rows.
 // force_cfg / force_ks < 0 (<= 0): choose automatically.
-hipError_t launch_gemm_mfma(GemmP p, int nb, int allow_splitk, int force_cfg, int force_ks, hipStream_t st);
+// c_zeroed: C is already zero, so a product that splits k (atomic accumulation) skips its own fill.
+hipError_t launch_gemm_mfma(GemmP p, int nb, int allow_splitk, int force_cfg, int force_ks, hipStream_t st, int c_zeroed = 0);
 // Two products of one shape (primal and tangent) in one launch; hipErrorNotSupported = launch them separately.
 hipError_t launch_gemm_mfma_pair(GemmP a, GemmP b, int nb, hipStream_t st);
 

@@ -62,6 +62,7 @@ struct Gemm {
                    // 2: k >= m (A upper-triangular in (m,k))
   int skip_upper = 0;  // skip output tiles with n0 > m_last (causal scores)
   int allow_splitk = 0;  // fp32 C only: few output tiles, long k -> split k with atomics
+  int c_zeroed = 0;      // with allow_splitk: the caller has cleared C already
   // Dual output (Ct != nullptr): additionally Ct = alpha (At op B[0] + A[0] op Bt) + bias_t + Cadd_t in
   // the same launch; C then takes bias and Cadd only, Ct takes bias_t and Cadd_t only.
   const void* At = nullptr;
@@ -92,6 +93,8 @@ enum { EPI_NONE = 0, EPI_FWD_STATS = 1, EPI_FWD_SOFTMAX = 2, EPI_BWD_STATS = 3, 
 
 hipError_t launch_gemm(const Gemm& g, hipStream_t st);
 hipError_t launch_gemm_dual(const Gemm& g, hipStream_t st);  // bf16, aligned operands only
+// bf16 A^T B product [M, N] over k = K with fp32 result and split-K allowed: will it accumulate with atomics?
+bool gemm_mfma_splits_k(int M, int N, int K, int nterm);
 
 // -------------------------------------------------------- row / pointwise ----
 // AT = operand type of activations (float or bf16); PT = parameter type.
