@@ -145,7 +145,7 @@ int hf_ctx::plan_and_alloc() {
     pl.add(loss_rows, T * 4);
     pl.add(sc, SS * 4); pl.add(sc_t, SS * 4);
     att_SS = SS;
-    pl.add(norm_part, (int64_t)NORM_PART_BLOCKS * 2 * D * 4);
+    pl.add(norm_part, (int64_t)NORM_PART_BLOCKS * 3 * D * 4);
     if (bf) pl.add(gemm_ws, GEMM_WS_ELEMS * 4);
     if (bf) {
       const int64_t rows = SS / desc.max_seq, np = (desc.max_seq + 63) / 64;  // B*H*S rows
@@ -527,16 +527,19 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
     if ((rc = L.bwd_dw(xf, xf_t, dz, dz_t, T, D, V, D, ldz, off_head, -1, nullptr, 0))) return rc;
     if ((rc = L.bwd_dx(dz, dz_t, T, D, V, ldz, off_head, tmpd, tmpd_t, D, 0))) return rc;
   }
-  // each norm adjoint also leaves the bf16 copies (dxb, dxb_t) that the next products read
+  // each norm adjoint also leaves the bf16 copies (dxb, dxb_t) that the next products read, and adds
+  // the column sums of its dx_t to the H v block of the bias that this adjoint belongs to (the output
+  // bias of the linear layer applied just before, in forward order)
   CK(launch_norm_bwd(bf, rms, tmpd, tmpd_t, xL, xL_t, stf, L.Wp(off_nfg), v + off_nfg, T, D, 0, dx, dx_t,
-                     out + off_nfg, rms ? nullptr : out + off_nfb, norm_part, st, bf ? dxb : nullptr, bf ? dxb_t : nullptr));
+                     out + off_nfg, rms ? nullptr : out + off_nfb, norm_part, st, bf ? dxb : nullptr, bf ? dxb_t : nullptr,
+                     loff[NL - 1].bproj >= 0 ? out + loff[NL - 1].bproj : nullptr));
 
   for (int l = NL - 1; l >= 0; --l) {
     LayerBuf& b = lb[l];
     const LayerOff& o = loff[l];
     // ---- MLP branch
     if (!llama) {
-      if ((rc = L.bwd_dw(b.g, b.g_t, dxb, dxb_t, T, F, D, F, D, o.wproj, o.bproj, dx_t, 0))) return rc;
+      if ((rc = L.bwd_dw(b.g, b.g_t, dxb, dxb_t, T, F, D, F, D, o.wproj, -1, nullptr, 0))) return rc;
       if ((rc = L.bwd_dx(dxb, dxb_t, T, F, D, D, o.wproj, dg, dg_t, F, bf))) return rc;
       CK(launch_act_bwd(bf, gelu_kind, b.f, b.f_t, dg, dg_t, dg, dg_t, (int64_t)T * F, st));
       if ((rc = L.bwd_dw(b.m, b.m_t, dg, dg_t, T, D, F, D, F, o.wfc, o.bfc, dg_t, bf))) return rc;
@@ -551,9 +554,10 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
       if ((rc = L.bwd_dx(dup, dup_t, T, D, F, F, o.wup, tmpd, tmpd_t, D, 0, tmpd, tmpd_t))) return rc;
     }
     CK(launch_norm_bwd(bf, rms, tmpd, tmpd_t, b.x2, b.x2_t, b.st2, L.Wp(o.n2g), v + o.n2g, T, D, 1, dx, dx_t,
-                       out + o.n2g, rms ? nullptr : out + o.n2b, norm_part, st, bf ? dxb : nullptr, bf ? dxb_t : nullptr));
+                       out + o.n2g, rms ? nullptr : out + o.n2b, norm_part, st, bf ? dxb : nullptr, bf ? dxb_t : nullptr,
+                       o.bo >= 0 ? out + o.bo : nullptr));
     // ---- attention branch
-    if ((rc = L.bwd_dw(b.o, b.o_t, dxb, dxb_t, T, D, D, D, D, o.wo, o.bo, dx_t, 0))) return rc;
+    if ((rc = L.bwd_dw(b.o, b.o_t, dxb, dxb_t, T, D, D, D, D, o.wo, -1, nullptr, 0))) return rc;
     if ((rc = L.bwd_dx(dxb, dxb_t, T, D, D, D, o.wo, dob, dob_t, D, bf))) return rc;
     // Products whose result belongs to a key/value head sum over the grp query heads that share
     // it: one launch per member j of the groups (batch = key/value heads, query head kv * grp + j),
@@ -658,7 +662,8 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
       }
     }
     CK(launch_norm_bwd(bf, rms, tmpd, tmpd_t, b.x1, b.x1_t, b.st1, L.Wp(o.n1g), v + o.n1g, T, D, 1, dx, dx_t,
-                       out + o.n1g, rms ? nullptr : out + o.n1b, norm_part, st, bf ? dxb : nullptr, bf ? dxb_t : nullptr));
+                       out + o.n1g, rms ? nullptr : out + o.n1b, norm_part, st, bf ? dxb : nullptr, bf ? dxb_t : nullptr,
+                       (l > 0 && loff[l - 1].bproj >= 0) ? out + loff[l - 1].bproj : nullptr));
   }
   CK(launch_embed_bwd(dx_t, tok, T, S, D, V, out + off_wte, llama ? nullptr : out + off_wpe, st));
   return HF_OK;

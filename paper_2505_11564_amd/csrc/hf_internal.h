@@ -149,7 +149,8 @@ constexpr int NORM_PART_BLOCKS = 1024;  // upper bound of the blocks launch_norm
 hipError_t launch_norm_bwd(int bf, int rms, const float* dy, const float* dy_t, const float* x, const float* x_t,
                            const float* stats, const void* gam, const float* gam_t, int T, int d, int accumulate,
                            float* dx, float* dx_t, float* hv_gam, float* hv_bet, float* part, hipStream_t st,
-                           void* dxb = nullptr, void* dxb_t = nullptr);  // optional bf16 copies of dx, dx_t
+                           void* dxb = nullptr, void* dxb_t = nullptr,  // optional bf16 copies of dx, dx_t
+                           float* hv_out = nullptr);  // optional: hv_out[c] += column sums of the dx_t written
 
 enum Act { ACT_TANH = 0, ACT_GELU = 1, ACT_GELU_TANH = 2 };
 // a_lo / y_lo (nullable): low-order halves of the primal input / output.

@@ -571,14 +571,15 @@ __global__ __launch_bounds__(256) void norm_bwd_vec_kernel(const float* __restri
                                                            const float* __restrict__ stats, const PT* gam,
                                                            const float* gam_t, int T, int d, int rows_per_block,
                                                            int accumulate, float* dx, float* dx_t, float* hv_gam,
-                                                           float* hv_bet, float* part, bf16* dxb, bf16* dxb_t) {
+                                                           float* hv_bet, float* part, bf16* dxb, bf16* dxb_t, float* hv_out) {
   __shared__ float red[16];
   const int d4 = d >> 2;
-  float4 pg[NCH], pb[NCH], gm[NCH], gmt[NCH];
+  float4 pg[NCH], pb[NCH], po[NCH], gm[NCH], gmt[NCH];
 #pragma unroll
   for (int j = 0; j < NCH; ++j) {
     pg[j] = make_float4(0.f, 0.f, 0.f, 0.f);
     pb[j] = pg[j];
+    po[j] = pg[j];
     const int c4 = j * 256 + threadIdx.x;
     gm[j] = c4 < d4 ? ld4(gam, c4) : pg[j];
     gmt[j] = c4 < d4 ? ld4(gam_t, c4) : pg[j];
@@ -638,6 +639,7 @@ __global__ __launch_bounds__(256) void norm_bwd_vec_kernel(const float* __restri
         }
         ((float4*)dx)[base4 + c4] = o;
         ((float4*)dx_t)[base4 + c4] = ot;
+        po[j].x += ot.x; po[j].y += ot.y; po[j].z += ot.z; po[j].w += ot.w;
         if (dxb) {  // operand-type copies for the products that consume the adjoint next
           const bf16 h[4] = {(bf16)o.x, (bf16)o.y, (bf16)o.z, (bf16)o.w}, ht[4] = {(bf16)ot.x, (bf16)ot.y, (bf16)ot.z, (bf16)ot.w};
           ((uint2*)dxb)[base4 + c4] = *(const uint2*)h;
@@ -651,9 +653,14 @@ __global__ __launch_bounds__(256) void norm_bwd_vec_kernel(const float* __restri
     const int c = 4 * (j * 256 + threadIdx.x);
     if (c < d) {
       if (part) {  // per-block partial sums, summed by norm_colsum_kernel
-        *(float4*)(part + ((size_t)blockIdx.x * 2) * d + c) = pg[j];
-        if (!RMS) *(float4*)(part + ((size_t)blockIdx.x * 2 + 1) * d + c) = pb[j];
+        *(float4*)(part + ((size_t)blockIdx.x * 3) * d + c) = pg[j];
+        if (!RMS) *(float4*)(part + ((size_t)blockIdx.x * 3 + 1) * d + c) = pb[j];
+        if (hv_out) *(float4*)(part + ((size_t)blockIdx.x * 3 + 2) * d + c) = po[j];
       } else {
+        if (hv_out) {
+          atomicAdd(hv_out + c, po[j].x); atomicAdd(hv_out + c + 1, po[j].y);
+          atomicAdd(hv_out + c + 2, po[j].z); atomicAdd(hv_out + c + 3, po[j].w);
+        }
         atomicAdd(hv_gam + c, pg[j].x); atomicAdd(hv_gam + c + 1, pg[j].y);
         atomicAdd(hv_gam + c + 2, pg[j].z); atomicAdd(hv_gam + c + 3, pg[j].w);
         if (!RMS) {
@@ -675,15 +682,16 @@ __global__ __launch_bounds__(256) void norm_bwd_wave_kernel(const float* __restr
                                                             const float* __restrict__ stats, const PT* gam,
                                                             const float* gam_t, int T, int d, int rows_per_block,
                                                             int accumulate, float* dx, float* dx_t, float* hv_gam,
-                                                            float* hv_bet, float* part, bf16* dxb, bf16* dxb_t) {
-  extern __shared__ float colred[];  // [2][4][d]
+                                                            float* hv_bet, float* part, bf16* dxb, bf16* dxb_t, float* hv_out) {
+  extern __shared__ float colred[];  // [2 or 3][4][d]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int d4 = d >> 2;
-  float4 pg[NJ], pb[NJ], gm[NJ], gmt[NJ];
+  float4 pg[NJ], pb[NJ], po[NJ], gm[NJ], gmt[NJ];
 #pragma unroll
   for (int j = 0; j < NJ; ++j) {
     pg[j] = make_float4(0.f, 0.f, 0.f, 0.f);
     pb[j] = pg[j];
+    po[j] = pg[j];
     const int c4 = j * 64 + lane;
     gm[j] = c4 < d4 ? ld4(gam, c4) : pg[j];
     gmt[j] = c4 < d4 ? ld4(gam_t, c4) : pg[j];
@@ -743,6 +751,7 @@ __global__ __launch_bounds__(256) void norm_bwd_wave_kernel(const float* __restr
         }
         ((float4*)dx)[base4 + c4] = o;
         ((float4*)dx_t)[base4 + c4] = ot;
+        po[j].x += ot.x; po[j].y += ot.y; po[j].z += ot.z; po[j].w += ot.w;
         if (dxb) {  // operand-type copies for the products that consume the adjoint next
           const bf16 h[4] = {(bf16)o.x, (bf16)o.y, (bf16)o.z, (bf16)o.w}, ht[4] = {(bf16)ot.x, (bf16)ot.y, (bf16)ot.z, (bf16)ot.w};
           ((uint2*)dxb)[base4 + c4] = *(const uint2*)h;
@@ -757,15 +766,17 @@ __global__ __launch_bounds__(256) void norm_bwd_wave_kernel(const float* __restr
     if (c4 < d4) {
       ((float4*)(colred + (size_t)wave * d))[c4] = pg[j];
       ((float4*)(colred + (size_t)(4 + wave) * d))[c4] = pb[j];
+      if (hv_out) ((float4*)(colred + (size_t)(8 + wave) * d))[c4] = po[j];
     }
   }
   __syncthreads();
   for (int c = threadIdx.x; c < d; c += 256) {
+    if (hv_out) atomicAdd(hv_out + c, (colred[8 * d + c] + colred[9 * d + c]) + (colred[10 * d + c] + colred[11 * d + c]));
     const float sg = (colred[c] + colred[d + c]) + (colred[2 * d + c] + colred[3 * d + c]);
     const float sb = (colred[4 * d + c] + colred[5 * d + c]) + (colred[6 * d + c] + colred[7 * d + c]);
     if (part) {
-      part[((size_t)blockIdx.x * 2) * d + c] = sg;
-      if (!RMS) part[((size_t)blockIdx.x * 2 + 1) * d + c] = sb;
+      part[((size_t)blockIdx.x * 3) * d + c] = sg;
+      if (!RMS) part[((size_t)blockIdx.x * 3 + 1) * d + c] = sb;
     } else {
       atomicAdd(hv_gam + c, sg);
       if (!RMS) atomicAdd(hv_bet + c, sb);
@@ -773,32 +784,36 @@ __global__ __launch_bounds__(256) void norm_bwd_wave_kernel(const float* __restr
   }
 }
 
-// hv[c] += sum over blocks of part[block][which][c]: grid (d / 256, groups, 2);
+// hv[c] += sum over blocks of part[block][which][c]: grid (d / 256, groups, 3);
 // each block sums its share of the partial rows and adds once per column.
-__global__ void norm_colsum_kernel(const float* __restrict__ part, int nblocks, int d, float* hv_gam, float* hv_bet) {
+__global__ void norm_colsum_kernel(const float* __restrict__ part, int nblocks, int d, float* hv_gam, float* hv_bet, float* hv_out) {
   const int c = blockIdx.x * 256 + threadIdx.x;
   if (c >= d) return;
   const int which = blockIdx.z;
-  float* hv = which ? hv_bet : hv_gam;
+  float* hv = which == 0 ? hv_gam : which == 1 ? hv_bet : hv_out;
+  if (!hv) return;
   const int per = (nblocks + gridDim.y - 1) / gridDim.y;
   const int b0 = blockIdx.y * per, b1 = min(nblocks, b0 + per);
   float s = 0.f;
-  for (int b = b0; b < b1; ++b) s += part[((size_t)b * 2 + which) * d + c];
+  for (int b = b0; b < b1; ++b) s += part[((size_t)b * 3 + which) * d + c];
   if (b1 > b0) atomicAdd(hv + c, s);
 }
 
 hipError_t launch_norm_bwd(int bf, int rms, const float* dy, const float* dy_t, const float* x, const float* x_t,
                            const float* stats, const void* gam, const float* gam_t, int T, int d, int accumulate,
                            float* dx, float* dx_t, float* hv_gam, float* hv_bet, float* part, hipStream_t st, void* dxb_v,
-                           void* dxb_t_v) {
+                           void* dxb_t_v, float* hv_out) {
   if (d > 256 * NORM_MAXC) return hipErrorInvalidValue;
   bf16* dxb = (bf16*)dxb_v;
   bf16* dxb_t = (bf16*)dxb_t_v;
   if ((dxb == nullptr) != (dxb_t == nullptr) || (((uintptr_t)dxb | (uintptr_t)dxb_t) & 7)) return hipErrorInvalidValue;
-  // part (optional): room for NORM_PART_BLOCKS x 2 x d floats; the vector kernels then leave their
+  // part (optional): room for NORM_PART_BLOCKS x 3 x d floats; the vector kernels then leave their
   // column sums there and a second kernel adds them up (the atomics otherwise cost more than the rows)
+  // hv_out (optional): also hv_out[c] += sum over rows of the dx_t written here, i.e. the H v block of
+  // the bias of the linear layer whose output adjoint this is.
   auto finish = [&](int blocks) {
-    hipLaunchKernelGGL(norm_colsum_kernel, dim3((d + 255) / 256, 16, rms ? 1 : 2), dim3(256), 0, st, part, blocks, d, hv_gam, hv_bet);
+    hipLaunchKernelGGL(norm_colsum_kernel, dim3((d + 255) / 256, 16, hv_out ? 3 : (rms ? 1 : 2)), dim3(256), 0, st, part, blocks, d, hv_gam,
+                       rms ? nullptr : hv_bet, hv_out);
     return hipGetLastError();
   };
   const bool vec_ok = d % 4 == 0 && all_aligned16({dy, dy_t, x, x_t, dx, dx_t, gam_t}) && ((uintptr_t)gam & (bf ? 7 : 15)) == 0;
@@ -807,8 +822,8 @@ hipError_t launch_norm_bwd(int bf, int rms, const float* dy, const float* dy_t, 
     const int blocks = (T + rpb - 1) / rpb;
     const int nj = (d / 4 + 63) / 64;
     part = nullptr;  // narrow rows: the atomics are cheaper than a second launch
-    const size_t lds = (size_t)8 * d * sizeof(float);
-#define HF_NBW2(PT, R, N) hipLaunchKernelGGL((norm_bwd_wave_kernel<PT, R, N>), dim3(blocks), dim3(256), lds, st, dy, dy_t, x, x_t, stats, (const PT*)gam, gam_t, T, d, rpb, accumulate, dx, dx_t, hv_gam, hv_bet, part, dxb, dxb_t)
+    const size_t lds = (size_t)(hv_out ? 12 : 8) * d * sizeof(float);
+#define HF_NBW2(PT, R, N) hipLaunchKernelGGL((norm_bwd_wave_kernel<PT, R, N>), dim3(blocks), dim3(256), lds, st, dy, dy_t, x, x_t, stats, (const PT*)gam, gam_t, T, d, rpb, accumulate, dx, dx_t, hv_gam, hv_bet, part, dxb, dxb_t, hv_out)
 #define HF_NBW1(PT, R) { if (nj <= 1) HF_NBW2(PT, R, 1); else if (nj <= 2) HF_NBW2(PT, R, 2); else if (nj <= 3) HF_NBW2(PT, R, 3); else HF_NBW2(PT, R, 4); }
     if (bf) { if (rms) HF_NBW1(bf16, true) else HF_NBW1(bf16, false) }
     else { if (rms) HF_NBW1(float, true) else HF_NBW1(float, false) }
@@ -822,7 +837,7 @@ hipError_t launch_norm_bwd(int bf, int rms, const float* dy, const float* dy_t, 
     const int blocks = (T + rpb - 1) / rpb;
     const int nch = (d / 4 + 255) / 256;
     if (blocks > NORM_PART_BLOCKS) part = nullptr;
-#define HF_NBV2(PT, R, N) hipLaunchKernelGGL((norm_bwd_vec_kernel<PT, R, N>), dim3(blocks), dim3(256), 0, st, dy, dy_t, x, x_t, stats, (const PT*)gam, gam_t, T, d, rpb, accumulate, dx, dx_t, hv_gam, hv_bet, part, dxb, dxb_t)
+#define HF_NBV2(PT, R, N) hipLaunchKernelGGL((norm_bwd_vec_kernel<PT, R, N>), dim3(blocks), dim3(256), 0, st, dy, dy_t, x, x_t, stats, (const PT*)gam, gam_t, T, d, rpb, accumulate, dx, dx_t, hv_gam, hv_bet, part, dxb, dxb_t, hv_out)
 #define HF_NBV1(PT, R) { if (nch <= 1) HF_NBV2(PT, R, 1); else if (nch <= 2) HF_NBV2(PT, R, 2); else if (nch <= 4) HF_NBV2(PT, R, 4); else HF_NBV2(PT, R, 8); }
     if (bf) { if (rms) HF_NBV1(bf16, true) else HF_NBV1(bf16, false) }
     else { if (rms) HF_NBV1(float, true) else HF_NBV1(float, false) }
@@ -837,7 +852,8 @@ hipError_t launch_norm_bwd(int bf, int rms, const float* dy, const float* dy_t, 
   if (bf) { if (rms) HF_NB(bf16, true); else HF_NB(bf16, false); }
   else { if (rms) HF_NB(float, true); else HF_NB(float, false); }
 #undef HF_NB
-  return hipGetLastError();
+  if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
+  return hv_out ? launch_colsum(0, dx_t, T, d, d, hv_out, st) : hipSuccess;
 }
 
 // ------------------------------------------------------------ activations ----
