@@ -35,9 +35,15 @@ def _oracle_case(cfg, model, batch=None):
     _free()
     want_loss, _, want, _ = om.loss_grad_hvp(model, p.astype(np.float64), x, y, v.astype(np.float64))
     err = rel_l2(got, want)
+    rows = sorted(block_errors(model, got, want, om.layout(model)), key=lambda r: -r[1])
     if not err <= TOL_BF16:
-        rows = sorted(block_errors(model, got, want, om.layout(model)), key=lambda r: -r[1])[:10]
-        raise AssertionError(f"rel L2 {err:.3e}; worst blocks {rows}")
+        raise AssertionError(f"rel L2 {err:.3e}; worst blocks {rows[:10]}")
+    print("worst blocks:", [(r[0], f"{r[1]:.2e}") for r in rows[:4]])
+    # every parameter tensor's block on its own (twice the bar: a block of a few hundred entries
+    # does not average the bf16 rounding of its inputs the way the whole vector does)
+    total = float(np.linalg.norm(want))
+    bad = [r for r in rows if r[2] > 1e-6 * total and not r[1] <= 2 * TOL_BF16]
+    assert not bad, f"blocks above {2 * TOL_BF16}: {bad[:10]}"
     assert abs(loss - want_loss) <= 1e-2 * abs(want_loss)
     print(f"rel L2 error {err:.3e}, loss {loss:.5f} vs {want_loss:.5f}")
 
