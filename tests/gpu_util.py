@@ -25,7 +25,8 @@ def gpu_hvp(model, params_f32, inputs, labels, v, param_dtype="f32", ctx=None, m
     x = torch.from_numpy(np.ascontiguousarray(inputs)).cuda()
     y = torch.from_numpy(np.ascontiguousarray(labels.astype(np.int32))).cuda()
     vd = torch.from_numpy(np.ascontiguousarray(v.astype(np.float32))).cuda()
-    out = torch.empty(ctx.n, dtype=torch.float32, device="cuda")
+    # NaN-filled result buffer: every element must be written (or cleared) by the library itself
+    out = torch.full((ctx.n,), float("nan"), dtype=torch.float32, device="cuda")
     loss = ctx.hf_hvp(p, x, y, B, S, vd, out)
     res = out.cpu().numpy().astype(np.float64)
     if own:

@@ -84,7 +84,7 @@ def _full_depth_invariants(name):
     pb = device_params(model, "bf16")
     v, w = device_randn(n, 1), device_randn(n, 2)
     ctx = hf.Context(model, B, 4, "bf16", cfg["basis_dtype"])
-    hv, tmp = torch.empty_like(v), torch.empty_like(v)
+    hv, tmp = torch.full_like(v, float("nan")), torch.full_like(v, float("nan"))  # every element must be written
     loss = ctx.hf_hvp(pb, xd, yd, B, S, v, hv)
     assert abs(loss - np.log(model["vocab"])) < 1.5          # random init: near-uniform predictions
     assert np.isfinite(_ddot(hv, hv))

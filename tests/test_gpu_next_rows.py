@@ -35,7 +35,7 @@ def _accumulate(cfg, n_samples, micro, param_dtype, seed=0):
         v = si.bf16_bits_to_f32(si.f32_to_bf16_bits(v))
     S = x.shape[1] if model["arch"] != "mlp" else 1
     ctx = hf.Context(model, micro, 0, param_dtype)
-    out = torch.empty(ctx.n, dtype=torch.float32, device="cuda")
+    out = torch.full((ctx.n,), float("nan"), dtype=torch.float32, device="cuda")  # must be overwritten, not added to
     loss = ctx.hf_hvp_accumulate(to_dev_params(p, param_dtype), _dev(x), _dev(y.astype(np.int32)), n_samples, micro, S,
                                  _dev(v), out)
     got = out.cpu().numpy().astype(np.float64)
