@@ -172,8 +172,8 @@ int hf_ctx::plan_and_alloc() {
     ldq = round_up(n, 64);
     if (desc.basis_dtype != HF_NONE) pl.add(basis, (int64_t)max_m * ldq * (desc.basis_dtype == HF_BF16 ? 2 : 4));
     pl.add(scal, S_COUNT * 8);
-    pl.add(cvec, (int64_t)max_m * 8);
-    pl.add(partials, std::max<int64_t>((int64_t)LZ_NBLK * max_m, LZ_NBLK_VEC) * 8);
+    pl.add(cvec, (int64_t)(max_m + 1) * 8);
+    pl.add(partials, std::max<int64_t>((int64_t)LZ_NBLK * (max_m + 1), LZ_NBLK_VEC) * 8);
   }
   arena_bytes = pl.off;
   hipError_t e1 = hipMalloc((void**)&arena, (size_t)arena_bytes);
@@ -677,11 +677,18 @@ int hf_ctx::lanczos_update(float* r, double tol, double* alpha_k, double* beta_k
   const int bq = desc.basis_dtype == HF_BF16;
   float* q = lz_vec[iq];
   float* qp = lz_vec[iqp];
-  CK(lz_axpy_dot(r, q, qp, n, k > 0, scal, partials, st));
-  CK(lz_axpy_nrm(r, q, n, scal, partials, st));
-  if (lz_reorth == HF_REORTH_FULL) {
-    CK(lz_reorth_pass(basis, bq, ldq, r, n, k + 1, 0, scal, cvec, partials, st));
+  if (lz_reorth == HF_REORTH_FULL && !bq) {
+    // fp32 basis: rows k and k - 1 are q_k and q_{k-1} themselves, so Gram-Schmidt of H q_k
+    // against rows 0..k is the three-term subtraction and the orthogonalisation in one
+    CK(lz_gs_first_pass((const float*)basis, ldq, r, n, k + 1, scal, cvec, partials, st));
     CK(lz_reorth_pass(basis, bq, ldq, r, n, k + 1, 1, scal, cvec, partials, st));
+  } else {
+    CK(lz_axpy_dot(r, q, qp, n, k > 0, scal, partials, st));
+    CK(lz_axpy_nrm(r, q, n, scal, partials, st));
+    if (lz_reorth == HF_REORTH_FULL) {
+      CK(lz_reorth_pass(basis, bq, ldq, r, n, k + 1, 0, scal, cvec, partials, st));
+      CK(lz_reorth_pass(basis, bq, ldq, r, n, k + 1, 1, scal, cvec, partials, st));
+    }
   }
   CK(hipMemcpyAsync(host_scal, scal, S_COUNT * sizeof(double), hipMemcpyDeviceToHost, st));
   CK(hipStreamSynchronize(st));

@@ -29,6 +29,10 @@ hipError_t lz_scale(const float* src, float* dst, void* basis, int basis_bf16, b
 // unless pass 0 set the redo flag.
 hipError_t lz_reorth_pass(const void* Q, int basis_bf16, int64_t ldq, float* r, int64_t n, int nq, int pass,
                           double* scal, double* c, double* partials, hipStream_t st);
+// The first pass applied to w = H q_k itself against an fp32 basis holding q_0 .. q_k (nq = k + 1):
+// also yields alpha_k, in place of lz_axpy_dot and lz_axpy_nrm.
+hipError_t lz_gs_first_pass(const float* Q, int64_t ldq, float* r, int64_t n, int nq, double* scal, double* c,
+                            double* partials, hipStream_t st);
 hipError_t lz_widen(const void* src, int is_bf16, float* dst, int64_t n, hipStream_t st);
 
 }  // namespace hf

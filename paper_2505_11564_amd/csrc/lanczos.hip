@@ -8,6 +8,8 @@
 //   lz_qtr      : c = Q^T r      (k+1 dot products, Q read once)
 //   lz_sub_qc   : r -= Q c;  beta_k = ||r||   (Q read once)
 //   lz_scale    : q_{k+1} = r / beta_k, appended to the basis         (1R + 1W)
+// With an fp32 basis (rows k and k-1 are q_k and q_{k-1} themselves) lz_qtr / lz_sub_qc are applied
+// to H q_k directly: alpha_k is the k-th coefficient and the first two kernels are not run.
 // Scalars stay on the device (array `scal` of doubles) so consecutive kernels
 // need no host round trip.  Reductions: fp64 per-thread accumulators, one
 // partial per block, summed in a fixed order by a small second kernel, so
@@ -239,21 +241,31 @@ __device__ __forceinline__ void load_q_slice(const BT* __restrict__ q, int64_t b
 }
 
 // c_j = <Q_j, r>: partials[j * nblk + block] (fp64), summed by lz_qtr_finish_kernel.
-template <typename BT>
+// RR: one more result, c_nq = <r, r>.
+template <typename BT, bool RR = false>
 __global__ __launch_bounds__(256) void lz_qtr_kernel(const BT* __restrict__ Q, int64_t ldq, const float* __restrict__ r,
                                                      int64_t n, int nq, int64_t nslices, const double* scal, int pass,
                                                      double* __restrict__ partials) {
   typedef QVec<BT> V;
-  extern __shared__ double accs[];  // [4 waves][nq]
+  extern __shared__ double accs[];  // [4 waves][na]
   if (pass == 1 && scal[S_REDO] == 0.0) return;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  for (int j = threadIdx.x; j < 4 * nq; j += 256) accs[j] = 0.0;
+  const int na = nq + (RR ? 1 : 0);
+  for (int j = threadIdx.x; j < 4 * na; j += 256) accs[j] = 0.0;
   __syncthreads();
   for (int64_t sl = blockIdx.x; sl < nslices; sl += gridDim.x) {
     const int64_t base = sl * LZ_SLICE;
     const bool full = base + LZ_SLICE <= n;
     float rv[LZ_RPT];
     load_r_slice<BT>(r, base, n, rv);
+    if (RR) {
+      float s = 0.f;
+#pragma unroll
+      for (int k = 0; k < LZ_RPT; ++k) s = fmaf(rv[k], rv[k], s);
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+      if (lane == 0) accs[wave * na + nq] += (double)s;
+    }
     auto dot_j = [&](const typename V::raw (&qv)[V::U], int j) {
       float s = 0.f;
 #pragma unroll
@@ -265,7 +277,7 @@ __global__ __launch_bounds__(256) void lz_qtr_kernel(const BT* __restrict__ Q, i
       }
 #pragma unroll
       for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
-      if (lane == 0) accs[wave * nq + j] += (double)s;
+      if (lane == 0) accs[wave * na + j] += (double)s;
     };
     typename V::raw qa[V::U], qb[V::U];
     load_q_slice<BT>(Q, base, n, full, qa);
@@ -278,8 +290,22 @@ __global__ __launch_bounds__(256) void lz_qtr_kernel(const BT* __restrict__ Q, i
     }
   }
   __syncthreads();
-  for (int j = threadIdx.x; j < nq; j += 256)
-    partials[(int64_t)j * gridDim.x + blockIdx.x] = accs[j] + accs[nq + j] + accs[2 * nq + j] + accs[3 * nq + j];
+  for (int j = threadIdx.x; j < na; j += 256)
+    partials[(int64_t)j * gridDim.x + blockIdx.x] = accs[j] + accs[na + j] + accs[2 * na + j] + accs[3 * na + j];
+}
+
+// After c = Q^T w and c_nq = <w, w> (w = H q_k, Q = q_0 .. q_k in fp32): alpha_k = c_k, and the
+// norm that the three-term recurrence would have left before the orthogonalisation pass,
+// ||w - alpha_k q_k - c_{k-1} q_{k-1}||, follows from the three numbers.  Where that difference
+// has lost its digits (beta_k tiny against alpha_k) the norm is set to infinity, which makes the
+// pass that follows ask for a second one.
+__global__ void lz_direct_scal_kernel(const double* __restrict__ c, int nq, double* __restrict__ scal) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  const double a = c[nq - 1], p = nq >= 2 ? c[nq - 2] : 0.0, ww = c[nq];
+  const double rest = ww - a * a - p * p;
+  scal[S_ALPHA] = a;
+  scal[S_NRM_BEFORE] = rest > 1e-5 * ww ? sqrt(rest) : INFINITY;
+  scal[S_REDO] = 0.0;
 }
 
 __global__ __launch_bounds__(256) void lz_qtr_finish_kernel(const double* partials, int nblk, const double* scal,
@@ -410,6 +436,25 @@ hipError_t lz_reorth_pass(const void* Q, int basis_bf16, int64_t ldq, float* r, 
     hipLaunchKernelGGL(lz_sub_qc_kernel<float>, dim3(nb), dim3(256), sh2, st, (const float*)Q, ldq, r, n, nq, nslices, c, scal, pass, partials);
   }
   hipLaunchKernelGGL(lz_finish_kernel, dim3(1), dim3(256), 0, st, partials, nb, 3, pass, scal);
+  return hipGetLastError();
+}
+
+// First Gram-Schmidt pass straight on w = H q_k against an fp32 basis that holds q_0 .. q_k
+// (nq = k + 1 rows): the coefficients of rows k and k - 1 are alpha_k and (up to rounding)
+// beta_{k-1}, so the pass subsumes the three-term subtraction, which saves its two passes over the
+// vectors.  Leaves alpha_k, ||r|| and the redo flag in scal as the three-term kernels followed by
+// lz_reorth_pass(pass 0) do.  c: nq + 1 doubles, partials: (nq + 1) * LZ_NBLK doubles.
+hipError_t lz_gs_first_pass(const float* Q, int64_t ldq, float* r, int64_t n, int nq, double* scal, double* c,
+                            double* partials, hipStream_t st) {
+  if (nq <= 0) return hipErrorInvalidValue;
+  const int64_t nslices = (n + LZ_SLICE - 1) / LZ_SLICE;
+  const int nb = (int)std::max<int64_t>(1, std::min<int64_t>(nslices, LZ_NBLK));
+  const size_t sh1 = (size_t)4 * (nq + 1) * sizeof(double), sh2 = (size_t)nq * sizeof(float);
+  hipLaunchKernelGGL((lz_qtr_kernel<float, true>), dim3(nb), dim3(256), sh1, st, Q, ldq, r, n, nq, nslices, scal, 0, partials);
+  hipLaunchKernelGGL(lz_qtr_finish_kernel, dim3(nq + 1), dim3(256), 0, st, partials, nb, scal, 0, c);
+  hipLaunchKernelGGL(lz_direct_scal_kernel, dim3(1), dim3(64), 0, st, c, nq, scal);
+  hipLaunchKernelGGL(lz_sub_qc_kernel<float>, dim3(nb), dim3(256), sh2, st, Q, ldq, r, n, nq, nslices, c, scal, 0, partials);
+  hipLaunchKernelGGL(lz_finish_kernel, dim3(1), dim3(256), 0, st, partials, nb, 3, 0, scal);
   return hipGetLastError();
 }
 
