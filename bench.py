@@ -45,20 +45,23 @@ def hvp_flops(model, batch, seq):
 
 
 def lanczos_bytes(n, k, reorth, basis_bytes, bf16_operands=False):
-    """Algorithmic HBM bytes of the vector update of iteration k.  Three-term
-    part: 7 fp32 words per element (3R+1W, 2R+1W); normalisation 1R+1W; one
-    classical Gram-Schmidt pass reads the k+1 stored vectors twice and r three
-    times (2R+1W); appending q_{k+1} writes one basis vector; with bf16
-    operands the normalisation also writes the bf16 copy of q_{k+1} that the
-    next Hessian-vector product multiplies with.  Against an fp32 basis the
-    Gram-Schmidt pass is applied to H q_k itself (rows k and k-1 of the basis
-    are q_k and q_{k-1}), so the three-term part moves no bytes of its own."""
-    b = 8.0 * n + (2.0 * n if bf16_operands else 0.0)
-    if reorth == "full":
-        b += 2.0 * (k + 1) * n * basis_bytes + 12.0 * n + basis_bytes * n
-    if not (reorth == "full" and basis_bytes == 4):
-        b += 28.0 * n
-    return b
+    """Algorithmic HBM bytes of the vector update of iteration k.  Without a
+    basis: 9 fp32 words per element (3R+1W, 2R+1W, normalisation 1R+1W).  With
+    full re-orthogonalisation the Gram-Schmidt pass is applied to H q_k itself
+    and subsumes the three-term part: it reads q_0..q_k twice (an fp32 basis
+    holds them all; with a bf16 basis q_k and q_{k-1} are read from the fp32
+    working vectors and the k-1 older ones from the basis) and r three times
+    (2R+1W); then normalisation (1R+1W) and the appended basis vector.  With
+    bf16 operands the normalisation also writes the bf16 copy of q_{k+1} that
+    the next Hessian-vector product multiplies with."""
+    vb = 2.0 * n if bf16_operands else 0.0
+    if reorth != "full":
+        return 36.0 * n + vb
+    if basis_bytes == 4:
+        rows = (k + 1) * 4.0 * n
+    else:
+        rows = max(0, k - 1) * 2.0 * n + min(k + 1, 2) * 4.0 * n
+    return 8.0 * n + vb + 2.0 * rows + 12.0 * n + basis_bytes * n
 
 
 def measured_traffic(workload):

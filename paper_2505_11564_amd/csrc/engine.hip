@@ -677,18 +677,16 @@ int hf_ctx::lanczos_update(float* r, double tol, double* alpha_k, double* beta_k
   const int bq = desc.basis_dtype == HF_BF16;
   float* q = lz_vec[iq];
   float* qp = lz_vec[iqp];
-  if (lz_reorth == HF_REORTH_FULL && !bq) {
-    // fp32 basis: rows k and k - 1 are q_k and q_{k-1} themselves, so Gram-Schmidt of H q_k
-    // against rows 0..k is the three-term subtraction and the orthogonalisation in one
-    CK(lz_gs_first_pass((const float*)basis, ldq, r, n, k + 1, scal, cvec, partials, st));
+  if (lz_reorth == HF_REORTH_FULL) {
+    // Gram-Schmidt of H q_k against q_0 .. q_k is the three-term subtraction and the
+    // orthogonalisation in one.  An fp32 basis holds q_k and q_{k-1} as its rows k and k - 1; a
+    // bf16 basis holds rounded copies, so those two come from the working vectors instead.
+    if (!bq) CK(lz_gs_first_pass((const float*)basis, ldq, r, n, k + 1, scal, cvec, partials, st));
+    else CK(lz_gs_first_pass_bf16((const bf16*)basis, ldq, qp, q, r, n, k, scal, cvec, partials, st));
     CK(lz_reorth_pass(basis, bq, ldq, r, n, k + 1, 1, scal, cvec, partials, st));
   } else {
     CK(lz_axpy_dot(r, q, qp, n, k > 0, scal, partials, st));
     CK(lz_axpy_nrm(r, q, n, scal, partials, st));
-    if (lz_reorth == HF_REORTH_FULL) {
-      CK(lz_reorth_pass(basis, bq, ldq, r, n, k + 1, 0, scal, cvec, partials, st));
-      CK(lz_reorth_pass(basis, bq, ldq, r, n, k + 1, 1, scal, cvec, partials, st));
-    }
   }
   CK(hipMemcpyAsync(host_scal, scal, S_COUNT * sizeof(double), hipMemcpyDeviceToHost, st));
   CK(hipStreamSynchronize(st));

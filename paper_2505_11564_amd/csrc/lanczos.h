@@ -33,6 +33,9 @@ hipError_t lz_reorth_pass(const void* Q, int basis_bf16, int64_t ldq, float* r, 
 // also yields alpha_k, in place of lz_axpy_dot and lz_axpy_nrm.
 hipError_t lz_gs_first_pass(const float* Q, int64_t ldq, float* r, int64_t n, int nq, double* scal, double* c,
                             double* partials, hipStream_t st);
+// The same for a bf16 basis: q_k and q_{k-1} come from the fp32 working vectors, rows 0 .. k-2 from the basis.
+hipError_t lz_gs_first_pass_bf16(const bf16* Q, int64_t ldq, const float* qkm1, const float* qk, float* r, int64_t n, int k,
+                                 double* scal, double* c, double* partials, hipStream_t st);
 hipError_t lz_widen(const void* src, int is_bf16, float* dst, int64_t n, hipStream_t st);
 
 }  // namespace hf

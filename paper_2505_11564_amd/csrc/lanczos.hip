@@ -8,8 +8,9 @@
 //   lz_qtr      : c = Q^T r      (k+1 dot products, Q read once)
 //   lz_sub_qc   : r -= Q c;  beta_k = ||r||   (Q read once)
 //   lz_scale    : q_{k+1} = r / beta_k, appended to the basis         (1R + 1W)
-// With an fp32 basis (rows k and k-1 are q_k and q_{k-1} themselves) lz_qtr / lz_sub_qc are applied
-// to H q_k directly: alpha_k is the k-th coefficient and the first two kernels are not run.
+// With a stored basis lz_qtr / lz_sub_qc are applied to H q_k directly (Gram-Schmidt against
+// q_0 .. q_k; with a bf16 basis q_k and q_{k-1} are taken from the fp32 working vectors): alpha_k is
+// the k-th coefficient and the first two kernels are not run.
 // Scalars stay on the device (array `scal` of doubles) so consecutive kernels
 // need no host round trip.  Reductions: fp64 per-thread accumulators, one
 // partial per block, summed in a fixed order by a small second kernel, so
@@ -242,15 +243,19 @@ __device__ __forceinline__ void load_q_slice(const BT* __restrict__ q, int64_t b
 
 // c_j = <Q_j, r>: partials[j * nblk + block] (fp64), summed by lz_qtr_finish_kernel.
 // RR: one more result, c_nq = <r, r>.
-template <typename BT, bool RR = false>
+// x0, x1 (optional, fp32 vectors): two more "rows" after the nq stored ones, results nq and nq + 1
+// (x1 alone is not allowed); the <r, r> result then follows them.
+template <typename BT, bool RR = false, bool XR = false>
 __global__ __launch_bounds__(256) void lz_qtr_kernel(const BT* __restrict__ Q, int64_t ldq, const float* __restrict__ r,
                                                      int64_t n, int nq, int64_t nslices, const double* scal, int pass,
-                                                     double* __restrict__ partials) {
+                                                     double* __restrict__ partials, const float* __restrict__ x0 = nullptr,
+                                                     const float* __restrict__ x1 = nullptr) {
   typedef QVec<BT> V;
   extern __shared__ double accs[];  // [4 waves][na]
   if (pass == 1 && scal[S_REDO] == 0.0) return;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int na = nq + (RR ? 1 : 0);
+  const int nx = XR ? (x0 ? 1 : 0) + (x1 ? 1 : 0) : 0;
+  const int na = nq + nx + (RR ? 1 : 0);
   for (int j = threadIdx.x; j < 4 * na; j += 256) accs[j] = 0.0;
   __syncthreads();
   for (int64_t sl = blockIdx.x; sl < nslices; sl += gridDim.x) {
@@ -264,7 +269,23 @@ __global__ __launch_bounds__(256) void lz_qtr_kernel(const BT* __restrict__ Q, i
       for (int k = 0; k < LZ_RPT; ++k) s = fmaf(rv[k], rv[k], s);
 #pragma unroll
       for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
-      if (lane == 0) accs[wave * na + nq] += (double)s;
+      if (lane == 0) accs[wave * na + nq + nx] += (double)s;
+    }
+    // the fp32 rows, in r's register layout
+    auto dot_x = [&](const float* __restrict__ x, int j) {
+      float xv[LZ_RPT];
+      load_r_slice<BT>(x, base, n, xv);
+      float s = 0.f;
+#pragma unroll
+      for (int k = 0; k < LZ_RPT; ++k) s = fmaf(xv[k], rv[k], s);
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+      if (lane == 0) accs[wave * na + j] += (double)s;
+    };
+    if constexpr (XR) {
+      if (x0) dot_x(x0, nq);
+      if (x1) dot_x(x1, nq + 1);
+      if (nq == 0) continue;
     }
     auto dot_j = [&](const typename V::raw (&qv)[V::U], int j) {
       float s = 0.f;
@@ -320,15 +341,18 @@ __global__ __launch_bounds__(256) void lz_qtr_finish_kernel(const double* partia
 }
 
 // r -= sum_j c_j Q_j, partial ||r||^2.
-template <typename BT>
+// x0, x1 (optional, fp32 vectors): two more rows with coefficients c[nq], c[nq + 1].
+template <typename BT, bool XR = false>
 __global__ __launch_bounds__(256) void lz_sub_qc_kernel(const BT* __restrict__ Q, int64_t ldq, float* __restrict__ r,
                                                         int64_t n, int nq, int64_t nslices, const double* __restrict__ c,
-                                                        const double* scal, int pass, double* __restrict__ partials) {
+                                                        const double* scal, int pass, double* __restrict__ partials,
+                                                        const float* __restrict__ x0 = nullptr, const float* __restrict__ x1 = nullptr) {
   typedef QVec<BT> V;
   extern __shared__ float cs[];
   __shared__ double red[4];
   if (pass == 1 && scal[S_REDO] == 0.0) return;
-  for (int j = threadIdx.x; j < nq; j += 256) cs[j] = (float)c[j];
+  const int nx = XR ? (x0 ? 1 : 0) + (x1 ? 1 : 0) : 0;
+  for (int j = threadIdx.x; j < nq + nx; j += 256) cs[j] = (float)c[j];
   __syncthreads();
   double acc = 0.0;
   for (int64_t sl = blockIdx.x; sl < nslices; sl += gridDim.x) {
@@ -346,14 +370,27 @@ __global__ __launch_bounds__(256) void lz_sub_qc_kernel(const BT* __restrict__ Q
         for (int k = 0; k < V::E; ++k) rv[u * V::E + k] = fmaf(-cj, qf[k], rv[u * V::E + k]);
       }
     };
-    typename V::raw qa[V::U], qb[V::U];
-    load_q_slice<BT>(Q, base, n, full, qa);
+    auto sub_x = [&](const float* __restrict__ x, int j) {
+      float xv[LZ_RPT];
+      load_r_slice<BT>(x, base, n, xv);
+      const float cj = cs[j];
+#pragma unroll
+      for (int k = 0; k < LZ_RPT; ++k) rv[k] = fmaf(-cj, xv[k], rv[k]);
+    };
+    if constexpr (XR) {
+      if (x0) sub_x(x0, nq);
+      if (x1) sub_x(x1, nq + 1);
+    }
+    if (!XR || nq > 0) {
+      typename V::raw qa[V::U], qb[V::U];
+      load_q_slice<BT>(Q, base, n, full, qa);
 #pragma unroll 1
-    for (int j = 0; j < nq; j += 2) {
-      if (j + 1 < nq) load_q_slice<BT>(Q + (int64_t)(j + 1) * ldq, base, n, full, qb);
-      sub_j(qa, j);
-      if (j + 2 < nq) load_q_slice<BT>(Q + (int64_t)(j + 2) * ldq, base, n, full, qa);
-      if (j + 1 < nq) sub_j(qb, j + 1);
+      for (int j = 0; j < nq; j += 2) {
+        if (j + 1 < nq) load_q_slice<BT>(Q + (int64_t)(j + 1) * ldq, base, n, full, qb);
+        sub_j(qa, j);
+        if (j + 2 < nq) load_q_slice<BT>(Q + (int64_t)(j + 2) * ldq, base, n, full, qa);
+        if (j + 1 < nq) sub_j(qb, j + 1);
+      }
     }
     float s = 0.f;
 #pragma unroll
@@ -454,6 +491,26 @@ hipError_t lz_gs_first_pass(const float* Q, int64_t ldq, float* r, int64_t n, in
   hipLaunchKernelGGL(lz_qtr_finish_kernel, dim3(nq + 1), dim3(256), 0, st, partials, nb, scal, 0, c);
   hipLaunchKernelGGL(lz_direct_scal_kernel, dim3(1), dim3(64), 0, st, c, nq, scal);
   hipLaunchKernelGGL(lz_sub_qc_kernel<float>, dim3(nb), dim3(256), sh2, st, Q, ldq, r, n, nq, nslices, c, scal, 0, partials);
+  hipLaunchKernelGGL(lz_finish_kernel, dim3(1), dim3(256), 0, st, partials, nb, 3, 0, scal);
+  return hipGetLastError();
+}
+
+// The same with a bf16 basis: its rows k and k - 1 are rounded copies, so the pass takes q_k and
+// q_{k-1} from the fp32 working vectors instead (alpha_k must come from the unrounded q_k) and the
+// rounded rows 0 .. k-2 from the basis.  qkm1 is ignored for k = 0.
+hipError_t lz_gs_first_pass_bf16(const bf16* Q, int64_t ldq, const float* qkm1, const float* qk, float* r, int64_t n, int k,
+                                 double* scal, double* c, double* partials, hipStream_t st) {
+  if (k < 0 || !qk || (k > 0 && !qkm1)) return hipErrorInvalidValue;
+  const int64_t nslices = (n + LZ_SLICE - 1) / LZ_SLICE;
+  const int nb = (int)std::max<int64_t>(1, std::min<int64_t>(nslices, LZ_NBLK));
+  const int nqb = std::max(0, k - 1);  // rows taken from the basis
+  const float* x0 = k > 0 ? qkm1 : qk;
+  const float* x1 = k > 0 ? qk : nullptr;
+  const size_t sh1 = (size_t)4 * (k + 2) * sizeof(double), sh2 = (size_t)(k + 1) * sizeof(float);
+  hipLaunchKernelGGL((lz_qtr_kernel<bf16, true, true>), dim3(nb), dim3(256), sh1, st, Q, ldq, r, n, nqb, nslices, scal, 0, partials, x0, x1);
+  hipLaunchKernelGGL(lz_qtr_finish_kernel, dim3(k + 2), dim3(256), 0, st, partials, nb, scal, 0, c);
+  hipLaunchKernelGGL(lz_direct_scal_kernel, dim3(1), dim3(64), 0, st, c, k + 1, scal);
+  hipLaunchKernelGGL((lz_sub_qc_kernel<bf16, true>), dim3(nb), dim3(256), sh2, st, Q, ldq, r, n, nqb, nslices, c, scal, 0, partials, x0, x1);
   hipLaunchKernelGGL(lz_finish_kernel, dim3(1), dim3(256), 0, st, partials, nb, 3, 0, scal);
   return hipGetLastError();
 }
