@@ -169,6 +169,9 @@ int32_t hf_lanczos_init(hf_ctx* ctx, const float* q0_dev, int32_t reorth,
  * alpha_k = <q_k, r>; r -= alpha_k q_k; [full orthogonalisation of r against
  * q_0..q_k: classical Gram-Schmidt, a second pass when the first shrank ||r||
  * below 1/sqrt(2)]; beta_k = ||r||; q_{k+1} = r / beta_k unless beta_k < tol.
+ * With full orthogonalisation the two subtractions are carried out by the
+ * first Gram-Schmidt pass itself, applied to H q_k against q_0..q_k (alpha_k
+ * is its k-th coefficient): the same r and alpha_k up to rounding.
  * alpha_k / beta_k: host outputs.  Returns HF_EBREAKDOWN when beta_k < tol
  * (the iteration has ended), HF_ESHAPE after max_m iterations with a basis. */
 int32_t hf_lanczos_step(hf_ctx* ctx, const void* params_dev,
