@@ -25,7 +25,8 @@
  *     retained after the call returns, except q0_dev which hf_lanczos_init
  *     copies.  Pointers without _dev are host pointers.
  *   - The library owns only what hf_create allocates (activation workspace for
- *     max_batch*max_seq tokens, three fp32 Lanczos vectors, max_m basis
+ *     max_batch*max_seq tokens, three fp32 Lanczos vectors (with an fp32 basis
+ *     its rows k and k-1 serve as q_k and q_{k-1}), max_m basis
  *     vectors, a bf16 copy of the direction when parameters are bf16) and
  *     frees it in hf_destroy.
  *   - Work is enqueued on the HIP stream passed as `hip_stream` (a hipStream_t
@@ -132,7 +133,8 @@ const char* hf_version(void);
 
 /* Allocates every buffer the calls below need for batches of at most
  * max_batch sequences of at most desc->max_seq tokens (MLP: max_batch rows)
- * and Lanczos runs of at most max_m iterations (max_m = 0: hvp only). */
+ * and Lanczos runs of at most max_m iterations (max_m = 0: hvp only;
+ * max_m > 2000: HF_ESHAPE). */
 int32_t hf_create(const hf_model_desc* desc, int32_t hip_device,
                   int32_t max_batch, int32_t max_m, hf_ctx** out);
 void hf_destroy(hf_ctx* ctx);
@@ -171,9 +173,16 @@ int32_t hf_lanczos_init(hf_ctx* ctx, const float* q0_dev, int32_t reorth,
  * below 1/sqrt(2)]; beta_k = ||r||; q_{k+1} = r / beta_k unless beta_k < tol.
  * With full orthogonalisation the two subtractions are carried out by the
  * first Gram-Schmidt pass itself, applied to H q_k against q_0..q_k (alpha_k
- * is its k-th coefficient): the same r and alpha_k up to rounding.
+ * is its k-th coefficient): the same r and alpha_k up to rounding.  Without a
+ * basis r is never stored: alpha_k, <r', r'> and <q_k, q_k> (r' = H q_k -
+ * beta_{k-1} q_{k-1}) come from one read-only pass, beta_k^2 = <r', r'> -
+ * alpha_k^2 (2 - <q_k, q_k>) (formed explicitly when that difference loses its
+ * digits), and one pass writes q_{k+1} over q_{k-1}.
  * alpha_k / beta_k: host outputs.  Returns HF_EBREAKDOWN when beta_k < tol
- * (the iteration has ended), HF_ESHAPE after max_m iterations with a basis. */
+ * (the iteration has ended), HF_ESHAPE after max_m iterations with a basis.
+ * A token or label error (HF_EINVAL, as hf_hvp) leaves the iteration where it
+ * was: the same step can be repeated with valid inputs.  Synchronises the
+ * stream once, after all work of the iteration has been enqueued. */
 int32_t hf_lanczos_step(hf_ctx* ctx, const void* params_dev,
                         const void* inputs_dev, const int32_t* labels_dev,
                         int32_t batch, int32_t seq, double tol,
@@ -206,7 +215,7 @@ int32_t hf_slq(hf_ctx* ctx, const void* params_dev, const void* inputs_dev,
 /* The Lanczos vector update of one iteration (everything in hf_lanczos_step
  * after the Hessian-vector product) applied to the current state with the
  * caller-supplied r_dev[n] standing in for H q_k.  r_dev (fp32, 16-byte
- * aligned) is used as the working vector r and is overwritten.  Used by the
+ * aligned) is used as the working vector r and may be overwritten.  Used by the
  * benchmark to time the bandwidth-bound part alone, and by tests to drive
  * Algorithm 2 with a synthetic operator. */
 int32_t hf_lanczos_update(hf_ctx* ctx, float* r_dev, double tol,
@@ -222,10 +231,12 @@ int32_t hf_lanczos_update(hf_ctx* ctx, float* r_dev, double tol,
  * u_B of its own mean loss is accumulated as h += u_B |B| with |B| the number of
  * samples in the batch, and out_dev (device, fp32[n], 16-byte aligned, must not
  * alias an input) receives h / n_samples.  loss_host (host, may be NULL)
- * receives the same weighted mean of the batch losses.  Allocates one
- * n-float auxiliary device vector on first use (HF_ENOMEM if that fails); it is
- * owned by the context.  Synchronises the stream once per batch.  Errors as
- * hf_hvp. */
+ * receives the same weighted mean of the batch losses.  The weight |B| /
+ * n_samples multiplies the adjoint seeds of the batch (the backward sweep is
+ * linear in them) and every block of the batch's product is added to out_dev in
+ * place, so no second vector is needed.  Synchronises the stream once, after
+ * the last batch has been enqueued.  Errors as hf_hvp (a batch without a valid
+ * label, a bad token or label in any batch: HF_EINVAL). */
 int32_t hf_hvp_accumulate(hf_ctx* ctx, const void* params_dev, const void* inputs_dev,
                           const int32_t* labels_dev, int32_t n_samples, int32_t micro_batch,
                           int32_t seq, const float* v_dev, float* out_dev, double* loss_host,
@@ -280,7 +291,8 @@ int32_t hf_slq_moments(const double* ritz, const double* weights, const int32_t*
  * hf_lanczos_export: writes the image to state_dev (device, caller-owned,
  * 256-byte aligned, capacity_bytes >= hf_lanczos_state_bytes).
  * hf_lanczos_import: restores an image into a context of the same parameter
- * count, basis precision and max_m >= stored rows, replacing whatever iteration
+ * count, basis precision and max_m >= stored rows (max_m == stored rows if the
+ * image was exported after its basis had filled), replacing whatever iteration
  * it held; the next hf_lanczos_step continues at iteration k.  The image is
  * plain device memory (copy it to a file or another process as you like); it
  * is only meaningful to this library version.  Both synchronise the stream.

@@ -126,6 +126,8 @@ int32_t hf_create(const hf_model_desc* desc, int32_t hip_device, int32_t max_bat
   if (!desc || !out) { set_create_err("hf_create: NULL argument"); return HF_EINVAL; }
   *out = nullptr;
   if (max_batch <= 0 || max_m < 0) { set_create_err("hf_create: max_batch must be > 0 and max_m >= 0"); return HF_EINVAL; }
+  // the orthogonalisation kernels keep 32 bytes of LDS per basis vector, and hf_tridiag_readout stops at 2048
+  if (max_m > HF_MAX_M) { set_create_err("hf_create: max_m must be at most 2000"); return HF_ESHAPE; }
   hf_ctx* c = new (std::nothrow) hf_ctx();
   if (!c) { set_create_err("hf_create: out of host memory"); return HF_ENOMEM; }
   c->desc = *desc;
@@ -227,25 +229,34 @@ int32_t hf_lanczos_init(hf_ctx* ctx, const float* q0_dev, int32_t reorth, void* 
   if (reorth == HF_REORTH_FULL && !c->basis) return c->fail(HF_ESHAPE, "hf_lanczos_init: context was created without a basis (basis_dtype HF_NONE)");
   c->lz_k = -1;
   c->iq = 0; c->iqp = 1; c->ir = 2;
-  float* q = c->lz_vec[c->iq];
+  c->lz_reorth = reorth;
   const int bq = c->desc.basis_dtype == HF_BF16;
+  const bool rows = c->lz_rows_are_vectors();
 #define CKI(expr)                                                                                   \
   do {                                                                                              \
     hipError_t e_ = (expr);                                                                         \
     if (e_ != hipSuccess) return c->fail(HF_EDEVICE, std::string(#expr) + ": " + hipGetErrorString(e_)); \
   } while (0)
-  CKI(hipMemcpyAsync(q, q0_dev, (size_t)c->n * 4, hipMemcpyDeviceToDevice, st));
   CKI(launch_fill_f32((float*)c->scal, S_COUNT * 2, 0.f, st));
-  CKI(lz_norm_q0(q, c->n, c->scal, c->partials, st));
+  if ((uintptr_t)q0_dev & 15) {  // the kernels read 16 bytes at a time: stage an unaligned probe in r
+    CKI(hipMemcpyAsync(c->lz_vec[c->ir], q0_dev, (size_t)c->n * 4, hipMemcpyDeviceToDevice, st));
+    q0_dev = c->lz_vec[c->ir];
+  }
+  CKI(lz_norm_q0(q0_dev, c->n, c->scal, c->partials, st));
   CKI(hipMemcpyAsync(c->host_scal, c->scal, S_COUNT * sizeof(double), hipMemcpyDeviceToHost, st));
   CKI(hipStreamSynchronize(st));
   const double nrm = c->host_scal[S_Q0NORM];
   if (!(nrm > 0.0) || !std::isfinite(nrm)) return c->fail(HF_EINVAL, "hf_lanczos_init: q0 has zero or non-finite norm");
-  CKI(lz_scale(q, q, reorth == HF_REORTH_FULL ? c->basis : nullptr, bq, c->bf ? c->vb : nullptr, c->n, c->scal, S_Q0NORM, st));
-  c->vb_of = c->bf ? q : nullptr;
-  c->lz_reorth = reorth;
+  // q_0 = q0 / ||q0||: row 0 of an fp32 basis is the working vector itself; a bf16 basis takes the
+  // rounded copy, which is also the bf16 operand of the first product
+  void* row0 = reorth == HF_REORTH_FULL ? c->basis : nullptr;
+  bf16* vdst = c->bf ? ((bq && row0) ? nullptr : c->vb) : nullptr;
+  CKI(lz_scale(q0_dev, rows ? nullptr : c->lz_vec[c->iq], row0, bq, vdst, c->n, c->scal, S_Q0NORM, 0.0, nullptr, st));
   c->lz_k = 0;
   c->lz_done = 0;
+  c->lz_beta_prev = 0.0;
+  c->vb_cur = c->bf ? ((bq && row0) ? (const bf16*)row0 : c->vb) : nullptr;
+  c->vb_of = c->bf ? c->cur_q() : nullptr;
   return HF_OK;
 }
 
@@ -258,17 +269,10 @@ int32_t hf_lanczos_step(hf_ctx* ctx, const void* params_dev, const void* inputs_
   if (c->lz_done) return c->fail(HF_ESTATE, "hf_lanczos_step: the iteration has ended (breakdown)");
   if (c->lz_reorth == HF_REORTH_FULL && c->lz_k >= c->max_m) return c->fail(HF_ESHAPE, "hf_lanczos_step: max_m iterations reached");
   float* r = c->lz_vec[c->ir];
-  int rc = c->hvp_enqueue(params_dev, inputs_dev, labels_dev, batch, seq, c->lz_vec[c->iq], r, st);
+  int rc = c->hvp_enqueue(params_dev, inputs_dev, labels_dev, batch, seq, c->cur_q(), r, st);
   if (rc != HF_OK) return rc;
-  rc = c->lanczos_update(r, tol, alpha_k, beta_k, st);
-  if (rc < 0) return rc;
-  // the stream was synchronised inside lanczos_update: surface device-side input errors
-  int fl[2];
-  CKI(hipMemcpy(fl, c->flags, sizeof(fl), hipMemcpyDeviceToHost));
-  if (fl[0] & 1) return c->fail(HF_EINVAL, "token id outside [0, vocab)");
-  if (fl[0] & 2) return c->fail(HF_EINVAL, "label >= number of classes");
-  if (fl[1] == 0) return c->fail(HF_EINVAL, "no valid label in the batch");
-  return rc;
+  // a bad token or label (found on the device) leaves the iteration where it was
+  return c->lanczos_update(r, tol, alpha_k, beta_k, c->flags, st);
 }
 
 int32_t hf_lanczos_update(hf_ctx* ctx, float* r_dev, double tol, double* alpha_k, double* beta_k,
@@ -281,7 +285,7 @@ int32_t hf_lanczos_update(hf_ctx* ctx, float* r_dev, double tol, double* alpha_k
   if (c->lz_done) return c->fail(HF_ESTATE, "hf_lanczos_update: the iteration has ended (breakdown)");
   if (c->lz_reorth == HF_REORTH_FULL && c->lz_k >= c->max_m) return c->fail(HF_ESHAPE, "hf_lanczos_update: max_m iterations reached");
   if ((uintptr_t)r_dev & 15) return c->fail(HF_EINVAL, "hf_lanczos_update: r_dev must be 16-byte aligned");
-  return c->lanczos_update(r_dev, tol, alpha_k, beta_k, st);
+  return c->lanczos_update(r_dev, tol, alpha_k, beta_k, nullptr, st);
 }
 
 int32_t hf_lanczos_iterations(const hf_ctx* ctx) { return ctx ? ctx->lz_k : (int32_t)HF_EINVAL; }
@@ -293,8 +297,8 @@ int32_t hf_lanczos_get_vector(hf_ctx* ctx, int32_t which, float* dst_dev, void* 
   if (!dst_dev) return c->fail(HF_EINVAL, "hf_lanczos_get_vector: NULL dst_dev");
   if (c->lz_k < 0) return c->fail(HF_ESTATE, "hf_lanczos_get_vector: no iteration in progress");
   if (which >= 0 && which < 3) {
-    const int idx = which == 0 ? c->iq : (which == 1 ? c->iqp : c->ir);
-    CKI(hipMemcpyAsync(dst_dev, c->lz_vec[idx], (size_t)c->n * 4, hipMemcpyDeviceToDevice, st));
+    const float* src = which == 0 ? c->cur_q() : (which == 1 ? c->prev_q() : c->lz_vec[c->ir]);
+    CKI(hipMemcpyAsync(dst_dev, src, (size_t)c->n * 4, hipMemcpyDeviceToDevice, st));
     return HF_OK;
   }
   const int j = which - 16;
@@ -345,28 +349,20 @@ int32_t hf_hvp_accumulate(hf_ctx* ctx, const void* params_dev, const void* input
   if (micro_batch > c->max_batch) return c->fail(HF_ESHAPE, "hf_hvp_accumulate: micro_batch exceeds max_batch of hf_create");
   if (out_dev == v_dev || (const void*)out_dev == params_dev) return c->fail(HF_EINVAL, "hf_hvp_accumulate: out_dev aliases an input");
   if ((uintptr_t)out_dev & 15) return c->fail(HF_EINVAL, "hf_hvp_accumulate: out_dev must be 16-byte aligned");
-  int rc = c->ensure_aux();
-  if (rc != HF_OK) return rc;
   const bool mlp = c->desc.arch == HF_ARCH_MLP;
   const int64_t in_row = mlp ? (int64_t)c->desc.mlp_in * 4 : (int64_t)seq * 4;  // bytes per sample
   const int64_t lab_row = mlp ? 1 : seq;
-  double loss_acc = 0.0;
   for (int b0 = 0; b0 < n_samples; b0 += micro_batch) {
     const int b = std::min(micro_batch, n_samples - b0);
     // the direction is the same for every micro-batch: its bf16 copy is made by the first product only
     if (b0 > 0 && c->bf) c->vb_of = v_dev;
-    rc = c->hvp_enqueue(params_dev, (const char*)inputs_dev + b0 * in_row, labels_dev + b0 * lab_row, b, seq, v_dev, c->aux_vec, st);
+    // h += u_B |B| / N: the weight goes into the adjoint seeds and every block of the product is added
+    // to out_dev in place; the loss and the input checks accumulate on the device as well
+    const int rc = c->hvp_enqueue(params_dev, (const char*)inputs_dev + b0 * in_row, labels_dev + b0 * lab_row, b, seq, v_dev,
+                                  out_dev, st, (float)((double)b / (double)n_samples), b0 > 0);
     if (rc != HF_OK) return rc;
-    double loss_b = 0.0;
-    rc = c->finish_hvp(&loss_b, st);
-    if (rc != HF_OK) return rc;
-    // h += u_B |B| with the final division by N folded in
-    CKI(launch_scale_add(out_dev, c->aux_vec, (float)((double)b / (double)n_samples), b0 == 0, c->n, st));
-    loss_acc += loss_b * b;
   }
-  CKI(hipStreamSynchronize(st));
-  if (loss_host) *loss_host = loss_acc / n_samples;
-  return HF_OK;
+  return c->finish_hvp(loss_host, st);
 }
 
 int32_t hf_hessian_column(hf_ctx* ctx, const void* params_dev, const void* inputs_dev, const int32_t* labels_dev,
@@ -387,17 +383,23 @@ int32_t hf_hessian_column(hf_ctx* ctx, const void* params_dev, const void* input
   return c->finish_hvp(loss_host, st);
 }
 
-int32_t hf_column_stats(hf_ctx* ctx, const float* h_dev, int64_t n, const float* thresholds, int32_t n_thresholds,
-                        int32_t n_bins, int64_t* below, float* max_abs, int64_t* hist, void* hip_stream) {
-  if (!ctx) return HF_EINVAL;
-  hf_ctx* c = ctx;
-  hipStream_t st = (hipStream_t)hip_stream;
-  if (n < 0 || (n > 0 && !h_dev)) return c->fail(HF_EINVAL, "hf_column_stats: bad h_dev / n");
-  if ((uintptr_t)h_dev & 3) return c->fail(HF_EINVAL, "hf_column_stats: h_dev must be 4-byte aligned");
-  if (n_thresholds < 0 || n_thresholds > CS_MAX_THRESHOLDS) return c->fail(HF_EINVAL, "hf_column_stats: at most 16 thresholds");
-  if (n_bins < 1 || n_bins > CS_MAX_BINS) return c->fail(HF_EINVAL, "hf_column_stats: n_bins must be in [1, 256]");
-  if ((n_thresholds > 0 && (!thresholds || !below)) || !hist || !max_abs) return c->fail(HF_EINVAL, "hf_column_stats: NULL argument");
-  if (n >= ((int64_t)1 << 40)) return c->fail(HF_ESHAPE, "hf_column_stats: n must be below 2^40");
+// Both column-statistics entry points: `stats` is CS_STATS_WORDS device counters (the context's, or
+// the library's static array); on failure *why names the reason.
+static int column_stats_run(unsigned long long* stats, const float* h_dev, int64_t n, const float* thresholds,
+                            int32_t n_thresholds, int32_t n_bins, int64_t* below, float* max_abs, int64_t* hist,
+                            hipStream_t st, std::string* why) {
+  auto bad = [&](int code, const std::string& m) { *why = m; return code; };
+#define CKS(expr)                                                                                 \
+  do {                                                                                            \
+    hipError_t e_ = (expr);                                                                       \
+    if (e_ != hipSuccess) return bad(HF_EDEVICE, std::string(#expr) + ": " + hipGetErrorString(e_)); \
+  } while (0)
+  if (n < 0 || (n > 0 && !h_dev)) return bad(HF_EINVAL, "bad h_dev / n");
+  if ((uintptr_t)h_dev & 3) return bad(HF_EINVAL, "h_dev must be 4-byte aligned");
+  if (n_thresholds < 0 || n_thresholds > CS_MAX_THRESHOLDS) return bad(HF_EINVAL, "at most 16 thresholds");
+  if (n_bins < 1 || n_bins > CS_MAX_BINS) return bad(HF_EINVAL, "n_bins must be in [1, 256]");
+  if ((n_thresholds > 0 && (!thresholds || !below)) || !hist || !max_abs) return bad(HF_EINVAL, "NULL argument");
+  if (n >= ((int64_t)1 << 40)) return bad(HF_ESHAPE, "n must be below 2^40");
   // sorted copy of the thresholds (padded with +inf), and where each caller threshold went
   ColThresholds thr;
   int order[CS_MAX_THRESHOLDS];
@@ -405,12 +407,14 @@ int32_t hf_column_stats(hf_ctx* ctx, const float* h_dev, int64_t n, const float*
   std::stable_sort(order, order + n_thresholds, [&](int a, int b) { return thresholds[a] < thresholds[b]; });
   for (int k = 0; k < CS_MAX_THRESHOLDS; ++k) thr.t[k] = k < n_thresholds ? thresholds[order[k]] : INFINITY;
   for (int k = 0; k < n_thresholds; ++k)
-    if (thresholds[k] != thresholds[k]) return c->fail(HF_EINVAL, "hf_column_stats: a threshold is NaN");
+    if (thresholds[k] != thresholds[k]) return bad(HF_EINVAL, "a threshold is NaN");
   unsigned long long hs[CS_STATS_WORDS];
-  CKI(launch_fill_f32((float*)c->stats_dev, CS_STATS_WORDS * 2, 0.f, st));
-  if (n > 0) CKI(launch_colstats_pass1(h_dev, n, thr, n_thresholds, c->stats_dev, st));
-  CKI(hipMemcpyAsync(hs, c->stats_dev, 32 * 8, hipMemcpyDeviceToHost, st));
-  CKI(hipStreamSynchronize(st));
+  // the counters keep the previous call's values: cleared by a fill kernel, not by a memset, so that
+  // the sequence stays valid under stream capture
+  CKS(launch_fill_f32((float*)stats, CS_STATS_WORDS * 2, 0.f, st));
+  if (n > 0) CKS(launch_colstats_pass1(h_dev, n, thr, n_thresholds, stats, st));
+  CKS(hipMemcpyAsync(hs, stats, 32 * 8, hipMemcpyDeviceToHost, st));
+  CKS(hipStreamSynchronize(st));
   // |h_i| < t_k (sorted) exactly when the entry reaches at most k thresholds: prefix sums of the buckets
   unsigned long long run = 0, valid = 0;
   for (int k = 0; k <= CS_MAX_THRESHOLDS; ++k) valid += hs[k];
@@ -429,11 +433,21 @@ int32_t hf_column_stats(hf_ctx* ctx, const float* h_dev, int64_t n, const float*
   }
   const volatile float nbf = (float)n_bins;
   const volatile float scale = nbf / mx;  // one float32 division, as the definition states
-  CKI(launch_colstats_hist(h_dev, n, scale, n_bins, c->stats_dev + 32, st));
-  CKI(hipMemcpyAsync(hs + 32, c->stats_dev + 32, (size_t)n_bins * 8, hipMemcpyDeviceToHost, st));
-  CKI(hipStreamSynchronize(st));
+  CKS(launch_colstats_hist(h_dev, n, scale, n_bins, stats + 32, st));
+  CKS(hipMemcpyAsync(hs + 32, stats + 32, (size_t)n_bins * 8, hipMemcpyDeviceToHost, st));
+  CKS(hipStreamSynchronize(st));
   for (int k = 0; k < n_bins; ++k) hist[k] = (int64_t)hs[32 + k];
   return HF_OK;
+#undef CKS
+}
+
+int32_t hf_column_stats(hf_ctx* ctx, const float* h_dev, int64_t n, const float* thresholds, int32_t n_thresholds,
+                        int32_t n_bins, int64_t* below, float* max_abs, int64_t* hist, void* hip_stream) {
+  if (!ctx) return HF_EINVAL;
+  std::string why;
+  const int rc = column_stats_run(ctx->stats_dev, h_dev, n, thresholds, n_thresholds, n_bins, below, max_abs, hist,
+                                  (hipStream_t)hip_stream, &why);
+  return rc == HF_OK ? rc : ctx->fail(rc, "hf_column_stats: " + why);
 }
 
 int32_t hf_slq_density(const double* ritz, const double* weights, const int32_t* m_eff, int32_t n_probes, int32_t m,
@@ -506,14 +520,13 @@ int32_t hf_lanczos_export(hf_ctx* ctx, void* state_dev, int64_t capacity_bytes, 
   if (capacity_bytes < need) return c->fail(HF_ESHAPE, "hf_lanczos_export: buffer too small (see hf_lanczos_state_bytes)");
   LzHeader h{};
   h.magic = kLzMagic; h.version = 1; h.n = c->n; h.k = c->lz_k; h.reorth = c->lz_reorth;
-  h.basis_dtype = c->desc.basis_dtype; h.done = c->lz_done; h.rows = rows; h.beta_prev = 0.0;
+  h.basis_dtype = c->desc.basis_dtype; h.done = c->lz_done; h.rows = rows; h.beta_prev = c->lz_beta_prev;
   char* base = (char*)state_dev;
   CKI(hipMemcpyAsync(base, &h, sizeof(h), hipMemcpyHostToDevice, st));
   CKI(hipStreamSynchronize(st));  // h lives on this stack frame
-  CKI(hipMemcpyAsync(base + offsetof(LzHeader, beta_prev), c->scal + S_BETA_PREV, sizeof(double), hipMemcpyDeviceToDevice, st));
   const int64_t vb = lz_align(c->n * 4);
-  CKI(hipMemcpyAsync(base + 128, c->lz_vec[c->iq], (size_t)c->n * 4, hipMemcpyDeviceToDevice, st));
-  CKI(hipMemcpyAsync(base + 128 + vb, c->lz_vec[c->iqp], (size_t)c->n * 4, hipMemcpyDeviceToDevice, st));
+  CKI(hipMemcpyAsync(base + 128, c->cur_q(), (size_t)c->n * 4, hipMemcpyDeviceToDevice, st));
+  CKI(hipMemcpyAsync(base + 128 + vb, c->prev_q(), (size_t)c->n * 4, hipMemcpyDeviceToDevice, st));
   const int64_t be = c->desc.basis_dtype == HF_BF16 ? 2 : 4;
   if (rows > 0)
     CKI(hipMemcpy2DAsync(base + 128 + 2 * vb, (size_t)c->n * be, c->basis, (size_t)c->ldq * be, (size_t)c->n * be, (size_t)rows,
@@ -537,7 +550,10 @@ int32_t hf_lanczos_import(hf_ctx* ctx, const void* state_dev, int64_t bytes, voi
   if (h.reorth == HF_REORTH_FULL) {
     if (!c->basis) return c->fail(HF_ESHAPE, "hf_lanczos_import: the image holds a basis, the context was created without one");
     if (h.basis_dtype != c->desc.basis_dtype) return c->fail(HF_ESHAPE, "hf_lanczos_import: basis precision differs from the context's");
-    if (h.rows > c->max_m || h.rows != std::min<int64_t>(h.k + 1, h.rows)) return c->fail(HF_ESHAPE, "hf_lanczos_import: more basis rows than max_m of hf_create");
+    if (h.rows > c->max_m) return c->fail(HF_ESHAPE, "hf_lanczos_import: more basis rows than max_m of hf_create");
+    // rows = k + 1, or k once the exporter's basis was full; such an image continues nowhere, and a
+    // context with room for more rows would orthogonalise against a row k that was never stored
+    if (h.rows != std::min<int64_t>(h.k + 1, c->max_m)) return c->fail(HF_ESHAPE, "hf_lanczos_import: the image was exported with its basis full; max_m of this context must equal its number of rows");
   } else if (h.rows != 0) {
     return c->fail(HF_EINVAL, "hf_lanczos_import: corrupt header");
   }
@@ -546,7 +562,8 @@ int32_t hf_lanczos_import(hf_ctx* ctx, const void* state_dev, int64_t bytes, voi
   const int64_t vb = lz_align(c->n * 4);
   c->iq = 0; c->iqp = 1; c->ir = 2;
   CKI(launch_fill_f32((float*)c->scal, S_COUNT * 2, 0.f, st));
-  CKI(hipMemcpyAsync(c->scal + S_BETA_PREV, base + offsetof(LzHeader, beta_prev), sizeof(double), hipMemcpyDeviceToDevice, st));
+  // (with an fp32 basis q_k and q_{k-1} are also rows k and k - 1 below, which is where the
+  // iteration reads them; the copies in lz_vec serve a full basis, whose last q has no row)
   CKI(hipMemcpyAsync(c->lz_vec[0], base + 128, (size_t)c->n * 4, hipMemcpyDeviceToDevice, st));
   c->vb_of = nullptr;  // the imported q_k has no bf16 copy yet
   CKI(hipMemcpyAsync(c->lz_vec[1], base + 128 + vb, (size_t)c->n * 4, hipMemcpyDeviceToDevice, st));
@@ -558,6 +575,7 @@ int32_t hf_lanczos_import(hf_ctx* ctx, const void* state_dev, int64_t bytes, voi
   c->lz_k = (int)h.k;
   c->lz_reorth = (int)h.reorth;
   c->lz_done = (int)h.done;
+  c->lz_beta_prev = h.beta_prev;
   return HF_OK;
 }
 

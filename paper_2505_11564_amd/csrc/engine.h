@@ -56,7 +56,9 @@ struct hf_ctx {
   int64_t arena_bytes = 0;
   std::vector<hf::LayerBuf> lb;
   hf::bf16* vb = nullptr;  // bf16 copy of the direction (bf16 mode)
-  const float* vb_of = nullptr;  // the Lanczos vector whose bf16 copy vb currently holds (written by the update), or nullptr
+  const float* vb_of = nullptr;  // the Lanczos vector whose bf16 copy vb_cur holds (written by the update), or nullptr
+  const hf::bf16* vb_cur = nullptr;   // the bf16 copy the running product multiplies with: vb, or a row of a bf16 basis
+  const hf::bf16* next_vb = nullptr;  // scratch of lanczos_update
   float *xL = nullptr, *xL_t = nullptr, *stf = nullptr;
   void *xf = nullptr, *xf_t = nullptr, *xf_lo = nullptr;
   // bf16 mode: low-order halves of the primal forward activations (reused by every layer)
@@ -87,7 +89,10 @@ struct hf_ctx {
   int ensure_aux();
 
   // Lanczos state
-  float* lz_vec[3] = {nullptr, nullptr, nullptr};  // rotating q, q_prev, r
+  // Working vectors.  With an fp32 basis and full orthogonalisation the basis rows k and k - 1 are
+  // q_k and q_{k-1} themselves (cur_q / prev_q) and lz_vec holds only r and, once the basis is
+  // full, the last q; otherwise lz_vec rotates q, q_prev and r.
+  float* lz_vec[3] = {nullptr, nullptr, nullptr};
   int iq = 0, iqp = 1, ir = 2;
   void* basis = nullptr;
   int64_t ldq = 0;
@@ -96,15 +101,24 @@ struct hf_ctx {
   int lz_k = -1;                // iterations done; -1 = not initialised
   int lz_reorth = 0;
   int lz_done = 0;
+  double lz_beta_prev = 0.0;    // beta_{k-1}
+  bool lz_rows_are_vectors() const { return lz_reorth == HF_REORTH_FULL && desc.basis_dtype == HF_F32; }
+  float* cur_q() const;         // q_k
+  float* prev_q() const;        // q_{k-1} (meaningful for k >= 1)
 
   int fail(int code, const std::string& m) { err = m; return code; }
   int plan_and_alloc();
+  // out = seed_scale * H v, or out += seed_scale * H v when accumulate (the batch loop of Algorithm 1:
+  // the weight of a batch multiplies the adjoint seeds, in which the backward sweep is linear)
   int hvp_enqueue(const void* params, const void* inputs, const int32_t* labels, int batch, int seq, const float* v,
-                  float* out, hipStream_t st);
+                  float* out, hipStream_t st, float seed_scale = 1.f, int accumulate = 0);
+  int acc_mode = 0;   // the product being enqueued adds to out
+  float seed = 1.f;   // and scales its adjoint seeds by this
   int hvp_mlp(const void* params, const void* inputs, const int32_t* labels, int B, const float* v, float* out,
               hipStream_t st);
   int hvp_transformer(const void* params, const int32_t* tok, const int32_t* labels, int B, int S, const float* v,
                       float* out, hipStream_t st);
   int finish_hvp(double* loss_host, hipStream_t st);
-  int lanczos_update(float* r, double tol, double* alpha_k, double* beta_k, hipStream_t st);
+  // hvp_flags: the device flags of the product that made r (NULL when r came from the caller)
+  int lanczos_update(float* r, double tol, double* alpha_k, double* beta_k, const int* hvp_flags, hipStream_t st);
 };

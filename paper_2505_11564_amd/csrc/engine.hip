@@ -173,7 +173,7 @@ int hf_ctx::plan_and_alloc() {
     if (desc.basis_dtype != HF_NONE) pl.add(basis, (int64_t)max_m * ldq * (desc.basis_dtype == HF_BF16 ? 2 : 4));
     pl.add(scal, S_COUNT * 8);
     pl.add(cvec, (int64_t)(max_m + 1) * 8);
-    pl.add(partials, std::max<int64_t>((int64_t)LZ_NBLK * (max_m + 1), LZ_NBLK_VEC) * 8);
+    pl.add(partials, std::max<int64_t>((int64_t)LZ_NBLK * (max_m + 1), 3 * LZ_NBLK_VEC) * 8);
   }
   arena_bytes = pl.off;
   hipError_t e1 = hipMalloc((void**)&arena, (size_t)arena_bytes);
@@ -209,7 +209,7 @@ struct Lin {
   hipStream_t st;
   int bf;
   const void* Wp(int64_t off) const { return (const char*)params + off * (bf ? 2 : 4); }
-  const void* Wt(int64_t off) const { return bf ? (const void*)(c->vb + off) : (const void*)(v + off); }
+  const void* Wt(int64_t off) const { return bf ? (const void*)(c->vb_cur + off) : (const void*)(v + off); }
 
   // Y = X W (+ b) (+ add);  Y_t = X_t W + X W_t (+ b_t) (+ add_t).   W: [K, N] at woff.
   // X_t == nullptr means a zero input tangent.
@@ -279,6 +279,7 @@ struct Lin {
     g.allow_splitk = 1;
     g.c_zeroed = c->dw_prezeroed && woff >= c->layers_begin && woff < c->layers_end;
     g.C = out + woff;
+    if (c->acc_mode) g.Cadd = out + woff;
     if (X_t) { g.A[0] = X_t; g.B[0] = dY; g.A[1] = X; g.B[1] = dY_t; }
     else { g.A[0] = X; g.B[0] = dY_t; }
     CK(launch_gemm(g, st));
@@ -292,19 +293,24 @@ struct Lin {
 // ------------------------------------------------------------------- common ----
 
 int hf_ctx::hvp_enqueue(const void* params, const void* inputs, const int32_t* labels, int batch, int seq,
-                        const float* v, float* out, hipStream_t st) {
+                        const float* v, float* out, hipStream_t st, float seed_scale, int accumulate) {
   hf_ctx* c = this;
   if (!params || !inputs || !labels || !v || !out) return fail(HF_EINVAL, "hf_hvp: NULL pointer argument");
   if (((uintptr_t)v | (uintptr_t)out | (uintptr_t)params) & 15) return fail(HF_EINVAL, "hf_hvp: params, v and out must be 16-byte aligned");
   if (batch <= 0 || batch > max_batch) return fail(HF_ESHAPE, "hf_hvp: batch outside [1, max_batch]");
   if (desc.arch != HF_ARCH_MLP && (seq <= 0 || seq > desc.max_seq)) return fail(HF_ESHAPE, "hf_hvp: seq outside [1, max_seq]");
   if (desc.arch != HF_ARCH_MLP && (int64_t)batch * seq > (int64_t)max_batch * desc.max_seq) return fail(HF_ESHAPE, "hf_hvp: too many tokens");
-  CK(launch_fill_f32((float*)flags, 2, 0.f, st));
+  // accumulate: out += seed_scale * H v (every block of H v is written through Cadd = C or added with
+  // atomics, so nothing is cleared); the error bits stay, the count of valid labels starts over
+  acc_mode = accumulate;
+  seed = seed_scale;
+  if (accumulate) CK(launch_fill_f32((float*)(flags + 1), 1, 0.f, st));
+  else CK(launch_fill_f32((float*)flags, 2, 0.f, st));
   // Small models: every weight-gradient product of a layer splits k and adds into a cleared
   // result, and the vectors between them are accumulated with atomics as well.  One pass over the
   // layers' whole range then replaces a fill per matrix and per group of vectors.
   dw_prezeroed = 0;
-  if (bf && desc.arch != HF_ARCH_MLP && layers_end > layers_begin) {
+  if (!accumulate && bf && desc.arch != HF_ARCH_MLP && layers_end > layers_begin) {
     const int T = batch * seq, D = desc.d_model, F = desc.d_ff;
     const int hkv = desc.n_kv_head > 0 ? desc.n_kv_head : desc.n_head, Dkv = D / desc.n_head * hkv;
     bool all = gemm_mfma_splits_k(D, D, T, 2) && gemm_mfma_splits_k(D, F, T, 2) && gemm_mfma_splits_k(F, D, T, 2);
@@ -315,12 +321,15 @@ int hf_ctx::hvp_enqueue(const void* params, const void* inputs, const int32_t* l
       dw_prezeroed = 1;
     }
   }
-  for (auto& zr : zero_ranges) {
+  if (!accumulate) for (auto& zr : zero_ranges) {
     if (dw_prezeroed && zr.first >= layers_begin && zr.first + zr.second <= layers_end) continue;
     CK(launch_fill_f32(out + zr.first, zr.second, 0.f, st));
   }
   // The Lanczos update leaves the bf16 copy of q_{k+1} in vb; every other direction is converted here.
-  if (bf && !(vb_of != nullptr && vb_of == v)) CK(launch_f32_to_bf16(v, vb, n, st));
+  if (bf && !(vb_of != nullptr && vb_of == v)) {
+    CK(launch_f32_to_bf16(v, vb, n, st));
+    vb_cur = vb;
+  }
   vb_of = nullptr;
   if (desc.arch == HF_ARCH_MLP) return hvp_mlp(params, inputs, labels, batch, v, out, st);
   return hvp_transformer(params, (const int32_t*)inputs, labels, batch, seq, v, out, st);
@@ -345,7 +354,7 @@ int hf_ctx::finish_hvp(double* loss_host, hipStream_t st) {
   CK(hipStreamSynchronize(st));
   if (h.flags[0] & 1) return fail(HF_EINVAL, "token id outside [0, vocab)");
   if (h.flags[0] & 2) return fail(HF_EINVAL, "label >= number of classes");
-  if (h.flags[1] == 0) return fail(HF_EINVAL, "no valid label in the batch");
+  if (h.flags[1] == 0 || (h.flags[0] & 4)) return fail(HF_EINVAL, "no valid label in the batch");
   if (loss_host) *loss_host = h.loss;
   return HF_OK;
 }
@@ -365,8 +374,8 @@ int hf_ctx::hvp_mlp(const void* params, const void* inputs, const int32_t* label
   CK(launch_act_fwd(bf, ACT_TANH, b.f, b.f_t, nullptr, b.g, b.g_t, nullptr, (int64_t)B * Hd, st));
   if ((rc = L.fwd(b.g, b.g_t, B, Hd, O, Hd, off_w2, off_b2, z, z_t, ldz, 0))) return rc;
   CK(launch_count_valid(labels, B, O, flags + 1, flags, st));
-  CK(launch_ce(bf, z, z_t, labels, flags + 1, B, O, ldz, dz, dz_t, loss_rows, st));
-  CK(launch_sum_rows_f64(loss_rows, B, flags + 1, loss_dev, st));
+  CK(launch_ce(bf, z, z_t, labels, flags + 1, B, O, ldz, dz, dz_t, loss_rows, seed, st));
+  CK(launch_sum_rows_f64(loss_rows, B, flags + 1, loss_dev, (double)seed, acc_mode, flags, st));
   if ((rc = L.bwd_dw(b.g, b.g_t, dz, dz_t, B, Hd, O, Hd, ldz, off_w2, off_b2, dz_t, bf))) return rc;
   if ((rc = L.bwd_dx(dz, dz_t, B, Hd, O, ldz, off_w2, dg, dg_t, Hd, bf))) return rc;
   CK(launch_act_bwd(bf, ACT_TANH, b.f, b.f_t, dg, dg_t, dg, dg_t, (int64_t)B * Hd, st));
@@ -420,6 +429,9 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
     CK(launch_fill_f32((float*)dS_t, words, 0.f, st));
     att_zero_B = B; att_zero_S = S;
   }
+  // The unfused path writes whole score matrices in its own [B,H,S,S] layout, so the tiles the
+  // fused kernels rely on being zero must be cleared again before their next use.
+  if (bf && !fused_att) att_zero_B = att_zero_S = -1;
 
   // ------------------------------ forward with tangents ----------------------
   CK(launch_embed_fwd(bf, L.Wp(off_wte), llama ? nullptr : L.Wp(off_wpe), v + off_wte, llama ? nullptr : v + off_wpe,
@@ -512,8 +524,8 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
 
   // ------------------------------ loss and adjoint seeds ----------------------
   CK(launch_count_valid(labels, T, V, flags + 1, flags, st));
-  CK(launch_ce(bf, z, z_t, labels, flags + 1, T, V, ldz, dz, dz_t, loss_rows, st));
-  CK(launch_sum_rows_f64(loss_rows, T, flags + 1, loss_dev, st));
+  CK(launch_ce(bf, z, z_t, labels, flags + 1, T, V, ldz, dz, dz_t, loss_rows, seed, st));
+  CK(launch_sum_rows_f64(loss_rows, T, flags + 1, loss_dev, (double)seed, acc_mode, flags, st));
 
   // ------------------------------ backward with tangents ----------------------
   if (tied) {
@@ -521,6 +533,7 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
     Gemm g;
     g.M = V; g.N = D; g.K = T; g.lda = ldz; g.ldb = D; g.ldc = D; g.transA = 1; g.in_bf16 = bf;
     g.A[0] = dz_t; g.B[0] = xf; g.A[1] = dz; g.B[1] = xf_t; g.C = out + off_wte;
+    if (acc_mode) g.Cadd = out + off_wte;
     CK(launch_gemm(g, st));
     if ((rc = L.bwd_dx(dz, dz_t, T, D, V, ldz, off_wte, tmpd, tmpd_t, D, 0, nullptr, nullptr, 1, D))) return rc;
   } else {
@@ -671,12 +684,24 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
 
 // ------------------------------------------------------------------ Lanczos ----
 
-int hf_ctx::lanczos_update(float* r, double tol, double* alpha_k, double* beta_k, hipStream_t st) {
+float* hf_ctx::cur_q() const {
+  if (lz_rows_are_vectors() && lz_k < max_m) return (float*)basis + (int64_t)lz_k * ldq;
+  return lz_vec[iq];
+}
+
+float* hf_ctx::prev_q() const {
+  if (lz_rows_are_vectors() && lz_k >= 1) return (float*)basis + (int64_t)(lz_k - 1) * ldq;
+  return lz_vec[iqp];
+}
+
+int hf_ctx::lanczos_update(float* r, double tol, double* alpha_k, double* beta_k, const int* hvp_flags, hipStream_t st) {
   hf_ctx* c = this;
   const int k = lz_k;
   const int bq = desc.basis_dtype == HF_BF16;
-  float* q = lz_vec[iq];
-  float* qp = lz_vec[iqp];
+  const bool rows = lz_rows_are_vectors();
+  float* q = cur_q();
+  float* qp = prev_q();
+  float* spill = nullptr;  // fp32 destination of q_{k+1} outside the basis
   if (lz_reorth == HF_REORTH_FULL) {
     // Gram-Schmidt of H q_k against q_0 .. q_k is the three-term subtraction and the
     // orthogonalisation in one.  An fp32 basis holds q_k and q_{k-1} as its rows k and k - 1; a
@@ -684,26 +709,38 @@ int hf_ctx::lanczos_update(float* r, double tol, double* alpha_k, double* beta_k
     if (!bq) CK(lz_gs_first_pass((const float*)basis, ldq, r, n, k + 1, scal, cvec, partials, st));
     else CK(lz_gs_first_pass_bf16((const bf16*)basis, ldq, qp, q, r, n, k, scal, cvec, partials, st));
     CK(lz_reorth_pass(basis, bq, ldq, r, n, k + 1, 1, scal, cvec, partials, st));
+    // q_{k+1} = r / beta_k: an fp32 basis takes it as row k + 1 and nowhere else (the rows are the
+    // working vectors); a bf16 basis takes the rounded copy, which is also the operand-type copy
+    // the next product multiplies with, and the fp32 vector goes over q_{k-1}.
+    void* row = k + 1 < max_m ? (char*)basis + (int64_t)(k + 1) * ldq * (bq ? 2 : 4) : nullptr;
+    spill = rows ? (row ? nullptr : lz_vec[iq]) : qp;
+    bf16* vdst = nullptr;
+    if (bf) vdst = (bq && row) ? nullptr : vb;
+    CK(lz_scale(r, spill, row, bq, vdst, n, scal, S_BETA, tol, hvp_flags, st));
+    next_vb = bf ? ((bq && row) ? (const bf16*)row : vb) : nullptr;
   } else {
-    CK(lz_axpy_dot(r, q, qp, n, k > 0, scal, partials, st));
-    CK(lz_axpy_nrm(r, q, n, scal, partials, st));
+    CK(lz3_update(r, q, qp, bf ? vb : nullptr, n, k > 0, lz_beta_prev, tol, hvp_flags, scal, partials, st));
+    next_vb = bf ? vb : nullptr;
   }
   CK(hipMemcpyAsync(host_scal, scal, S_COUNT * sizeof(double), hipMemcpyDeviceToHost, st));
   CK(hipStreamSynchronize(st));
+  if (hvp_flags) {  // the product's input checks; q_{k+1} was not written if any failed
+    const int f0 = (int)host_scal[S_FLAG0], f1 = (int)host_scal[S_FLAG1];
+    if (f0 & 1) return fail(HF_EINVAL, "token id outside [0, vocab)");
+    if (f0 & 2) return fail(HF_EINVAL, "label >= number of classes");
+    if (f1 == 0) return fail(HF_EINVAL, "no valid label in the batch");
+  }
   const double a = host_scal[S_ALPHA], bt = host_scal[S_BETA];
   if (alpha_k) *alpha_k = a;
   if (beta_k) *beta_k = bt;
   lz_k = k + 1;
-  if (!(bt >= tol) || !(bt > 0.0)) {  // also catches NaN
+  if (!(bt >= tol) || !(bt > 0.0)) {  // also catches NaN; the kernels made the same test
     lz_done = 1;
     return HF_EBREAKDOWN;
   }
-  // q_{k+1} = r / beta_k into the q_{k-1} buffer, then rotate; beta_prev <- beta
-  void* bdst = nullptr;
-  if (lz_reorth == HF_REORTH_FULL && lz_k < max_m) bdst = (char*)basis + (int64_t)lz_k * ldq * (bq ? 2 : 4);
-  CK(lz_scale(r, qp, bdst, bq, bf ? vb : nullptr, n, scal, S_BETA, st));
-  vb_of = bf ? qp : nullptr;
-  CK(hipMemcpyAsync(scal + S_BETA_PREV, scal + S_BETA, sizeof(double), hipMemcpyDeviceToDevice, st));
-  std::swap(iq, iqp);
+  lz_beta_prev = bt;
+  if (!rows) std::swap(iq, iqp);  // q_{k+1} went over q_{k-1}
+  vb_of = next_vb ? cur_q() : nullptr;
+  vb_cur = next_vb;
   return HF_OK;
 }

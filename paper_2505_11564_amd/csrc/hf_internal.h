@@ -177,11 +177,14 @@ hipError_t launch_rope(int bf, const float* src, const float* src_t, int64_t lds
 
 // Softmax cross-entropy with tangent: dz, dz_t (operand type) from z, z_t
 // (fp32, leading dimension ldz); loss_rows[T] = per-row loss (0 if ignored);
-// n_valid: device int.  err_flag set if a label >= V.
+// n_valid: device int.  err_flag: bit 1 set if a label >= V.  `scale` multiplies dz and dz_t (the
+// weight |B| / N of a batch in the batch loop of Algorithm 1; the backward sweep is linear in them).
 hipError_t launch_count_valid(const int32_t* labels, int T, int V, int* n_valid, int* err_flag, hipStream_t st);
 hipError_t launch_ce(int bf, const float* z, const float* z_t, const int32_t* labels, const int* n_valid, int T, int V,
-                     int64_t ldz, void* dz, void* dz_t, float* loss_rows, hipStream_t st);
-hipError_t launch_sum_rows_f64(const float* v, int n, const int* n_valid, double* out, hipStream_t st);
+                     int64_t ldz, void* dz, void* dz_t, float* loss_rows, float scale, hipStream_t st);
+// out[0] (+)= weight * sum(v) / n_valid; bit 2 of err_flag set when n_valid is 0.
+hipError_t launch_sum_rows_f64(const float* v, int n, const int* n_valid, double* out, double weight, int accumulate,
+                               int* err_flag, hipStream_t st);
 
 // hv_b[c] = sum_rows y_t[r, c]   (y_t operand type or fp32)
 hipError_t launch_colsum(int is_bf16, const void* y, int T, int N, int64_t ld, float* out, hipStream_t st);

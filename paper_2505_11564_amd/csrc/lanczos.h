@@ -9,22 +9,29 @@ namespace hf {
 enum {
   S_ALPHA = 0,       // alpha_k
   S_BETA = 1,        // current ||r|| (beta_k once the iteration's updates are done)
-  S_BETA_PREV = 2,   // beta_{k-1}
   S_NRM_BEFORE = 3,  // ||r|| before the orthogonalisation pass in flight
   S_REDO = 4,        // 1.0 when a second orthogonalisation pass is required
   S_Q0NORM = 5,      // ||q0|| before normalisation
+  S_FLAG0 = 6,       // error bits and number of valid labels of the Hessian-vector product that made
+  S_FLAG1 = 7,       //   w, copied here by the kernel that writes q_{k+1}
   S_COUNT = 8
 };
 
+constexpr int HF_MAX_M = 2000;  // most basis vectors a context may hold
 constexpr int LZ_NBLK = 2048;  // upper bound on blocks (= partial sums per basis vector) of the re-orthogonalisation kernels
 constexpr int LZ_NBLK_VEC = 4096;  // upper bound on blocks (= partial sums) of the three-term kernels
 
 hipError_t lz_norm_q0(const float* z, int64_t n, double* scal, double* partials, hipStream_t st);
-hipError_t lz_axpy_dot(float* r, const float* q, const float* qp, int64_t n, int use_prev, double* scal,
-                       double* partials, hipStream_t st);
-hipError_t lz_axpy_nrm(float* r, const float* q, int64_t n, double* scal, double* partials, hipStream_t st);
-hipError_t lz_scale(const float* src, float* dst, void* basis, int basis_bf16, bf16* vb, int64_t n, const double* scal, int idx,
-                    hipStream_t st);
+// Iteration k of the three-term recurrence without a basis: alpha_k, beta_k into scal, and
+// q_{k+1} = (w - beta_prev qp - alpha_k q) / beta_k written over qp (with its bf16 copy in vb, may be
+// NULL) unless beta_k < tol or `flags` (device, may be NULL: [0] error bits, [1] valid labels)
+// report a failed product.  partials: 3 * LZ_NBLK_VEC doubles.
+hipError_t lz3_update(const float* w, const float* q, float* qp, bf16* vb, int64_t n, int use_prev, double beta_prev,
+                      double tol, const int* flags, double* scal, double* partials, hipStream_t st);
+// q_{k+1} = src / scal[idx] into dst (fp32, may be NULL), its basis row (may be NULL) and vb (bf16,
+// may be NULL), under the same test.
+hipError_t lz_scale(const float* src, float* dst, void* basis, int basis_bf16, bf16* vb, int64_t n, double* scal, int idx,
+                    double tol, const int* flags, hipStream_t st);
 // One classical Gram-Schmidt pass of r against Q[0..nq); pass 1 is a no-op
 // unless pass 0 set the redo flag.
 hipError_t lz_reorth_pass(const void* Q, int basis_bf16, int64_t ldq, float* r, int64_t n, int nq, int pass,

@@ -2,19 +2,27 @@
 // paper) and of the full orthogonalisation against a stored basis Q that
 // Section "Memory Compute trade off" uses as its baseline.
 //
-// Per iteration, with r = H q_k already computed:
-//   lz_axpy_dot : r -= beta_{k-1} q_{k-1};  alpha_k = <q_k, r>        (3R + 1W)
-//   lz_axpy_nrm : r -= alpha_k q_k;         beta_k  = ||r||           (2R + 1W)
+// Per iteration, with w = H q_k already computed.
+// Without a basis (three-term recurrence), r' = w - beta_{k-1} q_{k-1}, r = r' - alpha_k q_k:
+//   lz3_dots      : alpha_k = <q_k, r'>, <r', r'>, <q_k, q_k>; r' is formed on the fly   (3R)
+//   lz3_finish    : beta_k^2 = ||r||^2 = <r', r'> - alpha_k^2 (2 - <q_k, q_k>), an identity of the
+//                   fp32 vectors as stored; where the difference has lost its digits
+//   lz3_norm      : forms ||r||^2 explicitly (3R), else returns at once
+//   lz3_normalise : q_{k+1} = (w - beta_{k-1} q_{k-1} - alpha_k q_k) / beta_k written over
+//                   q_{k-1}                                                              (3R + 1W)
+// With a stored basis the first Gram-Schmidt pass is applied to w itself (against q_0 .. q_k; with
+// a bf16 basis q_k and q_{k-1} are taken from the fp32 working vectors): alpha_k is its k-th
+// coefficient and the two three-term subtractions are part of the pass:
 //   lz_qtr      : c = Q^T r      (k+1 dot products, Q read once)
 //   lz_sub_qc   : r -= Q c;  beta_k = ||r||   (Q read once)
-//   lz_scale    : q_{k+1} = r / beta_k, appended to the basis         (1R + 1W)
-// With a stored basis lz_qtr / lz_sub_qc are applied to H q_k directly (Gram-Schmidt against
-// q_0 .. q_k; with a bf16 basis q_k and q_{k-1} are taken from the fp32 working vectors): alpha_k is
-// the k-th coefficient and the first two kernels are not run.
+//   lz_scale    : q_{k+1} = r / beta_k, written to its basis row                          (1R + 1W)
 // Scalars stay on the device (array `scal` of doubles) so consecutive kernels
-// need no host round trip.  Reductions: fp64 per-thread accumulators, one
-// partial per block, summed in a fixed order by a small second kernel, so
-// results are bitwise reproducible.
+// need no host round trip; the kernels that write q_{k+1} test beta_k against the
+// tolerance (and the error flags of the product that made w) themselves and leave
+// the state untouched when the iteration must not advance, so the host reads the
+// scalars once, after everything has been enqueued.  Reductions: fp64 per-thread
+// accumulators, one partial per block, summed in a fixed order by a small second
+// kernel, so results are bitwise reproducible.
 #include "hf_internal.h"
 #include "lanczos.h"
 
@@ -34,67 +42,123 @@ __device__ __forceinline__ double block_sum_d(double v, double* red) {
   return red[0] + red[1] + red[2] + red[3];
 }
 
-// mode 0: partial sum of z^2 (r unused)
-// mode 1: r -= scal[S_BETA_PREV] * qp (if use_prev); partial <q, r>
-// mode 2: r -= scal[S_ALPHA] * q; partial <r, r>
-template <int MODE>
-__global__ __launch_bounds__(256) void lz_fused_kernel(float* __restrict__ r, const float* __restrict__ q,
-                                                       const float* __restrict__ qp, int64_t n, int use_prev,
-                                                       const double* __restrict__ scal, double* __restrict__ partials) {
+// Range of 16-byte groups that block b of a streaming kernel walks: one contiguous run per block
+// (measured faster than a grid-stride walk for these passes once the grid has 4096 blocks).
+struct Range { int64_t i, end; };
+__device__ __forceinline__ Range block_range(int64_t n4) {
+  const int64_t per = (n4 + gridDim.x - 1) / gridDim.x;
+  Range g;
+  g.i = (int64_t)blockIdx.x * per + threadIdx.x;
+  g.end = min(n4, (int64_t)(blockIdx.x + 1) * per);
+  return g;
+}
+
+__device__ __forceinline__ float4 fnma4(float c, const float4& x, const float4& y) {  // y - c x
+  return make_float4(fmaf(-c, x.x, y.x), fmaf(-c, x.y, y.y), fmaf(-c, x.z, y.z), fmaf(-c, x.w, y.w));
+}
+__device__ __forceinline__ double dot4(const float4& a, const float4& b) {
+  return (double)a.x * b.x + (double)a.y * b.y + (double)a.z * b.z + (double)a.w * b.w;
+}
+__device__ __forceinline__ uint2 pack_bf16x4(const float4& v) {
+  bf16 o[4] = {(bf16)v.x, (bf16)v.y, (bf16)v.z, (bf16)v.w};
+  return *(const uint2*)o;
+}
+
+// partials[block] = sum of z^2 over the block's range
+__global__ __launch_bounds__(256) void lz_sumsq_kernel(const float* __restrict__ z, int64_t n, double* __restrict__ partials) {
   __shared__ double red[4];
-  float coef = 0.f;
-  if (MODE == 1 && use_prev) coef = (float)scal[S_BETA_PREV];
-  if (MODE == 2) coef = (float)scal[S_ALPHA];
   double acc = 0.0;
   const int64_t n4 = n >> 2;
-  const int64_t stride = (int64_t)gridDim.x * 256;
-  // each block streams one contiguous range (measured faster than a grid-stride walk for these
-  // read-modify-write passes once the grid has 4096 blocks)
-  const int64_t per = (n4 + gridDim.x - 1) / gridDim.x;
-  const int64_t i_end = min(n4, (int64_t)(blockIdx.x + 1) * per);
+  const Range g = block_range(n4);
 #pragma unroll 2
-  for (int64_t i = (int64_t)blockIdx.x * per + threadIdx.x; i < i_end; i += 256) {
-    if (MODE == 0) {
-      const float4 a = ((const float4*)q)[i];
-      acc += (double)(a.x * a.x + a.y * a.y) + (double)(a.z * a.z + a.w * a.w);
-    } else if (MODE == 1) {
-      float4 rv = ((float4*)r)[i];
-      const float4 qv = ((const float4*)q)[i];
-      if (use_prev) {
-        const float4 pv = ((const float4*)qp)[i];
-        rv.x = fmaf(-coef, pv.x, rv.x); rv.y = fmaf(-coef, pv.y, rv.y);
-        rv.z = fmaf(-coef, pv.z, rv.z); rv.w = fmaf(-coef, pv.w, rv.w);
-        ((float4*)r)[i] = rv;
-      }
-      acc += (double)rv.x * qv.x + (double)rv.y * qv.y + (double)rv.z * qv.z + (double)rv.w * qv.w;
-    } else {
-      float4 rv = ((float4*)r)[i];
-      const float4 qv = ((const float4*)q)[i];
-      rv.x = fmaf(-coef, qv.x, rv.x); rv.y = fmaf(-coef, qv.y, rv.y);
-      rv.z = fmaf(-coef, qv.z, rv.z); rv.w = fmaf(-coef, qv.w, rv.w);
-      ((float4*)r)[i] = rv;
-      acc += (double)rv.x * rv.x + (double)rv.y * rv.y + (double)rv.z * rv.z + (double)rv.w * rv.w;
-    }
+  for (int64_t i = g.i; i < g.end; i += 256) {
+    const float4 a = ((const float4*)z)[i];
+    acc += dot4(a, a);
   }
-  // ragged tail (n not a multiple of 4)
-  for (int64_t i = (n4 << 2) + (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) {
-    if (MODE == 0) { acc += (double)q[i] * q[i]; }
-    else if (MODE == 1) {
-      float rv = r[i];
-      if (use_prev) { rv = fmaf(-coef, qp[i], rv); r[i] = rv; }
-      acc += (double)rv * q[i];
-    } else {
-      const float rv = fmaf(-coef, q[i], r[i]);
-      r[i] = rv;
-      acc += (double)rv * rv;
-    }
+  for (int64_t i = (n4 << 2) + (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) acc += (double)z[i] * z[i];
+  acc = block_sum_d(acc, red);
+  if (threadIdx.x == 0) partials[blockIdx.x] = acc;
+}
+
+// Three-term recurrence, first pass (read only).  With r' = w - bprev qp formed on the fly
+// (use_prev = 0: r' = w): partials[0][block] = <q, r'>, [1][block] = <r', r'>, [2][block] = <q, q>.
+__global__ __launch_bounds__(256) void lz3_dots_kernel(const float* __restrict__ w, const float* __restrict__ q,
+                                                       const float* __restrict__ qp, int64_t n, int use_prev, float bprev,
+                                                       double* __restrict__ partials) {
+  __shared__ double red[4];
+  double a0 = 0.0, a1 = 0.0, a2 = 0.0;
+  const int64_t n4 = n >> 2;
+  const Range g = block_range(n4);
+#pragma unroll 2
+  for (int64_t i = g.i; i < g.end; i += 256) {
+    float4 rv = ((const float4*)w)[i];
+    const float4 qv = ((const float4*)q)[i];
+    if (use_prev) rv = fnma4(bprev, ((const float4*)qp)[i], rv);
+    a0 += dot4(rv, qv); a1 += dot4(rv, rv); a2 += dot4(qv, qv);
+  }
+  for (int64_t i = (n4 << 2) + (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    float rv = w[i];
+    if (use_prev) rv = fmaf(-bprev, qp[i], rv);
+    a0 += (double)rv * q[i]; a1 += (double)rv * rv; a2 += (double)q[i] * q[i];
+  }
+  a0 = block_sum_d(a0, red);
+  a1 = block_sum_d(a1, red);
+  a2 = block_sum_d(a2, red);
+  if (threadIdx.x == 0) {
+    partials[blockIdx.x] = a0;
+    partials[gridDim.x + blockIdx.x] = a1;
+    partials[2 * (int64_t)gridDim.x + blockIdx.x] = a2;
+  }
+}
+
+// alpha_k and, from the three sums, ||r' - alpha q||^2 = <r',r'> - 2 alpha <q,r'> + alpha^2 <q,q>
+// = <r',r'> - alpha^2 (2 - <q,q>): an identity of the fp32 vectors as the passes read them, so
+// only the fp64 summation error (about 1e-15 <r',r'>) is amplified by the cancellation; below
+// 1e-6 <r',r'> the norm is formed explicitly instead (scal[S_REDO] = 1 asks lz3_norm for it).
+__global__ __launch_bounds__(256) void lz3_finish_kernel(const double* __restrict__ partials, int nblk, double* __restrict__ scal) {
+  __shared__ double red[4];
+  double s[3];
+  for (int j = 0; j < 3; ++j) {
+    double a = 0.0;
+    for (int i = threadIdx.x; i < nblk; i += 256) a += partials[(int64_t)j * nblk + i];
+    s[j] = block_sum_d(a, red);
+  }
+  if (threadIdx.x != 0) return;
+  const double al = s[0], rest = s[1] - al * al * (2.0 - s[2]);
+  scal[S_ALPHA] = al;
+  if (rest > 1e-6 * s[1]) { scal[S_BETA] = sqrt(rest); scal[S_REDO] = 0.0; }
+  else { scal[S_BETA] = 0.0; scal[S_REDO] = 1.0; }   // also taken when a sum is NaN
+}
+
+// Only when lz3_finish asked for it: partials[block] = ||w - bprev qp - alpha q||^2 (read only).
+__global__ __launch_bounds__(256) void lz3_norm_kernel(const float* __restrict__ w, const float* __restrict__ q,
+                                                       const float* __restrict__ qp, int64_t n, int use_prev, float bprev,
+                                                       const double* __restrict__ scal, double* __restrict__ partials) {
+  __shared__ double red[4];
+  if (scal[S_REDO] == 0.0) return;
+  const float al = (float)scal[S_ALPHA];
+  double acc = 0.0;
+  const int64_t n4 = n >> 2;
+  const Range g = block_range(n4);
+#pragma unroll 2
+  for (int64_t i = g.i; i < g.end; i += 256) {
+    float4 rv = ((const float4*)w)[i];
+    if (use_prev) rv = fnma4(bprev, ((const float4*)qp)[i], rv);
+    rv = fnma4(al, ((const float4*)q)[i], rv);
+    acc += dot4(rv, rv);
+  }
+  for (int64_t i = (n4 << 2) + (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    float rv = w[i];
+    if (use_prev) rv = fmaf(-bprev, qp[i], rv);
+    rv = fmaf(-al, q[i], rv);
+    acc += (double)rv * rv;
   }
   acc = block_sum_d(acc, red);
   if (threadIdx.x == 0) partials[blockIdx.x] = acc;
 }
 
-// what 0: scal[S_Q0NORM] = sqrt(sum); 1: scal[S_ALPHA] = sum;
-// 2: scal[S_BETA] = scal[S_NRM_BEFORE] = sqrt(sum), redo flag cleared;
+// what 0: scal[S_Q0NORM] = sqrt(sum);
+// 2 (after lz3_norm, only when it ran): scal[S_BETA] = sqrt(sum);
 // 3 (after an orthogonalisation pass): scal[S_BETA] = sqrt(sum), redo flag set
 //    iff this was the first pass and the norm fell below 1/sqrt(2) of its
 //    value before the pass.
@@ -102,13 +166,13 @@ __global__ __launch_bounds__(256) void lz_finish_kernel(const double* partials, 
                                                         double* scal) {
   __shared__ double red[4];
   if (what == 3 && pass == 1 && scal[S_REDO] == 0.0) return;
+  if (what == 2 && scal[S_REDO] == 0.0) return;
   double s = 0.0;
   for (int i = threadIdx.x; i < nblk; i += 256) s += partials[i];
   s = block_sum_d(s, red);
   if (threadIdx.x != 0) return;
   if (what == 0) scal[S_Q0NORM] = sqrt(s);
-  else if (what == 1) scal[S_ALPHA] = s;
-  else if (what == 2) { scal[S_BETA] = sqrt(s); scal[S_NRM_BEFORE] = sqrt(s); scal[S_REDO] = 0.0; }
+  else if (what == 2) { scal[S_BETA] = sqrt(s); scal[S_REDO] = 0.0; }
   else {
     const double nb = sqrt(s);
     scal[S_BETA] = nb;
@@ -117,37 +181,75 @@ __global__ __launch_bounds__(256) void lz_finish_kernel(const double* partials, 
   }
 }
 
-// dst = src / scal[idx]; optional basis copy (fp32 or bf16, round-to-nearest-even) and optional
-// bf16 copy `vb` (the operand-type copy of the next Hessian-vector product's direction, which
-// would otherwise cost that product a pass over q_{k+1}).
+// Whether iteration k may write q_{k+1}: beta_k (scal[idx]) is a positive number not below the
+// tolerance, and the product that made w reported no bad token / label (flags, may be NULL).
+// The first thread of the grid also leaves the flags in scal[S_FLAG0], scal[S_FLAG1] for the host.
+__device__ __forceinline__ bool lz_may_advance(double* scal, int idx, double tol, const int* flags) {
+  const double b = scal[idx];
+  bool ok = (b >= tol) && (b > 0.0);
+  if (flags) {
+    const int f0 = flags[0], f1 = flags[1];
+    if (blockIdx.x == 0 && threadIdx.x == 0) { scal[S_FLAG0] = (double)f0; scal[S_FLAG1] = (double)f1; }
+    ok = ok && f0 == 0 && f1 != 0;
+  }
+  return ok;
+}
+
+// Three-term recurrence, last pass: qp <- (w - bprev qp - alpha q) / beta (q_{k+1} over q_{k-1}), and
+// optionally vb = its bf16 copy (the operand-type copy of the next Hessian-vector product's
+// direction, which would otherwise cost that product a pass over q_{k+1}).
+__global__ __launch_bounds__(256) void lz3_normalise_kernel(const float* __restrict__ w, const float* __restrict__ q,
+                                                            float* __restrict__ qp, bf16* __restrict__ vb, int64_t n,
+                                                            int use_prev, float bprev, double* scal, double tol,
+                                                            const int* flags) {
+  if (!lz_may_advance(scal, S_BETA, tol, flags)) return;
+  const float al = (float)scal[S_ALPHA];
+  const float inv = (float)(1.0 / scal[S_BETA]);
+  const int64_t n4 = n >> 2;
+  const Range g = block_range(n4);
+#pragma unroll 2
+  for (int64_t i = g.i; i < g.end; i += 256) {
+    float4 rv = ((const float4*)w)[i];
+    const float4 qv = ((const float4*)q)[i];
+    if (use_prev) rv = fnma4(bprev, ((const float4*)qp)[i], rv);
+    rv = fnma4(al, qv, rv);
+    rv.x *= inv; rv.y *= inv; rv.z *= inv; rv.w *= inv;
+    ((float4*)qp)[i] = rv;
+    if (vb) ((uint2*)vb)[i] = pack_bf16x4(rv);
+  }
+  for (int64_t i = (n4 << 2) + (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    float rv = w[i];
+    if (use_prev) rv = fmaf(-bprev, qp[i], rv);
+    rv = fmaf(-al, q[i], rv) * inv;
+    qp[i] = rv;
+    if (vb) vb[i] = (bf16)rv;
+  }
+}
+
+// q_{k+1} = src / scal[idx] into any of: dst (fp32 working vector), basis (its row of the stored
+// basis, fp32 or bf16 rounded to nearest even), vb (bf16 copy for the next Hessian-vector product).
 template <typename BT>
-__global__ __launch_bounds__(256) void lz_scale_kernel(const float* src, float* dst, BT* basis, bf16* vb, int64_t n,
-                                                       const double* scal, int idx) {
+__global__ __launch_bounds__(256) void lz_scale_kernel(const float* __restrict__ src, float* __restrict__ dst,
+                                                       BT* __restrict__ basis, bf16* __restrict__ vb, int64_t n,
+                                                       double* scal, int idx, double tol, const int* flags) {
+  if (!lz_may_advance(scal, idx, tol, flags)) return;
   const float inv = (float)(1.0 / scal[idx]);
   const int64_t n4 = n >> 2;
-  const int64_t stride = (int64_t)gridDim.x * 256;
-  const int64_t per = (n4 + gridDim.x - 1) / gridDim.x;
-  const int64_t i_end = min(n4, (int64_t)(blockIdx.x + 1) * per);
+  const Range g = block_range(n4);
 #pragma unroll 2
-  for (int64_t i = (int64_t)blockIdx.x * per + threadIdx.x; i < i_end; i += 256) {
+  for (int64_t i = g.i; i < g.end; i += 256) {
     float4 v = ((const float4*)src)[i];
     v.x *= inv; v.y *= inv; v.z *= inv; v.w *= inv;
-    ((float4*)dst)[i] = v;
+    if (dst) ((float4*)dst)[i] = v;
     if (basis) {
       if (sizeof(BT) == 4) ((float4*)basis)[i] = v;
-      else {
-        bf16 o[4] = {(bf16)v.x, (bf16)v.y, (bf16)v.z, (bf16)v.w};
-        ((uint2*)basis)[i] = *(const uint2*)o;
-      }
+      else ((uint2*)basis)[i] = pack_bf16x4(v);
     }
-    if (vb) {
-      bf16 o[4] = {(bf16)v.x, (bf16)v.y, (bf16)v.z, (bf16)v.w};
-      ((uint2*)vb)[i] = *(const uint2*)o;
-    }
+    if (vb) ((uint2*)vb)[i] = pack_bf16x4(v);
   }
-  for (int64_t i = (n4 << 2) + (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) {
+  for (int64_t i = (n4 << 2) + (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
     const float v = src[i] * inv;
-    dst[i] = v;
+    if (dst) dst[i] = v;
     if (basis) basis[i] = (BT)v;
     if (vb) vb[i] = (bf16)v;
   }
@@ -173,10 +275,7 @@ __device__ __forceinline__ float4 load4<bf16>(const bf16* p, int64_t i4) {
 // basis byte is read exactly once per kernel with many loads in flight and
 // contiguous 16 KB / 8 KB runs per vector (measured best among 2K..16K); the loads of vector
 // j+1 are issued before vector j is consumed.
-#ifndef HF_LZ_SLICE
-#define HF_LZ_SLICE 4096
-#endif
-constexpr int LZ_SLICE = HF_LZ_SLICE;     // elements per slice
+constexpr int LZ_SLICE = 4096;            // elements per slice
 constexpr int LZ_RPT = LZ_SLICE / 256;    // r elements per thread
 
 typedef float lz_f32x4 __attribute__((ext_vector_type(4)));
@@ -228,11 +327,7 @@ __device__ __forceinline__ void load_q_slice(const BT* __restrict__ q, int64_t b
   for (int u = 0; u < V::U; ++u) {
     const int64_t e0 = base + (int64_t)(threadIdx.x + 256 * u) * V::E;
     if (full || e0 + V::E <= n) {
-#ifdef HF_LZ_PLAIN_LOADS
-      qv[u] = *(const typename V::raw*)(q + e0);
-#else
       qv[u] = __builtin_nontemporal_load((const typename V::raw*)(q + e0));
-#endif
     } else {
       BT t8[V::E];
       for (int k = 0; k < V::E; ++k) t8[k] = (e0 + k < n) ? q[e0 + k] : (BT)0.f;
@@ -429,31 +524,28 @@ static int vec_blocks(int64_t n) {
 
 hipError_t lz_norm_q0(const float* z, int64_t n, double* scal, double* partials, hipStream_t st) {
   const int nb = vec_blocks(n);
-  hipLaunchKernelGGL(lz_fused_kernel<0>, dim3(nb), dim3(256), 0, st, nullptr, z, nullptr, n, 0, scal, partials);
+  hipLaunchKernelGGL(lz_sumsq_kernel, dim3(nb), dim3(256), 0, st, z, n, partials);
   hipLaunchKernelGGL(lz_finish_kernel, dim3(1), dim3(256), 0, st, partials, nb, 0, 0, scal);
   return hipGetLastError();
 }
 
-hipError_t lz_axpy_dot(float* r, const float* q, const float* qp, int64_t n, int use_prev, double* scal,
-                       double* partials, hipStream_t st) {
+hipError_t lz3_update(const float* w, const float* q, float* qp, bf16* vb, int64_t n, int use_prev, double beta_prev,
+                      double tol, const int* flags, double* scal, double* partials, hipStream_t st) {
   const int nb = vec_blocks(n);
-  hipLaunchKernelGGL(lz_fused_kernel<1>, dim3(nb), dim3(256), 0, st, r, q, qp, n, use_prev, scal, partials);
-  hipLaunchKernelGGL(lz_finish_kernel, dim3(1), dim3(256), 0, st, partials, nb, 1, 0, scal);
-  return hipGetLastError();
-}
-
-hipError_t lz_axpy_nrm(float* r, const float* q, int64_t n, double* scal, double* partials, hipStream_t st) {
-  const int nb = vec_blocks(n);
-  hipLaunchKernelGGL(lz_fused_kernel<2>, dim3(nb), dim3(256), 0, st, r, q, nullptr, n, 0, scal, partials);
+  const float bp = (float)beta_prev;
+  hipLaunchKernelGGL(lz3_dots_kernel, dim3(nb), dim3(256), 0, st, w, q, qp, n, use_prev, bp, partials);
+  hipLaunchKernelGGL(lz3_finish_kernel, dim3(1), dim3(256), 0, st, partials, nb, scal);
+  hipLaunchKernelGGL(lz3_norm_kernel, dim3(nb), dim3(256), 0, st, w, q, qp, n, use_prev, bp, scal, partials);
   hipLaunchKernelGGL(lz_finish_kernel, dim3(1), dim3(256), 0, st, partials, nb, 2, 0, scal);
+  hipLaunchKernelGGL(lz3_normalise_kernel, dim3(nb), dim3(256), 0, st, w, q, qp, vb, n, use_prev, bp, scal, tol, flags);
   return hipGetLastError();
 }
 
-hipError_t lz_scale(const float* src, float* dst, void* basis, int basis_bf16, bf16* vb, int64_t n, const double* scal, int idx,
-                    hipStream_t st) {
+hipError_t lz_scale(const float* src, float* dst, void* basis, int basis_bf16, bf16* vb, int64_t n, double* scal, int idx,
+                    double tol, const int* flags, hipStream_t st) {
   const int nb = vec_blocks(n);
-  if (basis_bf16) hipLaunchKernelGGL(lz_scale_kernel<bf16>, dim3(nb), dim3(256), 0, st, src, dst, (bf16*)basis, vb, n, scal, idx);
-  else hipLaunchKernelGGL(lz_scale_kernel<float>, dim3(nb), dim3(256), 0, st, src, dst, (float*)basis, vb, n, scal, idx);
+  if (basis_bf16) hipLaunchKernelGGL(lz_scale_kernel<bf16>, dim3(nb), dim3(256), 0, st, src, dst, (bf16*)basis, vb, n, scal, idx, tol, flags);
+  else hipLaunchKernelGGL(lz_scale_kernel<float>, dim3(nb), dim3(256), 0, st, src, dst, (float*)basis, vb, n, scal, idx, tol, flags);
   return hipGetLastError();
 }
 

@@ -1216,7 +1216,7 @@ __device__ __forceinline__ void st4f(bf16* p, int64_t i, float a, float b, float
 template <typename AT>
 __global__ __launch_bounds__(256) void ce_kernel(const float* __restrict__ z, const float* __restrict__ z_t,
                                                  const int32_t* labels, const int* n_valid, int V, int64_t ldz, AT* dz,
-                                                 AT* dz_t, float* loss_rows) {
+                                                 AT* dz_t, float* loss_rows, float scale) {
   __shared__ float red[16];
   const int64_t row = blockIdx.x;
   const float* zr = z + row * ldz;
@@ -1255,7 +1255,7 @@ __global__ __launch_bounds__(256) void ce_kernel(const float* __restrict__ z, co
   block_sum<2>(s, red);
   const float inv = 1.f / s[0];
   const float pz = s[1] * inv;
-  const float invN = 1.f / (float)max(1, *n_valid);
+  const float invN = scale / (float)max(1, *n_valid);
   for (int c = threadIdx.x; c < V4; c += 256) {
     const float4 x = ((const float4*)zr)[c], t = ((const float4*)ztr)[c];
     const float p0 = __expf(x.x - mx) * inv, p1 = __expf(x.y - mx) * inv, p2 = __expf(x.z - mx) * inv, p3 = __expf(x.w - mx) * inv;
@@ -1278,7 +1278,7 @@ template <typename AT, int EPT>
 __global__ __launch_bounds__(1024) void ce_row_kernel(const float* __restrict__ z, const float* __restrict__ z_t,
                                                       const int32_t* __restrict__ labels, const int* __restrict__ n_valid,
                                                       int V, int64_t ldz, AT* __restrict__ dz, AT* __restrict__ dz_t,
-                                                      float* __restrict__ loss_rows) {
+                                                      float* __restrict__ loss_rows, float scale) {
   __shared__ float red[48];
   const int64_t row = blockIdx.x;
   const float* zr = z + row * ldz;
@@ -1328,7 +1328,7 @@ __global__ __launch_bounds__(1024) void ce_row_kernel(const float* __restrict__ 
   for (int w = 0; w < 16; ++w) { s0 += red[16 + w]; s1 += red[32 + w]; }
   const float inv = 1.f / s0;
   const float pz = s1 * inv;
-  const float invN = 1.f / (float)max(1, *n_valid);
+  const float invN = scale / (float)max(1, *n_valid);
 #pragma unroll
   for (int j = 0; j < EPT; ++j) {
     const int c = t + 1024 * j;
@@ -1350,17 +1350,20 @@ __global__ __launch_bounds__(1024) void ce_row_kernel(const float* __restrict__ 
 }
 
 hipError_t launch_ce(int bf, const float* z, const float* z_t, const int32_t* labels, const int* n_valid, int T, int V,
-                     int64_t ldz, void* dz, void* dz_t, float* loss_rows, hipStream_t st) {
+                     int64_t ldz, void* dz, void* dz_t, float* loss_rows, float scale, hipStream_t st) {
   if (bf && V >= 8192 && ldz % 4 == 0) {  // wide rows: the two-pass kernel reads them twice
-    if (V <= 4096 * 8) { hipLaunchKernelGGL((ce_row_kernel<bf16, 8>), dim3(T), dim3(1024), 0, st, z, z_t, labels, n_valid, V, ldz, (bf16*)dz, (bf16*)dz_t, loss_rows); return hipGetLastError(); }
-    if (V <= 4096 * 13) { hipLaunchKernelGGL((ce_row_kernel<bf16, 13>), dim3(T), dim3(1024), 0, st, z, z_t, labels, n_valid, V, ldz, (bf16*)dz, (bf16*)dz_t, loss_rows); return hipGetLastError(); }
+    if (V <= 4096 * 8) { hipLaunchKernelGGL((ce_row_kernel<bf16, 8>), dim3(T), dim3(1024), 0, st, z, z_t, labels, n_valid, V, ldz, (bf16*)dz, (bf16*)dz_t, loss_rows, scale); return hipGetLastError(); }
+    if (V <= 4096 * 13) { hipLaunchKernelGGL((ce_row_kernel<bf16, 13>), dim3(T), dim3(1024), 0, st, z, z_t, labels, n_valid, V, ldz, (bf16*)dz, (bf16*)dz_t, loss_rows, scale); return hipGetLastError(); }
   }
-  if (bf) hipLaunchKernelGGL(ce_kernel<bf16>, dim3(T), dim3(256), 0, st, z, z_t, labels, n_valid, V, ldz, (bf16*)dz, (bf16*)dz_t, loss_rows);
-  else hipLaunchKernelGGL(ce_kernel<float>, dim3(T), dim3(256), 0, st, z, z_t, labels, n_valid, V, ldz, (float*)dz, (float*)dz_t, loss_rows);
+  if (bf) hipLaunchKernelGGL(ce_kernel<bf16>, dim3(T), dim3(256), 0, st, z, z_t, labels, n_valid, V, ldz, (bf16*)dz, (bf16*)dz_t, loss_rows, scale);
+  else hipLaunchKernelGGL(ce_kernel<float>, dim3(T), dim3(256), 0, st, z, z_t, labels, n_valid, V, ldz, (float*)dz, (float*)dz_t, loss_rows, scale);
   return hipGetLastError();
 }
 
-__global__ __launch_bounds__(256) void sum_rows_f64_kernel(const float* v, int n, const int* n_valid, double* out) {
+// out[0] = weight * mean over the valid rows (added to out[0] when accumulate); a batch without a
+// valid label sets bit 2 of err_flag.
+__global__ __launch_bounds__(256) void sum_rows_f64_kernel(const float* v, int n, const int* n_valid, double* out, double weight,
+                                                           int accumulate, int* err_flag) {
   __shared__ double red[256];
   double s = 0.0;
   for (int i = threadIdx.x; i < n; i += 256) s += (double)v[i];
@@ -1370,10 +1373,15 @@ __global__ __launch_bounds__(256) void sum_rows_f64_kernel(const float* v, int n
     if (threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
     __syncthreads();
   }
-  if (threadIdx.x == 0) out[0] = red[0] / (double)max(1, *n_valid);
+  if (threadIdx.x == 0) {
+    const int nv = *n_valid;
+    if (nv == 0) atomicOr(err_flag, 4);
+    out[0] = (accumulate ? out[0] : 0.0) + weight * red[0] / (double)max(1, nv);
+  }
 }
-hipError_t launch_sum_rows_f64(const float* v, int n, const int* n_valid, double* out, hipStream_t st) {
-  hipLaunchKernelGGL(sum_rows_f64_kernel, dim3(1), dim3(256), 0, st, v, n, n_valid, out);
+hipError_t launch_sum_rows_f64(const float* v, int n, const int* n_valid, double* out, double weight, int accumulate,
+                               int* err_flag, hipStream_t st) {
+  hipLaunchKernelGGL(sum_rows_f64_kernel, dim3(1), dim3(256), 0, st, v, n, n_valid, out, weight, accumulate, err_flag);
   return hipGetLastError();
 }
 

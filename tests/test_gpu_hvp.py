@@ -36,6 +36,11 @@ SHAPES = {
     # 2000 x 4088 products with k = 264: several hundred tiles with a ragged last tile in every
     # dimension
     "gpt_wide_ffn": dict(model=si._gpt(1, 264, 4, 4088, 97, 500), batch=4, seq=500, tokens="zipf"),
+    # more than two layers (per-layer buffers, layer >= 2 of each family's schedule), with and
+    # without grouped key/value heads
+    "gpt_deep": dict(model=si._gpt(6, 64, 2, 136, 211, 40), batch=2, seq=40, tokens="zipf"),
+    "llama_deep": dict(model=si._llama(6, 64, 2, 96, 211, 40), batch=2, seq=40, tokens="zipf"),
+    "llama_gqa_deep": dict(model=si._llama(5, 128, 4, 176, 211, 40, n_kv=2), batch=2, seq=40, tokens="zipf"),
 }
 
 
@@ -81,7 +86,8 @@ def test_hvp_shorter_sequence_than_max():
 def test_hvp_bf16_sequence_length_changes_on_one_context():
     # The fused attention kernels write only the score tiles on and below the diagonal and rely on
     # the rest having been cleared for the current [batch, seq] layout: alternate layouts on one
-    # context and check every product against the oracle.
+    # context and check every product against the oracle.  Sequence length 77 is not a multiple of
+    # 8 and takes the unfused kernels, which write whole score matrices in another layout.
     import paper_2505_11564_amd as hf
     from gpu_util import gpu_hvp, rel_l2
     cfg = SHAPES["gpt_fused"]
@@ -89,7 +95,7 @@ def test_hvp_bf16_sequence_length_changes_on_one_context():
     p = si.bf16_bits_to_f32(si.f32_to_bf16_bits(si.make_params(model, param_dtype="bf16", perturb=0.1)))
     n = om.num_params(model)
     ctx = hf.Context(model, cfg["batch"], 0, "bf16")
-    for k, (batch, seq) in enumerate([(2, 200), (2, 136), (1, 200), (2, 72), (2, 200)]):
+    for k, (batch, seq) in enumerate([(2, 200), (2, 136), (1, 200), (2, 72), (2, 200), (2, 77), (2, 200)]):
         x, y = si.make_batch(cfg, seed=50 + k, batch=batch, seq=seq)
         v = si.make_direction(n, 60 + k)
         want = om.hvp(model, p.astype(np.float64), x, y, v.astype(np.float64))

@@ -38,14 +38,20 @@ def run_update_only(ctx, dvec, z, m, reorth, tol=0.0):
     return np.array(al), np.array(be)
 
 
+# only the models' parameter counts matter here: a multiple of 4, and one that leaves a tail of one
+# element after the 16-byte groups
+UPDATE_MODELS = {"n54032": si._gpt(1, 40, 2, 72, 1001, 33), "n56981_ragged": si._gpt(1, 42, 2, 71, 1001, 33)}
+
+
 @pytest.mark.parametrize("basis", ["f32", "bf16"])
 @pytest.mark.parametrize("reorth", ["none", "full"])
-def test_update_kernels_diagonal_operator(reorth, basis):
+@pytest.mark.parametrize("size", list(UPDATE_MODELS))
+def test_update_kernels_diagonal_operator(size, reorth, basis):
     import paper_2505_11564_amd as hf
-    model = si._gpt(1, 40, 2, 72, 1001, 33)          # only its parameter count matters here
+    model = UPDATE_MODELS[size]
     ctx = hf.Context(model, 1, 48, "f32", basis)
     n = ctx.n
-    assert n % 4 != 0 or True
+    assert (n % 4 != 0) == size.endswith("ragged")
     rng = np.random.default_rng(5)
     dvec = np.concatenate([rng.uniform(-1, 1, n - 3), [-7.0, 9.0, 12.0]]).astype(np.float32)
     z = si.make_probe(n, 0)
@@ -71,7 +77,18 @@ def test_update_kernels_diagonal_operator(reorth, basis):
         for j in range(10):
             ctx.hf_lanczos_get_vector(16 + j, Q[j])
         G = (Q.double() @ Q.double().T).cpu().numpy()
-        assert np.abs(G - np.eye(10)).max() <= (1e-5 if basis == "f32" else 5e-3)
+        # (bf16: every stored entry carries a relative rounding error of up to 2^-9, which does not
+        # average out where it is systematic: the equal-magnitude entries of the normalised
+        # Rademacher probe q_0 all round the same way, and the later vectors concentrate on the
+        # three planted coordinates, so <q_i, q_j> of the stored copies is off by up to about 2^-7)
+        dev = np.abs(G - np.eye(10))
+        assert dev.max() <= (1e-5 if basis == "f32" else 2.0 ** -7)
+        # the newest row is the working vector q_m itself (fp32) or its rounding to nearest even
+        # (bf16), to the last element of a ragged length
+        qm, row = torch.empty(n, device="cuda"), torch.empty(n, device="cuda")
+        ctx.hf_lanczos_get_vector(0, qm)
+        ctx.hf_lanczos_get_vector(16 + m, row)
+        assert torch.equal(row, qm if basis == "f32" else qm.bfloat16().float())
         # no ghost copies of the converged top eigenvalue
         assert int(np.sum(np.abs(th - 12.0) <= 1e-3 * 12.0)) == 1
     ctx.close()

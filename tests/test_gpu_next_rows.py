@@ -137,6 +137,24 @@ def test_column_stats_synthetic_vectors(n, offset):
     ctx.close()
 
 
+def test_column_stats_infinite_entries():
+    # an infinite maximum: finite entries in the first bin, infinite ones in the last, NaN nowhere
+    rng = np.random.default_rng(8)
+    n = 300_007
+    h = (rng.standard_normal(n) * 10.0 ** rng.uniform(-14, 0, n)).astype(np.float32)
+    h[[2, 4099, n - 1]] = [np.inf, -np.inf, np.inf]
+    h[9] = np.nan
+    model = si.CONFIGS["mlp_tiny"]["model"]
+    ctx = hf.Context(model, 4, 0, "f32")
+    below, mx, hist = ctx.hf_column_stats(_dev(h), n, THRESHOLDS, 50)
+    o_below, o_mx, o_hist = column_probe.column_stats(h, THRESHOLDS, 50)
+    np.testing.assert_array_equal(below, o_below)
+    assert mx == o_mx == np.float32(np.inf)
+    np.testing.assert_array_equal(hist, o_hist)
+    assert hist[0] == n - 4 and hist[-1] == 3
+    ctx.close()
+
+
 def test_column_stats_zero_vector_and_bad_arguments():
     model = si.CONFIGS["mlp_tiny"]["model"]
     ctx = hf.Context(model, 4, 0, "f32")

@@ -116,6 +116,38 @@ def test_column_stats_degenerate():
     assert np.all(np.diff(below) >= 0) and below[-1] <= len(h)
 
 
+def test_column_stats_infinite_entries():
+    # Section "Banded Hessians" histograms |H_ij| over [0, max].  With an infinite maximum every bin
+    # is infinitely wide: each finite entry lies in the first bin and the maximum itself (every
+    # infinite entry, of either sign) belongs to the last one; an infinite entry is below no finite
+    # threshold and NaN entries are counted nowhere.  Expected values written out by hand.
+    inf, nan = np.inf, np.nan
+    h = np.array([0.5, -inf, 2.0, inf, nan, 0.0, -1e-3, inf, 7e30], np.float32)
+    below, mx, hist = column_probe.column_stats(h, [1e-2, 1.0, 3.0e38], 4)
+    assert list(below) == [2, 3, 5]          # {0, -1e-3}; + 0.5; + 2.0 and 7e30
+    assert mx == np.float32(inf)
+    assert list(hist) == [5, 0, 0, 3]        # five finite entries, three infinite ones, the NaN nowhere
+    # the same by a plain loop over the entries, for a seeded vector with planted infinities
+    rng = np.random.default_rng(3)
+    h = rng.standard_normal(2000).astype(np.float32)
+    planted = [3, 777, 1999]
+    h[planted[0]], h[planted[1]], h[planted[2]] = inf, -inf, inf
+    h[11] = nan
+    thr = [0.1, 1.0, 2.5]
+    below, mx, hist = column_probe.column_stats(h, thr, 50)
+    want_below = [0] * len(thr)
+    want_hist = [0] * 50
+    for val in h.tolist():
+        if val != val:
+            continue
+        for j, t in enumerate(thr):
+            if abs(val) < float(np.float32(t)):
+                want_below[j] += 1
+        want_hist[49 if abs(val) == inf else 0] += 1
+    assert list(below) == want_below and list(hist) == want_hist and mx == np.float32(inf)
+    assert hist[0] == 2000 - 4 and hist[-1] == 3
+
+
 def test_density_closed_forms():
     ritz = np.array([[-1.0, 0.5, 2.0, 0.0], [0.25, 3.0, 0.0, 0.0]])
     w = np.array([[0.2, 0.3, 0.5, 0.0], [0.6, 0.4, 0.0, 0.0]])
