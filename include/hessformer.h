@@ -267,6 +267,22 @@ int32_t hf_column_stats(hf_ctx* ctx, const float* h_dev, int64_t n, const float*
                         int32_t n_thresholds, int32_t n_bins, int64_t* below, float* max_abs,
                         int64_t* hist, void* hip_stream);
 
+/* hf_column_stats for callers that cannot allocate device memory or hold a
+ * context: code under HIP graph capture set-up, tight serving loops, harnesses
+ * that forbid hipMalloc.  Same arguments, results and errors as
+ * hf_column_stats, without a context: the counters the two passes need (2304
+ * bytes) live in a fixed array inside the library's device image, one copy per
+ * GPU, held until the process ends.  Limits: n < 2^40, n_thresholds <= 16,
+ * n_bins <= 256 (HF_ESHAPE / HF_EINVAL beyond them).  The call allocates and
+ * frees nothing.  It runs on the device that is current on the calling thread,
+ * which must own h_dev.  Every call on a GPU shares that GPU's array, which
+ * keeps the previous call's contents: the call clears it first (a fill kernel
+ * on hip_stream), and two calls that overlap on one GPU race.  The message of a
+ * failure is available from hf_last_error(NULL). */
+int32_t hf_column_stats_noalloc(const float* h_dev, int64_t n, const float* thresholds,
+                                int32_t n_thresholds, int32_t n_bins, int64_t* below,
+                                float* max_abs, int64_t* hist, void* hip_stream);
+
 /* Smoothed spectral density from the quadrature nodes and weights of hf_slq
  * (the smoothed densities the paper plots; Table 2 lists the underlying nodes
  * and weights): density[g] = (1/n_probes) sum_p sum_{i < m_eff[p]}

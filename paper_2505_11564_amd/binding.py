@@ -25,7 +25,7 @@ EXPORTS = [
     "hf_hvp", "hf_lanczos_init", "hf_lanczos_step", "hf_lanczos_iterations", "hf_lanczos_get_vector",
     "hf_slq", "hf_lanczos_update",
     "hf_hvp_accumulate", "hf_hessian_column", "hf_column_stats", "hf_slq_density", "hf_slq_moments",
-    "hf_lanczos_state_bytes", "hf_lanczos_export", "hf_lanczos_import",
+    "hf_lanczos_state_bytes", "hf_lanczos_export", "hf_lanczos_import", "hf_column_stats_noalloc",
 ]
 
 
@@ -93,6 +93,9 @@ def lib():
     L.hf_column_stats.argtypes = [vp, vp, i64, C.POINTER(C.c_float), i32, i32, C.POINTER(i64), C.POINTER(C.c_float),
                                   C.POINTER(i64), vp]
     L.hf_column_stats.restype = i32
+    L.hf_column_stats_noalloc.argtypes = [vp, i64, C.POINTER(C.c_float), i32, i32, C.POINTER(i64), C.POINTER(C.c_float),
+                                          C.POINTER(i64), vp]
+    L.hf_column_stats_noalloc.restype = i32
     L.hf_slq_density.argtypes = [dp, dp, C.POINTER(i32), i32, i32, C.c_double, dp, i32, dp]
     L.hf_slq_density.restype = i32
     L.hf_slq_moments.argtypes = [dp, dp, C.POINTER(i32), i32, i32, i32, dp]
@@ -214,6 +217,20 @@ def hf_slq_moments(ritz, weights, m_eff, n_moments):
     if rc != HF_OK:
         raise HessformerError(rc, "hf_slq_moments")
     return out
+
+
+def hf_column_stats_noalloc(h, n, thresholds, n_bins, stream=None):
+    """Context-free column statistics on the library's static counters."""
+    thr = np.ascontiguousarray(thresholds, dtype=np.float32)
+    below = np.zeros(max(len(thr), 1), dtype=np.int64)
+    hist = np.zeros(max(n_bins, 1), dtype=np.int64)
+    mx = C.c_float(0.0)
+    i64p = C.POINTER(C.c_int64)
+    rc = lib().hf_column_stats_noalloc(_ptr(h), int(n), thr.ctypes.data_as(C.POINTER(C.c_float)), len(thr), n_bins,
+                                       below.ctypes.data_as(i64p), C.byref(mx), hist.ctypes.data_as(i64p), _stream(stream))
+    if rc != HF_OK:
+        raise HessformerError(rc, lib().hf_last_error(None).decode())
+    return below[:len(thr)], np.float32(mx.value), hist[:n_bins]
 
 
 # ---- context ----------------------------------------------------------------

@@ -450,6 +450,22 @@ int32_t hf_column_stats(hf_ctx* ctx, const float* h_dev, int64_t n, const float*
   return rc == HF_OK ? rc : ctx->fail(rc, "hf_column_stats: " + why);
 }
 
+int32_t hf_column_stats_noalloc(const float* h_dev, int64_t n, const float* thresholds, int32_t n_thresholds,
+                                int32_t n_bins, int64_t* below, float* max_abs, int64_t* hist, void* hip_stream) {
+  unsigned long long* counters = nullptr;
+  const hipError_t e = colstats_static_counters(&counters);
+  if (e != hipSuccess) {
+    set_create_err(std::string("hf_column_stats_noalloc: no address for the static counters: ") + hipGetErrorString(e));
+    (void)hipGetLastError();
+    return HF_EDEVICE;
+  }
+  std::string why;
+  const int rc = column_stats_run(counters, h_dev, n, thresholds, n_thresholds, n_bins, below, max_abs, hist,
+                                  (hipStream_t)hip_stream, &why);
+  if (rc != HF_OK) set_create_err("hf_column_stats_noalloc: " + why);
+  return rc;
+}
+
 int32_t hf_slq_density(const double* ritz, const double* weights, const int32_t* m_eff, int32_t n_probes, int32_t m,
                        double sigma, const double* grid, int32_t n_grid, double* density) {
   if (!ritz || !weights || !m_eff || !grid || !density || n_probes <= 0 || m <= 0 || n_grid < 0 || !(sigma > 0.0))

@@ -2,6 +2,8 @@
 // Algorithm 1 and the Hessian-column statistics of the section "Banded
 // Hessians" (counts of entries below thresholds, equal-width histogram of the
 // absolute values).  All HBM-bound streaming passes.
+#include <mutex>
+
 #include "hf_internal.h"
 
 namespace hf {
@@ -160,6 +162,32 @@ hipError_t launch_colstats_pass1(const float* h, int64_t n, const ColThresholds&
 hipError_t launch_colstats_hist(const float* h, int64_t n, float scale, int nb, unsigned long long* hist, hipStream_t st) {
   hipLaunchKernelGGL(colstats_hist_kernel, dim3(colstats_blocks(n)), dim3(256), 0, st, h, n, scale, nb, hist);
   return hipGetLastError();
+}
+
+// ---- counters for callers that cannot allocate -------------------------------------
+// A fixed array in the library's device image, one copy per GPU, held until the process ends.
+// Host code must not hand the symbol itself to a kernel: its device address is looked up once per
+// device (with that device current) and only that pointer is used afterwards.
+static __device__ __align__(256) unsigned long long scratch[CS_STATS_WORDS];
+
+hipError_t colstats_static_counters(unsigned long long** out) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static unsigned long long* ptr[kMaxDevices] = {};
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lk(mu);
+  if (!ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    ptr[dev] = (unsigned long long*)p;
+  }
+  *out = ptr[dev];
+  return hipSuccess;
 }
 
 }  // namespace hf
