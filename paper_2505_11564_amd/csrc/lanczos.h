@@ -19,7 +19,7 @@ enum {
 
 constexpr int HF_MAX_M = 2000;  // most basis vectors a context may hold
 constexpr int LZ_NBLK = 2048;  // upper bound on blocks (= partial sums per basis vector) of the re-orthogonalisation kernels
-constexpr int LZ_NBLK_VEC = 4096;  // upper bound on blocks (= partial sums) of the three-term kernels
+constexpr int LZ_NBLK_VEC = 16384;  // upper bound on blocks (= partial sums) of the read-only passes over one vector
 
 hipError_t lz_norm_q0(const float* z, int64_t n, double* scal, double* partials, hipStream_t st);
 // Iteration k of the three-term recurrence without a basis: alpha_k, beta_k into scal, and

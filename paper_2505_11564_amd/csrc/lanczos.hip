@@ -42,40 +42,48 @@ __device__ __forceinline__ double block_sum_d(double v, double* red) {
   return red[0] + red[1] + red[2] + red[3];
 }
 
-// Range of 16-byte groups that block b of a streaming kernel walks: one contiguous run per block
-// (measured faster than a grid-stride walk for these passes once the grid has 4096 blocks).
-struct Range { int64_t i, end; };
-__device__ __forceinline__ Range block_range(int64_t n4) {
-  const int64_t per = (n4 + gridDim.x - 1) / gridDim.x;
-  Range g;
-  g.i = (int64_t)blockIdx.x * per + threadIdx.x;
-  g.end = min(n4, (int64_t)(blockIdx.x + 1) * per);
-  return g;
+// Streaming passes over n-vectors, 16 bytes per access, as measured at n = 1.2e8 .. 6.7e9:
+//  - passes that only read (dot products) walk the vector with a grid-wide stride, two groups in
+//    flight per thread, at most LZ_NBLK_VEC blocks (one partial sum each): 6.6-7.0 TB/s with
+//    non-temporal loads (5.3-5.9 with plain ones, or with one contiguous run per block);
+//  - passes that also write launch one thread per two groups (no loop; the thread's second group
+//    lies half a vector further on): 6.0-6.6 TB/s with non-temporal loads and stores, against
+//    4.0-5.1 for a looping grid of a few thousand blocks.
+typedef float lz_f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned lz_u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float4 ldnt4(const float* p, int64_t i4) {
+  const lz_f32x4 v = __builtin_nontemporal_load((const lz_f32x4*)p + i4);
+  return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void stnt4(float* p, int64_t i4, const float4& v) {
+  lz_f32x4 x = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(x, (lz_f32x4*)p + i4);
+}
+__device__ __forceinline__ void stnt_bf16x4(bf16* p, int64_t i4, const float4& v) {
+  const bf16 o[4] = {(bf16)v.x, (bf16)v.y, (bf16)v.z, (bf16)v.w};
+  __builtin_nontemporal_store(*(const lz_u32x2*)o, (lz_u32x2*)p + i4);
 }
 
 __device__ __forceinline__ float4 fnma4(float c, const float4& x, const float4& y) {  // y - c x
   return make_float4(fmaf(-c, x.x, y.x), fmaf(-c, x.y, y.y), fmaf(-c, x.z, y.z), fmaf(-c, x.w, y.w));
 }
+__device__ __forceinline__ float4 scale4(const float4& x, float c) { return make_float4(x.x * c, x.y * c, x.z * c, x.w * c); }
 __device__ __forceinline__ double dot4(const float4& a, const float4& b) {
   return (double)a.x * b.x + (double)a.y * b.y + (double)a.z * b.z + (double)a.w * b.w;
 }
-__device__ __forceinline__ uint2 pack_bf16x4(const float4& v) {
-  bf16 o[4] = {(bf16)v.x, (bf16)v.y, (bf16)v.z, (bf16)v.w};
-  return *(const uint2*)o;
-}
 
-// partials[block] = sum of z^2 over the block's range
+// partials[block] = sum of z^2 over the groups the block visits
 __global__ __launch_bounds__(256) void lz_sumsq_kernel(const float* __restrict__ z, int64_t n, double* __restrict__ partials) {
   __shared__ double red[4];
   double acc = 0.0;
-  const int64_t n4 = n >> 2;
-  const Range g = block_range(n4);
-#pragma unroll 2
-  for (int64_t i = g.i; i < g.end; i += 256) {
-    const float4 a = ((const float4*)z)[i];
-    acc += dot4(a, a);
+  const int64_t n4 = n >> 2, step = (int64_t)gridDim.x * 256;
+  int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  for (; i + step < n4; i += 2 * step) {
+    const float4 a = ldnt4(z, i), b = ldnt4(z, i + step);
+    acc += dot4(a, a) + dot4(b, b);
   }
-  for (int64_t i = (n4 << 2) + (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) acc += (double)z[i] * z[i];
+  if (i < n4) { const float4 a = ldnt4(z, i); acc += dot4(a, a); }
+  for (int64_t e = (n4 << 2) + (int64_t)blockIdx.x * 256 + threadIdx.x; e < n; e += step) acc += (double)z[e] * z[e];
   acc = block_sum_d(acc, red);
   if (threadIdx.x == 0) partials[blockIdx.x] = acc;
 }
@@ -87,19 +95,24 @@ __global__ __launch_bounds__(256) void lz3_dots_kernel(const float* __restrict__
                                                        double* __restrict__ partials) {
   __shared__ double red[4];
   double a0 = 0.0, a1 = 0.0, a2 = 0.0;
-  const int64_t n4 = n >> 2;
-  const Range g = block_range(n4);
-#pragma unroll 2
-  for (int64_t i = g.i; i < g.end; i += 256) {
-    float4 rv = ((const float4*)w)[i];
-    const float4 qv = ((const float4*)q)[i];
-    if (use_prev) rv = fnma4(bprev, ((const float4*)qp)[i], rv);
+  const int64_t n4 = n >> 2, step = (int64_t)gridDim.x * 256;
+  auto take = [&](float4 rv, const float4& qv, const float4& pv) {
+    if (use_prev) rv = fnma4(bprev, pv, rv);
     a0 += dot4(rv, qv); a1 += dot4(rv, rv); a2 += dot4(qv, qv);
+  };
+  const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
+  int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  for (; i + step < n4; i += 2 * step) {
+    const float4 r0 = ldnt4(w, i), r1 = ldnt4(w, i + step), q0 = ldnt4(q, i), q1 = ldnt4(q, i + step);
+    const float4 p0 = use_prev ? ldnt4(qp, i) : zero, p1 = use_prev ? ldnt4(qp, i + step) : zero;
+    take(r0, q0, p0);
+    take(r1, q1, p1);
   }
-  for (int64_t i = (n4 << 2) + (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
-    float rv = w[i];
-    if (use_prev) rv = fmaf(-bprev, qp[i], rv);
-    a0 += (double)rv * q[i]; a1 += (double)rv * rv; a2 += (double)q[i] * q[i];
+  if (i < n4) take(ldnt4(w, i), ldnt4(q, i), use_prev ? ldnt4(qp, i) : zero);
+  for (int64_t e = (n4 << 2) + (int64_t)blockIdx.x * 256 + threadIdx.x; e < n; e += step) {
+    float rv = w[e];
+    if (use_prev) rv = fmaf(-bprev, qp[e], rv);
+    a0 += (double)rv * q[e]; a1 += (double)rv * rv; a2 += (double)q[e] * q[e];
   }
   a0 = block_sum_d(a0, red);
   a1 = block_sum_d(a1, red);
@@ -138,19 +151,17 @@ __global__ __launch_bounds__(256) void lz3_norm_kernel(const float* __restrict__
   if (scal[S_REDO] == 0.0) return;
   const float al = (float)scal[S_ALPHA];
   double acc = 0.0;
-  const int64_t n4 = n >> 2;
-  const Range g = block_range(n4);
-#pragma unroll 2
-  for (int64_t i = g.i; i < g.end; i += 256) {
-    float4 rv = ((const float4*)w)[i];
-    if (use_prev) rv = fnma4(bprev, ((const float4*)qp)[i], rv);
-    rv = fnma4(al, ((const float4*)q)[i], rv);
+  const int64_t n4 = n >> 2, step = (int64_t)gridDim.x * 256;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += step) {
+    float4 rv = ldnt4(w, i);
+    if (use_prev) rv = fnma4(bprev, ldnt4(qp, i), rv);
+    rv = fnma4(al, ldnt4(q, i), rv);
     acc += dot4(rv, rv);
   }
-  for (int64_t i = (n4 << 2) + (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
-    float rv = w[i];
-    if (use_prev) rv = fmaf(-bprev, qp[i], rv);
-    rv = fmaf(-al, q[i], rv);
+  for (int64_t e = (n4 << 2) + (int64_t)blockIdx.x * 256 + threadIdx.x; e < n; e += step) {
+    float rv = w[e];
+    if (use_prev) rv = fmaf(-bprev, qp[e], rv);
+    rv = fmaf(-al, q[e], rv);
     acc += (double)rv * rv;
   }
   acc = block_sum_d(acc, red);
@@ -197,7 +208,8 @@ __device__ __forceinline__ bool lz_may_advance(double* scal, int idx, double tol
 
 // Three-term recurrence, last pass: qp <- (w - bprev qp - alpha q) / beta (q_{k+1} over q_{k-1}), and
 // optionally vb = its bf16 copy (the operand-type copy of the next Hessian-vector product's
-// direction, which would otherwise cost that product a pass over q_{k+1}).
+// direction, which would otherwise cost that product a pass over q_{k+1}).  One thread per two
+// 16-byte groups: i and i + gridDim.x * 256.
 __global__ __launch_bounds__(256) void lz3_normalise_kernel(const float* __restrict__ w, const float* __restrict__ q,
                                                             float* __restrict__ qp, bf16* __restrict__ vb, int64_t n,
                                                             int use_prev, float bprev, double* scal, double tol,
@@ -205,53 +217,67 @@ __global__ __launch_bounds__(256) void lz3_normalise_kernel(const float* __restr
   if (!lz_may_advance(scal, S_BETA, tol, flags)) return;
   const float al = (float)scal[S_ALPHA];
   const float inv = (float)(1.0 / scal[S_BETA]);
-  const int64_t n4 = n >> 2;
-  const Range g = block_range(n4);
-#pragma unroll 2
-  for (int64_t i = g.i; i < g.end; i += 256) {
-    float4 rv = ((const float4*)w)[i];
-    const float4 qv = ((const float4*)q)[i];
-    if (use_prev) rv = fnma4(bprev, ((const float4*)qp)[i], rv);
-    rv = fnma4(al, qv, rv);
-    rv.x *= inv; rv.y *= inv; rv.z *= inv; rv.w *= inv;
-    ((float4*)qp)[i] = rv;
-    if (vb) ((uint2*)vb)[i] = pack_bf16x4(rv);
+  const int64_t n4 = n >> 2, half = (int64_t)gridDim.x * 256;
+  const int64_t i0 = (int64_t)blockIdx.x * 256 + threadIdx.x, i1 = i0 + half;
+  const bool ok0 = i0 < n4, ok1 = i1 < n4;
+  const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
+  float4 r0 = zero, r1 = zero, q0 = zero, q1 = zero, p0 = zero, p1 = zero;
+  if (ok0) { r0 = ldnt4(w, i0); q0 = ldnt4(q, i0); if (use_prev) p0 = ldnt4(qp, i0); }
+  if (ok1) { r1 = ldnt4(w, i1); q1 = ldnt4(q, i1); if (use_prev) p1 = ldnt4(qp, i1); }
+  if (ok0) {
+    if (use_prev) r0 = fnma4(bprev, p0, r0);
+    r0 = scale4(fnma4(al, q0, r0), inv);
+    stnt4(qp, i0, r0);
+    if (vb) stnt_bf16x4(vb, i0, r0);
   }
-  for (int64_t i = (n4 << 2) + (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
-    float rv = w[i];
-    if (use_prev) rv = fmaf(-bprev, qp[i], rv);
-    rv = fmaf(-al, q[i], rv) * inv;
-    qp[i] = rv;
-    if (vb) vb[i] = (bf16)rv;
+  if (ok1) {
+    if (use_prev) r1 = fnma4(bprev, p1, r1);
+    r1 = scale4(fnma4(al, q1, r1), inv);
+    stnt4(qp, i1, r1);
+    if (vb) stnt_bf16x4(vb, i1, r1);
+  }
+  const int64_t e = (n4 << 2) + threadIdx.x;   // ragged tail: at most three elements, block 0
+  if (blockIdx.x == 0 && e < n) {
+    float rv = w[e];
+    if (use_prev) rv = fmaf(-bprev, qp[e], rv);
+    rv = fmaf(-al, q[e], rv) * inv;
+    qp[e] = rv;
+    if (vb) vb[e] = (bf16)rv;
   }
 }
 
 // q_{k+1} = src / scal[idx] into any of: dst (fp32 working vector), basis (its row of the stored
 // basis, fp32 or bf16 rounded to nearest even), vb (bf16 copy for the next Hessian-vector product).
+// One thread per two 16-byte groups.
 template <typename BT>
 __global__ __launch_bounds__(256) void lz_scale_kernel(const float* __restrict__ src, float* __restrict__ dst,
                                                        BT* __restrict__ basis, bf16* __restrict__ vb, int64_t n,
                                                        double* scal, int idx, double tol, const int* flags) {
   if (!lz_may_advance(scal, idx, tol, flags)) return;
   const float inv = (float)(1.0 / scal[idx]);
-  const int64_t n4 = n >> 2;
-  const Range g = block_range(n4);
-#pragma unroll 2
-  for (int64_t i = g.i; i < g.end; i += 256) {
-    float4 v = ((const float4*)src)[i];
-    v.x *= inv; v.y *= inv; v.z *= inv; v.w *= inv;
-    if (dst) ((float4*)dst)[i] = v;
+  const int64_t n4 = n >> 2, half = (int64_t)gridDim.x * 256;
+  const int64_t i0 = (int64_t)blockIdx.x * 256 + threadIdx.x, i1 = i0 + half;
+  const bool ok0 = i0 < n4, ok1 = i1 < n4;
+  float4 v0 = make_float4(0.f, 0.f, 0.f, 0.f), v1 = v0;
+  if (ok0) v0 = ldnt4(src, i0);
+  if (ok1) v1 = ldnt4(src, i1);
+  auto put = [&](int64_t i, float4 v) {
+    v = scale4(v, inv);
+    if (dst) stnt4(dst, i, v);
     if (basis) {
-      if (sizeof(BT) == 4) ((float4*)basis)[i] = v;
-      else ((uint2*)basis)[i] = pack_bf16x4(v);
+      if (sizeof(BT) == 4) stnt4((float*)basis, i, v);
+      else stnt_bf16x4((bf16*)basis, i, v);
     }
-    if (vb) ((uint2*)vb)[i] = pack_bf16x4(v);
-  }
-  for (int64_t i = (n4 << 2) + (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
-    const float v = src[i] * inv;
-    if (dst) dst[i] = v;
-    if (basis) basis[i] = (BT)v;
-    if (vb) vb[i] = (bf16)v;
+    if (vb) stnt_bf16x4(vb, i, v);
+  };
+  if (ok0) put(i0, v0);
+  if (ok1) put(i1, v1);
+  const int64_t e = (n4 << 2) + threadIdx.x;
+  if (blockIdx.x == 0 && e < n) {
+    const float v = src[e] * inv;
+    if (dst) dst[e] = v;
+    if (basis) basis[e] = (BT)v;
+    if (vb) vb[e] = (bf16)v;
   }
 }
 
@@ -278,7 +304,6 @@ __device__ __forceinline__ float4 load4<bf16>(const bf16* p, int64_t i4) {
 constexpr int LZ_SLICE = 4096;            // elements per slice
 constexpr int LZ_RPT = LZ_SLICE / 256;    // r elements per thread
 
-typedef float lz_f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned lz_u32x4 __attribute__((ext_vector_type(4)));
 template <typename BT> struct QVec;
 template <> struct QVec<float> {  // 4 elements per 16 B load, 16 loads per slice
@@ -517,10 +542,13 @@ __global__ void lz_widen_kernel(const BT* src, float* dst, int64_t n) {
 
 // ------------------------------------------------------------- launchers ----
 
+// grid of a pass that only reads: grid-wide stride, two groups per thread in flight
 static int vec_blocks(int64_t n) {
-  const int64_t want = (n / 4 + 255) / 256;
+  const int64_t want = (n / 4 + 511) / 512;
   return (int)std::max<int64_t>(1, std::min<int64_t>(want, LZ_NBLK_VEC));
 }
+// grid of a pass that writes: one thread per two groups
+static unsigned wide_blocks(int64_t n) { return (unsigned)std::max<int64_t>(1, (n / 4 + 511) / 512); }
 
 hipError_t lz_norm_q0(const float* z, int64_t n, double* scal, double* partials, hipStream_t st) {
   const int nb = vec_blocks(n);
@@ -537,13 +565,13 @@ hipError_t lz3_update(const float* w, const float* q, float* qp, bf16* vb, int64
   hipLaunchKernelGGL(lz3_finish_kernel, dim3(1), dim3(256), 0, st, partials, nb, scal);
   hipLaunchKernelGGL(lz3_norm_kernel, dim3(nb), dim3(256), 0, st, w, q, qp, n, use_prev, bp, scal, partials);
   hipLaunchKernelGGL(lz_finish_kernel, dim3(1), dim3(256), 0, st, partials, nb, 2, 0, scal);
-  hipLaunchKernelGGL(lz3_normalise_kernel, dim3(nb), dim3(256), 0, st, w, q, qp, vb, n, use_prev, bp, scal, tol, flags);
+  hipLaunchKernelGGL(lz3_normalise_kernel, dim3(wide_blocks(n)), dim3(256), 0, st, w, q, qp, vb, n, use_prev, bp, scal, tol, flags);
   return hipGetLastError();
 }
 
 hipError_t lz_scale(const float* src, float* dst, void* basis, int basis_bf16, bf16* vb, int64_t n, double* scal, int idx,
                     double tol, const int* flags, hipStream_t st) {
-  const int nb = vec_blocks(n);
+  const unsigned nb = wide_blocks(n);
   if (basis_bf16) hipLaunchKernelGGL(lz_scale_kernel<bf16>, dim3(nb), dim3(256), 0, st, src, dst, (bf16*)basis, vb, n, scal, idx, tol, flags);
   else hipLaunchKernelGGL(lz_scale_kernel<float>, dim3(nb), dim3(256), 0, st, src, dst, (float*)basis, vb, n, scal, idx, tol, flags);
   return hipGetLastError();
