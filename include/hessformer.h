@@ -76,6 +76,11 @@ typedef enum { HF_ARCH_MLP = 0, HF_ARCH_GPT = 1, HF_ARCH_LLAMA = 2 } hf_arch;
 typedef enum { HF_F32 = 0, HF_BF16 = 1, HF_NONE = 2 /* basis_dtype only: store no basis */ } hf_dtype;
 typedef enum { HF_REORTH_NONE = 0, HF_REORTH_FULL = 1 } hf_reorth;
 typedef enum { HF_ACT_GELU_ERF = 0, HF_ACT_GELU_TANH = 1 } hf_activation;
+/* How attention is evaluated (same result up to rounding): streamed over key / query tiles with
+ * the probabilities recomputed in the backward sweep (bf16 parameters, head width 32, 64 or 128),
+ * or with the S x S probabilities and score adjoints of every layer stored.  AUTO takes the
+ * streamed kernels where they are supported and measured faster. */
+typedef enum { HF_ATTN_AUTO = 0, HF_ATTN_STREAMED = 1, HF_ATTN_STORED = 2 } hf_attention;
 
 /* Model description.  MLP uses mlp_*; GPT/LLAMA use the transformer fields.
  * GPT: pre-LayerNorm decoder, learned positions, GELU (erf or tanh form, see
@@ -102,6 +107,8 @@ typedef struct {
                              reads key/value head h / (n_head / n_kv_head)); Wk, Wv are
                              [d_model, n_kv_head * d_model / n_head].  0 = n_head.  Must divide
                              n_head; GPT takes 0 or n_head. */
+  int32_t attention;      /* hf_attention; HF_ATTN_STREAMED where it is not supported: hf_create
+                             returns HF_ESHAPE */
 } hf_model_desc;
 
 /* ---- host-only helpers (no GPU needed) ---------------------------------- */

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhessformer_hip.so")
-SOURCES = ["gemm.hip", "gemm_mfma.hip", "gemm_dual.hip", "ops.hip", "lanczos.hip", "probe.hip", "engine.hip", "api.hip"]
+SOURCES = ["gemm.hip", "gemm_mfma.hip", "gemm_dual.hip", "ops.hip", "attn_flash.hip", "lanczos.hip", "probe.hip", "engine.hip", "api.hip"]
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument",

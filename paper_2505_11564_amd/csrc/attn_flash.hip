@@ -1,0 +1,630 @@
+// Causal softmax attention with its tangent, streamed tile by tile (bf16 operands, fp32
+// accumulation): forward, and the backward sweep that recomputes the probabilities from saved row
+// statistics, so that no S x S tensor ever reaches memory.  Section "Distributed Pearlmutter"
+// (Algorithm 1) of the paper disables fused attention because its autograd kernel has no double
+// backward; here the second-order terms are written out, per (batch, head), with c = 1/sqrt(dh):
+//   S = c Q K^T            S_t = c (Q_t K^T + Q K_t^T)
+//   P = softmax(S)         P_t = P (S_t - r),  r = rowsum(P S_t)
+//   O = P V                O_t = P_t V + P V_t
+//   dV = P^T dO            dV_t = P_t^T dO + P^T dO_t
+//   dP = dO V^T            dP_t = dO_t V^T + dO V_t^T
+//   dS = P (dP - delta)    dS_t = P_t (dP - delta) + P (dP_t - delta_t)
+//   dQ = c dS K            dQ_t = c (dS_t K + dS K_t)
+//   dK = c dS^T Q          dK_t = c (dS_t^T Q + dS^T Q_t)
+// delta = rowsum(P dP) = <dO, O> and delta_t = <dO_t, O> + <dO, O_t> come from attn_delta_kernel.
+// The primal scores and P V take the low-order halves of their bf16 operands as extra terms
+// (A_hi B_hi + A_lo B_hi + A_hi B_lo); tangents and adjoints use the high halves.
+//
+// Kernel shapes (v_mfma_f32_32x32x16_bf16, 4 wavefronts of 64 lanes per block):
+//   forward, dQ : a block owns 128 queries (32 per wave) of one head and walks the key tiles
+//                 0 .. diagonal, 32 keys at a time, staged in LDS.  The products are formed
+//                 transposed, S^T = K Q^T (32 keys x 32 queries per wave): the accumulator layout
+//                 then has one query per lane (rows = keys spread over the 16 registers), so the
+//                 softmax statistics are per lane plus one exchange between the lane halves, and
+//                 the probabilities are already the B operand (k = keys) of O^T = V^T P^T; the
+//                 k index of that product is a permutation of the keys that the A operand (V^T,
+//                 read from LDS with transposing reads) follows.
+//   dK, dV      : a block owns 128 keys (32 per wave) of one key/value head and walks the query
+//                 tiles diagonal .. end (and the query heads of its group), with S = Q K^T formed
+//                 untransposed so that one key sits per lane and P, dS are the B operands of
+//                 dV^T = dO^T P and dK^T = Q^T dS.
+// Online softmax: running maximum m, sum l and tangent sum per query; the forward saves
+// (m + log l, r) per row, the backward recomputes P = exp(S - lse), P_t = P (S_t - r).
+#include "gemm_mfma_common.h"
+
+namespace hf {
+
+namespace {
+
+#define HF_MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16((a), (b), (c), 0, 0, 0)
+typedef unsigned at_u32x4 __attribute__((ext_vector_type(4)));
+typedef float at_f32x4 __attribute__((ext_vector_type(4)));
+
+// LDS tile of 32 rows x DH bf16, rows contiguous.  Two permutations of a row's 16-byte chunks:
+// kc for tiles read as fragments with one tile row per lane (16 consecutive rows at one chunk
+// index fall on 16 different bank groups), rc for tiles read with transposing reads (four
+// consecutive rows at one column fall on four different quarters of the banks).
+template <int DH>
+__device__ __forceinline__ int kc_off(int r, int c) { return r * DH + ((c ^ ((r / (128 / DH)) & (DH / 8 - 1))) << 3); }
+template <int DH>
+__device__ __forceinline__ int rc_off(int r, int c) { return r * DH + ((c ^ rc_rot(r, DH)) << 3); }
+
+// Fragment with tile rows on lanes: lane holds row lane % 32, columns kk*16 + (lane/32)*8 .. +8.
+template <int DH>
+__device__ __forceinline__ bf16x8 frag_rows(const HF_LDS bf16* tile, int lane, int kk) {
+  return *(const HF_LDS bf16x8*)(tile + kc_off<DH>(lane & 31, kk * 2 + (lane >> 5)));
+}
+// Fragment with tile columns on lanes (the tile transposed): lane holds column rt*32 + lane % 32 and,
+// as its 8 values, the tile rows ks*16 + {4G .. 4G+3, 8+4G .. 8+4G+3}, G = lane / 32: the order in
+// which a 32x32 accumulator holds its rows in registers 8 ks .. 8 ks + 7 (row of register v:
+// 8 (v/4) + 4 G + v % 4), so an accumulator tile converted to bf16 multiplies against it directly.
+template <int DH>
+__device__ __forceinline__ bf16x8 frag_cols(const HF_LDS bf16* tile, int lane, int rt, int ks) {
+  const int i = lane & 15, g = lane >> 4;
+  const int kq = ks * 16 + (g >> 1) * 4 + (i >> 2);
+  const int c = rt * 32 + (g & 1) * 16 + (i & 3) * 4;
+  const HF_LDS bf16* p0 = tile + kq * DH + ((((c >> 3) ^ rc_rot(kq, DH))) << 3) + (c & 7);
+  const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((HF_LDS bf16x4*)p0);
+  const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((HF_LDS bf16x4*)(p0 + 8 * DH));  // rows + 8: same rotation
+  return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+
+__device__ __forceinline__ bf16x8 pack8(const float* x) {
+  bf16x8 v;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) v[j] = (bf16)x[j];
+  return v;
+}
+
+// Global -> registers -> LDS staging of NT tiles of 32 rows x DH (16 bytes per thread and step;
+// rows beyond rmax are clamped to the last valid row and masked by the caller).
+template <int DH>
+struct StageDim {
+  static constexpr int CH = 4 * DH;               // 16-byte chunks per tile
+  static constexpr int PER = (CH + 255) / 256;    // chunks per thread and tile
+};
+template <int DH, int I>
+__device__ __forceinline__ void stage_load_one(at_u32x4 (&pre)[StageDim<DH>::PER], const bf16* src, int64_t ld, int r0, int rmax, int t) {
+  constexpr int CH = StageDim<DH>::CH, PER = StageDim<DH>::PER;
+#pragma unroll
+  for (int u = 0; u < PER; ++u) {
+    const int idx = t + 256 * u;
+    if (CH >= 256 || idx < CH) {
+      const int row = idx / (DH / 8), c = idx % (DH / 8);
+      const int rr = min(r0 + row, rmax - 1);
+      pre[u] = *(const at_u32x4*)(src + (int64_t)rr * ld + c * 8);
+    }
+  }
+}
+// kc_tile / rc_tile: LDS tile that takes the chunks in the kc / rc permutation (-1: none)
+template <int DH, int KC_TILE, int RC_TILE>
+__device__ __forceinline__ void stage_store_one(const at_u32x4 (&pre)[StageDim<DH>::PER], HF_LDS bf16* sm, int t) {
+  constexpr int CH = StageDim<DH>::CH, PER = StageDim<DH>::PER;
+#pragma unroll
+  for (int u = 0; u < PER; ++u) {
+    const int idx = t + 256 * u;
+    if (CH >= 256 || idx < CH) {
+      const int row = idx / (DH / 8), c = idx % (DH / 8);
+      if (KC_TILE >= 0) *(HF_LDS at_u32x4*)(sm + KC_TILE * (32 * DH) + kc_off<DH>(row, c)) = pre[u];
+      if (RC_TILE >= 0) *(HF_LDS at_u32x4*)(sm + RC_TILE * (32 * DH) + rc_off<DH>(row, c)) = pre[u];
+    }
+  }
+}
+
+// Four consecutive columns (col .. col+3) of row `row` of a [rows, ld] result, bf16 or fp32.
+__device__ __forceinline__ void store4(void* base, int f32, int64_t row, int64_t ld, int col, float a, float b, float c, float d) {
+  if (f32) {
+    *(float4*)((float*)base + row * ld + col) = make_float4(a, b, c, d);
+  } else {
+    const bf16 o[4] = {(bf16)a, (bf16)b, (bf16)c, (bf16)d};
+    *(uint2*)((bf16*)base + row * ld + col) = *(const uint2*)o;
+  }
+}
+
+// block -> (batch * head index, tile): whole heads per XCD (launch order L goes to XCD L % 8, so
+// head hh runs on XCD hh % 8 and its operands stay in that L2), tiles in the given order.
+__device__ __forceinline__ bool block_map(int nheads, int ntiles, int& hh, int& tile) {
+  const int L = blockIdx.x, xcd = L & 7, slot = L >> 3;
+  hh = (slot / ntiles) * 8 + xcd;
+  tile = slot % ntiles;
+  return hh < nheads;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------ forward ----
+
+template <int DH>
+__global__ __launch_bounds__(256) void attn_fwd_kernel(const AttnP p) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
+  HF_LDS bf16* sm = (HF_LDS bf16*)smem_raw;
+  constexpr int TILE = 32 * DH, KS = DH / 16, RT = DH / 32;
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int nqt = (p.S + 127) / 128;
+  int hh, tile;
+  if (!block_map(p.B * p.H, nqt, hh, tile)) return;
+  const int qt = nqt - 1 - tile;  // long rows first
+  const int b = hh / p.H, h = hh % p.H, hk = h / p.grp;
+  const int m0 = qt * 128, mw = m0 + wave * 32;
+  const int64_t row0 = (int64_t)b * p.S;
+  const int mq = mw + (lane & 31);            // this lane's query
+  const int qm = min(mq, p.S - 1);
+
+  bf16x8 qh[KS], ql[KS], qd[KS];
+  {
+    const int64_t off = (row0 + qm) * p.ldq + (int64_t)h * DH + (lane >> 5) * 8;
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) {
+      qh[kk] = *(const bf16x8*)(p.qkv + off + kk * 16);
+      ql[kk] = *(const bf16x8*)(p.qkv_lo + off + kk * 16);
+      qd[kk] = *(const bf16x8*)(p.qkv_t + off + kk * 16);
+    }
+  }
+  const int64_t ok = row0 * p.ldq + p.offK + (int64_t)hk * DH, ov = row0 * p.ldq + p.offV + (int64_t)hk * DH;
+  const bf16 *sKh = p.qkv + ok, *sKl = p.qkv_lo + ok, *sKd = p.qkv_t + ok, *sVh = p.qkv + ov, *sVl = p.qkv_lo + ov, *sVd = p.qkv_t + ov;
+  const HF_LDS bf16 *Kh = sm, *Kl = sm + TILE, *Kd = sm + 2 * TILE, *Vh = sm + 3 * TILE, *Vl = sm + 4 * TILE, *Vd = sm + 5 * TILE;
+
+  f32x16 o[RT], a1[RT];
+#pragma unroll
+  for (int i = 0; i < RT; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { o[i][v] = 0.f; a1[i][v] = 0.f; }
+  float m_run = -INFINITY, l_run = 0.f, rs_run = 0.f;
+
+  const int n_end = min(p.S, m0 + 128);
+  const int nkt = (n_end + 31) / 32;
+  constexpr int PER = StageDim<DH>::PER;
+  at_u32x4 g0[PER], g1[PER], g2[PER], g3[PER], g4[PER], g5[PER];
+  auto load_stage = [&](int r0) {
+    stage_load_one<DH, 0>(g0, sKh, p.ldq, r0, p.S, t); stage_load_one<DH, 1>(g1, sKl, p.ldq, r0, p.S, t);
+    stage_load_one<DH, 2>(g2, sKd, p.ldq, r0, p.S, t); stage_load_one<DH, 3>(g3, sVh, p.ldq, r0, p.S, t);
+    stage_load_one<DH, 4>(g4, sVl, p.ldq, r0, p.S, t); stage_load_one<DH, 5>(g5, sVd, p.ldq, r0, p.S, t);
+  };
+  load_stage(0);
+  for (int kt = 0; kt < nkt; ++kt) {
+    const int n0 = kt * 32;
+    __syncthreads();  // the previous tile has been consumed
+    stage_store_one<DH, 0, -1>(g0, sm, t); stage_store_one<DH, 1, -1>(g1, sm, t); stage_store_one<DH, 2, -1>(g2, sm, t);
+    stage_store_one<DH, -1, 3>(g3, sm, t); stage_store_one<DH, -1, 4>(g4, sm, t); stage_store_one<DH, -1, 5>(g5, sm, t);
+    __syncthreads();
+    if (kt + 1 < nkt) load_stage(n0 + 32);
+    if (n0 > mw + 31 || mw >= p.S) continue;  // (wave-uniform) keys beyond this wave's diagonal, or no query
+    f32x16 st, su;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { st[v] = 0.f; su[v] = 0.f; }
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) {
+      const bf16x8 kh = frag_rows<DH>(Kh, lane, kk), kl = frag_rows<DH>(Kl, lane, kk), kd = frag_rows<DH>(Kd, lane, kk);
+      st = HF_MFMA(kh, qh[kk], st);
+      st = HF_MFMA(kl, qh[kk], st);
+      st = HF_MFMA(kh, ql[kk], st);
+      su = HF_MFMA(kd, qh[kk], su);
+      su = HF_MFMA(kh, qd[kk], su);
+    }
+    // register v of this lane: key n0 + 8 (v/4) + 4 (lane/32) + v%4 against query mq
+    float s[16], u[16];
+    float mx = -INFINITY;
+    const bool diag = n0 + 31 > mw;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int key = n0 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+      s[v] = st[v] * p.scale;
+      u[v] = su[v] * p.scale;
+      if (diag && key > mq) s[v] = -INFINITY;
+      mx = fmaxf(mx, s[v]);
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(m_run, mx);      // finite: key n0 <= mw <= mq is never masked
+    const float alpha = __expf(m_run - m_new);  // 0 on the first tile
+    float ls = 0.f, rsum = 0.f;
+    float eu[16];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      s[v] = __expf(s[v] - m_new);
+      eu[v] = s[v] * u[v];
+      ls += s[v];
+      rsum += eu[v];
+    }
+    l_run = l_run * alpha + ls;
+    rs_run = rs_run * alpha + rsum;
+    m_run = m_new;
+    if (__any(alpha != 1.f)) {
+#pragma unroll
+      for (int i = 0; i < RT; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) { o[i][v] *= alpha; a1[i][v] *= alpha; }
+    }
+    bf16x8 eh[2], el[2], es[2];
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      float lo8[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const bf16 hi = (bf16)s[ks * 8 + j];
+        eh[ks][j] = hi;
+        lo8[j] = s[ks * 8 + j] - (float)hi;
+      }
+      el[ks] = pack8(lo8);
+      es[ks] = pack8(eu + ks * 8);
+    }
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        const bf16x8 vh = frag_cols<DH>(Vh, lane, rt, ks), vl = frag_cols<DH>(Vl, lane, rt, ks), vd = frag_cols<DH>(Vd, lane, rt, ks);
+        o[rt] = HF_MFMA(vh, eh[ks], o[rt]);
+        o[rt] = HF_MFMA(vh, el[ks], o[rt]);
+        o[rt] = HF_MFMA(vl, eh[ks], o[rt]);
+        a1[rt] = HF_MFMA(vh, es[ks], a1[rt]);
+        a1[rt] = HF_MFMA(vd, eh[ks], a1[rt]);
+      }
+    }
+  }
+  if (mw >= p.S) return;
+  const float l = l_run + __shfl_xor(l_run, 32, 64);
+  const float rs = rs_run + __shfl_xor(rs_run, 32, 64);
+  if (mq >= p.S) return;
+  const float inv = 1.f / l, r = rs * inv;
+  const int64_t orow = row0 + mq;
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+#pragma unroll
+    for (int g4 = 0; g4 < 4; ++g4) {
+      const int col = h * DH + rt * 32 + 8 * g4 + 4 * (lane >> 5);
+      float x[4], xl[4], xt[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float ov_ = o[rt][g4 * 4 + q];
+        x[q] = ov_ * inv;
+        xl[q] = x[q] - (float)(bf16)x[q];
+        xt[q] = (a1[rt][g4 * 4 + q] - r * ov_) * inv;
+      }
+      store4(p.o, 0, orow, p.ldo, col, x[0], x[1], x[2], x[3]);
+      store4(p.o_lo, 0, orow, p.ldo, col, xl[0], xl[1], xl[2], xl[3]);
+      store4(p.o_t, 0, orow, p.ldo, col, xt[0], xt[1], xt[2], xt[3]);
+    }
+  }
+  if (lane < 32) {
+    float* sp = p.stat + (((int64_t)b * p.H + h) * p.S + mq) * 2;
+    sp[0] = m_run + __logf(l);
+    sp[1] = r;
+  }
+}
+
+// ---------------------------------------------------------------- backward: dQ ----
+
+template <int DH>
+__global__ __launch_bounds__(256) void attn_bwd_q_kernel(const AttnP p) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
+  HF_LDS bf16* sm = (HF_LDS bf16*)smem_raw;
+  constexpr int TILE = 32 * DH, KS = DH / 16, RT = DH / 32;
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int nqt = (p.S + 127) / 128;
+  int hh, tile;
+  if (!block_map(p.B * p.H, nqt, hh, tile)) return;
+  const int qt = nqt - 1 - tile;
+  const int b = hh / p.H, h = hh % p.H, hk = h / p.grp;
+  const int m0 = qt * 128, mw = m0 + wave * 32;
+  const int64_t row0 = (int64_t)b * p.S;
+  const int mq = mw + (lane & 31);
+  const int qm = min(mq, p.S - 1);
+
+  bf16x8 qh[KS], ql[KS], qd[KS], gh[KS], gd[KS];
+  {
+    const int64_t off = (row0 + qm) * p.ldq + (int64_t)h * DH + (lane >> 5) * 8;
+    const int64_t offg = (row0 + qm) * p.lddo + (int64_t)h * DH + (lane >> 5) * 8;
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) {
+      qh[kk] = *(const bf16x8*)(p.qkv + off + kk * 16);
+      ql[kk] = *(const bf16x8*)(p.qkv_lo + off + kk * 16);
+      qd[kk] = *(const bf16x8*)(p.qkv_t + off + kk * 16);
+      gh[kk] = *(const bf16x8*)(p.dO + offg + kk * 16);
+      gd[kk] = *(const bf16x8*)(p.dO_t + offg + kk * 16);
+    }
+  }
+  const int64_t srow = ((int64_t)b * p.H + h) * p.S + qm;
+  const float lse = p.stat[srow * 2], rr = p.stat[srow * 2 + 1];
+  const float dl = p.delta[srow * 3], dlt = p.delta[srow * 3 + 1];
+
+  const int64_t ok = row0 * p.ldq + p.offK + (int64_t)hk * DH, ov = row0 * p.ldq + p.offV + (int64_t)hk * DH;
+  const bf16 *sKh = p.qkv + ok, *sKl = p.qkv_lo + ok, *sKd = p.qkv_t + ok, *sVh = p.qkv + ov, *sVd = p.qkv_t + ov;
+  // K (high half) and K_t are needed with keys on lanes (scores) and transposed (dQ^T = K^T dS^T)
+  const HF_LDS bf16 *Kh = sm, *Kl = sm + TILE, *Kd = sm + 2 * TILE, *Vh = sm + 3 * TILE, *Vd = sm + 4 * TILE;
+  const HF_LDS bf16 *KhT = sm + 5 * TILE, *KdT = sm + 6 * TILE;
+
+  f32x16 dq[RT], dqt[RT];
+#pragma unroll
+  for (int i = 0; i < RT; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { dq[i][v] = 0.f; dqt[i][v] = 0.f; }
+
+  const int n_end = min(p.S, m0 + 128);
+  const int nkt = (n_end + 31) / 32;
+  constexpr int PER = StageDim<DH>::PER;
+  at_u32x4 g0[PER], g1[PER], g2[PER], g3[PER], g4[PER];
+  auto load_stage = [&](int r0) {
+    stage_load_one<DH, 0>(g0, sKh, p.ldq, r0, p.S, t); stage_load_one<DH, 1>(g1, sKl, p.ldq, r0, p.S, t);
+    stage_load_one<DH, 2>(g2, sKd, p.ldq, r0, p.S, t); stage_load_one<DH, 3>(g3, sVh, p.ldq, r0, p.S, t);
+    stage_load_one<DH, 4>(g4, sVd, p.ldq, r0, p.S, t);
+  };
+  load_stage(0);
+  for (int kt = 0; kt < nkt; ++kt) {
+    const int n0 = kt * 32;
+    __syncthreads();
+    stage_store_one<DH, 0, 5>(g0, sm, t); stage_store_one<DH, 1, -1>(g1, sm, t); stage_store_one<DH, 2, 6>(g2, sm, t);
+    stage_store_one<DH, 3, -1>(g3, sm, t); stage_store_one<DH, 4, -1>(g4, sm, t);
+    __syncthreads();
+    if (kt + 1 < nkt) load_stage(n0 + 32);
+    if (n0 > mw + 31 || mw >= p.S) continue;
+    f32x16 st, su, dp, dpt;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { st[v] = 0.f; su[v] = 0.f; dp[v] = 0.f; dpt[v] = 0.f; }
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) {
+      const bf16x8 kh = frag_rows<DH>(Kh, lane, kk), kl = frag_rows<DH>(Kl, lane, kk), kd = frag_rows<DH>(Kd, lane, kk);
+      const bf16x8 vh = frag_rows<DH>(Vh, lane, kk), vd = frag_rows<DH>(Vd, lane, kk);
+      st = HF_MFMA(kh, qh[kk], st);
+      st = HF_MFMA(kl, qh[kk], st);
+      st = HF_MFMA(kh, ql[kk], st);
+      su = HF_MFMA(kd, qh[kk], su);
+      su = HF_MFMA(kh, qd[kk], su);
+      dp = HF_MFMA(vh, gh[kk], dp);       // dP^T = V dO^T
+      dpt = HF_MFMA(vh, gd[kk], dpt);     // dP_t^T = V dO_t^T + V_t dO^T
+      dpt = HF_MFMA(vd, gh[kk], dpt);
+    }
+    float ds[16], dst_[16];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int key = n0 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+      const float pr = key > mq ? 0.f : __expf(st[v] * p.scale - lse);
+      const float pt = pr * (su[v] * p.scale - rr);
+      ds[v] = pr * (dp[v] - dl);
+      dst_[v] = pt * (dp[v] - dl) + pr * (dpt[v] - dlt);
+    }
+    bf16x8 dsb[2], dtb[2];
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) { dsb[ks] = pack8(ds + ks * 8); dtb[ks] = pack8(dst_ + ks * 8); }
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        const bf16x8 kT = frag_cols<DH>(KhT, lane, rt, ks), kdT = frag_cols<DH>(KdT, lane, rt, ks);
+        dq[rt] = HF_MFMA(kT, dsb[ks], dq[rt]);
+        dqt[rt] = HF_MFMA(kT, dtb[ks], dqt[rt]);
+        dqt[rt] = HF_MFMA(kdT, dsb[ks], dqt[rt]);
+      }
+    }
+  }
+  if (mq >= p.S) return;
+  const int64_t orow = row0 + mq;
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+#pragma unroll
+    for (int g4 = 0; g4 < 4; ++g4) {
+      const int col = h * DH + rt * 32 + 8 * g4 + 4 * (lane >> 5);
+      store4(p.dq, p.dq_f32, orow, p.lddq, col, dq[rt][g4 * 4] * p.scale, dq[rt][g4 * 4 + 1] * p.scale, dq[rt][g4 * 4 + 2] * p.scale,
+             dq[rt][g4 * 4 + 3] * p.scale);
+      store4(p.dq_t, p.dq_f32, orow, p.lddq, col, dqt[rt][g4 * 4] * p.scale, dqt[rt][g4 * 4 + 1] * p.scale,
+             dqt[rt][g4 * 4 + 2] * p.scale, dqt[rt][g4 * 4 + 3] * p.scale);
+    }
+  }
+}
+
+// ------------------------------------------------------------ backward: dK, dV ----
+// WHAT & 1: dV, dV_t;  WHAT & 2: dK, dK_t.
+
+template <int DH, int WHAT>
+__global__ __launch_bounds__(256) void attn_bwd_kv_kernel(const AttnP p) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
+  HF_LDS bf16* sm = (HF_LDS bf16*)smem_raw;
+  constexpr int TILE = 32 * DH, KS = DH / 16, RT = DH / 32;
+  constexpr bool DV = (WHAT & 1) != 0, DK = (WHAT & 2) != 0;
+  // LDS tiles: Q hi / lo / t with queries on lanes; dO, dO_t the same (dK only); transposed copies
+  // of Q hi / t (dK) and of dO, dO_t (dV)
+  constexpr int T_QH = 0, T_QL = 1, T_QD = 2;
+  constexpr int T_GH = DK ? 3 : -1, T_GD = DK ? 4 : -1;
+  constexpr int NKC = DK ? 5 : 3;
+  constexpr int T_QHT = DK ? NKC : -1, T_QDT = DK ? NKC + 1 : -1;
+  constexpr int T_GHT = DV ? NKC + (DK ? 2 : 0) : -1, T_GDT = DV ? NKC + (DK ? 2 : 0) + 1 : -1;
+  constexpr int NTILE = NKC + (DK ? 2 : 0) + (DV ? 2 : 0);
+  HF_LDS float* stats = (HF_LDS float*)(sm + NTILE * TILE);  // [32 queries][4] = lse, r, delta, delta_t
+
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int nkb = (p.S + 127) / 128;
+  const int Hkv = p.H / p.grp;
+  int hh, kb;
+  if (!block_map(p.B * Hkv, nkb, hh, kb)) return;  // key block 0 (the longest) first
+  const int b = hh / Hkv, hk = hh % Hkv;
+  const int k0 = kb * 128, kw = k0 + wave * 32;
+  const int64_t row0 = (int64_t)b * p.S;
+  const int nk = kw + (lane & 31);            // this lane's key
+  const int nkc = min(nk, p.S - 1);
+
+  bf16x8 kh[KS], kl[KS], kd[KS], vh[DK ? KS : 1], vd[DK ? KS : 1];
+  {
+    const int64_t off = (row0 + nkc) * p.ldq + (int64_t)hk * DH + (lane >> 5) * 8;
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) {
+      kh[kk] = *(const bf16x8*)(p.qkv + p.offK + off + kk * 16);
+      kl[kk] = *(const bf16x8*)(p.qkv_lo + p.offK + off + kk * 16);
+      kd[kk] = *(const bf16x8*)(p.qkv_t + p.offK + off + kk * 16);
+      if (DK) {
+        vh[kk] = *(const bf16x8*)(p.qkv + p.offV + off + kk * 16);
+        vd[kk] = *(const bf16x8*)(p.qkv_t + p.offV + off + kk * 16);
+      }
+    }
+  }
+  f32x16 dv[DV ? RT : 1], dvt[DV ? RT : 1], dk[DK ? RT : 1], dkt[DK ? RT : 1];
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+#pragma unroll
+    for (int i = 0; i < (DV ? RT : 1); ++i) { dv[i][v] = 0.f; dvt[i][v] = 0.f; }
+#pragma unroll
+    for (int i = 0; i < (DK ? RT : 1); ++i) { dk[i][v] = 0.f; dkt[i][v] = 0.f; }
+  }
+  const int nqs = (p.S - k0 + 31) / 32;  // query sub-tiles k0, k0 + 32, ... (k0 < S)
+
+  for (int j = 0; j < p.grp; ++j) {
+    const int h = hk * p.grp + j;
+    const int64_t oq = row0 * p.ldq + (int64_t)h * DH, og = row0 * p.lddo + (int64_t)h * DH;
+    const bf16 *sQh = p.qkv + oq, *sQl = p.qkv_lo + oq, *sQd = p.qkv_t + oq, *sGh = p.dO + og, *sGd = p.dO_t + og;
+    const int64_t sbase = ((int64_t)b * p.H + h) * p.S;
+    constexpr int PER = StageDim<DH>::PER;
+    at_u32x4 g0[PER], g1[PER], g2[PER], g3[PER], g4[PER];
+    auto load_stage = [&](int r0) {
+      stage_load_one<DH, 0>(g0, sQh, p.ldq, r0, p.S, t); stage_load_one<DH, 1>(g1, sQl, p.ldq, r0, p.S, t);
+      stage_load_one<DH, 2>(g2, sQd, p.ldq, r0, p.S, t); stage_load_one<DH, 3>(g3, sGh, p.lddo, r0, p.S, t);
+      stage_load_one<DH, 4>(g4, sGd, p.lddo, r0, p.S, t);
+    };
+    load_stage(k0);
+    at_f32x4 spre = {0.f, 0.f, 0.f, 0.f};
+    auto load_stats = [&](int q0) {
+      if (t < 32) {
+        const int q = min(q0 + t, p.S - 1);
+        spre = at_f32x4{p.stat[(sbase + q) * 2], p.stat[(sbase + q) * 2 + 1], p.delta[(sbase + q) * 3], p.delta[(sbase + q) * 3 + 1]};
+      }
+    };
+    load_stats(k0);
+    for (int qs = 0; qs < nqs; ++qs) {
+      const int q0 = k0 + qs * 32;
+      __syncthreads();
+      stage_store_one<DH, T_QH, T_QHT>(g0, sm, t); stage_store_one<DH, T_QL, -1>(g1, sm, t); stage_store_one<DH, T_QD, T_QDT>(g2, sm, t);
+      stage_store_one<DH, T_GH, T_GHT>(g3, sm, t); stage_store_one<DH, T_GD, T_GDT>(g4, sm, t);
+      if (t < 32) *(HF_LDS at_f32x4*)(stats + t * 4) = spre;
+      __syncthreads();
+      if (qs + 1 < nqs) { load_stage(q0 + 32); load_stats(q0 + 32); }
+      if (q0 + 31 < kw || kw >= p.S) continue;  // (wave-uniform) every query of the tile precedes this wave's keys
+      f32x16 st, su, dp, dpt;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) { st[v] = 0.f; su[v] = 0.f; dp[v] = 0.f; dpt[v] = 0.f; }
+#pragma unroll
+      for (int kk = 0; kk < KS; ++kk) {
+        const bf16x8 qa = frag_rows<DH>(sm + T_QH * TILE, lane, kk), qb = frag_rows<DH>(sm + T_QL * TILE, lane, kk),
+                     qc = frag_rows<DH>(sm + T_QD * TILE, lane, kk);
+        st = HF_MFMA(qa, kh[kk], st);
+        st = HF_MFMA(qb, kh[kk], st);
+        st = HF_MFMA(qa, kl[kk], st);
+        su = HF_MFMA(qc, kh[kk], su);
+        su = HF_MFMA(qa, kd[kk], su);
+        if (DK) {
+          const bf16x8 ga = frag_rows<DH>(sm + T_GH * TILE, lane, kk), gb = frag_rows<DH>(sm + T_GD * TILE, lane, kk);
+          dp = HF_MFMA(ga, vh[kk], dp);       // dP = dO V^T
+          dpt = HF_MFMA(gb, vh[kk], dpt);     // dP_t = dO_t V^T + dO V_t^T
+          dpt = HF_MFMA(ga, vd[kk], dpt);
+        }
+      }
+      // register v of this lane: query q0 + 8 (v/4) + 4 (lane/32) + v%4 against key nk
+      float pr[16], pt[16], ds[16], dsx[16];
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int qi = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        const at_f32x4 sq = *(const HF_LDS at_f32x4*)(stats + qi * 4);
+        const int q = q0 + qi;
+        pr[v] = (q < nk || q >= p.S) ? 0.f : __expf(st[v] * p.scale - sq.x);
+        pt[v] = pr[v] * (su[v] * p.scale - sq.y);
+        if (DK) {
+          ds[v] = pr[v] * (dp[v] - sq.z);
+          dsx[v] = pt[v] * (dp[v] - sq.z) + pr[v] * (dpt[v] - sq.w);
+        }
+      }
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        if (DV) {
+          const bf16x8 pb = pack8(pr + ks * 8), ptb = pack8(pt + ks * 8);
+#pragma unroll
+          for (int rt = 0; rt < RT; ++rt) {
+            const bf16x8 gT = frag_cols<DH>(sm + T_GHT * TILE, lane, rt, ks), gdT = frag_cols<DH>(sm + T_GDT * TILE, lane, rt, ks);
+            dv[rt] = HF_MFMA(gT, pb, dv[rt]);       // dV^T = dO^T P
+            dvt[rt] = HF_MFMA(gT, ptb, dvt[rt]);    // dV_t^T = dO^T P_t + dO_t^T P
+            dvt[rt] = HF_MFMA(gdT, pb, dvt[rt]);
+          }
+        }
+        if (DK) {
+          const bf16x8 sb = pack8(ds + ks * 8), sxb = pack8(dsx + ks * 8);
+#pragma unroll
+          for (int rt = 0; rt < RT; ++rt) {
+            const bf16x8 qT = frag_cols<DH>(sm + T_QHT * TILE, lane, rt, ks), qdT = frag_cols<DH>(sm + T_QDT * TILE, lane, rt, ks);
+            dk[rt] = HF_MFMA(qT, sb, dk[rt]);       // dK^T = Q^T dS
+            dkt[rt] = HF_MFMA(qT, sxb, dkt[rt]);    // dK_t^T = Q^T dS_t + Q_t^T dS
+            dkt[rt] = HF_MFMA(qdT, sb, dkt[rt]);
+          }
+        }
+      }
+    }
+    __syncthreads();  // the next head's first store must not overtake this head's last reads
+  }
+  if (nk >= p.S) return;
+  const int64_t orow = row0 + nk;
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+#pragma unroll
+    for (int g4 = 0; g4 < 4; ++g4) {
+      const int col = hk * DH + rt * 32 + 8 * g4 + 4 * (lane >> 5);
+      if (DV) {
+        store4(p.dv, p.dv_f32, orow, p.lddv, col, dv[rt][g4 * 4], dv[rt][g4 * 4 + 1], dv[rt][g4 * 4 + 2], dv[rt][g4 * 4 + 3]);
+        store4(p.dv_t, p.dv_f32, orow, p.lddv, col, dvt[rt][g4 * 4], dvt[rt][g4 * 4 + 1], dvt[rt][g4 * 4 + 2], dvt[rt][g4 * 4 + 3]);
+      }
+      if (DK) {
+        store4(p.dk, p.dk_f32, orow, p.lddk, col, dk[rt][g4 * 4] * p.scale, dk[rt][g4 * 4 + 1] * p.scale, dk[rt][g4 * 4 + 2] * p.scale,
+               dk[rt][g4 * 4 + 3] * p.scale);
+        store4(p.dk_t, p.dk_f32, orow, p.lddk, col, dkt[rt][g4 * 4] * p.scale, dkt[rt][g4 * 4 + 1] * p.scale,
+               dkt[rt][g4 * 4 + 2] * p.scale, dkt[rt][g4 * 4 + 3] * p.scale);
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------ launchers ----
+
+static bool attn_shape_ok(const AttnP& p) {
+  const int dh = p.dh;
+  if (dh != 32 && dh != 64 && dh != 128) return false;
+  if (p.B <= 0 || p.H <= 0 || p.S <= 0 || p.grp <= 0 || p.H % p.grp) return false;
+  if (p.ldq % 8 || p.offK % 8 || p.offV % 8) return false;
+  return true;
+}
+static bool al16(const void* x) { return x != nullptr && ((uintptr_t)x & 15) == 0; }
+
+bool attn_flash_supported(int dh, int64_t ldq, int64_t ldo) { return (dh == 32 || dh == 64 || dh == 128) && ldq % 8 == 0 && ldo % 8 == 0; }
+
+bool attn_flash_preferred(int dh) { return dh <= 64; }
+
+hipError_t launch_attn_fwd(const AttnP& p, hipStream_t st) {
+  if (!attn_shape_ok(p) || p.ldo % 8) return hipErrorInvalidValue;
+  if (!al16(p.qkv) || !al16(p.qkv_lo) || !al16(p.qkv_t) || !al16(p.o) || !al16(p.o_lo) || !al16(p.o_t) || !p.stat) return hipErrorInvalidValue;
+  const int nqt = (p.S + 127) / 128;
+  const unsigned grid = (unsigned)(((p.B * p.H + 7) / 8) * 8 * nqt);
+  const size_t lds = (size_t)6 * 32 * p.dh * 2;
+  if (p.dh == 32) hipLaunchKernelGGL(attn_fwd_kernel<32>, dim3(grid), dim3(256), lds, st, p);
+  else if (p.dh == 64) hipLaunchKernelGGL(attn_fwd_kernel<64>, dim3(grid), dim3(256), lds, st, p);
+  else hipLaunchKernelGGL(attn_fwd_kernel<128>, dim3(grid), dim3(256), lds, st, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_attn_bwd(const AttnP& p, hipStream_t st) {
+  if (!attn_shape_ok(p) || p.lddo % 8) return hipErrorInvalidValue;
+  if (!al16(p.qkv) || !al16(p.qkv_lo) || !al16(p.qkv_t) || !al16(p.dO) || !al16(p.dO_t) || !p.stat || !p.delta) return hipErrorInvalidValue;
+  if (!al16(p.dq) || !al16(p.dq_t) || !al16(p.dk) || !al16(p.dk_t) || !al16(p.dv) || !al16(p.dv_t)) return hipErrorInvalidValue;
+  if (p.lddq % 4 || p.lddk % 4 || p.lddv % 4) return hipErrorInvalidValue;
+  const int nqt = (p.S + 127) / 128;
+  const unsigned gq = (unsigned)(((p.B * p.H + 7) / 8) * 8 * nqt);
+  const unsigned gk = (unsigned)(((p.B * (p.H / p.grp) + 7) / 8) * 8 * nqt);
+  const size_t tile = (size_t)32 * p.dh * 2;
+  const size_t lq = 7 * tile, stats = 32 * 4 * sizeof(float);
+  if (p.dh == 32) {
+    hipLaunchKernelGGL(attn_bwd_q_kernel<32>, dim3(gq), dim3(256), lq, st, p);
+    hipLaunchKernelGGL((attn_bwd_kv_kernel<32, 3>), dim3(gk), dim3(256), 9 * tile + stats, st, p);
+  } else if (p.dh == 64) {
+    hipLaunchKernelGGL(attn_bwd_q_kernel<64>, dim3(gq), dim3(256), lq, st, p);
+    hipLaunchKernelGGL((attn_bwd_kv_kernel<64, 3>), dim3(gk), dim3(256), 9 * tile + stats, st, p);
+  } else {
+    // at a head width of 128 the accumulators of dK and dV together exceed the register file:
+    // one launch each, both recomputing the scores
+    hipLaunchKernelGGL(attn_bwd_q_kernel<128>, dim3(gq), dim3(256), lq, st, p);
+    hipLaunchKernelGGL((attn_bwd_kv_kernel<128, 1>), dim3(gk), dim3(256), 5 * tile + stats, st, p);
+    hipLaunchKernelGGL((attn_bwd_kv_kernel<128, 2>), dim3(gk), dim3(256), 7 * tile + stats, st, p);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace hf

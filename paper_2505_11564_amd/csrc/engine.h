@@ -32,6 +32,11 @@ struct LayerBuf {
   void *a, *a_t, *qkv, *qkv_t, *P, *P_t, *o, *o_t;   // attention branch
   void *m, *m_t, *f, *f_t, *g, *g_t;                 // MLP branch: norm out, pre-activation, activation out
   void *up, *up_t;                                   // LLAMA: up projection (f = gate)
+  // streamed attention (bf16, head width 32 / 64 / 128): the backward sweep recomputes the scores,
+  // so each layer keeps the low-order halves of q | k | v and of the attention output, and the
+  // row statistics (m + log l, r) of its softmax
+  void *qkv_lo, *o_lo;
+  float* att_stat;
 };
 
 }  // namespace hf
@@ -41,6 +46,7 @@ struct hf_ctx {
   int device = 0;
   int max_batch = 0, max_m = 0;
   int bf = 0;  // 1: bf16 parameters / operands
+  int flash = 0;  // 1: attention runs in the streamed kernels (no S x S buffers are allocated)
   int64_t n = 0;
   std::vector<hf::LayoutEntry> layout;
   std::vector<hf::LayerOff> loff;

@@ -42,6 +42,7 @@ int hf::build_layout(const hf_model_desc& d, std::vector<LayoutEntry>& out, std:
   if (d.d_model > 8192) return bad("d_model > 8192 is not supported by the norm kernels");
   if (!(d.norm_eps > 0.f)) return bad("norm_eps must be positive");
   if (d.activation != HF_ACT_GELU_ERF && d.activation != HF_ACT_GELU_TANH) return bad("activation must be HF_ACT_GELU_ERF or HF_ACT_GELU_TANH");
+  if (d.attention != HF_ATTN_AUTO && d.attention != HF_ATTN_STREAMED && d.attention != HF_ATTN_STORED) return bad("attention must be HF_ATTN_AUTO, HF_ATTN_STREAMED or HF_ATTN_STORED");
   const int64_t D = d.d_model, F = d.d_ff, V = d.vocab;
   const int hkv = d.n_kv_head > 0 ? d.n_kv_head : d.n_head;
   if (hkv > d.n_head || d.n_head % hkv) return bad("n_kv_head must divide n_head");
@@ -113,6 +114,13 @@ int hf_ctx::plan_and_alloc() {
     const bool llama = desc.arch == HF_ARCH_LLAMA;
     const int64_t Dkv = D / H * (desc.n_kv_head > 0 ? desc.n_kv_head : H);  // key / value width
     const int64_t W3 = D + 2 * Dkv;                                           // packed q | k | v row
+    {
+      const bool can = bf && attn_flash_supported((int)(D / H), W3, D);
+      if (desc.attention == HF_ATTN_STREAMED && !can)
+        return fail(HF_ESHAPE, "HF_ATTN_STREAMED needs bf16 parameters, a head width of 32, 64 or 128 and d_model a multiple of 8");
+      flash = can && desc.attention != HF_ATTN_STORED && (desc.attention == HF_ATTN_STREAMED || attn_flash_preferred((int)(D / H)));
+    }
+    const int64_t SSa = flash ? 0 : SS;  // the S x S buffers exist only for the unstreamed paths
     lb.resize(desc.n_layer);
     for (auto& b : lb) {
       b = LayerBuf{};
@@ -120,7 +128,8 @@ int hf_ctx::plan_and_alloc() {
       pl.add(b.st1, T * 16); pl.add(b.st2, T * 16);
       pl.add(b.a, T * D * e); pl.add(b.a_t, T * D * e);
       pl.add(b.qkv, T * W3 * e); pl.add(b.qkv_t, T * W3 * e);
-      pl.add(b.P, SS * e); pl.add(b.P_t, SS * e);
+      pl.add(b.P, SSa * e); pl.add(b.P_t, SSa * e);
+      if (flash) { pl.add(b.qkv_lo, T * W3 * e); pl.add(b.o_lo, T * D * e); pl.add(b.att_stat, SS / S * 2 * 4); }
       pl.add(b.o, T * D * e); pl.add(b.o_t, T * D * e);
       pl.add(b.m, T * D * e); pl.add(b.m_t, T * D * e);
       pl.add(b.f, T * F * e); pl.add(b.f_t, T * F * e);
@@ -131,7 +140,7 @@ int hf_ctx::plan_and_alloc() {
     pl.add(xf, T * D * e); pl.add(xf_t, T * D * e);
     if (bf) {
       pl.add(xf_lo, T * D * e); pl.add(a_lo, T * D * e); pl.add(o_lo, T * D * e); pl.add(qkv_lo, T * W3 * e);
-      pl.add(P_lo, SS * e); pl.add(f_lo, T * F * e); pl.add(g_lo, T * F * e);
+      pl.add(P_lo, SSa * e); pl.add(f_lo, T * F * e); pl.add(g_lo, T * F * e);
       if (llama) pl.add(up_lo, T * F * e);
     }
     if (llama) { pl.add(rq, T * (D + Dkv) * 4); pl.add(rq_t, T * (D + Dkv) * 4); }
@@ -143,15 +152,15 @@ int hf_ctx::plan_and_alloc() {
     pl.add(z, T * ldz * 4); pl.add(z_t, T * ldz * 4);
     pl.add(dz, T * ldz * e); pl.add(dz_t, T * ldz * e);
     pl.add(loss_rows, T * 4);
-    pl.add(sc, SS * 4); pl.add(sc_t, SS * 4);
-    att_SS = SS;
+    pl.add(sc, SSa * 4); pl.add(sc_t, SSa * 4);
+    att_SS = SSa;
     pl.add(norm_part, (int64_t)NORM_PART_BLOCKS * 3 * D * 4);
     if (bf) pl.add(gemm_ws, GEMM_WS_ELEMS * 4);
     if (bf) {
       const int64_t rows = SS / desc.max_seq, np = (desc.max_seq + 63) / 64;  // B*H*S rows
-      pl.add(att_part, rows * np * 3 * 4); pl.add(att_rstat, rows * 3 * 4);
+      pl.add(att_part, (flash ? 0 : rows * np) * 3 * 4); pl.add(att_rstat, rows * 3 * 4);
     }
-    pl.add(dS, SS * e); pl.add(dS_t, SS * e);
+    pl.add(dS, SSa * e); pl.add(dS_t, SSa * e);
     pl.add(dx, T * D * 4); pl.add(dx_t, T * D * 4); pl.add(tmpd, T * D * 4); pl.add(tmpd_t, T * D * 4);
     if (bf) { pl.add(dxb, T * D * e); pl.add(dxb_t, T * D * e); }
     pl.add(dob, T * D * e); pl.add(dob_t, T * D * e);
@@ -417,7 +426,7 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
   // kernels write only the score tiles on and below the diagonal; tiles above it
   // are read as zeros by products that run with larger tiles, so they are
   // cleared whenever the [B,H,S,S] layout changes.
-  const bool fused_att = bf && D % 8 == 0 && dh % 32 == 0 && S % 8 == 0;
+  const bool fused_att = !flash && bf && D % 8 == 0 && dh % 32 == 0 && S % 8 == 0;
   if (fused_att && (att_zero_B != B || att_zero_S != S)) {
     const int64_t words = (int64_t)B * H * SS / 2;  // bf16 pairs
     for (auto& b : lb) {
@@ -432,6 +441,11 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
   // The unfused path writes whole score matrices in its own [B,H,S,S] layout, so the tiles the
   // fused kernels rely on being zero must be cleared again before their next use.
   if (bf && !fused_att) att_zero_B = att_zero_S = -1;
+  AttnP ap;  // streamed attention: what every layer shares
+  if (flash) {
+    ap.ldq = W3; ap.offK = offK; ap.offV = offV; ap.B = B; ap.H = H; ap.S = S; ap.grp = grp; ap.dh = dh; ap.scale = cs;
+    ap.ldo = D; ap.lddo = D; ap.delta = att_rstat;
+  }
 
   // ------------------------------ forward with tangents ----------------------
   CK(launch_embed_fwd(bf, L.Wp(off_wte), llama ? nullptr : L.Wp(off_wpe), v + off_wte, llama ? nullptr : v + off_wpe,
@@ -445,6 +459,9 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
     // of the primal activations of the forward chain.
     CK(launch_norm_fwd(bf, rms, b.x1, b.x1_t, L.Wp(o.n1g), rms ? nullptr : L.Wp(o.n1b), v + o.n1g,
                        rms ? nullptr : v + o.n1b, T, D, eps, b.a, b.a_t, a_lo, b.st1, st));
+    // (streamed attention keeps these two per layer: its backward sweep forms the scores again)
+    void* const qkv_lo = flash ? b.qkv_lo : this->qkv_lo;
+    void* const o_lo = flash ? b.o_lo : this->o_lo;
     if (!llama) {
       if ((rc = L.fwd(b.a, b.a_t, T, D, 3 * D, D, o.wqkv, o.bqkv, b.qkv, b.qkv_t, W3, bf, nullptr, nullptr, 0, -1, a_lo, qkv_lo))) return rc;
     } else {
@@ -455,6 +472,12 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
                       qkv_lo ? at(qkv_lo, offV) : nullptr))) return rc;
       CK(launch_rope(bf, rq, rq_t, RQ, b.qkv, b.qkv_t, qkv_lo, W3, T, S, H + Hkv, dh, desc.rope_theta, 0, st));
     }
+    if (flash) {
+      AttnP a = ap;
+      a.qkv = (const bf16*)b.qkv; a.qkv_lo = (const bf16*)qkv_lo; a.qkv_t = (const bf16*)b.qkv_t;
+      a.o = (bf16*)b.o; a.o_lo = (bf16*)o_lo; a.o_t = (bf16*)b.o_t; a.stat = b.att_stat;
+      CK(launch_attn_fwd(a, st));
+    } else {
     if (fused_att) {
       // scores without a trip through memory: the product is formed twice by the
       // dual-output kernel, first to reduce (max, sum, tangent sum) per row over
@@ -499,6 +522,7 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
       }
       g.At = b.P_t; g.Bt = cat(b.qkv_t, offV); g.Ct = b.o_t;
       CK(launch_gemm(g, st));
+    }
     }
     if ((rc = L.fwd(b.o, b.o_t, T, D, D, D, o.wo, o.bo, b.x2, b.x2_t, D, 0, b.x1, b.x1_t, 0, -1, o_lo))) return rc;
     CK(launch_norm_fwd(bf, rms, b.x2, b.x2_t, L.Wp(o.n2g), rms ? nullptr : L.Wp(o.n2b), v + o.n2g,
@@ -588,6 +612,21 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
       }
       return hipSuccess;
     };
+    if (flash) {
+      // delta, delta_t from <dO, O>, then dQ, dK, dV and their tangents with the probabilities
+      // recomputed tile by tile from the saved row statistics
+      CK(launch_attn_delta(dob, dob_t, b.o, b.o_lo, b.o_t, T, S, H, dh, att_rstat, st));
+      AttnP a = ap;
+      a.qkv = (const bf16*)b.qkv; a.qkv_lo = (const bf16*)b.qkv_lo; a.qkv_t = (const bf16*)b.qkv_t; a.stat = b.att_stat;
+      a.dO = (const bf16*)dob; a.dO_t = (const bf16*)dob_t;
+      a.dv = at(dqkv, offV); a.dv_t = at(dqkv_t, offV); a.lddv = W3; a.dv_f32 = 0;
+      if (llama) {  // fp32 staging [T, D + Dkv]; rounded once after the inverse rotation
+        a.dq = rq; a.dq_t = rq_t; a.dk = rq + D; a.dk_t = rq_t + D; a.lddq = a.lddk = RQ; a.dq_f32 = a.dk_f32 = 1;
+      } else {
+        a.dq = dqkv; a.dq_t = dqkv_t; a.dk = at(dqkv, offK); a.dk_t = at(dqkv_t, offK); a.lddq = a.lddk = W3;
+      }
+      CK(launch_attn_bwd(a, st));
+    } else {
     {  // dV = P^T dO, dV_t = P_t^T dO + P^T dO_t   -> v part of dqkv
       Gemm g; att(g);
       g.M = S; g.N = dh; g.K = S; g.lda = S; g.ldb = D; g.ldc = W3; g.transA = 1; g.klimit = 2; g.out_bf16 = bf;
@@ -612,7 +651,8 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
       g.At = dob_t; g.Bt = cat(b.qkv_t, offV);
       g.C = dS; g.Ct = dS_t; g.out_bf16 = 1; g.E0 = b.P; g.E1 = b.P_t;
       // delta, delta_t from <dO, O> where the head width allows, else by a statistics pass
-      hipError_t ed = launch_attn_delta(dob, dob_t, b.o, o_lo, b.o_t, T, S, H, dh, att_rstat, st);
+      // (the shared low-order buffer of O still holds this layer's only for the last layer)
+      hipError_t ed = launch_attn_delta(dob, dob_t, b.o, l == NL - 1 ? o_lo : nullptr, b.o_t, T, S, H, dh, att_rstat, st);
       if (ed == hipErrorNotSupported) {
         g.epi = EPI_BWD_STATS; g.part = att_part;
         CK(launch_gemm(g, st));
@@ -653,6 +693,7 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
       if (grp == 1) CK(launch_gemm(g, st));
       else CK(grouped(g, SS, dh, (float*)ck, (float*)ck_t));  // grp > 1 is LLAMA: ck is the fp32 staging
     }
+    }
     if (!llama) {
       if ((rc = L.bwd_dw(b.a, b.a_t, dqkv, dqkv_t, T, D, 3 * D, D, W3, o.wqkv, o.bqkv, dqkv_t, bf))) return rc;
       if ((rc = L.bwd_dx(dqkv, dqkv_t, T, D, 3 * D, W3, o.wqkv, tmpd, tmpd_t, D, 0))) return rc;
@@ -665,7 +706,7 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
         const void* dyi_t = cat(dqkv_t, offs[i]);
         int64_t ldy = W3;
         const int Ni = i ? Dkv : D;
-        if (i == 2 && grp > 1) {  // dV of grouped heads lives in its own [T, Dkv] buffer
+        if (i == 2 && grp > 1 && !flash) {  // dV of grouped heads lives in its own [T, Dkv] buffer
           dyi = bf ? (const void*)dvb : (const void*)rv;
           dyi_t = bf ? (const void*)dvb_t : (const void*)rv_t;
           ldy = Dkv;

@@ -108,6 +108,35 @@ hipError_t launch_attn_delta(const void* dO, const void* dO_t, const void* O, co
                              int H, int dh, float* rstat, hipStream_t st);
 hipError_t launch_attn_combine(int backward, const float* part, int NP, int M, int64_t rows, float* rstat, hipStream_t st);
 
+// attn_flash.hip: causal attention with tangents, streamed over key / query tiles (bf16 operands,
+// head width 32, 64 or 128).  Activations are packed rows [T, ldq] = q | k | v: head h of q at
+// column h*dh, its key and value at offK + (h / grp) * dh and offV + (h / grp) * dh (grp query heads
+// share one key/value head); token of (batch b, position s) is row b*S + s.
+struct AttnP {
+  const bf16 *qkv = nullptr, *qkv_lo = nullptr, *qkv_t = nullptr;  // primal (high, low half) and tangent
+  int64_t ldq = 0;
+  int offK = 0, offV = 0;
+  int B = 0, H = 0, S = 0, grp = 1, dh = 0;
+  float scale = 1.f;
+  // forward results [T, ldo], head h at column h*dh; stat[(b*H + h)*S + s] = (m + log l, r)
+  bf16 *o = nullptr, *o_lo = nullptr, *o_t = nullptr;
+  int64_t ldo = 0;
+  float* stat = nullptr;
+  // backward: adjoint of the output and its tangent [T, lddo]; delta[(b*H + h)*S + s] = (delta, delta_t, -)
+  const bf16 *dO = nullptr, *dO_t = nullptr;
+  int64_t lddo = 0;
+  const float* delta = nullptr;
+  // results, bf16 or fp32 (x_f32), rows of ldd? elements: dq / dq_t [T, H*dh], dk, dv (and tangents)
+  // [T, (H/grp)*dh] summed over the query heads of a group; the pointers address column 0 of head 0
+  void *dq = nullptr, *dq_t = nullptr, *dk = nullptr, *dk_t = nullptr, *dv = nullptr, *dv_t = nullptr;
+  int64_t lddq = 0, lddk = 0, lddv = 0;
+  int dq_f32 = 0, dk_f32 = 0, dv_f32 = 0;
+};
+bool attn_flash_supported(int dh, int64_t ldq, int64_t ldo);
+bool attn_flash_preferred(int dh);  // measured faster than the stored-probability path at this head width
+hipError_t launch_attn_fwd(const AttnP& p, hipStream_t st);
+hipError_t launch_attn_bwd(const AttnP& p, hipStream_t st);  // dQ, dK, dV with tangents (needs delta)
+
 // probe.hip: batch-loop accumulation and Hessian-column statistics
 constexpr int CS_MAX_THRESHOLDS = 16, CS_MAX_BINS = 256, CS_STATS_WORDS = 32 + CS_MAX_BINS;
 struct ColThresholds { float t[CS_MAX_THRESHOLDS]; };

@@ -67,6 +67,12 @@ def test_workload4_1p3b_reduced_depth_vs_oracle():
     _oracle_case(cfg, si.scaled(cfg["model"], n_layer=2))
 
 
+def test_workload4_widths_streamed_attention_vs_oracle():
+    # head width 128 at full sequence length through the streamed attention kernels
+    cfg = si.CONFIGS["gpt_1p3b"]
+    _oracle_case(cfg, dict(si.scaled(cfg["model"], n_layer=1), attention="streamed"))
+
+
 def test_workload5_llama7b_reduced_depth_vs_oracle():
     cfg = si.CONFIGS["llama_7b"]
     _oracle_case(cfg, si.scaled(cfg["model"], n_layer=2))

@@ -41,6 +41,11 @@ SHAPES = {
     "gpt_deep": dict(model=si._gpt(6, 64, 2, 136, 211, 40), batch=2, seq=40, tokens="zipf"),
     "llama_deep": dict(model=si._llama(6, 64, 2, 96, 211, 40), batch=2, seq=40, tokens="zipf"),
     "llama_gqa_deep": dict(model=si._llama(5, 128, 4, 176, 211, 40, n_kv=2), batch=2, seq=40, tokens="zipf"),
+    # head widths 64 and 128 (bf16: the streamed attention kernels), several query blocks of 128 with a
+    # ragged last one, grouped key/value heads at width 128
+    "gpt_dh64_long": dict(model=si._gpt(1, 128, 2, 136, 301, 300), batch=1, seq=300, tokens="zipf"),
+    "gpt_dh128": dict(model=si._gpt(2, 256, 2, 264, 301, 200), batch=2, seq=200, tokens="zipf"),
+    "llama_gqa_dh128": dict(model=si._llama(2, 512, 4, 344, 301, 136, n_kv=2), batch=2, seq=136, tokens="zipf"),
 }
 
 
@@ -72,6 +77,26 @@ def run_case(cfg, dtype, seed=0, short_seq=None):
 @pytest.mark.parametrize("name", list(SHAPES))
 def test_hvp_parity_small(name, dtype):
     run_case(SHAPES[name], dtype)
+
+
+@pytest.mark.parametrize("mode", ["streamed", "stored"])
+@pytest.mark.parametrize("name", ["gpt_fused", "gpt_heads8", "llama_gqa_mid", "gpt_mid", "gpt_dh64_long", "gpt_dh128",
+                                  "llama_gqa_dh128", "llama_gqa_deep"])
+def test_hvp_attention_modes(name, mode):
+    # both evaluations of attention at every head width the streamed kernels take (32, 64, 128),
+    # whichever of them the library would choose by itself
+    cfg = SHAPES[name]
+    run_case(dict(cfg, model=dict(cfg["model"], attention=mode)), "bf16", seed=3)
+
+
+def test_hvp_streamed_attention_needs_a_supported_head_width():
+    import paper_2505_11564_amd as hf
+    model = dict(si._gpt(1, 48, 2, 64, 97, 16), attention="streamed")   # head width 24
+    with pytest.raises(hf.HessformerError) as e:
+        hf.Context(model, 1, 0, "bf16")
+    assert e.value.code == hf.binding.HF_ESHAPE
+    with pytest.raises(hf.HessformerError):
+        hf.Context(dict(SHAPES["gpt_fused"]["model"], attention="streamed"), 1, 0, "f32")   # fp32 parameters
 
 
 def test_hvp_parity_many_whole_tiles():
