@@ -155,17 +155,18 @@ def device_params(model, dtype):
     return flat
 
 
-def time_update_only(ctx, cfg, n, k_first, k_last, dtype, stream):
+def time_update_only(ctx, cfg, n, k_first, k_last, dtype, stream, probe=None, q=None, r=None):
     """The vector update alone over the iterations k_first .. k_last of one run, driven by a seeded
     diagonal operator (r = d * q_k) so that the recurrence is a genuine Lanczos run and the kernels
-    see the same sequence of calls as in a real iteration.  HIP events on the library's stream."""
+    see the same sequence of calls as in a real iteration.  HIP events on the library's stream.
+    probe / q / r: n-vectors the caller already holds (the 7B-size vectors are 27 GB each)."""
     import torch
     basis = cfg["basis_dtype"]
     gen = torch.Generator(device="cuda").manual_seed(1)
     dvec = torch.empty(n, dtype=torch.float32, device="cuda").uniform_(-1.0, 1.0, generator=gen)
-    zd = torch.empty(n, dtype=torch.float32, device="cuda").uniform_(-1.0, 1.0, generator=gen).sign_()
-    q = torch.empty(n, dtype=torch.float32, device="cuda")
-    r = torch.empty(n, dtype=torch.float32, device="cuda")
+    zd = probe if probe is not None else torch.empty(n, dtype=torch.float32, device="cuda").uniform_(-1.0, 1.0, generator=gen).sign_()
+    q = q if q is not None else torch.empty(n, dtype=torch.float32, device="cuda")
+    r = r if r is not None else torch.empty(n, dtype=torch.float32, device="cuda")
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     ctx.hf_lanczos_init(zd, cfg["reorth"])
     del zd
@@ -240,7 +241,8 @@ def measure(name, K, W, hvp_reps, pd=None, params_host=None):
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
 
-    lz = time_update_only(ctx, cfg, n, k0, k0 + K - 1, dtype, stream)
+    lz = time_update_only(ctx, cfg, n, k0, k0 + K - 1, dtype, stream, probe=zd, q=out, r=vd)
+    vd.copy_(zd).div_(float(np.sqrt(n)))  # (r was scratch: the direction again, for the legs that follow)
     res = {
         "steps_per_s": K / elapsed, "ms_per_step": 1e3 * elapsed / K, "depth_range": [k0, k0 + K - 1],
         "hvps_per_s": 1e3 / hvp_ms, "hvp_ms": hvp_ms,
@@ -262,6 +264,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the 1.3B and Llama-7B-size legs")
     ap.add_argument("--hvp-reps", type=int, default=10)
+    ap.add_argument("--attention", default="auto", choices=["auto", "streamed", "stored"],
+                    help="how attention is evaluated (hf_model_desc.attention); auto = the library's choice")
     ap.add_argument("--hvp-only", type=int, default=0, metavar="N",
                     help="profiling aid: run N Hessian-vector products, then one elementwise pass over a "
                          "1 GiB fp32 tensor (a kernel of known HBM traffic that calibrates the byte counters), and exit")
@@ -278,6 +282,9 @@ def main():
     import paper_2505_11564_amd as hf
     import synth_inputs as si
 
+    if args.attention != "auto":
+        for c in si.CONFIGS.values():
+            c["model"] = dict(c["model"], attention=args.attention)
     cfg = si.CONFIGS[args.workload]
     model, B, S, m = cfg["model"], cfg["batch"], cfg["seq"], cfg["m"]
     dtype, basis = cfg["param_dtype"], cfg["basis_dtype"]
@@ -335,7 +342,7 @@ def main():
         "warmup": W, "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16" if dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": args.workload, "n_params": n, "batch": B, "seq": Sarg, "lanczos_m": m,
-                   "reorth": cfg["reorth"], "basis_dtype": basis, "tokens": cfg["tokens"],
+                   "reorth": cfg["reorth"], "basis_dtype": basis, "tokens": cfg["tokens"], "attention": args.attention,
                    "depth_range": head["depth_range"],
                    "depth_note": "timed steps are iterations depth_range[0]..depth_range[1] of one m-step run "
                                  "(mean basis depth = that of the whole run); earlier iterations run untimed"},

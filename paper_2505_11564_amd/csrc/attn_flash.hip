@@ -132,14 +132,55 @@ __device__ __forceinline__ bool block_map(int nheads, int ntiles, int& hh, int& 
 
 }  // namespace
 
+// ---- direct global -> LDS staging and hand-scheduled fragment reads ------------------------
+// A stage is a run of tiles (32 rows x DH, 64*DH bytes each); one global_load_lds instruction fills
+// 1 KB of it (64 lanes x 16 bytes, consecutive), so instruction q of a stage covers bytes
+// [q KB, (q+1) KB): tile q / (DH/16), chunks (q % (DH/16)) * 64 + lane.  The chunk permutation of
+// a tile is applied on the source side: the lane that fills chunk slot s of row r fetches the
+// logical chunk s ^ swz(r).  Wave w issues the instructions q = w, w + 4, ...
+template <int DH>
+struct LdsLoad {
+  static constexpr int NI_T = DH / 16, CPR = DH / 8;
+  // row (0..31) and column (elements) that `lane` fetches for instruction q; rc: the tile's permutation
+  __device__ static __forceinline__ void lane_chunk(int q, int lane, bool rc, int& row, int& col) {
+    const int P = (q % NI_T) * 64 + lane;
+    row = P / CPR;
+    const int slot = P % CPR;
+    const int swz = rc ? rc_rot(row, DH) : ((row / (128 / DH)) & (CPR - 1));
+    col = (slot ^ swz) * 8;
+  }
+};
+template <int N>
+__device__ __forceinline__ void lds_wait() { asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N) : "memory"); }
+
+// Per-lane LDS byte offsets (relative to a tile) of the fragments a wave reads:
+//   rows on lanes, k-step kk   : (kc_off(lane % 32, 2 kk + lane / 32)) * 2
+//   columns on lanes, row tile rt : the address of frag_cols at ks = 0; ks adds 16 * DH * 2 bytes,
+//                                   the second transposing read 8 * DH * 2 more
+template <int DH>
+__device__ __forceinline__ uint32_t addr_rows(int lane, int kk) { return (uint32_t)(kc_off<DH>(lane & 31, kk * 2 + (lane >> 5)) * 2); }
+template <int DH>
+__device__ __forceinline__ uint32_t addr_cols(int lane, int rt) {
+  const int i = lane & 15, g = lane >> 4;
+  const int kq = (g >> 1) * 4 + (i >> 2);
+  const int c = rt * 32 + (g & 1) * 16 + (i & 3) * 4;
+  return (uint32_t)((kq * DH + ((((c >> 3) ^ rc_rot(kq, DH))) << 3) + (c & 7)) * 2);
+}
+
 // ------------------------------------------------------------------ forward ----
+// Two LDS stages of six tiles (K hi / lo / t with keys on lanes, V hi / lo / t for transposing
+// reads), filled by direct global -> LDS loads one key tile ahead; one barrier per key tile.
+// Fragment reads are issued one step ahead of the matrix instructions that use them.
+// Online softmax with a lazy reference maximum: the running maximum is only moved (and the
+// accumulators rescaled) when a tile exceeds it by more than 8, which keeps exp() below e^8.
 
 template <int DH>
-__global__ __launch_bounds__(256) void attn_fwd_kernel(const AttnP p) {
+__global__ __launch_bounds__(256, (DH <= 64 ? 2 : 1)) void attn_fwd_kernel(const AttnP p) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
-  HF_LDS bf16* sm = (HF_LDS bf16*)smem_raw;
-  constexpr int TILE = 32 * DH, KS = DH / 16, RT = DH / 32;
-  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  constexpr int TILE_B = 64 * DH, STAGE_B = 6 * TILE_B, KS = DH / 16, RT = DH / 32;
+  constexpr int NI = 6 * (DH / 16) / 4;  // load instructions per wave and stage
+  const int t = threadIdx.x, lane = t & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(t >> 6) & 3;  // (masked so that tile indices below fold)
   const int nqt = (p.S + 127) / 128;
   int hh, tile;
   if (!block_map(p.B * p.H, nqt, hh, tile)) return;
@@ -160,9 +201,33 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const AttnP p) {
       qd[kk] = *(const bf16x8*)(p.qkv_t + off + kk * 16);
     }
   }
+  // this wave's load instructions: per lane the row within the tile and the column (elements), packed
   const int64_t ok = row0 * p.ldq + p.offK + (int64_t)hk * DH, ov = row0 * p.ldq + p.offV + (int64_t)hk * DH;
-  const bf16 *sKh = p.qkv + ok, *sKl = p.qkv_lo + ok, *sKd = p.qkv_t + ok, *sVh = p.qkv + ov, *sVl = p.qkv_lo + ov, *sVd = p.qkv_t + ov;
-  const HF_LDS bf16 *Kh = sm, *Kl = sm + TILE, *Kd = sm + 2 * TILE, *Vh = sm + 3 * TILE, *Vl = sm + 4 * TILE, *Vd = sm + 5 * TILE;
+  uint32_t gpk[NI];
+#pragma unroll
+  for (int i = 0; i < NI; ++i) {
+    const int q = wave + 4 * i;
+    int row, col;
+    LdsLoad<DH>::lane_chunk(q, lane, q / (DH / 16) >= 3, row, col);
+    gpk[i] = (uint32_t)(row | (col << 8));
+  }
+  HF_LDS char* const smem_c = (HF_LDS char*)smem_raw;
+  auto issue = [&](int stage, int r0) {
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const int T = (wave + 4 * i) / (DH / 16);  // (wave-uniform) tile: K hi / lo / t, V hi / lo / t
+      const bf16* base = T == 0 ? p.qkv + ok : T == 1 ? p.qkv_lo + ok : T == 2 ? p.qkv_t + ok : T == 3 ? p.qkv + ov : T == 4 ? p.qkv_lo + ov : p.qkv_t + ov;
+      const int rr = min(r0 + (int)(gpk[i] & 255u), p.S - 1);
+      __builtin_amdgcn_global_load_lds((const void*)(base + ((int64_t)rr * p.ldq + (gpk[i] >> 8))),
+                                       (HF_LDS void*)(smem_c + stage * STAGE_B + (wave + 4 * i) * 1024), 16, 0, 0);
+    }
+  };
+  const uint32_t lds0 = (uint32_t)(uintptr_t)smem_c;
+  uint32_t adK[KS], adV[RT];
+#pragma unroll
+  for (int kk = 0; kk < KS; ++kk) adK[kk] = lds0 + addr_rows<DH>(lane, kk);
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) adV[rt] = lds0 + addr_cols<DH>(lane, rt);
 
   f32x16 o[RT], a1[RT];
 #pragma unroll
@@ -171,69 +236,74 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const AttnP p) {
     for (int v = 0; v < 16; ++v) { o[i][v] = 0.f; a1[i][v] = 0.f; }
   float m_run = -INFINITY, l_run = 0.f, rs_run = 0.f;
 
-  const int n_end = min(p.S, m0 + 128);
-  const int nkt = (n_end + 31) / 32;
-  constexpr int PER = StageDim<DH>::PER;
-  at_u32x4 g0[PER], g1[PER], g2[PER], g3[PER], g4[PER], g5[PER];
-  auto load_stage = [&](int r0) {
-    stage_load_one<DH, 0>(g0, sKh, p.ldq, r0, p.S, t); stage_load_one<DH, 1>(g1, sKl, p.ldq, r0, p.S, t);
-    stage_load_one<DH, 2>(g2, sKd, p.ldq, r0, p.S, t); stage_load_one<DH, 3>(g3, sVh, p.ldq, r0, p.S, t);
-    stage_load_one<DH, 4>(g4, sVl, p.ldq, r0, p.S, t); stage_load_one<DH, 5>(g5, sVd, p.ldq, r0, p.S, t);
-  };
-  load_stage(0);
-  for (int kt = 0; kt < nkt; ++kt) {
-    const int n0 = kt * 32;
-    __syncthreads();  // the previous tile has been consumed
-    stage_store_one<DH, 0, -1>(g0, sm, t); stage_store_one<DH, 1, -1>(g1, sm, t); stage_store_one<DH, 2, -1>(g2, sm, t);
-    stage_store_one<DH, -1, 3>(g3, sm, t); stage_store_one<DH, -1, 4>(g4, sm, t); stage_store_one<DH, -1, 5>(g5, sm, t);
-    __syncthreads();
-    if (kt + 1 < nkt) load_stage(n0 + 32);
-    if (n0 > mw + 31 || mw >= p.S) continue;  // (wave-uniform) keys beyond this wave's diagonal, or no query
+  // the work of one key tile held in LDS stage S (compile-time)
+  auto compute = [&](auto S_c, int n0) {
+    constexpr int SB = decltype(S_c)::value * STAGE_B;
     f32x16 st, su;
 #pragma unroll
     for (int v = 0; v < 16; ++v) { st[v] = 0.f; su[v] = 0.f; }
-#pragma unroll
-    for (int kk = 0; kk < KS; ++kk) {
-      const bf16x8 kh = frag_rows<DH>(Kh, lane, kk), kl = frag_rows<DH>(Kl, lane, kk), kd = frag_rows<DH>(Kd, lane, kk);
-      st = HF_MFMA(kh, qh[kk], st);
-      st = HF_MFMA(kl, qh[kk], st);
-      st = HF_MFMA(kh, ql[kk], st);
-      su = HF_MFMA(kd, qh[kk], su);
-      su = HF_MFMA(kh, qd[kk], su);
-    }
+    bf16x8 kh[2], kl[2], kd[2];
+    kh[0] = lds_read_b128<SB>(adK[0]); kl[0] = lds_read_b128<SB + TILE_B>(adK[0]); kd[0] = lds_read_b128<SB + 2 * TILE_B>(adK[0]);
+    static_for<KS>([&](auto kk_c) {
+      constexpr int kk = decltype(kk_c)::value, c = kk & 1, nx = c ^ 1;
+      if constexpr (kk + 1 < KS) {
+        kh[nx] = lds_read_b128<SB>(adK[kk + 1]); kl[nx] = lds_read_b128<SB + TILE_B>(adK[kk + 1]);
+        kd[nx] = lds_read_b128<SB + 2 * TILE_B>(adK[kk + 1]);
+        lds_wait<3>();
+      } else {
+        lds_wait<0>();
+      }
+      lds_tie(kh[c]); lds_tie(kl[c]); lds_tie(kd[c]);
+      st = HF_MFMA(kh[c], qh[kk], st);
+      su = HF_MFMA(kd[c], qh[kk], su);
+      st = HF_MFMA(kl[c], qh[kk], st);
+      su = HF_MFMA(kh[c], qd[kk], su);
+      st = HF_MFMA(kh[c], ql[kk], st);
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    // first V fragments on their way while the softmax arithmetic runs
+    bf16x4 vh[2][2], vl[2][2], vd[2][2];
+    auto req_v = [&](auto s_c, auto set_c) {
+      constexpr int s = decltype(s_c)::value, set = decltype(set_c)::value;
+      constexpr int rt = s % RT, ks = s / RT, OFF = SB + ks * 16 * DH * 2;
+      vh[set][0] = lds_read_tr64<OFF + 3 * TILE_B>(adV[rt]); vh[set][1] = lds_read_tr64<OFF + 3 * TILE_B + 8 * DH * 2>(adV[rt]);
+      vl[set][0] = lds_read_tr64<OFF + 4 * TILE_B>(adV[rt]); vl[set][1] = lds_read_tr64<OFF + 4 * TILE_B + 8 * DH * 2>(adV[rt]);
+      vd[set][0] = lds_read_tr64<OFF + 5 * TILE_B>(adV[rt]); vd[set][1] = lds_read_tr64<OFF + 5 * TILE_B + 8 * DH * 2>(adV[rt]);
+    };
+    req_v(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
     // register v of this lane: key n0 + 8 (v/4) + 4 (lane/32) + v%4 against query mq
-    float s[16], u[16];
+    float s[16], eu[16];
     float mx = -INFINITY;
     const bool diag = n0 + 31 > mw;
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       const int key = n0 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
       s[v] = st[v] * p.scale;
-      u[v] = su[v] * p.scale;
       if (diag && key > mq) s[v] = -INFINITY;
       mx = fmaxf(mx, s[v]);
     }
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m_run, mx);      // finite: key n0 <= mw <= mq is never masked
-    const float alpha = __expf(m_run - m_new);  // 0 on the first tile
-    float ls = 0.f, rsum = 0.f;
-    float eu[16];
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      s[v] = __expf(s[v] - m_new);
-      eu[v] = s[v] * u[v];
-      ls += s[v];
-      rsum += eu[v];
-    }
-    l_run = l_run * alpha + ls;
-    rs_run = rs_run * alpha + rsum;
-    m_run = m_new;
-    if (__any(alpha != 1.f)) {
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));  // finite: key n0 <= mw <= mq is never masked
+    if (__any(mx > m_run + 8.f)) {
+      const float m_new = mx > m_run + 8.f ? mx : m_run;
+      const float alpha = __expf(m_run - m_new);  // 0 on the first tile, 1 for lanes that keep their maximum
+      l_run *= alpha;
+      rs_run *= alpha;
+      m_run = m_new;
 #pragma unroll
       for (int i = 0; i < RT; ++i)
 #pragma unroll
         for (int v = 0; v < 16; ++v) { o[i][v] *= alpha; a1[i][v] *= alpha; }
     }
+    float ls = 0.f, rsum = 0.f;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      s[v] = __expf(s[v] - m_run);
+      eu[v] = s[v] * (su[v] * p.scale);
+      ls += s[v];
+      rsum += eu[v];
+    }
+    l_run += ls;
+    rs_run += rsum;
     bf16x8 eh[2], el[2], es[2];
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) {
@@ -247,18 +317,46 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const AttnP p) {
       el[ks] = pack8(lo8);
       es[ks] = pack8(eu + ks * 8);
     }
-#pragma unroll
-    for (int rt = 0; rt < RT; ++rt) {
-#pragma unroll
-      for (int ks = 0; ks < 2; ++ks) {
-        const bf16x8 vh = frag_cols<DH>(Vh, lane, rt, ks), vl = frag_cols<DH>(Vl, lane, rt, ks), vd = frag_cols<DH>(Vd, lane, rt, ks);
-        o[rt] = HF_MFMA(vh, eh[ks], o[rt]);
-        o[rt] = HF_MFMA(vh, el[ks], o[rt]);
-        o[rt] = HF_MFMA(vl, eh[ks], o[rt]);
-        a1[rt] = HF_MFMA(vh, es[ks], a1[rt]);
-        a1[rt] = HF_MFMA(vd, eh[ks], a1[rt]);
+    __builtin_amdgcn_sched_barrier(0);
+    static_for<2 * RT>([&](auto s_c) {
+      constexpr int sI = decltype(s_c)::value, c = sI & 1, rt = sI % RT, ks = sI / RT;
+      if constexpr (sI + 1 < 2 * RT) {
+        req_v(std::integral_constant<int, sI + 1>{}, std::integral_constant<int, c ^ 1>{});
+        lds_wait<6>();
+      } else {
+        lds_wait<0>();
       }
-    }
+      lds_tie(vh[c][0]); lds_tie(vh[c][1]); lds_tie(vl[c][0]); lds_tie(vl[c][1]); lds_tie(vd[c][0]); lds_tie(vd[c][1]);
+      const bf16x8 a_h = __builtin_shufflevector(vh[c][0], vh[c][1], 0, 1, 2, 3, 4, 5, 6, 7);
+      const bf16x8 a_l = __builtin_shufflevector(vl[c][0], vl[c][1], 0, 1, 2, 3, 4, 5, 6, 7);
+      const bf16x8 a_d = __builtin_shufflevector(vd[c][0], vd[c][1], 0, 1, 2, 3, 4, 5, 6, 7);
+      o[rt] = HF_MFMA(a_h, eh[ks], o[rt]);
+      a1[rt] = HF_MFMA(a_h, es[ks], a1[rt]);
+      o[rt] = HF_MFMA(a_h, el[ks], o[rt]);
+      a1[rt] = HF_MFMA(a_d, eh[ks], a1[rt]);
+      o[rt] = HF_MFMA(a_l, eh[ks], o[rt]);
+      __builtin_amdgcn_sched_barrier(0);
+    });
+  };
+
+  const int n_end = min(p.S, m0 + 128);
+  const int nkt = (n_end + 31) / 32;
+  issue(0, 0);
+  for (int kt0 = 0; kt0 < nkt; kt0 += 2) {
+    static_for<2>([&](auto s_c) {
+      constexpr int S = decltype(s_c)::value;
+      const int kt = kt0 + S;
+      if (kt < nkt) {
+        const int n0 = kt * 32;
+        HF_WAIT_VMCNT(0);                 // this wave's part of tile kt has landed
+        __builtin_amdgcn_s_barrier();     // everyone's has, and stage 1 - S has been read for the last time
+        __builtin_amdgcn_sched_barrier(0);
+        if (kt + 1 < nkt) issue(1 - S, n0 + 32);
+        // (wave-uniform) keys beyond this wave's diagonal, or a wave without a valid query: nothing to do
+        if (n0 <= mw + 31 && mw < p.S) compute(s_c, n0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    });
   }
   if (mw >= p.S) return;
   const float l = l_run + __shfl_xor(l_run, 32, 64);
@@ -294,7 +392,7 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const AttnP p) {
 // ---------------------------------------------------------------- backward: dQ ----
 
 template <int DH>
-__global__ __launch_bounds__(256) void attn_bwd_q_kernel(const AttnP p) {
+__global__ __launch_bounds__(256, (DH <= 64 ? 2 : 1)) void attn_bwd_q_kernel(const AttnP p) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
   HF_LDS bf16* sm = (HF_LDS bf16*)smem_raw;
   constexpr int TILE = 32 * DH, KS = DH / 16, RT = DH / 32;
@@ -414,7 +512,7 @@ __global__ __launch_bounds__(256) void attn_bwd_q_kernel(const AttnP p) {
 // WHAT & 1: dV, dV_t;  WHAT & 2: dK, dK_t.
 
 template <int DH, int WHAT>
-__global__ __launch_bounds__(256) void attn_bwd_kv_kernel(const AttnP p) {
+__global__ __launch_bounds__(256, (DH <= 32 ? 2 : 1)) void attn_bwd_kv_kernel(const AttnP p) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
   HF_LDS bf16* sm = (HF_LDS bf16*)smem_raw;
   constexpr int TILE = 32 * DH, KS = DH / 16, RT = DH / 32;
@@ -594,10 +692,15 @@ hipError_t launch_attn_fwd(const AttnP& p, hipStream_t st) {
   if (!al16(p.qkv) || !al16(p.qkv_lo) || !al16(p.qkv_t) || !al16(p.o) || !al16(p.o_lo) || !al16(p.o_t) || !p.stat) return hipErrorInvalidValue;
   const int nqt = (p.S + 127) / 128;
   const unsigned grid = (unsigned)(((p.B * p.H + 7) / 8) * 8 * nqt);
-  const size_t lds = (size_t)6 * 32 * p.dh * 2;
+  const size_t lds = (size_t)2 * 6 * 32 * p.dh * 2;  // two stages of six tiles
   if (p.dh == 32) hipLaunchKernelGGL(attn_fwd_kernel<32>, dim3(grid), dim3(256), lds, st, p);
   else if (p.dh == 64) hipLaunchKernelGGL(attn_fwd_kernel<64>, dim3(grid), dim3(256), lds, st, p);
-  else hipLaunchKernelGGL(attn_fwd_kernel<128>, dim3(grid), dim3(256), lds, st, p);
+  else {
+    static OncePerDevice once;
+    const hipError_t e = once.lds_limit((const void*)attn_fwd_kernel<128>, (int)lds);  // 96 KB
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(attn_fwd_kernel<128>, dim3(grid), dim3(256), lds, st, p);
+  }
   return hipGetLastError();
 }
 

@@ -84,6 +84,7 @@ struct hf_ctx {
   void *dS = nullptr, *dS_t = nullptr;
   float *dx = nullptr, *dx_t = nullptr, *tmpd = nullptr, *tmpd_t = nullptr;
   void *dxb = nullptr, *dxb_t = nullptr, *dob = nullptr, *dob_t = nullptr;
+  void *dxb2 = nullptr, *dxb2_t = nullptr;  // second pair of bf16 adjoint copies (grouped weight-gradient launches)
   void *dqkv = nullptr, *dqkv_t = nullptr;
   void *dg = nullptr, *dg_t = nullptr, *dup = nullptr, *dup_t = nullptr, *dy = nullptr, *dy_t = nullptr;
   void* xin = nullptr;  // MLP input in operand type (bf16 mode)

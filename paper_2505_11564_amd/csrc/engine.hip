@@ -162,7 +162,7 @@ int hf_ctx::plan_and_alloc() {
     }
     pl.add(dS, SSa * e); pl.add(dS_t, SSa * e);
     pl.add(dx, T * D * 4); pl.add(dx_t, T * D * 4); pl.add(tmpd, T * D * 4); pl.add(tmpd_t, T * D * 4);
-    if (bf) { pl.add(dxb, T * D * e); pl.add(dxb_t, T * D * e); }
+    if (bf) { pl.add(dxb, T * D * e); pl.add(dxb_t, T * D * e); pl.add(dxb2, T * D * e); pl.add(dxb2_t, T * D * e); }
     pl.add(dob, T * D * e); pl.add(dob_t, T * D * e);
     pl.add(dqkv, T * W3 * e); pl.add(dqkv_t, T * W3 * e);
     pl.add(dg, T * F * e); pl.add(dg_t, T * F * e);
@@ -192,7 +192,7 @@ int hf_ctx::plan_and_alloc() {
     return fail(HF_ENOMEM, "hipMalloc of " + std::to_string(arena_bytes) + " bytes failed: " + hipGetErrorString(e1));
   }
   for (auto& f : pl.fix) *f.first = arena + f.second;
-  if (!bf) { dxb = dx; dxb_t = dx_t; }
+  if (!bf) { dxb = dx; dxb_t = dx_t; dxb2 = dx; dxb2_t = dx_t; }
   if (max_m > 0) {
     e1 = hipHostMalloc((void**)&host_scal, (S_COUNT + 2) * sizeof(double), hipHostMallocDefault);
     if (e1 != hipSuccess) return fail(HF_ENOMEM, std::string("hipHostMalloc failed: ") + hipGetErrorString(e1));
@@ -280,8 +280,10 @@ struct Lin {
   }
 
   // (Hv)_W = X_t^T dY + X^T dY_t  -> out[woff] as [Kin, Nout];  (Hv)_b += colsum(dY_t).
+  // defer != nullptr: the product is described there instead of launched (the caller launches the
+  // products of a layer together); the bias sums are still taken at once.
   int bwd_dw(const void* X, const void* X_t, const void* dY, const void* dY_t, int T, int Kin, int Nout, int64_t ldx,
-             int64_t lddy, int64_t woff, int64_t boff, const void* dYt_for_bias, int bias_src_bf16) const {
+             int64_t lddy, int64_t woff, int64_t boff, const void* dYt_for_bias, int bias_src_bf16, Gemm* defer = nullptr) const {
     Gemm g;
     g.M = Kin; g.N = Nout; g.K = T; g.lda = ldx; g.ldb = lddy; g.ldc = Nout; g.transA = 1;
     g.in_bf16 = bf; g.out_bf16 = 0;
@@ -291,7 +293,8 @@ struct Lin {
     if (c->acc_mode) g.Cadd = out + woff;
     if (X_t) { g.A[0] = X_t; g.B[0] = dY; g.A[1] = X; g.B[1] = dY_t; }
     else { g.A[0] = X; g.B[0] = dY_t; }
-    CK(launch_gemm(g, st));
+    if (defer) *defer = g;
+    else CK(launch_gemm(g, st));
     if (boff >= 0) CK(launch_colsum(bias_src_bf16, dYt_for_bias, T, Nout, lddy, out + boff, st));
     return HF_OK;
   }
@@ -575,11 +578,22 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
     LayerBuf& b = lb[l];
     const LayerOff& o = loff[l];
     // ---- MLP branch
+    // GPT, small models: the four weight-gradient products of a layer (few output tiles each, a long
+    // contraction over the tokens) are only described here and launched together once the last of
+    // their operands exists; the two norm adjoints of a layer then write their bf16 copies to
+    // different buffers, so that the first is still there when the group runs.
+    Gemm dw[4];
+    int ndw = 0;
+    const bool group_dw = bf && !llama && (dw_prezeroed || acc_mode);
+    void* const dxa = dxb;                        // adjoint entering the layer (bf16 copy) and its tangent
+    void* const dxa_t = dxb_t;
+    void* const dxm = group_dw ? dxb2 : dxb;      // adjoint between the two branches
+    void* const dxm_t = group_dw ? dxb2_t : dxb_t;
     if (!llama) {
-      if ((rc = L.bwd_dw(b.g, b.g_t, dxb, dxb_t, T, F, D, F, D, o.wproj, -1, nullptr, 0))) return rc;
-      if ((rc = L.bwd_dx(dxb, dxb_t, T, F, D, D, o.wproj, dg, dg_t, F, bf))) return rc;
+      if ((rc = L.bwd_dw(b.g, b.g_t, dxa, dxa_t, T, F, D, F, D, o.wproj, -1, nullptr, 0, group_dw ? &dw[ndw++] : nullptr))) return rc;
+      if ((rc = L.bwd_dx(dxa, dxa_t, T, F, D, D, o.wproj, dg, dg_t, F, bf))) return rc;
       CK(launch_act_bwd(bf, gelu_kind, b.f, b.f_t, dg, dg_t, dg, dg_t, (int64_t)T * F, st));
-      if ((rc = L.bwd_dw(b.m, b.m_t, dg, dg_t, T, D, F, D, F, o.wfc, o.bfc, dg_t, bf))) return rc;
+      if ((rc = L.bwd_dw(b.m, b.m_t, dg, dg_t, T, D, F, D, F, o.wfc, o.bfc, dg_t, bf, group_dw ? &dw[ndw++] : nullptr))) return rc;
       if ((rc = L.bwd_dx(dg, dg_t, T, D, F, F, o.wfc, tmpd, tmpd_t, D, 0))) return rc;
     } else {
       if ((rc = L.bwd_dw(b.g, b.g_t, dxb, dxb_t, T, F, D, F, D, o.wdown, -1, nullptr, 0))) return rc;
@@ -591,11 +605,11 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
       if ((rc = L.bwd_dx(dup, dup_t, T, D, F, F, o.wup, tmpd, tmpd_t, D, 0, tmpd, tmpd_t))) return rc;
     }
     CK(launch_norm_bwd(bf, rms, tmpd, tmpd_t, b.x2, b.x2_t, b.st2, L.Wp(o.n2g), v + o.n2g, T, D, 1, dx, dx_t,
-                       out + o.n2g, rms ? nullptr : out + o.n2b, norm_part, st, bf ? dxb : nullptr, bf ? dxb_t : nullptr,
+                       out + o.n2g, rms ? nullptr : out + o.n2b, norm_part, st, bf ? dxm : nullptr, bf ? dxm_t : nullptr,
                        o.bo >= 0 ? out + o.bo : nullptr));
     // ---- attention branch
-    if ((rc = L.bwd_dw(b.o, b.o_t, dxb, dxb_t, T, D, D, D, D, o.wo, -1, nullptr, 0))) return rc;
-    if ((rc = L.bwd_dx(dxb, dxb_t, T, D, D, D, o.wo, dob, dob_t, D, bf))) return rc;
+    if ((rc = L.bwd_dw(b.o, b.o_t, dxm, dxm_t, T, D, D, D, D, o.wo, -1, nullptr, 0, group_dw ? &dw[ndw++] : nullptr))) return rc;
+    if ((rc = L.bwd_dx(dxm, dxm_t, T, D, D, D, o.wo, dob, dob_t, D, bf))) return rc;
     // Products whose result belongs to a key/value head sum over the grp query heads that share
     // it: one launch per member j of the groups (batch = key/value heads, query head kv * grp + j),
     // the first writing and the others adding to an fp32 result.
@@ -695,7 +709,8 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
     }
     }
     if (!llama) {
-      if ((rc = L.bwd_dw(b.a, b.a_t, dqkv, dqkv_t, T, D, 3 * D, D, W3, o.wqkv, o.bqkv, dqkv_t, bf))) return rc;
+      if ((rc = L.bwd_dw(b.a, b.a_t, dqkv, dqkv_t, T, D, 3 * D, D, W3, o.wqkv, o.bqkv, dqkv_t, bf, group_dw ? &dw[ndw++] : nullptr))) return rc;
+      if (ndw > 0) CK(launch_gemm_group(dw, ndw, st));
       if ((rc = L.bwd_dx(dqkv, dqkv_t, T, D, 3 * D, W3, o.wqkv, tmpd, tmpd_t, D, 0))) return rc;
     } else {
       CK(launch_rope(bf, rq, rq_t, RQ, dqkv, dqkv_t, nullptr, W3, T, S, H + Hkv, dh, desc.rope_theta, 1, st));

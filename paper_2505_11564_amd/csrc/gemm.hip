@@ -391,6 +391,29 @@ static hipError_t launch_prepared(int kind, const Gemm& g, GemmP& p, hipStream_t
   return launch_bf16_cfg<BM, BN, 64, 64>(p, grid, st);
 }
 
+// Several single-output products in one launch where that pays (A^T B products with few output
+// tiles each: the weight-gradient products of a layer of a small model); otherwise one by one.
+hipError_t launch_gemm_group(const Gemm* gs, int n, hipStream_t st) {
+  if (n >= 2 && n <= 4) {
+    GemmP ps[4];
+    bool ok = true;
+    for (int i = 0; i < n && ok; ++i) {
+      const Gemm& g = gs[i];
+      ok = !g.Ct && g.nb1 == 1 && g.nb2 == 1 && g.allow_splitk && g.in_bf16 && g.force_cfg < 0 &&
+           (g.c_zeroed || (g.Cadd && g.Cadd == (const float*)g.C)) && prepare_single(g, ps[i]) == 2;
+    }
+    if (ok) {
+      const hipError_t e = launch_gemm_mfma_group(ps, n, st);
+      if (e != hipErrorNotSupported) return e;
+    }
+  }
+  for (int i = 0; i < n; ++i) {
+    const hipError_t e = launch_gemm(gs[i], st);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
 static hipError_t launch_gemm_single(const Gemm& g, hipStream_t st) {
   GemmP p;
   const int kind = prepare_single(g, p);

@@ -43,8 +43,10 @@ template <int BM, int BN, int KT, int NS>
 constexpr int min_blocks() { return (BM == 128 && BN == 128 && KT == 32 && NS == 2) ? 3 : 1; }
 
 // The body of the kernel: one block's product.  ks / nks: this block's part of a k-split.
+// given_tile >= 0: the block's tile index is given (a launch that deals the tiles of several
+// products to its blocks itself) instead of derived from the block index.
 template <int BM, int BN, int WM, int WN, int KT, int NS, bool TA, bool TB, int FL>
-__device__ __forceinline__ void gemm_mfma_body(const GemmP& p, const int ks, const int nks) {
+__device__ __forceinline__ void gemm_mfma_body(const GemmP& p, const int ks, const int nks, const int given_tile = -1) {
   static_assert((BM / WM) * (BN / WN) == 4, "four waves");
   static_assert(NS == 2, "stages");
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
@@ -61,7 +63,10 @@ __device__ __forceinline__ void gemm_mfma_body(const GemmP& p, const int ks, con
   // batch entries (heads) c, c + 8, ...: every XCD gets the same mix of long and short tile
   // rows, and a head's B operand (V, K, Q or dO) is fetched by one L2 only.
   int tile = blockIdx.x, z = blockIdx.y;
-  {
+  if (given_tile >= 0) {
+    tile = given_tile;
+    z = 0;
+  } else {
     const int nt = gridDim.x;
     if (p.klimit && (gridDim.y & 7) == 0) {
       // launch-order index L: XCD L % 8, its r-th block; XCD c walks the tiles of batch entry c,
@@ -94,7 +99,7 @@ __device__ __forceinline__ void gemm_mfma_body(const GemmP& p, const int ks, con
   // Causal products (k clipped to the tile row's triangle) cost in proportion to the row index.
   // The second half of the batch walks the rows in reverse, so that the two blocks a CU holds at a
   // time (ids b and b + half the grid) are a heavy and a light one.
-  if (p.klimit && blockIdx.y * 2 >= gridDim.y) tm = tiles_m - 1 - tm;
+  if (given_tile < 0 && p.klimit && blockIdx.y * 2 >= gridDim.y) tm = tiles_m - 1 - tm;
   const int m0 = tm * BM, n0 = tn * BN;
   if (p.skip_upper && n0 > m0 + BM - 1) return;
   const int z1 = z / p.nb2, z2 = z % p.nb2;
@@ -426,6 +431,26 @@ __global__ __launch_bounds__(256, (min_blocks<BM, BN, KT, NS>())) void gemm_mfma
   gemm_mfma_body<BM, BN, WM, WN, KT, NS, TA, TB, FL>(pp.g[blockIdx.z], 0, 1);
 }
 
+// Up to four A^T B products (the weight-gradient products of one layer: few output tiles each, a
+// long contraction over the tokens) as one launch of 256 x 256 tiles: block b works on part
+// (b - first[g]) / tiles[g] of the k-split of tile (b - first[g]) % tiles[g] of product g and adds
+// its result with atomics, so every C must hold zeros (or what the sum is added to) beforehand.
+struct GemmGroup {
+  GemmP g[4];
+  int first[5];   // first block of each product; first[n] = number of blocks
+  int tiles[4];
+  int nks[4];
+  int n;
+};
+template <int BM, int BN, int WM, int WN, int KT, int NS, bool TA, bool TB, int FL = 1>
+__global__ __launch_bounds__(256, 1) void gemm_mfma_group_kernel(GemmGroup gg) {
+  const int b = blockIdx.x;
+  int g = 0;
+  while (g + 1 < gg.n && b >= gg.first[g + 1]) ++g;
+  const int local = b - gg.first[g];
+  gemm_mfma_body<BM, BN, WM, WN, KT, NS, TA, TB, FL>(gg.g[g], local / gg.tiles[g], gg.nks[g], local % gg.tiles[g]);
+}
+
 template <int BM, int BN, int WM, int WN, int KT, int NS, bool TA, bool TB, int FL = 1>
 static hipError_t launch_one(const GemmP& p, dim3 grid, hipStream_t st) {
   constexpr int smem_pipe = NS * (BM + BN) * KT * 2, smem_epi = 4 * 32 * (WN + 4) * 4;
@@ -621,6 +646,54 @@ hipError_t launch_gemm_mfma_pair(GemmP a, GemmP b, int nb, hipStream_t st) {
   dim3 grid((unsigned)t128, 1, 2);
   if (!a.transA && !a.transB && a.K < 1536) return launch_pair_cfg<128, 128, 64, 64, 32, 2, 2>(pp, grid, st);
   return launch_pair_cfg<128, 128, 64, 64, 64, 2, 2>(pp, grid, st);
+}
+
+// The A^T B products ps[0..n) (fp32 results that are zero or hold what the sum is added to, no
+// bias, operands on the fast path) as one launch.  hipErrorNotSupported: launch them one by one.
+hipError_t launch_gemm_mfma_group(const GemmP* ps, int n, hipStream_t st) {
+  if (n < 2 || n > 4) return hipErrorNotSupported;
+  GemmGroup gg = {};
+  gg.n = n;
+  int64_t tiles_total = 0;
+  int min_slabs = 1 << 30;
+  for (int i = 0; i < n; ++i) {
+    const GemmP& p = ps[i];
+    if (!p.transA || p.transB || p.out_bf16 || p.klimit || p.skip_upper || p.bias || p.bias_t || p.C_lo) return hipErrorNotSupported;
+    if (p.Cadd && p.Cadd != (const float*)p.C) return hipErrorNotSupported;
+    if (p.ldc != p.N || p.K < 512) return hipErrorNotSupported;
+    gg.g[i] = p;
+    gg.g[i].tiles_n = (p.N + 255) / 256;
+    gg.g[i].Cadd = nullptr;  // the parts add to C with atomics
+    {
+      auto al = [&](const void* x) { return x == nullptr || ((uintptr_t)x % 16) == 0; };
+      gg.g[i].vecA = al(p.C) && p.ldc % 4 == 0;
+    }
+    gg.tiles[i] = ((p.M + 255) / 256) * ((p.N + 255) / 256);
+    tiles_total += gg.tiles[i];
+    min_slabs = std::min(min_slabs, p.K / 64);
+  }
+  if (tiles_total >= 256 || tiles_total < 16) return hipErrorNotSupported;
+  // parts per tile: as many as keep all blocks resident at once (one per CU).  More rounds of
+  // shorter parts were slower: a part ends with 65536 atomic adds, which cost as much as about 40
+  // slabs of the product (756 blocks of 18 slabs: 262 us for the four products of a GPT-2-small
+  // layer; 216 blocks of 64 slabs: see the kernel trace).
+  int best = (int)(256 / tiles_total);
+  while (best > 1 && min_slabs / best < 8) --best;
+  if (best < 2) return hipErrorNotSupported;  // nothing is split: atomics would only cost
+  int first = 0;
+  for (int i = 0; i < n; ++i) {
+    gg.first[i] = first;
+    gg.nks[i] = best;
+    first += gg.tiles[i] * best;
+  }
+  gg.first[n] = first;
+  constexpr int smem_pipe = 2 * (256 + 256) * 64 * 2, smem_epi = 4 * 32 * (128 + 4) * 4;
+  constexpr int smem = smem_pipe > smem_epi ? smem_pipe : smem_epi;
+  static OncePerDevice once;
+  auto kern = gemm_mfma_group_kernel<256, 256, 128, 128, 64, 2, true, false, 2>;
+  if (hipError_t e = once.lds_limit((const void*)kern, smem); e != hipSuccess) return e;
+  hipLaunchKernelGGL(kern, dim3((unsigned)first), dim3(256), smem, st, gg);
+  return hipGetLastError();
 }
 
 }  // namespace hf

@@ -34,4 +34,8 @@ hipError_t launch_gemm_mfma(GemmP p, int nb, int allow_splitk, int force_cfg, in
 // Two products of one shape (primal and tangent) in one launch; hipErrorNotSupported = launch them separately.
 hipError_t launch_gemm_mfma_pair(GemmP a, GemmP b, int nb, hipStream_t st);
 
+// Several A^T B products with fp32 results as one launch of 256 x 256 tiles with split k (atomic
+// accumulation into results that are zero or hold the addend); hipErrorNotSupported = launch them separately.
+hipError_t launch_gemm_mfma_group(const GemmP* ps, int n, hipStream_t st);
+
 }  // namespace hf

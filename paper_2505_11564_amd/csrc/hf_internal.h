@@ -93,6 +93,9 @@ enum { EPI_NONE = 0, EPI_FWD_STATS = 1, EPI_FWD_SOFTMAX = 2, EPI_BWD_STATS = 3, 
 
 hipError_t launch_gemm(const Gemm& g, hipStream_t st);
 hipError_t launch_gemm_dual(const Gemm& g, hipStream_t st);  // bf16, aligned operands only
+// gs[0..n): single-output products whose results are already zero (c_zeroed) or are added to
+// (Cadd == C); launched as one grid where that is faster, else in turn.
+hipError_t launch_gemm_group(const Gemm* gs, int n, hipStream_t st);
 // bf16 A^T B product [M, N] over k = K with fp32 result and split-K allowed: will it accumulate with atomics?
 bool gemm_mfma_splits_k(int M, int N, int K, int nterm);
 
