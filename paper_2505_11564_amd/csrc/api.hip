@@ -250,12 +250,12 @@ int32_t hf_lanczos_init(hf_ctx* ctx, const float* q0_dev, int32_t reorth, void* 
   // q_0 = q0 / ||q0||: row 0 of an fp32 basis is the working vector itself; a bf16 basis takes the
   // rounded copy, which is also the bf16 operand of the first product
   void* row0 = reorth == HF_REORTH_FULL ? c->basis : nullptr;
-  bf16* vdst = c->bf ? ((bq && row0) ? nullptr : c->vb) : nullptr;
+  bf16* vdst = c->bf ? ((bq && row0) ? nullptr : ((rows && c->basis_bf) ? c->basis_bf : c->vb)) : nullptr;
   CKI(lz_scale(q0_dev, rows ? nullptr : c->lz_vec[c->iq], row0, bq, vdst, c->n, c->scal, S_Q0NORM, 0.0, nullptr, st));
   c->lz_k = 0;
   c->lz_done = 0;
   c->lz_beta_prev = 0.0;
-  c->vb_cur = c->bf ? ((bq && row0) ? (const bf16*)row0 : c->vb) : nullptr;
+  c->vb_cur = c->bf ? ((bq && row0) ? (const bf16*)row0 : vdst) : nullptr;
   c->vb_of = c->bf ? c->cur_q() : nullptr;
   return HF_OK;
 }
@@ -587,6 +587,9 @@ int32_t hf_lanczos_import(hf_ctx* ctx, const void* state_dev, int64_t bytes, voi
   if (h.rows > 0)
     CKI(hipMemcpy2DAsync(c->basis, (size_t)c->ldq * be, base + 128 + 2 * vb, (size_t)c->n * be, (size_t)c->n * be, (size_t)h.rows,
                          hipMemcpyDeviceToDevice, st));
+  if (c->basis_bf)  // the bf16 copies of the rows are not part of the image
+    for (int64_t j = 0; j < h.rows; ++j)
+      CKI(launch_f32_to_bf16((const float*)c->basis + j * c->ldq, c->basis_bf + j * c->ldq, c->n, st));
   CKI(hipStreamSynchronize(st));
   c->lz_k = (int)h.k;
   c->lz_reorth = (int)h.reorth;

@@ -102,6 +102,11 @@ struct hf_ctx {
   float* lz_vec[3] = {nullptr, nullptr, nullptr};
   int iq = 0, iqp = 1, ir = 2;
   void* basis = nullptr;
+  // bf16 copies of the rows of an fp32 basis, kept by contexts with bf16 parameters: row k is the
+  // operand-type copy of q_k that the product multiplies with anyway, and the subtraction pass of
+  // the orthogonalisation reads rows 0 .. k-2 from here at half the bytes (their coefficients are
+  // at rounding level, so the rounding of the copies is below that of the fp32 result)
+  hf::bf16* basis_bf = nullptr;
   int64_t ldq = 0;
   double *scal = nullptr, *cvec = nullptr, *partials = nullptr;
   double* host_scal = nullptr;  // pinned, S_COUNT + 2 doubles

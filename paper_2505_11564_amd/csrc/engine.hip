@@ -180,6 +180,7 @@ int hf_ctx::plan_and_alloc() {
     for (int i = 0; i < 3; ++i) pl.add(lz_vec[i], n * 4);
     ldq = round_up(n, 64);
     if (desc.basis_dtype != HF_NONE) pl.add(basis, (int64_t)max_m * ldq * (desc.basis_dtype == HF_BF16 ? 2 : 4));
+    if (desc.basis_dtype == HF_F32 && bf) pl.add(basis_bf, (int64_t)max_m * ldq * 2);
     pl.add(scal, S_COUNT * 8);
     pl.add(cvec, (int64_t)(max_m + 1) * 8);
     pl.add(partials, std::max<int64_t>((int64_t)LZ_NBLK * (max_m + 1), 3 * LZ_NBLK_VEC) * 8);
@@ -762,18 +763,18 @@ int hf_ctx::lanczos_update(float* r, double tol, double* alpha_k, double* beta_k
     // Gram-Schmidt of H q_k against q_0 .. q_k is the three-term subtraction and the
     // orthogonalisation in one.  An fp32 basis holds q_k and q_{k-1} as its rows k and k - 1; a
     // bf16 basis holds rounded copies, so those two come from the working vectors instead.
-    if (!bq) CK(lz_gs_first_pass((const float*)basis, ldq, r, n, k + 1, scal, cvec, partials, st));
+    if (!bq) CK(lz_gs_first_pass((const float*)basis, basis_bf, ldq, r, n, k + 1, scal, cvec, partials, st));
     else CK(lz_gs_first_pass_bf16((const bf16*)basis, ldq, qp, q, r, n, k, scal, cvec, partials, st));
-    CK(lz_reorth_pass(basis, bq, ldq, r, n, k + 1, 1, scal, cvec, partials, st));
+    CK(lz_reorth_pass(basis, bq, bq ? nullptr : basis_bf, ldq, r, n, k + 1, 1, scal, cvec, partials, st));
     // q_{k+1} = r / beta_k: an fp32 basis takes it as row k + 1 and nowhere else (the rows are the
     // working vectors); a bf16 basis takes the rounded copy, which is also the operand-type copy
     // the next product multiplies with, and the fp32 vector goes over q_{k-1}.
     void* row = k + 1 < max_m ? (char*)basis + (int64_t)(k + 1) * ldq * (bq ? 2 : 4) : nullptr;
     spill = rows ? (row ? nullptr : lz_vec[iq]) : qp;
     bf16* vdst = nullptr;
-    if (bf) vdst = (bq && row) ? nullptr : vb;
+    if (bf) vdst = (bq && row) ? nullptr : ((basis_bf && row) ? basis_bf + (int64_t)(k + 1) * ldq : vb);
     CK(lz_scale(r, spill, row, bq, vdst, n, scal, S_BETA, tol, hvp_flags, st));
-    next_vb = bf ? ((bq && row) ? (const bf16*)row : vb) : nullptr;
+    next_vb = bf ? ((bq && row) ? (const bf16*)row : vdst) : nullptr;
   } else {
     CK(lz3_update(r, q, qp, bf ? vb : nullptr, n, k > 0, lz_beta_prev, tol, hvp_flags, scal, partials, st));
     next_vb = bf ? vb : nullptr;

@@ -34,12 +34,14 @@ hipError_t lz_scale(const float* src, float* dst, void* basis, int basis_bf16, b
                     double tol, const int* flags, hipStream_t st);
 // One classical Gram-Schmidt pass of r against Q[0..nq); pass 1 is a no-op
 // unless pass 0 set the redo flag.
-hipError_t lz_reorth_pass(const void* Q, int basis_bf16, int64_t ldq, float* r, int64_t n, int nq, int pass,
+// copies (optional, fp32 basis only): bf16 copies of the rows, same row stride; the subtraction
+// reads rows 0 .. nq-3 from them.
+hipError_t lz_reorth_pass(const void* Q, int basis_bf16, const bf16* copies, int64_t ldq, float* r, int64_t n, int nq, int pass,
                           double* scal, double* c, double* partials, hipStream_t st);
 // The first pass applied to w = H q_k itself against an fp32 basis holding q_0 .. q_k (nq = k + 1):
 // also yields alpha_k, in place of lz_axpy_dot and lz_axpy_nrm.
-hipError_t lz_gs_first_pass(const float* Q, int64_t ldq, float* r, int64_t n, int nq, double* scal, double* c,
-                            double* partials, hipStream_t st);
+hipError_t lz_gs_first_pass(const float* Q, const bf16* copies, int64_t ldq, float* r, int64_t n, int nq, double* scal,
+                            double* c, double* partials, hipStream_t st);
 // The same for a bf16 basis: q_k and q_{k-1} come from the fp32 working vectors, rows 0 .. k-2 from the basis.
 hipError_t lz_gs_first_pass_bf16(const bf16* Q, int64_t ldq, const float* qkm1, const float* qk, float* r, int64_t n, int k,
                                  double* scal, double* c, double* partials, hipStream_t st);

@@ -577,7 +577,21 @@ hipError_t lz_scale(const float* src, float* dst, void* basis, int basis_bf16, b
   return hipGetLastError();
 }
 
-hipError_t lz_reorth_pass(const void* Q, int basis_bf16, int64_t ldq, float* r, int64_t n, int nq, int pass,
+// r -= Q c for an fp32 basis of nq rows.  With bf16 copies of the rows at hand, rows 0 .. nq-3 are
+// read from the copies (their coefficients are what rounding left of the orthogonality, so the
+// rounding of a copy changes r far below its own last bit) and rows nq-2, nq-1, which carry
+// beta_{k-1} and alpha_k, from the basis.
+static void launch_sub_f32(const float* Q, const bf16* copies, int64_t ldq, float* r, int64_t n, int nq, int64_t nslices,
+                           int nb, const double* c, const double* scal, int pass, double* partials, hipStream_t st) {
+  const size_t sh = (size_t)nq * sizeof(float);
+  if (copies && nq >= 3)
+    hipLaunchKernelGGL((lz_sub_qc_kernel<bf16, true>), dim3(nb), dim3(256), sh, st, copies, ldq, r, n, nq - 2, nslices, c, scal,
+                       pass, partials, Q + (int64_t)(nq - 2) * ldq, Q + (int64_t)(nq - 1) * ldq);
+  else
+    hipLaunchKernelGGL(lz_sub_qc_kernel<float>, dim3(nb), dim3(256), sh, st, Q, ldq, r, n, nq, nslices, c, scal, pass, partials);
+}
+
+hipError_t lz_reorth_pass(const void* Q, int basis_bf16, const bf16* copies, int64_t ldq, float* r, int64_t n, int nq, int pass,
                           double* scal, double* c, double* partials, hipStream_t st) {
   if (nq <= 0) return hipSuccess;
   const int64_t nslices = (n + LZ_SLICE - 1) / LZ_SLICE;
@@ -590,7 +604,7 @@ hipError_t lz_reorth_pass(const void* Q, int basis_bf16, int64_t ldq, float* r, 
   } else {
     hipLaunchKernelGGL(lz_qtr_kernel<float>, dim3(nb), dim3(256), sh1, st, (const float*)Q, ldq, r, n, nq, nslices, scal, pass, partials);
     hipLaunchKernelGGL(lz_qtr_finish_kernel, dim3(nq), dim3(256), 0, st, partials, nb, scal, pass, c);
-    hipLaunchKernelGGL(lz_sub_qc_kernel<float>, dim3(nb), dim3(256), sh2, st, (const float*)Q, ldq, r, n, nq, nslices, c, scal, pass, partials);
+    launch_sub_f32((const float*)Q, copies, ldq, r, n, nq, nslices, nb, c, scal, pass, partials, st);
   }
   hipLaunchKernelGGL(lz_finish_kernel, dim3(1), dim3(256), 0, st, partials, nb, 3, pass, scal);
   return hipGetLastError();
@@ -601,16 +615,16 @@ hipError_t lz_reorth_pass(const void* Q, int basis_bf16, int64_t ldq, float* r, 
 // beta_{k-1}, so the pass subsumes the three-term subtraction, which saves its two passes over the
 // vectors.  Leaves alpha_k, ||r|| and the redo flag in scal as the three-term kernels followed by
 // lz_reorth_pass(pass 0) do.  c: nq + 1 doubles, partials: (nq + 1) * LZ_NBLK doubles.
-hipError_t lz_gs_first_pass(const float* Q, int64_t ldq, float* r, int64_t n, int nq, double* scal, double* c,
-                            double* partials, hipStream_t st) {
+hipError_t lz_gs_first_pass(const float* Q, const bf16* copies, int64_t ldq, float* r, int64_t n, int nq, double* scal,
+                            double* c, double* partials, hipStream_t st) {
   if (nq <= 0) return hipErrorInvalidValue;
   const int64_t nslices = (n + LZ_SLICE - 1) / LZ_SLICE;
   const int nb = (int)std::max<int64_t>(1, std::min<int64_t>(nslices, LZ_NBLK));
-  const size_t sh1 = (size_t)4 * (nq + 1) * sizeof(double), sh2 = (size_t)nq * sizeof(float);
+  const size_t sh1 = (size_t)4 * (nq + 1) * sizeof(double);
   hipLaunchKernelGGL((lz_qtr_kernel<float, true>), dim3(nb), dim3(256), sh1, st, Q, ldq, r, n, nq, nslices, scal, 0, partials);
   hipLaunchKernelGGL(lz_qtr_finish_kernel, dim3(nq + 1), dim3(256), 0, st, partials, nb, scal, 0, c);
   hipLaunchKernelGGL(lz_direct_scal_kernel, dim3(1), dim3(64), 0, st, c, nq, scal);
-  hipLaunchKernelGGL(lz_sub_qc_kernel<float>, dim3(nb), dim3(256), sh2, st, Q, ldq, r, n, nq, nslices, c, scal, 0, partials);
+  launch_sub_f32(Q, copies, ldq, r, n, nq, nslices, nb, c, scal, 0, partials, st);
   hipLaunchKernelGGL(lz_finish_kernel, dim3(1), dim3(256), 0, st, partials, nb, 3, 0, scal);
   return hipGetLastError();
 }

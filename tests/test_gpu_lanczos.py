@@ -43,13 +43,15 @@ def run_update_only(ctx, dvec, z, m, reorth, tol=0.0):
 UPDATE_MODELS = {"n54032": si._gpt(1, 40, 2, 72, 1001, 33), "n56981_ragged": si._gpt(1, 42, 2, 71, 1001, 33)}
 
 
-@pytest.mark.parametrize("basis", ["f32", "bf16"])
+# (parameter type, basis type): with bf16 parameters and an fp32 basis the subtraction pass reads
+# the old rows from bf16 copies, which must leave the coefficients at fp32 level
+@pytest.mark.parametrize("dtype,basis", [("f32", "f32"), ("f32", "bf16"), ("bf16", "f32")])
 @pytest.mark.parametrize("reorth", ["none", "full"])
 @pytest.mark.parametrize("size", list(UPDATE_MODELS))
-def test_update_kernels_diagonal_operator(size, reorth, basis):
+def test_update_kernels_diagonal_operator(size, reorth, basis, dtype):
     import paper_2505_11564_amd as hf
     model = UPDATE_MODELS[size]
-    ctx = hf.Context(model, 1, 48, "f32", basis)
+    ctx = hf.Context(model, 1, 48, dtype, basis)
     n = ctx.n
     assert (n % 4 != 0) == size.endswith("ragged")
     rng = np.random.default_rng(5)
@@ -217,15 +219,18 @@ def _continue_update_only(ctx, d_dev, steps):
     return al, be
 
 
-@pytest.mark.parametrize("reorth,basis", [("none", "none"), ("full", "f32"), ("full", "bf16")])
-def test_state_export_import_continues_the_same_iteration(reorth, basis):
+@pytest.mark.parametrize("reorth,basis,dtype", [("none", "none", "f32"), ("full", "f32", "f32"), ("full", "bf16", "f32"),
+                                                 ("full", "f32", "bf16")])
+def test_state_export_import_continues_the_same_iteration(reorth, basis, dtype):
     # A run interrupted after 7 iterations, moved through the state image into a
     # fresh context and continued, yields the coefficients of the uninterrupted
-    # run bit for bit (the vector kernels are deterministic).
+    # run bit for bit (the vector kernels are deterministic).  A context with bf16 parameters
+    # keeps bf16 copies of the rows of an fp32 basis, which the image does not hold: the import
+    # rebuilds them.
     import torch
     import paper_2505_11564_amd as hf
     model = si._gpt(1, 40, 2, 72, 1001, 33)
-    a_ctx = hf.Context(model, 1, 20, "f32", basis)
+    a_ctx = hf.Context(model, 1, 20, dtype, basis)
     n = a_ctx.n
     rng = np.random.default_rng(9)
     d_dev = _dev(rng.uniform(-2, 3, n).astype(np.float32))
@@ -236,7 +241,7 @@ def test_state_export_import_continues_the_same_iteration(reorth, basis):
     a_ctx.hf_lanczos_export(image, nbytes)
     rest = _continue_update_only(a_ctx, d_dev, 9)
     a_ctx.close()
-    b_ctx = hf.Context(model, 1, 20, "f32", basis)
+    b_ctx = hf.Context(model, 1, 20, dtype, basis)
     host_copy = image.cpu()                       # the image is plain memory: through the host and back
     image2 = host_copy.cuda()
     b_ctx.hf_lanczos_import(image2, nbytes)
