@@ -121,12 +121,24 @@ __device__ __forceinline__ void store4(void* base, int f32, int64_t row, int64_t
   }
 }
 
-// block -> (batch * head index, tile): whole heads per XCD (launch order L goes to XCD L % 8, so
-// head hh runs on XCD hh % 8 and its operands stay in that L2), tiles in the given order.
-__device__ __forceinline__ bool block_map(int nheads, int ntiles, int& hh, int& tile) {
-  const int L = blockIdx.x, xcd = L & 7, slot = L >> 3;
-  hh = (slot / ntiles) * 8 + xcd;
-  tile = slot % ntiles;
+// block -> (batch * head index, tile rank): whole heads per XCD (launch order L goes to XCD L % 8, so
+// head hh runs on XCD hh % 8 and its operands stay in that L2).  Rank 0 is a head's longest tile
+// (work falls linearly with the rank), and the slots s = L / 8 of an XCD take the (head, rank) items
+// longest first, which is what balances a launch whose later blocks start as earlier ones end.
+// A launch of at most two resident blocks per CU starts all at once instead: the slots go round
+// the XCD's 32 CUs (measured: slots s and s + 32 share a CU), so with N <= 64 items the 64 - N
+// longest run alone and the others in pairs of a longer and a shorter one.
+__device__ __forceinline__ bool block_map(int nheads, int ntiles, int occ, int& hh, int& tile) {
+  constexpr int C = 32;  // CUs per XCD
+  const int L = blockIdx.x, xcd = L & 7, s = L >> 3;
+  const int nhx = (nheads + 7) >> 3, N = nhx * ntiles;
+  int i = s;
+  if (occ == 2 && N > C && N <= 2 * C) {
+    const int P = N - C;  // CUs with two blocks: slots [0, P) and [C, N)
+    i = s < P ? (2 * C - N) + s : (s < C ? s - P : N - 1 - (s - C));
+  }
+  tile = i / nhx;
+  hh = (i % nhx) * 8 + xcd;
   return hh < nheads;
 }
 
@@ -183,7 +195,7 @@ __global__ __launch_bounds__(256, (DH <= 64 ? 2 : 1)) void attn_fwd_kernel(const
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6) & 3;  // (masked so that tile indices below fold)
   const int nqt = (p.S + 127) / 128;
   int hh, tile;
-  if (!block_map(p.B * p.H, nqt, hh, tile)) return;
+  if (!block_map(p.B * p.H, nqt, DH <= 64 ? 2 : 1, hh, tile)) return;
   const int qt = nqt - 1 - tile;  // long rows first
   const int b = hh / p.H, h = hh % p.H, hk = h / p.grp;
   const int m0 = qt * 128, mw = m0 + wave * 32;
@@ -390,16 +402,20 @@ __global__ __launch_bounds__(256, (DH <= 64 ? 2 : 1)) void attn_fwd_kernel(const
 }
 
 // ---------------------------------------------------------------- backward: dQ ----
+// Staged like the forward kernel: two LDS stages of seven tiles (K hi / lo / t and V hi / t with keys
+// on lanes for the score-shaped products, K hi / t once more in the layout of transposing reads for
+// dQ^T = K^T dS^T), filled by direct loads one key tile ahead, one barrier per key tile.
 
 template <int DH>
 __global__ __launch_bounds__(256, (DH <= 64 ? 2 : 1)) void attn_bwd_q_kernel(const AttnP p) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
-  HF_LDS bf16* sm = (HF_LDS bf16*)smem_raw;
-  constexpr int TILE = 32 * DH, KS = DH / 16, RT = DH / 32;
-  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  constexpr int TILE_B = 64 * DH, NT = 7, STAGE_B = NT * TILE_B, KS = DH / 16, RT = DH / 32;
+  constexpr int NQ = NT * (DH / 16), NI = (NQ + 3) / 4;  // load instructions per stage, per wave
+  const int t = threadIdx.x, lane = t & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(t >> 6) & 3;
   const int nqt = (p.S + 127) / 128;
   int hh, tile;
-  if (!block_map(p.B * p.H, nqt, hh, tile)) return;
+  if (!block_map(p.B * p.H, nqt, DH <= 64 ? 2 : 1, hh, tile)) return;
   const int qt = nqt - 1 - tile;
   const int b = hh / p.H, h = hh % p.H, hk = h / p.grp;
   const int m0 = qt * 128, mw = m0 + wave * 32;
@@ -425,10 +441,35 @@ __global__ __launch_bounds__(256, (DH <= 64 ? 2 : 1)) void attn_bwd_q_kernel(con
   const float dl = p.delta[srow * 3], dlt = p.delta[srow * 3 + 1];
 
   const int64_t ok = row0 * p.ldq + p.offK + (int64_t)hk * DH, ov = row0 * p.ldq + p.offV + (int64_t)hk * DH;
-  const bf16 *sKh = p.qkv + ok, *sKl = p.qkv_lo + ok, *sKd = p.qkv_t + ok, *sVh = p.qkv + ov, *sVd = p.qkv_t + ov;
-  // K (high half) and K_t are needed with keys on lanes (scores) and transposed (dQ^T = K^T dS^T)
-  const HF_LDS bf16 *Kh = sm, *Kl = sm + TILE, *Kd = sm + 2 * TILE, *Vh = sm + 3 * TILE, *Vd = sm + 4 * TILE;
-  const HF_LDS bf16 *KhT = sm + 5 * TILE, *KdT = sm + 6 * TILE;
+  uint32_t gpk[NI];
+#pragma unroll
+  for (int i = 0; i < NI; ++i) {
+    const int q = min(wave + 4 * i, NQ - 1);
+    int row, col;
+    LdsLoad<DH>::lane_chunk(q, lane, q / (DH / 16) >= 5, row, col);
+    gpk[i] = (uint32_t)(row | (col << 8));
+  }
+  HF_LDS char* const smem_c = (HF_LDS char*)smem_raw;
+  auto issue = [&](int stage, int r0) {
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const int q = wave + 4 * i;  // (wave-uniform)
+      if (NQ % 4 == 0 || q < NQ) {
+        const int T = q / (DH / 16);  // K hi / lo / t, V hi / t with keys on lanes; K hi / t for transposing reads
+        const bf16* base = T == 0 ? p.qkv + ok : T == 1 ? p.qkv_lo + ok : T == 2 ? p.qkv_t + ok : T == 3 ? p.qkv + ov : T == 4 ? p.qkv_t + ov
+                           : T == 5 ? p.qkv + ok : p.qkv_t + ok;
+        const int rr_ = min(r0 + (int)(gpk[i] & 255u), p.S - 1);
+        __builtin_amdgcn_global_load_lds((const void*)(base + ((int64_t)rr_ * p.ldq + (gpk[i] >> 8))),
+                                         (HF_LDS void*)(smem_c + stage * STAGE_B + q * 1024), 16, 0, 0);
+      }
+    }
+  };
+  const uint32_t lds0 = (uint32_t)(uintptr_t)smem_c;
+  uint32_t adK[KS], adT[RT];
+#pragma unroll
+  for (int kk = 0; kk < KS; ++kk) adK[kk] = lds0 + addr_rows<DH>(lane, kk);
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) adT[rt] = lds0 + addr_cols<DH>(lane, rt);
 
   f32x16 dq[RT], dqt[RT];
 #pragma unroll
@@ -436,40 +477,48 @@ __global__ __launch_bounds__(256, (DH <= 64 ? 2 : 1)) void attn_bwd_q_kernel(con
 #pragma unroll
     for (int v = 0; v < 16; ++v) { dq[i][v] = 0.f; dqt[i][v] = 0.f; }
 
-  const int n_end = min(p.S, m0 + 128);
-  const int nkt = (n_end + 31) / 32;
-  constexpr int PER = StageDim<DH>::PER;
-  at_u32x4 g0[PER], g1[PER], g2[PER], g3[PER], g4[PER];
-  auto load_stage = [&](int r0) {
-    stage_load_one<DH, 0>(g0, sKh, p.ldq, r0, p.S, t); stage_load_one<DH, 1>(g1, sKl, p.ldq, r0, p.S, t);
-    stage_load_one<DH, 2>(g2, sKd, p.ldq, r0, p.S, t); stage_load_one<DH, 3>(g3, sVh, p.ldq, r0, p.S, t);
-    stage_load_one<DH, 4>(g4, sVd, p.ldq, r0, p.S, t);
-  };
-  load_stage(0);
-  for (int kt = 0; kt < nkt; ++kt) {
-    const int n0 = kt * 32;
-    __syncthreads();
-    stage_store_one<DH, 0, 5>(g0, sm, t); stage_store_one<DH, 1, -1>(g1, sm, t); stage_store_one<DH, 2, 6>(g2, sm, t);
-    stage_store_one<DH, 3, -1>(g3, sm, t); stage_store_one<DH, 4, -1>(g4, sm, t);
-    __syncthreads();
-    if (kt + 1 < nkt) load_stage(n0 + 32);
-    if (n0 > mw + 31 || mw >= p.S) continue;
+  auto compute = [&](auto S_c, int n0) {
+    constexpr int SB = decltype(S_c)::value * STAGE_B;
     f32x16 st, su, dp, dpt;
 #pragma unroll
     for (int v = 0; v < 16; ++v) { st[v] = 0.f; su[v] = 0.f; dp[v] = 0.f; dpt[v] = 0.f; }
-#pragma unroll
-    for (int kk = 0; kk < KS; ++kk) {
-      const bf16x8 kh = frag_rows<DH>(Kh, lane, kk), kl = frag_rows<DH>(Kl, lane, kk), kd = frag_rows<DH>(Kd, lane, kk);
-      const bf16x8 vh = frag_rows<DH>(Vh, lane, kk), vd = frag_rows<DH>(Vd, lane, kk);
-      st = HF_MFMA(kh, qh[kk], st);
-      st = HF_MFMA(kl, qh[kk], st);
-      st = HF_MFMA(kh, ql[kk], st);
-      su = HF_MFMA(kd, qh[kk], su);
-      su = HF_MFMA(kh, qd[kk], su);
-      dp = HF_MFMA(vh, gh[kk], dp);       // dP^T = V dO^T
-      dpt = HF_MFMA(vh, gd[kk], dpt);     // dP_t^T = V dO_t^T + V_t dO^T
-      dpt = HF_MFMA(vd, gh[kk], dpt);
-    }
+    bf16x8 kh[2], kl[2], kd[2], vh[2], vd[2];
+    auto req_k = [&](auto kk_c, auto set_c) {
+      constexpr int kk = decltype(kk_c)::value, set = decltype(set_c)::value;
+      kh[set] = lds_read_b128<SB>(adK[kk]); kl[set] = lds_read_b128<SB + TILE_B>(adK[kk]);
+      kd[set] = lds_read_b128<SB + 2 * TILE_B>(adK[kk]); vh[set] = lds_read_b128<SB + 3 * TILE_B>(adK[kk]);
+      vd[set] = lds_read_b128<SB + 4 * TILE_B>(adK[kk]);
+    };
+    req_k(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+    static_for<KS>([&](auto kk_c) {
+      constexpr int kk = decltype(kk_c)::value, c = kk & 1;
+      if constexpr (kk + 1 < KS) {
+        req_k(std::integral_constant<int, kk + 1>{}, std::integral_constant<int, c ^ 1>{});
+        lds_wait<5>();
+      } else {
+        lds_wait<0>();
+      }
+      lds_tie(kh[c]); lds_tie(kl[c]); lds_tie(kd[c]); lds_tie(vh[c]); lds_tie(vd[c]);
+      st = HF_MFMA(kh[c], qh[kk], st);
+      su = HF_MFMA(kd[c], qh[kk], su);
+      dp = HF_MFMA(vh[c], gh[kk], dp);       // dP^T = V dO^T
+      dpt = HF_MFMA(vh[c], gd[kk], dpt);     // dP_t^T = V dO_t^T + V_t dO^T
+      st = HF_MFMA(kl[c], qh[kk], st);
+      su = HF_MFMA(kh[c], qd[kk], su);
+      dpt = HF_MFMA(vd[c], gh[kk], dpt);
+      st = HF_MFMA(kh[c], ql[kk], st);
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    // first transposed fragments on their way while the pointwise arithmetic runs
+    bf16x4 th[2][2], td[2][2];
+    auto req_t = [&](auto s_c, auto set_c) {
+      constexpr int sI = decltype(s_c)::value, set = decltype(set_c)::value;
+      constexpr int rt = sI % RT, ks = sI / RT, OFF = SB + ks * 16 * DH * 2;
+      th[set][0] = lds_read_tr64<OFF + 5 * TILE_B>(adT[rt]); th[set][1] = lds_read_tr64<OFF + 5 * TILE_B + 8 * DH * 2>(adT[rt]);
+      td[set][0] = lds_read_tr64<OFF + 6 * TILE_B>(adT[rt]); td[set][1] = lds_read_tr64<OFF + 6 * TILE_B + 8 * DH * 2>(adT[rt]);
+    };
+    req_t(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+    // register v of this lane: key n0 + 8 (v/4) + 4 (lane/32) + v%4 against query mq
     float ds[16], dst_[16];
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
@@ -482,16 +531,42 @@ __global__ __launch_bounds__(256, (DH <= 64 ? 2 : 1)) void attn_bwd_q_kernel(con
     bf16x8 dsb[2], dtb[2];
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) { dsb[ks] = pack8(ds + ks * 8); dtb[ks] = pack8(dst_ + ks * 8); }
-#pragma unroll
-    for (int rt = 0; rt < RT; ++rt) {
-#pragma unroll
-      for (int ks = 0; ks < 2; ++ks) {
-        const bf16x8 kT = frag_cols<DH>(KhT, lane, rt, ks), kdT = frag_cols<DH>(KdT, lane, rt, ks);
-        dq[rt] = HF_MFMA(kT, dsb[ks], dq[rt]);
-        dqt[rt] = HF_MFMA(kT, dtb[ks], dqt[rt]);
-        dqt[rt] = HF_MFMA(kdT, dsb[ks], dqt[rt]);
+    __builtin_amdgcn_sched_barrier(0);
+    static_for<2 * RT>([&](auto s_c) {
+      constexpr int sI = decltype(s_c)::value, c = sI & 1, rt = sI % RT, ks = sI / RT;
+      if constexpr (sI + 1 < 2 * RT) {
+        req_t(std::integral_constant<int, sI + 1>{}, std::integral_constant<int, c ^ 1>{});
+        lds_wait<4>();
+      } else {
+        lds_wait<0>();
       }
-    }
+      lds_tie(th[c][0]); lds_tie(th[c][1]); lds_tie(td[c][0]); lds_tie(td[c][1]);
+      const bf16x8 kT = __builtin_shufflevector(th[c][0], th[c][1], 0, 1, 2, 3, 4, 5, 6, 7);
+      const bf16x8 kdT = __builtin_shufflevector(td[c][0], td[c][1], 0, 1, 2, 3, 4, 5, 6, 7);
+      dq[rt] = HF_MFMA(kT, dsb[ks], dq[rt]);
+      dqt[rt] = HF_MFMA(kT, dtb[ks], dqt[rt]);
+      dqt[rt] = HF_MFMA(kdT, dsb[ks], dqt[rt]);
+      __builtin_amdgcn_sched_barrier(0);
+    });
+  };
+
+  const int n_end = min(p.S, m0 + 128);
+  const int nkt = (n_end + 31) / 32;
+  issue(0, 0);
+  for (int kt0 = 0; kt0 < nkt; kt0 += 2) {
+    static_for<2>([&](auto s_c) {
+      constexpr int S = decltype(s_c)::value;
+      const int kt = kt0 + S;
+      if (kt < nkt) {
+        const int n0 = kt * 32;
+        HF_WAIT_VMCNT(0);                 // this wave's part of tile kt has landed
+        __builtin_amdgcn_s_barrier();     // everyone's has, and stage 1 - S has been read for the last time
+        __builtin_amdgcn_sched_barrier(0);
+        if (kt + 1 < nkt) issue(1 - S, n0 + 32);
+        if (n0 <= mw + 31 && mw < p.S) compute(s_c, n0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    });
   }
   if (mq >= p.S) return;
   const int64_t orow = row0 + mq;
@@ -531,7 +606,7 @@ __global__ __launch_bounds__(256, (DH <= 32 ? 2 : 1)) void attn_bwd_kv_kernel(co
   const int nkb = (p.S + 127) / 128;
   const int Hkv = p.H / p.grp;
   int hh, kb;
-  if (!block_map(p.B * Hkv, nkb, hh, kb)) return;  // key block 0 (the longest) first
+  if (!block_map(p.B * Hkv, nkb, DH <= 32 ? 2 : 1, hh, kb)) return;  // key block 0 (the longest) first
   const int b = hh / Hkv, hk = hh % Hkv;
   const int k0 = kb * 128, kw = k0 + wave * 32;
   const int64_t row0 = (int64_t)b * p.S;
@@ -713,7 +788,7 @@ hipError_t launch_attn_bwd(const AttnP& p, hipStream_t st) {
   const unsigned gq = (unsigned)(((p.B * p.H + 7) / 8) * 8 * nqt);
   const unsigned gk = (unsigned)(((p.B * (p.H / p.grp) + 7) / 8) * 8 * nqt);
   const size_t tile = (size_t)32 * p.dh * 2;
-  const size_t lq = 7 * tile, stats = 32 * 4 * sizeof(float);
+  const size_t lq = 2 * 7 * tile, stats = 32 * 4 * sizeof(float);  // dQ: two stages of seven tiles
   if (p.dh == 32) {
     hipLaunchKernelGGL(attn_bwd_q_kernel<32>, dim3(gq), dim3(256), lq, st, p);
     hipLaunchKernelGGL((attn_bwd_kv_kernel<32, 3>), dim3(gk), dim3(256), 9 * tile + stats, st, p);
@@ -723,6 +798,9 @@ hipError_t launch_attn_bwd(const AttnP& p, hipStream_t st) {
   } else {
     // at a head width of 128 the accumulators of dK and dV together exceed the register file:
     // one launch each, both recomputing the scores
+    static OncePerDevice once;
+    const hipError_t e = once.lds_limit((const void*)attn_bwd_q_kernel<128>, (int)lq);  // 112 KB
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL(attn_bwd_q_kernel<128>, dim3(gq), dim3(256), lq, st, p);
     hipLaunchKernelGGL((attn_bwd_kv_kernel<128, 1>), dim3(gk), dim3(256), 5 * tile + stats, st, p);
     hipLaunchKernelGGL((attn_bwd_kv_kernel<128, 2>), dim3(gk), dim3(256), 7 * tile + stats, st, p);
