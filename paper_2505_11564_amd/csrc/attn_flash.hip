@@ -152,16 +152,40 @@ __device__ __forceinline__ bool block_map(int nheads, int ntiles, int occ, int& 
 // logical chunk s ^ swz(r).  Wave w issues the instructions q = w, w + 4, ...
 template <int DH>
 struct LdsLoad {
-  static constexpr int NI_T = DH / 16, CPR = DH / 8;
-  // row (0..31) and column (elements) that `lane` fetches for instruction q; rc: the tile's permutation
-  __device__ static __forceinline__ void lane_chunk(int q, int lane, bool rc, int& row, int& col) {
-    const int P = (q % NI_T) * 64 + lane;
-    row = P / CPR;
-    const int slot = P % CPR;
-    const int swz = rc ? rc_rot(row, DH) : ((row / (128 / DH)) & (CPR - 1));
-    col = (slot ^ swz) * 8;
+  static constexpr int NI_T = DH / 16, CPR = DH / 8, RPI = 64 / CPR;
+  // With a = q % NI_T, b = lane / CPR, slot = lane % CPR the lane fetches row a RPI + b and the chunk
+  // slot ^ swz(row); both permutations split into a lane part and a part of a alone (rows on lanes:
+  // swz = ((4 a) & (CPR - 1)) | b / (128 / DH); transposing reads: swz depends on b alone), so one
+  // packed register per lane serves every instruction: b | (chunk, rows on lanes) << 8 | (chunk,
+  // transposing reads) << 16.
+  __device__ static __forceinline__ uint32_t lane_part(int lane) {
+    const int b = lane / CPR, slot = lane % CPR;
+    return (uint32_t)(b | ((slot ^ (b / (128 / DH))) << 8) | ((slot ^ rc_rot(b, DH)) << 16));
+  }
+  // row (0..31) and column (elements) for instruction q; rc: the tile is one for transposing reads
+  __device__ static __forceinline__ void lane_chunk(uint32_t lp, int q, bool rc, int& row, int& col) {
+    const int a = q % NI_T;
+    row = a * RPI + (int)(lp & 255u);
+    col = (int)((rc ? (lp >> 16) & 255u : ((lp >> 8) & 255u) ^ (uint32_t)((4 * a) & (CPR - 1))) << 3);
   }
 };
+// addr ^ IMM, kept where it is written (the fragment addresses of the k-steps and column tiles differ
+// from the first one by one flipped bit field; forming them at the point of use costs an instruction
+// and saves the registers that would hold them across the loop)
+template <int IMM>
+__device__ __forceinline__ uint32_t lds_xor(uint32_t addr) {
+  if constexpr (IMM == 0) return addr;
+  uint32_t r;
+  asm volatile("v_xor_b32 %0, %1, %2" : "=v"(r) : "n"(IMM), "v"(addr));
+  return r;
+}
+// Places a fragment in the accumulator half of the register file at this point (matrix instructions
+// read their operands from either half; everything else needs the other one).
+__device__ __forceinline__ void agpr_pin(bf16x8& v) { asm volatile("" : "+a"(v)); }
+// Tile filled by load instruction wave + 4 i (NI_T instructions per tile): a constant of i wherever a
+// tile takes a multiple of four instructions.
+template <int NI_T>
+__device__ __forceinline__ int tile_of(int wave, int i) { return NI_T % 4 == 0 ? (4 * i) / NI_T : (wave + 4 * i) / NI_T; }
 template <int N>
 __device__ __forceinline__ void lds_wait() { asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N) : "memory"); }
 
@@ -213,33 +237,24 @@ __global__ __launch_bounds__(256, (DH <= 64 ? 2 : 1)) void attn_fwd_kernel(const
       qd[kk] = *(const bf16x8*)(p.qkv_t + off + kk * 16);
     }
   }
-  // this wave's load instructions: per lane the row within the tile and the column (elements), packed
   const int64_t ok = row0 * p.ldq + p.offK + (int64_t)hk * DH, ov = row0 * p.ldq + p.offV + (int64_t)hk * DH;
-  uint32_t gpk[NI];
-#pragma unroll
-  for (int i = 0; i < NI; ++i) {
-    const int q = wave + 4 * i;
-    int row, col;
-    LdsLoad<DH>::lane_chunk(q, lane, q / (DH / 16) >= 3, row, col);
-    gpk[i] = (uint32_t)(row | (col << 8));
-  }
+  const bf16 *const sKh = p.qkv + ok, *const sKl = p.qkv_lo + ok, *const sKd = p.qkv_t + ok, *const sVh = p.qkv + ov, *const sVl = p.qkv_lo + ov, *const sVd = p.qkv_t + ov;
+  const uint32_t lp = LdsLoad<DH>::lane_part(lane);
   HF_LDS char* const smem_c = (HF_LDS char*)smem_raw;
   auto issue = [&](int stage, int r0) {
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
-      const int T = (wave + 4 * i) / (DH / 16);  // (wave-uniform) tile: K hi / lo / t, V hi / lo / t
-      const bf16* base = T == 0 ? p.qkv + ok : T == 1 ? p.qkv_lo + ok : T == 2 ? p.qkv_t + ok : T == 3 ? p.qkv + ov : T == 4 ? p.qkv_lo + ov : p.qkv_t + ov;
-      const int rr = min(r0 + (int)(gpk[i] & 255u), p.S - 1);
-      __builtin_amdgcn_global_load_lds((const void*)(base + ((int64_t)rr * p.ldq + (gpk[i] >> 8))),
+      const int T = tile_of<DH / 16>(wave, i);  // (wave-uniform) tile: K hi / lo / t, V hi / lo / t
+      const bf16* base = T == 0 ? sKh : T == 1 ? sKl : T == 2 ? sKd : T == 3 ? sVh : T == 4 ? sVl : sVd;
+      int row, col;
+      LdsLoad<DH>::lane_chunk(lp, wave + 4 * i, T >= 3, row, col);
+      const int rr = min(r0 + row, p.S - 1);
+      __builtin_amdgcn_global_load_lds((const void*)(base + ((int64_t)rr * p.ldq + col)),
                                        (HF_LDS void*)(smem_c + stage * STAGE_B + (wave + 4 * i) * 1024), 16, 0, 0);
     }
   };
   const uint32_t lds0 = (uint32_t)(uintptr_t)smem_c;
-  uint32_t adK[KS], adV[RT];
-#pragma unroll
-  for (int kk = 0; kk < KS; ++kk) adK[kk] = lds0 + addr_rows<DH>(lane, kk);
-#pragma unroll
-  for (int rt = 0; rt < RT; ++rt) adV[rt] = lds0 + addr_cols<DH>(lane, rt);
+  const uint32_t adK0 = lds0 + addr_rows<DH>(lane, 0), adV0 = lds0 + addr_cols<DH>(lane, 0);  // k-step kk: ^ kk << 5, column tile rt: ^ rt << 6
 
   f32x16 o[RT], a1[RT];
 #pragma unroll
@@ -255,12 +270,13 @@ __global__ __launch_bounds__(256, (DH <= 64 ? 2 : 1)) void attn_fwd_kernel(const
 #pragma unroll
     for (int v = 0; v < 16; ++v) { st[v] = 0.f; su[v] = 0.f; }
     bf16x8 kh[2], kl[2], kd[2];
-    kh[0] = lds_read_b128<SB>(adK[0]); kl[0] = lds_read_b128<SB + TILE_B>(adK[0]); kd[0] = lds_read_b128<SB + 2 * TILE_B>(adK[0]);
+    kh[0] = lds_read_b128<SB>(adK0); kl[0] = lds_read_b128<SB + TILE_B>(adK0); kd[0] = lds_read_b128<SB + 2 * TILE_B>(adK0);
     static_for<KS>([&](auto kk_c) {
       constexpr int kk = decltype(kk_c)::value, c = kk & 1, nx = c ^ 1;
       if constexpr (kk + 1 < KS) {
-        kh[nx] = lds_read_b128<SB>(adK[kk + 1]); kl[nx] = lds_read_b128<SB + TILE_B>(adK[kk + 1]);
-        kd[nx] = lds_read_b128<SB + 2 * TILE_B>(adK[kk + 1]);
+        const uint32_t ad = lds_xor<((kk + 1) << 5)>(adK0);
+        kh[nx] = lds_read_b128<SB>(ad); kl[nx] = lds_read_b128<SB + TILE_B>(ad);
+        kd[nx] = lds_read_b128<SB + 2 * TILE_B>(ad);
         lds_wait<3>();
       } else {
         lds_wait<0>();
@@ -278,9 +294,10 @@ __global__ __launch_bounds__(256, (DH <= 64 ? 2 : 1)) void attn_fwd_kernel(const
     auto req_v = [&](auto s_c, auto set_c) {
       constexpr int s = decltype(s_c)::value, set = decltype(set_c)::value;
       constexpr int rt = s % RT, ks = s / RT, OFF = SB + ks * 16 * DH * 2;
-      vh[set][0] = lds_read_tr64<OFF + 3 * TILE_B>(adV[rt]); vh[set][1] = lds_read_tr64<OFF + 3 * TILE_B + 8 * DH * 2>(adV[rt]);
-      vl[set][0] = lds_read_tr64<OFF + 4 * TILE_B>(adV[rt]); vl[set][1] = lds_read_tr64<OFF + 4 * TILE_B + 8 * DH * 2>(adV[rt]);
-      vd[set][0] = lds_read_tr64<OFF + 5 * TILE_B>(adV[rt]); vd[set][1] = lds_read_tr64<OFF + 5 * TILE_B + 8 * DH * 2>(adV[rt]);
+      const uint32_t ad = lds_xor<(rt << 6)>(adV0);
+      vh[set][0] = lds_read_tr64<OFF + 3 * TILE_B>(ad); vh[set][1] = lds_read_tr64<OFF + 3 * TILE_B + 8 * DH * 2>(ad);
+      vl[set][0] = lds_read_tr64<OFF + 4 * TILE_B>(ad); vl[set][1] = lds_read_tr64<OFF + 4 * TILE_B + 8 * DH * 2>(ad);
+      vd[set][0] = lds_read_tr64<OFF + 5 * TILE_B>(ad); vd[set][1] = lds_read_tr64<OFF + 5 * TILE_B + 8 * DH * 2>(ad);
     };
     req_v(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
     // register v of this lane: key n0 + 8 (v/4) + 4 (lane/32) + v%4 against query mq
@@ -441,35 +458,26 @@ __global__ __launch_bounds__(256, (DH <= 64 ? 2 : 1)) void attn_bwd_q_kernel(con
   const float dl = p.delta[srow * 3], dlt = p.delta[srow * 3 + 1];
 
   const int64_t ok = row0 * p.ldq + p.offK + (int64_t)hk * DH, ov = row0 * p.ldq + p.offV + (int64_t)hk * DH;
-  uint32_t gpk[NI];
-#pragma unroll
-  for (int i = 0; i < NI; ++i) {
-    const int q = min(wave + 4 * i, NQ - 1);
-    int row, col;
-    LdsLoad<DH>::lane_chunk(q, lane, q / (DH / 16) >= 5, row, col);
-    gpk[i] = (uint32_t)(row | (col << 8));
-  }
+  const bf16 *const sKh = p.qkv + ok, *const sKl = p.qkv_lo + ok, *const sKd = p.qkv_t + ok, *const sVh = p.qkv + ov, *const sVd = p.qkv_t + ov;
+  const uint32_t lp = LdsLoad<DH>::lane_part(lane);
   HF_LDS char* const smem_c = (HF_LDS char*)smem_raw;
   auto issue = [&](int stage, int r0) {
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
       const int q = wave + 4 * i;  // (wave-uniform)
       if (NQ % 4 == 0 || q < NQ) {
-        const int T = q / (DH / 16);  // K hi / lo / t, V hi / t with keys on lanes; K hi / t for transposing reads
-        const bf16* base = T == 0 ? p.qkv + ok : T == 1 ? p.qkv_lo + ok : T == 2 ? p.qkv_t + ok : T == 3 ? p.qkv + ov : T == 4 ? p.qkv_t + ov
-                           : T == 5 ? p.qkv + ok : p.qkv_t + ok;
-        const int rr_ = min(r0 + (int)(gpk[i] & 255u), p.S - 1);
-        __builtin_amdgcn_global_load_lds((const void*)(base + ((int64_t)rr_ * p.ldq + (gpk[i] >> 8))),
+        const int T = tile_of<DH / 16>(wave, i);  // K hi / lo / t, V hi / t with keys on lanes; K hi / t for transposing reads
+        const bf16* base = (T == 0 || T == 5) ? sKh : T == 1 ? sKl : (T == 2 || T == 6) ? sKd : T == 3 ? sVh : sVd;
+        int row, col;
+        LdsLoad<DH>::lane_chunk(lp, q, T >= 5, row, col);
+        const int rr_ = min(r0 + row, p.S - 1);
+        __builtin_amdgcn_global_load_lds((const void*)(base + ((int64_t)rr_ * p.ldq + col)),
                                          (HF_LDS void*)(smem_c + stage * STAGE_B + q * 1024), 16, 0, 0);
       }
     }
   };
   const uint32_t lds0 = (uint32_t)(uintptr_t)smem_c;
-  uint32_t adK[KS], adT[RT];
-#pragma unroll
-  for (int kk = 0; kk < KS; ++kk) adK[kk] = lds0 + addr_rows<DH>(lane, kk);
-#pragma unroll
-  for (int rt = 0; rt < RT; ++rt) adT[rt] = lds0 + addr_cols<DH>(lane, rt);
+  const uint32_t adK0 = lds0 + addr_rows<DH>(lane, 0), adT0 = lds0 + addr_cols<DH>(lane, 0);  // k-step kk: ^ kk << 5, column tile rt: ^ rt << 6
 
   f32x16 dq[RT], dqt[RT];
 #pragma unroll
@@ -485,9 +493,10 @@ __global__ __launch_bounds__(256, (DH <= 64 ? 2 : 1)) void attn_bwd_q_kernel(con
     bf16x8 kh[2], kl[2], kd[2], vh[2], vd[2];
     auto req_k = [&](auto kk_c, auto set_c) {
       constexpr int kk = decltype(kk_c)::value, set = decltype(set_c)::value;
-      kh[set] = lds_read_b128<SB>(adK[kk]); kl[set] = lds_read_b128<SB + TILE_B>(adK[kk]);
-      kd[set] = lds_read_b128<SB + 2 * TILE_B>(adK[kk]); vh[set] = lds_read_b128<SB + 3 * TILE_B>(adK[kk]);
-      vd[set] = lds_read_b128<SB + 4 * TILE_B>(adK[kk]);
+      const uint32_t ad = lds_xor<(kk << 5)>(adK0);
+      kh[set] = lds_read_b128<SB>(ad); kl[set] = lds_read_b128<SB + TILE_B>(ad);
+      kd[set] = lds_read_b128<SB + 2 * TILE_B>(ad); vh[set] = lds_read_b128<SB + 3 * TILE_B>(ad);
+      vd[set] = lds_read_b128<SB + 4 * TILE_B>(ad);
     };
     req_k(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
     static_for<KS>([&](auto kk_c) {
@@ -514,8 +523,9 @@ __global__ __launch_bounds__(256, (DH <= 64 ? 2 : 1)) void attn_bwd_q_kernel(con
     auto req_t = [&](auto s_c, auto set_c) {
       constexpr int sI = decltype(s_c)::value, set = decltype(set_c)::value;
       constexpr int rt = sI % RT, ks = sI / RT, OFF = SB + ks * 16 * DH * 2;
-      th[set][0] = lds_read_tr64<OFF + 5 * TILE_B>(adT[rt]); th[set][1] = lds_read_tr64<OFF + 5 * TILE_B + 8 * DH * 2>(adT[rt]);
-      td[set][0] = lds_read_tr64<OFF + 6 * TILE_B>(adT[rt]); td[set][1] = lds_read_tr64<OFF + 6 * TILE_B + 8 * DH * 2>(adT[rt]);
+      const uint32_t ad = lds_xor<(rt << 6)>(adT0);
+      th[set][0] = lds_read_tr64<OFF + 5 * TILE_B>(ad); th[set][1] = lds_read_tr64<OFF + 5 * TILE_B + 8 * DH * 2>(ad);
+      td[set][0] = lds_read_tr64<OFF + 6 * TILE_B>(ad); td[set][1] = lds_read_tr64<OFF + 6 * TILE_B + 8 * DH * 2>(ad);
     };
     req_t(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
     // register v of this lane: key n0 + 8 (v/4) + 4 (lane/32) + v%4 against query mq
@@ -585,24 +595,42 @@ __global__ __launch_bounds__(256, (DH <= 64 ? 2 : 1)) void attn_bwd_q_kernel(con
 
 // ------------------------------------------------------------ backward: dK, dV ----
 // WHAT & 1: dV, dV_t;  WHAT & 2: dK, dK_t.
+// LDS: two stages of up to nine tiles, filled by direct loads one query tile ahead -- Q hi / lo / t
+// with queries on lanes; dO, dO_t the same (dK only); copies of Q hi / t (dK) and of dO, dO_t (dV) in
+// the layout of transposing reads -- and two small tiles of row statistics (lse, r, delta, delta_t
+// per query), which go through registers two tiles ahead.  One barrier per query tile; the tiles of
+// all query heads of a group form one sequence.
+
+template <int DH, int WHAT>
+struct KvTiles {
+  static constexpr bool DV = (WHAT & 1) != 0, DK = (WHAT & 2) != 0;
+  static constexpr int T_QH = 0, T_QL = 1, T_QD = 2;
+  static constexpr int T_GH = DK ? 3 : -1, T_GD = DK ? 4 : -1;
+  static constexpr int NKC = DK ? 5 : 3;                    // tiles with queries on lanes
+  static constexpr int T_QHT = DK ? NKC : -1, T_QDT = DK ? NKC + 1 : -1;
+  static constexpr int T_GHT = DV ? NKC + (DK ? 2 : 0) : -1, T_GDT = DV ? NKC + (DK ? 2 : 0) + 1 : -1;
+  static constexpr int NT = NKC + (DK ? 2 : 0) + (DV ? 2 : 0);
+  static constexpr int TILE_B = 64 * DH, STAGE_B = NT * TILE_B;
+  static constexpr int STATS_B = 32 * 4 * 4;                // one statistics tile
+  static constexpr int LDS_B = 2 * STAGE_B + 2 * STATS_B;
+  // source of a tile: 0 Q hi, 1 Q lo, 2 Q t, 3 dO, 4 dO t
+  __device__ static constexpr int src(int T) {
+    return T == T_QH || T == T_QHT ? 0 : T == T_QL ? 1 : T == T_QD || T == T_QDT ? 2 : T == T_GH || T == T_GHT ? 3 : 4;
+  }
+};
 
 template <int DH, int WHAT>
 __global__ __launch_bounds__(256, (DH <= 32 ? 2 : 1)) void attn_bwd_kv_kernel(const AttnP p) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
-  HF_LDS bf16* sm = (HF_LDS bf16*)smem_raw;
-  constexpr int TILE = 32 * DH, KS = DH / 16, RT = DH / 32;
-  constexpr bool DV = (WHAT & 1) != 0, DK = (WHAT & 2) != 0;
-  // LDS tiles: Q hi / lo / t with queries on lanes; dO, dO_t the same (dK only); transposed copies
-  // of Q hi / t (dK) and of dO, dO_t (dV)
-  constexpr int T_QH = 0, T_QL = 1, T_QD = 2;
-  constexpr int T_GH = DK ? 3 : -1, T_GD = DK ? 4 : -1;
-  constexpr int NKC = DK ? 5 : 3;
-  constexpr int T_QHT = DK ? NKC : -1, T_QDT = DK ? NKC + 1 : -1;
-  constexpr int T_GHT = DV ? NKC + (DK ? 2 : 0) : -1, T_GDT = DV ? NKC + (DK ? 2 : 0) + 1 : -1;
-  constexpr int NTILE = NKC + (DK ? 2 : 0) + (DV ? 2 : 0);
-  HF_LDS float* stats = (HF_LDS float*)(sm + NTILE * TILE);  // [32 queries][4] = lse, r, delta, delta_t
+  typedef KvTiles<DH, WHAT> L;
+  constexpr bool DV = L::DV, DK = L::DK;
+  constexpr int TILE_B = L::TILE_B, STAGE_B = L::STAGE_B, KS = DH / 16, RT = DH / 32;
+  constexpr int NQ = L::NT * (DH / 16), NI = (NQ + 3) / 4;
+  HF_LDS char* const smem_c = (HF_LDS char*)smem_raw;
+  HF_LDS float* const stats = (HF_LDS float*)(smem_c + 2 * STAGE_B);  // [2][32 queries][4]
 
-  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int t = threadIdx.x, lane = t & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(t >> 6) & 3;
   const int nkb = (p.S + 127) / 128;
   const int Hkv = p.H / p.grp;
   int hh, kb;
@@ -626,6 +654,13 @@ __global__ __launch_bounds__(256, (DH <= 32 ? 2 : 1)) void attn_bwd_kv_kernel(co
         vd[kk] = *(const bf16x8*)(p.qkv_t + p.offV + off + kk * 16);
       }
     }
+    if constexpr (DH == 128) {  // 160 registers of loop constants that only matrix instructions read: the accumulator file
+#pragma unroll
+      for (int kk = 0; kk < KS; ++kk) {
+        agpr_pin(kh[kk]); agpr_pin(kl[kk]); agpr_pin(kd[kk]);
+        if (DK) { agpr_pin(vh[kk]); agpr_pin(vd[kk]); }
+      }
+    }
   }
   f32x16 dv[DV ? RT : 1], dvt[DV ? RT : 1], dk[DK ? RT : 1], dkt[DK ? RT : 1];
 #pragma unroll
@@ -635,96 +670,182 @@ __global__ __launch_bounds__(256, (DH <= 32 ? 2 : 1)) void attn_bwd_kv_kernel(co
 #pragma unroll
     for (int i = 0; i < (DK ? RT : 1); ++i) { dk[i][v] = 0.f; dkt[i][v] = 0.f; }
   }
-  const int nqs = (p.S - k0 + 31) / 32;  // query sub-tiles k0, k0 + 32, ... (k0 < S)
+  const int nqs = (p.S - k0 + 31) / 32;  // query sub-tiles k0, k0 + 32, ... (k0 < S) of one head
+  const int nit = nqs * p.grp;           // ... of all query heads of the group
 
-  for (int j = 0; j < p.grp; ++j) {
+  const uint32_t lp = LdsLoad<DH>::lane_part(lane);
+  const bf16 *const pq = p.qkv, *const pql = p.qkv_lo, *const pqt = p.qkv_t, *const pg = p.dO, *const pgt = p.dO_t;
+  const int64_t ldq = p.ldq, lddo = p.lddo;
+  auto issue = [&](int stage, int it) {
+    const int j = it / nqs, r0 = k0 + (it - j * nqs) * 32;
     const int h = hk * p.grp + j;
-    const int64_t oq = row0 * p.ldq + (int64_t)h * DH, og = row0 * p.lddo + (int64_t)h * DH;
-    const bf16 *sQh = p.qkv + oq, *sQl = p.qkv_lo + oq, *sQd = p.qkv_t + oq, *sGh = p.dO + og, *sGd = p.dO_t + og;
-    const int64_t sbase = ((int64_t)b * p.H + h) * p.S;
-    constexpr int PER = StageDim<DH>::PER;
-    at_u32x4 g0[PER], g1[PER], g2[PER], g3[PER], g4[PER];
-    auto load_stage = [&](int r0) {
-      stage_load_one<DH, 0>(g0, sQh, p.ldq, r0, p.S, t); stage_load_one<DH, 1>(g1, sQl, p.ldq, r0, p.S, t);
-      stage_load_one<DH, 2>(g2, sQd, p.ldq, r0, p.S, t); stage_load_one<DH, 3>(g3, sGh, p.lddo, r0, p.S, t);
-      stage_load_one<DH, 4>(g4, sGd, p.lddo, r0, p.S, t);
-    };
-    load_stage(k0);
-    at_f32x4 spre = {0.f, 0.f, 0.f, 0.f};
-    auto load_stats = [&](int q0) {
-      if (t < 32) {
-        const int q = min(q0 + t, p.S - 1);
-        spre = at_f32x4{p.stat[(sbase + q) * 2], p.stat[(sbase + q) * 2 + 1], p.delta[(sbase + q) * 3], p.delta[(sbase + q) * 3 + 1]};
-      }
-    };
-    load_stats(k0);
-    for (int qs = 0; qs < nqs; ++qs) {
-      const int q0 = k0 + qs * 32;
-      __syncthreads();
-      stage_store_one<DH, T_QH, T_QHT>(g0, sm, t); stage_store_one<DH, T_QL, -1>(g1, sm, t); stage_store_one<DH, T_QD, T_QDT>(g2, sm, t);
-      stage_store_one<DH, T_GH, T_GHT>(g3, sm, t); stage_store_one<DH, T_GD, T_GDT>(g4, sm, t);
-      if (t < 32) *(HF_LDS at_f32x4*)(stats + t * 4) = spre;
-      __syncthreads();
-      if (qs + 1 < nqs) { load_stage(q0 + 32); load_stats(q0 + 32); }
-      if (q0 + 31 < kw || kw >= p.S) continue;  // (wave-uniform) every query of the tile precedes this wave's keys
-      f32x16 st, su, dp, dpt;
+    const int64_t oq = row0 * ldq + (int64_t)h * DH, og = row0 * lddo + (int64_t)h * DH;
+    const bf16 *const sQh = pq + oq, *const sQl = pql + oq, *const sQd = pqt + oq, *const sGh = pg + og, *const sGd = pgt + og;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) { st[v] = 0.f; su[v] = 0.f; dp[v] = 0.f; dpt[v] = 0.f; }
-#pragma unroll
-      for (int kk = 0; kk < KS; ++kk) {
-        const bf16x8 qa = frag_rows<DH>(sm + T_QH * TILE, lane, kk), qb = frag_rows<DH>(sm + T_QL * TILE, lane, kk),
-                     qc = frag_rows<DH>(sm + T_QD * TILE, lane, kk);
-        st = HF_MFMA(qa, kh[kk], st);
-        st = HF_MFMA(qb, kh[kk], st);
-        st = HF_MFMA(qa, kl[kk], st);
-        su = HF_MFMA(qc, kh[kk], su);
-        su = HF_MFMA(qa, kd[kk], su);
-        if (DK) {
-          const bf16x8 ga = frag_rows<DH>(sm + T_GH * TILE, lane, kk), gb = frag_rows<DH>(sm + T_GD * TILE, lane, kk);
-          dp = HF_MFMA(ga, vh[kk], dp);       // dP = dO V^T
-          dpt = HF_MFMA(gb, vh[kk], dpt);     // dP_t = dO_t V^T + dO V_t^T
-          dpt = HF_MFMA(ga, vd[kk], dpt);
-        }
-      }
-      // register v of this lane: query q0 + 8 (v/4) + 4 (lane/32) + v%4 against key nk
-      float pr[16], pt[16], ds[16], dsx[16];
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int qi = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-        const at_f32x4 sq = *(const HF_LDS at_f32x4*)(stats + qi * 4);
-        const int q = q0 + qi;
-        pr[v] = (q < nk || q >= p.S) ? 0.f : __expf(st[v] * p.scale - sq.x);
-        pt[v] = pr[v] * (su[v] * p.scale - sq.y);
-        if (DK) {
-          ds[v] = pr[v] * (dp[v] - sq.z);
-          dsx[v] = pt[v] * (dp[v] - sq.z) + pr[v] * (dpt[v] - sq.w);
-        }
-      }
-#pragma unroll
-      for (int ks = 0; ks < 2; ++ks) {
-        if (DV) {
-          const bf16x8 pb = pack8(pr + ks * 8), ptb = pack8(pt + ks * 8);
-#pragma unroll
-          for (int rt = 0; rt < RT; ++rt) {
-            const bf16x8 gT = frag_cols<DH>(sm + T_GHT * TILE, lane, rt, ks), gdT = frag_cols<DH>(sm + T_GDT * TILE, lane, rt, ks);
-            dv[rt] = HF_MFMA(gT, pb, dv[rt]);       // dV^T = dO^T P
-            dvt[rt] = HF_MFMA(gT, ptb, dvt[rt]);    // dV_t^T = dO^T P_t + dO_t^T P
-            dvt[rt] = HF_MFMA(gdT, pb, dvt[rt]);
-          }
-        }
-        if (DK) {
-          const bf16x8 sb = pack8(ds + ks * 8), sxb = pack8(dsx + ks * 8);
-#pragma unroll
-          for (int rt = 0; rt < RT; ++rt) {
-            const bf16x8 qT = frag_cols<DH>(sm + T_QHT * TILE, lane, rt, ks), qdT = frag_cols<DH>(sm + T_QDT * TILE, lane, rt, ks);
-            dk[rt] = HF_MFMA(qT, sb, dk[rt]);       // dK^T = Q^T dS
-            dkt[rt] = HF_MFMA(qT, sxb, dkt[rt]);    // dK_t^T = Q^T dS_t + Q_t^T dS
-            dkt[rt] = HF_MFMA(qdT, sb, dkt[rt]);
-          }
-        }
+    for (int i = 0; i < NI; ++i) {
+      const int q = wave + 4 * i;  // (wave-uniform)
+      if (NQ % 4 == 0 || q < NQ) {
+        const int T = tile_of<DH / 16>(wave, i), sr = L::src(T);
+        const bf16* base = sr == 0 ? sQh : sr == 1 ? sQl : sr == 2 ? sQd : sr == 3 ? sGh : sGd;
+        const int64_t ld = sr >= 3 ? lddo : ldq;
+        int row, col;
+        LdsLoad<DH>::lane_chunk(lp, q, T >= L::NKC, row, col);
+        const int rr_ = min(r0 + row, p.S - 1);
+        __builtin_amdgcn_global_load_lds((const void*)(base + (rr_ * ld + col)),
+                                         (HF_LDS void*)(smem_c + stage * STAGE_B + q * 1024), 16, 0, 0);
       }
     }
-    __syncthreads();  // the next head's first store must not overtake this head's last reads
+  };
+  at_f32x4 spre = {0.f, 0.f, 0.f, 0.f};
+  auto load_stats = [&](int it) {  // (threads 0..31)
+    const int j = it / nqs, q0 = k0 + (it - j * nqs) * 32;
+    const int64_t sbase = ((int64_t)b * p.H + hk * p.grp + j) * p.S;
+    const int q = min(q0 + t, p.S - 1);
+    spre = at_f32x4{p.stat[(sbase + q) * 2], p.stat[(sbase + q) * 2 + 1], p.delta[(sbase + q) * 3], p.delta[(sbase + q) * 3 + 1]};
+  };
+  const uint32_t lds0 = (uint32_t)(uintptr_t)smem_c;
+  const uint32_t adQ0 = lds0 + addr_rows<DH>(lane, 0), adT0 = lds0 + addr_cols<DH>(lane, 0);  // k-step kk: ^ kk << 5, column tile rt: ^ rt << 6
+
+  auto compute = [&](auto S_c, int q0) {
+    constexpr int SI = decltype(S_c)::value, SB = SI * STAGE_B;
+    f32x16 st, su, dp, dpt;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { st[v] = 0.f; su[v] = 0.f; dp[v] = 0.f; dpt[v] = 0.f; }
+    bf16x8 qa[2], qb[2], qc[2], ga[2], gb[2];
+    auto req_q = [&](auto kk_c, auto set_c) {
+      constexpr int kk = decltype(kk_c)::value, set = decltype(set_c)::value;
+      const uint32_t ad = lds_xor<(kk << 5)>(adQ0);
+      qa[set] = lds_read_b128<SB + L::T_QH * TILE_B>(ad); qb[set] = lds_read_b128<SB + L::T_QL * TILE_B>(ad);
+      qc[set] = lds_read_b128<SB + L::T_QD * TILE_B>(ad);
+      if constexpr (DK) {
+        ga[set] = lds_read_b128<SB + L::T_GH * TILE_B>(ad); gb[set] = lds_read_b128<SB + L::T_GD * TILE_B>(ad);
+      }
+    };
+    // (fragments one step ahead of their use, except at head width 128, where the registers are all taken)
+    constexpr bool AHEAD = DH <= 64;
+    if constexpr (AHEAD) req_q(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+    static_for<KS>([&](auto kk_c) {
+      constexpr int kk = decltype(kk_c)::value, c = AHEAD ? (kk & 1) : 0;
+      if constexpr (!AHEAD) {
+        req_q(kk_c, std::integral_constant<int, 0>{});
+        lds_wait<0>();
+      } else if constexpr (kk + 1 < KS) {
+        req_q(std::integral_constant<int, kk + 1>{}, std::integral_constant<int, c ^ 1>{});
+        lds_wait<(DK ? 5 : 3)>();
+      } else {
+        lds_wait<0>();
+      }
+      lds_tie(qa[c]); lds_tie(qb[c]); lds_tie(qc[c]);
+      if constexpr (DK) { lds_tie(ga[c]); lds_tie(gb[c]); }
+      st = HF_MFMA(qa[c], kh[kk], st);
+      su = HF_MFMA(qc[c], kh[kk], su);
+      if constexpr (DK) {
+        dp = HF_MFMA(ga[c], vh[kk], dp);       // dP = dO V^T
+        dpt = HF_MFMA(gb[c], vh[kk], dpt);     // dP_t = dO_t V^T + dO V_t^T
+      }
+      st = HF_MFMA(qb[c], kh[kk], st);
+      su = HF_MFMA(qa[c], kd[kk], su);
+      if constexpr (DK) dpt = HF_MFMA(ga[c], vd[kk], dpt);
+      st = HF_MFMA(qa[c], kl[kk], st);
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    // the products of the second half, in order: per key step ks, the dV products of the RT column
+    // tiles, then the dK ones; each takes two transposed fragments (four reads)
+    constexpr int UK = (DV ? RT : 0) + (DK ? RT : 0), NU = 2 * UK;
+    bf16x4 ta[2][2], tb[2][2];
+    auto req_t = [&](auto u_c, auto set_c) {
+      constexpr int u = decltype(u_c)::value, set = decltype(set_c)::value;
+      constexpr int ks = u / UK, w = u % UK;
+      constexpr bool isV = DV && w < RT;
+      constexpr int rt = isV ? w : w - (DV ? RT : 0);
+      constexpr int TA = isV ? L::T_GHT : L::T_QHT, TB = isV ? L::T_GDT : L::T_QDT;
+      constexpr int OFF = SB + ks * 16 * DH * 2;
+      const uint32_t ad = lds_xor<(rt << 6)>(adT0);
+      ta[set][0] = lds_read_tr64<OFF + TA * TILE_B>(ad); ta[set][1] = lds_read_tr64<OFF + TA * TILE_B + 8 * DH * 2>(ad);
+      tb[set][0] = lds_read_tr64<OFF + TB * TILE_B>(ad); tb[set][1] = lds_read_tr64<OFF + TB * TILE_B + 8 * DH * 2>(ad);
+    };
+    if constexpr (AHEAD) req_t(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+    // register v of this lane: query q0 + 8 (v/4) + 4 (lane/32) + v%4 against key nk
+    float pr[16], pt[16], ds[DK ? 16 : 1], dsx[DK ? 16 : 1];
+    const HF_LDS float* sq_base = stats + SI * 128;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int qi = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+      const at_f32x4 sq = *(const HF_LDS at_f32x4*)(sq_base + qi * 4);
+      const int q = q0 + qi;
+      pr[v] = (q < nk || q >= p.S) ? 0.f : __expf(st[v] * p.scale - sq.x);
+      pt[v] = pr[v] * (su[v] * p.scale - sq.y);
+      if constexpr (DK) {
+        ds[v] = pr[v] * (dp[v] - sq.z);
+        dsx[v] = pt[v] * (dp[v] - sq.z) + pr[v] * (dpt[v] - sq.w);
+      }
+    }
+    bf16x8 pb[2], ptb[2], sb[DK ? 2 : 1], sxb[DK ? 2 : 1];
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      pb[ks] = pack8(pr + ks * 8); ptb[ks] = pack8(pt + ks * 8);
+      if constexpr (DK) { sb[ks] = pack8(ds + ks * 8); sxb[ks] = pack8(dsx + ks * 8); }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    static_for<NU>([&](auto u_c) {
+      constexpr int u = decltype(u_c)::value, c = AHEAD ? (u & 1) : 0;
+      constexpr int ks = u / UK, w = u % UK;
+      constexpr bool isV = DV && w < RT;
+      constexpr int rt = isV ? w : w - (DV ? RT : 0);
+      if constexpr (!AHEAD) {
+        req_t(u_c, std::integral_constant<int, 0>{});
+        lds_wait<0>();
+      } else if constexpr (u + 1 < NU) {
+        req_t(std::integral_constant<int, u + 1>{}, std::integral_constant<int, c ^ 1>{});
+        lds_wait<4>();
+      } else {
+        lds_wait<0>();
+      }
+      lds_tie(ta[c][0]); lds_tie(ta[c][1]); lds_tie(tb[c][0]); lds_tie(tb[c][1]);
+      const bf16x8 xa = __builtin_shufflevector(ta[c][0], ta[c][1], 0, 1, 2, 3, 4, 5, 6, 7);
+      const bf16x8 xb = __builtin_shufflevector(tb[c][0], tb[c][1], 0, 1, 2, 3, 4, 5, 6, 7);
+      if constexpr (isV) {
+        dv[rt] = HF_MFMA(xa, pb[ks], dv[rt]);       // dV^T = dO^T P
+        dvt[rt] = HF_MFMA(xa, ptb[ks], dvt[rt]);    // dV_t^T = dO^T P_t + dO_t^T P
+        dvt[rt] = HF_MFMA(xb, pb[ks], dvt[rt]);
+      } else {
+        dk[rt] = HF_MFMA(xa, sb[ks], dk[rt]);       // dK^T = Q^T dS
+        dkt[rt] = HF_MFMA(xa, sxb[ks], dkt[rt]);    // dK_t^T = Q^T dS_t + Q_t^T dS
+        dkt[rt] = HF_MFMA(xb, sb[ks], dkt[rt]);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    });
+  };
+
+  // statistics of tile 0 straight into their LDS tile, those of tile 1 into registers
+  if (t < 32) {
+    load_stats(0);
+    *(HF_LDS at_f32x4*)(stats + t * 4) = spre;
+    if (nit > 1) load_stats(1);
+  }
+  issue(0, 0);
+  for (int it0 = 0; it0 < nit; it0 += 2) {
+    static_for<2>([&](auto s_c) {
+      constexpr int S = decltype(s_c)::value;
+      const int it = it0 + S;
+      if (it < nit) {
+        const int qs = it % nqs, q0 = k0 + qs * 32;
+        HF_WAIT_VMCNT(0);                 // this wave's part of tile `it` has landed (and the statistics in registers)
+        lds_wait<0>();                    // ... and its statistics store of the previous turn
+        __builtin_amdgcn_s_barrier();     // everyone's has, and stage 1 - S has been read for the last time
+        __builtin_amdgcn_sched_barrier(0);
+        if (it + 1 < nit) {
+          issue(1 - S, it + 1);
+          if (t < 32) {
+            *(HF_LDS at_f32x4*)(stats + (1 - S) * 128 + t * 4) = spre;
+            if (it + 2 < nit) load_stats(it + 2);
+          }
+        }
+        // (wave-uniform) nothing to do where every query of the tile precedes this wave's keys
+        if (!(q0 + 31 < kw || kw >= p.S)) compute(s_c, q0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    });
   }
   if (nk >= p.S) return;
   const int64_t orow = row0 + nk;
@@ -760,7 +881,11 @@ static bool al16(const void* x) { return x != nullptr && ((uintptr_t)x & 15) == 
 
 bool attn_flash_supported(int dh, int64_t ldq, int64_t ldo) { return (dh == 32 || dh == 64 || dh == 128) && ldq % 8 == 0 && ldo % 8 == 0; }
 
-bool attn_flash_preferred(int dh) { return dh <= 64; }
+// Up to head width 64 two blocks share a CU and the streamed kernels win at every size measured.  At
+// 128 a block needs the whole register file; the kernels still win once a launch has a block for
+// every CU (1.3B shape, 512 blocks: 14.2 against 16 ms per product), but not at a batch of one
+// sequence (Llama-7B shape, 128 blocks: 1 % behind).
+bool attn_flash_preferred(int dh, int64_t heads, int64_t S) { return dh <= 64 || heads * ((S + 127) / 128) >= 256; }
 
 hipError_t launch_attn_fwd(const AttnP& p, hipStream_t st) {
   if (!attn_shape_ok(p) || p.ldo % 8) return hipErrorInvalidValue;
@@ -779,6 +904,18 @@ hipError_t launch_attn_fwd(const AttnP& p, hipStream_t st) {
   return hipGetLastError();
 }
 
+template <int DH, int WHAT>
+static hipError_t launch_kv(const AttnP& p, unsigned grid, hipStream_t st) {
+  constexpr int lds = KvTiles<DH, WHAT>::LDS_B;
+  static_assert(lds <= 160 * 1024, "LDS");
+  static OncePerDevice once;
+  auto kern = attn_bwd_kv_kernel<DH, WHAT>;
+  if (lds > 64 * 1024)
+    if (const hipError_t e = once.lds_limit((const void*)kern, lds); e != hipSuccess) return e;
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, p);
+  return hipGetLastError();
+}
+
 hipError_t launch_attn_bwd(const AttnP& p, hipStream_t st) {
   if (!attn_shape_ok(p) || p.lddo % 8) return hipErrorInvalidValue;
   if (!al16(p.qkv) || !al16(p.qkv_lo) || !al16(p.qkv_t) || !al16(p.dO) || !al16(p.dO_t) || !p.stat || !p.delta) return hipErrorInvalidValue;
@@ -787,25 +924,23 @@ hipError_t launch_attn_bwd(const AttnP& p, hipStream_t st) {
   const int nqt = (p.S + 127) / 128;
   const unsigned gq = (unsigned)(((p.B * p.H + 7) / 8) * 8 * nqt);
   const unsigned gk = (unsigned)(((p.B * (p.H / p.grp) + 7) / 8) * 8 * nqt);
-  const size_t tile = (size_t)32 * p.dh * 2;
-  const size_t lq = 2 * 7 * tile, stats = 32 * 4 * sizeof(float);  // dQ: two stages of seven tiles
+  const size_t lq = (size_t)2 * 7 * 32 * p.dh * 2;  // dQ: two stages of seven tiles
   if (p.dh == 32) {
     hipLaunchKernelGGL(attn_bwd_q_kernel<32>, dim3(gq), dim3(256), lq, st, p);
-    hipLaunchKernelGGL((attn_bwd_kv_kernel<32, 3>), dim3(gk), dim3(256), 9 * tile + stats, st, p);
-  } else if (p.dh == 64) {
-    hipLaunchKernelGGL(attn_bwd_q_kernel<64>, dim3(gq), dim3(256), lq, st, p);
-    hipLaunchKernelGGL((attn_bwd_kv_kernel<64, 3>), dim3(gk), dim3(256), 9 * tile + stats, st, p);
-  } else {
-    // at a head width of 128 the accumulators of dK and dV together exceed the register file:
-    // one launch each, both recomputing the scores
-    static OncePerDevice once;
-    const hipError_t e = once.lds_limit((const void*)attn_bwd_q_kernel<128>, (int)lq);  // 112 KB
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(attn_bwd_q_kernel<128>, dim3(gq), dim3(256), lq, st, p);
-    hipLaunchKernelGGL((attn_bwd_kv_kernel<128, 1>), dim3(gk), dim3(256), 5 * tile + stats, st, p);
-    hipLaunchKernelGGL((attn_bwd_kv_kernel<128, 2>), dim3(gk), dim3(256), 7 * tile + stats, st, p);
+    return launch_kv<32, 3>(p, gk, st);
   }
-  return hipGetLastError();
+  if (p.dh == 64) {
+    hipLaunchKernelGGL(attn_bwd_q_kernel<64>, dim3(gq), dim3(256), lq, st, p);
+    return launch_kv<64, 3>(p, gk, st);
+  }
+  // at a head width of 128 the accumulators of dK and dV together exceed the register file:
+  // one launch each, both recomputing the scores
+  static OncePerDevice once;
+  const hipError_t e = once.lds_limit((const void*)attn_bwd_q_kernel<128>, (int)lq);  // 112 KB
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(attn_bwd_q_kernel<128>, dim3(gq), dim3(256), lq, st, p);
+  if (const hipError_t e1 = launch_kv<128, 1>(p, gk, st); e1 != hipSuccess) return e1;
+  return launch_kv<128, 2>(p, gk, st);
 }
 
 }  // namespace hf

@@ -118,7 +118,7 @@ int hf_ctx::plan_and_alloc() {
       const bool can = bf && attn_flash_supported((int)(D / H), W3, D);
       if (desc.attention == HF_ATTN_STREAMED && !can)
         return fail(HF_ESHAPE, "HF_ATTN_STREAMED needs bf16 parameters, a head width of 32, 64 or 128 and d_model a multiple of 8");
-      flash = can && desc.attention != HF_ATTN_STORED && (desc.attention == HF_ATTN_STREAMED || attn_flash_preferred((int)(D / H)));
+      flash = can && desc.attention != HF_ATTN_STORED && (desc.attention == HF_ATTN_STREAMED || attn_flash_preferred((int)(D / H), B * H, S));
     }
     const int64_t SSa = flash ? 0 : SS;  // the S x S buffers exist only for the unstreamed paths
     lb.resize(desc.n_layer);

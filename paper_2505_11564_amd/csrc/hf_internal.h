@@ -136,7 +136,8 @@ struct AttnP {
   int dq_f32 = 0, dk_f32 = 0, dv_f32 = 0;
 };
 bool attn_flash_supported(int dh, int64_t ldq, int64_t ldo);
-bool attn_flash_preferred(int dh);  // measured faster than the stored-probability path at this head width
+// measured faster than the stored-probability path at this head width and launch size (heads = batch x heads)
+bool attn_flash_preferred(int dh, int64_t heads, int64_t S);
 hipError_t launch_attn_fwd(const AttnP& p, hipStream_t st);
 hipError_t launch_attn_bwd(const AttnP& p, hipStream_t st);  // dQ, dK, dV with tangents (needs delta)
 
