@@ -361,7 +361,7 @@ def main():
     res["next_rows"] = {"column_stats": {"bound": "hbm", "bytes": 8.0 * n, "ms": cs_ms,
                                          "achieved": 8.0 * n / (cs_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                                          "frac": 8.0 * n / (cs_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
-                                         "note": "wall clock of hf_column_stats incl. its two host synchronisations"}}
+                                         "note": "wall clock of hf_column_stats incl. its host synchronisation"}}
     if B >= 2:
         half = B // 2
         ctx.hf_hvp_accumulate(pd, xd, yd, B, half, Sarg, vd, out)

@@ -412,8 +412,11 @@ static int column_stats_run(unsigned long long* stats, const float* h_dev, int64
   // the counters keep the previous call's values: cleared by a fill kernel, not by a memset, so that
   // the sequence stays valid under stream capture
   CKS(launch_fill_f32((float*)stats, CS_STATS_WORDS * 2, 0.f, st));
-  if (n > 0) CKS(launch_colstats_pass1(h_dev, n, thr, n_thresholds, stats, st));
-  CKS(hipMemcpyAsync(hs, stats, 32 * 8, hipMemcpyDeviceToHost, st));
+  if (n > 0) {
+    CKS(launch_colstats_pass1(h_dev, n, thr, n_thresholds, stats, st));
+    CKS(launch_colstats_hist(h_dev, n, stats + 24, n_bins, stats + 32, st));  // reads the maximum of the first pass
+  }
+  CKS(hipMemcpyAsync(hs, stats, (size_t)(32 + n_bins) * 8, hipMemcpyDeviceToHost, st));
   CKS(hipStreamSynchronize(st));
   // |h_i| < t_k (sorted) exactly when the entry reaches at most k thresholds: prefix sums of the buckets
   unsigned long long run = 0, valid = 0;
@@ -426,17 +429,8 @@ static int column_stats_run(unsigned long long* stats, const float* h_dev, int64
   const unsigned bits = (unsigned)hs[24];
   memcpy(&mx, &bits, 4);
   *max_abs = mx;
-  for (int k = 0; k < n_bins; ++k) hist[k] = 0;
-  if (!(mx > 0.f)) {
-    hist[0] = (int64_t)valid;  // a column of zeros: every entry in the first bin
-    return HF_OK;
-  }
-  const volatile float nbf = (float)n_bins;
-  const volatile float scale = nbf / mx;  // one float32 division, as the definition states
-  CKS(launch_colstats_hist(h_dev, n, scale, n_bins, stats + 32, st));
-  CKS(hipMemcpyAsync(hs + 32, stats + 32, (size_t)n_bins * 8, hipMemcpyDeviceToHost, st));
-  CKS(hipStreamSynchronize(st));
-  for (int k = 0; k < n_bins; ++k) hist[k] = (int64_t)hs[32 + k];
+  for (int k = 0; k < n_bins; ++k) hist[k] = mx > 0.f ? (int64_t)hs[32 + k] : 0;
+  if (!(mx > 0.f)) hist[0] = (int64_t)valid;  // a column of zeros: every entry in the first bin
   return HF_OK;
 #undef CKS
 }

@@ -161,7 +161,8 @@ hipError_t launch_splitk_reduce(const SplitKOut& o0, const SplitKOut& o1, int sp
 hipError_t launch_scale_add(float* h, const float* u, float w, int first, int64_t n, hipStream_t st);
 hipError_t launch_colstats_pass1(const float* h, int64_t n, const ColThresholds& thr, int nt, unsigned long long* stats,
                                  hipStream_t st);
-hipError_t launch_colstats_hist(const float* h, int64_t n, float scale, int nb, unsigned long long* hist, hipStream_t st);
+hipError_t launch_colstats_hist(const float* h, int64_t n, const unsigned long long* max_bits, int nb, unsigned long long* hist,
+                                hipStream_t st);
 // Device address, on the current device, of the library's static array of CS_STATS_WORDS counters.
 hipError_t colstats_static_counters(unsigned long long** out);
 hipError_t launch_f32_to_bf16(const float* src, bf16* dst, int64_t n, hipStream_t st);

@@ -108,12 +108,18 @@ __global__ __launch_bounds__(256) void colstats_pass1_kernel(const float* __rest
   }
 }
 
-// Bin of |h_i|: floor(|h_i| * scale), scale = n_bins / max as a float32
-// quotient formed on the host; the maximum itself (and a product that is not a
-// number, which needs an infinite maximum) lands in the last bin.
-__global__ __launch_bounds__(256) void colstats_hist_kernel(const float* __restrict__ h, int64_t n, float scale, int nb,
+// Bin of |h_i|: floor(|h_i| * scale), scale = n_bins / max as one correctly rounded float32
+// quotient; the maximum itself (and a product that is not a number, which needs an infinite
+// maximum) lands in the last bin.  The maximum is the first pass's result, read from the counters
+// (max_bits: its bit pattern), so no host round trip separates the passes; a column without a
+// positive maximum (all zeros, or empty) leaves the bins untouched for the host to fill in.
+__global__ __launch_bounds__(256) void colstats_hist_kernel(const float* __restrict__ h, int64_t n,
+                                                           const unsigned long long* __restrict__ max_bits, int nb,
                                                            unsigned long long* hist) {
   __shared__ unsigned lh[CS_MAX_BINS];
+  const float mx = __uint_as_float((unsigned)*max_bits);
+  if (!(mx > 0.f)) return;
+  const float scale = __fdiv_rn((float)nb, mx);
   for (int i = threadIdx.x; i < nb; i += 256) lh[i] = 0;
   __syncthreads();
   // consecutive entries of a thread that fall in the same bin are counted in a register and added
@@ -159,8 +165,9 @@ hipError_t launch_colstats_pass1(const float* h, int64_t n, const ColThresholds&
   hipLaunchKernelGGL(colstats_pass1_kernel, dim3(colstats_blocks(n)), dim3(256), 0, st, h, n, thr, nt, stats);
   return hipGetLastError();
 }
-hipError_t launch_colstats_hist(const float* h, int64_t n, float scale, int nb, unsigned long long* hist, hipStream_t st) {
-  hipLaunchKernelGGL(colstats_hist_kernel, dim3(colstats_blocks(n)), dim3(256), 0, st, h, n, scale, nb, hist);
+hipError_t launch_colstats_hist(const float* h, int64_t n, const unsigned long long* max_bits, int nb, unsigned long long* hist,
+                                hipStream_t st) {
+  hipLaunchKernelGGL(colstats_hist_kernel, dim3(colstats_blocks(n)), dim3(256), 0, st, h, n, max_bits, nb, hist);
   return hipGetLastError();
 }
 
