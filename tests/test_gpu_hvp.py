@@ -47,6 +47,10 @@ SHAPES = {
     "gpt_dh128": dict(model=si._gpt(2, 256, 2, 264, 301, 200), batch=2, seq=200, tokens="zipf"),
     "llama_gqa_dh128": dict(model=si._llama(2, 512, 4, 344, 301, 136, n_kv=2), batch=2, seq=136, tokens="zipf"),
 }
+# (attention modes only) 45 (batch, head) pairs of 6 query tiles each: 36 blocks per XCD, i.e. more
+# than its 32 CUs and at most two per CU, which is where the streamed kernels pair long and short
+# tiles on a CU; 45 is not a multiple of 8, so three of the 48 head slots of a launch are empty
+ATTN_SHAPES = dict(SHAPES, gpt_many_heads=dict(model=si._gpt(1, 288, 9, 136, 97, 700), batch=5, seq=700, tokens="zipf"))
 
 
 def run_case(cfg, dtype, seed=0, short_seq=None):
@@ -81,11 +85,11 @@ def test_hvp_parity_small(name, dtype):
 
 @pytest.mark.parametrize("mode", ["streamed", "stored"])
 @pytest.mark.parametrize("name", ["gpt_fused", "gpt_heads8", "llama_gqa_mid", "gpt_mid", "gpt_dh64_long", "gpt_dh128",
-                                  "llama_gqa_dh128", "llama_gqa_deep"])
+                                  "llama_gqa_dh128", "llama_gqa_deep", "gpt_many_heads"])
 def test_hvp_attention_modes(name, mode):
     # both evaluations of attention at every head width the streamed kernels take (32, 64, 128),
     # whichever of them the library would choose by itself
-    cfg = SHAPES[name]
+    cfg = ATTN_SHAPES[name]
     run_case(dict(cfg, model=dict(cfg["model"], attention=mode)), "bf16", seed=3)
 
 
