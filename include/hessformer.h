@@ -81,6 +81,15 @@ typedef enum { HF_ACT_GELU_ERF = 0, HF_ACT_GELU_TANH = 1 } hf_activation;
  * or with the S x S probabilities and score adjoints of every layer stored.  AUTO takes the
  * streamed kernels where they are supported and measured faster. */
 typedef enum { HF_ATTN_AUTO = 0, HF_ATTN_STREAMED = 1, HF_ATTN_STORED = 2 } hf_attention;
+/* bf16 parameters: whether the primal forward activations that feed matrix products (and the
+ * attention probabilities) are carried as pairs of bf16 numbers, a rounded value and the rounding's
+ * remainder, which enter the products as extra terms.  Tangents and adjoints are single bf16
+ * numbers either way.  AUTO: pairs for LLAMA, whose product misses the 2e-2 bar against a float64
+ * evaluation without them beyond a few layers at width 4096; single numbers for GPT, where the
+ * pairs change the error of the product by less than a tenth of itself (2.2e-3 -> 2.6e-3 at 24
+ * layers of width 2048) and cost a quarter more forward matrix work.  Ignored for fp32 parameters
+ * and for the MLP. */
+typedef enum { HF_PRIMAL_AUTO = 0, HF_PRIMAL_PAIRS = 1, HF_PRIMAL_SINGLE = 2 } hf_primal;
 
 /* Model description.  MLP uses mlp_*; GPT/LLAMA use the transformer fields.
  * GPT: pre-LayerNorm decoder, learned positions, GELU (erf or tanh form, see
@@ -89,7 +98,7 @@ typedef enum { HF_ATTN_AUTO = 0, HF_ATTN_STREAMED = 1, HF_ATTN_STORED = 2 } hf_a
  * (i, i + dh/2) with base rope_theta, SwiGLU, no biases, optional grouped-query
  * attention (n_kv_head).
  * param_dtype HF_BF16: weights are bf16 MFMA operands, activations fed to
- * matrix products are rounded to bf16, accumulation / residual stream /
+ * matrix products are rounded to bf16 (see `primal`), accumulation / residual stream /
  * normalisation and softmax statistics are fp32.  HF_F32: fp32 throughout. */
 typedef struct {
   int32_t arch;           /* hf_arch */
@@ -109,6 +118,7 @@ typedef struct {
                              n_head; GPT takes 0 or n_head. */
   int32_t attention;      /* hf_attention; HF_ATTN_STREAMED where it is not supported: hf_create
                              returns HF_ESHAPE */
+  int32_t primal;         /* hf_primal */
 } hf_model_desc;
 
 /* ---- host-only helpers (no GPU needed) ---------------------------------- */

@@ -19,6 +19,7 @@ HF_DTYPE = {"f32": 0, "bf16": 1, "none": 2}
 HF_REORTH = {"none": 0, "full": 1}
 HF_ACT = {"gelu_erf": 0, "gelu_tanh": 1}
 HF_ATTN = {"auto": 0, "streamed": 1, "stored": 2}
+HF_PRIMAL = {"auto": 0, "pairs": 1, "single": 2}
 
 EXPORTS = [
     "hf_desc_num_params", "hf_layout_count", "hf_layout_entry", "hf_tridiag_readout", "hf_version",
@@ -36,7 +37,7 @@ class hf_model_desc(C.Structure):
                 ("mlp_hidden", C.c_int32), ("mlp_out", C.c_int32), ("tie_embeddings", C.c_int32),
                 ("norm_eps", C.c_float), ("rope_theta", C.c_float), ("param_dtype", C.c_int32),
                 ("basis_dtype", C.c_int32), ("activation", C.c_int32), ("n_kv_head", C.c_int32),
-                ("attention", C.c_int32)]
+                ("attention", C.c_int32), ("primal", C.c_int32)]
 
 
 class HessformerError(RuntimeError):
@@ -122,6 +123,7 @@ def make_desc(model, param_dtype="f32", basis_dtype="f32"):
     d.activation = HF_ACT[model.get("act", "gelu_erf")]
     d.n_kv_head = int(model.get("n_kv_head", 0) or 0) if model["arch"] == "llama" else 0
     d.attention = HF_ATTN[model.get("attention", "auto")]
+    d.primal = HF_PRIMAL[model.get("primal", "auto")]
     return d
 
 

@@ -210,11 +210,14 @@ __device__ __forceinline__ uint32_t addr_cols(int lane, int rt) {
 // Online softmax with a lazy reference maximum: the running maximum is only moved (and the
 // accumulators rescaled) when a tile exceeds it by more than 8, which keeps exp() below e^8.
 
-template <int DH>
+// LO: the primal operands come as pairs of a high and a low half (extra terms, extra tiles).
+template <int DH, bool LO>
 __global__ __launch_bounds__(256, (DH <= 64 ? 2 : 1)) void attn_fwd_kernel(const AttnP p) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
-  constexpr int TILE_B = 64 * DH, STAGE_B = 6 * TILE_B, KS = DH / 16, RT = DH / 32;
-  constexpr int NI = 6 * (DH / 16) / 4;  // load instructions per wave and stage
+  // tiles of a stage: K hi / (lo) / t with keys on lanes, V hi / (lo) / t for transposing reads
+  constexpr int T_KD = LO ? 2 : 1, T_VH = LO ? 3 : 2, T_VL = 4, T_VD = LO ? 5 : 3, NT = LO ? 6 : 4;
+  constexpr int TILE_B = 64 * DH, STAGE_B = NT * TILE_B, KS = DH / 16, RT = DH / 32;
+  constexpr int NI = NT * (DH / 16) / 4;  // load instructions per wave and stage
   const int t = threadIdx.x, lane = t & 63;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6) & 3;  // (masked so that tile indices below fold)
   const int nqt = (p.S + 127) / 128;
@@ -227,27 +230,28 @@ __global__ __launch_bounds__(256, (DH <= 64 ? 2 : 1)) void attn_fwd_kernel(const
   const int mq = mw + (lane & 31);            // this lane's query
   const int qm = min(mq, p.S - 1);
 
-  bf16x8 qh[KS], ql[KS], qd[KS];
+  bf16x8 qh[KS], ql[LO ? KS : 1], qd[KS];
   {
     const int64_t off = (row0 + qm) * p.ldq + (int64_t)h * DH + (lane >> 5) * 8;
 #pragma unroll
     for (int kk = 0; kk < KS; ++kk) {
       qh[kk] = *(const bf16x8*)(p.qkv + off + kk * 16);
-      ql[kk] = *(const bf16x8*)(p.qkv_lo + off + kk * 16);
+      if constexpr (LO) ql[kk] = *(const bf16x8*)(p.qkv_lo + off + kk * 16);
       qd[kk] = *(const bf16x8*)(p.qkv_t + off + kk * 16);
     }
   }
   const int64_t ok = row0 * p.ldq + p.offK + (int64_t)hk * DH, ov = row0 * p.ldq + p.offV + (int64_t)hk * DH;
-  const bf16 *const sKh = p.qkv + ok, *const sKl = p.qkv_lo + ok, *const sKd = p.qkv_t + ok, *const sVh = p.qkv + ov, *const sVl = p.qkv_lo + ov, *const sVd = p.qkv_t + ov;
+  const bf16 *const sKh = p.qkv + ok, *const sKl = LO ? p.qkv_lo + ok : nullptr, *const sKd = p.qkv_t + ok, *const sVh = p.qkv + ov,
+             *const sVl = LO ? p.qkv_lo + ov : nullptr, *const sVd = p.qkv_t + ov;
   const uint32_t lp = LdsLoad<DH>::lane_part(lane);
   HF_LDS char* const smem_c = (HF_LDS char*)smem_raw;
   auto issue = [&](int stage, int r0) {
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
-      const int T = tile_of<DH / 16>(wave, i);  // (wave-uniform) tile: K hi / lo / t, V hi / lo / t
-      const bf16* base = T == 0 ? sKh : T == 1 ? sKl : T == 2 ? sKd : T == 3 ? sVh : T == 4 ? sVl : sVd;
+      const int T = tile_of<DH / 16>(wave, i);  // (wave-uniform)
+      const bf16* base = T == 0 ? sKh : T == T_KD ? sKd : T == T_VH ? sVh : T == T_VD ? sVd : (T == 1 ? sKl : sVl);
       int row, col;
-      LdsLoad<DH>::lane_chunk(lp, wave + 4 * i, T >= 3, row, col);
+      LdsLoad<DH>::lane_chunk(lp, wave + 4 * i, T >= T_VH, row, col);
       const int rr = min(r0 + row, p.S - 1);
       __builtin_amdgcn_global_load_lds((const void*)(base + ((int64_t)rr * p.ldq + col)),
                                        (HF_LDS void*)(smem_c + stage * STAGE_B + (wave + 4 * i) * 1024), 16, 0, 0);
@@ -270,23 +274,25 @@ __global__ __launch_bounds__(256, (DH <= 64 ? 2 : 1)) void attn_fwd_kernel(const
 #pragma unroll
     for (int v = 0; v < 16; ++v) { st[v] = 0.f; su[v] = 0.f; }
     bf16x8 kh[2], kl[2], kd[2];
-    kh[0] = lds_read_b128<SB>(adK0); kl[0] = lds_read_b128<SB + TILE_B>(adK0); kd[0] = lds_read_b128<SB + 2 * TILE_B>(adK0);
+    kh[0] = lds_read_b128<SB>(adK0); kd[0] = lds_read_b128<SB + T_KD * TILE_B>(adK0);
+    if constexpr (LO) kl[0] = lds_read_b128<SB + TILE_B>(adK0);
     static_for<KS>([&](auto kk_c) {
       constexpr int kk = decltype(kk_c)::value, c = kk & 1, nx = c ^ 1;
       if constexpr (kk + 1 < KS) {
         const uint32_t ad = lds_xor<((kk + 1) << 5)>(adK0);
-        kh[nx] = lds_read_b128<SB>(ad); kl[nx] = lds_read_b128<SB + TILE_B>(ad);
-        kd[nx] = lds_read_b128<SB + 2 * TILE_B>(ad);
-        lds_wait<3>();
+        kh[nx] = lds_read_b128<SB>(ad); kd[nx] = lds_read_b128<SB + T_KD * TILE_B>(ad);
+        if constexpr (LO) kl[nx] = lds_read_b128<SB + TILE_B>(ad);
+        lds_wait<(LO ? 3 : 2)>();
       } else {
         lds_wait<0>();
       }
-      lds_tie(kh[c]); lds_tie(kl[c]); lds_tie(kd[c]);
+      lds_tie(kh[c]); lds_tie(kd[c]);
+      if constexpr (LO) lds_tie(kl[c]);
       st = HF_MFMA(kh[c], qh[kk], st);
       su = HF_MFMA(kd[c], qh[kk], su);
-      st = HF_MFMA(kl[c], qh[kk], st);
+      if constexpr (LO) st = HF_MFMA(kl[c], qh[kk], st);
       su = HF_MFMA(kh[c], qd[kk], su);
-      st = HF_MFMA(kh[c], ql[kk], st);
+      if constexpr (LO) st = HF_MFMA(kh[c], ql[kk], st);
       __builtin_amdgcn_sched_barrier(0);
     });
     // first V fragments on their way while the softmax arithmetic runs
@@ -295,9 +301,9 @@ __global__ __launch_bounds__(256, (DH <= 64 ? 2 : 1)) void attn_fwd_kernel(const
       constexpr int s = decltype(s_c)::value, set = decltype(set_c)::value;
       constexpr int rt = s % RT, ks = s / RT, OFF = SB + ks * 16 * DH * 2;
       const uint32_t ad = lds_xor<(rt << 6)>(adV0);
-      vh[set][0] = lds_read_tr64<OFF + 3 * TILE_B>(ad); vh[set][1] = lds_read_tr64<OFF + 3 * TILE_B + 8 * DH * 2>(ad);
-      vl[set][0] = lds_read_tr64<OFF + 4 * TILE_B>(ad); vl[set][1] = lds_read_tr64<OFF + 4 * TILE_B + 8 * DH * 2>(ad);
-      vd[set][0] = lds_read_tr64<OFF + 5 * TILE_B>(ad); vd[set][1] = lds_read_tr64<OFF + 5 * TILE_B + 8 * DH * 2>(ad);
+      vh[set][0] = lds_read_tr64<OFF + T_VH * TILE_B>(ad); vh[set][1] = lds_read_tr64<OFF + T_VH * TILE_B + 8 * DH * 2>(ad);
+      vd[set][0] = lds_read_tr64<OFF + T_VD * TILE_B>(ad); vd[set][1] = lds_read_tr64<OFF + T_VD * TILE_B + 8 * DH * 2>(ad);
+      if constexpr (LO) { vl[set][0] = lds_read_tr64<OFF + T_VL * TILE_B>(ad); vl[set][1] = lds_read_tr64<OFF + T_VL * TILE_B + 8 * DH * 2>(ad); }
     };
     req_v(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
     // register v of this lane: key n0 + 8 (v/4) + 4 (lane/32) + v%4 against query mq
@@ -343,7 +349,7 @@ __global__ __launch_bounds__(256, (DH <= 64 ? 2 : 1)) void attn_fwd_kernel(const
         eh[ks][j] = hi;
         lo8[j] = s[ks * 8 + j] - (float)hi;
       }
-      el[ks] = pack8(lo8);
+      if constexpr (LO) el[ks] = pack8(lo8);
       es[ks] = pack8(eu + ks * 8);
     }
     __builtin_amdgcn_sched_barrier(0);
@@ -351,19 +357,22 @@ __global__ __launch_bounds__(256, (DH <= 64 ? 2 : 1)) void attn_fwd_kernel(const
       constexpr int sI = decltype(s_c)::value, c = sI & 1, rt = sI % RT, ks = sI / RT;
       if constexpr (sI + 1 < 2 * RT) {
         req_v(std::integral_constant<int, sI + 1>{}, std::integral_constant<int, c ^ 1>{});
-        lds_wait<6>();
+        lds_wait<(LO ? 6 : 4)>();
       } else {
         lds_wait<0>();
       }
-      lds_tie(vh[c][0]); lds_tie(vh[c][1]); lds_tie(vl[c][0]); lds_tie(vl[c][1]); lds_tie(vd[c][0]); lds_tie(vd[c][1]);
+      lds_tie(vh[c][0]); lds_tie(vh[c][1]); lds_tie(vd[c][0]); lds_tie(vd[c][1]);
       const bf16x8 a_h = __builtin_shufflevector(vh[c][0], vh[c][1], 0, 1, 2, 3, 4, 5, 6, 7);
-      const bf16x8 a_l = __builtin_shufflevector(vl[c][0], vl[c][1], 0, 1, 2, 3, 4, 5, 6, 7);
       const bf16x8 a_d = __builtin_shufflevector(vd[c][0], vd[c][1], 0, 1, 2, 3, 4, 5, 6, 7);
       o[rt] = HF_MFMA(a_h, eh[ks], o[rt]);
       a1[rt] = HF_MFMA(a_h, es[ks], a1[rt]);
-      o[rt] = HF_MFMA(a_h, el[ks], o[rt]);
+      if constexpr (LO) o[rt] = HF_MFMA(a_h, el[ks], o[rt]);
       a1[rt] = HF_MFMA(a_d, eh[ks], a1[rt]);
-      o[rt] = HF_MFMA(a_l, eh[ks], o[rt]);
+      if constexpr (LO) {
+        lds_tie(vl[c][0]); lds_tie(vl[c][1]);
+        const bf16x8 a_l = __builtin_shufflevector(vl[c][0], vl[c][1], 0, 1, 2, 3, 4, 5, 6, 7);
+        o[rt] = HF_MFMA(a_l, eh[ks], o[rt]);
+      }
       __builtin_amdgcn_sched_barrier(0);
     });
   };
@@ -407,7 +416,7 @@ __global__ __launch_bounds__(256, (DH <= 64 ? 2 : 1)) void attn_fwd_kernel(const
         xt[q] = (a1[rt][g4 * 4 + q] - r * ov_) * inv;
       }
       store4(p.o, 0, orow, p.ldo, col, x[0], x[1], x[2], x[3]);
-      store4(p.o_lo, 0, orow, p.ldo, col, xl[0], xl[1], xl[2], xl[3]);
+      if constexpr (LO) store4(p.o_lo, 0, orow, p.ldo, col, xl[0], xl[1], xl[2], xl[3]);
       store4(p.o_t, 0, orow, p.ldo, col, xt[0], xt[1], xt[2], xt[3]);
     }
   }
@@ -423,10 +432,12 @@ __global__ __launch_bounds__(256, (DH <= 64 ? 2 : 1)) void attn_fwd_kernel(const
 // on lanes for the score-shaped products, K hi / t once more in the layout of transposing reads for
 // dQ^T = K^T dS^T), filled by direct loads one key tile ahead, one barrier per key tile.
 
-template <int DH>
+template <int DH, bool LO>
 __global__ __launch_bounds__(256, (DH <= 64 ? 2 : 1)) void attn_bwd_q_kernel(const AttnP p) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
-  constexpr int TILE_B = 64 * DH, NT = 7, STAGE_B = NT * TILE_B, KS = DH / 16, RT = DH / 32;
+  // tiles of a stage: K hi / (lo) / t, V hi / t with keys on lanes; K hi / t for transposing reads
+  constexpr int T_KD = LO ? 2 : 1, T_VH = T_KD + 1, T_VD = T_KD + 2, T_KHT = T_KD + 3, T_KDT = T_KD + 4, NT = T_KD + 5;
+  constexpr int TILE_B = 64 * DH, STAGE_B = NT * TILE_B, KS = DH / 16, RT = DH / 32;
   constexpr int NQ = NT * (DH / 16), NI = (NQ + 3) / 4;  // load instructions per stage, per wave
   const int t = threadIdx.x, lane = t & 63;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6) & 3;
@@ -440,14 +451,14 @@ __global__ __launch_bounds__(256, (DH <= 64 ? 2 : 1)) void attn_bwd_q_kernel(con
   const int mq = mw + (lane & 31);
   const int qm = min(mq, p.S - 1);
 
-  bf16x8 qh[KS], ql[KS], qd[KS], gh[KS], gd[KS];
+  bf16x8 qh[KS], ql[LO ? KS : 1], qd[KS], gh[KS], gd[KS];
   {
     const int64_t off = (row0 + qm) * p.ldq + (int64_t)h * DH + (lane >> 5) * 8;
     const int64_t offg = (row0 + qm) * p.lddo + (int64_t)h * DH + (lane >> 5) * 8;
 #pragma unroll
     for (int kk = 0; kk < KS; ++kk) {
       qh[kk] = *(const bf16x8*)(p.qkv + off + kk * 16);
-      ql[kk] = *(const bf16x8*)(p.qkv_lo + off + kk * 16);
+      if constexpr (LO) ql[kk] = *(const bf16x8*)(p.qkv_lo + off + kk * 16);
       qd[kk] = *(const bf16x8*)(p.qkv_t + off + kk * 16);
       gh[kk] = *(const bf16x8*)(p.dO + offg + kk * 16);
       gd[kk] = *(const bf16x8*)(p.dO_t + offg + kk * 16);
@@ -458,7 +469,7 @@ __global__ __launch_bounds__(256, (DH <= 64 ? 2 : 1)) void attn_bwd_q_kernel(con
   const float dl = p.delta[srow * 3], dlt = p.delta[srow * 3 + 1];
 
   const int64_t ok = row0 * p.ldq + p.offK + (int64_t)hk * DH, ov = row0 * p.ldq + p.offV + (int64_t)hk * DH;
-  const bf16 *const sKh = p.qkv + ok, *const sKl = p.qkv_lo + ok, *const sKd = p.qkv_t + ok, *const sVh = p.qkv + ov, *const sVd = p.qkv_t + ov;
+  const bf16 *const sKh = p.qkv + ok, *const sKl = LO ? p.qkv_lo + ok : nullptr, *const sKd = p.qkv_t + ok, *const sVh = p.qkv + ov, *const sVd = p.qkv_t + ov;
   const uint32_t lp = LdsLoad<DH>::lane_part(lane);
   HF_LDS char* const smem_c = (HF_LDS char*)smem_raw;
   auto issue = [&](int stage, int r0) {
@@ -466,10 +477,10 @@ __global__ __launch_bounds__(256, (DH <= 64 ? 2 : 1)) void attn_bwd_q_kernel(con
     for (int i = 0; i < NI; ++i) {
       const int q = wave + 4 * i;  // (wave-uniform)
       if (NQ % 4 == 0 || q < NQ) {
-        const int T = tile_of<DH / 16>(wave, i);  // K hi / lo / t, V hi / t with keys on lanes; K hi / t for transposing reads
-        const bf16* base = (T == 0 || T == 5) ? sKh : T == 1 ? sKl : (T == 2 || T == 6) ? sKd : T == 3 ? sVh : sVd;
+        const int T = tile_of<DH / 16>(wave, i);
+        const bf16* base = (T == 0 || T == T_KHT) ? sKh : (T == T_KD || T == T_KDT) ? sKd : T == T_VH ? sVh : T == T_VD ? sVd : sKl;
         int row, col;
-        LdsLoad<DH>::lane_chunk(lp, q, T >= 5, row, col);
+        LdsLoad<DH>::lane_chunk(lp, q, T >= T_KHT, row, col);
         const int rr_ = min(r0 + row, p.S - 1);
         __builtin_amdgcn_global_load_lds((const void*)(base + ((int64_t)rr_ * p.ldq + col)),
                                          (HF_LDS void*)(smem_c + stage * STAGE_B + q * 1024), 16, 0, 0);
@@ -494,28 +505,29 @@ __global__ __launch_bounds__(256, (DH <= 64 ? 2 : 1)) void attn_bwd_q_kernel(con
     auto req_k = [&](auto kk_c, auto set_c) {
       constexpr int kk = decltype(kk_c)::value, set = decltype(set_c)::value;
       const uint32_t ad = lds_xor<(kk << 5)>(adK0);
-      kh[set] = lds_read_b128<SB>(ad); kl[set] = lds_read_b128<SB + TILE_B>(ad);
-      kd[set] = lds_read_b128<SB + 2 * TILE_B>(ad); vh[set] = lds_read_b128<SB + 3 * TILE_B>(ad);
-      vd[set] = lds_read_b128<SB + 4 * TILE_B>(ad);
+      kh[set] = lds_read_b128<SB>(ad); kd[set] = lds_read_b128<SB + T_KD * TILE_B>(ad);
+      vh[set] = lds_read_b128<SB + T_VH * TILE_B>(ad); vd[set] = lds_read_b128<SB + T_VD * TILE_B>(ad);
+      if constexpr (LO) kl[set] = lds_read_b128<SB + TILE_B>(ad);
     };
     req_k(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
     static_for<KS>([&](auto kk_c) {
       constexpr int kk = decltype(kk_c)::value, c = kk & 1;
       if constexpr (kk + 1 < KS) {
         req_k(std::integral_constant<int, kk + 1>{}, std::integral_constant<int, c ^ 1>{});
-        lds_wait<5>();
+        lds_wait<(LO ? 5 : 4)>();
       } else {
         lds_wait<0>();
       }
-      lds_tie(kh[c]); lds_tie(kl[c]); lds_tie(kd[c]); lds_tie(vh[c]); lds_tie(vd[c]);
+      lds_tie(kh[c]); lds_tie(kd[c]); lds_tie(vh[c]); lds_tie(vd[c]);
+      if constexpr (LO) lds_tie(kl[c]);
       st = HF_MFMA(kh[c], qh[kk], st);
       su = HF_MFMA(kd[c], qh[kk], su);
       dp = HF_MFMA(vh[c], gh[kk], dp);       // dP^T = V dO^T
       dpt = HF_MFMA(vh[c], gd[kk], dpt);     // dP_t^T = V dO_t^T + V_t dO^T
-      st = HF_MFMA(kl[c], qh[kk], st);
+      if constexpr (LO) st = HF_MFMA(kl[c], qh[kk], st);
       su = HF_MFMA(kh[c], qd[kk], su);
       dpt = HF_MFMA(vd[c], gh[kk], dpt);
-      st = HF_MFMA(kh[c], ql[kk], st);
+      if constexpr (LO) st = HF_MFMA(kh[c], ql[kk], st);
       __builtin_amdgcn_sched_barrier(0);
     });
     // first transposed fragments on their way while the pointwise arithmetic runs
@@ -524,8 +536,8 @@ __global__ __launch_bounds__(256, (DH <= 64 ? 2 : 1)) void attn_bwd_q_kernel(con
       constexpr int sI = decltype(s_c)::value, set = decltype(set_c)::value;
       constexpr int rt = sI % RT, ks = sI / RT, OFF = SB + ks * 16 * DH * 2;
       const uint32_t ad = lds_xor<(rt << 6)>(adT0);
-      th[set][0] = lds_read_tr64<OFF + 5 * TILE_B>(ad); th[set][1] = lds_read_tr64<OFF + 5 * TILE_B + 8 * DH * 2>(ad);
-      td[set][0] = lds_read_tr64<OFF + 6 * TILE_B>(ad); td[set][1] = lds_read_tr64<OFF + 6 * TILE_B + 8 * DH * 2>(ad);
+      th[set][0] = lds_read_tr64<OFF + T_KHT * TILE_B>(ad); th[set][1] = lds_read_tr64<OFF + T_KHT * TILE_B + 8 * DH * 2>(ad);
+      td[set][0] = lds_read_tr64<OFF + T_KDT * TILE_B>(ad); td[set][1] = lds_read_tr64<OFF + T_KDT * TILE_B + 8 * DH * 2>(ad);
     };
     req_t(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
     // register v of this lane: key n0 + 8 (v/4) + 4 (lane/32) + v%4 against query mq
@@ -601,12 +613,12 @@ __global__ __launch_bounds__(256, (DH <= 64 ? 2 : 1)) void attn_bwd_q_kernel(con
 // per query), which go through registers two tiles ahead.  One barrier per query tile; the tiles of
 // all query heads of a group form one sequence.
 
-template <int DH, int WHAT>
+template <int DH, int WHAT, bool LO>
 struct KvTiles {
   static constexpr bool DV = (WHAT & 1) != 0, DK = (WHAT & 2) != 0;
-  static constexpr int T_QH = 0, T_QL = 1, T_QD = 2;
-  static constexpr int T_GH = DK ? 3 : -1, T_GD = DK ? 4 : -1;
-  static constexpr int NKC = DK ? 5 : 3;                    // tiles with queries on lanes
+  static constexpr int T_QH = 0, T_QL = LO ? 1 : -1, T_QD = LO ? 2 : 1;
+  static constexpr int T_GH = DK ? T_QD + 1 : -1, T_GD = DK ? T_QD + 2 : -1;
+  static constexpr int NKC = T_QD + 1 + (DK ? 2 : 0);       // tiles with queries on lanes
   static constexpr int T_QHT = DK ? NKC : -1, T_QDT = DK ? NKC + 1 : -1;
   static constexpr int T_GHT = DV ? NKC + (DK ? 2 : 0) : -1, T_GDT = DV ? NKC + (DK ? 2 : 0) + 1 : -1;
   static constexpr int NT = NKC + (DK ? 2 : 0) + (DV ? 2 : 0);
@@ -619,10 +631,10 @@ struct KvTiles {
   }
 };
 
-template <int DH, int WHAT>
+template <int DH, int WHAT, bool LO>
 __global__ __launch_bounds__(256, (DH <= 32 ? 2 : 1)) void attn_bwd_kv_kernel(const AttnP p) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
-  typedef KvTiles<DH, WHAT> L;
+  typedef KvTiles<DH, WHAT, LO> L;
   constexpr bool DV = L::DV, DK = L::DK;
   constexpr int TILE_B = L::TILE_B, STAGE_B = L::STAGE_B, KS = DH / 16, RT = DH / 32;
   constexpr int NQ = L::NT * (DH / 16), NI = (NQ + 3) / 4;
@@ -641,13 +653,13 @@ __global__ __launch_bounds__(256, (DH <= 32 ? 2 : 1)) void attn_bwd_kv_kernel(co
   const int nk = kw + (lane & 31);            // this lane's key
   const int nkc = min(nk, p.S - 1);
 
-  bf16x8 kh[KS], kl[KS], kd[KS], vh[DK ? KS : 1], vd[DK ? KS : 1];
+  bf16x8 kh[KS], kl[LO ? KS : 1], kd[KS], vh[DK ? KS : 1], vd[DK ? KS : 1];
   {
     const int64_t off = (row0 + nkc) * p.ldq + (int64_t)hk * DH + (lane >> 5) * 8;
 #pragma unroll
     for (int kk = 0; kk < KS; ++kk) {
       kh[kk] = *(const bf16x8*)(p.qkv + p.offK + off + kk * 16);
-      kl[kk] = *(const bf16x8*)(p.qkv_lo + p.offK + off + kk * 16);
+      if constexpr (LO) kl[kk] = *(const bf16x8*)(p.qkv_lo + p.offK + off + kk * 16);
       kd[kk] = *(const bf16x8*)(p.qkv_t + p.offK + off + kk * 16);
       if (DK) {
         vh[kk] = *(const bf16x8*)(p.qkv + p.offV + off + kk * 16);
@@ -657,7 +669,8 @@ __global__ __launch_bounds__(256, (DH <= 32 ? 2 : 1)) void attn_bwd_kv_kernel(co
     if constexpr (DH == 128) {  // 160 registers of loop constants that only matrix instructions read: the accumulator file
 #pragma unroll
       for (int kk = 0; kk < KS; ++kk) {
-        agpr_pin(kh[kk]); agpr_pin(kl[kk]); agpr_pin(kd[kk]);
+        agpr_pin(kh[kk]); agpr_pin(kd[kk]);
+        if constexpr (LO) agpr_pin(kl[kk]);
         if (DK) { agpr_pin(vh[kk]); agpr_pin(vd[kk]); }
       }
     }
@@ -674,7 +687,7 @@ __global__ __launch_bounds__(256, (DH <= 32 ? 2 : 1)) void attn_bwd_kv_kernel(co
   const int nit = nqs * p.grp;           // ... of all query heads of the group
 
   const uint32_t lp = LdsLoad<DH>::lane_part(lane);
-  const bf16 *const pq = p.qkv, *const pql = p.qkv_lo, *const pqt = p.qkv_t, *const pg = p.dO, *const pgt = p.dO_t;
+  const bf16 *const pq = p.qkv, *const pql = LO ? p.qkv_lo : nullptr, *const pqt = p.qkv_t, *const pg = p.dO, *const pgt = p.dO_t;
   const int64_t ldq = p.ldq, lddo = p.lddo;
   auto issue = [&](int stage, int it) {
     const int j = it / nqs, r0 = k0 + (it - j * nqs) * 32;
@@ -715,8 +728,8 @@ __global__ __launch_bounds__(256, (DH <= 32 ? 2 : 1)) void attn_bwd_kv_kernel(co
     auto req_q = [&](auto kk_c, auto set_c) {
       constexpr int kk = decltype(kk_c)::value, set = decltype(set_c)::value;
       const uint32_t ad = lds_xor<(kk << 5)>(adQ0);
-      qa[set] = lds_read_b128<SB + L::T_QH * TILE_B>(ad); qb[set] = lds_read_b128<SB + L::T_QL * TILE_B>(ad);
-      qc[set] = lds_read_b128<SB + L::T_QD * TILE_B>(ad);
+      qa[set] = lds_read_b128<SB + L::T_QH * TILE_B>(ad); qc[set] = lds_read_b128<SB + L::T_QD * TILE_B>(ad);
+      if constexpr (LO) qb[set] = lds_read_b128<SB + L::T_QL * TILE_B>(ad);
       if constexpr (DK) {
         ga[set] = lds_read_b128<SB + L::T_GH * TILE_B>(ad); gb[set] = lds_read_b128<SB + L::T_GD * TILE_B>(ad);
       }
@@ -731,11 +744,12 @@ __global__ __launch_bounds__(256, (DH <= 32 ? 2 : 1)) void attn_bwd_kv_kernel(co
         lds_wait<0>();
       } else if constexpr (kk + 1 < KS) {
         req_q(std::integral_constant<int, kk + 1>{}, std::integral_constant<int, c ^ 1>{});
-        lds_wait<(DK ? 5 : 3)>();
+        lds_wait<((LO ? 3 : 2) + (DK ? 2 : 0))>();
       } else {
         lds_wait<0>();
       }
-      lds_tie(qa[c]); lds_tie(qb[c]); lds_tie(qc[c]);
+      lds_tie(qa[c]); lds_tie(qc[c]);
+      if constexpr (LO) lds_tie(qb[c]);
       if constexpr (DK) { lds_tie(ga[c]); lds_tie(gb[c]); }
       st = HF_MFMA(qa[c], kh[kk], st);
       su = HF_MFMA(qc[c], kh[kk], su);
@@ -743,10 +757,10 @@ __global__ __launch_bounds__(256, (DH <= 32 ? 2 : 1)) void attn_bwd_kv_kernel(co
         dp = HF_MFMA(ga[c], vh[kk], dp);       // dP = dO V^T
         dpt = HF_MFMA(gb[c], vh[kk], dpt);     // dP_t = dO_t V^T + dO V_t^T
       }
-      st = HF_MFMA(qb[c], kh[kk], st);
+      if constexpr (LO) st = HF_MFMA(qb[c], kh[kk], st);
       su = HF_MFMA(qa[c], kd[kk], su);
       if constexpr (DK) dpt = HF_MFMA(ga[c], vd[kk], dpt);
-      st = HF_MFMA(qa[c], kl[kk], st);
+      if constexpr (LO) st = HF_MFMA(qa[c], kl[kk], st);
       __builtin_amdgcn_sched_barrier(0);
     });
     // the products of the second half, in order: per key step ks, the dV products of the RT column
@@ -887,60 +901,76 @@ bool attn_flash_supported(int dh, int64_t ldq, int64_t ldo) { return (dh == 32 |
 // sequence (Llama-7B shape, 128 blocks: 1 % behind).
 bool attn_flash_preferred(int dh, int64_t heads, int64_t S) { return dh <= 64 || heads * ((S + 127) / 128) >= 256; }
 
-hipError_t launch_attn_fwd(const AttnP& p, hipStream_t st) {
-  if (!attn_shape_ok(p) || p.ldo % 8) return hipErrorInvalidValue;
-  if (!al16(p.qkv) || !al16(p.qkv_lo) || !al16(p.qkv_t) || !al16(p.o) || !al16(p.o_lo) || !al16(p.o_t) || !p.stat) return hipErrorInvalidValue;
-  const int nqt = (p.S + 127) / 128;
-  const unsigned grid = (unsigned)(((p.B * p.H + 7) / 8) * 8 * nqt);
-  const size_t lds = (size_t)2 * 6 * 32 * p.dh * 2;  // two stages of six tiles
-  if (p.dh == 32) hipLaunchKernelGGL(attn_fwd_kernel<32>, dim3(grid), dim3(256), lds, st, p);
-  else if (p.dh == 64) hipLaunchKernelGGL(attn_fwd_kernel<64>, dim3(grid), dim3(256), lds, st, p);
-  else {
-    static OncePerDevice once;
-    const hipError_t e = once.lds_limit((const void*)attn_fwd_kernel<128>, (int)lds);  // 96 KB
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(attn_fwd_kernel<128>, dim3(grid), dim3(256), lds, st, p);
-  }
+template <int DH, bool LO>
+static hipError_t launch_fwd_t(const AttnP& p, unsigned grid, hipStream_t st) {
+  constexpr int lds = 2 * (LO ? 6 : 4) * 64 * DH;  // two stages of six (four) tiles
+  static OncePerDevice once;
+  auto kern = attn_fwd_kernel<DH, LO>;
+  if (lds > 64 * 1024)
+    if (const hipError_t e = once.lds_limit((const void*)kern, lds); e != hipSuccess) return e;
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, p);
   return hipGetLastError();
 }
-
-template <int DH, int WHAT>
+template <int DH, bool LO>
+static hipError_t launch_q_t(const AttnP& p, unsigned grid, hipStream_t st) {
+  constexpr int lds = 2 * (LO ? 7 : 6) * 64 * DH;  // two stages of seven (six) tiles
+  static OncePerDevice once;
+  auto kern = attn_bwd_q_kernel<DH, LO>;
+  if (lds > 64 * 1024)
+    if (const hipError_t e = once.lds_limit((const void*)kern, lds); e != hipSuccess) return e;
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, p);
+  return hipGetLastError();
+}
+template <int DH, int WHAT, bool LO>
 static hipError_t launch_kv(const AttnP& p, unsigned grid, hipStream_t st) {
-  constexpr int lds = KvTiles<DH, WHAT>::LDS_B;
+  constexpr int lds = KvTiles<DH, WHAT, LO>::LDS_B;
   static_assert(lds <= 160 * 1024, "LDS");
   static OncePerDevice once;
-  auto kern = attn_bwd_kv_kernel<DH, WHAT>;
+  auto kern = attn_bwd_kv_kernel<DH, WHAT, LO>;
   if (lds > 64 * 1024)
     if (const hipError_t e = once.lds_limit((const void*)kern, lds); e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, p);
   return hipGetLastError();
 }
 
+// p.qkv_lo == nullptr: the primal operands have no low-order halves (and no o_lo is written).
+hipError_t launch_attn_fwd(const AttnP& p, hipStream_t st) {
+  if (!attn_shape_ok(p) || p.ldo % 8) return hipErrorInvalidValue;
+  const bool lo = p.qkv_lo != nullptr;
+  if (!al16(p.qkv) || !al16(p.qkv_t) || !al16(p.o) || !al16(p.o_t) || !p.stat) return hipErrorInvalidValue;
+  if (lo && (!al16(p.qkv_lo) || !al16(p.o_lo))) return hipErrorInvalidValue;
+  const int nqt = (p.S + 127) / 128;
+  const unsigned grid = (unsigned)(((p.B * p.H + 7) / 8) * 8 * nqt);
+  if (p.dh == 32) return lo ? launch_fwd_t<32, true>(p, grid, st) : launch_fwd_t<32, false>(p, grid, st);
+  if (p.dh == 64) return lo ? launch_fwd_t<64, true>(p, grid, st) : launch_fwd_t<64, false>(p, grid, st);
+  return lo ? launch_fwd_t<128, true>(p, grid, st) : launch_fwd_t<128, false>(p, grid, st);
+}
+
+template <int DH, bool LO>
+static hipError_t launch_bwd_t(const AttnP& p, unsigned gq, unsigned gk, hipStream_t st) {
+  if (const hipError_t e = launch_q_t<DH, LO>(p, gq, st); e != hipSuccess) return e;
+  if constexpr (DH <= 64) {
+    return launch_kv<DH, 3, LO>(p, gk, st);
+  } else {
+    // at a head width of 128 the accumulators of dK and dV together exceed the register file:
+    // one launch each, both recomputing the scores
+    if (const hipError_t e1 = launch_kv<DH, 1, LO>(p, gk, st); e1 != hipSuccess) return e1;
+    return launch_kv<DH, 2, LO>(p, gk, st);
+  }
+}
+
 hipError_t launch_attn_bwd(const AttnP& p, hipStream_t st) {
   if (!attn_shape_ok(p) || p.lddo % 8) return hipErrorInvalidValue;
-  if (!al16(p.qkv) || !al16(p.qkv_lo) || !al16(p.qkv_t) || !al16(p.dO) || !al16(p.dO_t) || !p.stat || !p.delta) return hipErrorInvalidValue;
+  const bool lo = p.qkv_lo != nullptr;
+  if (!al16(p.qkv) || (lo && !al16(p.qkv_lo)) || !al16(p.qkv_t) || !al16(p.dO) || !al16(p.dO_t) || !p.stat || !p.delta) return hipErrorInvalidValue;
   if (!al16(p.dq) || !al16(p.dq_t) || !al16(p.dk) || !al16(p.dk_t) || !al16(p.dv) || !al16(p.dv_t)) return hipErrorInvalidValue;
   if (p.lddq % 4 || p.lddk % 4 || p.lddv % 4) return hipErrorInvalidValue;
   const int nqt = (p.S + 127) / 128;
   const unsigned gq = (unsigned)(((p.B * p.H + 7) / 8) * 8 * nqt);
   const unsigned gk = (unsigned)(((p.B * (p.H / p.grp) + 7) / 8) * 8 * nqt);
-  const size_t lq = (size_t)2 * 7 * 32 * p.dh * 2;  // dQ: two stages of seven tiles
-  if (p.dh == 32) {
-    hipLaunchKernelGGL(attn_bwd_q_kernel<32>, dim3(gq), dim3(256), lq, st, p);
-    return launch_kv<32, 3>(p, gk, st);
-  }
-  if (p.dh == 64) {
-    hipLaunchKernelGGL(attn_bwd_q_kernel<64>, dim3(gq), dim3(256), lq, st, p);
-    return launch_kv<64, 3>(p, gk, st);
-  }
-  // at a head width of 128 the accumulators of dK and dV together exceed the register file:
-  // one launch each, both recomputing the scores
-  static OncePerDevice once;
-  const hipError_t e = once.lds_limit((const void*)attn_bwd_q_kernel<128>, (int)lq);  // 112 KB
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(attn_bwd_q_kernel<128>, dim3(gq), dim3(256), lq, st, p);
-  if (const hipError_t e1 = launch_kv<128, 1>(p, gk, st); e1 != hipSuccess) return e1;
-  return launch_kv<128, 2>(p, gk, st);
+  if (p.dh == 32) return lo ? launch_bwd_t<32, true>(p, gq, gk, st) : launch_bwd_t<32, false>(p, gq, gk, st);
+  if (p.dh == 64) return lo ? launch_bwd_t<64, true>(p, gq, gk, st) : launch_bwd_t<64, false>(p, gq, gk, st);
+  return lo ? launch_bwd_t<128, true>(p, gq, gk, st) : launch_bwd_t<128, false>(p, gq, gk, st);
 }
 
 }  // namespace hf

@@ -47,6 +47,7 @@ struct hf_ctx {
   int max_batch = 0, max_m = 0;
   int bf = 0;  // 1: bf16 parameters / operands
   int flash = 0;  // 1: attention runs in the streamed kernels (no S x S buffers are allocated)
+  int pairs = 0;  // 1: bf16 primal activations are carried as (rounded value, remainder) pairs; the *_lo buffers exist
   int64_t n = 0;
   std::vector<hf::LayoutEntry> layout;
   std::vector<hf::LayerOff> loff;

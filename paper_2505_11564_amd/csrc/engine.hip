@@ -43,6 +43,7 @@ int hf::build_layout(const hf_model_desc& d, std::vector<LayoutEntry>& out, std:
   if (!(d.norm_eps > 0.f)) return bad("norm_eps must be positive");
   if (d.activation != HF_ACT_GELU_ERF && d.activation != HF_ACT_GELU_TANH) return bad("activation must be HF_ACT_GELU_ERF or HF_ACT_GELU_TANH");
   if (d.attention != HF_ATTN_AUTO && d.attention != HF_ATTN_STREAMED && d.attention != HF_ATTN_STORED) return bad("attention must be HF_ATTN_AUTO, HF_ATTN_STREAMED or HF_ATTN_STORED");
+  if (d.primal != HF_PRIMAL_AUTO && d.primal != HF_PRIMAL_PAIRS && d.primal != HF_PRIMAL_SINGLE) return bad("primal must be HF_PRIMAL_AUTO, HF_PRIMAL_PAIRS or HF_PRIMAL_SINGLE");
   const int64_t D = d.d_model, F = d.d_ff, V = d.vocab;
   const int hkv = d.n_kv_head > 0 ? d.n_kv_head : d.n_head;
   if (hkv > d.n_head || d.n_head % hkv) return bad("n_kv_head must divide n_head");
@@ -120,6 +121,7 @@ int hf_ctx::plan_and_alloc() {
         return fail(HF_ESHAPE, "HF_ATTN_STREAMED needs bf16 parameters, a head width of 32, 64 or 128 and d_model a multiple of 8");
       flash = can && desc.attention != HF_ATTN_STORED && (desc.attention == HF_ATTN_STREAMED || attn_flash_preferred((int)(D / H), B * H, S));
     }
+    pairs = bf && (desc.primal == HF_PRIMAL_PAIRS || (desc.primal == HF_PRIMAL_AUTO && llama));
     const int64_t SSa = flash ? 0 : SS;  // the S x S buffers exist only for the unstreamed paths
     lb.resize(desc.n_layer);
     for (auto& b : lb) {
@@ -129,7 +131,8 @@ int hf_ctx::plan_and_alloc() {
       pl.add(b.a, T * D * e); pl.add(b.a_t, T * D * e);
       pl.add(b.qkv, T * W3 * e); pl.add(b.qkv_t, T * W3 * e);
       pl.add(b.P, SSa * e); pl.add(b.P_t, SSa * e);
-      if (flash) { pl.add(b.qkv_lo, T * W3 * e); pl.add(b.o_lo, T * D * e); pl.add(b.att_stat, SS / S * 2 * 4); }
+      if (flash) pl.add(b.att_stat, SS / S * 2 * 4);
+      if (flash && pairs) { pl.add(b.qkv_lo, T * W3 * e); pl.add(b.o_lo, T * D * e); }
       pl.add(b.o, T * D * e); pl.add(b.o_t, T * D * e);
       pl.add(b.m, T * D * e); pl.add(b.m_t, T * D * e);
       pl.add(b.f, T * F * e); pl.add(b.f_t, T * F * e);
@@ -138,7 +141,7 @@ int hf_ctx::plan_and_alloc() {
     }
     pl.add(xL, T * D * 4); pl.add(xL_t, T * D * 4); pl.add(stf, T * 16);
     pl.add(xf, T * D * e); pl.add(xf_t, T * D * e);
-    if (bf) {
+    if (pairs) {
       pl.add(xf_lo, T * D * e); pl.add(a_lo, T * D * e); pl.add(o_lo, T * D * e); pl.add(qkv_lo, T * W3 * e);
       pl.add(P_lo, SSa * e); pl.add(f_lo, T * F * e); pl.add(g_lo, T * F * e);
       if (llama) pl.add(up_lo, T * F * e);
@@ -437,7 +440,7 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
       CK(launch_fill_f32((float*)b.P, words, 0.f, st));
       CK(launch_fill_f32((float*)b.P_t, words, 0.f, st));
     }
-    CK(launch_fill_f32((float*)P_lo, words, 0.f, st));
+    if (P_lo) CK(launch_fill_f32((float*)P_lo, words, 0.f, st));
     CK(launch_fill_f32((float*)dS, words, 0.f, st));
     CK(launch_fill_f32((float*)dS_t, words, 0.f, st));
     att_zero_B = B; att_zero_S = S;
@@ -490,8 +493,10 @@ int hf_ctx::hvp_transformer(const void* params, const int32_t* tok, const int32_
       g.M = S; g.N = S; g.K = dh; g.lda = W3; g.ldb = W3; g.ldc = S; g.transB = 1; g.alpha = cs; g.skip_upper = 1; g.divB = grp;
       set_qkv(g.sA1, g.sA2); set_qkv(g.sB1, g.sB2); set_sc(g.sC1, g.sC2);
       g.A[0] = b.qkv; g.B[0] = cat(b.qkv, offK);
-      g.A[1] = qkv_lo; g.B[1] = cat(b.qkv, offK);
-      g.A[2] = b.qkv; g.B[2] = cat(qkv_lo, offK);
+      if (qkv_lo) {
+        g.A[1] = qkv_lo; g.B[1] = cat(b.qkv, offK);
+        g.A[2] = b.qkv; g.B[2] = cat(qkv_lo, offK);
+      }
       g.At = b.qkv_t; g.Bt = cat(b.qkv_t, offK);
       g.C = b.P; g.Ct = b.P_t; g.out_bf16 = 1;
       g.epi = EPI_FWD_STATS; g.part = att_part;

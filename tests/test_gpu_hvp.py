@@ -93,6 +93,17 @@ def test_hvp_attention_modes(name, mode):
     run_case(dict(cfg, model=dict(cfg["model"], attention=mode)), "bf16", seed=3)
 
 
+@pytest.mark.parametrize("primal", ["pairs", "single"])
+@pytest.mark.parametrize("mode", ["streamed", "stored"])
+@pytest.mark.parametrize("name", ["gpt_fused", "gpt_dh64_long", "gpt_dh128", "gpt_deep", "llama_gqa_mid", "llama_gqa_dh128"])
+def test_hvp_primal_pairs_and_single(name, mode, primal):
+    # bf16 parameters with the primal activations carried as (value, remainder) pairs or as single
+    # bf16 numbers, whichever of the two the library would choose for the family, on both
+    # evaluations of attention and at every head width of the streamed kernels
+    cfg = SHAPES[name]
+    run_case(dict(cfg, model=dict(cfg["model"], attention=mode, primal=primal)), "bf16", seed=5)
+
+
 def test_hvp_streamed_attention_needs_a_supported_head_width():
     import paper_2505_11564_amd as hf
     model = dict(si._gpt(1, 48, 2, 64, 97, 16), attention="streamed")   # head width 24
