@@ -343,6 +343,7 @@ def main():
         "vs_baseline": None, "dtype": "bf16" if dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": args.workload, "n_params": n, "batch": B, "seq": Sarg, "lanczos_m": m,
                    "reorth": cfg["reorth"], "basis_dtype": basis, "tokens": cfg["tokens"], "attention": args.attention,
+                   "primal": "auto (GPT: single bf16 numbers, Llama: bf16 pairs)",
                    "depth_range": head["depth_range"],
                    "depth_note": "timed steps are iterations depth_range[0]..depth_range[1] of one m-step run "
                                  "(mean basis depth = that of the whole run); earlier iterations run untimed"},
