@@ -27,8 +27,9 @@
  *   - The library owns only what hf_create allocates (activation workspace for
  *     max_batch*max_seq tokens, three fp32 Lanczos vectors (with an fp32 basis
  *     its rows k and k-1 serve as q_k and q_{k-1}), max_m basis
- *     vectors, a bf16 copy of the direction when parameters are bf16) and
- *     frees it in hf_destroy.
+ *     vectors, a bf16 copy of the direction when parameters are bf16, and with
+ *     bf16 parameters and an fp32 basis a bf16 copy of every basis row, i.e.
+ *     half the basis again) and frees it in hf_destroy.
  *   - Work is enqueued on the HIP stream passed as `hip_stream` (a hipStream_t
  *     cast to void*, NULL = the default stream).  Calls that return host
  *     scalars synchronise that stream before returning.
@@ -190,7 +191,10 @@ int32_t hf_lanczos_init(hf_ctx* ctx, const float* q0_dev, int32_t reorth,
  * below 1/sqrt(2)]; beta_k = ||r||; q_{k+1} = r / beta_k unless beta_k < tol.
  * With full orthogonalisation the two subtractions are carried out by the
  * first Gram-Schmidt pass itself, applied to H q_k against q_0..q_k (alpha_k
- * is its k-th coefficient): the same r and alpha_k up to rounding.  Without a
+ * is its k-th coefficient): the same r and alpha_k up to rounding.  The
+ * coefficients are always formed against the stored rows; where the context
+ * also holds bf16 copies of an fp32 basis, the subtraction reads rows 0..k-2
+ * (whose coefficients are at rounding level) from the copies.  Without a
  * basis r is never stored: alpha_k, <r', r'> and <q_k, q_k> (r' = H q_k -
  * beta_{k-1} q_{k-1}) come from one read-only pass, beta_k^2 = <r', r'> -
  * alpha_k^2 (2 - <q_k, q_k>) (formed explicitly when that difference loses its
@@ -199,7 +203,9 @@ int32_t hf_lanczos_init(hf_ctx* ctx, const float* q0_dev, int32_t reorth,
  * (the iteration has ended), HF_ESHAPE after max_m iterations with a basis.
  * A token or label error (HF_EINVAL, as hf_hvp) leaves the iteration where it
  * was: the same step can be repeated with valid inputs.  Synchronises the
- * stream once, after all work of the iteration has been enqueued. */
+ * stream once, after all work of the iteration has been enqueued.
+ * The iteration is that of one fixed operator: parameters and batch must be
+ * the same in every step of a run (the library does not check this). */
 int32_t hf_lanczos_step(hf_ctx* ctx, const void* params_dev,
                         const void* inputs_dev, const int32_t* labels_dev,
                         int32_t batch, int32_t seq, double tol,
