@@ -502,14 +502,28 @@ __global__ __launch_bounds__(256) void lz_sub_qc_kernel(const BT* __restrict__ Q
       if (x1) sub_x(x1, nq + 1);
     }
     if (!XR || nq > 0) {
-      typename V::raw qa[V::U], qb[V::U];
-      load_q_slice<BT>(Q, base, n, full, qa);
+      // three rows in flight ahead of the one being subtracted
+      typename V::raw q0[V::U], q1[V::U], q2[V::U], q3[V::U];
+      auto row = [&](int j) { return Q + (int64_t)j * ldq; };
+      load_q_slice<BT>(row(0), base, n, full, q0);
+      if (1 < nq) load_q_slice<BT>(row(1), base, n, full, q1);
+      if (2 < nq) load_q_slice<BT>(row(2), base, n, full, q2);
 #pragma unroll 1
-      for (int j = 0; j < nq; j += 2) {
-        if (j + 1 < nq) load_q_slice<BT>(Q + (int64_t)(j + 1) * ldq, base, n, full, qb);
-        sub_j(qa, j);
-        if (j + 2 < nq) load_q_slice<BT>(Q + (int64_t)(j + 2) * ldq, base, n, full, qa);
-        if (j + 1 < nq) sub_j(qb, j + 1);
+      for (int j = 0; j < nq; j += 4) {
+        if (j + 3 < nq) load_q_slice<BT>(row(j + 3), base, n, full, q3);
+        sub_j(q0, j);
+        if (j + 1 < nq) {
+          if (j + 4 < nq) load_q_slice<BT>(row(j + 4), base, n, full, q0);
+          sub_j(q1, j + 1);
+        }
+        if (j + 2 < nq) {
+          if (j + 5 < nq) load_q_slice<BT>(row(j + 5), base, n, full, q1);
+          sub_j(q2, j + 2);
+        }
+        if (j + 3 < nq) {
+          if (j + 6 < nq) load_q_slice<BT>(row(j + 6), base, n, full, q2);
+          sub_j(q3, j + 3);
+        }
       }
     }
     float s = 0.f;
